@@ -1,0 +1,205 @@
+"""Seeded synthetic inputs for the attention-variant forward path.
+
+This module is the one piece shared by the CPU oracle's tests and the HIP path's
+tests / benchmark.  It holds no attention arithmetic: it only draws random tensors,
+rounds them to the storage precision, and names the workload shapes.
+
+Every tensor is returned as a float32 NumPy array whose values are exactly
+representable in the storage dtype (bf16 or fp32), so that the oracle (which
+upcasts to fp64) and the GPU (which receives the same bits) see identical inputs.
+
+The paper's own kernel benchmarks run on randomly generated tensors (artifact
+appendix, "Data sets"), so synthetic N(0,1) data *is* the paper's workload.
+
+Logical layout used everywhere: q [B, G, H, Sq, D], k [B, G, Hkv, Sk, D],
+v [B, G, Hkv, Sk, Dv], where G is an extra independent row axis (1 for ordinary
+attention, the MSA-sequence axis for Evoformer row-wise attention).
+"""
+from __future__ import annotations
+
+import dataclasses
+from typing import Dict, Optional
+
+import numpy as np
+
+SEED_BASE = 251102043 * 1000
+
+
+def tensor_seed(config: int, tensor_index: int, salt: int = 0) -> int:
+    """One independent PCG64 stream per (config, tensor)."""
+    return SEED_BASE + 10 * config + tensor_index + 100000 * salt
+
+
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Round float32 values to the nearest bf16 (ties to even), in integer arithmetic.
+
+    Returns float32 holding bf16-representable values.  NaN is not expected in inputs.
+    """
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    bits = x.view(np.uint32)
+    lsb = (bits >> np.uint32(16)) & np.uint32(1)
+    rounded = bits + np.uint32(0x7FFF) + lsb
+    rounded &= np.uint32(0xFFFF0000)
+    return rounded.view(np.float32)
+
+
+def bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Upper 16 bits of float32 values that are already bf16-representable."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    bits = x.view(np.uint32)
+    if np.any(bits & np.uint32(0xFFFF)):
+        raise ValueError("values are not bf16-representable")
+    return (bits >> np.uint32(16)).astype(np.uint16)
+
+
+def normal(shape, seed: int, dtype: str = "bf16", scale: float = 1.0) -> np.ndarray:
+    """N(0, scale^2) tensor from its own PCG64 stream, rounded to `dtype`."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    x = rng.standard_normal(size=shape, dtype=np.float32)
+    if scale != 1.0:
+        x = x * np.float32(scale)
+    if dtype == "bf16":
+        return round_to_bf16(x)
+    if dtype == "f32":
+        return x
+    raise ValueError(f"unknown dtype {dtype!r}")
+
+
+def alibi_slopes(n_heads: int) -> np.ndarray:
+    """Geometric slope sequence 2^(-8 (h+1) / H) for zero-based head h (float32)."""
+    h = np.arange(1, n_heads + 1, dtype=np.float64)
+    return np.exp2(-8.0 * h / n_heads).astype(np.float32)
+
+
+def doc_ids(batch: int, seq: int, seed: int, lo: int = 64, hi: int = 1024) -> np.ndarray:
+    """Per-token document ids [batch, seq] (int32).
+
+    For each batch element independently: integer run lengths uniform on [lo, hi]
+    inclusive, concatenated until the sequence is covered, last run truncated;
+    the id of a token is the index of its run.
+    """
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = np.empty((batch, seq), dtype=np.int32)
+    for b in range(batch):
+        pos, doc = 0, 0
+        while pos < seq:
+            run = int(rng.integers(lo, hi + 1))
+            out[b, pos:pos + run] = doc
+            pos += run
+            doc += 1
+    return out
+
+
+@dataclasses.dataclass
+class Workload:
+    """A named problem instance: tensors plus the variant's parameters."""
+    name: str
+    dtype: str                      # storage dtype of q/k/v: "bf16" | "f32"
+    q: np.ndarray                   # [B, G, H, Sq, D]
+    k: np.ndarray                   # [B, G, Hkv, Sk, D]
+    v: np.ndarray                   # [B, G, Hkv, Sk, Dv]
+    scale: float
+    causal: bool = False
+    window: Optional[int] = None    # allowed iff 0 <= i - j <= window (with causal)
+    prefix: Optional[int] = None    # prefix-LM: keys j < prefix are visible to every query
+    softcap: Optional[float] = None
+    alibi: Optional[np.ndarray] = None      # [H] float32 slopes
+    q_doc: Optional[np.ndarray] = None      # [B, Sq] int32
+    kv_doc: Optional[np.ndarray] = None     # [B, Sk] int32
+    biases: tuple = ()                      # each broadcastable to [B, G, H, Sq, Sk]
+    gate: Optional[np.ndarray] = None       # [B, G, H, Sq, Dv] pre-sigmoid
+    q2: Optional[np.ndarray] = None         # differential: second stream
+    k2: Optional[np.ndarray] = None
+    lam: Optional[np.ndarray] = None        # [H] float32
+    rmsnorm: bool = False
+    rms_eps: float = 1e-6
+    rms_weight: Optional[np.ndarray] = None  # [Dv] float32
+
+    @property
+    def dims(self) -> Dict[str, int]:
+        B, G, H, Sq, D = self.q.shape
+        return dict(B=B, G=G, H=H, Hkv=self.k.shape[2], Sq=Sq, Sk=self.k.shape[3],
+                    D=D, Dv=self.v.shape[4])
+
+
+def _qkv(cfg, B, G, H, Sq, Sk, D, Dv, dtype, Hkv=None, salt=0, qscale=1.0):
+    Hkv = H if Hkv is None else Hkv
+    q = normal((B, G, H, Sq, D), tensor_seed(cfg, 0, salt), dtype, qscale)
+    k = normal((B, G, Hkv, Sk, D), tensor_seed(cfg, 1, salt), dtype)
+    v = normal((B, G, Hkv, Sk, Dv), tensor_seed(cfg, 2, salt), dtype)
+    return q, k, v
+
+
+# --- the five benchmark configurations, each shrinkable for parity tests -----------------
+
+def plain_f32(B=1, H=2, S=128, D=64, Sk=None, salt=0) -> Workload:
+    """Config 1: plain softmax attention, fp32 storage, no mask."""
+    Sk = S if Sk is None else Sk
+    q, k, v = _qkv(1, B, 1, H, S, Sk, D, D, "f32", salt=salt)
+    return Workload("plain_f32", "f32", q, k, v, scale=D ** -0.5)
+
+
+def causal_bf16(B=4, H=16, S=8192, D=128, Hkv=None, Sk=None, salt=0, causal=True) -> Workload:
+    """Config 2: causal attention, bf16 storage (D=128, repeated at D=64)."""
+    Sk = S if Sk is None else Sk
+    q, k, v = _qkv(2, B, 1, H, S, Sk, D, D, "bf16", Hkv=Hkv, salt=salt)
+    return Workload(f"causal_bf16_d{D}" if causal else f"plain_bf16_d{D}", "bf16", q, k, v,
+                    scale=D ** -0.5, causal=causal)
+
+
+def alibi_bf16(B=8, H=16, S=2048, D=64, salt=0) -> Workload:
+    """Config 3a: ALiBi bias -slope_h |i-j| on the scaled score, no mask."""
+    q, k, v = _qkv(3, B, 1, H, S, S, D, D, "bf16", salt=salt)
+    return Workload("alibi_bf16", "bf16", q, k, v, scale=D ** -0.5, alibi=alibi_slopes(H))
+
+
+def softcap_bf16(B=8, H=16, S=2048, D=64, cap=30.0, qscale=1.0, salt=0) -> Workload:
+    """Config 3b: tanh soft-capping of the scaled score at `cap`.
+
+    qscale > 1 widens the score distribution so that tanh actually saturates.
+    """
+    q, k, v = _qkv(3, B, 1, H, S, S, D, D, "bf16", salt=salt, qscale=qscale)
+    return Workload("softcap_bf16", "bf16", q, k, v, scale=D ** -0.5, softcap=cap)
+
+
+def window_doc_bf16(B=8, H=16, S=2048, D=64, window=512, lo=64, hi=1024, salt=0) -> Workload:
+    """Config 3c: sliding-window causal mask AND a document mask from per-token ids."""
+    q, k, v = _qkv(3, B, 1, H, S, S, D, D, "bf16", salt=salt)
+    ids = doc_ids(B, S, tensor_seed(3, 3, salt), lo, hi)
+    return Workload("window_doc_bf16", "bf16", q, k, v, scale=D ** -0.5, causal=True,
+                    window=window, q_doc=ids, kv_doc=ids)
+
+
+def differential_bf16(B=2, H=16, S=4096, D=64, Dv=128, lam=0.8, salt=0, dtype="bf16") -> Workload:
+    """Config 4: differential attention (two softmax streams sharing V), causal, RMSNorm.
+
+    One allocation of 2H heads for q and for k; pair h is (head h, head H + h),
+    as in the paper's differential-attention listing (chunk along the head axis).
+    """
+    q_all = normal((B, 1, 2 * H, S, D), tensor_seed(4, 0, salt), dtype)
+    k_all = normal((B, 1, 2 * H, S, D), tensor_seed(4, 1, salt), dtype)
+    v = normal((B, 1, H, S, Dv), tensor_seed(4, 2, salt), dtype)
+    return Workload("differential_" + dtype, dtype, q_all[:, :, :H], k_all[:, :, :H], v,
+                    scale=D ** -0.5, causal=True, q2=q_all[:, :, H:], k2=k_all[:, :, H:],
+                    lam=np.full((H,), lam, dtype=np.float32), rmsnorm=True, rms_eps=1e-6)
+
+
+def evoformer_bf16(B=1, Nseq=128, Nres=384, H=8, D=32, two_biases=False, salt=0,
+                   dtype="bf16") -> Workload:
+    """Config 5: Evoformer row-wise gated self-attention with pair bias.
+
+    Activations are stored [B, Nseq, Nres, H, D]; the returned arrays are the
+    [B, G=Nseq, H, S=Nres, D] *views* of that storage (non-contiguous), which is the
+    layout the kernel must consume.  The pair bias [B, 1, H, Nres, Nres] broadcasts
+    over the Nseq axis; the optional second bias [B, Nseq, 1, 1, Nres] is the
+    per-row key mask bias of the MSA stack, broadcast over heads and queries.
+    """
+    def act(idx):
+        x = normal((B, Nseq, Nres, H, D), tensor_seed(5, idx, salt), dtype)
+        return x.transpose(0, 1, 3, 2, 4)
+    q, k, v, gate = act(0), act(1), act(2), act(4)
+    biases = [normal((B, 1, H, Nres, Nres), tensor_seed(5, 3, salt), dtype)]
+    if two_biases:
+        biases.append(normal((B, Nseq, 1, 1, Nres), tensor_seed(5, 5, salt), dtype))
+    return Workload("evoformer_" + dtype, dtype, q, k, v, scale=D ** -0.5,
+                    biases=tuple(biases), gate=gate)
