@@ -1,0 +1,168 @@
+/*
+ * fl_attn.h -- C ABI of the fused attention-variant forward library for AMD MI355X (gfx950).
+ *
+ * One call computes, for every (b, g, h) and every query row i, without ever writing the
+ * [Sq, Sk] score matrix to device memory:
+ *
+ *     s_ij   = scale * <q_i, k_j>                                     (paper Eq. 3)
+ *     s_ij   = score_mod(s_ij)                 soft-cap / ALiBi       (paper Eq. 4)
+ *     s_ij  += bias_0[b,g,h,i,j] + bias_1[b,g,h,i,j]                  (Evoformer biases, Sec. 4.1)
+ *     s_ij   = -inf where masked               causal / window / prefix / document
+ *                                              (attention listing; sliding-window listings)
+ *     P_ij   = softmax over j, computed with the online recurrence    (Eq. 2, Alg. 2, Sec. 3.4)
+ *     o_i    = sum_j P_ij v_j                                         (Eq. 3)
+ *     differential:  o_i = o_i(q,k) - lambda_h * o_i(q2,k2), same v   (differential listing)
+ *     epilogue:      RMSNorm over the Dv channels, then * sigmoid(gate)
+ *     lse_i  = m_i + ln(l_i)   (m_i, l_i: post-condition of Alg. 1 / Alg. 2)
+ *
+ * Fixed order of the score pipeline when several parts are enabled:
+ *     scale -> soft-cap -> ALiBi -> + biases -> mask.
+ *
+ * All tensor pointers are DEVICE pointers owned by the caller.  The library never allocates,
+ * frees or keeps device memory; work is enqueued on the caller's stream and the call returns
+ * without synchronising.  Every validation failure returns before anything is launched and
+ * leaves the outputs untouched.  There is no CPU fallback and no generic slow path for a
+ * descriptor without a compiled specialisation: that is FL_ERR_UNSUPPORTED.
+ */
+#ifndef FL_ATTN_H
+#define FL_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FL_OK = 0,
+  FL_ERR_NULL = 1,         /* a required pointer is NULL                                   */
+  FL_ERR_DTYPE = 2,        /* dtype combination not supported                              */
+  FL_ERR_SHAPE = 3,        /* sizes inconsistent between tensors                           */
+  FL_ERR_STRIDE = 4,       /* innermost stride != 1, or a negative / forbidden-zero stride */
+  FL_ERR_ALIGN = 5,        /* base pointer or row stride not 16-byte aligned               */
+  FL_ERR_UNSUPPORTED = 6,  /* no compiled specialisation for this descriptor / head dim    */
+  FL_ERR_AUX_MISSING = 7,  /* descriptor needs an aux tensor that was not given            */
+  FL_ERR_WORKSPACE = 8,    /* workspace NULL or smaller than fl_attn_fwd_workspace_size    */
+  FL_ERR_LAUNCH = 9,       /* the HIP runtime refused a launch (see fl_last_error_detail)  */
+  FL_ERR_DESC = 10         /* descriptor fields contradict each other / bad struct_size    */
+} fl_status;
+
+typedef enum { FL_BF16 = 1, FL_F32 = 2, FL_I32 = 3 } fl_dtype;
+
+/* A strided view with logical dims [B, G, H, S, D].
+ *   G is an extra independent row axis: 1 for ordinary attention, the MSA-sequence axis for
+ *   Evoformer row-wise attention.  Strides are in ELEMENTS.  stride[4] must be 1.
+ *   For q/k/v/out/gate all strides are >= 0 and every row (last axis) starts 16-byte aligned.
+ *   Bias tensors have logical dims [B, G, H, Sq, Sk]; a stride of 0 broadcasts that axis.   */
+typedef struct {
+  void*   ptr;
+  int32_t dtype;           /* fl_dtype */
+  int32_t reserved;
+  int64_t size[5];
+  int64_t stride[5];
+} fl_tensor;
+
+/* score_mod (paper Eq. 4): elementwise old score -> new score, on the SCALED score. */
+enum { FL_MOD_NONE = 0, FL_MOD_ALIBI = 1, FL_MOD_SOFTCAP = 2 };
+
+/* mask bits (True = masked, combined by OR), i = query index, j = key index:
+ *   CAUSAL  masked iff j > i                                   (attention listing + causal)
+ *   WINDOW  masked iff j > i or i - j > window                 (sliding-window listings);
+ *           implies CAUSAL, so window + 1 keys are visible including j = i
+ *   PREFIX  masked iff j > i and j >= prefix_len               (PrefixLM, Sec. 4.1); excludes
+ *           CAUSAL and WINDOW
+ *   DOC     masked iff q_doc_ids[b,i] != kv_doc_ids[b,j]       (Document mask, Sec. 4.1)      */
+enum { FL_MASK_CAUSAL = 1, FL_MASK_WINDOW = 2, FL_MASK_DOC = 4, FL_MASK_PREFIX = 8 };
+
+enum { FL_SINGLE = 0, FL_DIFFERENTIAL = 1 };
+
+/* epilogue bits, applied in this order after normalisation by l_i (and after the differential
+ * subtraction): RMSNorm over the Dv channels of a row (x * w / sqrt(mean(x^2) + rms_eps)),
+ * then multiplication by sigmoid(gate).                                                      */
+enum { FL_EPI_RMSNORM = 1, FL_EPI_GATE_SIGMOID = 2 };
+
+typedef struct {
+  uint32_t struct_size;    /* sizeof(fl_variant_desc) */
+  float    scale;          /* multiplies <q,k>; 1/sqrt(D) for Eq. 3                           */
+  uint32_t score_mod;      /* FL_MOD_*                                                        */
+  float    softcap;        /* cap of cap*tanh(s/cap); > 0 when FL_MOD_SOFTCAP                 */
+  uint32_t mask;           /* bit-or of FL_MASK_*                                             */
+  int32_t  window;         /* >= 0 when FL_MASK_WINDOW                                        */
+  int32_t  prefix_len;     /* >= 0 when FL_MASK_PREFIX                                        */
+  uint32_t n_bias;         /* 0..2 additive bias tensors in aux->bias                         */
+  uint32_t combine;        /* FL_SINGLE | FL_DIFFERENTIAL                                     */
+  uint32_t epilogue;       /* bit-or of FL_EPI_*                                              */
+  float    rms_eps;
+  uint32_t reserved;
+} fl_variant_desc;
+
+typedef struct {
+  uint32_t       struct_size;   /* sizeof(fl_aux) */
+  uint32_t       reserved;
+  const float*   alibi_slopes;  /* [H] device, FL_MOD_ALIBI                                    */
+  const int32_t* q_doc_ids;     /* [B, Sq] device, contiguous, FL_MASK_DOC                     */
+  const int32_t* kv_doc_ids;    /* [B, Sk] device, contiguous (may alias q_doc_ids)            */
+  fl_tensor      bias[2];       /* logical [B, G, H, Sq, Sk]; dtype bf16 or f32; stride 0 ok;
+                                   innermost stride 1 (or 0 when Sk-broadcast is not needed)  */
+  fl_tensor      gate;          /* logical shape of out, pre-sigmoid; dtype of q               */
+  fl_tensor      q2, k2;        /* second softmax stream (FL_DIFFERENTIAL); shapes of q, k     */
+  const float*   lambda;        /* [H] device, FL_DIFFERENTIAL                                 */
+  const float*   rms_weight;    /* [Dv] device, or NULL for all-ones                           */
+  void*          workspace;     /* device scratch for the tile skipper (FL_MASK_DOC only)      */
+  size_t         workspace_bytes;
+} fl_aux;
+
+/* The fused forward pass (Sec. 3, "each thread block computes tiles of S = QK^T/sqrt(d), applies
+ * the online softmax to each tile via a fused max-reduction and rescaled accumulation, and
+ * multiplies by the tiles of V"), for the variant named by `desc`.
+ *
+ *   q    [B, G, H,   Sq, D ]  bf16 or f32 (all of q, k, v, q2, k2, gate share one dtype)
+ *   k    [B, G, Hkv, Sk, D ]  Hkv divides H; query head h reads kv head h / (H / Hkv)
+ *   v    [B, G, Hkv, Sk, Dv]
+ *   out  [B, G, H,   Sq, Dv]  dtype of q, or f32
+ *   lse  [B, G, H, Sq, 1] f32, or NULL / ptr == NULL to skip it.  For FL_DIFFERENTIAL the two
+ *        streams' values go to axis G: size[1] must be 2*G, stream s of row-axis g at 2*g + s
+ *        (with G = 1: lse[:, 0] is stream 1, lse[:, 1] is stream 2).
+ *   aux  may be NULL when the descriptor needs nothing from it.
+ *   stream  a hipStream_t (NULL = the default stream).
+ *
+ * A row whose keys are all masked gets out = 0 and lse = -inf.
+ * Supported head dims: D, Dv in {32, 64, 128} for bf16 (the pairs listed by
+ * fl_variant_supported), any multiple of 4 up to 128 for f32.  Sq, Sk >= 1 are arbitrary;
+ * empty problems (any of B, G, H, Sq equal to 0) return FL_OK without a launch; Sk == 0 is
+ * treated as every row fully masked.
+ * Returns FL_OK or an error code; on error nothing was launched.                            */
+fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v,
+                      const fl_variant_desc* desc, const fl_aux* aux,
+                      fl_tensor* out, fl_tensor* lse, void* stream);
+
+/* Bytes of aux->workspace that fl_attn_fwd needs for these shapes and this descriptor
+ * (0 unless FL_MASK_DOC: the skipper's per-tile [min, max] document-id summaries; Sec. 4.3 notes
+ * that the paper's own kernels do not skip masked blocks -- this goes beyond it).           */
+size_t fl_attn_fwd_workspace_size(const fl_tensor* q, const fl_tensor* k,
+                                  const fl_variant_desc* desc);
+
+/* 1 if a kernel specialisation exists for (descriptor, dtype, D, Dv), else 0. */
+int fl_variant_supported(const fl_variant_desc* desc, int dtype, int D, int Dv);
+
+/* Static text for a status code. */
+const char* fl_strerror(fl_status status);
+
+/* Thread-local detail of the last failure in this thread (which check failed, or the HIP error
+ * string); valid until the next library call of the thread.                                 */
+const char* fl_last_error_detail(void);
+
+/* Tuning knobs for benchmarking sweeps: choose a non-default kernel shape.  `key` is one of
+ * "bm" (query rows per workgroup), "bn" (keys per tile), "order" (workgroup ordering).
+ * Value 0 restores the built-in choice.  Returns FL_OK or FL_ERR_UNSUPPORTED.  Not thread-safe
+ * with respect to concurrent fl_attn_fwd calls.                                             */
+fl_status fl_set_tuning(const char* key, int value);
+
+/* ABI version: major << 16 | minor. */
+uint32_t fl_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FL_ATTN_H */

@@ -1,0 +1,175 @@
+"""ctypes binding of libflattn.so: the same entry points as include/fl_attn.h.
+
+Argument marshalling only.  PyTorch supplies device memory and streams; every step of
+the attention path runs in the library's HIP kernels.  There is no fallback: if the
+shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libflattn.so")
+
+# --- enums (include/fl_attn.h) -----------------------------------------------------------
+FL_OK, FL_ERR_NULL, FL_ERR_DTYPE, FL_ERR_SHAPE, FL_ERR_STRIDE, FL_ERR_ALIGN = 0, 1, 2, 3, 4, 5
+FL_ERR_UNSUPPORTED, FL_ERR_AUX_MISSING, FL_ERR_WORKSPACE, FL_ERR_LAUNCH, FL_ERR_DESC = 6, 7, 8, 9, 10
+FL_BF16, FL_F32, FL_I32 = 1, 2, 3
+FL_MOD_NONE, FL_MOD_ALIBI, FL_MOD_SOFTCAP = 0, 1, 2
+FL_MASK_CAUSAL, FL_MASK_WINDOW, FL_MASK_DOC, FL_MASK_PREFIX = 1, 2, 4, 8
+FL_SINGLE, FL_DIFFERENTIAL = 0, 1
+FL_EPI_RMSNORM, FL_EPI_GATE_SIGMOID = 1, 2
+
+
+class fl_tensor(C.Structure):
+    _fields_ = [("ptr", C.c_void_p), ("dtype", C.c_int32), ("reserved", C.c_int32),
+                ("size", C.c_int64 * 5), ("stride", C.c_int64 * 5)]
+
+
+class fl_variant_desc(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("scale", C.c_float), ("score_mod", C.c_uint32),
+                ("softcap", C.c_float), ("mask", C.c_uint32), ("window", C.c_int32),
+                ("prefix_len", C.c_int32), ("n_bias", C.c_uint32), ("combine", C.c_uint32),
+                ("epilogue", C.c_uint32), ("rms_eps", C.c_float), ("reserved", C.c_uint32)]
+
+
+class fl_aux(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("reserved", C.c_uint32),
+                ("alibi_slopes", C.c_void_p), ("q_doc_ids", C.c_void_p), ("kv_doc_ids", C.c_void_p),
+                ("bias", fl_tensor * 2), ("gate", fl_tensor), ("q2", fl_tensor), ("k2", fl_tensor),
+                ("lambda_", C.c_void_p), ("rms_weight", C.c_void_p),
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+
+
+class FlError(RuntimeError):
+    def __init__(self, status: int, text: str, detail: str):
+        super().__init__(f"fl_attn status {status} ({text}): {detail}")
+        self.status = status
+        self.detail = detail
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load the shared library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} not found: build it with __graft_entry__.build() "
+                "(or make -C paper_2511_02043_amd/csrc); there is no fallback path")
+        L = C.CDLL(LIB_PATH)
+        TP = C.POINTER(fl_tensor)
+        L.fl_attn_fwd.restype = C.c_int
+        L.fl_attn_fwd.argtypes = [TP, TP, TP, C.POINTER(fl_variant_desc), C.POINTER(fl_aux), TP, TP,
+                                  C.c_void_p]
+        L.fl_attn_fwd_workspace_size.restype = C.c_size_t
+        L.fl_attn_fwd_workspace_size.argtypes = [TP, TP, C.POINTER(fl_variant_desc)]
+        L.fl_variant_supported.restype = C.c_int
+        L.fl_variant_supported.argtypes = [C.POINTER(fl_variant_desc), C.c_int, C.c_int, C.c_int]
+        L.fl_strerror.restype = C.c_char_p
+        L.fl_strerror.argtypes = [C.c_int]
+        L.fl_last_error_detail.restype = C.c_char_p
+        L.fl_last_error_detail.argtypes = []
+        L.fl_set_tuning.restype = C.c_int
+        L.fl_set_tuning.argtypes = [C.c_char_p, C.c_int]
+        L.fl_version.restype = C.c_uint32
+        L.fl_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+EXPORTS = ["fl_attn_fwd", "fl_attn_fwd_workspace_size", "fl_variant_supported", "fl_strerror",
+           "fl_last_error_detail", "fl_set_tuning", "fl_version"]
+
+
+def _dtype_code(t) -> int:
+    import torch
+    return {torch.bfloat16: FL_BF16, torch.float32: FL_F32, torch.int32: FL_I32}[t.dtype]
+
+
+def tensor_desc(t, sizes: Optional[Sequence[int]] = None) -> fl_tensor:
+    """fl_tensor for a 5-D torch tensor (or None -> a null descriptor)."""
+    d = fl_tensor()
+    if t is None:
+        return d
+    if t.dim() != 5:
+        raise ValueError(f"expected a 5-D [B,G,H,S,D] view, got {tuple(t.shape)}")
+    d.ptr = t.data_ptr()
+    d.dtype = _dtype_code(t)
+    for a in range(5):
+        d.size[a] = t.shape[a] if sizes is None else sizes[a]
+        d.stride[a] = t.stride(a)
+    return d
+
+
+def variant_desc(*, scale: float, score_mod: int = FL_MOD_NONE, softcap: float = 0.0, mask: int = 0,
+                 window: int = 0, prefix_len: int = 0, n_bias: int = 0, combine: int = FL_SINGLE,
+                 epilogue: int = 0, rms_eps: float = 0.0) -> fl_variant_desc:
+    d = fl_variant_desc()
+    d.struct_size = C.sizeof(fl_variant_desc)
+    d.scale, d.score_mod, d.softcap, d.mask = scale, score_mod, softcap, mask
+    d.window, d.prefix_len, d.n_bias, d.combine = window, prefix_len, n_bias, combine
+    d.epilogue, d.rms_eps = epilogue, rms_eps
+    return d
+
+
+def aux_desc(*, alibi_slopes=None, q_doc_ids=None, kv_doc_ids=None, biases=(), gate=None, q2=None,
+             k2=None, lambda_=None, rms_weight=None, workspace=None) -> fl_aux:
+    a = fl_aux()
+    a.struct_size = C.sizeof(fl_aux)
+
+    def p(t):
+        return None if t is None else t.data_ptr()
+    a.alibi_slopes, a.q_doc_ids, a.kv_doc_ids = p(alibi_slopes), p(q_doc_ids), p(kv_doc_ids)
+    for n, b in enumerate(biases):
+        a.bias[n] = tensor_desc(b)
+    a.gate, a.q2, a.k2 = tensor_desc(gate), tensor_desc(q2), tensor_desc(k2)
+    a.lambda_, a.rms_weight = p(lambda_), p(rms_weight)
+    if workspace is not None:
+        a.workspace = workspace.data_ptr()
+        a.workspace_bytes = workspace.numel() * workspace.element_size()
+    return a
+
+
+def _ref(x):
+    return None if x is None else C.byref(x)
+
+
+def fl_attn_fwd(q: fl_tensor, k: fl_tensor, v: fl_tensor, desc: fl_variant_desc, aux: Optional[fl_aux],
+                out: fl_tensor, lse: Optional[fl_tensor], stream: int = 0) -> int:
+    """Raw call; returns the fl_status code."""
+    return lib().fl_attn_fwd(_ref(q), _ref(k), _ref(v), _ref(desc), _ref(aux), _ref(out), _ref(lse),
+                             C.c_void_p(stream))
+
+
+def fl_attn_fwd_workspace_size(q: fl_tensor, k: fl_tensor, desc: fl_variant_desc) -> int:
+    return lib().fl_attn_fwd_workspace_size(_ref(q), _ref(k), _ref(desc))
+
+
+def fl_variant_supported(desc: fl_variant_desc, dtype: int, D: int, Dv: int) -> bool:
+    return bool(lib().fl_variant_supported(_ref(desc), dtype, D, Dv))
+
+
+def fl_strerror(status: int) -> str:
+    return lib().fl_strerror(status).decode()
+
+
+def fl_last_error_detail() -> str:
+    return lib().fl_last_error_detail().decode()
+
+
+def fl_set_tuning(key: str, value: int) -> int:
+    return lib().fl_set_tuning(key.encode(), value)
+
+
+def fl_version() -> int:
+    return lib().fl_version()
+
+
+def check(status: int) -> None:
+    if status != FL_OK:
+        raise FlError(status, fl_strerror(status), fl_last_error_detail())

@@ -1,0 +1,399 @@
+// C-ABI entry points: argument validation, descriptor -> kernel-specialisation lookup, launch.
+// Nothing here computes attention; every step of the path runs in the kernels.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "../../include/fl_attn.h"
+#include "fl_registry.hpp"
+
+static_assert(FL_MASK_CAUSAL == fl::kMaskCausal && FL_MASK_WINDOW == fl::kMaskWindow &&
+                  FL_MASK_DOC == fl::kMaskDoc && FL_MASK_PREFIX == fl::kMaskPrefix,
+              "mask bits");
+static_assert(FL_MOD_NONE == fl::kModNone && FL_MOD_ALIBI == fl::kModAlibi && FL_MOD_SOFTCAP == fl::kModSoftcap,
+              "score_mod values");
+static_assert(FL_EPI_RMSNORM == fl::kEpiRms && FL_EPI_GATE_SIGMOID == fl::kEpiGate, "epilogue bits");
+
+namespace {
+
+thread_local char g_detail[384] = "";
+
+fl_status fail(fl_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_detail, sizeof(g_detail), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+struct Tuning {
+  int bm = 0, bn = 0, order = -1;
+} g_tuning;
+
+int elem_size(int dtype) { return dtype == FL_BF16 ? 2 : 4; }
+
+// Common checks of a [B, G, H, S, D] data tensor (q, k, v, out, gate, q2, k2).
+fl_status check_data_tensor(const fl_tensor* t, const char* name, int want_dtype, const int64_t want[5]) {
+  if (t == nullptr || t->ptr == nullptr) return fail(FL_ERR_NULL, "%s is NULL", name);
+  if (t->dtype != want_dtype) return fail(FL_ERR_DTYPE, "%s has dtype %d, expected %d", name, t->dtype, want_dtype);
+  for (int a = 0; a < 5; ++a)
+    if (t->size[a] != want[a])
+      return fail(FL_ERR_SHAPE, "%s size[%d] = %lld, expected %lld", name, a, (long long)t->size[a],
+                  (long long)want[a]);
+  if (t->stride[4] != 1) return fail(FL_ERR_STRIDE, "%s innermost stride must be 1", name);
+  const int es = elem_size(t->dtype);
+  if (((uintptr_t)t->ptr) % 16 != 0) return fail(FL_ERR_ALIGN, "%s base pointer not 16-byte aligned", name);
+  for (int a = 0; a < 4; ++a) {
+    if (t->stride[a] < 0) return fail(FL_ERR_STRIDE, "%s stride[%d] negative", name, a);
+    if (t->size[a] > 1 && t->stride[a] == 0) return fail(FL_ERR_STRIDE, "%s stride[%d] is 0 (no broadcast here)", name, a);
+    if (t->size[a] > 1 && (t->stride[a] * es) % 16 != 0)
+      return fail(FL_ERR_ALIGN, "%s stride[%d] not a multiple of 16 bytes", name, a);
+  }
+  return FL_OK;
+}
+
+fl::View make_view(const fl_tensor* t) {
+  fl::View v;
+  v.ptr = t->ptr;
+  v.sb = t->size[0] > 1 ? t->stride[0] : 0;
+  v.sg = t->size[1] > 1 ? t->stride[1] : 0;
+  v.sh = t->size[2] > 1 ? t->stride[2] : 0;
+  v.ss = t->size[3] > 1 ? t->stride[3] : 0;
+  return v;
+}
+
+struct Registry {
+  const fl::KernelEntry* tab[5];
+  int n[5];
+  Registry() {
+    tab[0] = fl::entries_core(&n[0]);
+    tab[1] = fl::entries_mods(&n[1]);
+    tab[2] = fl::entries_evo(&n[2]);
+    tab[3] = fl::entries_diff(&n[3]);
+    tab[4] = fl::entries_f32(&n[4]);
+  }
+};
+const Registry& registry() {
+  static Registry r;
+  return r;
+}
+
+// Canonical mask bits: WINDOW implies CAUSAL.
+uint32_t canonical_mask(uint32_t m) { return (m & FL_MASK_WINDOW) ? (m | FL_MASK_CAUSAL) : m; }
+
+fl_status check_desc(const fl_variant_desc* d) {
+  if (d == nullptr) return fail(FL_ERR_NULL, "desc is NULL");
+  if (d->struct_size != sizeof(fl_variant_desc))
+    return fail(FL_ERR_DESC, "desc->struct_size = %u, expected %zu", d->struct_size, sizeof(fl_variant_desc));
+  if (!(d->scale > 0.f) || !std::isfinite(d->scale)) return fail(FL_ERR_DESC, "scale must be finite and > 0");
+  if (d->score_mod > FL_MOD_SOFTCAP) return fail(FL_ERR_DESC, "unknown score_mod %u", d->score_mod);
+  if (d->score_mod == FL_MOD_SOFTCAP && (!(d->softcap > 0.f) || !std::isfinite(d->softcap)))
+    return fail(FL_ERR_DESC, "softcap must be finite and > 0");
+  if (d->mask & ~(uint32_t)(FL_MASK_CAUSAL | FL_MASK_WINDOW | FL_MASK_DOC | FL_MASK_PREFIX))
+    return fail(FL_ERR_DESC, "unknown mask bits 0x%x", d->mask);
+  if ((d->mask & FL_MASK_PREFIX) && (d->mask & (FL_MASK_CAUSAL | FL_MASK_WINDOW)))
+    return fail(FL_ERR_DESC, "FL_MASK_PREFIX excludes FL_MASK_CAUSAL and FL_MASK_WINDOW");
+  if ((d->mask & FL_MASK_WINDOW) && d->window < 0) return fail(FL_ERR_DESC, "window must be >= 0");
+  if ((d->mask & FL_MASK_PREFIX) && d->prefix_len < 0) return fail(FL_ERR_DESC, "prefix_len must be >= 0");
+  if (d->n_bias > 2) return fail(FL_ERR_DESC, "n_bias must be 0..2");
+  if (d->combine > FL_DIFFERENTIAL) return fail(FL_ERR_DESC, "unknown combine %u", d->combine);
+  if (d->epilogue & ~(uint32_t)(FL_EPI_RMSNORM | FL_EPI_GATE_SIGMOID))
+    return fail(FL_ERR_DESC, "unknown epilogue bits 0x%x", d->epilogue);
+  if ((d->epilogue & FL_EPI_RMSNORM) && (!(d->rms_eps >= 0.f) || !std::isfinite(d->rms_eps)))
+    return fail(FL_ERR_DESC, "rms_eps must be finite and >= 0");
+  return FL_OK;
+}
+
+const fl::KernelEntry* find_entry(const fl_variant_desc* d, int dtype, int D, int Dv) {
+  const Registry& r = registry();
+  const int mask = (int)canonical_mask(d->mask);
+  const fl::KernelEntry* best = nullptr;
+  for (int t = 0; t < 5; ++t)
+    for (int e = 0; e < r.n[t]; ++e) {
+      const fl::KernelEntry& k = r.tab[t][e];
+      if (k.key.dtype != dtype || k.key.diff != (int)d->combine) continue;
+      if (dtype == FL_F32) {
+        if (D > k.key.D || Dv > k.key.DV) continue;
+        if (best == nullptr || k.key.D < best->key.D) best = &k;   // smallest register budget that fits
+        continue;
+      }
+      if (k.key.D != D || k.key.DV != Dv || k.key.mod != (int)d->score_mod || k.key.mask != mask ||
+          k.key.nbias != (int)d->n_bias || k.key.epi != (int)d->epilogue)
+        continue;
+      // shape preference: tuning request if it exists, else the first listed
+      const bool want = (g_tuning.bm == 0 || k.bm == g_tuning.bm) && (g_tuning.bn == 0 || k.key.bn == g_tuning.bn);
+      if (best == nullptr) best = &k;
+      else {
+        const bool best_want = (g_tuning.bm == 0 || best->bm == g_tuning.bm) && (g_tuning.bn == 0 || best->key.bn == g_tuning.bn);
+        if (want && !best_want) best = &k;
+      }
+    }
+  return best;
+}
+
+size_t workspace_bytes(int64_t B, int64_t Sq, int64_t Sk, uint32_t mask) {
+  if (!(mask & FL_MASK_DOC)) return 0;
+  const int64_t nq = (Sq + fl::kSumBlock - 1) / fl::kSumBlock, nk = (Sk + fl::kSumBlock - 1) / fl::kSumBlock;
+  return (size_t)(B * (nq + nk)) * sizeof(int2);
+}
+
+// (min, max) of the document ids of each block of 32 tokens: one wave per block.
+__global__ void doc_summary_kernel(const int32_t* __restrict__ ids, int2* __restrict__ sum, int S, int nblk,
+                                   int total) {
+  const int w = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int lane = threadIdx.x & 63;
+  if (w >= total) return;
+  const int b = w / nblk, blk = w % nblk;
+  const int j = blk * fl::kSumBlock + (lane & 31);
+  const int jc = j < S ? j : S - 1;
+  int lo = ids[(int64_t)b * S + jc], hi = lo;
+#pragma unroll
+  for (int o = 16; o >= 1; o >>= 1) {
+    lo = min(lo, __shfl_xor(lo, o));
+    hi = max(hi, __shfl_xor(hi, o));
+  }
+  if (lane == 0) sum[w] = make_int2(lo, hi);
+}
+
+// Degenerate Sk == 0: every row is fully masked, so out = 0 and lse = -inf.
+__global__ void empty_keys_kernel(fl::View out, int out_f32, float* lse, int64_t lse_sb, int64_t lse_sg,
+                                  int64_t lse_sh, int G, int H, int Sq, int Dv, int n_lse_g, int64_t total) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int i = (int)(idx % Sq);
+  const int h = (int)((idx / Sq) % H);
+  const int g = (int)((idx / ((int64_t)Sq * H)) % G);
+  const int b = (int)(idx / ((int64_t)Sq * H * G));
+  const int64_t o = b * out.sb + g * out.sg + h * out.sh + (int64_t)i * out.ss;
+  for (int c = 0; c < Dv; ++c) {
+    if (out_f32) ((float*)out.ptr)[o + c] = 0.f;
+    else ((uint16_t*)out.ptr)[o + c] = 0;
+  }
+  if (lse != nullptr)
+    for (int s = 0; s < n_lse_g; ++s)
+      lse[b * lse_sb + (int64_t)(g * n_lse_g + s) * lse_sg + h * lse_sh + i] = -INFINITY;
+}
+
+}  // namespace
+
+extern "C" {
+
+uint32_t fl_version(void) { return (1u << 16) | 0u; }
+
+const char* fl_strerror(fl_status s) {
+  switch (s) {
+    case FL_OK: return "ok";
+    case FL_ERR_NULL: return "required pointer is NULL";
+    case FL_ERR_DTYPE: return "unsupported dtype combination";
+    case FL_ERR_SHAPE: return "inconsistent tensor sizes";
+    case FL_ERR_STRIDE: return "unsupported stride";
+    case FL_ERR_ALIGN: return "pointer or stride not 16-byte aligned";
+    case FL_ERR_UNSUPPORTED: return "no compiled specialisation for this variant / head dim";
+    case FL_ERR_AUX_MISSING: return "descriptor needs an aux tensor that was not given";
+    case FL_ERR_WORKSPACE: return "workspace missing or too small";
+    case FL_ERR_LAUNCH: return "HIP launch failed";
+    case FL_ERR_DESC: return "invalid variant descriptor";
+  }
+  return "unknown status";
+}
+
+const char* fl_last_error_detail(void) { return g_detail; }
+
+fl_status fl_set_tuning(const char* key, int value) {
+  if (key == nullptr) return fail(FL_ERR_NULL, "key is NULL");
+  if (value < 0) return fail(FL_ERR_UNSUPPORTED, "negative tuning value");
+  if (!strcmp(key, "bm")) g_tuning.bm = value;
+  else if (!strcmp(key, "bn")) g_tuning.bn = value;
+  else if (!strcmp(key, "order")) g_tuning.order = value == 0 ? -1 : value - 1;
+  else return fail(FL_ERR_UNSUPPORTED, "unknown tuning key '%s'", key);
+  return FL_OK;
+}
+
+int fl_variant_supported(const fl_variant_desc* desc, int dtype, int D, int Dv) {
+  if (check_desc(desc) != FL_OK) return 0;
+  if (dtype == FL_F32 && (D % 4 != 0 || Dv % 4 != 0 || D <= 0 || Dv <= 0)) return 0;
+  return find_entry(desc, dtype, D, Dv) != nullptr ? 1 : 0;
+}
+
+size_t fl_attn_fwd_workspace_size(const fl_tensor* q, const fl_tensor* k, const fl_variant_desc* desc) {
+  if (q == nullptr || k == nullptr || desc == nullptr) return 0;
+  return workspace_bytes(q->size[0], q->size[3], k->size[3], desc->mask);
+}
+
+fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v, const fl_variant_desc* desc,
+                      const fl_aux* aux, fl_tensor* out, fl_tensor* lse, void* stream_v) {
+  g_detail[0] = 0;
+  fl_status st = check_desc(desc);
+  if (st != FL_OK) return st;
+  if (q == nullptr || k == nullptr || v == nullptr || out == nullptr) return fail(FL_ERR_NULL, "q, k, v or out is NULL");
+  if (aux != nullptr && aux->struct_size != sizeof(fl_aux))
+    return fail(FL_ERR_DESC, "aux->struct_size = %u, expected %zu", aux->struct_size, sizeof(fl_aux));
+
+  const int dtype = q->dtype;
+  if (dtype != FL_BF16 && dtype != FL_F32) return fail(FL_ERR_DTYPE, "q dtype %d not bf16/f32", dtype);
+  const int64_t B = q->size[0], G = q->size[1], H = q->size[2], Sq = q->size[3], D = q->size[4];
+  const int64_t Hkv = k->size[2], Sk = k->size[3], Dv = v->size[4];
+  if (B < 0 || G < 0 || H < 0 || Sq < 0 || Sk < 0 || D <= 0 || Dv <= 0) return fail(FL_ERR_SHAPE, "negative size");
+  if (Sq > 0x7fffff00LL || Sk > 0x7fffff00LL || B * G * H > 0x7fffffffLL) return fail(FL_ERR_SHAPE, "size too large");
+  if (Hkv <= 0 || H % (Hkv > 0 ? Hkv : 1) != 0)
+    if (H != 0) return fail(FL_ERR_SHAPE, "k heads (%lld) must divide q heads (%lld)", (long long)Hkv, (long long)H);
+  const bool empty = (B == 0 || G == 0 || H == 0 || Sq == 0);
+
+  const int64_t qsz[5] = {B, G, H, Sq, D}, ksz[5] = {B, G, Hkv, Sk, D}, vsz[5] = {B, G, Hkv, Sk, Dv},
+                osz[5] = {B, G, H, Sq, Dv};
+  const bool diff = desc->combine == FL_DIFFERENTIAL;
+  if (!empty) {
+    if ((st = check_data_tensor(q, "q", dtype, qsz)) != FL_OK) return st;
+    if (Sk > 0) {
+      if ((st = check_data_tensor(k, "k", dtype, ksz)) != FL_OK) return st;
+      if ((st = check_data_tensor(v, "v", dtype, vsz)) != FL_OK) return st;
+    }
+    if (out->dtype != dtype && out->dtype != FL_F32) return fail(FL_ERR_DTYPE, "out dtype %d", out->dtype);
+    if ((st = check_data_tensor(out, "out", out->dtype, osz)) != FL_OK) return st;
+  }
+  const uint32_t mask = canonical_mask(desc->mask);
+
+  // ---- aux requirements
+  const bool need_aux = desc->score_mod == FL_MOD_ALIBI || (mask & FL_MASK_DOC) || desc->n_bias > 0 || diff ||
+                        (desc->epilogue & FL_EPI_GATE_SIGMOID);
+  if (need_aux && aux == nullptr) return fail(FL_ERR_AUX_MISSING, "descriptor needs aux but aux is NULL");
+  if (desc->score_mod == FL_MOD_ALIBI && aux->alibi_slopes == nullptr) return fail(FL_ERR_AUX_MISSING, "alibi_slopes");
+  if ((mask & FL_MASK_DOC) && (aux->q_doc_ids == nullptr || aux->kv_doc_ids == nullptr))
+    return fail(FL_ERR_AUX_MISSING, "q_doc_ids / kv_doc_ids");
+  if (diff && aux->lambda == nullptr) return fail(FL_ERR_AUX_MISSING, "lambda");
+
+  fl::FwdParams p;
+  memset(&p, 0, sizeof(p));
+  if (!empty) {
+    if (diff && Sk > 0) {
+      if ((st = check_data_tensor(&aux->q2, "q2", dtype, qsz)) != FL_OK) return st == FL_ERR_NULL ? fail(FL_ERR_AUX_MISSING, "q2") : st;
+      if ((st = check_data_tensor(&aux->k2, "k2", dtype, ksz)) != FL_OK) return st == FL_ERR_NULL ? fail(FL_ERR_AUX_MISSING, "k2") : st;
+      p.q2 = make_view(&aux->q2);
+      p.k2 = make_view(&aux->k2);
+    }
+    if (desc->epilogue & FL_EPI_GATE_SIGMOID) {
+      if ((st = check_data_tensor(&aux->gate, "gate", dtype, osz)) != FL_OK) return st == FL_ERR_NULL ? fail(FL_ERR_AUX_MISSING, "gate") : st;
+      p.gate = make_view(&aux->gate);
+    }
+    for (uint32_t nb = 0; nb < desc->n_bias; ++nb) {
+      const fl_tensor* bt = &aux->bias[nb];
+      if (bt->ptr == nullptr) return fail(FL_ERR_AUX_MISSING, "bias[%u]", nb);
+      if (bt->dtype != FL_BF16 && bt->dtype != FL_F32) return fail(FL_ERR_DTYPE, "bias[%u] dtype %d", nb, bt->dtype);
+      const int64_t want[5] = {B, G, H, Sq, Sk};
+      int64_t bs[5];
+      for (int a = 0; a < 5; ++a) {
+        if (bt->size[a] != want[a] && bt->size[a] != 1)
+          return fail(FL_ERR_SHAPE, "bias[%u] size[%d] = %lld, expected %lld or 1", nb, a, (long long)bt->size[a],
+                      (long long)want[a]);
+        bs[a] = (bt->size[a] == 1 && want[a] != 1) ? 0 : bt->stride[a];
+        if (bs[a] < 0) return fail(FL_ERR_STRIDE, "bias[%u] stride[%d] negative", nb, a);
+      }
+      if (Sk > 1 && bs[4] != 1 && bs[4] != 0) return fail(FL_ERR_STRIDE, "bias[%u] innermost stride must be 1 or 0", nb);
+      fl::BiasView& bv = p.bias[nb];
+      bv.ptr = bt->ptr;
+      bv.sb = bs[0]; bv.sg = bs[1]; bv.sh = bs[2]; bv.si = bs[3]; bv.sj = Sk > 1 ? bs[4] : 0;
+      bv.is_f32 = bt->dtype == FL_F32;
+    }
+  }
+
+  // ---- lse
+  const bool want_lse = lse != nullptr && lse->ptr != nullptr;
+  if (want_lse && !empty) {
+    if (lse->dtype != FL_F32) return fail(FL_ERR_DTYPE, "lse must be f32");
+    const int64_t lsz[5] = {B, diff ? 2 * G : G, H, Sq, 1};
+    for (int a = 0; a < 5; ++a)
+      if (lse->size[a] != lsz[a])
+        return fail(FL_ERR_SHAPE, "lse size[%d] = %lld, expected %lld", a, (long long)lse->size[a], (long long)lsz[a]);
+    if (Sq > 1 && lse->stride[3] != 1) return fail(FL_ERR_STRIDE, "lse must be contiguous along Sq");
+    for (int a = 0; a < 3; ++a)
+      if (lse->stride[a] < 0) return fail(FL_ERR_STRIDE, "lse stride[%d] negative", a);
+    if (((uintptr_t)lse->ptr) % 4 != 0) return fail(FL_ERR_ALIGN, "lse pointer not 4-byte aligned");
+  }
+
+  // ---- specialisation lookup (before the empty-problem return so unsupported is reported)
+  if (dtype == FL_F32) {
+    if (D % 4 != 0 || Dv % 4 != 0) return fail(FL_ERR_UNSUPPORTED, "f32 head dims must be multiples of 4");
+    if (!empty && out->dtype != FL_F32) return fail(FL_ERR_DTYPE, "f32 inputs need f32 out");
+  }
+  const fl::KernelEntry* ke = find_entry(desc, dtype, (int)D, (int)Dv);
+  if (ke == nullptr)
+    return fail(FL_ERR_UNSUPPORTED,
+                "no specialisation for dtype=%d D=%lld Dv=%lld score_mod=%u mask=0x%x n_bias=%u combine=%u epilogue=0x%x",
+                dtype, (long long)D, (long long)Dv, desc->score_mod, mask, desc->n_bias, desc->combine, desc->epilogue);
+
+  const size_t ws_need = workspace_bytes(B, Sq, Sk, mask);
+  if (ws_need > 0 && !empty && Sk > 0) {
+    if (aux->workspace == nullptr || aux->workspace_bytes < ws_need)
+      return fail(FL_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", ws_need, aux->workspace ? aux->workspace_bytes : (size_t)0);
+    if (((uintptr_t)aux->workspace) % 8 != 0) return fail(FL_ERR_ALIGN, "workspace not 8-byte aligned");
+  }
+  if (empty) return FL_OK;
+
+  // ---- parameter block
+  p.q = make_view(q);
+  p.out = make_view(out);
+  if (Sk > 0) {
+    p.k = make_view(k);
+    p.v = make_view(v);
+  }
+  if (want_lse) {
+    p.lse = (float*)lse->ptr;
+    p.lse_sb = lse->size[0] > 1 ? lse->stride[0] : 0;
+    p.lse_sg = lse->size[1] > 1 ? lse->stride[1] : 0;
+    p.lse_sh = lse->size[2] > 1 ? lse->stride[2] : 0;
+  }
+  if (aux != nullptr) {
+    p.alibi_slopes = aux->alibi_slopes;
+    p.lambda = aux->lambda;
+    p.rms_weight = aux->rms_weight;
+    p.q_doc = aux->q_doc_ids;
+    p.kv_doc = aux->kv_doc_ids;
+  }
+  p.B = (int)B; p.G = (int)G; p.H = (int)H; p.Hkv = (int)Hkv; p.Sq = (int)Sq; p.Sk = (int)Sk;
+  p.D = (int)D; p.Dv = (int)Dv;
+  p.window = desc->window;
+  p.prefix = desc->prefix_len;
+  p.scale = desc->scale;
+  p.softcap = desc->softcap;
+  p.rms_eps = desc->rms_eps;
+  p.out_f32 = out->dtype == FL_F32;
+  p.mod = (int)desc->score_mod;
+  p.mask = (int)mask;
+  p.n_bias = (int)desc->n_bias;
+  p.epi = (int)desc->epilogue;
+  p.n_qtiles = (int)((Sq + ke->bm - 1) / ke->bm);
+  const int64_t nbh = B * G * H;
+  const int64_t nblocks = nbh * p.n_qtiles;
+  if (nblocks > 0x7fffffffLL || nbh * Sq > 0x7fffffff00LL) return fail(FL_ERR_SHAPE, "too many workgroups");
+  int order = g_tuning.order >= 0 ? g_tuning.order : 0;
+  if (order == 1 && nbh % 8 != 0) order = 0;
+  p.order = order;
+
+  hipStream_t stream = (hipStream_t)stream_v;
+  if (Sk == 0) {
+    const int64_t total = nbh * Sq;
+    hipLaunchKernelGGL(empty_keys_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, p.out,
+                       p.out_f32, p.lse, p.lse_sb, p.lse_sg, p.lse_sh, p.G, p.H, p.Sq, p.Dv, diff ? 2 : 1, total);
+    hipError_t e0 = hipGetLastError();
+    if (e0 != hipSuccess) return fail(FL_ERR_LAUNCH, "empty-keys launch: %s", hipGetErrorString(e0));
+    return FL_OK;
+  }
+  if (mask & FL_MASK_DOC) {
+    const int nqs = (int)((Sq + fl::kSumBlock - 1) / fl::kSumBlock), nks = (int)((Sk + fl::kSumBlock - 1) / fl::kSumBlock);
+    p.q_sum = (int2*)aux->workspace;
+    p.kv_sum = p.q_sum + B * nqs;
+    const int tq = (int)(B * nqs), tk = (int)(B * nks);
+    hipLaunchKernelGGL(doc_summary_kernel, dim3((tq + 3) / 4), dim3(256), 0, stream, aux->q_doc_ids, p.q_sum, (int)Sq, nqs, tq);
+    hipLaunchKernelGGL(doc_summary_kernel, dim3((tk + 3) / 4), dim3(256), 0, stream, aux->kv_doc_ids, p.kv_sum, (int)Sk, nks, tk);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(FL_ERR_LAUNCH, "doc summary launch: %s", hipGetErrorString(e));
+  }
+  hipError_t e = ke->launch(p, (int)nblocks, stream);
+  if (e != hipSuccess) return fail(FL_ERR_LAUNCH, "kernel launch: %s", hipGetErrorString(e));
+  return FL_OK;
+}
+
+}  // extern "C"

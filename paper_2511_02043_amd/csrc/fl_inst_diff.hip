@@ -1,0 +1,16 @@
+// Differential attention: two softmax streams over one V, subtraction with lambda, optional
+// per-head RMSNorm (differential-attention listing, Sec. 3), bf16.
+#include "fl_registry.hpp"
+namespace fl {
+#define E(D, DV, MASK, EPI) bf16_entry<D, DV, 4, 64, kModNone, MASK, 0, true, EPI>()
+static const KernelEntry kEntries[] = {
+    E(64, 128, kMaskCausal, kEpiRms), E(64, 128, kMaskCausal, 0), E(64, 128, 0, kEpiRms), E(64, 128, 0, 0),
+    E(128, 128, kMaskCausal, kEpiRms), E(128, 128, kMaskCausal, 0),
+    E(64, 64, kMaskCausal, kEpiRms), E(64, 64, kMaskCausal, 0),
+};
+#undef E
+const KernelEntry* entries_diff(int* n) {
+  *n = (int)(sizeof(kEntries) / sizeof(kEntries[0]));
+  return kEntries;
+}
+}  // namespace fl

@@ -1,0 +1,19 @@
+// Score modifications (ALiBi, tanh soft-cap; Eq. 4) and the mask family (sliding window,
+// PrefixLM, document mask; Sec. 4.1 benchmark variants), bf16.
+#include "fl_registry.hpp"
+namespace fl {
+#define E(D, MOD, MASK) bf16_entry<D, D, 4, 64, MOD, MASK, 0, false, 0>()
+constexpr uint32_t CW = kMaskCausal | kMaskWindow;
+static const KernelEntry kEntries[] = {
+    E(64, kModAlibi, 0),   E(64, kModAlibi, kMaskCausal),   E(64, kModSoftcap, 0), E(64, kModSoftcap, kMaskCausal),
+    E(64, kModNone, CW),   E(64, kModNone, CW | kMaskDoc),  E(64, kModNone, kMaskDoc),
+    E(64, kModNone, kMaskCausal | kMaskDoc), E(64, kModNone, kMaskPrefix), E(64, kModNone, kMaskPrefix | kMaskDoc),
+    E(128, kModAlibi, 0),  E(128, kModSoftcap, 0), E(128, kModNone, CW), E(128, kModNone, CW | kMaskDoc),
+    E(128, kModNone, kMaskDoc), E(128, kModNone, kMaskCausal | kMaskDoc), E(128, kModNone, kMaskPrefix),
+};
+#undef E
+const KernelEntry* entries_mods(int* n) {
+  *n = (int)(sizeof(kEntries) / sizeof(kEntries[0]));
+  return kEntries;
+}
+}  // namespace fl

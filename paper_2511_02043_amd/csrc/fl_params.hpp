@@ -1,0 +1,112 @@
+// Kernel-side parameter block and small device helpers shared by every kernel of the library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fl {
+
+// Mask bits / enums mirror include/fl_attn.h (kept numerically identical; checked in fl_api.hip).
+constexpr uint32_t kMaskCausal = 1, kMaskWindow = 2, kMaskDoc = 4, kMaskPrefix = 8;
+constexpr int kModNone = 0, kModAlibi = 1, kModSoftcap = 2;
+constexpr uint32_t kEpiRms = 1, kEpiGate = 2;
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Granularity (rows / keys) of the document-id summaries used by the tile skipper.
+constexpr int kSumBlock = 32;
+
+struct View {            // a [B, G, H, S, D] view: element strides of the four outer axes
+  const void* ptr;
+  int64_t sb, sg, sh, ss;
+};
+
+struct BiasView {        // logical [B, G, H, Sq, Sk]; any stride may be 0 (broadcast)
+  const void* ptr;
+  int64_t sb, sg, sh, si, sj;
+  int32_t is_f32;
+  int32_t pad;
+};
+
+struct FwdParams {
+  View q, k, v, q2, k2, gate;
+  View out;              // ptr is written
+  BiasView bias[2];
+  float* lse;            // may be null
+  int64_t lse_sb, lse_sg, lse_sh;   // element strides of lse [B, G(or 2G), H, Sq]
+  const float* alibi_slopes;
+  const float* lambda;
+  const float* rms_weight;
+  const int32_t* q_doc;  // [B, Sq]
+  const int32_t* kv_doc; // [B, Sk]
+  int2* q_sum;           // [B, ceil(Sq/32)]  (min, max) of q_doc per 32-row block
+  int2* kv_sum;          // [B, ceil(Sk/32)]
+  int32_t B, G, H, Hkv, Sq, Sk;
+  int32_t D, Dv;         // head dims (compile-time in the bf16 kernels, read by the fp32 kernel)
+  int32_t window, prefix;
+  float scale, softcap, rms_eps;
+  int32_t out_f32;       // 1: out is float, 0: out has the input dtype
+  int32_t mod, mask, n_bias, epi;   // runtime copy of the descriptor (fp32 kernel reads these)
+  int32_t n_qtiles;      // ceil(Sq / rows per workgroup)
+  int32_t order;         // workgroup ordering scheme
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+
+// Is score (i, j) masked?  MASK is the set of active mask kinds; the bf16 kernels pass a
+// compile-time constant (the tests fold away), the fp32 kernel a runtime value.
+__device__ __forceinline__ bool is_masked(const uint32_t MASK, int i, int j, int window, int prefix,
+                                          int qdoc, int kdoc) {
+  bool m = false;
+  if ((MASK & kMaskPrefix) != 0) m = m || (j > i && j >= prefix);
+  else if ((MASK & (kMaskCausal | kMaskWindow)) != 0) m = m || (j > i);
+  if ((MASK & kMaskWindow) != 0) m = m || (i - j > window);
+  if ((MASK & kMaskDoc) != 0) m = m || (qdoc != kdoc);
+  return m;
+}
+
+// Key range [lo, hi) that can be visible to any query row in [i_min, i_max] under the
+// positional masks (document masks are handled per tile through the summaries).
+__device__ __forceinline__ void key_range(const uint32_t MASK, int i_min, int i_max, int Sk,
+                                          int window, int prefix, int& lo, int& hi) {
+  lo = 0;
+  hi = Sk;
+  if ((MASK & kMaskPrefix) != 0) {
+    int h = i_max + 1 > prefix ? i_max + 1 : prefix;
+    hi = h < Sk ? h : Sk;
+  } else if ((MASK & (kMaskCausal | kMaskWindow)) != 0) {
+    hi = i_max + 1 < Sk ? i_max + 1 : Sk;
+  }
+  if ((MASK & kMaskWindow) != 0) lo = i_min - window > 0 ? i_min - window : 0;
+}
+
+enum BlockClass : int { kSkip = 0, kFull = 1, kPartial = 2 };
+
+// Classify the block of query rows [q_lo, q_hi] x keys [k_lo, k_hi] (all inclusive, k_hi may
+// exceed Sk - 1 for a ragged tail): kSkip = every score masked, kFull = none masked.
+__device__ __forceinline__ int classify_block(const uint32_t MASK, int q_lo, int q_hi, int k_lo,
+                                              int k_hi, int Sk, int window, int prefix, int2 qs,
+                                              int2 ks) {
+  if (k_lo >= Sk) return kSkip;
+  bool full = k_hi < Sk;
+  const int k_last = k_hi < Sk ? k_hi : Sk - 1;
+  if ((MASK & kMaskPrefix) != 0) {
+    if (k_lo > q_hi && k_lo >= prefix) return kSkip;
+    full = full && (k_last <= q_lo || k_last < prefix);
+  } else if ((MASK & (kMaskCausal | kMaskWindow)) != 0) {
+    if (k_lo > q_hi) return kSkip;
+    full = full && (k_last <= q_lo);
+  }
+  if ((MASK & kMaskWindow) != 0) {
+    if (q_lo - k_last > window) return kSkip;
+    full = full && (q_hi - k_lo <= window);
+  }
+  if ((MASK & kMaskDoc) != 0) {
+    if (qs.y < ks.x || ks.y < qs.x) return kSkip;     // id ranges disjoint: nothing can match
+    full = full && (qs.x == qs.y && ks.x == ks.y && qs.x == ks.x);
+  }
+  return full ? kFull : kPartial;
+}
+
+}  // namespace fl

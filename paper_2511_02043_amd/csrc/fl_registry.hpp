@@ -1,0 +1,62 @@
+// Table of compiled kernel specialisations: the "variant specialisation layer".
+// Each instance translation unit contributes an array of entries; fl_api.hip looks a descriptor
+// up in the concatenation of those arrays.  There is deliberately no generic fallback kernel.
+#pragma once
+#include "fl_kernel_bf16.hpp"
+
+namespace fl {
+
+struct KernelKey {
+  int dtype;        // 1 = bf16, 2 = f32 (values of fl_dtype)
+  int D, DV;        // head dims (f32 entries: the maximum they accept)
+  int mod;          // -1 in f32 entries (runtime)
+  int mask;         // -1 in f32 entries
+  int nbias;        // -1 in f32 entries
+  int diff;
+  int epi;          // -1 in f32 entries
+  int nwaves, bn;   // kernel shape (bf16 entries)
+};
+
+typedef hipError_t (*LaunchFn)(const FwdParams& p, int nblocks, hipStream_t stream);
+
+struct KernelEntry {
+  KernelKey key;
+  int bm;           // query rows per workgroup
+  int lds_bytes;
+  LaunchFn launch;
+};
+
+template <class C>
+hipError_t launch_bf16(const FwdParams& p, int nblocks, hipStream_t stream) {
+  if (C::LDS_BYTES > 48 * 1024) {
+    // Raising the dynamic-LDS limit is per device and sticky; cheap enough to repeat per device.
+    static bool done[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64 || !done[dev]) {
+      e = hipFuncSetAttribute((const void*)fwd_bf16_kernel<C>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              C::LDS_BYTES);
+      if (e != hipSuccess) return e;
+      if (dev >= 0 && dev < 64) done[dev] = true;
+    }
+  }
+  hipLaunchKernelGGL(fwd_bf16_kernel<C>, dim3(nblocks), dim3(C::NT), C::LDS_BYTES, stream, p);
+  return hipGetLastError();
+}
+
+template <int D, int DV, int NWAVES, int BN, int MOD, uint32_t MASK, int NBIAS, bool DIFF, uint32_t EPI>
+constexpr KernelEntry bf16_entry() {
+  typedef Bf16Cfg<D, DV, NWAVES, BN, MOD, MASK, NBIAS, DIFF, EPI> C;
+  return KernelEntry{KernelKey{1, D, DV, MOD, (int)MASK, NBIAS, DIFF ? 1 : 0, (int)EPI, NWAVES, BN}, C::BM,
+                     C::LDS_BYTES, &launch_bf16<C>};
+}
+
+// Each instance file defines one of these.
+const KernelEntry* entries_core(int* n);      // plain / causal, all head dims, tuning shapes
+const KernelEntry* entries_mods(int* n);      // ALiBi / soft-cap / window / prefix / document masks
+const KernelEntry* entries_evo(int* n);       // biases + sigmoid gate
+const KernelEntry* entries_diff(int* n);      // differential two-stream + RMSNorm
+const KernelEntry* entries_f32(int* n);       // fp32 storage
+
+}  // namespace fl

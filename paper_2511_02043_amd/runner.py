@@ -1,0 +1,133 @@
+"""Upload an inputs.Workload to the GPU and call fl_attn_fwd on it (marshalling only).
+
+Used by the GPU tests, the smoke check and the benchmark.  The NumPy layouts of the
+workload (including the Evoformer [B, Nseq, Nres, H, D] storage viewed as [B,G,H,S,D])
+are reproduced on the device, so the kernels see the strides the workload describes.
+"""
+from __future__ import annotations
+
+import dataclasses
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+from . import binding as fb
+
+
+def to_device(x: np.ndarray, dtype: torch.dtype, device) -> torch.Tensor:
+    """Copy to the device keeping the stride ORDER of `x` (dense in its own axis order)."""
+    order = sorted(range(x.ndim), key=lambda a: (-abs(x.strides[a]), a))
+    xp = np.ascontiguousarray(np.transpose(x, order))
+    t = torch.from_numpy(xp).to(device=device, dtype=dtype)
+    inv = [0] * x.ndim
+    for pos, a in enumerate(order):
+        inv[a] = pos
+    return t.permute(inv)
+
+
+def empty_like_layout(ref: torch.Tensor, last: int, dtype: torch.dtype) -> torch.Tensor:
+    """Uninitialised tensor with ref's shape except the last dim, in ref's axis order."""
+    shape = list(ref.shape[:-1]) + [last]
+    order = sorted(range(ref.dim()), key=lambda a: (-ref.stride(a), a))
+    t = torch.empty([shape[a] for a in order], dtype=dtype, device=ref.device)
+    inv = [0] * ref.dim()
+    for pos, a in enumerate(order):
+        inv[a] = pos
+    return t.permute(inv)
+
+
+@dataclasses.dataclass
+class DeviceWorkload:
+    name: str
+    q: torch.Tensor
+    k: torch.Tensor
+    v: torch.Tensor
+    out: torch.Tensor
+    lse: Optional[torch.Tensor]
+    desc: fb.fl_variant_desc
+    aux: Optional[fb.fl_aux]
+    keep: List[torch.Tensor]            # aux tensors kept alive
+    tq: fb.fl_tensor = None
+    tk: fb.fl_tensor = None
+    tv: fb.fl_tensor = None
+    tout: fb.fl_tensor = None
+    tlse: Optional[fb.fl_tensor] = None
+
+    def run(self, stream: int = 0) -> int:
+        return fb.fl_attn_fwd(self.tq, self.tk, self.tv, self.desc, self.aux, self.tout, self.tlse, stream)
+
+    def run_checked(self, stream: int = 0) -> None:
+        fb.check(self.run(stream))
+
+
+def upload(w, out_dtype: str = "f32", device="cuda:0", want_lse: bool = True) -> DeviceWorkload:
+    """Build device tensors, the variant descriptor and aux block for a Workload."""
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    q, k, v = (to_device(x, tdt, device) for x in (w.q, w.k, w.v))
+    B, G, H, Sq, D = q.shape
+    Dv = v.shape[4]
+    odt = torch.float32 if (out_dtype == "f32" or w.dtype == "f32") else tdt
+    out = empty_like_layout(q, Dv, odt)
+    keep: List[torch.Tensor] = []
+    mask = 0
+    if w.causal:
+        mask |= fb.FL_MASK_CAUSAL
+    if w.window is not None:
+        mask |= fb.FL_MASK_WINDOW | fb.FL_MASK_CAUSAL
+    if w.prefix is not None:
+        mask |= fb.FL_MASK_PREFIX
+    if w.q_doc is not None:
+        mask |= fb.FL_MASK_DOC
+    mod = fb.FL_MOD_NONE
+    if w.softcap is not None:
+        mod = fb.FL_MOD_SOFTCAP
+    if w.alibi is not None:
+        if mod != fb.FL_MOD_NONE:
+            raise ValueError("one score_mod at a time")
+        mod = fb.FL_MOD_ALIBI
+    diff = w.q2 is not None
+    epi = (fb.FL_EPI_RMSNORM if w.rmsnorm else 0) | (fb.FL_EPI_GATE_SIGMOID if w.gate is not None else 0)
+    desc = fb.variant_desc(scale=float(w.scale), score_mod=mod, softcap=float(w.softcap or 0.0), mask=mask,
+                           window=int(w.window or 0), prefix_len=int(w.prefix or 0), n_bias=len(w.biases),
+                           combine=fb.FL_DIFFERENTIAL if diff else fb.FL_SINGLE, epilogue=epi,
+                           rms_eps=float(w.rms_eps) if w.rmsnorm else 0.0)
+
+    def dev(x, dt):
+        t = None if x is None else to_device(np.asarray(x), dt, device)
+        if t is not None:
+            keep.append(t)
+        return t
+
+    slopes = dev(w.alibi, torch.float32)
+    qd = dev(w.q_doc, torch.int32)
+    kd = qd if (w.kv_doc is w.q_doc) else dev(w.kv_doc, torch.int32)
+    biases = [dev(b, tdt) for b in w.biases]
+    gate = dev(w.gate, tdt)
+    q2, k2 = dev(w.q2, tdt), dev(w.k2, tdt)
+    lam = dev(w.lam, torch.float32)
+    rmsw = dev(None if w.rms_weight is None else np.asarray(w.rms_weight, np.float32), torch.float32)
+    tq, tk, tv, tout = (fb.tensor_desc(x) for x in (q, k, v, out))
+    ws = None
+    nbytes = fb.fl_attn_fwd_workspace_size(tq, tk, desc)
+    if nbytes:
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        keep.append(ws)
+    need_aux = any(x is not None for x in (slopes, qd, gate, q2, lam, rmsw, ws)) or biases
+    aux = fb.aux_desc(alibi_slopes=slopes, q_doc_ids=qd, kv_doc_ids=kd, biases=biases, gate=gate, q2=q2, k2=k2,
+                      lambda_=lam, rms_weight=rmsw, workspace=ws) if need_aux else None
+    lse = None
+    tlse = None
+    if want_lse:
+        lse = torch.empty((B, 2 * G if diff else G, H, Sq, 1), dtype=torch.float32, device=device)
+        tlse = fb.tensor_desc(lse)
+    return DeviceWorkload(w.name, q, k, v, out, lse, desc, aux, keep, tq, tk, tv, tout, tlse)
+
+
+def lse_to_oracle_layout(dw: DeviceWorkload) -> np.ndarray:
+    """Device lse [B, G or 2G, H, Sq, 1] -> [B,G,H,Sq] or, for differential, [B,2,G,H,Sq]."""
+    l = dw.lse.cpu().numpy()[..., 0]
+    if dw.desc.combine == fb.FL_DIFFERENTIAL:
+        B, G2, H, Sq = l.shape
+        return l.reshape(B, G2 // 2, 2, H, Sq).transpose(0, 2, 1, 3, 4)
+    return l

@@ -1,0 +1,102 @@
+"""The C-ABI library loads and exports every symbol that include/fl_attn.h declares (CPU only)."""
+import ctypes
+import os
+import re
+
+from paper_2511_02043_amd import binding as fb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "fl_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fl_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_functions_are_exported_and_bound():
+    names = declared_functions()
+    assert "fl_attn_fwd" in names and len(names) >= 7
+    L = fb.lib()
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in fl_attn.h but not exported"
+        assert n in fb.EXPORTS and callable(getattr(fb, n)), f"{n} has no Python binding of the same name"
+
+
+def test_struct_layouts_match_the_header(tmp_path):
+    """Compile the header with gcc (it must be plain C) and compare sizes and offsets."""
+    import subprocess
+    src = tmp_path / "sz.c"
+    src.write_text('''#include <stdio.h>
+#include <stddef.h>
+#include "fl_attn.h"
+int main(void) {
+  printf("%zu %zu %zu %zu %zu %zu %zu %zu\\n", sizeof(fl_tensor), sizeof(fl_variant_desc), sizeof(fl_aux),
+         offsetof(fl_tensor, stride), offsetof(fl_variant_desc, rms_eps), offsetof(fl_aux, gate),
+         offsetof(fl_aux, lambda), offsetof(fl_aux, workspace_bytes));
+  return 0;
+}''')
+    exe = tmp_path / "sz"
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                           str(src), "-o", str(exe)])
+    got = [int(x) for x in subprocess.check_output([str(exe)]).split()]
+    want = [ctypes.sizeof(fb.fl_tensor), ctypes.sizeof(fb.fl_variant_desc), ctypes.sizeof(fb.fl_aux),
+            fb.fl_tensor.stride.offset, fb.fl_variant_desc.rms_eps.offset, fb.fl_aux.gate.offset,
+            fb.fl_aux.lambda_.offset, fb.fl_aux.workspace_bytes.offset]
+    assert got == want
+
+
+def test_host_only_calls():
+    assert fb.fl_version() >> 16 == 1
+    assert fb.fl_strerror(fb.FL_OK) == "ok"
+    assert "specialisation" in fb.fl_strerror(fb.FL_ERR_UNSUPPORTED)
+    d = fb.variant_desc(scale=0.125, mask=fb.FL_MASK_CAUSAL)
+    assert fb.fl_variant_supported(d, fb.FL_BF16, 128, 128)
+    assert not fb.fl_variant_supported(d, fb.FL_BF16, 96, 96)
+    assert fb.fl_variant_supported(d, fb.FL_F32, 40, 72)
+    bad = fb.variant_desc(scale=0.125, mask=fb.FL_MASK_CAUSAL | fb.FL_MASK_PREFIX)
+    assert not fb.fl_variant_supported(bad, fb.FL_BF16, 64, 64)
+    assert fb.fl_set_tuning("nonsense", 1) == fb.FL_ERR_UNSUPPORTED
+    assert fb.fl_set_tuning("bm", 0) == fb.FL_OK
+
+
+def test_validation_errors_need_no_gpu():
+    """Descriptor and pointer validation happens before any HIP call."""
+    t = fb.fl_tensor()
+    d = fb.variant_desc(scale=0.125)
+    assert fb.fl_attn_fwd(t, t, t, None, None, t, None) == fb.FL_ERR_NULL
+    d.struct_size = 4
+    assert fb.fl_attn_fwd(t, t, t, d, None, t, None) == fb.FL_ERR_DESC
+    d = fb.variant_desc(scale=-1.0)
+    assert fb.fl_attn_fwd(t, t, t, d, None, t, None) == fb.FL_ERR_DESC
+    assert "scale" in fb.fl_last_error_detail()
+    d = fb.variant_desc(scale=0.125, score_mod=fb.FL_MOD_SOFTCAP, softcap=0.0)
+    assert fb.fl_attn_fwd(t, t, t, d, None, t, None) == fb.FL_ERR_DESC
+    d = fb.variant_desc(scale=0.125)
+    t.dtype = 7
+    t.size[:] = [1, 1, 1, 4, 64]
+    assert fb.fl_attn_fwd(t, t, t, d, None, t, None) == fb.FL_ERR_DTYPE
+    t.dtype = fb.FL_BF16
+    assert fb.fl_attn_fwd(t, t, t, d, None, t, None) == fb.FL_ERR_NULL      # q.ptr is NULL
+    t.ptr = 0x1008
+    t.stride[:] = [256, 256, 256, 64, 1]
+    assert fb.fl_attn_fwd(t, t, t, d, None, t, None) == fb.FL_ERR_ALIGN
+    t.ptr = 0x1000
+    t.stride[4] = 2
+    assert fb.fl_attn_fwd(t, t, t, d, None, t, None) == fb.FL_ERR_STRIDE
+    t.stride[4] = 1
+    t.size[4] = 96
+    assert fb.fl_attn_fwd(t, t, t, d, None, t, None) == fb.FL_ERR_UNSUPPORTED
+    t.size[4] = 64
+    d = fb.variant_desc(scale=0.125, score_mod=fb.FL_MOD_ALIBI)
+    assert fb.fl_attn_fwd(t, t, t, d, None, t, None) == fb.FL_ERR_AUX_MISSING
+    d = fb.variant_desc(scale=0.125, mask=fb.FL_MASK_DOC)
+    a = fb.aux_desc()
+    a.q_doc_ids = a.kv_doc_ids = 0x2000
+    assert fb.fl_attn_fwd(t, t, t, d, a, t, None) == fb.FL_ERR_WORKSPACE
+    k = fb.fl_tensor()
+    k.ptr, k.dtype = 0x1000, fb.FL_BF16
+    k.size[:] = [1, 1, 3, 4, 64]
+    k.stride[:] = [768, 768, 256, 64, 1]
+    d = fb.variant_desc(scale=0.125)
+    assert fb.fl_attn_fwd(t, k, k, d, None, t, None) == fb.FL_ERR_SHAPE      # 3 kv heads vs 1 q head

@@ -1,0 +1,127 @@
+"""GPU parity: HIP path through the C-ABI vs the fp64 CPU oracle, element by element, on the
+same seeded inputs.  Sizes span several tiles and ragged tails; the oracle finishes in seconds."""
+import numpy as np
+import pytest
+
+from paper_2511_02043_amd import inputs
+from tests.gpu_util import run_and_compare
+
+pytestmark = pytest.mark.gpu
+
+
+def as_f32(w):
+    """Same (bf16-representable) values, stored and computed as fp32."""
+    w.dtype = "f32"
+    w.name += "_as_f32"
+    return w
+
+
+# ---- config 1 and the fp32 kernel on every variant ------------------------------------------
+
+def test_c1_plain_f32_exact_config():
+    run_and_compare(inputs.plain_f32())
+
+
+@pytest.mark.parametrize("S,Sk,D", [(200, 333, 64), (65, 31, 40), (1, 70, 128), (130, 1, 16)])
+def test_f32_plain_ragged(S, Sk, D):
+    run_and_compare(inputs.plain_f32(B=2, H=3, S=S, Sk=Sk, D=D))
+
+
+def f32_variants():
+    yield as_f32(inputs.causal_bf16(B=1, H=2, S=150, D=64))
+    yield as_f32(inputs.causal_bf16(B=1, H=4, S=97, D=32, Hkv=2))
+    yield as_f32(inputs.alibi_bf16(B=1, H=4, S=150, D=64))
+    yield as_f32(inputs.softcap_bf16(B=1, H=2, S=150, D=64, qscale=8.0))
+    yield as_f32(inputs.window_doc_bf16(B=2, H=2, S=300, D=64, window=50, lo=10, hi=120))
+    yield as_f32(inputs.differential_bf16(B=1, H=2, S=150, D=64, Dv=128))
+    yield as_f32(inputs.evoformer_bf16(B=1, Nseq=3, Nres=100, H=2, D=32, two_biases=True))
+    w = as_f32(inputs.causal_bf16(B=1, H=2, S=150, D=64, causal=False))
+    w.prefix = 40
+    yield w
+
+
+@pytest.mark.parametrize("w", list(f32_variants()), ids=lambda w: w.name)
+def test_f32_variants(w):
+    run_and_compare(w)
+
+
+# ---- bf16 MFMA kernels --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("D", [128, 64, 32])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("S,Sk", [(300, 300), (64, 257), (257, 64), (1, 1)])
+def test_bf16_plain_causal(D, causal, S, Sk):
+    run_and_compare(inputs.causal_bf16(B=2, H=2, S=S, Sk=Sk, D=D, causal=causal))
+
+
+def test_c2_shrunk_causal_d128():
+    run_and_compare(inputs.causal_bf16(B=1, H=2, S=1024, D=128))
+
+
+def test_c2_shrunk_causal_d64_bf16_out():
+    run_and_compare(inputs.causal_bf16(B=1, H=2, S=1024, D=64), out_dtype="same")
+
+
+def test_gqa():
+    run_and_compare(inputs.causal_bf16(B=1, H=8, S=200, D=64, Hkv=2))
+
+
+def test_c3a_alibi():
+    run_and_compare(inputs.alibi_bf16(B=1, H=4, S=333, D=64))
+
+
+@pytest.mark.parametrize("qscale", [1.0, 8.0])
+def test_c3b_softcap(qscale):
+    run_and_compare(inputs.softcap_bf16(B=1, H=2, S=333, D=64, qscale=qscale))
+
+
+@pytest.mark.parametrize("S,window,lo,hi", [(700, 100, 20, 300), (515, 64, 5, 40), (300, 512, 64, 1024)])
+def test_c3c_window_doc(S, window, lo, hi):
+    run_and_compare(inputs.window_doc_bf16(B=2, H=2, S=S, D=64, window=window, lo=lo, hi=hi))
+
+
+def test_window_only_and_doc_only_and_prefix():
+    w = inputs.window_doc_bf16(B=1, H=2, S=400, D=64, window=70)
+    w.q_doc = w.kv_doc = None
+    run_and_compare(w, label="window_only")
+    w = inputs.window_doc_bf16(B=2, H=2, S=400, D=64, lo=10, hi=150)
+    w.causal, w.window = False, None
+    run_and_compare(w, label="doc_only")
+    w = inputs.causal_bf16(B=1, H=2, S=400, D=64, causal=False)
+    w.prefix = 100
+    run_and_compare(w, label="prefix")
+
+
+def test_fully_masked_rows_and_unsorted_doc_ids():
+    """Rows whose document id matches no key: out = 0, lse = -inf; ids need not be sorted."""
+    w = inputs.window_doc_bf16(B=1, H=2, S=200, D=64, lo=10, hi=60)
+    w.causal, w.window = False, None
+    rng = np.random.Generator(np.random.PCG64(5))
+    q_doc = rng.integers(0, 4, (1, 200)).astype(np.int32)
+    kv_doc = rng.integers(0, 4, (1, 200)).astype(np.int32)
+    q_doc[0, 17] = 99
+    q_doc[0, 64:100] = 77                      # a whole 32-row block with no visible key
+    w.q_doc, w.kv_doc = q_doc, kv_doc
+    run_and_compare(w)
+
+
+def test_c4_differential():
+    run_and_compare(inputs.differential_bf16(B=1, H=2, S=500, D=64, Dv=128))
+
+
+def test_c5_evoformer():
+    run_and_compare(inputs.evoformer_bf16(B=1, Nseq=4, Nres=200, H=4, D=32))
+    run_and_compare(inputs.evoformer_bf16(B=2, Nseq=3, Nres=70, H=2, D=32, two_biases=True))
+
+
+def test_deterministic_run_to_run():
+    import torch
+    from paper_2511_02043_amd import runner
+    dw = runner.upload(inputs.causal_bf16(B=1, H=2, S=700, D=128))
+    dw.run_checked()
+    torch.cuda.synchronize()
+    a = dw.out.clone()
+    dw.out.zero_()
+    dw.run_checked()
+    torch.cuda.synchronize()
+    assert torch.equal(a, dw.out)
