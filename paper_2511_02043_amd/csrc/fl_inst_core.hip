@@ -4,6 +4,7 @@
 namespace fl {
 #define E(D, NW, BN, MASK) bf16_entry<D, D, NW, BN, kModNone, MASK, 0, false, 0>()
 static const KernelEntry kEntries[] = {
+    E(128, 8, 32, 0), E(128, 8, 32, kMaskCausal), E(128, 4, 32, 0), E(128, 4, 32, kMaskCausal),
     E(128, 8, 64, 0), E(128, 8, 64, kMaskCausal), E(128, 4, 64, 0), E(128, 4, 64, kMaskCausal),
     E(64, 8, 64, 0),  E(64, 8, 64, kMaskCausal),  E(64, 4, 64, 0),  E(64, 4, 64, kMaskCausal),
     E(32, 8, 64, 0),  E(32, 8, 64, kMaskCausal),  E(32, 4, 64, 0),  E(32, 4, 64, kMaskCausal),

@@ -1,5 +1,5 @@
 // bf16 attention-variant forward kernel for gfx950: both contractions on bf16 MFMA with fp32
-// accumulation, scores and softmax state in registers, K/V tiles double-buffered in LDS and
+// accumulation, scores and softmax state in registers, K/V tiles ring-buffered in LDS and
 // filled by direct global->LDS loads.
 //
 // Structure (Sec. 3 of the paper describes the fused pass this realises: score tiles, online
@@ -21,7 +21,19 @@
 //   * V^T as the A operand comes from row-major V in LDS through ds_read_b64_tr_b16.
 // Within one 16-key MFMA step the contraction index order is (half, element) -> key
 // 16*ks + 8*(e/4) + 4*half + e%4 for both operands.
+//
+// Software pipeline (single-stream variants).  Iteration n owns tile t0 (scores already in
+// registers, transformed, masked, row max folded into m) and its successor t1:
+//     phase A:  S1 = K(t1) Q^T on the matrix core   ||   P0 = exp2(S0 - m), l += sum P0 on the VALU
+//     phase B:  O += V(t0)^T P0 on the matrix core  ||   transform / mask / row max of S1, m update
+// so the matrix core and the vector ALU of one wave have independent work at the same time, and
+// the two waves that share a SIMD fill each other's gaps.  The running max is only advanced when
+// a row's new maximum exceeds the old one by more than 2^8 (the exponent of P stays bounded by
+// 8), which makes the O rescale a rare, wave-uniform branch; l and the final normalisation use
+// the same reference, so the result is unchanged in real arithmetic.
 #pragma once
+#include <type_traits>
+
 #include "fl_params.hpp"
 
 namespace fl {
@@ -33,9 +45,11 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
-typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((ext_vector_type(2))) int i32x2;
 typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void global_cvoid;
+
+constexpr float kLazyMaxLog2 = 8.f;   // advance the running max only past this gap (log2 units)
 
 __device__ __forceinline__ float half_swap_max(float x) {
   // {x.lo, x.lo}, {x.hi, x.hi} -> max of lanes L and L^32 in every lane
@@ -55,9 +69,10 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 __device__ __forceinline__ float bf16_to_f32(uint16_t u) { return __uint_as_float((uint32_t)u << 16); }
 
 // 16-byte chunk swizzles of the LDS tiles (row r, chunk c of a row of ROW_ELEMS bf16); both are
-// XORs, hence their own inverses.  K is read one 16-byte chunk per lane with 32 consecutive rows
-// per instruction; V is read by the transposing load as 4 rows x 64 bytes per 32 lanes.  Both
-// layouts spread those accesses over all 64 banks.
+// XORs, hence their own inverses, and both depend on r only through bits that are the same for
+// every row a given lane ever touches.  K is read one 16-byte chunk per lane with 32 consecutive
+// rows per instruction; V is read by the transposing load as 4 rows x 64 bytes per 32 lanes.
+// Both layouts spread those accesses over all 64 banks (measured: zero bank-conflict cycles).
 template <int ROW_ELEMS>
 __device__ __forceinline__ int swz_k(int r, int c) {
   constexpr int CH = ROW_ELEMS / 8;
@@ -81,6 +96,8 @@ struct Bf16Cfg {
   // amplifies the bf16 rounding of the probabilities; there P is split into a bf16 high part
   // and a bf16 remainder and the second contraction runs on both.
   static constexpr bool PSPLIT = DIFF_ && (EPI_ & kEpiRms) != 0;
+  static constexpr bool PIPE = !DIFF_;             // two score tiles in flight (see header)
+  static constexpr int WPE = (DIFF_ && DV_ > 64) ? 1 : 2;   // waves per SIMD the registers allow
   static constexpr int NT = NWAVES * 64;
   static constexpr int BM = NWAVES * 32;
   static constexpr int NB = BN / 32;               // 32-key blocks per tile
@@ -89,107 +106,145 @@ struct Bf16Cfg {
   static constexpr int NS = DIFF ? 2 : 1;          // softmax streams
   static constexpr int K_BYTES = BN * D * 2;
   static constexpr int V_BYTES = BN * DV * 2;
-  static constexpr int STAGE_BYTES = NS * K_BYTES + V_BYTES;
-  static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+  static constexpr int K_RING = 0;                 // LDS layout: K ring [2][NS][K_BYTES], V ring [2][V_BYTES]
+  static constexpr int V_RING = 2 * NS * K_BYTES;
+  static constexpr int LDS_BYTES = V_RING + 2 * V_BYTES;
   static constexpr int K_INSTR = K_BYTES / 1024;   // 64-lane x 16-byte direct loads per K tile
   static constexpr int V_INSTR = V_BYTES / 1024;
+  static constexpr int K_ROWS_PI = 64 / (D / 8);   // tile rows covered by one direct-load instruction
+  static constexpr int V_ROWS_PI = 64 / (DV / 8);
+  static_assert(NWAVES % 4 == 0, "the direct-load lane offsets assume NWAVES % 4 == 0");
 };
+
+enum TileClass : int { kTileSkip = 0, kTileFull = 1, kTilePartial = 2 };
 
 template <class C>
-struct WaveState {
-  bf16x8 qf[C::NS][C::KK];                         // Q fragments (B operand)
-  f32x16 oacc[C::NS][C::DVB];                      // O^T accumulators
-  float m_run[C::NS], l_run[C::NS];                // log2-domain running max; per-lane partial sum
-};
+struct Wave {
+  static constexpr int D = C::D, DV = C::DV, NB = C::NB, KK = C::KK, DVB = C::DVB, NS = C::NS;
+  static constexpr bool kPlain = (C::MOD == kModNone && C::NBIAS == 0);
+  typedef f32x16 Scores[C::NB];
+  struct Probs {
+    bf16x8 hi[C::NB][2];
+    bf16x8 lo[C::PSPLIT ? C::NB : 1][2];
+  };
 
-// One tile of work for one wave.  FAST: every block of the tile is fully visible to every row
-// of the wave (no mask arithmetic, no per-block branches).
-template <class C, bool FAST>
-__device__ __forceinline__ void process_tile(WaveState<C>& ws, const FwdParams& p, const unsigned char* st,
-                                             const int (&cls)[C::NB], int j0, int i, int ic, int lane, int b,
-                                             int g, int h, float c_scale, float slope_l2, int qdoc) {
-  constexpr int D = C::D, DV = C::DV, NB = C::NB, KK = C::KK, DVB = C::DVB, NS = C::NS;
-  constexpr uint32_t MASK = C::MASK;
-  constexpr bool kPlain = (C::MOD == kModNone && C::NBIAS == 0);
-  const int half = lane >> 5, col = lane & 31;
-  const unsigned char* lv = st + NS * C::K_BYTES;
+  const FwdParams& p;
+  unsigned char* lds;
+  int lane, half, col;
+  int b, g, h;
+  int i, ic;                    // this lane's query row (unclamped / clamped)
+  int iw;                       // first query row of the wave (uniform)
+  float c_scale, slope_l2;
+  int qdoc;
+  uint32_t ka[C::KK];           // per-lane byte offset of the K fragment of k-step kk (block 0)
+  uint32_t va[C::DVB];          // per-lane byte offset of the V^T fragment of channel block d (key block 0)
+  bf16x8 qf[C::NS][C::KK];
+  f32x16 oacc[C::NS][C::DVB];
+  float m_run[C::NS], l_run[C::NS];
 
-#pragma unroll
-  for (int s = 0; s < NS; ++s) {
-    const unsigned char* lk = st + s * C::K_BYTES;
-    f32x16 sc[NB];
-    // ---- first contraction: S^T = K Q^T
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      const int row = 32 * nb + col;
-      if (FAST || cls[nb] != kSkip) {
-        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        f32x16 acc = zero;
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-          const bf16x8 a = *(const bf16x8*)(lk + row * (D * 2) + swz_k<D>(row, 2 * kk + half) * 16);
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, ws.qf[s][kk], acc, 0, 0, 0);
-        }
-        sc[nb] = acc;
+  __device__ __forceinline__ Wave(const FwdParams& p_, unsigned char* lds_) : p(p_), lds(lds_) {}
+
+  // ---- first contraction of one stream: S^T = K Q^T, K tile at LDS byte offset koff.
+  // The K fragments are read by hand two MFMAs ahead (explicit lgkmcnt waits, LDS returns in
+  // order): the compiler then sees no LDS read in the loop, so it cannot tie one to the
+  // in-flight direct global->LDS loads, and the number of live fragments is fixed.
+  template <int KOFF>
+  __device__ __forceinline__ void qk(Scores& sc, int s) const {
+    constexpr int NF = NB * KK;                    // fragments: (nb, kk)
+    constexpr int PD = 2;
+    constexpr bool kImm = KOFF + (NB - 1) * (32 * D * 2) + (D * 2) * 32 <= 65535;   // fits the 16-bit offset field
+    i32x4 kf[NF];
+    auto issue = [&](int f) {
+      const int kk = f % KK, nb = f / KK;
+      if constexpr (kImm) {
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(kf[f]) : "v"(ka[kk]), "n"(KOFF + nb * (32 * D * 2)) : "memory");
       } else {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sc[nb][r] = -INFINITY;
+        const uint32_t a = ka[kk] + (uint32_t)(KOFF + nb * (32 * D * 2));
+        asm volatile("ds_read_b128 %0, %1" : "=v"(kf[f]) : "v"(a) : "memory");
       }
+    };
+#pragma unroll
+    for (int f = 0; f < PD; ++f) issue(f);
+    f32x16 acc;
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+      if (f + PD < NF) issue(f + PD);
+      const int ahead = (NF - 1 - f) < PD ? (NF - 1 - f) : PD;
+      if (ahead == 2) asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(kf[f]));
+      else if (ahead == 1) asm volatile("s_waitcnt lgkmcnt(1)" : "+v"(kf[f]));
+      else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kf[f]));
+      const int kk = f % KK, nb = f / KK;
+      if (kk == 0) {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        acc = zero;
+      }
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[f]), qf[s][kk], acc, 0, 0, 0);
+      if (kk == KK - 1) sc[nb] = acc;
     }
+  }
 
-    // ---- variant transform in registers (Eq. 4 score_mod, biases, masks)
+  // ---- variant transform (Eq. 4 score_mod, additive biases) of one score register, in place.
+  // Leaves the score in the domain exp_sum() expects: raw for the plain variants (the scale is
+  // folded into the exponent's FMA), log2-scaled otherwise.  j0 is the tile's first key.
+  __device__ __forceinline__ float transform_one(float x, int j0, int nb, int r) const {
+    if constexpr (kPlain) {
+      return x;
+    } else {
+      const int j = j0 + 32 * nb + 4 * half + 8 * (r >> 2) + (r & 3);   // key of register r
+      if constexpr (C::MOD == kModSoftcap) {
+        // cap*tanh(x*scale/cap) in the log2 domain; tanh(y) = 1 - 2/(exp(2y)+1)
+        const float e = fast_exp2(x * (2.f * c_scale / p.softcap));
+        const float cl = p.softcap * kLog2e;
+        x = fmaf(fast_rcp(e + 1.f), -2.f * cl, cl);
+      } else {
+        x *= c_scale;
+      }
+      if constexpr (C::MOD == kModAlibi) x -= slope_l2 * fabsf((float)(i - j));
+#pragma unroll
+      for (int nbias = 0; nbias < C::NBIAS; ++nbias) {
+        const BiasView& bv = p.bias[nbias];
+        const int64_t off = b * bv.sb + g * bv.sg + h * bv.sh + (int64_t)ic * bv.si +
+                            (int64_t)(j < p.Sk ? j : p.Sk - 1) * bv.sj;
+        const float bb = bv.is_f32 ? ((const float*)bv.ptr)[off] : bf16_to_f32(((const uint16_t*)bv.ptr)[off]);
+        x = fmaf(bb, kLog2e, x);
+      }
+      return x;
+    }
+  }
+  __device__ __forceinline__ void transform(Scores& sc, int j0) const {
+    if constexpr (!kPlain) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sc[nb][r] = transform_one(sc[nb][r], j0, nb, r);
+    }
+  }
+
+  // ---- masks of a partially visible tile: hidden scores become -inf (attention listing)
+  __device__ __forceinline__ void mask(Scores& sc, int j0) const {
+    constexpr uint32_t MASK = C::MASK;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-      if (!FAST && cls[nb] == kSkip) continue;
-      const int jb = j0 + 32 * nb + 4 * half;      // key of register r: jb + 8*(r/4) + r%4
-      if constexpr (!kPlain) {
+      const int jb = j0 + 32 * nb + 4 * half;
+      int kd[16];
+      if constexpr ((MASK & kMaskDoc) != 0) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int j = jb + 8 * (r >> 2) + (r & 3);
-          float x = sc[nb][r];
-          if constexpr (C::MOD == kModSoftcap) {
-            // cap*tanh(x*scale/cap) in the log2 domain; tanh(y) = 1 - 2/(exp(2y)+1)
-            const float e = fast_exp2(x * (2.f * c_scale / p.softcap));
-            const float cl = p.softcap * kLog2e;
-            x = fmaf(fast_rcp(e + 1.f), -2.f * cl, cl);
-          } else {
-            x *= c_scale;
-          }
-          if constexpr (C::MOD == kModAlibi) x -= slope_l2 * fabsf((float)(i - j));
-          sc[nb][r] = x;
-        }
-#pragma unroll
-        for (int nbias = 0; nbias < C::NBIAS; ++nbias) {
-          const BiasView& bv = p.bias[nbias];
-          const int64_t roff = b * bv.sb + g * bv.sg + h * bv.sh + (int64_t)ic * bv.si;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int j = jb + 8 * (r >> 2) + (r & 3);
-            const int64_t off = roff + (int64_t)(j < p.Sk ? j : p.Sk - 1) * bv.sj;
-            const float bb = bv.is_f32 ? ((const float*)bv.ptr)[off] : bf16_to_f32(((const uint16_t*)bv.ptr)[off]);
-            sc[nb][r] = fmaf(bb, kLog2e, sc[nb][r]);
-          }
+          kd[r] = p.kv_doc[(int64_t)b * p.Sk + (j < p.Sk ? j : p.Sk - 1)];
         }
       }
-      if (!FAST && cls[nb] == kPartial) {
-        int kd[16];
-        if constexpr ((MASK & kMaskDoc) != 0) {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int j = jb + 8 * (r >> 2) + (r & 3);
-            kd[r] = p.kv_doc[(int64_t)b * p.Sk + (j < p.Sk ? j : p.Sk - 1)];
-          }
-        }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int j = jb + 8 * (r >> 2) + (r & 3);
-          const bool hide = j >= p.Sk || is_masked(MASK, i, j, p.window, p.prefix, qdoc, (MASK & kMaskDoc) ? kd[r] : 0);
-          if (hide) sc[nb][r] = -INFINITY;
-        }
+      for (int r = 0; r < 16; ++r) {
+        const int j = jb + 8 * (r >> 2) + (r & 3);
+        const bool hide = j >= p.Sk || is_masked(MASK, i, j, p.window, p.prefix, qdoc, (MASK & kMaskDoc) ? kd[r] : 0);
+        if (hide) sc[nb][r] = -INFINITY;
       }
     }
+  }
 
-    // ---- online softmax (Alg. 2 per tile; Sec. 3.4)
+  // ---- row max of the tile in log2 units
+  __device__ __forceinline__ float rowmax(const Scores& sc) const {
     float mx = -INFINITY;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
@@ -197,20 +252,32 @@ __device__ __forceinline__ void process_tile(WaveState<C>& ws, const FwdParams& 
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[nb][r]);
     mx = half_swap_max(mx);
     if constexpr (kPlain) mx *= c_scale;           // scale > 0 (checked on the host)
-    const float m_new = fmaxf(ws.m_run[s], mx);
-    const float m_safe = (!FAST && m_new == -INFINITY) ? 0.f : m_new;
-    if (__builtin_amdgcn_ballot_w64(m_new > ws.m_run[s]) != 0) {   // rescale only when some max moved
-      const float alpha = fast_exp2(ws.m_run[s] - m_safe);
-      ws.l_run[s] *= alpha;
+    return mx;
+  }
+
+  // ---- running-max update of stream s with the next tile's row max (Alg. 2 / Sec. 3.4).
+  // Returns the factor by which l and O of this row shrink (1 when the max is kept).
+  __device__ __forceinline__ float advance_max(int s, float mx) {
+    const float m_old = m_run[s];
+    const float m_new = (mx - m_old > kLazyMaxLog2) ? mx : m_old;   // false for NaN (-inf - -inf)
+    const float alpha = fast_exp2(m_old - (m_new == -INFINITY ? 0.f : m_new));
+    m_run[s] = m_new;
+    l_run[s] *= (m_new != m_old) ? alpha : 1.f;
+    return (m_new != m_old) ? alpha : 1.f;
+  }
+  __device__ __forceinline__ void rescale(int s, float alpha) {
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {          // rare and wave-uniform
 #pragma unroll
       for (int d = 0; d < DVB; ++d)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) ws.oacc[s][d][r] *= alpha;
+        for (int r = 0; r < 16; ++r) oacc[s][d][r] *= alpha;
     }
-    ws.m_run[s] = m_new;
+  }
 
+  // ---- P = exp2(S - m) rounded to bf16 operand fragments; l += row sum of the unrounded P
+  __device__ __forceinline__ void exp_sum(const Scores& sc, int s, Probs& pr) {
+    const float m_safe = m_run[s] == -INFINITY ? 0.f : m_run[s];
     float psum = 0.f;
-    bf16x8 pf[NB][2], pl[C::PSPLIT ? NB : 1][2];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       uint32_t w[8], wl[8];
@@ -229,56 +296,180 @@ __device__ __forceinline__ void process_tile(WaveState<C>& ws, const FwdParams& 
         if constexpr (C::PSPLIT)
           wl[r >> 1] = pack_bf16(p0 - __uint_as_float(w[r >> 1] << 16), p1 - __uint_as_float(w[r >> 1] & 0xFFFF0000u));
       }
-      pf[nb][0] = __builtin_bit_cast(bf16x8, (i32x4){(int)w[0], (int)w[1], (int)w[2], (int)w[3]});
-      pf[nb][1] = __builtin_bit_cast(bf16x8, (i32x4){(int)w[4], (int)w[5], (int)w[6], (int)w[7]});
+      pr.hi[nb][0] = __builtin_bit_cast(bf16x8, (i32x4){(int)w[0], (int)w[1], (int)w[2], (int)w[3]});
+      pr.hi[nb][1] = __builtin_bit_cast(bf16x8, (i32x4){(int)w[4], (int)w[5], (int)w[6], (int)w[7]});
       if constexpr (C::PSPLIT) {
-        pl[nb][0] = __builtin_bit_cast(bf16x8, (i32x4){(int)wl[0], (int)wl[1], (int)wl[2], (int)wl[3]});
-        pl[nb][1] = __builtin_bit_cast(bf16x8, (i32x4){(int)wl[4], (int)wl[5], (int)wl[6], (int)wl[7]});
+        pr.lo[nb][0] = __builtin_bit_cast(bf16x8, (i32x4){(int)wl[0], (int)wl[1], (int)wl[2], (int)wl[3]});
+        pr.lo[nb][1] = __builtin_bit_cast(bf16x8, (i32x4){(int)wl[4], (int)wl[5], (int)wl[6], (int)wl[7]});
       }
     }
-    ws.l_run[s] += psum;
+    l_run[s] += psum;
+  }
 
-    // ---- second contraction: O^T += V^T P^T
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      if (!FAST && cls[nb] == kSkip) continue;
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        // transposing read: each lane supplies the address of 4 channels of one key; the 16-lane
-        // group returns, per lane, 4 keys of one channel.
-        const int s16 = lane & 15;
-        const int key0 = 32 * nb + 16 * ks + 4 * half + (s16 >> 2);
-#pragma unroll
-        for (int d = 0; d < DVB; ++d) {
-          const int ch = 32 * d + 16 * ((lane >> 4) & 1) + 4 * (s16 & 3);   // channel (element) index
-          const int c16 = ch >> 3, within = (ch & 7) * 2;
-          const unsigned char* a0 = lv + key0 * (DV * 2) + swz_v<DV>(key0, c16) * 16 + within;
-          const unsigned char* a1 = lv + (key0 + 8) * (DV * 2) + swz_v<DV>(key0 + 8, c16) * 16 + within;
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)a0);
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)a1);
-          const s16x8 av = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-          const bf16x8 a = __builtin_bit_cast(bf16x8, av);
-          ws.oacc[s][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[nb][ks], ws.oacc[s][d], 0, 0, 0);
-          if constexpr (C::PSPLIT)
-            ws.oacc[s][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pl[nb][ks], ws.oacc[s][d], 0, 0, 0);
-        }
+  // ---- second contraction: O^T += V^T P^T, V tile at LDS byte offset voff.
+  // The transposing LDS reads are issued by hand three fragments ahead of their MFMA, with
+  // explicit lgkmcnt waits (LDS returns in order), so the compiler neither serialises them nor
+  // ties them to the in-flight direct global->LDS loads of the next tile.
+  template <int VOFF>
+  __device__ __forceinline__ void pv(const Probs& pr, int s) {
+    constexpr int NF = NB * 2 * DVB;               // fragments: (nb, ks, d)
+    constexpr int PD = NF < 3 ? NF : 3;            // prefetch distance in fragments
+    constexpr bool kImm = VOFF + C::V_BYTES <= 65535;
+    i32x2 lo[NF], hi[NF];
+    auto issue = [&](int f) {
+      const int d = f % DVB, ks = (f / DVB) % 2, nb = f / (2 * DVB);
+      // "memory": no compiler-tracked LDS access may slip between these reads and their waits
+      if constexpr (kImm) {
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo[f]) : "v"(va[d]), "n"(VOFF + (32 * nb + 16 * ks) * (DV * 2)) : "memory");
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi[f]) : "v"(va[d]), "n"(VOFF + (32 * nb + 16 * ks + 8) * (DV * 2)) : "memory");
+      } else {
+        const uint32_t a = va[d] + (uint32_t)(VOFF + (32 * nb + 16 * ks) * (DV * 2));
+        asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo[f]) : "v"(a) : "memory");
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi[f]) : "v"(a), "n"(8 * DV * 2) : "memory");
       }
+    };
+#pragma unroll
+    for (int f = 0; f < PD; ++f) issue(f);
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+      if (f + PD < NF) issue(f + PD);
+      const int ahead = (NF - 1 - f) < PD ? (NF - 1 - f) : PD;     // fragments still allowed in flight
+      if (ahead == 3) asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(lo[f]), "+v"(hi[f]));
+      else if (ahead == 2) asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(lo[f]), "+v"(hi[f]));
+      else if (ahead == 1) asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(lo[f]), "+v"(hi[f]));
+      else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(lo[f]), "+v"(hi[f]));
+      const int d = f % DVB, ks = (f / DVB) % 2, nb = f / (2 * DVB);
+      const i32x4 av = {lo[f][0], lo[f][1], hi[f][0], hi[f][1]};
+      const bf16x8 a = __builtin_bit_cast(bf16x8, av);
+      oacc[s][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pr.hi[nb][ks], oacc[s][d], 0, 0, 0);
+      if constexpr (C::PSPLIT)
+        oacc[s][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pr.lo[nb][ks], oacc[s][d], 0, 0, 0);
     }
   }
-}
+
+  // ---- one probability pair: p = exp2(s - m), running row sum, bf16 pair (and remainder)
+  __device__ __forceinline__ void exp_pair(const Scores& sc, int nb, int r, float m_safe, float& psum, uint32_t& w,
+                                           uint32_t& wl) const {
+    float p0, p1;
+    if constexpr (kPlain) {
+      p0 = fast_exp2(fmaf(sc[nb][r], c_scale, -m_safe));
+      p1 = fast_exp2(fmaf(sc[nb][r + 1], c_scale, -m_safe));
+    } else {
+      p0 = fast_exp2(sc[nb][r] - m_safe);
+      p1 = fast_exp2(sc[nb][r + 1] - m_safe);
+    }
+    psum += p0 + p1;
+    w = pack_bf16(p0, p1);
+    if constexpr (C::PSPLIT) wl = pack_bf16(p0 - __uint_as_float(w << 16), p1 - __uint_as_float(w & 0xFFFF0000u));
+  }
+
+  // ---- phase A of the pipeline, interleaved by construction: after every QK MFMA of the next
+  // tile comes the exponential / sum / convert work of 16/KK scores of the current tile, and a
+  // scheduling barrier keeps that order.
+  template <int KOFF>
+  __device__ __forceinline__ void phase_a(Scores& nxt, const Scores& cur, Probs& pr) {
+    static_assert(!C::PSPLIT && NS == 1, "pipelined path is single-stream");
+    constexpr int NF = NB * KK, PD = 2, PER = 16 / KK;     // PER scores of cur per MFMA (even)
+    const float m_safe = m_run[0] == -INFINITY ? 0.f : m_run[0];
+    float psum = 0.f;
+    uint32_t w[NB][8], wl_unused = 0;
+    i32x4 kf[NF];
+    auto issue = [&](int f) {
+      const int kk = f % KK, nb = f / KK;
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(kf[f]) : "v"(ka[kk]), "n"(KOFF + nb * (32 * D * 2)) : "memory");
+    };
+#pragma unroll
+    for (int f = 0; f < PD; ++f) issue(f);
+    f32x16 acc;
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+      if (f + PD < NF) issue(f + PD);
+      const int ahead = (NF - 1 - f) < PD ? (NF - 1 - f) : PD;
+      if (ahead == 2) asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(kf[f]));
+      else if (ahead == 1) asm volatile("s_waitcnt lgkmcnt(1)" : "+v"(kf[f]));
+      else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kf[f]));
+      const int kk = f % KK, nb = f / KK;
+      if (kk == 0) {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        acc = zero;
+      }
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[f]), qf[0][kk], acc, 0, 0, 0);
+      if (kk == KK - 1) nxt[nb] = acc;
+#pragma unroll
+      for (int e = 0; e < PER; e += 2) {
+        const int idx = f * PER + e;               // score index within the tile: nb * 16 + r
+        exp_pair(cur, idx / 16, idx % 16, m_safe, psum, w[idx / 16][(idx % 16) >> 1], wl_unused);
+        // pins this chunk between the surrounding MFMAs (ordered with the other asm statements)
+        asm volatile("" : "+v"(w[idx / 16][(idx % 16) >> 1]), "+v"(psum));
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      pr.hi[nb][0] = __builtin_bit_cast(bf16x8, (i32x4){(int)w[nb][0], (int)w[nb][1], (int)w[nb][2], (int)w[nb][3]});
+      pr.hi[nb][1] = __builtin_bit_cast(bf16x8, (i32x4){(int)w[nb][4], (int)w[nb][5], (int)w[nb][6], (int)w[nb][7]});
+    }
+    l_run[0] += psum;
+  }
+
+  // ---- phase B: after every PV MFMA of the current tile comes the transform and running max
+  // of 16/(2*DVB) scores of the next tile.  Returns the next tile's row max (log2 units),
+  // valid when that tile is fully visible.
+  template <int VOFF>
+  __device__ __forceinline__ float phase_b(const Probs& pr, Scores& nxt, int j1) {
+    constexpr int NF = NB * 2 * DVB, PD = NF < 3 ? NF : 3, PER = 16 / (2 * DVB);   // PER in {2, 4, 8}
+    i32x2 lo[NF], hi[NF];
+    float mx = -INFINITY;
+    auto issue = [&](int f) {
+      const int d = f % DVB, ks = (f / DVB) % 2, nb = f / (2 * DVB);
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo[f]) : "v"(va[d]), "n"(VOFF + (32 * nb + 16 * ks) * (DV * 2)) : "memory");
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi[f]) : "v"(va[d]), "n"(VOFF + (32 * nb + 16 * ks + 8) * (DV * 2)) : "memory");
+    };
+#pragma unroll
+    for (int f = 0; f < PD; ++f) issue(f);
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+      if (f + PD < NF) issue(f + PD);
+      const int ahead = (NF - 1 - f) < PD ? (NF - 1 - f) : PD;
+      if (ahead == 3) asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(lo[f]), "+v"(hi[f]));
+      else if (ahead == 2) asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(lo[f]), "+v"(hi[f]));
+      else if (ahead == 1) asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(lo[f]), "+v"(hi[f]));
+      else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(lo[f]), "+v"(hi[f]));
+      const int d = f % DVB, ks = (f / DVB) % 2, nb = f / (2 * DVB);
+      const i32x4 av = {lo[f][0], lo[f][1], hi[f][0], hi[f][1]};
+      oacc[0][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pr.hi[nb][ks], oacc[0][d], 0, 0, 0);
+#pragma unroll
+      for (int e = 0; e < PER; e += 2) {
+        const int idx = f * PER + e, tb = idx / 16, r = idx % 16;
+        const float x0 = transform_one(nxt[tb][r], j1, tb, r), x1 = transform_one(nxt[tb][r + 1], j1, tb, r + 1);
+        nxt[tb][r] = x0;
+        nxt[tb][r + 1] = x1;
+        mx = fmaxf(fmaxf(mx, x0), x1);
+        asm volatile("" : "+v"(mx));
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    mx = half_swap_max(mx);
+    if constexpr (kPlain) mx *= c_scale;
+    return mx;
+  }
+};
 
 template <class C>
-__global__ void __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__global__ void __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE)))
 fwd_bf16_kernel(const FwdParams p) {
   constexpr int D = C::D, DV = C::DV, BN = C::BN, NB = C::NB, KK = C::KK, DVB = C::DVB, NS = C::NS;
   constexpr uint32_t MASK = C::MASK;
+  typedef Wave<C> W;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int half = lane >> 5;
-  const int col = lane & 31;
+  W w(p, lds_raw);
+  w.lane = lane;
+  w.half = lane >> 5;
+  w.col = lane & 31;
 
   // ---- logical grid decode (Sec. 3.6): 1-D launch -> (b, g, h, q-tile)
   const int nq = p.n_qtiles;
@@ -286,7 +477,7 @@ fwd_bf16_kernel(const FwdParams p) {
   int qt, bh;
   if (p.order == 1) {
     // XCD-aware: consecutive workgroup ids go round-robin to the 8 XCDs; give each XCD whole
-    // (b, g, h) problems so a head's K/V stay in one L2.  Needs (B*G*H) % 8 == 0 (host checks).
+    // (b, g, h) problems so that a head's K/V stay in one L2 (host checks (B*G*H) % 8 == 0).
     const int xcd = bid & 7;
     const int idx = bid >> 3;
     bh = (idx / nq) * 8 + xcd;
@@ -301,37 +492,49 @@ fwd_bf16_kernel(const FwdParams p) {
   const int hk = h / (p.H / p.Hkv);
   const int i0 = qt * C::BM;                       // first query row of the workgroup
   const int iw = i0 + wave * 32;                   // first query row of the wave
-  const int i = iw + col;                          // this lane's query row
+  const int i = iw + w.col;                        // this lane's query row
   const int ic = i < p.Sq ? i : p.Sq - 1;
+  w.b = b; w.g = g; w.h = h; w.i = i; w.ic = ic; w.iw = iw;
 
-  WaveState<C> ws;
   {
     const uint16_t* qp = (const uint16_t*)p.q.ptr + b * p.q.sb + g * p.q.sg + h * p.q.sh + (int64_t)ic * p.q.ss;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) ws.qf[0][kk] = *(const bf16x8*)(qp + 16 * kk + 8 * half);
+    for (int kk = 0; kk < KK; ++kk) w.qf[0][kk] = *(const bf16x8*)(qp + 16 * kk + 8 * w.half);
     if constexpr (C::DIFF) {
       const uint16_t* q2 = (const uint16_t*)p.q2.ptr + b * p.q2.sb + g * p.q2.sg + h * p.q2.sh + (int64_t)ic * p.q2.ss;
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) ws.qf[1][kk] = *(const bf16x8*)(q2 + 16 * kk + 8 * half);
+      for (int kk = 0; kk < KK; ++kk) w.qf[1][kk] = *(const bf16x8*)(q2 + 16 * kk + 8 * w.half);
     }
   }
 #pragma unroll
   for (int s = 0; s < NS; ++s) {
-    ws.m_run[s] = -INFINITY;
-    ws.l_run[s] = 0.f;
+    w.m_run[s] = -INFINITY;
+    w.l_run[s] = 0.f;
 #pragma unroll
     for (int d = 0; d < DVB; ++d)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) ws.oacc[s][d][r] = 0.f;
+      for (int r = 0; r < 16; ++r) w.oacc[s][d][r] = 0.f;
+  }
+  w.c_scale = p.scale * kLog2e;                    // raw score -> log2 domain
+  w.slope_l2 = 0.f;
+  if constexpr (C::MOD == kModAlibi) w.slope_l2 = p.alibi_slopes[h] * kLog2e;
+  w.qdoc = 0;
+  if constexpr ((MASK & kMaskDoc) != 0) w.qdoc = p.q_doc[(int64_t)b * p.Sq + ic];
+
+  // ---- loop-invariant per-lane LDS offsets
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) w.ka[kk] = w.col * (D * 2) + swz_k<D>(w.col, 2 * kk + w.half) * 16;
+  {
+    const int s16 = lane & 15;
+    const int key0 = 4 * w.half + (s16 >> 2);      // row this lane addresses in the transposing read
+#pragma unroll
+    for (int d = 0; d < DVB; ++d) {
+      const int ch = 32 * d + 16 * ((lane >> 4) & 1) + 4 * (s16 & 3);   // first of its 4 channels
+      w.va[d] = key0 * (DV * 2) + swz_v<DV>(key0, ch >> 3) * 16 + (ch & 7) * 2;
+    }
   }
 
-  const float c_scale = p.scale * kLog2e;          // raw score -> log2 domain
-  float slope_l2 = 0.f;
-  if constexpr (C::MOD == kModAlibi) slope_l2 = p.alibi_slopes[h] * kLog2e;
-  int qdoc = 0;
-  if constexpr ((MASK & kMaskDoc) != 0) qdoc = p.q_doc[(int64_t)b * p.Sq + ic];
-
-  // ---- tile skipper: visible key range and document-id summaries
+  // ---- tile skipper (a0): visible key range and document-id summaries
   const int i_last = (i0 + C::BM - 1 < p.Sq ? i0 + C::BM : p.Sq) - 1;
   int k_lo, k_hi;
   key_range(MASK, i0, i_last, p.Sk, p.window, p.prefix, k_lo, k_hi);
@@ -344,9 +547,9 @@ fwd_bf16_kernel(const FwdParams p) {
     const int2* qsum = p.q_sum + (int64_t)b * nqs;
     const int s0 = i0 / kSumBlock;
     qs_wg = qsum[s0];
-    for (int w = 1; w < C::NWAVES; ++w)
-      if (s0 + w < nqs) {
-        const int2 t = qsum[s0 + w];
+    for (int ww = 1; ww < C::NWAVES; ++ww)
+      if (s0 + ww < nqs) {
+        const int2 t = qsum[s0 + ww];
         qs_wg.x = min(qs_wg.x, t.x);
         qs_wg.y = max(qs_wg.y, t.y);
       }
@@ -354,106 +557,182 @@ fwd_bf16_kernel(const FwdParams p) {
   }
   const int2* ksum = (MASK & kMaskDoc) ? p.kv_sum + (int64_t)b * nks : nullptr;
 
-  auto tile_visible = [&](int t) -> bool {         // uniform over the workgroup
-    if constexpr ((MASK & kMaskDoc) != 0) {
-      int2 ks = ksum[min(t * NB, nks - 1)];
+  auto tile_keys = [&](int t) -> int2 {            // document-id range of the keys of tile t
+    int2 ks = ksum[min(t * NB, nks - 1)];
 #pragma unroll
-      for (int u = 1; u < NB; ++u)
-        if (t * NB + u < nks) {
-          const int2 x = ksum[t * NB + u];
-          ks.x = min(ks.x, x.x);
-          ks.y = max(ks.y, x.y);
-        }
-      return classify_block(MASK, i0, i_last, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg, ks) != kSkip;
-    } else {
-      return true;                                 // positional masks are already in [t_lo, t_hi)
+    for (int u = 1; u < NB; ++u)
+      if (t * NB + u < nks) {
+        const int2 x = ksum[t * NB + u];
+        ks.x = min(ks.x, x.x);
+        ks.y = max(ks.y, x.y);
+      }
+    return ks;
+  };
+  auto next_tile = [&](int t) -> int {             // uniform over the workgroup
+    if constexpr ((MASK & kMaskDoc) != 0) {
+      while (t < t_hi && classify_block(MASK, i0, i_last, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg,
+                                        tile_keys(t)) == kSkip)
+        ++t;
+    }
+    return t;                                      // positional masks are already in [t_lo, t_hi)
+  };
+  auto wave_class = [&](int t) -> int {            // uniform over the wave
+    if (t >= t_hi) return kTileSkip;
+    int2 ks = make_int2(0, 0);
+    if constexpr ((MASK & kMaskDoc) != 0) ks = tile_keys(t);
+    const int c = classify_block(MASK, iw, iw + 31, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wave, ks);
+    return __builtin_amdgcn_readfirstlane(c);
+  };
+
+  // ---- direct global -> LDS loads of one K or V tile (a2): every wave instruction moves
+  // 64 x 16 B into 1 KiB of consecutive LDS; the swizzle is applied by choosing which global
+  // chunk each lane fetches, which is the same for every instruction of a lane.  Rows past Sk
+  // are clamped to the last row (their scores are masked, their probabilities exactly 0).
+  const unsigned char* kbase[NS];
+  kbase[0] = (const unsigned char*)((const uint16_t*)p.k.ptr + b * p.k.sb + g * p.k.sg + hk * p.k.sh);
+  if constexpr (C::DIFF)
+    kbase[NS - 1] = (const unsigned char*)((const uint16_t*)p.k2.ptr + b * p.k2.sb + g * p.k2.sg + hk * p.k2.sh);
+  const int64_t kss[2] = {p.k.ss * 2, C::DIFF ? p.k2.ss * 2 : 0};   // row strides in bytes
+  const unsigned char* vbase = (const unsigned char*)((const uint16_t*)p.v.ptr + b * p.v.sb + g * p.v.sg + hk * p.v.sh);
+  const int64_t vss = p.v.ss * 2;
+  const int kr_lane = lane / (D / 8), vr_lane = lane / (DV / 8);     // row within an instruction
+  const uint32_t kc_lane = swz_k<D>(kr_lane + wave * C::K_ROWS_PI, lane % (D / 8)) * 16;
+  const uint32_t vc_lane = swz_v<DV>(vr_lane + wave * C::V_ROWS_PI, lane % (DV / 8)) * 16;
+
+  auto load_rows = [&](const unsigned char* base, int64_t stride, int j0, int n_instr, int rows_pi, int r_lane,
+                       uint32_t c_lane, int lds_off) {
+    const bool tail = j0 + BN > p.Sk;              // uniform
+    for (int u = 0; u * C::NWAVES < n_instr; ++u) {
+      const int gi = wave + u * C::NWAVES;         // wave-uniform instruction index
+      if (n_instr % C::NWAVES != 0 && gi >= n_instr) break;
+      lds_void* dst = (lds_void*)(lds_raw + lds_off + gi * 1024);
+      if (!tail) {
+        const unsigned char* rowbase = base + (int64_t)(j0 + gi * rows_pi) * stride;        // uniform
+        const uint32_t voff = (uint32_t)r_lane * (uint32_t)stride + c_lane;
+        __builtin_amdgcn_global_load_lds((global_cvoid*)(rowbase + voff), dst, 16, 0, 0);
+      } else {
+        int jr = j0 + gi * rows_pi + r_lane;
+        jr = jr < p.Sk ? jr : p.Sk - 1;
+        __builtin_amdgcn_global_load_lds((global_cvoid*)(base + (int64_t)jr * stride + c_lane), dst, 16, 0, 0);
+      }
     }
   };
-  auto next_tile = [&](int t) -> int {
-    while (t < t_hi && !tile_visible(t)) ++t;
-    return t;
-  };
-
-  // ---- direct global -> LDS loads of one K/V tile (a2): every wave instruction moves 64 x 16 B
-  // into 1 KiB of consecutive LDS; the swizzle is applied by choosing which global chunk each
-  // lane fetches.  Rows past Sk are clamped to the last row (their scores are masked, and their
-  // probabilities are exactly 0).
-  const uint16_t* kbase[NS];
-  kbase[0] = (const uint16_t*)p.k.ptr + b * p.k.sb + g * p.k.sg + hk * p.k.sh;
-  if constexpr (C::DIFF) kbase[NS - 1] = (const uint16_t*)p.k2.ptr + b * p.k2.sb + g * p.k2.sg + hk * p.k2.sh;
-  const int64_t kss[2] = {p.k.ss, C::DIFF ? p.k2.ss : 0};
-  const uint16_t* vbase = (const uint16_t*)p.v.ptr + b * p.v.sb + g * p.v.sg + hk * p.v.sh;
-
-  auto load_tile = [&](int t, int buf) {
-    unsigned char* st = lds_raw + buf * C::STAGE_BYTES;
-    const int j0 = t * BN;
+  auto load_k = [&](int t, int buf) {
 #pragma unroll
     for (int s = 0; s < NS; ++s)
-#pragma unroll
-      for (int u = 0; u < (C::K_INSTR + C::NWAVES - 1) / C::NWAVES; ++u) {
-        const int gi = wave + u * C::NWAVES;       // wave-uniform instruction index
-        if (C::K_INSTR % C::NWAVES == 0 || gi < C::K_INSTR) {
-          const int slot = gi * 64 + lane;
-          const int r = slot / (D / 8), pc = slot % (D / 8);
-          const int jr = j0 + r < p.Sk ? j0 + r : p.Sk - 1;
-          const uint16_t* src = kbase[s] + (int64_t)jr * kss[s] + 8 * swz_k<D>(r, pc);
-          __builtin_amdgcn_global_load_lds((global_cvoid*)src, (lds_void*)(st + s * C::K_BYTES + gi * 1024), 16, 0, 0);
-        }
-      }
-#pragma unroll
-    for (int u = 0; u < (C::V_INSTR + C::NWAVES - 1) / C::NWAVES; ++u) {
-      const int gi = wave + u * C::NWAVES;
-      if (C::V_INSTR % C::NWAVES == 0 || gi < C::V_INSTR) {
-        const int slot = gi * 64 + lane;
-        const int r = slot / (DV / 8), pc = slot % (DV / 8);
-        const int jr = j0 + r < p.Sk ? j0 + r : p.Sk - 1;
-        const uint16_t* src = vbase + (int64_t)jr * p.v.ss + 8 * swz_v<DV>(r, pc);
-        __builtin_amdgcn_global_load_lds((global_cvoid*)src, (lds_void*)(st + NS * C::K_BYTES + gi * 1024), 16, 0, 0);
-      }
-    }
+      load_rows(kbase[s], kss[s], t * BN, C::K_INSTR, C::K_ROWS_PI, kr_lane, kc_lane,
+                C::K_RING + (buf * NS + s) * C::K_BYTES);
   };
-
-  auto compute_tile = [&](int t, int buf) {
-    const unsigned char* st = lds_raw + buf * C::STAGE_BYTES;
-    const int j0 = t * BN;
-    int cls[NB];
-    bool any = false, all_full = true;
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      int2 ks = make_int2(0, 0);
-      if constexpr ((MASK & kMaskDoc) != 0) ks = ksum[min(t * NB + nb, nks - 1)];
-      cls[nb] = classify_block(MASK, iw, iw + 31, j0 + 32 * nb, j0 + 32 * nb + 31, p.Sk, p.window, p.prefix,
-                               qs_wave, ks);
-      any = any || cls[nb] != kSkip;
-      all_full = all_full && cls[nb] == kFull;
-    }
-    if (all_full) process_tile<C, true>(ws, p, st, cls, j0, i, ic, lane, b, g, h, c_scale, slope_l2, qdoc);
-    else if (any) process_tile<C, false>(ws, p, st, cls, j0, i, ic, lane, b, g, h, c_scale, slope_l2, qdoc);
+  auto load_v = [&](int t, int buf) {
+    load_rows(vbase, vss, t * BN, C::V_INSTR, C::V_ROWS_PI, vr_lane, vc_lane, C::V_RING + buf * C::V_BYTES);
   };
-
-  // ---- main loop over visible key tiles; the next tile streams into the other LDS buffer
-  int t = next_tile(t_lo);
-  if (t < t_hi) load_tile(t, 0);
-  __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): this wave's direct loads have landed
-  __syncthreads();
-  int buf = 0;
-  while (t < t_hi) {
-    const int tn = next_tile(t + 1);
-    if (tn < t_hi) load_tile(tn, buf ^ 1);
-    compute_tile(t, buf);
-    __builtin_amdgcn_s_waitcnt(0x0F70);
+  auto wait_loads_and_sync = [&]() {
+    __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wave's direct loads have landed
     __syncthreads();
-    t = tn;
-    buf ^= 1;
+  };
+
+  typedef std::integral_constant<int, 0> Buf0;
+  typedef std::integral_constant<int, 1> Buf1;
+  if constexpr (C::PIPE) {
+    // ============ pipelined single-stream loop (see the header comment) ============
+    // Inside the workgroup's tile list every wave processes every tile; a tile that a wave
+    // does not need is simply fully masked for it (its probabilities are exactly 0).
+    typename W::Scores sa, sb;                     // the two score tiles in flight
+    typename W::Probs pr;
+    int t0 = next_tile(t_lo);
+    if (t0 < t_hi) {
+      int t1 = next_tile(t0 + 1);
+      load_k(t0, 0);
+      load_v(t0, 0);
+      if (t1 < t_hi) load_k(t1, 1);
+      wait_loads_and_sync();
+      w.template qk<C::K_RING>(sa, 0);
+      w.transform(sa, t0 * BN);
+      float mx = w.rowmax(sa);                     // valid if the tile is fully visible
+      bool full0 = wave_class(t0) == kTileFull;
+      __syncthreads();                             // everyone is done with K ring slot 0
+      // Start of every step: finish the softmax bookkeeping of the current tile.  Only the
+      // (rare) mask branch and the (rare) rescale branch live outside the big basic block.
+      auto settle = [&](typename W::Scores& cur) {
+        if (!full0) {
+          w.mask(cur, t0 * BN);
+          mx = w.rowmax(cur);
+        }
+        w.rescale(0, w.advance_max(0, mx));
+      };
+      // One pipeline step.  cur / nxt hold the scores of t0 / t1; BUF is the ring slot of K(t0)
+      // and V(t0), so K(t1) sits in slot BUF ^ 1.  The last tile takes the same step: its
+      // "next tile" contraction then runs on stale LDS contents and is never used.
+      auto step = [&](auto bufc, typename W::Scores& cur, typename W::Scores& nxt) {
+        constexpr int BUF = decltype(bufc)::value;
+        const int t2 = t1 < t_hi ? next_tile(t1 + 1) : t_hi;
+        const bool full1 = wave_class(t1) == kTileFull;
+        settle(cur);
+        if (t2 < t_hi) load_k(t2, BUF);
+        if (t1 < t_hi) load_v(t1, BUF ^ 1);
+        w.template phase_a<C::K_RING + (BUF ^ 1) * C::K_BYTES>(nxt, cur, pr);
+        mx = w.template phase_b<C::V_RING + BUF * C::V_BYTES>(pr, nxt, t1 * BN);
+        wait_loads_and_sync();
+        t0 = t1;
+        t1 = t2;
+        full0 = full1;
+      };
+      while (true) {
+        step(Buf0(), sa, sb);
+        if (t0 >= t_hi) break;
+        step(Buf1(), sb, sa);
+        if (t0 >= t_hi) break;
+      }
+    }
+  } else {
+    // ============ two-stream (differential) loop: streams share V, one score tile at a time ====
+    typename W::Scores sc;
+    typename W::Probs pr;
+    int t0 = next_tile(t_lo);
+    if (t0 < t_hi) {
+      load_k(t0, 0);
+      load_v(t0, 0);
+    }
+    wait_loads_and_sync();
+    auto step = [&](auto bufc) {
+      constexpr int BUF = decltype(bufc)::value;
+      const int t1 = next_tile(t0 + 1);
+      if (t1 < t_hi) {
+        load_k(t1, BUF ^ 1);
+        load_v(t1, BUF ^ 1);
+      }
+      const int c0 = wave_class(t0);
+      if (c0 != kTileSkip) {
+        w.template qk<C::K_RING + (BUF * NS) * C::K_BYTES>(sc, 0);
+        w.transform(sc, t0 * BN);
+        if (c0 != kTileFull) w.mask(sc, t0 * BN);
+        w.rescale(0, w.advance_max(0, w.rowmax(sc)));
+        w.exp_sum(sc, 0, pr);
+        w.template pv<C::V_RING + BUF * C::V_BYTES>(pr, 0);
+        w.template qk<C::K_RING + (BUF * NS + NS - 1) * C::K_BYTES>(sc, NS - 1);
+        w.transform(sc, t0 * BN);
+        if (c0 != kTileFull) w.mask(sc, t0 * BN);
+        w.rescale(NS - 1, w.advance_max(NS - 1, w.rowmax(sc)));
+        w.exp_sum(sc, NS - 1, pr);
+        w.template pv<C::V_RING + BUF * C::V_BYTES>(pr, NS - 1);
+      }
+      wait_loads_and_sync();
+      t0 = t1;
+    };
+    while (t0 < t_hi) {
+      step(Buf0());
+      if (t0 >= t_hi) break;
+      step(Buf1());
+    }
   }
 
-  // ---- epilogue: normalise by l, combine streams, RMSNorm, gate, store (a7)
+  // ---- epilogue (a7): normalise by l, combine streams, RMSNorm, gate, store
   float inv[NS], lse_v[NS];
 #pragma unroll
   for (int s = 0; s < NS; ++s) {
-    const float lt = half_swap_sum(ws.l_run[s]);
+    const float lt = half_swap_sum(w.l_run[s]);
     inv[s] = lt > 0.f ? 1.f / lt : 0.f;
-    lse_v[s] = lt > 0.f ? ws.m_run[s] * kLn2 + __logf(lt) : -INFINITY;
+    lse_v[s] = lt > 0.f ? w.m_run[s] * kLn2 + __logf(lt) : -INFINITY;
   }
   const float lam = C::DIFF ? p.lambda[h] : 0.f;
   float ssq = 0.f;
@@ -461,9 +740,9 @@ fwd_bf16_kernel(const FwdParams p) {
   for (int d = 0; d < DVB; ++d)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      float x = ws.oacc[0][d][r] * inv[0];
-      if constexpr (C::DIFF) x -= lam * (ws.oacc[NS - 1][d][r] * inv[NS - 1]);
-      ws.oacc[0][d][r] = x;
+      float x = w.oacc[0][d][r] * inv[0];
+      if constexpr (C::DIFF) x -= lam * (w.oacc[NS - 1][d][r] * inv[NS - 1]);
+      w.oacc[0][d][r] = x;
       ssq = fmaf(x, x, ssq);
     }
   float rn = 1.f;
@@ -478,10 +757,10 @@ fwd_bf16_kernel(const FwdParams p) {
     for (int d = 0; d < DVB; ++d)
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
-        const int ch = 32 * d + 8 * r4 + 4 * half;   // 4 consecutive channels ch..ch+3
+        const int ch = 32 * d + 8 * r4 + 4 * w.half;   // 4 consecutive channels ch..ch+3
         float x[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) x[e] = ws.oacc[0][d][4 * r4 + e];
+        for (int e = 0; e < 4; ++e) x[e] = w.oacc[0][d][4 * r4 + e];
         if constexpr ((C::EPI & kEpiRms) != 0) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) x[e] *= rn * (p.rms_weight ? p.rms_weight[ch + e] : 1.f);
@@ -501,7 +780,7 @@ fwd_bf16_kernel(const FwdParams p) {
           *(uint2*)((uint16_t*)p.out.ptr + orow + ch) = make_uint2(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]));
         }
       }
-    if (p.lse != nullptr && half == 0) {
+    if (p.lse != nullptr && w.half == 0) {
 #pragma unroll
       for (int s = 0; s < NS; ++s)
         p.lse[b * p.lse_sb + (int64_t)(C::DIFF ? 2 * g + s : g) * p.lse_sg + h * p.lse_sh + i] = lse_v[s];
