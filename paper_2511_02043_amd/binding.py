@@ -11,7 +11,7 @@ import os
 from typing import Optional, Sequence
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libflattn.so")
+LIB_PATH = os.environ.get("FL_ATTN_LIB") or os.path.join(_HERE, "libflattn.so")
 
 # --- enums (include/fl_attn.h) -----------------------------------------------------------
 FL_OK, FL_ERR_NULL, FL_ERR_DTYPE, FL_ERR_SHAPE, FL_ERR_STRIDE, FL_ERR_ALIGN = 0, 1, 2, 3, 4, 5

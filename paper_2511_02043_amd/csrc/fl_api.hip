@@ -30,7 +30,7 @@ fl_status fail(fl_status st, const char* fmt, ...) {
 }
 
 struct Tuning {
-  int bm = 0, bn = 0, order = -1;
+  int bm = 0, bn = 0, rb = 0, nw = 0, order = -1;
 } g_tuning;
 
 int elem_size(int dtype) { return dtype == FL_BF16 ? 2 : 4; }
@@ -124,12 +124,11 @@ const fl::KernelEntry* find_entry(const fl_variant_desc* d, int dtype, int D, in
           k.key.nbias != (int)d->n_bias || k.key.epi != (int)d->epilogue)
         continue;
       // shape preference: tuning request if it exists, else the first listed
-      const bool want = (g_tuning.bm == 0 || k.bm == g_tuning.bm) && (g_tuning.bn == 0 || k.key.bn == g_tuning.bn);
-      if (best == nullptr) best = &k;
-      else {
-        const bool best_want = (g_tuning.bm == 0 || best->bm == g_tuning.bm) && (g_tuning.bn == 0 || best->key.bn == g_tuning.bn);
-        if (want && !best_want) best = &k;
-      }
+      auto wanted = [](const fl::KernelEntry& e) {
+        return (g_tuning.bm == 0 || e.bm == g_tuning.bm) && (g_tuning.bn == 0 || e.key.bn == g_tuning.bn) &&
+               (g_tuning.rb == 0 || e.key.rb == g_tuning.rb) && (g_tuning.nw == 0 || e.key.nwaves == g_tuning.nw);
+      };
+      if (best == nullptr || (wanted(k) && !wanted(*best))) best = &k;
     }
   return best;
 }
@@ -207,6 +206,8 @@ fl_status fl_set_tuning(const char* key, int value) {
   if (value < 0) return fail(FL_ERR_UNSUPPORTED, "negative tuning value");
   if (!strcmp(key, "bm")) g_tuning.bm = value;
   else if (!strcmp(key, "bn")) g_tuning.bn = value;
+  else if (!strcmp(key, "rb")) g_tuning.rb = value;
+  else if (!strcmp(key, "nw")) g_tuning.nw = value;
   else if (!strcmp(key, "order")) g_tuning.order = value == 0 ? -1 : value - 1;
   else return fail(FL_ERR_UNSUPPORTED, "unknown tuning key '%s'", key);
   return FL_OK;
@@ -368,7 +369,8 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   const int64_t nbh = B * G * H;
   const int64_t nblocks = nbh * p.n_qtiles;
   if (nblocks > 0x7fffffffLL || nbh * Sq > 0x7fffffff00LL) return fail(FL_ERR_SHAPE, "too many workgroups");
-  int order = g_tuning.order >= 0 ? g_tuning.order : 0;
+  // default: XCD-aware order (whole (b, g, h) problems per XCD) whenever the problem count allows it
+  int order = g_tuning.order >= 0 ? g_tuning.order : 1;
   if (order == 1 && nbh % 8 != 0) order = 0;
   p.order = order;
 

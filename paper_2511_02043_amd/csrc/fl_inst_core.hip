@@ -2,13 +2,15 @@
 // tuning knobs can select.
 #include "fl_registry.hpp"
 namespace fl {
-#define E(D, NW, BN, MASK) bf16_entry<D, D, NW, BN, kModNone, MASK, 0, false, 0>()
+#define E(D, NW, RB, BN, WPE, MASK) bf16_entry<D, D, NW, RB, BN, WPE, kModNone, MASK, 0, false, 0>()
+#define BOTH(D, NW, RB, BN, WPE) E(D, NW, RB, BN, WPE, 0), E(D, NW, RB, BN, WPE, kMaskCausal)
 static const KernelEntry kEntries[] = {
-    E(128, 8, 32, 0), E(128, 8, 32, kMaskCausal), E(128, 4, 32, 0), E(128, 4, 32, kMaskCausal),
-    E(128, 8, 64, 0), E(128, 8, 64, kMaskCausal), E(128, 4, 64, 0), E(128, 4, 64, kMaskCausal),
-    E(64, 8, 64, 0),  E(64, 8, 64, kMaskCausal),  E(64, 4, 64, 0),  E(64, 4, 64, kMaskCausal),
-    E(32, 8, 64, 0),  E(32, 8, 64, kMaskCausal),  E(32, 4, 64, 0),  E(32, 4, 64, kMaskCausal),
+    // first entry of a head dim = default shape; the others are selectable with fl_set_tuning
+    BOTH(128, 8, 1, 64, 2), BOTH(128, 4, 1, 64, 2), BOTH(128, 4, 2, 64, 1), BOTH(128, 4, 2, 32, 1),
+    BOTH(64, 8, 1, 64, 2),  BOTH(64, 4, 1, 64, 2),  BOTH(64, 4, 2, 64, 2),  BOTH(64, 8, 2, 64, 2),
+    BOTH(32, 4, 1, 64, 2),  BOTH(32, 4, 2, 64, 2),
 };
+#undef BOTH
 #undef E
 const KernelEntry* entries_core(int* n) {
   *n = (int)(sizeof(kEntries) / sizeof(kEntries[0]));

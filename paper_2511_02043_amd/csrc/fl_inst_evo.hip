@@ -2,7 +2,7 @@
 // per-row key bias) and the sigmoid output gate (Sec. 4.1, "Evoformer"), bf16.
 #include "fl_registry.hpp"
 namespace fl {
-#define E(D, NBIAS, EPI) bf16_entry<D, D, 4, 64, kModNone, 0, NBIAS, false, EPI>()
+#define E(D, NBIAS, EPI) bf16_entry<D, D, 4, 1, 64, 2, kModNone, 0, NBIAS, false, EPI>()
 static const KernelEntry kEntries[] = {
     E(32, 1, kEpiGate), E(32, 2, kEpiGate), E(32, 1, 0), E(32, 2, 0),
     E(64, 1, kEpiGate), E(64, 2, kEpiGate), E(128, 1, kEpiGate), E(128, 2, kEpiGate),

@@ -9,7 +9,7 @@
 // Dv each fit one tile, so the twin matmul needs no loop over them; Sec. 3.6: 1-D launch whose
 // index is decoded in the kernel).
 //
-// Orientation.  Each wave owns 32 query rows and computes the TRANSPOSED score block
+// Orientation.  Each wave owns RB blocks of 32 query rows and computes TRANSPOSED score blocks
 //     S^T[key n][query m] = sum_d K[n][d] Q[m][d]          (v_mfma_f32_32x32x16_bf16)
 // with K as the A operand (one 16-byte LDS read per lane) and Q as the B operand (kept in
 // registers for the whole kernel).  In the 32x32 accumulator layout lane L then holds, for the
@@ -21,6 +21,10 @@
 //   * V^T as the A operand comes from row-major V in LDS through ds_read_b64_tr_b16.
 // Within one 16-key MFMA step the contraction index order is (half, element) -> key
 // 16*ks + 8*(e/4) + 4*half + e%4 for both operands.
+// Every K or V fragment read from LDS feeds the MFMAs of all RB row blocks of the wave: with
+// RB = 2 the LDS traffic per FLOP halves, which is what the LDS bandwidth of a CU needs to keep
+// the matrix cores busy at D = 128 (measured: with RB = 1 the LDS reads alone took 60% of the
+// kernel time).
 //
 // Software pipeline (single-stream variants).  Iteration n owns tile t0 (scores already in
 // registers, transformed, masked, row max folded into m) and its successor t1:
@@ -86,10 +90,10 @@ __device__ __forceinline__ int swz_v(int r, int c) {
   else return c;
 }
 
-template <int D_, int DV_, int NWAVES_, int BN_, int MOD_, uint32_t MASK_, int NBIAS_, bool DIFF_,
-          uint32_t EPI_>
+template <int D_, int DV_, int NWAVES_, int RB_, int BN_, int WPE_, int MOD_, uint32_t MASK_, int NBIAS_,
+          bool DIFF_, uint32_t EPI_>
 struct Bf16Cfg {
-  static constexpr int D = D_, DV = DV_, NWAVES = NWAVES_, BN = BN_, MOD = MOD_, NBIAS = NBIAS_;
+  static constexpr int D = D_, DV = DV_, NWAVES = NWAVES_, RB = RB_, BN = BN_, MOD = MOD_, NBIAS = NBIAS_;
   static constexpr uint32_t MASK = MASK_, EPI = EPI_;
   static constexpr bool DIFF = DIFF_;
   // Differential + RMSNorm divides a nearly cancelling difference by its own rms, which
@@ -97,9 +101,13 @@ struct Bf16Cfg {
   // and a bf16 remainder and the second contraction runs on both.
   static constexpr bool PSPLIT = DIFF_ && (EPI_ & kEpiRms) != 0;
   static constexpr bool PIPE = !DIFF_;             // two score tiles in flight (see header)
-  static constexpr int WPE = (DIFF_ && DV_ > 64) ? 1 : 2;   // waves per SIMD the registers allow
+  static constexpr int WPE = WPE_;                 // waves per SIMD the register budget is set for
+  static constexpr int PD_K = 2;                   // K fragments read ahead of their MFMA
+  static constexpr int PD_V = 3;                   // V^T fragments (two reads each) read ahead
+                                                   // (measured: deeper read-ahead changes nothing)
   static constexpr int NT = NWAVES * 64;
-  static constexpr int BM = NWAVES * 32;
+  static constexpr int WROWS = 32 * RB;            // query rows per wave
+  static constexpr int BM = NWAVES * WROWS;        // query rows per workgroup
   static constexpr int NB = BN / 32;               // 32-key blocks per tile
   static constexpr int KK = D / 16;                // MFMA k-steps of the first contraction
   static constexpr int DVB = DV / 32;              // 32-channel blocks of the output
@@ -114,79 +122,99 @@ struct Bf16Cfg {
   static constexpr int K_ROWS_PI = 64 / (D / 8);   // tile rows covered by one direct-load instruction
   static constexpr int V_ROWS_PI = 64 / (DV / 8);
   static_assert(NWAVES % 4 == 0, "the direct-load lane offsets assume NWAVES % 4 == 0");
+  static_assert(!(DIFF_ && RB_ != 1), "the two-stream path keeps one row block per wave");
 };
 
 enum TileClass : int { kTileSkip = 0, kTileFull = 1, kTilePartial = 2 };
 
 template <class C>
 struct Wave {
-  static constexpr int D = C::D, DV = C::DV, NB = C::NB, KK = C::KK, DVB = C::DVB, NS = C::NS;
+  static constexpr int D = C::D, DV = C::DV, NB = C::NB, KK = C::KK, DVB = C::DVB, NS = C::NS, RB = C::RB;
   static constexpr bool kPlain = (C::MOD == kModNone && C::NBIAS == 0);
-  typedef f32x16 Scores[C::NB];
+  typedef f32x16 Scores[C::RB][C::NB];
   struct Probs {
-    bf16x8 hi[C::NB][2];
-    bf16x8 lo[C::PSPLIT ? C::NB : 1][2];
+    bf16x8 hi[C::RB][C::NB][2];
+    bf16x8 lo[C::PSPLIT ? C::NB : 1][2];           // PSPLIT implies RB == 1
   };
 
   const FwdParams& p;
-  unsigned char* lds;
   int lane, half, col;
   int b, g, h;
-  int i, ic;                    // this lane's query row (unclamped / clamped)
-  int iw;                       // first query row of the wave (uniform)
+  int i[C::RB], ic[C::RB];      // this lane's query rows (unclamped / clamped), one per row block
+  int qdoc[C::RB];
   float c_scale, slope_l2;
-  int qdoc;
   uint32_t ka[C::KK];           // per-lane byte offset of the K fragment of k-step kk (block 0)
   uint32_t va[C::DVB];          // per-lane byte offset of the V^T fragment of channel block d (key block 0)
-  bf16x8 qf[C::NS][C::KK];
-  f32x16 oacc[C::NS][C::DVB];
-  float m_run[C::NS], l_run[C::NS];
+  bf16x8 qf[C::NS][C::RB][C::KK];
+  f32x16 oacc[C::NS][C::RB][C::DVB];
+  float m_run[C::NS][C::RB], l_run[C::NS][C::RB];  // log2-domain running max; per-lane partial sum
 
-  __device__ __forceinline__ Wave(const FwdParams& p_, unsigned char* lds_) : p(p_), lds(lds_) {}
+  __device__ __forceinline__ Wave(const FwdParams& p_) : p(p_) {}
 
-  // ---- first contraction of one stream: S^T = K Q^T, K tile at LDS byte offset koff.
-  // The K fragments are read by hand two MFMAs ahead (explicit lgkmcnt waits, LDS returns in
-  // order): the compiler then sees no LDS read in the loop, so it cannot tie one to the
-  // in-flight direct global->LDS loads, and the number of live fragments is fixed.
-  template <int KOFF>
-  __device__ __forceinline__ void qk(Scores& sc, int s) const {
-    constexpr int NF = NB * KK;                    // fragments: (nb, kk)
-    constexpr int PD = 2;
-    constexpr bool kImm = KOFF + (NB - 1) * (32 * D * 2) + (D * 2) * 32 <= 65535;   // fits the 16-bit offset field
-    i32x4 kf[NF];
-    auto issue = [&](int f) {
-      const int kk = f % KK, nb = f / KK;
-      if constexpr (kImm) {
-        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(kf[f]) : "v"(ka[kk]), "n"(KOFF + nb * (32 * D * 2)) : "memory");
-      } else {
-        const uint32_t a = ka[kk] + (uint32_t)(KOFF + nb * (32 * D * 2));
-        asm volatile("ds_read_b128 %0, %1" : "=v"(kf[f]) : "v"(a) : "memory");
-      }
-    };
-#pragma unroll
-    for (int f = 0; f < PD; ++f) issue(f);
-    f32x16 acc;
-#pragma unroll
-    for (int f = 0; f < NF; ++f) {
-      if (f + PD < NF) issue(f + PD);
-      const int ahead = (NF - 1 - f) < PD ? (NF - 1 - f) : PD;
-      if (ahead == 2) asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(kf[f]));
-      else if (ahead == 1) asm volatile("s_waitcnt lgkmcnt(1)" : "+v"(kf[f]));
-      else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kf[f]));
-      const int kk = f % KK, nb = f / KK;
-      if (kk == 0) {
-        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        acc = zero;
-      }
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[f]), qf[s][kk], acc, 0, 0, 0);
-      if (kk == KK - 1) sc[nb] = acc;
-    }
+  static __device__ __forceinline__ f32x16 zero16() {
+    return f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   }
 
-  // ---- variant transform (Eq. 4 score_mod, additive biases) of one score register, in place.
+  // The LDS fragment reads are issued by hand a few MFMAs ahead, with explicit lgkmcnt waits
+  // (LDS returns in order).  The compiler then sees no LDS read in the loop: it cannot tie one
+  // to the in-flight direct global->LDS loads of the next tile (it would wait for them), and the
+  // number of live fragments is fixed.  "memory" keeps compiler-tracked memory accesses from
+  // slipping between a read and its wait.
+  template <int OFF>
+  __device__ __forceinline__ void read_k(i32x4& dst, uint32_t addr) const {
+    if constexpr (OFF <= 65535) {
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
+    } else {
+      const uint32_t a = addr + (uint32_t)OFF;
+      asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(a) : "memory");
+    }
+  }
+  template <int OFF>
+  __device__ __forceinline__ void read_vt(i32x2& lo, i32x2& hi, uint32_t addr) const {
+    if constexpr (OFF + 8 * DV * 2 <= 65535) {
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(addr), "n"(OFF) : "memory");
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "n"(OFF + 8 * DV * 2) : "memory");
+    } else {
+      const uint32_t a = addr + (uint32_t)OFF;
+      asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(a) : "memory");
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(a), "n"(8 * DV * 2) : "memory");
+    }
+  }
+  template <int N>
+  static __device__ __forceinline__ void wait_k(i32x4& f) {       // allow N younger LDS ops in flight
+    static_assert(N >= 0 && N <= 15, "lgkmcnt is a 4-bit counter");
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(f) : "n"(N));
+  }
+  template <int N>
+  static __device__ __forceinline__ void wait_vt(i32x2& lo, i32x2& hi) {
+    static_assert(N >= 0 && N <= 15, "lgkmcnt is a 4-bit counter");
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(lo), "+v"(hi) : "n"(N));
+  }
+
+  // ---- first contraction of stream s: S^T = K Q^T for all row blocks, K tile at LDS offset KOFF
+  template <int KOFF>
+  __device__ __forceinline__ void qk(Scores& sc, int s) const {
+    constexpr int NF = NB * KK, PD = C::PD_K < NF ? C::PD_K : NF;   // fragments (nb, kk), prefetch distance
+    i32x4 kf[NF];
+    f32x16 acc[RB];
+    static_for<0, PD>([&](auto f) { read_k<KOFF + (f / KK) * (32 * D * 2)>(kf[f], ka[f % KK]); });
+    static_for<0, NF>([&](auto fc) {
+      constexpr int f = fc, kk = f % KK, nb = f / KK;
+      if constexpr (f + PD < NF) read_k<KOFF + ((f + PD) / KK) * (32 * D * 2)>(kf[f + PD], ka[(f + PD) % KK]);
+      wait_k<(NF - 1 - f) < PD ? (NF - 1 - f) : PD>(kf[f]);
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        if (kk == 0) acc[rb] = zero16();
+        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[f]), qf[s][rb][kk], acc[rb], 0, 0, 0);
+        if (kk == KK - 1) sc[rb][nb] = acc[rb];
+      }
+    });
+  }
+
+  // ---- variant transform (Eq. 4 score_mod, additive biases) of one score register.
   // Leaves the score in the domain exp_sum() expects: raw for the plain variants (the scale is
   // folded into the exponent's FMA), log2-scaled otherwise.  j0 is the tile's first key.
-  __device__ __forceinline__ float transform_one(float x, int j0, int nb, int r) const {
+  __device__ __forceinline__ float transform_one(float x, int j0, int rb, int nb, int r) const {
     if constexpr (kPlain) {
       return x;
     } else {
@@ -199,11 +227,11 @@ struct Wave {
       } else {
         x *= c_scale;
       }
-      if constexpr (C::MOD == kModAlibi) x -= slope_l2 * fabsf((float)(i - j));
+      if constexpr (C::MOD == kModAlibi) x -= slope_l2 * fabsf((float)(i[rb] - j));
 #pragma unroll
       for (int nbias = 0; nbias < C::NBIAS; ++nbias) {
         const BiasView& bv = p.bias[nbias];
-        const int64_t off = b * bv.sb + g * bv.sg + h * bv.sh + (int64_t)ic * bv.si +
+        const int64_t off = b * bv.sb + g * bv.sg + h * bv.sh + (int64_t)ic[rb] * bv.si +
                             (int64_t)(j < p.Sk ? j : p.Sk - 1) * bv.sj;
         const float bb = bv.is_f32 ? ((const float*)bv.ptr)[off] : bf16_to_f32(((const uint16_t*)bv.ptr)[off]);
         x = fmaf(bb, kLog2e, x);
@@ -214,9 +242,11 @@ struct Wave {
   __device__ __forceinline__ void transform(Scores& sc, int j0) const {
     if constexpr (!kPlain) {
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
+      for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sc[nb][r] = transform_one(sc[nb][r], j0, nb, r);
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sc[rb][nb][r] = transform_one(sc[rb][nb][r], j0, rb, nb, r);
     }
   }
 
@@ -235,230 +265,210 @@ struct Wave {
         }
       }
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int j = jb + 8 * (r >> 2) + (r & 3);
-        const bool hide = j >= p.Sk || is_masked(MASK, i, j, p.window, p.prefix, qdoc, (MASK & kMaskDoc) ? kd[r] : 0);
-        if (hide) sc[nb][r] = -INFINITY;
-      }
-    }
-  }
-
-  // ---- row max of the tile in log2 units
-  __device__ __forceinline__ float rowmax(const Scores& sc) const {
-    float mx = -INFINITY;
+      for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[nb][r]);
-    mx = half_swap_max(mx);
-    if constexpr (kPlain) mx *= c_scale;           // scale > 0 (checked on the host)
-    return mx;
-  }
-
-  // ---- running-max update of stream s with the next tile's row max (Alg. 2 / Sec. 3.4).
-  // Returns the factor by which l and O of this row shrink (1 when the max is kept).
-  __device__ __forceinline__ float advance_max(int s, float mx) {
-    const float m_old = m_run[s];
-    const float m_new = (mx - m_old > kLazyMaxLog2) ? mx : m_old;   // false for NaN (-inf - -inf)
-    const float alpha = fast_exp2(m_old - (m_new == -INFINITY ? 0.f : m_new));
-    m_run[s] = m_new;
-    l_run[s] *= (m_new != m_old) ? alpha : 1.f;
-    return (m_new != m_old) ? alpha : 1.f;
-  }
-  __device__ __forceinline__ void rescale(int s, float alpha) {
-    if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {          // rare and wave-uniform
-#pragma unroll
-      for (int d = 0; d < DVB; ++d)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[s][d][r] *= alpha;
-    }
-  }
-
-  // ---- P = exp2(S - m) rounded to bf16 operand fragments; l += row sum of the unrounded P
-  __device__ __forceinline__ void exp_sum(const Scores& sc, int s, Probs& pr) {
-    const float m_safe = m_run[s] == -INFINITY ? 0.f : m_run[s];
-    float psum = 0.f;
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      uint32_t w[8], wl[8];
-#pragma unroll
-      for (int r = 0; r < 16; r += 2) {
-        float p0, p1;
-        if constexpr (kPlain) {
-          p0 = fast_exp2(fmaf(sc[nb][r], c_scale, -m_safe));
-          p1 = fast_exp2(fmaf(sc[nb][r + 1], c_scale, -m_safe));
-        } else {
-          p0 = fast_exp2(sc[nb][r] - m_safe);
-          p1 = fast_exp2(sc[nb][r + 1] - m_safe);
+        for (int r = 0; r < 16; ++r) {
+          const int j = jb + 8 * (r >> 2) + (r & 3);
+          const bool hide = j >= p.Sk || is_masked(MASK, i[rb], j, p.window, p.prefix, qdoc[rb], (MASK & kMaskDoc) ? kd[r] : 0);
+          if (hide) sc[rb][nb][r] = -INFINITY;
         }
-        psum += p0 + p1;
-        w[r >> 1] = pack_bf16(p0, p1);
-        if constexpr (C::PSPLIT)
-          wl[r >> 1] = pack_bf16(p0 - __uint_as_float(w[r >> 1] << 16), p1 - __uint_as_float(w[r >> 1] & 0xFFFF0000u));
-      }
-      pr.hi[nb][0] = __builtin_bit_cast(bf16x8, (i32x4){(int)w[0], (int)w[1], (int)w[2], (int)w[3]});
-      pr.hi[nb][1] = __builtin_bit_cast(bf16x8, (i32x4){(int)w[4], (int)w[5], (int)w[6], (int)w[7]});
-      if constexpr (C::PSPLIT) {
-        pr.lo[nb][0] = __builtin_bit_cast(bf16x8, (i32x4){(int)wl[0], (int)wl[1], (int)wl[2], (int)wl[3]});
-        pr.lo[nb][1] = __builtin_bit_cast(bf16x8, (i32x4){(int)wl[4], (int)wl[5], (int)wl[6], (int)wl[7]});
-      }
     }
-    l_run[s] += psum;
   }
 
-  // ---- second contraction: O^T += V^T P^T, V tile at LDS byte offset voff.
-  // The transposing LDS reads are issued by hand three fragments ahead of their MFMA, with
-  // explicit lgkmcnt waits (LDS returns in order), so the compiler neither serialises them nor
-  // ties them to the in-flight direct global->LDS loads of the next tile.
-  template <int VOFF>
-  __device__ __forceinline__ void pv(const Probs& pr, int s) {
-    constexpr int NF = NB * 2 * DVB;               // fragments: (nb, ks, d)
-    constexpr int PD = NF < 3 ? NF : 3;            // prefetch distance in fragments
-    constexpr bool kImm = VOFF + C::V_BYTES <= 65535;
-    i32x2 lo[NF], hi[NF];
-    auto issue = [&](int f) {
-      const int d = f % DVB, ks = (f / DVB) % 2, nb = f / (2 * DVB);
-      // "memory": no compiler-tracked LDS access may slip between these reads and their waits
-      if constexpr (kImm) {
-        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo[f]) : "v"(va[d]), "n"(VOFF + (32 * nb + 16 * ks) * (DV * 2)) : "memory");
-        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi[f]) : "v"(va[d]), "n"(VOFF + (32 * nb + 16 * ks + 8) * (DV * 2)) : "memory");
-      } else {
-        const uint32_t a = va[d] + (uint32_t)(VOFF + (32 * nb + 16 * ks) * (DV * 2));
-        asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo[f]) : "v"(a) : "memory");
-        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi[f]) : "v"(a), "n"(8 * DV * 2) : "memory");
-      }
-    };
+  // ---- row max of the tile in log2 units, one per row block
+  __device__ __forceinline__ void rowmax(const Scores& sc, float (&mx)[C::RB]) const {
 #pragma unroll
-    for (int f = 0; f < PD; ++f) issue(f);
+    for (int rb = 0; rb < RB; ++rb) {
+      float m = -INFINITY;
 #pragma unroll
-    for (int f = 0; f < NF; ++f) {
-      if (f + PD < NF) issue(f + PD);
-      const int ahead = (NF - 1 - f) < PD ? (NF - 1 - f) : PD;     // fragments still allowed in flight
-      if (ahead == 3) asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(lo[f]), "+v"(hi[f]));
-      else if (ahead == 2) asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(lo[f]), "+v"(hi[f]));
-      else if (ahead == 1) asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(lo[f]), "+v"(hi[f]));
-      else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(lo[f]), "+v"(hi[f]));
-      const int d = f % DVB, ks = (f / DVB) % 2, nb = f / (2 * DVB);
-      const i32x4 av = {lo[f][0], lo[f][1], hi[f][0], hi[f][1]};
-      const bf16x8 a = __builtin_bit_cast(bf16x8, av);
-      oacc[s][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pr.hi[nb][ks], oacc[s][d], 0, 0, 0);
-      if constexpr (C::PSPLIT)
-        oacc[s][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pr.lo[nb][ks], oacc[s][d], 0, 0, 0);
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) m = fmaxf(m, sc[rb][nb][r]);
+      m = half_swap_max(m);
+      if constexpr (kPlain) m *= c_scale;          // scale > 0 (checked on the host)
+      mx[rb] = m;
+    }
+  }
+
+  // ---- running-max update of stream s with the next tile's row maxima (Alg. 2 / Sec. 3.4) and
+  // the rescale of l and O that goes with it.  The max of a row only advances when it grows by
+  // more than 2^kLazyMaxLog2, so the O rescale is a rare, wave-uniform branch.
+  __device__ __forceinline__ void advance_max(int s, const float (&mx)[C::RB]) {
+    float alpha[RB];
+    bool any = false;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      const float m_old = m_run[s][rb];
+      const float m_new = (mx[rb] - m_old > kLazyMaxLog2) ? mx[rb] : m_old;   // false for NaN (-inf - -inf)
+      const bool moved = m_new != m_old;
+      alpha[rb] = moved ? fast_exp2(m_old - (m_new == -INFINITY ? 0.f : m_new)) : 1.f;
+      m_run[s][rb] = m_new;
+      l_run[s][rb] *= alpha[rb];
+      any = any || moved;
+    }
+    if (__builtin_amdgcn_ballot_w64(any) != 0) {
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int d = 0; d < DVB; ++d)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[s][rb][d][r] *= alpha[rb];
     }
   }
 
   // ---- one probability pair: p = exp2(s - m), running row sum, bf16 pair (and remainder)
-  __device__ __forceinline__ void exp_pair(const Scores& sc, int nb, int r, float m_safe, float& psum, uint32_t& w,
-                                           uint32_t& wl) const {
+  __device__ __forceinline__ void exp_pair(float s0, float s1, float m_safe, float& psum, uint32_t& w, uint32_t& wl) const {
     float p0, p1;
     if constexpr (kPlain) {
-      p0 = fast_exp2(fmaf(sc[nb][r], c_scale, -m_safe));
-      p1 = fast_exp2(fmaf(sc[nb][r + 1], c_scale, -m_safe));
+      p0 = fast_exp2(fmaf(s0, c_scale, -m_safe));
+      p1 = fast_exp2(fmaf(s1, c_scale, -m_safe));
     } else {
-      p0 = fast_exp2(sc[nb][r] - m_safe);
-      p1 = fast_exp2(sc[nb][r + 1] - m_safe);
+      p0 = fast_exp2(s0 - m_safe);
+      p1 = fast_exp2(s1 - m_safe);
     }
     psum += p0 + p1;
     w = pack_bf16(p0, p1);
     if constexpr (C::PSPLIT) wl = pack_bf16(p0 - __uint_as_float(w << 16), p1 - __uint_as_float(w & 0xFFFF0000u));
   }
 
+  // ---- P = exp2(S - m) rounded to bf16 operand fragments; l += row sum of the unrounded P
+  __device__ __forceinline__ void exp_sum(const Scores& sc, int s, Probs& pr) {
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      const float m_safe = m_run[s][rb] == -INFINITY ? 0.f : m_run[s][rb];
+      float psum = 0.f;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        uint32_t w[8], wl[8];
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) exp_pair(sc[rb][nb][r], sc[rb][nb][r + 1], m_safe, psum, w[r >> 1], wl[r >> 1]);
+        pr.hi[rb][nb][0] = __builtin_bit_cast(bf16x8, (i32x4){(int)w[0], (int)w[1], (int)w[2], (int)w[3]});
+        pr.hi[rb][nb][1] = __builtin_bit_cast(bf16x8, (i32x4){(int)w[4], (int)w[5], (int)w[6], (int)w[7]});
+        if constexpr (C::PSPLIT) {
+          pr.lo[nb][0] = __builtin_bit_cast(bf16x8, (i32x4){(int)wl[0], (int)wl[1], (int)wl[2], (int)wl[3]});
+          pr.lo[nb][1] = __builtin_bit_cast(bf16x8, (i32x4){(int)wl[4], (int)wl[5], (int)wl[6], (int)wl[7]});
+        }
+      }
+      l_run[s][rb] += psum;
+    }
+  }
+
+  // ---- second contraction of stream s: O^T += V^T P^T, V tile at LDS byte offset VOFF
+  template <int VOFF>
+  __device__ __forceinline__ void pv(const Probs& pr, int s) {
+    constexpr int NF = NB * 2 * DVB, PD = NF < C::PD_V ? NF : C::PD_V;   // fragments (nb, ks, d), prefetch distance
+    i32x2 lo[NF], hi[NF];
+    static_for<0, PD>([&](auto f) {
+      read_vt<VOFF + (32 * (f / (2 * DVB)) + 16 * ((f / DVB) % 2)) * (DV * 2)>(lo[f], hi[f], va[f % DVB]);
+    });
+    static_for<0, NF>([&](auto fc) {
+      constexpr int f = fc, d = f % DVB, ks = (f / DVB) % 2, nb = f / (2 * DVB), g2 = f + PD;
+      if constexpr (g2 < NF)
+        read_vt<VOFF + (32 * (g2 / (2 * DVB)) + 16 * ((g2 / DVB) % 2)) * (DV * 2)>(lo[g2], hi[g2], va[g2 % DVB]);
+      wait_vt<2 * ((NF - 1 - f) < PD ? (NF - 1 - f) : PD)>(lo[f], hi[f]);
+      const bf16x8 a = __builtin_bit_cast(bf16x8, (i32x4){lo[f][0], lo[f][1], hi[f][0], hi[f][1]});
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        oacc[s][rb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pr.hi[rb][nb][ks], oacc[s][rb][d], 0, 0, 0);
+        if constexpr (C::PSPLIT)
+          oacc[s][rb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pr.lo[nb][ks], oacc[s][rb][d], 0, 0, 0);
+      }
+    });
+  }
+
   // ---- phase A of the pipeline, interleaved by construction: after every QK MFMA of the next
-  // tile comes the exponential / sum / convert work of 16/KK scores of the current tile, and a
-  // scheduling barrier keeps that order.
+  // tile comes the exponential / sum / convert work of 16/KK scores of the current tile; empty
+  // asm statements and scheduling barriers pin that order.
   template <int KOFF>
   __device__ __forceinline__ void phase_a(Scores& nxt, const Scores& cur, Probs& pr) {
     static_assert(!C::PSPLIT && NS == 1, "pipelined path is single-stream");
-    constexpr int NF = NB * KK, PD = 2, PER = 16 / KK;     // PER scores of cur per MFMA (even)
-    const float m_safe = m_run[0] == -INFINITY ? 0.f : m_run[0];
-    float psum = 0.f;
-    uint32_t w[NB][8], wl_unused = 0;
+    constexpr int NF = NB * KK, PD = C::PD_K < NF ? C::PD_K : NF, PER = 16 / KK;     // PER scores of cur per MFMA (even)
+    float m_safe[RB], psum[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      m_safe[rb] = m_run[0][rb] == -INFINITY ? 0.f : m_run[0][rb];
+      psum[rb] = 0.f;
+    }
+    uint32_t w[RB][NB][8], wl_unused = 0;
     i32x4 kf[NF];
-    auto issue = [&](int f) {
-      const int kk = f % KK, nb = f / KK;
-      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(kf[f]) : "v"(ka[kk]), "n"(KOFF + nb * (32 * D * 2)) : "memory");
-    };
+    f32x16 acc[RB];
+    static_for<0, PD>([&](auto f) { read_k<KOFF + (f / KK) * (32 * D * 2)>(kf[f], ka[f % KK]); });
+    static_for<0, NF>([&](auto fc) {
+      constexpr int f = fc, kk = f % KK, nb = f / KK;
+      if constexpr (f + PD < NF) read_k<KOFF + ((f + PD) / KK) * (32 * D * 2)>(kf[f + PD], ka[(f + PD) % KK]);
+      wait_k<(NF - 1 - f) < PD ? (NF - 1 - f) : PD>(kf[f]);
 #pragma unroll
-    for (int f = 0; f < PD; ++f) issue(f);
-    f32x16 acc;
+      for (int rb = 0; rb < RB; ++rb) {
+        if (kk == 0) acc[rb] = zero16();
+        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[f]), qf[0][rb][kk], acc[rb], 0, 0, 0);
+        if (kk == KK - 1) nxt[rb][nb] = acc[rb];
+        // this MFMA's share of the current tile: scores L .. L+PER-1 in [rb][nb][16] order
 #pragma unroll
-    for (int f = 0; f < NF; ++f) {
-      if (f + PD < NF) issue(f + PD);
-      const int ahead = (NF - 1 - f) < PD ? (NF - 1 - f) : PD;
-      if (ahead == 2) asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(kf[f]));
-      else if (ahead == 1) asm volatile("s_waitcnt lgkmcnt(1)" : "+v"(kf[f]));
-      else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kf[f]));
-      const int kk = f % KK, nb = f / KK;
-      if (kk == 0) {
-        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        acc = zero;
+        for (int e = 0; e < PER; e += 2) {
+          const int L = (f * RB + rb) * PER + e, crb = L / (NB * 16), cnb = (L / 16) % NB, r = L % 16;
+          exp_pair(cur[crb][cnb][r], cur[crb][cnb][r + 1], m_safe[crb], psum[crb], w[crb][cnb][r >> 1], wl_unused);
+          asm volatile("" : "+v"(w[crb][cnb][r >> 1]), "+v"(psum[crb]));
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[f]), qf[0][kk], acc, 0, 0, 0);
-      if (kk == KK - 1) nxt[nb] = acc;
+    });
 #pragma unroll
-      for (int e = 0; e < PER; e += 2) {
-        const int idx = f * PER + e;               // score index within the tile: nb * 16 + r
-        exp_pair(cur, idx / 16, idx % 16, m_safe, psum, w[idx / 16][(idx % 16) >> 1], wl_unused);
-        // pins this chunk between the surrounding MFMAs (ordered with the other asm statements)
-        asm volatile("" : "+v"(w[idx / 16][(idx % 16) >> 1]), "+v"(psum));
+    for (int rb = 0; rb < RB; ++rb) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        pr.hi[rb][nb][0] = __builtin_bit_cast(bf16x8, (i32x4){(int)w[rb][nb][0], (int)w[rb][nb][1], (int)w[rb][nb][2], (int)w[rb][nb][3]});
+        pr.hi[rb][nb][1] = __builtin_bit_cast(bf16x8, (i32x4){(int)w[rb][nb][4], (int)w[rb][nb][5], (int)w[rb][nb][6], (int)w[rb][nb][7]});
       }
-      __builtin_amdgcn_sched_barrier(0);
+      l_run[0][rb] += psum[rb];
     }
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      pr.hi[nb][0] = __builtin_bit_cast(bf16x8, (i32x4){(int)w[nb][0], (int)w[nb][1], (int)w[nb][2], (int)w[nb][3]});
-      pr.hi[nb][1] = __builtin_bit_cast(bf16x8, (i32x4){(int)w[nb][4], (int)w[nb][5], (int)w[nb][6], (int)w[nb][7]});
-    }
-    l_run[0] += psum;
   }
 
   // ---- phase B: after every PV MFMA of the current tile comes the transform and running max
-  // of 16/(2*DVB) scores of the next tile.  Returns the next tile's row max (log2 units),
-  // valid when that tile is fully visible.
+  // of 16/(2*DVB) scores of the next tile.  mx receives the next tile's row maxima (log2
+  // units), valid when that tile is fully visible.
   template <int VOFF>
-  __device__ __forceinline__ float phase_b(const Probs& pr, Scores& nxt, int j1) {
-    constexpr int NF = NB * 2 * DVB, PD = NF < 3 ? NF : 3, PER = 16 / (2 * DVB);   // PER in {2, 4, 8}
+  __device__ __forceinline__ void phase_b(const Probs& pr, Scores& nxt, int j1, float (&mx)[C::RB]) {
+    constexpr int NF = NB * 2 * DVB, PD = NF < C::PD_V ? NF : C::PD_V, PER = 16 / (2 * DVB);   // PER in {2, 4, 8}
     i32x2 lo[NF], hi[NF];
-    float mx = -INFINITY;
-    auto issue = [&](int f) {
-      const int d = f % DVB, ks = (f / DVB) % 2, nb = f / (2 * DVB);
-      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo[f]) : "v"(va[d]), "n"(VOFF + (32 * nb + 16 * ks) * (DV * 2)) : "memory");
-      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi[f]) : "v"(va[d]), "n"(VOFF + (32 * nb + 16 * ks + 8) * (DV * 2)) : "memory");
-    };
 #pragma unroll
-    for (int f = 0; f < PD; ++f) issue(f);
+    for (int rb = 0; rb < RB; ++rb) mx[rb] = -INFINITY;
+    static_for<0, PD>([&](auto f) {
+      read_vt<VOFF + (32 * (f / (2 * DVB)) + 16 * ((f / DVB) % 2)) * (DV * 2)>(lo[f], hi[f], va[f % DVB]);
+    });
+    static_for<0, NF>([&](auto fc) {
+      constexpr int f = fc, d = f % DVB, ks = (f / DVB) % 2, nb = f / (2 * DVB), g2 = f + PD;
+      if constexpr (g2 < NF)
+        read_vt<VOFF + (32 * (g2 / (2 * DVB)) + 16 * ((g2 / DVB) % 2)) * (DV * 2)>(lo[g2], hi[g2], va[g2 % DVB]);
+      wait_vt<2 * ((NF - 1 - f) < PD ? (NF - 1 - f) : PD)>(lo[f], hi[f]);
+      const bf16x8 a = __builtin_bit_cast(bf16x8, (i32x4){lo[f][0], lo[f][1], hi[f][0], hi[f][1]});
 #pragma unroll
-    for (int f = 0; f < NF; ++f) {
-      if (f + PD < NF) issue(f + PD);
-      const int ahead = (NF - 1 - f) < PD ? (NF - 1 - f) : PD;
-      if (ahead == 3) asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(lo[f]), "+v"(hi[f]));
-      else if (ahead == 2) asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(lo[f]), "+v"(hi[f]));
-      else if (ahead == 1) asm volatile("s_waitcnt lgkmcnt(2)" : "+v"(lo[f]), "+v"(hi[f]));
-      else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(lo[f]), "+v"(hi[f]));
-      const int d = f % DVB, ks = (f / DVB) % 2, nb = f / (2 * DVB);
-      const i32x4 av = {lo[f][0], lo[f][1], hi[f][0], hi[f][1]};
-      oacc[0][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pr.hi[nb][ks], oacc[0][d], 0, 0, 0);
+      for (int rb = 0; rb < RB; ++rb) {
+        oacc[0][rb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pr.hi[rb][nb][ks], oacc[0][rb][d], 0, 0, 0);
 #pragma unroll
-      for (int e = 0; e < PER; e += 2) {
-        const int idx = f * PER + e, tb = idx / 16, r = idx % 16;
-        const float x0 = transform_one(nxt[tb][r], j1, tb, r), x1 = transform_one(nxt[tb][r + 1], j1, tb, r + 1);
-        nxt[tb][r] = x0;
-        nxt[tb][r + 1] = x1;
-        mx = fmaxf(fmaxf(mx, x0), x1);
-        asm volatile("" : "+v"(mx));
+        for (int e = 0; e < PER; e += 2) {
+          const int L = (f * RB + rb) * PER + e, crb = L / (NB * 16), cnb = (L / 16) % NB, r = L % 16;
+          const float x0 = transform_one(nxt[crb][cnb][r], j1, crb, cnb, r);
+          const float x1 = transform_one(nxt[crb][cnb][r + 1], j1, crb, cnb, r + 1);
+          nxt[crb][cnb][r] = x0;
+          nxt[crb][cnb][r + 1] = x1;
+          mx[crb] = fmaxf(fmaxf(mx[crb], x0), x1);
+          asm volatile("" : "+v"(mx[crb]));
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
-      __builtin_amdgcn_sched_barrier(0);
+    });
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      mx[rb] = half_swap_max(mx[rb]);
+      if constexpr (kPlain) mx[rb] *= c_scale;
     }
-    mx = half_swap_max(mx);
-    if constexpr (kPlain) mx *= c_scale;
-    return mx;
   }
 };
 
 template <class C>
 __global__ void __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE)))
 fwd_bf16_kernel(const FwdParams p) {
-  constexpr int D = C::D, DV = C::DV, BN = C::BN, NB = C::NB, KK = C::KK, DVB = C::DVB, NS = C::NS;
+  constexpr int D = C::D, DV = C::DV, BN = C::BN, NB = C::NB, KK = C::KK, DVB = C::DVB, NS = C::NS, RB = C::RB;
   constexpr uint32_t MASK = C::MASK;
   typedef Wave<C> W;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
@@ -466,7 +476,7 @@ fwd_bf16_kernel(const FwdParams p) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  W w(p, lds_raw);
+  W w(p);
   w.lane = lane;
   w.half = lane >> 5;
   w.col = lane & 31;
@@ -491,35 +501,35 @@ fwd_bf16_kernel(const FwdParams p) {
   const int b = bh / (p.H * p.G);
   const int hk = h / (p.H / p.Hkv);
   const int i0 = qt * C::BM;                       // first query row of the workgroup
-  const int iw = i0 + wave * 32;                   // first query row of the wave
-  const int i = iw + w.col;                        // this lane's query row
-  const int ic = i < p.Sq ? i : p.Sq - 1;
-  w.b = b; w.g = g; w.h = h; w.i = i; w.ic = ic; w.iw = iw;
-
-  {
-    const uint16_t* qp = (const uint16_t*)p.q.ptr + b * p.q.sb + g * p.q.sg + h * p.q.sh + (int64_t)ic * p.q.ss;
+  const int iw = i0 + wave * C::WROWS;             // first query row of the wave
+  w.b = b; w.g = g; w.h = h;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) w.qf[0][kk] = *(const bf16x8*)(qp + 16 * kk + 8 * w.half);
+  for (int rb = 0; rb < RB; ++rb) {
+    w.i[rb] = iw + 32 * rb + w.col;
+    w.ic[rb] = w.i[rb] < p.Sq ? w.i[rb] : p.Sq - 1;
+    const uint16_t* qp = (const uint16_t*)p.q.ptr + b * p.q.sb + g * p.q.sg + h * p.q.sh + (int64_t)w.ic[rb] * p.q.ss;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) w.qf[0][rb][kk] = *(const bf16x8*)(qp + 16 * kk + 8 * w.half);
     if constexpr (C::DIFF) {
-      const uint16_t* q2 = (const uint16_t*)p.q2.ptr + b * p.q2.sb + g * p.q2.sg + h * p.q2.sh + (int64_t)ic * p.q2.ss;
+      const uint16_t* q2 = (const uint16_t*)p.q2.ptr + b * p.q2.sb + g * p.q2.sg + h * p.q2.sh + (int64_t)w.ic[rb] * p.q2.ss;
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) w.qf[1][kk] = *(const bf16x8*)(q2 + 16 * kk + 8 * w.half);
+      for (int kk = 0; kk < KK; ++kk) w.qf[NS - 1][rb][kk] = *(const bf16x8*)(q2 + 16 * kk + 8 * w.half);
     }
+    w.qdoc[rb] = 0;
+    if constexpr ((MASK & kMaskDoc) != 0) w.qdoc[rb] = p.q_doc[(int64_t)b * p.Sq + w.ic[rb]];
   }
 #pragma unroll
-  for (int s = 0; s < NS; ++s) {
-    w.m_run[s] = -INFINITY;
-    w.l_run[s] = 0.f;
+  for (int s = 0; s < NS; ++s)
 #pragma unroll
-    for (int d = 0; d < DVB; ++d)
+    for (int rb = 0; rb < RB; ++rb) {
+      w.m_run[s][rb] = -INFINITY;
+      w.l_run[s][rb] = 0.f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) w.oacc[s][d][r] = 0.f;
-  }
+      for (int d = 0; d < DVB; ++d) w.oacc[s][rb][d] = W::zero16();
+    }
   w.c_scale = p.scale * kLog2e;                    // raw score -> log2 domain
   w.slope_l2 = 0.f;
   if constexpr (C::MOD == kModAlibi) w.slope_l2 = p.alibi_slopes[h] * kLog2e;
-  w.qdoc = 0;
-  if constexpr ((MASK & kMaskDoc) != 0) w.qdoc = p.q_doc[(int64_t)b * p.Sq + ic];
 
   // ---- loop-invariant per-lane LDS offsets
 #pragma unroll
@@ -547,13 +557,20 @@ fwd_bf16_kernel(const FwdParams p) {
     const int2* qsum = p.q_sum + (int64_t)b * nqs;
     const int s0 = i0 / kSumBlock;
     qs_wg = qsum[s0];
-    for (int ww = 1; ww < C::NWAVES; ++ww)
+    for (int ww = 1; ww < C::BM / kSumBlock; ++ww)
       if (s0 + ww < nqs) {
         const int2 t = qsum[s0 + ww];
         qs_wg.x = min(qs_wg.x, t.x);
         qs_wg.y = max(qs_wg.y, t.y);
       }
-    qs_wave = qsum[min(s0 + wave, nqs - 1)];
+    const int sw = iw / kSumBlock;
+    qs_wave = qsum[min(sw, nqs - 1)];
+    for (int rb = 1; rb < RB; ++rb)
+      if (sw + rb < nqs) {
+        const int2 t = qsum[sw + rb];
+        qs_wave.x = min(qs_wave.x, t.x);
+        qs_wave.y = max(qs_wave.y, t.y);
+      }
   }
   const int2* ksum = (MASK & kMaskDoc) ? p.kv_sum + (int64_t)b * nks : nullptr;
 
@@ -580,7 +597,8 @@ fwd_bf16_kernel(const FwdParams p) {
     if (t >= t_hi) return kTileSkip;
     int2 ks = make_int2(0, 0);
     if constexpr ((MASK & kMaskDoc) != 0) ks = tile_keys(t);
-    const int c = classify_block(MASK, iw, iw + 31, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wave, ks);
+    const int c = classify_block(MASK, iw, iw + C::WROWS - 1, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix,
+                                 qs_wave, ks);
     return __builtin_amdgcn_readfirstlane(c);
   };
 
@@ -648,7 +666,8 @@ fwd_bf16_kernel(const FwdParams p) {
       wait_loads_and_sync();
       w.template qk<C::K_RING>(sa, 0);
       w.transform(sa, t0 * BN);
-      float mx = w.rowmax(sa);                     // valid if the tile is fully visible
+      float mx[RB];
+      w.rowmax(sa, mx);                            // valid if the tile is fully visible
       bool full0 = wave_class(t0) == kTileFull;
       __syncthreads();                             // everyone is done with K ring slot 0
       // Start of every step: finish the softmax bookkeeping of the current tile.  Only the
@@ -656,9 +675,9 @@ fwd_bf16_kernel(const FwdParams p) {
       auto settle = [&](typename W::Scores& cur) {
         if (!full0) {
           w.mask(cur, t0 * BN);
-          mx = w.rowmax(cur);
+          w.rowmax(cur, mx);
         }
-        w.rescale(0, w.advance_max(0, mx));
+        w.advance_max(0, mx);
       };
       // One pipeline step.  cur / nxt hold the scores of t0 / t1; BUF is the ring slot of K(t0)
       // and V(t0), so K(t1) sits in slot BUF ^ 1.  The last tile takes the same step: its
@@ -671,7 +690,7 @@ fwd_bf16_kernel(const FwdParams p) {
         if (t2 < t_hi) load_k(t2, BUF);
         if (t1 < t_hi) load_v(t1, BUF ^ 1);
         w.template phase_a<C::K_RING + (BUF ^ 1) * C::K_BYTES>(nxt, cur, pr);
-        mx = w.template phase_b<C::V_RING + BUF * C::V_BYTES>(pr, nxt, t1 * BN);
+        w.template phase_b<C::V_RING + BUF * C::V_BYTES>(pr, nxt, t1 * BN, mx);
         wait_loads_and_sync();
         t0 = t1;
         t1 = t2;
@@ -688,6 +707,7 @@ fwd_bf16_kernel(const FwdParams p) {
     // ============ two-stream (differential) loop: streams share V, one score tile at a time ====
     typename W::Scores sc;
     typename W::Probs pr;
+    float mx[RB];
     int t0 = next_tile(t_lo);
     if (t0 < t_hi) {
       load_k(t0, 0);
@@ -706,13 +726,15 @@ fwd_bf16_kernel(const FwdParams p) {
         w.template qk<C::K_RING + (BUF * NS) * C::K_BYTES>(sc, 0);
         w.transform(sc, t0 * BN);
         if (c0 != kTileFull) w.mask(sc, t0 * BN);
-        w.rescale(0, w.advance_max(0, w.rowmax(sc)));
+        w.rowmax(sc, mx);
+        w.advance_max(0, mx);
         w.exp_sum(sc, 0, pr);
         w.template pv<C::V_RING + BUF * C::V_BYTES>(pr, 0);
         w.template qk<C::K_RING + (BUF * NS + NS - 1) * C::K_BYTES>(sc, NS - 1);
         w.transform(sc, t0 * BN);
         if (c0 != kTileFull) w.mask(sc, t0 * BN);
-        w.rescale(NS - 1, w.advance_max(NS - 1, w.rowmax(sc)));
+        w.rowmax(sc, mx);
+        w.advance_max(NS - 1, mx);
         w.exp_sum(sc, NS - 1, pr);
         w.template pv<C::V_RING + BUF * C::V_BYTES>(pr, NS - 1);
       }
@@ -727,63 +749,67 @@ fwd_bf16_kernel(const FwdParams p) {
   }
 
   // ---- epilogue (a7): normalise by l, combine streams, RMSNorm, gate, store
-  float inv[NS], lse_v[NS];
-#pragma unroll
-  for (int s = 0; s < NS; ++s) {
-    const float lt = half_swap_sum(w.l_run[s]);
-    inv[s] = lt > 0.f ? 1.f / lt : 0.f;
-    lse_v[s] = lt > 0.f ? w.m_run[s] * kLn2 + __logf(lt) : -INFINITY;
-  }
   const float lam = C::DIFF ? p.lambda[h] : 0.f;
-  float ssq = 0.f;
 #pragma unroll
-  for (int d = 0; d < DVB; ++d)
+  for (int rb = 0; rb < RB; ++rb) {
+    float inv[NS], lse_v[NS];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      float x = w.oacc[0][d][r] * inv[0];
-      if constexpr (C::DIFF) x -= lam * (w.oacc[NS - 1][d][r] * inv[NS - 1]);
-      w.oacc[0][d][r] = x;
-      ssq = fmaf(x, x, ssq);
+    for (int s = 0; s < NS; ++s) {
+      const float lt = half_swap_sum(w.l_run[s][rb]);
+      inv[s] = lt > 0.f ? 1.f / lt : 0.f;
+      lse_v[s] = lt > 0.f ? w.m_run[s][rb] * kLn2 + __logf(lt) : -INFINITY;
     }
-  float rn = 1.f;
-  if constexpr ((C::EPI & kEpiRms) != 0) {
-    ssq = half_swap_sum(ssq);
-    rn = 1.f / sqrtf(ssq * (1.f / DV) + p.rms_eps);
-  }
-  if (i < p.Sq) {
-    const int64_t orow = b * p.out.sb + g * p.out.sg + h * p.out.sh + (int64_t)i * p.out.ss;
-    const int64_t grow = b * p.gate.sb + g * p.gate.sg + h * p.gate.sh + (int64_t)i * p.gate.ss;
+    float ssq = 0.f;
 #pragma unroll
     for (int d = 0; d < DVB; ++d)
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int ch = 32 * d + 8 * r4 + 4 * w.half;   // 4 consecutive channels ch..ch+3
-        float x[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) x[e] = w.oacc[0][d][4 * r4 + e];
-        if constexpr ((C::EPI & kEpiRms) != 0) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) x[e] *= rn * (p.rms_weight ? p.rms_weight[ch + e] : 1.f);
-        }
-        if constexpr ((C::EPI & kEpiGate) != 0) {
-          const uint2 gg = *(const uint2*)((const uint16_t*)p.gate.ptr + grow + ch);
-          const float g0 = __uint_as_float(gg.x << 16), g1 = __uint_as_float(gg.x & 0xFFFF0000u);
-          const float g2 = __uint_as_float(gg.y << 16), g3 = __uint_as_float(gg.y & 0xFFFF0000u);
-          x[0] *= fast_rcp(1.f + fast_exp2(-g0 * kLog2e));
-          x[1] *= fast_rcp(1.f + fast_exp2(-g1 * kLog2e));
-          x[2] *= fast_rcp(1.f + fast_exp2(-g2 * kLog2e));
-          x[3] *= fast_rcp(1.f + fast_exp2(-g3 * kLog2e));
-        }
-        if (p.out_f32) {
-          *(float4*)((float*)p.out.ptr + orow + ch) = make_float4(x[0], x[1], x[2], x[3]);
-        } else {
-          *(uint2*)((uint16_t*)p.out.ptr + orow + ch) = make_uint2(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]));
-        }
+      for (int r = 0; r < 16; ++r) {
+        float x = w.oacc[0][rb][d][r] * inv[0];
+        if constexpr (C::DIFF) x -= lam * (w.oacc[NS - 1][rb][d][r] * inv[NS - 1]);
+        w.oacc[0][rb][d][r] = x;
+        ssq = fmaf(x, x, ssq);
       }
-    if (p.lse != nullptr && w.half == 0) {
+    float rn = 1.f;
+    if constexpr ((C::EPI & kEpiRms) != 0) {
+      ssq = half_swap_sum(ssq);
+      rn = 1.f / sqrtf(ssq * (1.f / DV) + p.rms_eps);
+    }
+    const int i = w.i[rb];
+    if (i < p.Sq) {
+      const int64_t orow = b * p.out.sb + g * p.out.sg + h * p.out.sh + (int64_t)i * p.out.ss;
+      const int64_t grow = b * p.gate.sb + g * p.gate.sg + h * p.gate.sh + (int64_t)i * p.gate.ss;
 #pragma unroll
-      for (int s = 0; s < NS; ++s)
-        p.lse[b * p.lse_sb + (int64_t)(C::DIFF ? 2 * g + s : g) * p.lse_sg + h * p.lse_sh + i] = lse_v[s];
+      for (int d = 0; d < DVB; ++d)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int ch = 32 * d + 8 * r4 + 4 * w.half;   // 4 consecutive channels ch..ch+3
+          float x[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) x[e] = w.oacc[0][rb][d][4 * r4 + e];
+          if constexpr ((C::EPI & kEpiRms) != 0) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[e] *= rn * (p.rms_weight ? p.rms_weight[ch + e] : 1.f);
+          }
+          if constexpr ((C::EPI & kEpiGate) != 0) {
+            const uint2 gg = *(const uint2*)((const uint16_t*)p.gate.ptr + grow + ch);
+            const float g0 = __uint_as_float(gg.x << 16), g1 = __uint_as_float(gg.x & 0xFFFF0000u);
+            const float g2 = __uint_as_float(gg.y << 16), g3 = __uint_as_float(gg.y & 0xFFFF0000u);
+            x[0] *= fast_rcp(1.f + fast_exp2(-g0 * kLog2e));
+            x[1] *= fast_rcp(1.f + fast_exp2(-g1 * kLog2e));
+            x[2] *= fast_rcp(1.f + fast_exp2(-g2 * kLog2e));
+            x[3] *= fast_rcp(1.f + fast_exp2(-g3 * kLog2e));
+          }
+          if (p.out_f32) {
+            *(float4*)((float*)p.out.ptr + orow + ch) = make_float4(x[0], x[1], x[2], x[3]);
+          } else {
+            *(uint2*)((uint16_t*)p.out.ptr + orow + ch) = make_uint2(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]));
+          }
+        }
+      if (p.lse != nullptr && w.half == 0) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+          p.lse[b * p.lse_sb + (int64_t)(C::DIFF ? 2 * g + s : g) * p.lse_sg + h * p.lse_sh + i] = lse_v[s];
+      }
     }
   }
 }

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace fl {
 
 // Mask bits / enums mirror include/fl_attn.h (kept numerically identical; checked in fl_api.hip).
@@ -50,6 +52,15 @@ struct FwdParams {
   int32_t n_qtiles;      // ceil(Sq / rows per workgroup)
   int32_t order;         // workgroup ordering scheme
 };
+
+// Compile-time loop: f(std::integral_constant<int, I>) for I in [B, E).
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (B < E) {
+    f(std::integral_constant<int, B>());
+    static_for<B + 1, E>(f);
+  }
+}
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
