@@ -163,12 +163,24 @@ def main():
     ap.add_argument("--all", action="store_true", help="time every configuration (results in gpurun_out/bench_all.json)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tune", default="", help="comma list key=value passed to fl_set_tuning (sweeps)")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="only run a plain device-to-device copy of MIB MiB a few times (scale factor of the "
+                         "FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("this build runs on one GPU only: no sharding or collectives are part of it (use --gpus 1)")
     import torch
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU")
+    if args.calibrate_copy:
+        n = args.calibrate_copy * (1 << 20)
+        src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes": n, "repeats": 5}))
+        return
     from paper_2511_02043_amd import binding as fb
     fb.lib()
     for kv in filter(None, args.tune.split(",")):
@@ -195,7 +207,8 @@ def main():
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(args.config)
+        entry = json.load(open(tpath)).get(args.config)
+        traffic = entry["total"] if entry else None     # HBM bytes per launch, from rocprofv3 --pmc (see profiles/)
     line = {
         "metric": "attention fwd TFLOP/s per variant at 1 GPU; % of bf16 MFMA peak",
         "value": r["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
