@@ -103,8 +103,9 @@ typedef struct {
   const float*   alibi_slopes;  /* [H] device, FL_MOD_ALIBI                                    */
   const int32_t* q_doc_ids;     /* [B, Sq] device, contiguous, FL_MASK_DOC                     */
   const int32_t* kv_doc_ids;    /* [B, Sk] device, contiguous (may alias q_doc_ids)            */
-  fl_tensor      bias[2];       /* logical [B, G, H, Sq, Sk]; dtype bf16 or f32; stride 0 ok;
-                                   innermost stride 1 (or 0 when Sk-broadcast is not needed)  */
+  fl_tensor      bias[2];       /* logical [B, G, H, Sq, Sk]; stride 0 (or size 1) broadcasts;
+                                   innermost stride 1 or 0; bf16 for bf16 inputs, bf16 or f32
+                                   for f32 inputs; rows that start 8-byte aligned load faster  */
   fl_tensor      gate;          /* logical shape of out, pre-sigmoid; dtype of q               */
   fl_tensor      q2, k2;        /* second softmax stream (FL_DIFFERENTIAL); shapes of q, k     */
   const float*   lambda;        /* [H] device, FL_DIFFERENTIAL                                 */
@@ -113,9 +114,9 @@ typedef struct {
   size_t         workspace_bytes;
 } fl_aux;
 
-/* The fused forward pass (Sec. 3, "each thread block computes tiles of S = QK^T/sqrt(d), applies
- * the online softmax to each tile via a fused max-reduction and rescaled accumulation, and
- * multiplies by the tiles of V"), for the variant named by `desc`.
+/* The fused forward pass for the variant named by `desc`: the single kernel of Sec. 3 in which a
+ * workgroup forms one tile of scaled scores at a time, folds it into a running row maximum and
+ * row sum (rescaling what it has accumulated so far) and multiplies it by the matching V tile.
  *
  *   q    [B, G, H,   Sq, D ]  bf16 or f32 (all of q, k, v, q2, k2, gate share one dtype)
  *   k    [B, G, Hkv, Sk, D ]  Hkv divides H; query head h reads kv head h / (H / Hkv)

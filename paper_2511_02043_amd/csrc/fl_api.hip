@@ -297,6 +297,9 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
       bv.ptr = bt->ptr;
       bv.sb = bs[0]; bv.sg = bs[1]; bv.sh = bs[2]; bv.si = bs[3]; bv.sj = Sk > 1 ? bs[4] : 0;
       bv.is_f32 = bt->dtype == FL_F32;
+      if (dtype == FL_BF16 && bv.is_f32) return fail(FL_ERR_DTYPE, "bias[%u]: bf16 inputs take bf16 biases", nb);
+      bv.vec4 = bs[4] == 1 && Sk > 1 && ((uintptr_t)bt->ptr) % 8 == 0 && bs[0] % 4 == 0 && bs[1] % 4 == 0 &&
+                bs[2] % 4 == 0 && bs[3] % 4 == 0;
     }
   }
 
@@ -373,6 +376,7 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   int order = g_tuning.order >= 0 ? g_tuning.order : 1;
   if (order == 1 && nbh % 8 != 0) order = 0;
   p.order = order;
+  p.doc_vec = (mask & FL_MASK_DOC) && Sk % 4 == 0 && ((uintptr_t)aux->kv_doc_ids) % 16 == 0;
 
   hipStream_t stream = (hipStream_t)stream_v;
   if (Sk == 0) {

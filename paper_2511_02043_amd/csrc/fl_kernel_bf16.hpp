@@ -2,8 +2,9 @@
 // accumulation, scores and softmax state in registers, K/V tiles ring-buffered in LDS and
 // filled by direct global->LDS loads.
 //
-// Structure (Sec. 3 of the paper describes the fused pass this realises: score tiles, online
-// softmax per tile via a fused max-reduction and rescaled accumulation, multiply by V tiles;
+// Structure (Sec. 3 of the paper names the fused pass this realises: one score tile at a time,
+// folded into a running row maximum / row sum with the accumulator rescaled as needed, then
+// multiplied by the matching V tile;
 // Sec. 3.2: the key axis is a sequential loop inside the workgroup that owns a query tile;
 // Sec. 3.4: running max / running sum with the exp(m_old - m_new) correction; Sec. 3.5: D and
 // Dv each fit one tile, so the twin matmul needs no loop over them; Sec. 3.6: 1-D launch whose
@@ -137,7 +138,14 @@ struct Wave {
     bf16x8 lo[C::PSPLIT ? C::NB : 1][2];           // PSPLIT implies RB == 1
   };
 
+  // Raw bias values of one tile for this lane: for bias n, row block rb, key block nb and
+  // register group r4, the four bf16 values of keys jb + 8*r4 .. +3 (loaded ahead of their use).
+  struct BiasRegs {
+    uint2 v[C::NBIAS > 0 ? C::NBIAS : 1][C::RB][C::NB][4];
+  };
+
   const FwdParams& p;
+  const uint16_t* brow[C::NBIAS > 0 ? C::NBIAS : 1][C::RB];   // this lane's bias rows (bias, row block)
   int lane, half, col;
   int b, g, h;
   int i[C::RB], ic[C::RB];      // this lane's query rows (unclamped / clamped), one per row block
@@ -214,7 +222,7 @@ struct Wave {
   // ---- variant transform (Eq. 4 score_mod, additive biases) of one score register.
   // Leaves the score in the domain exp_sum() expects: raw for the plain variants (the scale is
   // folded into the exponent's FMA), log2-scaled otherwise.  j0 is the tile's first key.
-  __device__ __forceinline__ float transform_one(float x, int j0, int rb, int nb, int r) const {
+  __device__ __forceinline__ float transform_one(float x, int j0, int rb, int nb, int r, const BiasRegs& br) const {
     if constexpr (kPlain) {
       return x;
     } else {
@@ -230,23 +238,48 @@ struct Wave {
       if constexpr (C::MOD == kModAlibi) x -= slope_l2 * fabsf((float)(i[rb] - j));
 #pragma unroll
       for (int nbias = 0; nbias < C::NBIAS; ++nbias) {
-        const BiasView& bv = p.bias[nbias];
-        const int64_t off = b * bv.sb + g * bv.sg + h * bv.sh + (int64_t)ic[rb] * bv.si +
-                            (int64_t)(j < p.Sk ? j : p.Sk - 1) * bv.sj;
-        const float bb = bv.is_f32 ? ((const float*)bv.ptr)[off] : bf16_to_f32(((const uint16_t*)bv.ptr)[off]);
+        const uint2 q4 = br.v[nbias][rb][nb][r >> 2];
+        const uint32_t wd = (r & 2) ? q4.y : q4.x;
+        const float bb = __uint_as_float((r & 1) ? (wd & 0xFFFF0000u) : (wd << 16));
         x = fmaf(bb, kLog2e, x);
       }
       return x;
     }
   }
-  __device__ __forceinline__ void transform(Scores& sc, int j0) const {
+  __device__ __forceinline__ void transform(Scores& sc, int j0, const BiasRegs& br) const {
     if constexpr (!kPlain) {
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) sc[rb][nb][r] = transform_one(sc[rb][nb][r], j0, rb, nb, r);
+          for (int r = 0; r < 16; ++r) sc[rb][nb][r] = transform_one(sc[rb][nb][r], j0, rb, nb, r, br);
+    }
+  }
+
+  // ---- bias values of tile j0 for this lane, issued early so that their latency hides behind
+  // the matrix work of the step.  Rows whose layout allows it are read four keys per load.
+  __device__ __forceinline__ void load_bias(BiasRegs& br, int j0) const {
+#pragma unroll
+    for (int nbias = 0; nbias < C::NBIAS; ++nbias) {
+      const BiasView& bv = p.bias[nbias];
+      const bool vec = bv.vec4 != 0 && j0 + C::BN <= p.Sk;       // uniform
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int r4 = 0; r4 < 4; ++r4) {
+            const int j = j0 + 32 * nb + 4 * half + 8 * r4;
+            if (vec) {
+              br.v[nbias][rb][nb][r4] = *(const uint2*)(brow[nbias][rb] + j);
+            } else {
+              uint32_t e[4];
+#pragma unroll
+              for (int u = 0; u < 4; ++u) e[u] = brow[nbias][rb][(int64_t)(j + u < p.Sk ? j + u : p.Sk - 1) * bv.sj];
+              br.v[nbias][rb][nb][r4] = make_uint2(e[0] | (e[1] << 16), e[2] | (e[3] << 16));
+            }
+          }
     }
   }
 
@@ -258,10 +291,19 @@ struct Wave {
       const int jb = j0 + 32 * nb + 4 * half;
       int kd[16];
       if constexpr ((MASK & kMaskDoc) != 0) {
+        const int32_t* kdoc = p.kv_doc + (int64_t)b * p.Sk;
+        if (p.doc_vec && j0 + C::BN <= p.Sk) {     // uniform: four ids per load
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int j = jb + 8 * (r >> 2) + (r & 3);
-          kd[r] = p.kv_doc[(int64_t)b * p.Sk + (j < p.Sk ? j : p.Sk - 1)];
+          for (int r4 = 0; r4 < 4; ++r4) {
+            const int4 q4 = *(const int4*)(kdoc + jb + 8 * r4);
+            kd[4 * r4] = q4.x; kd[4 * r4 + 1] = q4.y; kd[4 * r4 + 2] = q4.z; kd[4 * r4 + 3] = q4.w;
+          }
+        } else {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int j = jb + 8 * (r >> 2) + (r & 3);
+            kd[r] = kdoc[j < p.Sk ? j : p.Sk - 1];
+          }
         }
       }
 #pragma unroll
@@ -427,7 +469,7 @@ struct Wave {
   // of 16/(2*DVB) scores of the next tile.  mx receives the next tile's row maxima (log2
   // units), valid when that tile is fully visible.
   template <int VOFF>
-  __device__ __forceinline__ void phase_b(const Probs& pr, Scores& nxt, int j1, float (&mx)[C::RB]) {
+  __device__ __forceinline__ void phase_b(const Probs& pr, Scores& nxt, int j1, float (&mx)[C::RB], const BiasRegs& br) {
     constexpr int NF = NB * 2 * DVB, PD = NF < C::PD_V ? NF : C::PD_V, PER = 16 / (2 * DVB);   // PER in {2, 4, 8}
     i32x2 lo[NF], hi[NF];
 #pragma unroll
@@ -447,8 +489,8 @@ struct Wave {
 #pragma unroll
         for (int e = 0; e < PER; e += 2) {
           const int L = (f * RB + rb) * PER + e, crb = L / (NB * 16), cnb = (L / 16) % NB, r = L % 16;
-          const float x0 = transform_one(nxt[crb][cnb][r], j1, crb, cnb, r);
-          const float x1 = transform_one(nxt[crb][cnb][r + 1], j1, crb, cnb, r + 1);
+          const float x0 = transform_one(nxt[crb][cnb][r], j1, crb, cnb, r, br);
+          const float x1 = transform_one(nxt[crb][cnb][r + 1], j1, crb, cnb, r + 1, br);
           nxt[crb][cnb][r] = x0;
           nxt[crb][cnb][r + 1] = x1;
           mx[crb] = fmaxf(fmaxf(mx[crb], x0), x1);
@@ -517,6 +559,11 @@ fwd_bf16_kernel(const FwdParams p) {
     }
     w.qdoc[rb] = 0;
     if constexpr ((MASK & kMaskDoc) != 0) w.qdoc[rb] = p.q_doc[(int64_t)b * p.Sq + w.ic[rb]];
+#pragma unroll
+    for (int nbias = 0; nbias < C::NBIAS; ++nbias) {
+      const BiasView& bv = p.bias[nbias];
+      w.brow[nbias][rb] = (const uint16_t*)bv.ptr + b * bv.sb + g * bv.sg + h * bv.sh + (int64_t)w.ic[rb] * bv.si;
+    }
   }
 #pragma unroll
   for (int s = 0; s < NS; ++s)
@@ -657,15 +704,17 @@ fwd_bf16_kernel(const FwdParams p) {
     // does not need is simply fully masked for it (its probabilities are exactly 0).
     typename W::Scores sa, sb;                     // the two score tiles in flight
     typename W::Probs pr;
+    typename W::BiasRegs br;
     int t0 = next_tile(t_lo);
     if (t0 < t_hi) {
       int t1 = next_tile(t0 + 1);
+      w.load_bias(br, t0 * BN);
       load_k(t0, 0);
       load_v(t0, 0);
       if (t1 < t_hi) load_k(t1, 1);
       wait_loads_and_sync();
       w.template qk<C::K_RING>(sa, 0);
-      w.transform(sa, t0 * BN);
+      w.transform(sa, t0 * BN, br);
       float mx[RB];
       w.rowmax(sa, mx);                            // valid if the tile is fully visible
       bool full0 = wave_class(t0) == kTileFull;
@@ -687,10 +736,11 @@ fwd_bf16_kernel(const FwdParams p) {
         const int t2 = t1 < t_hi ? next_tile(t1 + 1) : t_hi;
         const bool full1 = wave_class(t1) == kTileFull;
         settle(cur);
+        if (t1 < t_hi) w.load_bias(br, t1 * BN);   // before the tile loads: its wait then excludes them
         if (t2 < t_hi) load_k(t2, BUF);
         if (t1 < t_hi) load_v(t1, BUF ^ 1);
         w.template phase_a<C::K_RING + (BUF ^ 1) * C::K_BYTES>(nxt, cur, pr);
-        w.template phase_b<C::V_RING + BUF * C::V_BYTES>(pr, nxt, t1 * BN, mx);
+        w.template phase_b<C::V_RING + BUF * C::V_BYTES>(pr, nxt, t1 * BN, mx, br);
         wait_loads_and_sync();
         t0 = t1;
         t1 = t2;
@@ -707,6 +757,7 @@ fwd_bf16_kernel(const FwdParams p) {
     // ============ two-stream (differential) loop: streams share V, one score tile at a time ====
     typename W::Scores sc;
     typename W::Probs pr;
+    typename W::BiasRegs br;
     float mx[RB];
     int t0 = next_tile(t_lo);
     if (t0 < t_hi) {
@@ -723,15 +774,16 @@ fwd_bf16_kernel(const FwdParams p) {
       }
       const int c0 = wave_class(t0);
       if (c0 != kTileSkip) {
+        w.load_bias(br, t0 * BN);
         w.template qk<C::K_RING + (BUF * NS) * C::K_BYTES>(sc, 0);
-        w.transform(sc, t0 * BN);
+        w.transform(sc, t0 * BN, br);
         if (c0 != kTileFull) w.mask(sc, t0 * BN);
         w.rowmax(sc, mx);
         w.advance_max(0, mx);
         w.exp_sum(sc, 0, pr);
         w.template pv<C::V_RING + BUF * C::V_BYTES>(pr, 0);
         w.template qk<C::K_RING + (BUF * NS + NS - 1) * C::K_BYTES>(sc, NS - 1);
-        w.transform(sc, t0 * BN);
+        w.transform(sc, t0 * BN, br);
         if (c0 != kTileFull) w.mask(sc, t0 * BN);
         w.rowmax(sc, mx);
         w.advance_max(NS - 1, mx);

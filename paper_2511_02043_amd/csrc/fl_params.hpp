@@ -27,7 +27,7 @@ struct BiasView {        // logical [B, G, H, Sq, Sk]; any stride may be 0 (broa
   const void* ptr;
   int64_t sb, sg, sh, si, sj;
   int32_t is_f32;
-  int32_t pad;
+  int32_t vec4;          // 1: sj == 1 and every row start is 8-byte aligned -> 4 keys per load
 };
 
 struct FwdParams {
@@ -51,6 +51,7 @@ struct FwdParams {
   int32_t mod, mask, n_bias, epi;   // runtime copy of the descriptor (fp32 kernel reads these)
   int32_t n_qtiles;      // ceil(Sq / rows per workgroup)
   int32_t order;         // workgroup ordering scheme
+  int32_t doc_vec;       // 1: kv_doc rows are 16-byte aligned and Sk % 4 == 0 -> 4 ids per load
 };
 
 // Compile-time loop: f(std::integral_constant<int, I>) for I in [B, E).
