@@ -92,7 +92,7 @@ __device__ __forceinline__ int swz_v(int r, int c) {
 }
 
 template <int D_, int DV_, int NWAVES_, int RB_, int BN_, int WPE_, int MOD_, uint32_t MASK_, int NBIAS_,
-          bool DIFF_, uint32_t EPI_>
+          bool DIFF_, uint32_t EPI_, int RING_ = 2>
 struct Bf16Cfg {
   static constexpr int D = D_, DV = DV_, NWAVES = NWAVES_, RB = RB_, BN = BN_, MOD = MOD_, NBIAS = NBIAS_;
   static constexpr uint32_t MASK = MASK_, EPI = EPI_;
@@ -115,9 +115,11 @@ struct Bf16Cfg {
   static constexpr int NS = DIFF ? 2 : 1;          // softmax streams
   static constexpr int K_BYTES = BN * D * 2;
   static constexpr int V_BYTES = BN * DV * 2;
-  static constexpr int K_RING = 0;                 // LDS layout: K ring [2][NS][K_BYTES], V ring [2][V_BYTES]
-  static constexpr int V_RING = 2 * NS * K_BYTES;
-  static constexpr int LDS_BYTES = V_RING + 2 * V_BYTES;
+  static constexpr int RING = RING_;               // slots of the K ring and of the V ring (2 or 3)
+  static constexpr int K_RING = 0;                 // LDS layout: K ring [RING][NS][K_BYTES], V ring [RING][V_BYTES]
+  static constexpr int V_RING = RING * NS * K_BYTES;
+  static constexpr int LDS_BYTES = V_RING + RING * V_BYTES;
+  static_assert(RING_ == 2 || (RING_ == 3 && !DIFF_), "ring of 3 is for the pipelined single-stream loop");
   static constexpr int K_INSTR = K_BYTES / 1024;   // 64-lane x 16-byte direct loads per K tile
   static constexpr int V_INSTR = V_BYTES / 1024;
   static constexpr int K_ROWS_PI = 64 / (D / 8);   // tile rows covered by one direct-load instruction
@@ -707,11 +709,16 @@ fwd_bf16_kernel(const FwdParams p) {
     typename W::BiasRegs br;
     int t0 = next_tile(t_lo);
     if (t0 < t_hi) {
-      int t1 = next_tile(t0 + 1);
+      auto after = [&](int t) { return t < t_hi ? next_tile(t + 1) : t_hi; };
+      int t1 = after(t0), t2 = after(t1), t3 = after(t2);   // RING == 3 uses the full look-ahead
       w.load_bias(br, t0 * BN);
       load_k(t0, 0);
       load_v(t0, 0);
       if (t1 < t_hi) load_k(t1, 1);
+      if constexpr (C::RING == 3) {
+        if (t1 < t_hi) load_v(t1, 1);
+        if (t2 < t_hi) load_k(t2, 2);
+      }
       wait_loads_and_sync();
       w.template qk<C::K_RING>(sa, 0);
       w.transform(sa, t0 * BN, br);
@@ -728,29 +735,58 @@ fwd_bf16_kernel(const FwdParams p) {
         }
         w.advance_max(0, mx);
       };
-      // One pipeline step.  cur / nxt hold the scores of t0 / t1; BUF is the ring slot of K(t0)
-      // and V(t0), so K(t1) sits in slot BUF ^ 1.  The last tile takes the same step: its
-      // "next tile" contraction then runs on stale LDS contents and is never used.
-      auto step = [&](auto bufc, typename W::Scores& cur, typename W::Scores& nxt) {
-        constexpr int BUF = decltype(bufc)::value;
-        const int t2 = t1 < t_hi ? next_tile(t1 + 1) : t_hi;
+      // One pipeline step.  cur / nxt hold the scores of t0 / t1.  Step number N (mod 2 * RING)
+      // fixes the roles at compile time: K(t0) and V(t0) sit in ring slot N % RING, K(t1) in the
+      // next slot.  With RING = 2 the step streams K(t2) and V(t1) in and waits for both; with
+      // RING = 3 it streams K(t3) and V(t2) in and only waits for what the previous step
+      // started, so a tile has two full steps to arrive.  The last tile takes the same step:
+      // its "next tile" contraction then runs on stale LDS contents and is never used.
+      auto step = [&](auto nc, typename W::Scores& cur, typename W::Scores& nxt) {
+        constexpr int N = decltype(nc)::value, R = C::RING;
+        constexpr int s_cur = N % R, s_nxt = (N + 1) % R, s_far = (N + 2) % R;
         const bool full1 = wave_class(t1) == kTileFull;
         settle(cur);
         if (t1 < t_hi) w.load_bias(br, t1 * BN);   // before the tile loads: its wait then excludes them
-        if (t2 < t_hi) load_k(t2, BUF);
-        if (t1 < t_hi) load_v(t1, BUF ^ 1);
-        w.template phase_a<C::K_RING + (BUF ^ 1) * C::K_BYTES>(nxt, cur, pr);
-        w.template phase_b<C::V_RING + BUF * C::V_BYTES>(pr, nxt, t1 * BN, mx, br);
-        wait_loads_and_sync();
+        bool far_k = false, far_v = false;
+        if constexpr (R == 2) {
+          if (t2 < t_hi) load_k(t2, s_cur);
+          if (t1 < t_hi) load_v(t1, s_nxt);
+        } else {
+          far_k = t3 < t_hi;
+          far_v = t2 < t_hi;
+          if (far_k) load_k(t3, s_cur);
+          if (far_v) load_v(t2, s_far);
+        }
+        w.template phase_a<C::K_RING + s_nxt * C::K_BYTES>(nxt, cur, pr);
+        w.template phase_b<C::V_RING + s_cur * C::V_BYTES>(pr, nxt, t1 * BN, mx, br);
+        if constexpr (R == 2) {
+          __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
+        } else {
+          // loads of this step may stay in flight; every wave issued at least this many
+          constexpr int LK = C::K_INSTR / C::NWAVES, LV = C::V_INSTR / C::NWAVES;
+          static_assert(LK + LV <= 15, "vmcnt immediate");
+          if (far_k) __builtin_amdgcn_s_waitcnt(0x0F70 | (LK + LV));
+          else if (far_v) __builtin_amdgcn_s_waitcnt(0x0F70 | LV);
+          else __builtin_amdgcn_s_waitcnt(0x0F70);
+        }
+        __syncthreads();
         t0 = t1;
         t1 = t2;
+        t2 = t3;
+        t3 = after(t3);
         full0 = full1;
       };
       while (true) {
-        step(Buf0(), sa, sb);
-        if (t0 >= t_hi) break;
-        step(Buf1(), sb, sa);
-        if (t0 >= t_hi) break;
+        bool done = false;
+        static_for<0, 2 * C::RING>([&](auto nc) {
+          constexpr int N = decltype(nc)::value;
+          if (!done) {
+            if constexpr (N % 2 == 0) step(nc, sa, sb);
+            else step(nc, sb, sa);
+            done = t0 >= t_hi;
+          }
+        });
+        if (done) break;
       }
     }
   } else {

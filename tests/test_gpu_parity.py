@@ -125,3 +125,25 @@ def test_deterministic_run_to_run():
     dw.run_checked()
     torch.cuda.synchronize()
     assert torch.equal(a, dw.out)
+
+
+@pytest.mark.parametrize("D,tune", [
+    (128, dict(nw=8, rb=1, bn=64, ring=2)), (128, dict(nw=8, rb=1, bn=64, ring=3)), (128, dict(nw=4, rb=1, bn=64)),
+    (128, dict(nw=4, rb=2, bn=64)), (128, dict(nw=4, rb=2, bn=32)),
+    (64, dict(nw=8, rb=1)), (64, dict(nw=4, rb=1)), (64, dict(nw=4, rb=2)), (64, dict(nw=8, rb=2)),
+    (32, dict(nw=4, rb=1)), (32, dict(nw=4, rb=2)),
+])
+@pytest.mark.parametrize("order", [1, 2])
+def test_every_compiled_kernel_shape(D, tune, order):
+    """The shapes selectable with fl_set_tuning all compute the same thing (ragged sizes)."""
+    from paper_2511_02043_amd import binding as fb
+    try:
+        for k, v in tune.items():
+            fb.check(fb.fl_set_tuning(k, v))
+        fb.check(fb.fl_set_tuning("order", order))
+        run_and_compare(inputs.causal_bf16(B=2, H=4, S=777, D=D), label=f"causal D={D} {tune} order={order}")
+        run_and_compare(inputs.causal_bf16(B=1, H=8, S=300, Sk=650, D=D, causal=False),
+                        label=f"plain D={D} {tune} order={order}")
+    finally:
+        for k in ("nw", "rb", "bn", "ring", "wpe", "bm", "order"):
+            fb.fl_set_tuning(k, 0)
