@@ -207,8 +207,8 @@ struct Wave {
     constexpr int NF = NB * KK, PD = C::PD_K < NF ? C::PD_K : NF;   // fragments (nb, kk), prefetch distance
     i32x4 kf[NF];
     f32x16 acc[RB];
-    static_for<0, PD>([&](auto f) { read_k<KOFF + (f / KK) * (32 * D * 2)>(kf[f], ka[f % KK]); });
-    static_for<0, NF>([&](auto fc) {
+    static_for<0, PD>([&](auto f) __attribute__((always_inline)) { read_k<KOFF + (f / KK) * (32 * D * 2)>(kf[f], ka[f % KK]); });
+    static_for<0, NF>([&](auto fc) __attribute__((always_inline)) {
       constexpr int f = fc, kk = f % KK, nb = f / KK;
       if constexpr (f + PD < NF) read_k<KOFF + ((f + PD) / KK) * (32 * D * 2)>(kf[f + PD], ka[(f + PD) % KK]);
       wait_k<(NF - 1 - f) < PD ? (NF - 1 - f) : PD>(kf[f]);
@@ -402,10 +402,10 @@ struct Wave {
   __device__ __forceinline__ void pv(const Probs& pr, int s) {
     constexpr int NF = NB * 2 * DVB, PD = NF < C::PD_V ? NF : C::PD_V;   // fragments (nb, ks, d), prefetch distance
     i32x2 lo[NF], hi[NF];
-    static_for<0, PD>([&](auto f) {
+    static_for<0, PD>([&](auto f) __attribute__((always_inline)) {
       read_vt<VOFF + (32 * (f / (2 * DVB)) + 16 * ((f / DVB) % 2)) * (DV * 2)>(lo[f], hi[f], va[f % DVB]);
     });
-    static_for<0, NF>([&](auto fc) {
+    static_for<0, NF>([&](auto fc) __attribute__((always_inline)) {
       constexpr int f = fc, d = f % DVB, ks = (f / DVB) % 2, nb = f / (2 * DVB), g2 = f + PD;
       if constexpr (g2 < NF)
         read_vt<VOFF + (32 * (g2 / (2 * DVB)) + 16 * ((g2 / DVB) % 2)) * (DV * 2)>(lo[g2], hi[g2], va[g2 % DVB]);
@@ -436,8 +436,8 @@ struct Wave {
     uint32_t w[RB][NB][8], wl_unused = 0;
     i32x4 kf[NF];
     f32x16 acc[RB];
-    static_for<0, PD>([&](auto f) { read_k<KOFF + (f / KK) * (32 * D * 2)>(kf[f], ka[f % KK]); });
-    static_for<0, NF>([&](auto fc) {
+    static_for<0, PD>([&](auto f) __attribute__((always_inline)) { read_k<KOFF + (f / KK) * (32 * D * 2)>(kf[f], ka[f % KK]); });
+    static_for<0, NF>([&](auto fc) __attribute__((always_inline)) {
       constexpr int f = fc, kk = f % KK, nb = f / KK;
       if constexpr (f + PD < NF) read_k<KOFF + ((f + PD) / KK) * (32 * D * 2)>(kf[f + PD], ka[(f + PD) % KK]);
       wait_k<(NF - 1 - f) < PD ? (NF - 1 - f) : PD>(kf[f]);
@@ -467,19 +467,29 @@ struct Wave {
     }
   }
 
-  // ---- phase B: after every PV MFMA of the current tile comes the transform and running max
-  // of 16/(2*DVB) scores of the next tile.  mx receives the next tile's row maxima (log2
-  // units), valid when that tile is fully visible.
+  // ---- phase B: the PV MFMAs of the current tile, with the transform and running max of the
+  // next tile's scores spread over the first half of them and, right after, the running-max
+  // update (Alg. 2 / Sec. 3.4) that this row maximum triggers -- so that the next step can start
+  // straight away.  `advance` (uniform) is false when the next tile still needs its mask: then
+  // the update is left to the start of the next step.  The O rescale is a rare branch after
+  // the last MFMA.
   template <int VOFF>
-  __device__ __forceinline__ void phase_b(const Probs& pr, Scores& nxt, int j1, float (&mx)[C::RB], const BiasRegs& br) {
-    constexpr int NF = NB * 2 * DVB, PD = NF < C::PD_V ? NF : C::PD_V, PER = 16 / (2 * DVB);   // PER in {2, 4, 8}
+  __device__ __forceinline__ void phase_b(const Probs& pr, Scores& nxt, int j1, const BiasRegs& br, bool advance) {
+    constexpr int NF = NB * 2 * DVB, PD = NF < C::PD_V ? NF : C::PD_V;
+    constexpr int HALF = NF / 2, PER = 16 / DVB;   // scores of nxt per MFMA in the first half
+    static_assert(NF % 2 == 0 && PER % 2 == 0, "chunking");
     i32x2 lo[NF], hi[NF];
+    float mx[RB], alpha[RB];
+    bool any = false;
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) mx[rb] = -INFINITY;
-    static_for<0, PD>([&](auto f) {
+    for (int rb = 0; rb < RB; ++rb) {
+      mx[rb] = -INFINITY;
+      alpha[rb] = 1.f;
+    }
+    static_for<0, PD>([&](auto f) __attribute__((always_inline)) {
       read_vt<VOFF + (32 * (f / (2 * DVB)) + 16 * ((f / DVB) % 2)) * (DV * 2)>(lo[f], hi[f], va[f % DVB]);
     });
-    static_for<0, NF>([&](auto fc) {
+    static_for<0, NF>([&](auto fc) __attribute__((always_inline)) {
       constexpr int f = fc, d = f % DVB, ks = (f / DVB) % 2, nb = f / (2 * DVB), g2 = f + PD;
       if constexpr (g2 < NF)
         read_vt<VOFF + (32 * (g2 / (2 * DVB)) + 16 * ((g2 / DVB) % 2)) * (DV * 2)>(lo[g2], hi[g2], va[g2 % DVB]);
@@ -488,23 +498,42 @@ struct Wave {
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
         oacc[0][rb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pr.hi[rb][nb][ks], oacc[0][rb][d], 0, 0, 0);
+        if constexpr (f < HALF) {
 #pragma unroll
-        for (int e = 0; e < PER; e += 2) {
-          const int L = (f * RB + rb) * PER + e, crb = L / (NB * 16), cnb = (L / 16) % NB, r = L % 16;
-          const float x0 = transform_one(nxt[crb][cnb][r], j1, crb, cnb, r, br);
-          const float x1 = transform_one(nxt[crb][cnb][r + 1], j1, crb, cnb, r + 1, br);
-          nxt[crb][cnb][r] = x0;
-          nxt[crb][cnb][r + 1] = x1;
-          mx[crb] = fmaxf(fmaxf(mx[crb], x0), x1);
-          asm volatile("" : "+v"(mx[crb]));
+          for (int e = 0; e < PER; e += 2) {
+            const int L = (f * RB + rb) * PER + e, crb = L / (NB * 16), cnb = (L / 16) % NB, r = L % 16;
+            const float x0 = transform_one(nxt[crb][cnb][r], j1, crb, cnb, r, br);
+            const float x1 = transform_one(nxt[crb][cnb][r + 1], j1, crb, cnb, r + 1, br);
+            nxt[crb][cnb][r] = x0;
+            nxt[crb][cnb][r + 1] = x1;
+            mx[crb] = fmaxf(fmaxf(mx[crb], x0), x1);
+            asm volatile("" : "+v"(mx[crb]));
+          }
+        }
+        if constexpr (f == HALF) {
+          // all scores of the next tile are in: fold their row maxima into the running state
+          float mxs = half_swap_max(mx[rb]);
+          if constexpr (kPlain) mxs *= c_scale;    // scale > 0 (checked on the host)
+          const float m_old = m_run[0][rb];
+          float m_new = (mxs - m_old > kLazyMaxLog2) ? mxs : m_old;   // false for NaN (-inf - -inf)
+          m_new = advance ? m_new : m_old;
+          const bool moved = m_new != m_old;
+          alpha[rb] = moved ? fast_exp2(m_old - (m_new == -INFINITY ? 0.f : m_new)) : 1.f;
+          m_run[0][rb] = m_new;
+          l_run[0][rb] *= alpha[rb];
+          any = any || moved;
+          asm volatile("" : "+v"(alpha[rb]));
         }
         __builtin_amdgcn_sched_barrier(0);
       }
     });
+    if (__builtin_amdgcn_ballot_w64(any) != 0) {   // rare and wave-uniform
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      mx[rb] = half_swap_max(mx[rb]);
-      if constexpr (kPlain) mx[rb] *= c_scale;
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int d = 0; d < DVB; ++d)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[0][rb][d][r] *= alpha[rb];
     }
   }
 };
@@ -623,7 +652,7 @@ fwd_bf16_kernel(const FwdParams p) {
   }
   const int2* ksum = (MASK & kMaskDoc) ? p.kv_sum + (int64_t)b * nks : nullptr;
 
-  auto tile_keys = [&](int t) -> int2 {            // document-id range of the keys of tile t
+  auto tile_keys = [&](int t) __attribute__((always_inline)) -> int2 {            // document-id range of the keys of tile t
     int2 ks = ksum[min(t * NB, nks - 1)];
 #pragma unroll
     for (int u = 1; u < NB; ++u)
@@ -634,7 +663,7 @@ fwd_bf16_kernel(const FwdParams p) {
       }
     return ks;
   };
-  auto next_tile = [&](int t) -> int {             // uniform over the workgroup
+  auto next_tile = [&](int t) __attribute__((always_inline)) -> int {             // uniform over the workgroup
     if constexpr ((MASK & kMaskDoc) != 0) {
       while (t < t_hi && classify_block(MASK, i0, i_last, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg,
                                         tile_keys(t)) == kSkip)
@@ -642,7 +671,7 @@ fwd_bf16_kernel(const FwdParams p) {
     }
     return t;                                      // positional masks are already in [t_lo, t_hi)
   };
-  auto wave_class = [&](int t) -> int {            // uniform over the wave
+  auto wave_class = [&](int t) __attribute__((always_inline)) -> int {            // uniform over the wave
     if (t >= t_hi) return kTileSkip;
     int2 ks = make_int2(0, 0);
     if constexpr ((MASK & kMaskDoc) != 0) ks = tile_keys(t);
@@ -666,34 +695,40 @@ fwd_bf16_kernel(const FwdParams p) {
   const uint32_t kc_lane = swz_k<D>(kr_lane + wave * C::K_ROWS_PI, lane % (D / 8)) * 16;
   const uint32_t vc_lane = swz_v<DV>(vr_lane + wave * C::V_ROWS_PI, lane % (DV / 8)) * 16;
 
+  // Per-lane byte offsets inside one instruction's rows are loop invariant; per instruction only
+  // a uniform (scalar) row base changes.  In the ragged last tile, lanes whose row is past Sk
+  // take the address of row Sk - 1 instead.
+  const uint32_t k_lane_off[2] = {(uint32_t)kr_lane * (uint32_t)kss[0] + kc_lane,
+                                  (uint32_t)kr_lane * (uint32_t)kss[1] + kc_lane};
+  const uint32_t v_lane_off = (uint32_t)vr_lane * (uint32_t)vss + vc_lane;
   auto load_rows = [&](const unsigned char* base, int64_t stride, int j0, int n_instr, int rows_pi, int r_lane,
-                       uint32_t c_lane, int lds_off) {
+                       uint32_t lane_off, uint32_t c_lane, int lds_off) __attribute__((always_inline)) {
     const bool tail = j0 + BN > p.Sk;              // uniform
     for (int u = 0; u * C::NWAVES < n_instr; ++u) {
       const int gi = wave + u * C::NWAVES;         // wave-uniform instruction index
       if (n_instr % C::NWAVES != 0 && gi >= n_instr) break;
       lds_void* dst = (lds_void*)(lds_raw + lds_off + gi * 1024);
-      if (!tail) {
-        const unsigned char* rowbase = base + (int64_t)(j0 + gi * rows_pi) * stride;        // uniform
-        const uint32_t voff = (uint32_t)r_lane * (uint32_t)stride + c_lane;
-        __builtin_amdgcn_global_load_lds((global_cvoid*)(rowbase + voff), dst, 16, 0, 0);
+      const int jrow = j0 + gi * rows_pi;          // first row of this instruction (uniform)
+      const unsigned char* rowbase = base + (int64_t)jrow * stride;
+      if (__builtin_expect(!tail, 1)) {
+        __builtin_amdgcn_global_load_lds((global_cvoid*)(rowbase + lane_off), dst, 16, 0, 0);
       } else {
-        int jr = j0 + gi * rows_pi + r_lane;
-        jr = jr < p.Sk ? jr : p.Sk - 1;
-        __builtin_amdgcn_global_load_lds((global_cvoid*)(base + (int64_t)jr * stride + c_lane), dst, 16, 0, 0);
+        const unsigned char* last = base + (int64_t)(p.Sk - 1) * stride + c_lane;          // uniform + chunk
+        const unsigned char* src = jrow + r_lane < p.Sk ? rowbase + lane_off : last;
+        __builtin_amdgcn_global_load_lds((global_cvoid*)src, dst, 16, 0, 0);
       }
     }
   };
-  auto load_k = [&](int t, int buf) {
+  auto load_k = [&](int t, int buf) __attribute__((always_inline)) {
 #pragma unroll
     for (int s = 0; s < NS; ++s)
-      load_rows(kbase[s], kss[s], t * BN, C::K_INSTR, C::K_ROWS_PI, kr_lane, kc_lane,
+      load_rows(kbase[s], kss[s], t * BN, C::K_INSTR, C::K_ROWS_PI, kr_lane, k_lane_off[s], kc_lane,
                 C::K_RING + (buf * NS + s) * C::K_BYTES);
   };
-  auto load_v = [&](int t, int buf) {
-    load_rows(vbase, vss, t * BN, C::V_INSTR, C::V_ROWS_PI, vr_lane, vc_lane, C::V_RING + buf * C::V_BYTES);
+  auto load_v = [&](int t, int buf) __attribute__((always_inline)) {
+    load_rows(vbase, vss, t * BN, C::V_INSTR, C::V_ROWS_PI, vr_lane, v_lane_off, vc_lane, C::V_RING + buf * C::V_BYTES);
   };
-  auto wait_loads_and_sync = [&]() {
+  auto wait_loads_and_sync = [&]() __attribute__((always_inline)) {
     __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wave's direct loads have landed
     __syncthreads();
   };
@@ -709,7 +744,7 @@ fwd_bf16_kernel(const FwdParams p) {
     typename W::BiasRegs br;
     int t0 = next_tile(t_lo);
     if (t0 < t_hi) {
-      auto after = [&](int t) { return t < t_hi ? next_tile(t + 1) : t_hi; };
+      auto after = [&](int t) __attribute__((always_inline)) { return t < t_hi ? next_tile(t + 1) : t_hi; };
       int t1 = after(t0), t2 = after(t1), t3 = after(t2);   // RING == 3 uses the full look-ahead
       w.load_bias(br, t0 * BN);
       load_k(t0, 0);
@@ -723,17 +758,20 @@ fwd_bf16_kernel(const FwdParams p) {
       w.template qk<C::K_RING>(sa, 0);
       w.transform(sa, t0 * BN, br);
       float mx[RB];
-      w.rowmax(sa, mx);                            // valid if the tile is fully visible
       bool full0 = wave_class(t0) == kTileFull;
+      if (full0) {
+        w.rowmax(sa, mx);
+        w.advance_max(0, mx);
+      }
       __syncthreads();                             // everyone is done with K ring slot 0
       // Start of every step: finish the softmax bookkeeping of the current tile.  Only the
       // (rare) mask branch and the (rare) rescale branch live outside the big basic block.
-      auto settle = [&](typename W::Scores& cur) {
-        if (!full0) {
+      auto settle = [&](typename W::Scores& cur) __attribute__((always_inline)) {
+        if (!full0) {                              // fully visible tiles were settled in phase B
           w.mask(cur, t0 * BN);
           w.rowmax(cur, mx);
+          w.advance_max(0, mx);
         }
-        w.advance_max(0, mx);
       };
       // One pipeline step.  cur / nxt hold the scores of t0 / t1.  Step number N (mod 2 * RING)
       // fixes the roles at compile time: K(t0) and V(t0) sit in ring slot N % RING, K(t1) in the
@@ -741,7 +779,7 @@ fwd_bf16_kernel(const FwdParams p) {
       // RING = 3 it streams K(t3) and V(t2) in and only waits for what the previous step
       // started, so a tile has two full steps to arrive.  The last tile takes the same step:
       // its "next tile" contraction then runs on stale LDS contents and is never used.
-      auto step = [&](auto nc, typename W::Scores& cur, typename W::Scores& nxt) {
+      auto step = [&](auto nc, typename W::Scores& cur, typename W::Scores& nxt) __attribute__((always_inline)) {
         constexpr int N = decltype(nc)::value, R = C::RING;
         constexpr int s_cur = N % R, s_nxt = (N + 1) % R, s_far = (N + 2) % R;
         const bool full1 = wave_class(t1) == kTileFull;
@@ -758,7 +796,7 @@ fwd_bf16_kernel(const FwdParams p) {
           if (far_v) load_v(t2, s_far);
         }
         w.template phase_a<C::K_RING + s_nxt * C::K_BYTES>(nxt, cur, pr);
-        w.template phase_b<C::V_RING + s_cur * C::V_BYTES>(pr, nxt, t1 * BN, mx, br);
+        w.template phase_b<C::V_RING + s_cur * C::V_BYTES>(pr, nxt, t1 * BN, br, full1);
         if constexpr (R == 2) {
           __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
         } else {
@@ -778,7 +816,7 @@ fwd_bf16_kernel(const FwdParams p) {
       };
       while (true) {
         bool done = false;
-        static_for<0, 2 * C::RING>([&](auto nc) {
+        static_for<0, 2 * C::RING>([&](auto nc) __attribute__((always_inline)) {
           constexpr int N = decltype(nc)::value;
           if (!done) {
             if constexpr (N % 2 == 0) step(nc, sa, sb);
@@ -801,7 +839,7 @@ fwd_bf16_kernel(const FwdParams p) {
       load_v(t0, 0);
     }
     wait_loads_and_sync();
-    auto step = [&](auto bufc) {
+    auto step = [&](auto bufc) __attribute__((always_inline)) {
       constexpr int BUF = decltype(bufc)::value;
       const int t1 = next_tile(t0 + 1);
       if (t1 < t_hi) {
