@@ -52,6 +52,9 @@ fl_status check_data_tensor(const fl_tensor* t, const char* name, int want_dtype
     if (t->size[a] > 1 && (t->stride[a] * es) % 16 != 0)
       return fail(FL_ERR_ALIGN, "%s stride[%d] not a multiple of 16 bytes", name, a);
   }
+  // the kernels address the rows of one key tile with 32-bit byte offsets from the tile's base
+  if (t->size[3] > 1 && t->stride[3] >= (int64_t)1 << 23)
+    return fail(FL_ERR_STRIDE, "%s row stride %lld is not below 2^23 elements", name, (long long)t->stride[3]);
   return FL_OK;
 }
 

@@ -115,11 +115,11 @@ struct Bf16Cfg {
   static constexpr int NS = DIFF ? 2 : 1;          // softmax streams
   static constexpr int K_BYTES = BN * D * 2;
   static constexpr int V_BYTES = BN * DV * 2;
-  static constexpr int RING = RING_;               // slots of the K ring and of the V ring (2 or 3)
+  static constexpr int RING = RING_;               // slots of the K ring and of the V ring
   static constexpr int K_RING = 0;                 // LDS layout: K ring [RING][NS][K_BYTES], V ring [RING][V_BYTES]
   static constexpr int V_RING = RING * NS * K_BYTES;
   static constexpr int LDS_BYTES = V_RING + RING * V_BYTES;
-  static_assert(RING_ == 2 || (RING_ == 3 && !DIFF_), "ring of 3 is for the pipelined single-stream loop");
+  static_assert(RING_ == 2, "two slots per ring");
   static constexpr int K_INSTR = K_BYTES / 1024;   // 64-lane x 16-byte direct loads per K tile
   static constexpr int V_INSTR = V_BYTES / 1024;
   static constexpr int K_ROWS_PI = 64 / (D / 8);   // tile rows covered by one direct-load instruction
@@ -423,8 +423,8 @@ struct Wave {
   // ---- phase A of the pipeline, interleaved by construction: after every QK MFMA of the next
   // tile comes the exponential / sum / convert work of 16/KK scores of the current tile; empty
   // asm statements and scheduling barriers pin that order.
-  template <int KOFF>
-  __device__ __forceinline__ void phase_a(Scores& nxt, const Scores& cur, Probs& pr) {
+  template <int KOFF, class Hook>
+  __device__ __forceinline__ void phase_a(Scores& nxt, const Scores& cur, Probs& pr, Hook&& hook) {
     static_assert(!C::PSPLIT && NS == 1, "pipelined path is single-stream");
     constexpr int NF = NB * KK, PD = C::PD_K < NF ? C::PD_K : NF, PER = 16 / KK;     // PER scores of cur per MFMA (even)
     float m_safe[RB], psum[RB];
@@ -455,6 +455,8 @@ struct Wave {
         }
         __builtin_amdgcn_sched_barrier(0);
       }
+      hook(fc);                                    // the caller's tile loads, spread over the phase
+      __builtin_amdgcn_sched_barrier(0);
     });
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
@@ -692,41 +694,76 @@ fwd_bf16_kernel(const FwdParams p) {
   const unsigned char* vbase = (const unsigned char*)((const uint16_t*)p.v.ptr + b * p.v.sb + g * p.v.sg + hk * p.v.sh);
   const int64_t vss = p.v.ss * 2;
   const int kr_lane = lane / (D / 8), vr_lane = lane / (DV / 8);     // row within an instruction
-  const uint32_t kc_lane = swz_k<D>(kr_lane + wave * C::K_ROWS_PI, lane % (D / 8)) * 16;
-  const uint32_t vc_lane = swz_v<DV>(vr_lane + wave * C::V_ROWS_PI, lane % (DV / 8)) * 16;
 
-  // Per-lane byte offsets inside one instruction's rows are loop invariant; per instruction only
-  // a uniform (scalar) row base changes.  In the ragged last tile, lanes whose row is past Sk
-  // take the address of row Sk - 1 instead.
-  const uint32_t k_lane_off[2] = {(uint32_t)kr_lane * (uint32_t)kss[0] + kc_lane,
-                                  (uint32_t)kr_lane * (uint32_t)kss[1] + kc_lane};
-  const uint32_t v_lane_off = (uint32_t)vr_lane * (uint32_t)vss + vc_lane;
-  auto load_rows = [&](const unsigned char* base, int64_t stride, int j0, int n_instr, int rows_pi, int r_lane,
-                       uint32_t lane_off, uint32_t c_lane, int lds_off) __attribute__((always_inline)) {
-    const bool tail = j0 + BN > p.Sk;              // uniform
-    for (int u = 0; u * C::NWAVES < n_instr; ++u) {
-      const int gi = wave + u * C::NWAVES;         // wave-uniform instruction index
-      if (n_instr % C::NWAVES != 0 && gi >= n_instr) break;
-      lds_void* dst = (lds_void*)(lds_raw + lds_off + gi * 1024);
-      const int jrow = j0 + gi * rows_pi;          // first row of this instruction (uniform)
-      const unsigned char* rowbase = base + (int64_t)jrow * stride;
-      if (__builtin_expect(!tail, 1)) {
-        __builtin_amdgcn_global_load_lds((global_cvoid*)(rowbase + lane_off), dst, 16, 0, 0);
-      } else {
-        const unsigned char* last = base + (int64_t)(p.Sk - 1) * stride + c_lane;          // uniform + chunk
-        const unsigned char* src = jrow + r_lane < p.Sk ? rowbase + lane_off : last;
-        __builtin_amdgcn_global_load_lds((global_cvoid*)src, dst, 16, 0, 0);
+  // This wave issues instructions wave, wave + NWAVES, ... of a tile (wrapping around when a tile
+  // has fewer instructions than the workgroup has waves: the duplicates rewrite the same bytes).
+  // The byte offset of a lane inside the tile is loop invariant and fits 32 bits (the host bounds
+  // the row stride); per tile only a uniform 64-bit base changes.  In a ragged last tile the
+  // lanes whose row is past Sk take row Sk - 1 instead: clamp_k / clamp_v rewrite the offsets
+  // then, once, because tiles are visited in increasing order and nothing follows a ragged one.
+  constexpr int KPW = (C::K_INSTR + C::NWAVES - 1) / C::NWAVES, VPW = (C::V_INSTR + C::NWAVES - 1) / C::NWAVES;
+  uint32_t k_off[NS][KPW], v_off[VPW];
+  auto k_instr = [&](int u) __attribute__((always_inline)) { return (wave + u * C::NWAVES) % C::K_INSTR; };
+  auto v_instr = [&](int u) __attribute__((always_inline)) { return (wave + u * C::NWAVES) % C::V_INSTR; };
+  auto k_lane_off = [&](int s, int u, int row) __attribute__((always_inline)) {   // row: the tile row to fetch
+    const int dst_row = k_instr(u) * C::K_ROWS_PI + kr_lane;                         // decides the LDS chunk
+    return (uint32_t)row * (uint32_t)kss[s] + (uint32_t)swz_k<D>(dst_row, lane % (D / 8)) * 16u;
+  };
+  auto v_lane_off = [&](int u, int row) __attribute__((always_inline)) {
+    const int dst_row = v_instr(u) * C::V_ROWS_PI + vr_lane;
+    return (uint32_t)row * (uint32_t)vss + (uint32_t)swz_v<DV>(dst_row, lane % (DV / 8)) * 16u;
+  };
+#pragma unroll
+  for (int u = 0; u < KPW; ++u)
+#pragma unroll
+    for (int s = 0; s < NS; ++s) k_off[s][u] = k_lane_off(s, u, k_instr(u) * C::K_ROWS_PI + kr_lane);
+#pragma unroll
+  for (int u = 0; u < VPW; ++u) v_off[u] = v_lane_off(u, v_instr(u) * C::V_ROWS_PI + vr_lane);
+  auto clamp_k = [&](int t) __attribute__((always_inline)) {
+    const int nvalid = p.Sk - t * BN;              // uniform
+    if (nvalid < BN) {
+#pragma unroll
+      for (int u = 0; u < KPW; ++u)
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+          const int row = k_instr(u) * C::K_ROWS_PI + kr_lane;
+          k_off[s][u] = k_lane_off(s, u, row < nvalid ? row : nvalid - 1);
+        }
+    }
+  };
+  auto clamp_v = [&](int t) __attribute__((always_inline)) {
+    const int nvalid = p.Sk - t * BN;
+    if (nvalid < BN) {
+#pragma unroll
+      for (int u = 0; u < VPW; ++u) {
+        const int row = v_instr(u) * C::V_ROWS_PI + vr_lane;
+        v_off[u] = v_lane_off(u, row < nvalid ? row : nvalid - 1);
       }
     }
   };
+  // one load instruction of a K tile (stream s) / V tile whose first row is at `tile_base`
+  auto issue_k = [&](int s, int u, const unsigned char* tile_base, int lds_off) __attribute__((always_inline)) {
+    lds_void* dst = (lds_void*)(lds_raw + lds_off + k_instr(u) * 1024);
+    __builtin_amdgcn_global_load_lds((global_cvoid*)(tile_base + k_off[s][u]), dst, 16, 0, 0);
+  };
+  auto issue_v = [&](int u, const unsigned char* tile_base, int lds_off) __attribute__((always_inline)) {
+    lds_void* dst = (lds_void*)(lds_raw + lds_off + v_instr(u) * 1024);
+    __builtin_amdgcn_global_load_lds((global_cvoid*)(tile_base + v_off[u]), dst, 16, 0, 0);
+  };
+  auto k_tile_base = [&](int s, int t) __attribute__((always_inline)) { return kbase[s] + (int64_t)(t * BN) * kss[s]; };
+  auto v_tile_base = [&](int t) __attribute__((always_inline)) { return vbase + (int64_t)(t * BN) * vss; };
+  // whole-tile loads in one burst (prologue, two-stream loop)
   auto load_k = [&](int t, int buf) __attribute__((always_inline)) {
+    clamp_k(t);
 #pragma unroll
     for (int s = 0; s < NS; ++s)
-      load_rows(kbase[s], kss[s], t * BN, C::K_INSTR, C::K_ROWS_PI, kr_lane, k_lane_off[s], kc_lane,
-                C::K_RING + (buf * NS + s) * C::K_BYTES);
+#pragma unroll
+      for (int u = 0; u < KPW; ++u) issue_k(s, u, k_tile_base(s, t), C::K_RING + (buf * NS + s) * C::K_BYTES);
   };
   auto load_v = [&](int t, int buf) __attribute__((always_inline)) {
-    load_rows(vbase, vss, t * BN, C::V_INSTR, C::V_ROWS_PI, vr_lane, v_lane_off, vc_lane, C::V_RING + buf * C::V_BYTES);
+    clamp_v(t);
+#pragma unroll
+    for (int u = 0; u < VPW; ++u) issue_v(u, v_tile_base(t), C::V_RING + buf * C::V_BYTES);
   };
   auto wait_loads_and_sync = [&]() __attribute__((always_inline)) {
     __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wave's direct loads have landed
@@ -745,15 +782,11 @@ fwd_bf16_kernel(const FwdParams p) {
     int t0 = next_tile(t_lo);
     if (t0 < t_hi) {
       auto after = [&](int t) __attribute__((always_inline)) { return t < t_hi ? next_tile(t + 1) : t_hi; };
-      int t1 = after(t0), t2 = after(t1), t3 = after(t2);   // RING == 3 uses the full look-ahead
+      int t1 = after(t0), t2 = after(t1);
       w.load_bias(br, t0 * BN);
       load_k(t0, 0);
       load_v(t0, 0);
       if (t1 < t_hi) load_k(t1, 1);
-      if constexpr (C::RING == 3) {
-        if (t1 < t_hi) load_v(t1, 1);
-        if (t2 < t_hi) load_k(t2, 2);
-      }
       wait_loads_and_sync();
       w.template qk<C::K_RING>(sa, 0);
       w.transform(sa, t0 * BN, br);
@@ -773,50 +806,44 @@ fwd_bf16_kernel(const FwdParams p) {
           w.advance_max(0, mx);
         }
       };
-      // One pipeline step.  cur / nxt hold the scores of t0 / t1.  Step number N (mod 2 * RING)
-      // fixes the roles at compile time: K(t0) and V(t0) sit in ring slot N % RING, K(t1) in the
-      // next slot.  With RING = 2 the step streams K(t2) and V(t1) in and waits for both; with
-      // RING = 3 it streams K(t3) and V(t2) in and only waits for what the previous step
-      // started, so a tile has two full steps to arrive.  The last tile takes the same step:
-      // its "next tile" contraction then runs on stale LDS contents and is never used.
+      // One pipeline step.  cur / nxt hold the scores of t0 / t1.  Step number N (mod 4) fixes
+      // the roles at compile time: K(t0) and V(t0) sit in ring slot N % 2, K(t1) in the other
+      // one.  The step streams K(t2) into the slot K(t0) left in the previous step and V(t1) into
+      // the slot V(t-1) left; both are free for the whole step, so the load instructions are
+      // spread over phase A (a burst of them right after the barrier stalls every wave of the
+      // workgroup in the memory pipeline while the matrix cores idle).  Past the end of the tile
+      // list the loads simply repeat the last tile, and the last tile takes the same step: its
+      // "next tile" contraction then runs on stale LDS contents and is never used.
       auto step = [&](auto nc, typename W::Scores& cur, typename W::Scores& nxt) __attribute__((always_inline)) {
-        constexpr int N = decltype(nc)::value, R = C::RING;
-        constexpr int s_cur = N % R, s_nxt = (N + 1) % R, s_far = (N + 2) % R;
+        constexpr int N = decltype(nc)::value;
+        constexpr int s_cur = N % 2, s_nxt = (N + 1) % 2;
         const bool full1 = wave_class(t1) == kTileFull;
         settle(cur);
         if (t1 < t_hi) w.load_bias(br, t1 * BN);   // before the tile loads: its wait then excludes them
-        bool far_k = false, far_v = false;
-        if constexpr (R == 2) {
-          if (t2 < t_hi) load_k(t2, s_cur);
-          if (t1 < t_hi) load_v(t1, s_nxt);
-        } else {
-          far_k = t3 < t_hi;
-          far_v = t2 < t_hi;
-          if (far_k) load_k(t3, s_cur);
-          if (far_v) load_v(t2, s_far);
-        }
-        w.template phase_a<C::K_RING + s_nxt * C::K_BYTES>(nxt, cur, pr);
+        const int tk = t2 < t_hi ? t2 : t_hi - 1, tv = t1 < t_hi ? t1 : t_hi - 1;
+        clamp_k(tk);
+        clamp_v(tv);
+        const unsigned char* kb = k_tile_base(0, tk);
+        const unsigned char* vb = v_tile_base(tv);
+        w.template phase_a<C::K_RING + s_nxt * C::K_BYTES>(nxt, cur, pr, [&](auto fc) __attribute__((always_inline)) {
+          constexpr int f = decltype(fc)::value, NF = NB * KK, LPW = KPW + VPW;
+          static_for<0, KPW>([&](auto u) __attribute__((always_inline)) {
+            if constexpr (f == ((2 * u + 1) * NF) / (2 * LPW)) issue_k(0, u, kb, C::K_RING + s_cur * C::K_BYTES);
+          });
+          static_for<0, VPW>([&](auto u) __attribute__((always_inline)) {
+            if constexpr (f == ((2 * (KPW + u) + 1) * NF) / (2 * LPW)) issue_v(u, vb, C::V_RING + s_nxt * C::V_BYTES);
+          });
+        });
         w.template phase_b<C::V_RING + s_cur * C::V_BYTES>(pr, nxt, t1 * BN, br, full1);
-        if constexpr (R == 2) {
-          __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
-        } else {
-          // loads of this step may stay in flight; every wave issued at least this many
-          constexpr int LK = C::K_INSTR / C::NWAVES, LV = C::V_INSTR / C::NWAVES;
-          static_assert(LK + LV <= 15, "vmcnt immediate");
-          if (far_k) __builtin_amdgcn_s_waitcnt(0x0F70 | (LK + LV));
-          else if (far_v) __builtin_amdgcn_s_waitcnt(0x0F70 | LV);
-          else __builtin_amdgcn_s_waitcnt(0x0F70);
-        }
-        __syncthreads();
+        wait_loads_and_sync();
         t0 = t1;
         t1 = t2;
-        t2 = t3;
-        t3 = after(t3);
+        t2 = t2 < t_hi ? next_tile(t2 + 1) : t_hi;
         full0 = full1;
       };
       while (true) {
         bool done = false;
-        static_for<0, 2 * C::RING>([&](auto nc) __attribute__((always_inline)) {
+        static_for<0, 4>([&](auto nc) __attribute__((always_inline)) {
           constexpr int N = decltype(nc)::value;
           if (!done) {
             if constexpr (N % 2 == 0) step(nc, sa, sb);
