@@ -103,9 +103,8 @@ struct Bf16Cfg {
   static constexpr bool PSPLIT = DIFF_ && (EPI_ & kEpiRms) != 0;
   static constexpr bool PIPE = !DIFF_;             // two score tiles in flight (see header)
   static constexpr int WPE = WPE_;                 // waves per SIMD the register budget is set for
-  static constexpr int PD_K = 2;                   // K fragments read ahead of their MFMA
-  static constexpr int PD_V = 3;                   // V^T fragments (two reads each) read ahead
-                                                   // (measured: deeper read-ahead changes nothing)
+  static constexpr int GK = 2;                     // K fragments per LDS wait (read one group ahead)
+  static constexpr int GV = 2;                     // V^T fragments (two reads each) per LDS wait
   static constexpr int NT = NWAVES * 64;
   static constexpr int WROWS = 32 * RB;            // query rows per wave
   static constexpr int BM = NWAVES * WROWS;        // query rows per workgroup
@@ -190,32 +189,67 @@ struct Wave {
       asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(a), "n"(8 * DV * 2) : "memory");
     }
   }
+  // Wait until at most N younger LDS operations are in flight.  The scheduling barrier keeps the
+  // consumer of the fragment below the wait; no register operand ties the two together, because
+  // the hazard checker treats every register an asm statement writes as freshly written by an
+  // unknown instruction and pads the following MFMA with idle cycles.
   template <int N>
-  static __device__ __forceinline__ void wait_k(i32x4& f) {       // allow N younger LDS ops in flight
+  static __device__ __forceinline__ void wait_lds() {
     static_assert(N >= 0 && N <= 15, "lgkmcnt is a 4-bit counter");
-    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(f) : "n"(N));
+    asm volatile("s_waitcnt lgkmcnt(%0)" : : "n"(N) : "memory");
+    __builtin_amdgcn_sched_barrier(0);
   }
-  template <int N>
-  static __device__ __forceinline__ void wait_vt(i32x2& lo, i32x2& hi) {
-    static_assert(N >= 0 && N <= 15, "lgkmcnt is a 4-bit counter");
-    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(lo), "+v"(hi) : "n"(N));
+
+  // ---- fragment streams.  A wave issues at most one instruction every few cycles whatever its
+  // kind, so the loop is built to need few of them: fragments are read from LDS one group ahead
+  // and one wait covers a whole group.  body(f, fragment) is called in fragment order.
+  template <int KOFF, class Body>
+  __device__ __forceinline__ void k_stream(Body&& body) const {
+    constexpr int NF = NB * KK, G = C::GK < NF ? C::GK : NF, NG = NF / G;   // fragments (nb, kk)
+    static_assert(NF % G == 0, "K fragment groups");
+    i32x4 kf[NF];
+    static_for<0, G>([&](auto f) __attribute__((always_inline)) { read_k<KOFF + (f / KK) * (32 * D * 2)>(kf[f], ka[f % KK]); });
+    static_for<0, NG>([&](auto gc) __attribute__((always_inline)) {
+      constexpr int g = gc;
+      if constexpr (g + 1 < NG)
+        static_for<(g + 1) * G, (g + 2) * G>([&](auto f) __attribute__((always_inline)) {
+          read_k<KOFF + (f / KK) * (32 * D * 2)>(kf[f], ka[f % KK]);
+        });
+      wait_lds<(g + 1 < NG) ? G : 0>();
+      static_for<g * G, (g + 1) * G>([&](auto f) __attribute__((always_inline)) { body(f, __builtin_bit_cast(bf16x8, kf[f])); });
+    });
+  }
+  template <int VOFF, class Body>
+  __device__ __forceinline__ void v_stream(Body&& body) const {
+    constexpr int NF = NB * 2 * DVB, G = C::GV < NF ? C::GV : NF, NG = NF / G;   // fragments (nb, ks, d)
+    static_assert(NF % G == 0, "V fragment groups");
+    i32x2 lo[NF], hi[NF];
+    static_for<0, G>([&](auto f) __attribute__((always_inline)) {
+      read_vt<VOFF + (32 * (f / (2 * DVB)) + 16 * ((f / DVB) % 2)) * (DV * 2)>(lo[f], hi[f], va[f % DVB]);
+    });
+    static_for<0, NG>([&](auto gc) __attribute__((always_inline)) {
+      constexpr int g = gc;
+      if constexpr (g + 1 < NG)
+        static_for<(g + 1) * G, (g + 2) * G>([&](auto f) __attribute__((always_inline)) {
+          read_vt<VOFF + (32 * (f / (2 * DVB)) + 16 * ((f / DVB) % 2)) * (DV * 2)>(lo[f], hi[f], va[f % DVB]);
+        });
+      wait_lds<(g + 1 < NG) ? 2 * G : 0>();
+      static_for<g * G, (g + 1) * G>([&](auto f) __attribute__((always_inline)) {
+        body(f, __builtin_bit_cast(bf16x8, (i32x4){lo[f][0], lo[f][1], hi[f][0], hi[f][1]}));
+      });
+    });
   }
 
   // ---- first contraction of stream s: S^T = K Q^T for all row blocks, K tile at LDS offset KOFF
   template <int KOFF>
   __device__ __forceinline__ void qk(Scores& sc, int s) const {
-    constexpr int NF = NB * KK, PD = C::PD_K < NF ? C::PD_K : NF;   // fragments (nb, kk), prefetch distance
-    i32x4 kf[NF];
     f32x16 acc[RB];
-    static_for<0, PD>([&](auto f) __attribute__((always_inline)) { read_k<KOFF + (f / KK) * (32 * D * 2)>(kf[f], ka[f % KK]); });
-    static_for<0, NF>([&](auto fc) __attribute__((always_inline)) {
+    k_stream<KOFF>([&](auto fc, bf16x8 a) __attribute__((always_inline)) {
       constexpr int f = fc, kk = f % KK, nb = f / KK;
-      if constexpr (f + PD < NF) read_k<KOFF + ((f + PD) / KK) * (32 * D * 2)>(kf[f + PD], ka[(f + PD) % KK]);
-      wait_k<(NF - 1 - f) < PD ? (NF - 1 - f) : PD>(kf[f]);
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
         if (kk == 0) acc[rb] = zero16();
-        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[f]), qf[s][rb][kk], acc[rb], 0, 0, 0);
+        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s][rb][kk], acc[rb], 0, 0, 0);
         if (kk == KK - 1) sc[rb][nb] = acc[rb];
       }
     });
@@ -360,9 +394,8 @@ struct Wave {
     }
   }
 
-  // ---- one probability pair: p = exp2(s - m), running row sum, bf16 pair (and remainder)
-  __device__ __forceinline__ void exp_pair(float s0, float s1, float m_safe, float& psum, uint32_t& w, uint32_t& wl) const {
-    float p0, p1;
+  // ---- one probability pair: p = exp2(s - m); then running row sum and bf16 pair (and remainder)
+  __device__ __forceinline__ void exp_only(float s0, float s1, float m_safe, float& p0, float& p1) const {
     if constexpr (kPlain) {
       p0 = fast_exp2(fmaf(s0, c_scale, -m_safe));
       p1 = fast_exp2(fmaf(s1, c_scale, -m_safe));
@@ -370,6 +403,8 @@ struct Wave {
       p0 = fast_exp2(s0 - m_safe);
       p1 = fast_exp2(s1 - m_safe);
     }
+  }
+  __device__ __forceinline__ void sum_pack(float p0, float p1, float& psum, uint32_t& w, uint32_t& wl) const {
     psum += p0 + p1;
     w = pack_bf16(p0, p1);
     if constexpr (C::PSPLIT) wl = pack_bf16(p0 - __uint_as_float(w << 16), p1 - __uint_as_float(w & 0xFFFF0000u));
@@ -385,7 +420,11 @@ struct Wave {
       for (int nb = 0; nb < NB; ++nb) {
         uint32_t w[8], wl[8];
 #pragma unroll
-        for (int r = 0; r < 16; r += 2) exp_pair(sc[rb][nb][r], sc[rb][nb][r + 1], m_safe, psum, w[r >> 1], wl[r >> 1]);
+        for (int r = 0; r < 16; r += 2) {
+          float p0, p1;
+          exp_only(sc[rb][nb][r], sc[rb][nb][r + 1], m_safe, p0, p1);
+          sum_pack(p0, p1, psum, w[r >> 1], wl[r >> 1]);
+        }
         pr.hi[rb][nb][0] = __builtin_bit_cast(bf16x8, (i32x4){(int)w[0], (int)w[1], (int)w[2], (int)w[3]});
         pr.hi[rb][nb][1] = __builtin_bit_cast(bf16x8, (i32x4){(int)w[4], (int)w[5], (int)w[6], (int)w[7]});
         if constexpr (C::PSPLIT) {
@@ -400,17 +439,8 @@ struct Wave {
   // ---- second contraction of stream s: O^T += V^T P^T, V tile at LDS byte offset VOFF
   template <int VOFF>
   __device__ __forceinline__ void pv(const Probs& pr, int s) {
-    constexpr int NF = NB * 2 * DVB, PD = NF < C::PD_V ? NF : C::PD_V;   // fragments (nb, ks, d), prefetch distance
-    i32x2 lo[NF], hi[NF];
-    static_for<0, PD>([&](auto f) __attribute__((always_inline)) {
-      read_vt<VOFF + (32 * (f / (2 * DVB)) + 16 * ((f / DVB) % 2)) * (DV * 2)>(lo[f], hi[f], va[f % DVB]);
-    });
-    static_for<0, NF>([&](auto fc) __attribute__((always_inline)) {
-      constexpr int f = fc, d = f % DVB, ks = (f / DVB) % 2, nb = f / (2 * DVB), g2 = f + PD;
-      if constexpr (g2 < NF)
-        read_vt<VOFF + (32 * (g2 / (2 * DVB)) + 16 * ((g2 / DVB) % 2)) * (DV * 2)>(lo[g2], hi[g2], va[g2 % DVB]);
-      wait_vt<2 * ((NF - 1 - f) < PD ? (NF - 1 - f) : PD)>(lo[f], hi[f]);
-      const bf16x8 a = __builtin_bit_cast(bf16x8, (i32x4){lo[f][0], lo[f][1], hi[f][0], hi[f][1]});
+    v_stream<VOFF>([&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+      constexpr int f = fc, d = f % DVB, ks = (f / DVB) % 2, nb = f / (2 * DVB);
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
         oacc[s][rb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pr.hi[rb][nb][ks], oacc[s][rb][d], 0, 0, 0);
@@ -421,12 +451,17 @@ struct Wave {
   }
 
   // ---- phase A of the pipeline, interleaved by construction: after every QK MFMA of the next
-  // tile comes the exponential / sum / convert work of 16/KK scores of the current tile; empty
-  // asm statements and scheduling barriers pin that order.
+  // tile comes the exponential work of 16/KK scores of the current tile; their row sum and bf16
+  // conversion follow one pair later (a transcendental result cannot be consumed by the very
+  // next instruction without an idle cycle).  Scheduling barriers pin the order; the empty asm
+  // statement keeps the sum and the conversion from being sunk out of the loop body.
+  // hook(f) runs after the work of fragment f: the caller's tile loads.
   template <int KOFF, class Hook>
   __device__ __forceinline__ void phase_a(Scores& nxt, const Scores& cur, Probs& pr, Hook&& hook) {
     static_assert(!C::PSPLIT && NS == 1, "pipelined path is single-stream");
-    constexpr int NF = NB * KK, PD = C::PD_K < NF ? C::PD_K : NF, PER = 16 / KK;     // PER scores of cur per MFMA (even)
+    constexpr int PPM = 8 / KK;                    // score pairs of cur per MFMA (KK = 2, 4 or 8)
+    constexpr int NPAIR = RB * NB * 8;
+    static_assert(PPM * NB * KK * RB == NPAIR, "every pair is visited once");
     float m_safe[RB], psum[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
@@ -434,30 +469,35 @@ struct Wave {
       psum[rb] = 0.f;
     }
     uint32_t w[RB][NB][8], wl_unused = 0;
-    i32x4 kf[NF];
+    float e0 = 0.f, e1 = 0.f;                      // the pair whose sum / conversion is still due
     f32x16 acc[RB];
-    static_for<0, PD>([&](auto f) __attribute__((always_inline)) { read_k<KOFF + (f / KK) * (32 * D * 2)>(kf[f], ka[f % KK]); });
-    static_for<0, NF>([&](auto fc) __attribute__((always_inline)) {
+    k_stream<KOFF>([&](auto fc, bf16x8 a) __attribute__((always_inline)) {
       constexpr int f = fc, kk = f % KK, nb = f / KK;
-      if constexpr (f + PD < NF) read_k<KOFF + ((f + PD) / KK) * (32 * D * 2)>(kf[f + PD], ka[(f + PD) % KK]);
-      wait_k<(NF - 1 - f) < PD ? (NF - 1 - f) : PD>(kf[f]);
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
         if (kk == 0) acc[rb] = zero16();
-        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[f]), qf[0][rb][kk], acc[rb], 0, 0, 0);
+        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][rb][kk], acc[rb], 0, 0, 0);
         if (kk == KK - 1) nxt[rb][nb] = acc[rb];
-        // this MFMA's share of the current tile: scores L .. L+PER-1 in [rb][nb][16] order
 #pragma unroll
-        for (int e = 0; e < PER; e += 2) {
-          const int L = (f * RB + rb) * PER + e, crb = L / (NB * 16), cnb = (L / 16) % NB, r = L % 16;
-          exp_pair(cur[crb][cnb][r], cur[crb][cnb][r + 1], m_safe[crb], psum[crb], w[crb][cnb][r >> 1], wl_unused);
-          asm volatile("" : "+v"(w[crb][cnb][r >> 1]), "+v"(psum[crb]));
+        for (int e = 0; e < PPM; ++e) {
+          const int q = (f * RB + rb) * PPM + e;   // pair index in [rb][nb][8] order
+          const int crb = q / (NB * 8), cnb = (q / 8) % NB, r2 = q % 8;
+          float n0, n1;
+          exp_only(cur[crb][cnb][2 * r2], cur[crb][cnb][2 * r2 + 1], m_safe[crb], n0, n1);
+          if (q > 0) {
+            const int qp = q - 1, prb = qp / (NB * 8), pnb = (qp / 8) % NB, pr2 = qp % 8;
+            sum_pack(e0, e1, psum[prb], w[prb][pnb][pr2], wl_unused);
+            asm volatile("" : "+v"(w[prb][pnb][pr2]), "+v"(psum[prb]));
+          }
+          e0 = n0;
+          e1 = n1;
         }
         __builtin_amdgcn_sched_barrier(0);
       }
-      hook(fc);                                    // the caller's tile loads, spread over the phase
+      hook(fc);
       __builtin_amdgcn_sched_barrier(0);
     });
+    sum_pack(e0, e1, psum[RB - 1], w[RB - 1][NB - 1][7], wl_unused);
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
@@ -477,10 +517,9 @@ struct Wave {
   // the last MFMA.
   template <int VOFF>
   __device__ __forceinline__ void phase_b(const Probs& pr, Scores& nxt, int j1, const BiasRegs& br, bool advance) {
-    constexpr int NF = NB * 2 * DVB, PD = NF < C::PD_V ? NF : C::PD_V;
+    constexpr int NF = NB * 2 * DVB;
     constexpr int HALF = NF / 2, PER = 16 / DVB;   // scores of nxt per MFMA in the first half
     static_assert(NF % 2 == 0 && PER % 2 == 0, "chunking");
-    i32x2 lo[NF], hi[NF];
     float mx[RB], alpha[RB];
     bool any = false;
 #pragma unroll
@@ -488,15 +527,8 @@ struct Wave {
       mx[rb] = -INFINITY;
       alpha[rb] = 1.f;
     }
-    static_for<0, PD>([&](auto f) __attribute__((always_inline)) {
-      read_vt<VOFF + (32 * (f / (2 * DVB)) + 16 * ((f / DVB) % 2)) * (DV * 2)>(lo[f], hi[f], va[f % DVB]);
-    });
-    static_for<0, NF>([&](auto fc) __attribute__((always_inline)) {
-      constexpr int f = fc, d = f % DVB, ks = (f / DVB) % 2, nb = f / (2 * DVB), g2 = f + PD;
-      if constexpr (g2 < NF)
-        read_vt<VOFF + (32 * (g2 / (2 * DVB)) + 16 * ((g2 / DVB) % 2)) * (DV * 2)>(lo[g2], hi[g2], va[g2 % DVB]);
-      wait_vt<2 * ((NF - 1 - f) < PD ? (NF - 1 - f) : PD)>(lo[f], hi[f]);
-      const bf16x8 a = __builtin_bit_cast(bf16x8, (i32x4){lo[f][0], lo[f][1], hi[f][0], hi[f][1]});
+    v_stream<VOFF>([&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+      constexpr int f = fc, d = f % DVB, ks = (f / DVB) % 2, nb = f / (2 * DVB);
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
         oacc[0][rb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pr.hi[rb][nb][ks], oacc[0][rb][d], 0, 0, 0);
@@ -509,7 +541,6 @@ struct Wave {
             nxt[crb][cnb][r] = x0;
             nxt[crb][cnb][r + 1] = x1;
             mx[crb] = fmaxf(fmaxf(mx[crb], x0), x1);
-            asm volatile("" : "+v"(mx[crb]));
           }
         }
         if constexpr (f == HALF) {
@@ -524,7 +555,6 @@ struct Wave {
           m_run[0][rb] = m_new;
           l_run[0][rb] *= alpha[rb];
           any = any || moved;
-          asm volatile("" : "+v"(alpha[rb]));
         }
         __builtin_amdgcn_sched_barrier(0);
       }
