@@ -92,7 +92,7 @@ __device__ __forceinline__ int swz_v(int r, int c) {
 }
 
 template <int D_, int DV_, int NWAVES_, int RB_, int BN_, int WPE_, int MOD_, uint32_t MASK_, int NBIAS_,
-          bool DIFF_, uint32_t EPI_, int RING_ = 2>
+          bool DIFF_, uint32_t EPI_, bool STAG_ = false>
 struct Bf16Cfg {
   static constexpr int D = D_, DV = DV_, NWAVES = NWAVES_, RB = RB_, BN = BN_, MOD = MOD_, NBIAS = NBIAS_;
   static constexpr uint32_t MASK = MASK_, EPI = EPI_;
@@ -114,11 +114,17 @@ struct Bf16Cfg {
   static constexpr int NS = DIFF ? 2 : 1;          // softmax streams
   static constexpr int K_BYTES = BN * D * 2;
   static constexpr int V_BYTES = BN * DV * 2;
-  static constexpr int RING = RING_;               // slots of the K ring and of the V ring
+  static constexpr int RING = 2;                   // slots of the K ring and of the V ring
   static constexpr int K_RING = 0;                 // LDS layout: K ring [RING][NS][K_BYTES], V ring [RING][V_BYTES]
   static constexpr int V_RING = RING * NS * K_BYTES;
   static constexpr int LDS_BYTES = V_RING + RING * V_BYTES;
-  static_assert(RING_ == 2, "two slots per ring");
+  // Staggered schedule: the two waves of a SIMD (waves w and w + 4 of the workgroup) run half a
+  // pipeline step apart, so that the exponential-heavy phase A of one meets the matrix-heavy
+  // phase B of the other instead of both queueing for the vector ALU first and the matrix core
+  // afterwards.
+  static constexpr bool STAG = STAG_;
+  static_assert(!STAG_ || (!DIFF_ && NWAVES_ == 8 && D_ == DV_ && (BN_ * D_ * 2 / 1024) % 4 == 0),
+                "staggered schedule: pipelined 8-wave kernels with equal head dims");
   static constexpr int K_INSTR = K_BYTES / 1024;   // 64-lane x 16-byte direct loads per K tile
   static constexpr int V_INSTR = V_BYTES / 1024;
   static constexpr int K_ROWS_PI = 64 / (D / 8);   // tile rows covered by one direct-load instruction
@@ -450,26 +456,68 @@ struct Wave {
     });
   }
 
-  // ---- phase A of the pipeline, interleaved by construction: after every QK MFMA of the next
-  // tile comes the exponential work of 16/KK scores of the current tile; their row sum and bf16
-  // conversion follow one pair later (a transcendental result cannot be consumed by the very
-  // next instruction without an idle cycle).  Scheduling barriers pin the order; the empty asm
-  // statement keeps the sum and the conversion from being sunk out of the loop body.
+  // ---- software pipeline of the single-stream variants.  A wave issues at most one vector or
+  // matrix instruction every few cycles, so what bounds a step is the number of instructions of
+  // each phase; the softmax work of a tile is therefore cut in two halves of equal length:
+  //   phase A:  QK MFMAs of the next tile  +  exponentials of the first half of the current tile
+  //             (the half the second contraction consumes first), then the transform / row max
+  //             of the next tile's first key block, which is complete by then;
+  //   phase B:  PV MFMAs of the current tile  +  exponentials of its second half during the
+  //             MFMAs that consume the first, then the transform / row max of the next tile's
+  //             last key block and the running-max update (Alg. 2 / Sec. 3.4).
+  // The sum / bf16 conversion of a pair follows one pair after its exponentials (a
+  // transcendental result cannot be consumed by the very next instruction without an idle
+  // cycle).  Scheduling barriers pin the order; the empty asm statement keeps the sum and the
+  // conversion from being sunk out of the loop body.
+  struct Pipe {
+    uint32_t w[C::RB][C::NB][8];   // bf16 pairs of the current tile's probabilities
+    float e0, e1;                  // the pair of exponentials whose sum / conversion is still due
+    float psum[C::RB], m_safe[C::RB];
+    float mx[C::RB];               // row maxima of the next tile so far
+  };
+  static constexpr int NPAIR = C::RB * C::NB * 8;  // probability pairs of a tile per lane
+  static_assert(NB == 1 || NB == 2, "the pipeline splits a tile into at most two key blocks");
+
+  // pair q in the order the second contraction needs them: (key block, k-step) major, then row block
+  __device__ __forceinline__ void exp_step(const Scores& cur, Pipe& ps, int q, int q_first) {
+    const int h = q / (4 * RB), rb = (q / 4) % RB, nb = h / 2, r2 = (h % 2) * 4 + q % 4;
+    float n0, n1;
+    exp_only(cur[rb][nb][2 * r2], cur[rb][nb][2 * r2 + 1], ps.m_safe[rb], n0, n1);
+    if (q > q_first) finish_pair(ps, q - 1);
+    ps.e0 = n0;
+    ps.e1 = n1;
+  }
+  __device__ __forceinline__ void finish_pair(Pipe& ps, int q) {
+    const int h = q / (4 * RB), rb = (q / 4) % RB, nb = h / 2, r2 = (h % 2) * 4 + q % 4;
+    uint32_t unused = 0;
+    sum_pack(ps.e0, ps.e1, ps.psum[rb], ps.w[rb][nb][r2], unused);
+    asm volatile("" : "+v"(ps.w[rb][nb][r2]), "+v"(ps.psum[rb]));
+  }
+  // two scores of key block nb of the next tile: variant transform in place, row max
+  __device__ __forceinline__ void max_step(Scores& nxt, Pipe& ps, int nb, int L, int j1, const BiasRegs& br) {
+    const int rb = L / 16, r = L % 16;
+    const float x0 = transform_one(nxt[rb][nb][r], j1, rb, nb, r, br);
+    const float x1 = transform_one(nxt[rb][nb][r + 1], j1, rb, nb, r + 1, br);
+    nxt[rb][nb][r] = x0;
+    nxt[rb][nb][r + 1] = x1;
+    ps.mx[rb] = fmaxf(fmaxf(ps.mx[rb], x0), x1);
+  }
+
   // hook(f) runs after the work of fragment f: the caller's tile loads.
   template <int KOFF, class Hook>
-  __device__ __forceinline__ void phase_a(Scores& nxt, const Scores& cur, Probs& pr, Hook&& hook) {
+  __device__ __forceinline__ void phase_a(Scores& nxt, const Scores& cur, Pipe& ps, int j1, const BiasRegs& br,
+                                          Hook&& hook) {
     static_assert(!C::PSPLIT && NS == 1, "pipelined path is single-stream");
-    constexpr int PPM = 8 / KK;                    // score pairs of cur per MFMA (KK = 2, 4 or 8)
-    constexpr int NPAIR = RB * NB * 8;
-    static_assert(PPM * NB * KK * RB == NPAIR, "every pair is visited once");
-    float m_safe[RB], psum[RB];
+    constexpr int NF = NB * KK;
+    constexpr int SE = (NB == 2 ? KK : NF) * RB;   // slots (fragment, row block) that carry exponentials
+    constexpr int PA = NPAIR / 2;                  // pairs of the first half
+    constexpr int SM = NF * RB - SE;               // slots that carry the max of key block 0 (NB == 2)
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      m_safe[rb] = m_run[0][rb] == -INFINITY ? 0.f : m_run[0][rb];
-      psum[rb] = 0.f;
+      ps.m_safe[rb] = m_run[0][rb] == -INFINITY ? 0.f : m_run[0][rb];
+      ps.psum[rb] = 0.f;
+      ps.mx[rb] = -INFINITY;
     }
-    uint32_t w[RB][NB][8], wl_unused = 0;
-    float e0 = 0.f, e1 = 0.f;                      // the pair whose sum / conversion is still due
     f32x16 acc[RB];
     k_stream<KOFF>([&](auto fc, bf16x8 a) __attribute__((always_inline)) {
       constexpr int f = fc, kk = f % KK, nb = f / KK;
@@ -478,87 +526,70 @@ struct Wave {
         if (kk == 0) acc[rb] = zero16();
         acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][rb][kk], acc[rb], 0, 0, 0);
         if (kk == KK - 1) nxt[rb][nb] = acc[rb];
+        const int slot = f * RB + rb;
+        if (slot < SE) {
 #pragma unroll
-        for (int e = 0; e < PPM; ++e) {
-          const int q = (f * RB + rb) * PPM + e;   // pair index in [rb][nb][8] order
-          const int crb = q / (NB * 8), cnb = (q / 8) % NB, r2 = q % 8;
-          float n0, n1;
-          exp_only(cur[crb][cnb][2 * r2], cur[crb][cnb][2 * r2 + 1], m_safe[crb], n0, n1);
-          if (q > 0) {
-            const int qp = q - 1, prb = qp / (NB * 8), pnb = (qp / 8) % NB, pr2 = qp % 8;
-            sum_pack(e0, e1, psum[prb], w[prb][pnb][pr2], wl_unused);
-            asm volatile("" : "+v"(w[prb][pnb][pr2]), "+v"(psum[prb]));
-          }
-          e0 = n0;
-          e1 = n1;
+          for (int q = slot * PA / SE; q < (slot + 1) * PA / SE; ++q) exp_step(cur, ps, q, 0);
+        } else {
+          const int sm = slot - SE;                // pairs of scores of key block 0, all row blocks
+#pragma unroll
+          for (int u = sm * (8 * RB) / SM; u < (sm + 1) * (8 * RB) / SM; ++u) max_step(nxt, ps, 0, 2 * u, j1, br);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
       hook(fc);
       __builtin_amdgcn_sched_barrier(0);
     });
-    sum_pack(e0, e1, psum[RB - 1], w[RB - 1][NB - 1][7], wl_unused);
+    finish_pair(ps, PA - 1);
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        pr.hi[rb][nb][0] = __builtin_bit_cast(bf16x8, (i32x4){(int)w[rb][nb][0], (int)w[rb][nb][1], (int)w[rb][nb][2], (int)w[rb][nb][3]});
-        pr.hi[rb][nb][1] = __builtin_bit_cast(bf16x8, (i32x4){(int)w[rb][nb][4], (int)w[rb][nb][5], (int)w[rb][nb][6], (int)w[rb][nb][7]});
-      }
-      l_run[0][rb] += psum[rb];
-    }
+    for (int rb = 0; rb < RB; ++rb) asm volatile("" : "+v"(ps.mx[rb]));   // block 0's maxima stay in this phase
   }
 
-  // ---- phase B: the PV MFMAs of the current tile, with the transform and running max of the
-  // next tile's scores spread over the first half of them and, right after, the running-max
-  // update (Alg. 2 / Sec. 3.4) that this row maximum triggers -- so that the next step can start
-  // straight away.  `advance` (uniform) is false when the next tile still needs its mask: then
-  // the update is left to the start of the next step.  The O rescale is a rare branch after
-  // the last MFMA.
+  // `advance` (uniform) is false when the next tile still needs its mask: then the running-max
+  // update is left to the start of the next step.  The O rescale is a rare branch at the end.
   template <int VOFF>
-  __device__ __forceinline__ void phase_b(const Probs& pr, Scores& nxt, int j1, const BiasRegs& br, bool advance) {
-    constexpr int NF = NB * 2 * DVB;
-    constexpr int HALF = NF / 2, PER = 16 / DVB;   // scores of nxt per MFMA in the first half
-    static_assert(NF % 2 == 0 && PER % 2 == 0, "chunking");
-    float mx[RB], alpha[RB];
-    bool any = false;
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      mx[rb] = -INFINITY;
-      alpha[rb] = 1.f;
-    }
+  __device__ __forceinline__ void phase_b(Pipe& ps, const Scores& cur, Scores& nxt, int j1, const BiasRegs& br,
+                                          bool advance) {
+    constexpr int NF = NB * 2 * DVB, HALF = NF / 2;
+    constexpr int SE = HALF * RB, SM = NF * RB - SE, PA = NPAIR / 2;
+    static_assert(NF % 2 == 0, "chunking");
     v_stream<VOFF>([&](auto fc, bf16x8 a) __attribute__((always_inline)) {
       constexpr int f = fc, d = f % DVB, ks = (f / DVB) % 2, nb = f / (2 * DVB);
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
-        oacc[0][rb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pr.hi[rb][nb][ks], oacc[0][rb][d], 0, 0, 0);
-        if constexpr (f < HALF) {
+        const int slot = f * RB + rb;
+        if (slot == SE) finish_pair(ps, NPAIR - 1);
+        const bf16x8 pb = __builtin_bit_cast(bf16x8, (i32x4){(int)ps.w[rb][nb][4 * ks], (int)ps.w[rb][nb][4 * ks + 1],
+                                                             (int)ps.w[rb][nb][4 * ks + 2], (int)ps.w[rb][nb][4 * ks + 3]});
+        oacc[0][rb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[0][rb][d], 0, 0, 0);
+        if (slot < SE) {
 #pragma unroll
-          for (int e = 0; e < PER; e += 2) {
-            const int L = (f * RB + rb) * PER + e, crb = L / (NB * 16), cnb = (L / 16) % NB, r = L % 16;
-            const float x0 = transform_one(nxt[crb][cnb][r], j1, crb, cnb, r, br);
-            const float x1 = transform_one(nxt[crb][cnb][r + 1], j1, crb, cnb, r + 1, br);
-            nxt[crb][cnb][r] = x0;
-            nxt[crb][cnb][r + 1] = x1;
-            mx[crb] = fmaxf(fmaxf(mx[crb], x0), x1);
-          }
-        }
-        if constexpr (f == HALF) {
-          // all scores of the next tile are in: fold their row maxima into the running state
-          float mxs = half_swap_max(mx[rb]);
-          if constexpr (kPlain) mxs *= c_scale;    // scale > 0 (checked on the host)
-          const float m_old = m_run[0][rb];
-          float m_new = (mxs - m_old > kLazyMaxLog2) ? mxs : m_old;   // false for NaN (-inf - -inf)
-          m_new = advance ? m_new : m_old;
-          const bool moved = m_new != m_old;
-          alpha[rb] = moved ? fast_exp2(m_old - (m_new == -INFINITY ? 0.f : m_new)) : 1.f;
-          m_run[0][rb] = m_new;
-          l_run[0][rb] *= alpha[rb];
-          any = any || moved;
+          for (int q = PA + slot * PA / SE; q < PA + (slot + 1) * PA / SE; ++q) exp_step(cur, ps, q, PA);
+        } else {
+          const int sm = slot - SE;                // pairs of scores of the last key block
+#pragma unroll
+          for (int u = sm * (8 * RB) / SM; u < (sm + 1) * (8 * RB) / SM; ++u) max_step(nxt, ps, NB - 1, 2 * u, j1, br);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
     });
+    // the tile's row sums are complete; fold the next tile's row maxima into the running state
+    float alpha[RB];
+    bool any = false;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      l_run[0][rb] += ps.psum[rb];
+      float mxs = half_swap_max(ps.mx[rb]);
+      if constexpr (kPlain) mxs *= c_scale;        // scale > 0 (checked on the host)
+      const float m_old = m_run[0][rb];
+      float m_new = (mxs - m_old > kLazyMaxLog2) ? mxs : m_old;   // false for NaN (-inf - -inf)
+      m_new = advance ? m_new : m_old;
+      const bool moved = m_new != m_old;
+      alpha[rb] = moved ? fast_exp2(m_old - (m_new == -INFINITY ? 0.f : m_new)) : 1.f;
+      m_run[0][rb] = m_new;
+      l_run[0][rb] *= alpha[rb];
+      any = any || moved;
+    }
     if (__builtin_amdgcn_ballot_w64(any) != 0) {   // rare and wave-uniform
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
@@ -800,6 +831,44 @@ fwd_bf16_kernel(const FwdParams p) {
     __syncthreads();
   };
 
+  // Staggered schedule: group 0 (waves 0-3) streams the K tiles in, group 1 (waves 4-7) the V
+  // tiles; a wave's list has LPS instructions of its tensor, instruction u at index
+  // (wave & 3) + 4 u of the tile.
+  constexpr bool STAG = C::STAG;
+  constexpr int LPS = STAG ? C::K_INSTR / 4 : 1;
+  const int grp = STAG ? wave >> 2 : 0;
+  uint32_t s_off[LPS];
+  auto s_instr = [&](int u) __attribute__((always_inline)) { return (wave & 3) + 4 * u; };
+  auto s_lane_off = [&](int u, int nvalid) __attribute__((always_inline)) -> uint32_t {
+    if (grp == 0) {
+      const int row = s_instr(u) * C::K_ROWS_PI + kr_lane;
+      return (uint32_t)(row < nvalid ? row : nvalid - 1) * (uint32_t)kss[0] + (uint32_t)swz_k<D>(row, lane % (D / 8)) * 16u;
+    }
+    const int row = s_instr(u) * C::V_ROWS_PI + vr_lane;
+    return (uint32_t)(row < nvalid ? row : nvalid - 1) * (uint32_t)vss + (uint32_t)swz_v<DV>(row, lane % (DV / 8)) * 16u;
+  };
+  if constexpr (STAG) {
+#pragma unroll
+    for (int u = 0; u < LPS; ++u) s_off[u] = s_lane_off(u, BN);
+  }
+  auto s_clamp = [&](int t) __attribute__((always_inline)) {      // see clamp_k
+    const int nvalid = p.Sk - t * BN;
+    if (nvalid < BN) {
+#pragma unroll
+      for (int u = 0; u < LPS; ++u) s_off[u] = s_lane_off(u, nvalid);
+    }
+  };
+  auto s_tile_base = [&](int t) __attribute__((always_inline)) { return grp == 0 ? k_tile_base(0, t) : v_tile_base(t); };
+  auto s_issue = [&](int u, const unsigned char* tile_base, int lds_off) __attribute__((always_inline)) {
+    lds_void* dst = (lds_void*)(lds_raw + lds_off + s_instr(u) * 1024);
+    __builtin_amdgcn_global_load_lds((global_cvoid*)(tile_base + s_off[u]), dst, 16, 0, 0);
+  };
+  auto s_load = [&](int t, int lds_off) __attribute__((always_inline)) {          // this wave's share of a tile, in a burst
+    s_clamp(t);
+#pragma unroll
+    for (int u = 0; u < LPS; ++u) s_issue(u, s_tile_base(t), lds_off);
+  };
+
   typedef std::integral_constant<int, 0> Buf0;
   typedef std::integral_constant<int, 1> Buf1;
   if constexpr (C::PIPE) {
@@ -807,16 +876,25 @@ fwd_bf16_kernel(const FwdParams p) {
     // Inside the workgroup's tile list every wave processes every tile; a tile that a wave
     // does not need is simply fully masked for it (its probabilities are exactly 0).
     typename W::Scores sa, sb;                     // the two score tiles in flight
-    typename W::Probs pr;
+    typename W::Pipe ps;
     typename W::BiasRegs br;
     int t0 = next_tile(t_lo);
     if (t0 < t_hi) {
       auto after = [&](int t) __attribute__((always_inline)) { return t < t_hi ? next_tile(t + 1) : t_hi; };
       int t1 = after(t0), t2 = after(t1);
       w.load_bias(br, t0 * BN);
-      load_k(t0, 0);
-      load_v(t0, 0);
-      if (t1 < t_hi) load_k(t1, 1);
+      if constexpr (STAG) {
+        if (grp == 0) {
+          s_load(t0, C::K_RING);
+          if (t1 < t_hi) s_load(t1, C::K_RING + C::K_BYTES);
+        } else {
+          s_load(t0, C::V_RING);
+        }
+      } else {
+        load_k(t0, 0);
+        load_v(t0, 0);
+        if (t1 < t_hi) load_k(t1, 1);
+      }
       wait_loads_and_sync();
       w.template qk<C::K_RING>(sa, 0);
       w.transform(sa, t0 * BN, br);
@@ -851,26 +929,54 @@ fwd_bf16_kernel(const FwdParams p) {
         settle(cur);
         if (t1 < t_hi) w.load_bias(br, t1 * BN);   // before the tile loads: its wait then excludes them
         const int tk = t2 < t_hi ? t2 : t_hi - 1, tv = t1 < t_hi ? t1 : t_hi - 1;
-        clamp_k(tk);
-        clamp_v(tv);
-        const unsigned char* kb = k_tile_base(0, tk);
-        const unsigned char* vb = v_tile_base(tv);
-        w.template phase_a<C::K_RING + s_nxt * C::K_BYTES>(nxt, cur, pr, [&](auto fc) __attribute__((always_inline)) {
-          constexpr int f = decltype(fc)::value, NF = NB * KK, LPW = KPW + VPW;
-          static_for<0, KPW>([&](auto u) __attribute__((always_inline)) {
-            if constexpr (f == ((2 * u + 1) * NF) / (2 * LPW)) issue_k(0, u, kb, C::K_RING + s_cur * C::K_BYTES);
+        if (p.prio == 1) __builtin_amdgcn_s_setprio(1);
+        else if (p.prio == 2) __builtin_amdgcn_s_setprio(0);
+        if constexpr (STAG) {
+          const int tl = grp == 0 ? tk : tv;
+          s_clamp(tl);
+          const unsigned char* lb = s_tile_base(tl);
+          const int ls = grp == 0 ? C::K_RING + s_cur * C::K_BYTES : C::V_RING + s_nxt * C::V_BYTES;
+          w.template phase_a<C::K_RING + s_nxt * C::K_BYTES>(nxt, cur, ps, t1 * BN, br, [&](auto fc) __attribute__((always_inline)) {
+            constexpr int f = decltype(fc)::value, NF = NB * KK;
+            static_for<0, LPS>([&](auto u) __attribute__((always_inline)) {
+              if constexpr (f == ((2 * u + 1) * NF) / (2 * LPS)) s_issue(u, lb, ls);
+            });
           });
-          static_for<0, VPW>([&](auto u) __attribute__((always_inline)) {
-            if constexpr (f == ((2 * (KPW + u) + 1) * NF) / (2 * LPW)) issue_v(u, vb, C::V_RING + s_nxt * C::V_BYTES);
+          __builtin_amdgcn_s_barrier();              // half-step boundary: every LDS read of phase A has been consumed
+        } else {
+          clamp_k(tk);
+          clamp_v(tv);
+          const unsigned char* kb = k_tile_base(0, tk);
+          const unsigned char* vb = v_tile_base(tv);
+          w.template phase_a<C::K_RING + s_nxt * C::K_BYTES>(nxt, cur, ps, t1 * BN, br, [&](auto fc) __attribute__((always_inline)) {
+            constexpr int f = decltype(fc)::value, NF = NB * KK, LPW = KPW + VPW;
+            static_for<0, KPW>([&](auto u) __attribute__((always_inline)) {
+              if constexpr (f == ((2 * u + 1) * NF) / (2 * LPW)) issue_k(0, u, kb, C::K_RING + s_cur * C::K_BYTES);
+            });
+            static_for<0, VPW>([&](auto u) __attribute__((always_inline)) {
+              if constexpr (f == ((2 * (KPW + u) + 1) * NF) / (2 * LPW)) issue_v(u, vb, C::V_RING + s_nxt * C::V_BYTES);
+            });
           });
-        });
-        w.template phase_b<C::V_RING + s_cur * C::V_BYTES>(pr, nxt, t1 * BN, br, full1);
+        }
+        if (p.prio == 1) __builtin_amdgcn_s_setprio(0);
+        else if (p.prio == 2) __builtin_amdgcn_s_setprio(1);
+        w.template phase_b<C::V_RING + s_cur * C::V_BYTES>(ps, cur, nxt, t1 * BN, br, full1);
         wait_loads_and_sync();
         t0 = t1;
         t1 = t2;
         t2 = t2 < t_hi ? next_tile(t2 + 1) : t_hi;
         full0 = full1;
       };
+      if (p.prio == 3 && wave >= C::NWAVES / 2) __builtin_amdgcn_s_setprio(1);
+      // Half-step clock of the staggered schedule: group 0 runs phase A of step n in half step 2n
+      // and phase B in 2n + 1, group 1 one half step later.  K(t[n+1]) is then read in half steps
+      // 2n and 2n + 1, V(t[n]) in 2n + 1 and 2n + 2.  Group 0 issues K(t[n+2]) during half step
+      // 2n into the slot K(t[n]) left at 2n - 1 and waits for it at the end of 2n + 1, one
+      // barrier before its first reader; group 1 issues V(t[n+1]) during 2n + 1 into the slot
+      // V(t[n-1]) left at 2n and waits at the end of 2n + 2.  Two slots per ring are enough.
+      if constexpr (STAG) {
+        if (grp == 1) __builtin_amdgcn_s_barrier();
+      }
       while (true) {
         bool done = false;
         static_for<0, 4>([&](auto nc) __attribute__((always_inline)) {
@@ -882,6 +988,9 @@ fwd_bf16_kernel(const FwdParams p) {
           }
         });
         if (done) break;
+      }
+      if constexpr (STAG) {
+        if (grp == 0) __builtin_amdgcn_s_barrier();  // group 1's last half step
       }
     }
   } else {

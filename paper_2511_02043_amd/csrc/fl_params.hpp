@@ -52,6 +52,7 @@ struct FwdParams {
   int32_t n_qtiles;      // ceil(Sq / rows per workgroup)
   int32_t order;         // workgroup ordering scheme
   int32_t doc_vec;       // 1: kv_doc rows are 16-byte aligned and Sk % 4 == 0 -> 4 ids per load
+  int32_t prio;          // wave-priority scheme of the pipelined loop (0 = none)
 };
 
 // Compile-time loop: f(std::integral_constant<int, I>) for I in [B, E).
