@@ -30,7 +30,7 @@ fl_status fail(fl_status st, const char* fmt, ...) {
 }
 
 struct Tuning {
-  int bm = 0, bn = 0, rb = 0, nw = 0, wpe = 0, stag = 0, order = -1, prio = -1;
+  int bm = 0, bn = 0, rb = 0, nw = 0, wpe = 0, stag = 0, order = -1, pair = -1;
 } g_tuning;
 
 int elem_size(int dtype) { return dtype == FL_BF16 ? 2 : 4; }
@@ -215,7 +215,7 @@ fl_status fl_set_tuning(const char* key, int value) {
   else if (!strcmp(key, "wpe")) g_tuning.wpe = value;
   else if (!strcmp(key, "stag")) g_tuning.stag = value;
   else if (!strcmp(key, "order")) g_tuning.order = value == 0 ? -1 : value - 1;
-  else if (!strcmp(key, "prio")) g_tuning.prio = value == 0 ? -1 : value - 1;
+  else if (!strcmp(key, "pair")) g_tuning.pair = value == 0 ? -1 : value - 1;
   else return fail(FL_ERR_UNSUPPORTED, "unknown tuning key '%s'", key);
   return FL_OK;
 }
@@ -377,13 +377,18 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   p.epi = (int)desc->epilogue;
   p.n_qtiles = (int)((Sq + ke->bm - 1) / ke->bm);
   const int64_t nbh = B * G * H;
-  const int64_t nblocks = nbh * p.n_qtiles;
+  // bf16 kernels under a causal / prefix mask without a window: the work of a q-tile grows with
+  // its index, so a workgroup takes a long and a short one -- when that still leaves every CU
+  // several workgroups
+  const bool tri = (mask & (FL_MASK_CAUSAL | FL_MASK_PREFIX)) != 0 && (mask & (FL_MASK_WINDOW | FL_MASK_DOC)) == 0;
+  p.pair = g_tuning.pair >= 0 ? g_tuning.pair : (dtype == FL_BF16 && tri && nbh * ((p.n_qtiles + 1) / 2) >= 1024);
+  if (dtype != FL_BF16) p.pair = 0;
+  const int64_t nblocks = nbh * (p.pair ? (p.n_qtiles + 1) / 2 : p.n_qtiles);
   if (nblocks > 0x7fffffffLL || nbh * Sq > 0x7fffffff00LL) return fail(FL_ERR_SHAPE, "too many workgroups");
   // default: XCD-aware order (whole (b, g, h) problems per XCD) whenever the problem count allows it
   int order = g_tuning.order >= 0 ? g_tuning.order : 1;
   if (order == 1 && nbh % 8 != 0) order = 0;
   p.order = order;
-  p.prio = g_tuning.prio >= 0 ? g_tuning.prio : 0;
   p.doc_vec = (mask & FL_MASK_DOC) && Sk % 4 == 0 && ((uintptr_t)aux->kv_doc_ids) % 16 == 0;
 
   hipStream_t stream = (hipStream_t)stream_v;

@@ -9,7 +9,7 @@ namespace fl {
 static const KernelEntry kEntries[] = {
     // first entry of a head dim = default shape; the others are selectable with fl_set_tuning
     BOTH(128, 8, 1, 64, 2), STAGGERED(128), BOTH(128, 4, 1, 64, 2), BOTH(128, 4, 2, 64, 1), BOTH(128, 4, 2, 32, 1),
-    BOTH(64, 8, 1, 64, 2),  STAGGERED(64),  BOTH(64, 4, 1, 64, 2),  BOTH(64, 4, 2, 64, 2),  BOTH(64, 8, 2, 64, 2),
+    BOTH(64, 4, 1, 64, 2),  BOTH(64, 8, 1, 64, 2),  STAGGERED(64),  BOTH(64, 4, 2, 64, 2),  BOTH(64, 8, 2, 64, 2),
     BOTH(32, 4, 1, 64, 2),  BOTH(32, 4, 2, 64, 2),
 };
 #undef BOTH

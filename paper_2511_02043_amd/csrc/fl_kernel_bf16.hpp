@@ -610,28 +610,40 @@ fwd_bf16_kernel(const FwdParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   W w(p);
-  w.lane = lane;
-  w.half = lane >> 5;
-  w.col = lane & 31;
 
-  // ---- logical grid decode (Sec. 3.6): 1-D launch -> (b, g, h, q-tile)
-  const int nq = p.n_qtiles;
+  // ---- logical grid decode (Sec. 3.6): 1-D launch -> (b, g, h, q-tile or pair of q-tiles).
+  // With p.pair a workgroup takes q-tile nq - 1 - pi and then q-tile pi: under a causal mask the
+  // two together see the same number of key tiles for every pi, so all workgroups carry the same
+  // load and the launch has no tail of long stragglers.  Without it, q-tiles go out longest first.
+  const int nq = p.n_qtiles, npairs = p.pair ? (nq + 1) / 2 : nq;
   int bid = blockIdx.x;
-  int qt, bh;
+  int pi, bh;
   if (p.order == 1) {
     // XCD-aware: consecutive workgroup ids go round-robin to the 8 XCDs; give each XCD whole
     // (b, g, h) problems so that a head's K/V stay in one L2 (host checks (B*G*H) % 8 == 0).
     const int xcd = bid & 7;
     const int idx = bid >> 3;
-    bh = (idx / nq) * 8 + xcd;
-    qt = nq - 1 - (idx % nq);
+    bh = (idx / npairs) * 8 + xcd;
+    pi = idx % npairs;
   } else {
-    qt = nq - 1 - (bid % nq);                      // longest (causal) tiles first
-    bh = bid / nq;
+    pi = bid % npairs;
+    bh = bid / npairs;
   }
+#pragma nounroll
+  for (int pass = 0; pass < 2; ++pass) {
+  const int qt = pass == 0 ? nq - 1 - pi : pi;
+  if (pass == 1 && (!p.pair || qt == nq - 1 - pi)) break;   // odd tile count: the middle tile has no partner
+  if (pass == 1) __syncthreads();                  // LDS is reused by the second tile
+  // Everything per-lane is derived again for each tile from this opaque copy of the lane id:
+  // otherwise the loop-invariant part of it is hoisted out of the tile loop and stays live in
+  // registers that the main loop needs.
+  int lane = tid & 63;
+  asm volatile("" : "+v"(lane));
+  w.lane = lane;
+  w.half = lane >> 5;
+  w.col = lane & 31;
   const int h = bh % p.H;
   const int g = (bh / p.H) % p.G;
   const int b = bh / (p.H * p.G);
@@ -734,6 +746,10 @@ fwd_bf16_kernel(const FwdParams p) {
     }
     return t;                                      // positional masks are already in [t_lo, t_hi)
   };
+  int tf_lo = 0, tf_hi = 0;                        // tiles fully visible to this wave's rows (positional masks)
+  full_tile_range(MASK, iw, iw + C::WROWS - 1, p.Sk, p.window, p.prefix, BN, tf_lo, tf_hi);
+  tf_lo = __builtin_amdgcn_readfirstlane(tf_lo);
+  tf_hi = __builtin_amdgcn_readfirstlane(min(tf_hi, t_hi));
   auto wave_class = [&](int t) __attribute__((always_inline)) -> int {            // uniform over the wave
     if (t >= t_hi) return kTileSkip;
     int2 ks = make_int2(0, 0);
@@ -741,6 +757,11 @@ fwd_bf16_kernel(const FwdParams p) {
     const int c = classify_block(MASK, iw, iw + C::WROWS - 1, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix,
                                  qs_wave, ks);
     return __builtin_amdgcn_readfirstlane(c);
+  };
+
+  auto wave_full = [&](int t) __attribute__((always_inline)) -> bool {            // is tile t fully visible to the wave?
+    if constexpr ((MASK & kMaskDoc) != 0) return wave_class(t) == kTileFull;
+    else return t >= tf_lo && t < tf_hi;
   };
 
   // ---- direct global -> LDS loads of one K or V tile (a2): every wave instruction moves
@@ -899,12 +920,18 @@ fwd_bf16_kernel(const FwdParams p) {
       w.template qk<C::K_RING>(sa, 0);
       w.transform(sa, t0 * BN, br);
       float mx[RB];
-      bool full0 = wave_class(t0) == kTileFull;
+      bool full0 = wave_full(t0);
       if (full0) {
         w.rowmax(sa, mx);
         w.advance_max(0, mx);
       }
       __syncthreads();                             // everyone is done with K ring slot 0
+      // uniform state of the tile stream: the ragged tile (if any) and the bases of the next K and
+      // V tile to fetch, i.e. of tiles min(t2, t_hi - 1) and min(t1, t_hi - 1)
+      const int t_rag = p.Sk % BN != 0 ? p.Sk / BN : -1;
+      const int64_t kstep = (int64_t)BN * kss[0], vstep = (int64_t)BN * vss;
+      const unsigned char* kb = k_tile_base(0, t2 < t_hi ? t2 : t_hi - 1);
+      const unsigned char* vb = v_tile_base(t1 < t_hi ? t1 : t_hi - 1);
       // Start of every step: finish the softmax bookkeeping of the current tile.  Only the
       // (rare) mask branch and the (rare) rescale branch live outside the big basic block.
       auto settle = [&](typename W::Scores& cur) __attribute__((always_inline)) {
@@ -925,16 +952,18 @@ fwd_bf16_kernel(const FwdParams p) {
       auto step = [&](auto nc, typename W::Scores& cur, typename W::Scores& nxt) __attribute__((always_inline)) {
         constexpr int N = decltype(nc)::value;
         constexpr int s_cur = N % 2, s_nxt = (N + 1) % 2;
-        const bool full1 = wave_class(t1) == kTileFull;
+        const bool full1 = wave_full(t1);
         settle(cur);
         if (t1 < t_hi) w.load_bias(br, t1 * BN);   // before the tile loads: its wait then excludes them
         const int tk = t2 < t_hi ? t2 : t_hi - 1, tv = t1 < t_hi ? t1 : t_hi - 1;
-        if (p.prio == 1) __builtin_amdgcn_s_setprio(1);
-        else if (p.prio == 2) __builtin_amdgcn_s_setprio(0);
+        if constexpr ((MASK & kMaskDoc) != 0) {    // tiles may be skipped: no fixed stride between them
+          kb = k_tile_base(0, tk);
+          vb = v_tile_base(tv);
+        }
         if constexpr (STAG) {
           const int tl = grp == 0 ? tk : tv;
-          s_clamp(tl);
-          const unsigned char* lb = s_tile_base(tl);
+          if (__builtin_expect(tl == t_rag, 0)) s_clamp(tl);
+          const unsigned char* lb = grp == 0 ? kb : vb;
           const int ls = grp == 0 ? C::K_RING + s_cur * C::K_BYTES : C::V_RING + s_nxt * C::V_BYTES;
           w.template phase_a<C::K_RING + s_nxt * C::K_BYTES>(nxt, cur, ps, t1 * BN, br, [&](auto fc) __attribute__((always_inline)) {
             constexpr int f = decltype(fc)::value, NF = NB * KK;
@@ -944,10 +973,8 @@ fwd_bf16_kernel(const FwdParams p) {
           });
           __builtin_amdgcn_s_barrier();              // half-step boundary: every LDS read of phase A has been consumed
         } else {
-          clamp_k(tk);
-          clamp_v(tv);
-          const unsigned char* kb = k_tile_base(0, tk);
-          const unsigned char* vb = v_tile_base(tv);
+          if (__builtin_expect(tk == t_rag, 0)) clamp_k(tk);
+          if (__builtin_expect(tv == t_rag, 0)) clamp_v(tv);
           w.template phase_a<C::K_RING + s_nxt * C::K_BYTES>(nxt, cur, ps, t1 * BN, br, [&](auto fc) __attribute__((always_inline)) {
             constexpr int f = decltype(fc)::value, NF = NB * KK, LPW = KPW + VPW;
             static_for<0, KPW>([&](auto u) __attribute__((always_inline)) {
@@ -958,16 +985,17 @@ fwd_bf16_kernel(const FwdParams p) {
             });
           });
         }
-        if (p.prio == 1) __builtin_amdgcn_s_setprio(0);
-        else if (p.prio == 2) __builtin_amdgcn_s_setprio(1);
         w.template phase_b<C::V_RING + s_cur * C::V_BYTES>(ps, cur, nxt, t1 * BN, br, full1);
         wait_loads_and_sync();
         t0 = t1;
         t1 = t2;
         t2 = t2 < t_hi ? next_tile(t2 + 1) : t_hi;
         full0 = full1;
+        if constexpr ((MASK & kMaskDoc) == 0) {    // consecutive tiles: advance the bases until the list ends
+          if (t1 < t_hi) vb += vstep;
+          if (t2 < t_hi) kb += kstep;
+        }
       };
-      if (p.prio == 3 && wave >= C::NWAVES / 2) __builtin_amdgcn_s_setprio(1);
       // Half-step clock of the staggered schedule: group 0 runs phase A of step n in half step 2n
       // and phase B in 2n + 1, group 1 one half step later.  K(t[n+1]) is then read in half steps
       // 2n and 2n + 1, V(t[n]) in 2n + 1 and 2n + 2.  Group 0 issues K(t[n+2]) during half step
@@ -1104,6 +1132,7 @@ fwd_bf16_kernel(const FwdParams p) {
       }
     }
   }
+  }  // pass
 }
 
 }  // namespace fl

@@ -52,7 +52,7 @@ struct FwdParams {
   int32_t n_qtiles;      // ceil(Sq / rows per workgroup)
   int32_t order;         // workgroup ordering scheme
   int32_t doc_vec;       // 1: kv_doc rows are 16-byte aligned and Sk % 4 == 0 -> 4 ids per load
-  int32_t prio;          // wave-priority scheme of the pipelined loop (0 = none)
+  int32_t pair;          // bf16 kernels: 1 = a workgroup takes q-tiles nq - 1 - i and i (balanced causal work)
 };
 
 // Compile-time loop: f(std::integral_constant<int, I>) for I in [B, E).
@@ -120,6 +120,25 @@ __device__ __forceinline__ int classify_block(const uint32_t MASK, int q_lo, int
     full = full && (qs.x == qs.y && ks.x == ks.y && qs.x == ks.x);
   }
   return full ? kFull : kPartial;
+}
+
+// Tiles of BN keys that are fully visible (classify_block == kFull) to the query rows
+// [q_lo, q_hi] under the positional masks form one range [lo, hi); this is that range in closed
+// form (document masks need the per-tile summaries instead).
+__device__ __forceinline__ void full_tile_range(const uint32_t MASK, int q_lo, int q_hi, int Sk, int window,
+                                                int prefix, int BN, int& lo, int& hi) {
+  lo = 0;
+  hi = Sk / BN;                                    // tiles that end inside the key range
+  if ((MASK & kMaskPrefix) != 0) {
+    const int last = q_lo > prefix - 1 ? q_lo : prefix - 1;   // last key every row may see
+    hi = min(hi, (last + 1) / BN);
+  } else if ((MASK & (kMaskCausal | kMaskWindow)) != 0) {
+    hi = min(hi, (q_lo + 1) / BN);
+  }
+  if ((MASK & kMaskWindow) != 0) {
+    const int first = q_hi - window;               // first key every row may see
+    lo = first > 0 ? (first + BN - 1) / BN : 0;
+  }
 }
 
 }  // namespace fl

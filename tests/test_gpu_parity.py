@@ -147,3 +147,24 @@ def test_every_compiled_kernel_shape(D, tune, order):
     finally:
         for k in ("nw", "rb", "bn", "stag", "wpe", "bm", "order"):
             fb.fl_set_tuning(k, 0)
+
+
+@pytest.mark.parametrize("D,nw", [(128, 8), (128, 4), (64, 4), (32, 4)])
+@pytest.mark.parametrize("pair", [1, 2])
+def test_q_tile_pairing(D, nw, pair):
+    """One q-tile per workgroup and a long + a short one per workgroup give the same result, for an
+    even and an odd number of q-tiles, with and without a causal mask."""
+    from paper_2511_02043_amd import binding as fb
+    try:
+        fb.check(fb.fl_set_tuning("nw", nw))
+        fb.check(fb.fl_set_tuning("rb", 1))
+        fb.check(fb.fl_set_tuning("pair", pair))
+        bm = 32 * nw
+        for nq in (1, 2, 5):
+            S = bm * nq - 7
+            run_and_compare(inputs.causal_bf16(B=1, H=8, S=S, D=D), label=f"causal D={D} nw={nw} pair={pair} nq={nq}")
+        run_and_compare(inputs.causal_bf16(B=1, H=8, S=3 * bm, Sk=200, D=D, causal=False),
+                        label=f"plain D={D} nw={nw} pair={pair}")
+    finally:
+        for k in ("nw", "rb", "pair"):
+            fb.fl_set_tuning(k, 0)
