@@ -116,6 +116,57 @@ def time_config(name, steps, warmup, out_dtype="same"):
                 gbs=byt / (ev_ms * 1e-3) / 1e9, dims=w.dims), w
 
 
+def gemm_reference(n=8192, reps=50):
+    """TFLOP/s of torch.matmul on random bf16 data of size n^3: what the matrix cores sustain under the
+    board's power limit with nothing but a contraction to run (context for roofline.frac, not a target)."""
+    import torch
+    a = torch.randn(n, n, device="cuda", dtype=torch.bfloat16)
+    b = torch.randn(n, n, device="cuda", dtype=torch.bfloat16)
+    for _ in range(10):
+        a @ b
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        a @ b
+    e1.record()
+    torch.cuda.synchronize()
+    return 2.0 * n ** 3 * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
+def run_grid(steps, warmup):
+    """The paper's benchmark grid (Sec. 4.1): every cell timed like the default workload."""
+    import torch
+    from paper_2511_02043_amd import inputs, runner
+    rows = []
+    for variant in inputs.GRID_VARIANTS:
+        for gqa in (False, True):
+            for S in inputs.GRID_SEQ_LENS:
+                w = inputs.grid_bf16(variant, S, gqa=gqa)
+                flops, byt = flops_and_bytes(w)
+                dw = runner.upload(w, out_dtype="same")
+                stream = torch.cuda.current_stream().cuda_stream
+                for _ in range(warmup):
+                    dw.run_checked(stream)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(steps):
+                    dw.run_checked(stream)
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1) / steps
+                rows.append(dict(variant=variant, heads="gqa" if gqa else "mha", S=S, B=w.dims["B"], ms=ms,
+                                 tflops=flops / (ms * 1e-3) / 1e12, gbs=byt / (ms * 1e-3) / 1e9))
+                print(f"# {variant:15s} {'gqa' if gqa else 'mha'} S={S:5d} B={w.dims['B']:2d}: {ms:.4f} ms  "
+                      f"{rows[-1]['tflops']:.1f} TFLOP/s  {rows[-1]['gbs']:.0f} GB/s", file=sys.stderr, flush=True)
+                del dw
+    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+    with open(os.path.join(ROOT, "gpurun_out", "bench_grid.json"), "w") as f:
+        json.dump(rows, f, indent=1)
+    print(json.dumps({"grid_cells": len(rows), "file": "gpurun_out/bench_grid.json"}))
+
+
 def cpu_baseline(w, budget_s=15.0):
     """The oracle as it stands, timed on this host on a bounded sample of heads of the workload."""
     from oracle import attention_oracle as ao
@@ -157,11 +208,16 @@ def cpu_baseline(w, budget_s=15.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", default="c2_d128", choices=CONFIGS)
     ap.add_argument("--all", action="store_true", help="time every configuration (results in gpurun_out/bench_all.json)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--grid", action="store_true",
+                    help="time the paper's benchmark grid (7 variants x MHA/GQA x S = 512..16k, 16k tokens, D = 64); "
+                         "table on stderr, gpurun_out/bench_grid.json")
+    ap.add_argument("--no-gemm-reference", action="store_true",
+                    help="skip the bf16 GEMM that shows what the matrix cores sustain on random data")
     ap.add_argument("--tune", default="", help="comma list key=value passed to fl_set_tuning (sweeps)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run a plain device-to-device copy of MIB MiB a few times (scale factor of the "
@@ -187,6 +243,9 @@ def main():
         k, v = kv.split("=")
         fb.check(fb.fl_set_tuning(k, int(v)))
 
+    if args.grid:
+        run_grid(args.steps, args.warmup)
+        return
     results = []
     if args.all:
         for name in CONFIGS:
@@ -220,6 +279,8 @@ def main():
         "roofline": {"bound": "mfma", "achieved": r["kernel_tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": r["kernel_tflops"] / PEAK_BF16_TFLOPS, "traffic": traffic},
     }
+    if not args.no_gemm_reference:
+        line["config"]["gemm_bf16_random_tflops"] = gemm_reference()
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(line), flush=True)

@@ -203,3 +203,47 @@ def evoformer_bf16(B=1, Nseq=128, Nres=384, H=8, D=32, two_biases=False, salt=0,
         biases.append(normal((B, Nseq, 1, 1, Nres), tensor_seed(5, 5, salt), dtype))
     return Workload("evoformer_" + dtype, dtype, q, k, v, scale=D ** -0.5,
                     biases=tuple(biases), gate=gate)
+
+
+# --- the paper's benchmark grid (Sec. 4.1, "Benchmarks") -----------------------------------
+
+GRID_VARIANTS = ("vanilla", "alibi", "softcap", "causal", "sliding_window", "prefix_lm", "document_mask")
+GRID_SEQ_LENS = (512, 1024, 2048, 4096, 8192, 16384)
+
+
+def doc_ids_fixed_count(batch: int, seq: int, n_docs: int, seed: int) -> np.ndarray:
+    """Per-token document ids [batch, seq] (int32) with exactly n_docs documents per batch
+    element: n_docs - 1 distinct cut points drawn uniformly from 1..seq-1, sorted."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = np.empty((batch, seq), dtype=np.int32)
+    for b in range(batch):
+        cuts = np.sort(rng.choice(np.arange(1, seq), size=n_docs - 1, replace=False))
+        out[b] = np.searchsorted(cuts, np.arange(seq), side="right").astype(np.int32)
+    return out
+
+
+def grid_bf16(variant: str, S: int, gqa: bool = False, B: Optional[int] = None, tokens: int = 16384,
+              H: int = 16, D: int = 64, window: int = 256, prefix: int = 256, n_docs: int = 12,
+              cap: float = 30.0, salt: int = 0) -> Workload:
+    """One cell of the paper's grid: sequence length S with batch * S = 16k tokens, head dim 64,
+    16 query heads and 16 (MHA) or 2 (GQA) key/value heads; window and prefix length 256,
+    12 documents (Sec. 4.1).  Config number 6 in the seed recipe."""
+    if variant not in GRID_VARIANTS:
+        raise ValueError(f"unknown grid variant {variant!r}")
+    B = max(1, tokens // S) if B is None else B
+    q, k, v = _qkv(6, B, 1, H, S, S, D, D, "bf16", Hkv=2 if gqa else H, salt=salt + 100 * GRID_VARIANTS.index(variant))
+    w = Workload(f"grid_{variant}_{'gqa' if gqa else 'mha'}_s{S}", "bf16", q, k, v, scale=D ** -0.5)
+    if variant == "alibi":
+        w.alibi = alibi_slopes(H)
+    elif variant == "softcap":
+        w.softcap = cap
+    elif variant == "causal":
+        w.causal = True
+    elif variant == "sliding_window":
+        w.causal, w.window = True, window
+    elif variant == "prefix_lm":
+        w.prefix = min(prefix, S)
+    elif variant == "document_mask":
+        ids = doc_ids_fixed_count(B, S, min(n_docs, S), tensor_seed(6, 3, salt))
+        w.q_doc = w.kv_doc = ids
+    return w
