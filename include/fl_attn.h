@@ -157,7 +157,6 @@ const char* fl_last_error_detail(void);
 /* Tuning knobs for benchmarking sweeps: choose a non-default kernel shape among the compiled
  * ones.  `key` is one of "bm" (query rows per workgroup), "bn" (keys per tile), "nw" (waves per
  * workgroup), "rb" (32-row blocks per wave), "wpe" (waves per SIMD the kernel is built for),
- * "stag" (1 = all waves of a workgroup in step, 2 = the two waves of a SIMD half a step apart),
  * "order" (1 = plain, 2 = XCD-aware workgroup order), "pair" (1 = one q-tile per workgroup,
  * 2 = a long and a short q-tile per workgroup).
  * Value 0 restores the built-in choice.  Returns FL_OK or FL_ERR_UNSUPPORTED.  Not thread-safe

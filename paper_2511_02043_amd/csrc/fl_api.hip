@@ -30,7 +30,7 @@ fl_status fail(fl_status st, const char* fmt, ...) {
 }
 
 struct Tuning {
-  int bm = 0, bn = 0, rb = 0, nw = 0, wpe = 0, stag = 0, order = -1, pair = -1;
+  int bm = 0, bn = 0, rb = 0, nw = 0, wpe = 0, order = -1, pair = -1;
 } g_tuning;
 
 int elem_size(int dtype) { return dtype == FL_BF16 ? 2 : 4; }
@@ -130,7 +130,7 @@ const fl::KernelEntry* find_entry(const fl_variant_desc* d, int dtype, int D, in
       auto wanted = [](const fl::KernelEntry& e) {
         return (g_tuning.bm == 0 || e.bm == g_tuning.bm) && (g_tuning.bn == 0 || e.key.bn == g_tuning.bn) &&
                (g_tuning.rb == 0 || e.key.rb == g_tuning.rb) && (g_tuning.nw == 0 || e.key.nwaves == g_tuning.nw) &&
-               (g_tuning.wpe == 0 || e.key.wpe == g_tuning.wpe) && (g_tuning.stag == 0 || e.key.stag + 1 == g_tuning.stag);
+               (g_tuning.wpe == 0 || e.key.wpe == g_tuning.wpe);
       };
       if (best == nullptr || (wanted(k) && !wanted(*best))) best = &k;
     }
@@ -213,7 +213,6 @@ fl_status fl_set_tuning(const char* key, int value) {
   else if (!strcmp(key, "rb")) g_tuning.rb = value;
   else if (!strcmp(key, "nw")) g_tuning.nw = value;
   else if (!strcmp(key, "wpe")) g_tuning.wpe = value;
-  else if (!strcmp(key, "stag")) g_tuning.stag = value;
   else if (!strcmp(key, "order")) g_tuning.order = value == 0 ? -1 : value - 1;
   else if (!strcmp(key, "pair")) g_tuning.pair = value == 0 ? -1 : value - 1;
   else return fail(FL_ERR_UNSUPPORTED, "unknown tuning key '%s'", key);

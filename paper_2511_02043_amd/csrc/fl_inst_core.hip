@@ -4,17 +4,13 @@
 namespace fl {
 #define E(D, NW, RB, BN, WPE, MASK) bf16_entry<D, D, NW, RB, BN, WPE, kModNone, MASK, 0, false, 0>()
 #define BOTH(D, NW, RB, BN, WPE) E(D, NW, RB, BN, WPE, 0), E(D, NW, RB, BN, WPE, kMaskCausal)
-#define ES(D, MASK) bf16_entry<D, D, 8, 1, 64, 2, kModNone, MASK, 0, false, 0, true>()
-#define STAGGERED(D) ES(D, 0), ES(D, kMaskCausal)
 static const KernelEntry kEntries[] = {
     // first entry of a head dim = default shape; the others are selectable with fl_set_tuning
-    BOTH(128, 8, 1, 64, 2), STAGGERED(128), BOTH(128, 4, 1, 64, 2), BOTH(128, 4, 2, 64, 1), BOTH(128, 4, 2, 32, 1),
-    BOTH(64, 4, 1, 64, 2),  BOTH(64, 8, 1, 64, 2),  STAGGERED(64),  BOTH(64, 4, 2, 64, 2),  BOTH(64, 8, 2, 64, 2),
+    BOTH(128, 8, 1, 64, 2), BOTH(128, 4, 1, 64, 2), BOTH(128, 4, 2, 32, 1),
+    BOTH(64, 4, 1, 64, 2),  BOTH(64, 8, 1, 64, 2),
     BOTH(32, 4, 1, 64, 2),  BOTH(32, 4, 2, 64, 2),
 };
 #undef BOTH
-#undef STAGGERED
-#undef ES
 #undef E
 const KernelEntry* entries_core(int* n) {
   *n = (int)(sizeof(kEntries) / sizeof(kEntries[0]));

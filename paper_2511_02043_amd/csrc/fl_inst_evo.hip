@@ -8,7 +8,7 @@ namespace fl {
 static const KernelEntry kEntries[] = {
     E(32, 1, kEpiGate, 32, 4), E(32, 2, kEpiGate, 32, 4), E(32, 1, 0, 32, 4), E(32, 2, 0, 32, 4),
     E(32, 1, kEpiGate, 64, 2),
-    E(64, 1, kEpiGate, 64, 2), E(64, 2, kEpiGate, 64, 2), E(128, 1, kEpiGate, 64, 2), E(128, 2, kEpiGate, 64, 2),
+    E(64, 1, kEpiGate, 64, 2), E(64, 2, kEpiGate, 64, 2), E(128, 1, kEpiGate, 32, 2), E(128, 2, kEpiGate, 32, 2),
 };
 #undef E
 const KernelEntry* entries_evo(int* n) {

@@ -2,7 +2,8 @@
 // PrefixLM, document mask; Sec. 4.1 benchmark variants), bf16.
 #include "fl_registry.hpp"
 namespace fl {
-#define E(D, MOD, MASK) bf16_entry<D, D, 4, 1, 64, 2, MOD, MASK, 0, false, 0>()
+// Document masks at D = 128 keep 32-key tiles: their id registers do not fit beside two 64-key score tiles.
+#define E(D, MOD, MASK) bf16_entry<D, D, 4, 1, (D == 128 && ((MASK) & kMaskDoc) != 0) ? 32 : 64, 2, MOD, MASK, 0, false, 0>()
 constexpr uint32_t CW = kMaskCausal | kMaskWindow;
 static const KernelEntry kEntries[] = {
     E(64, kModAlibi, 0),   E(64, kModAlibi, kMaskCausal),   E(64, kModSoftcap, 0), E(64, kModSoftcap, kMaskCausal),

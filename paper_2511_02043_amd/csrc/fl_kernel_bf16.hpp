@@ -27,15 +27,21 @@
 // the matrix cores busy at D = 128 (measured: with RB = 1 the LDS reads alone took 60% of the
 // kernel time).
 //
-// Software pipeline (single-stream variants).  Iteration n owns tile t0 (scores already in
-// registers, transformed, masked, row max folded into m) and its successor t1:
-//     phase A:  S1 = K(t1) Q^T on the matrix core   ||   P0 = exp2(S0 - m), l += sum P0 on the VALU
-//     phase B:  O += V(t0)^T P0 on the matrix core  ||   transform / mask / row max of S1, m update
+// Software pipeline (single-stream variants).  Iteration n owns tile t0 (scores in registers,
+// transformed, row max folded into m) and its successor t1:
+//     phase A:  S1 = K(t1) Q^T on the matrix core   ||   P0 = exp2(S0 - m), first half, then the
+//               transform / row max of the first key block of S1
+//     phase B:  O += V(t0)^T P0 on the matrix core  ||   P0, second half (needed by the second
+//               half of the MFMAs), then transform / row max of the rest of S1 and the m update
 // so the matrix core and the vector ALU of one wave have independent work at the same time, and
-// the two waves that share a SIMD fill each other's gaps.  The running max is only advanced when
-// a row's new maximum exceeds the old one by more than 2^8 (the exponent of P stays bounded by
-// 8), which makes the O rescale a rare, wave-uniform branch; l and the final normalisation use
-// the same reference, so the result is unchanged in real arithmetic.
+// the two waves that share a SIMD fill each other's gaps.  What was measured on gfx950 and shaped
+// this loop: a SIMD issues one instruction per 4 clocks whatever its kind (exp2 and the 32x32x16
+// MFMA take two such slots), so the loop is built from as few instructions as possible -- one
+// LDS wait per fragment group, no idle-cycle padding, tile bookkeeping in a handful of scalar
+// instructions.  The running max is only advanced when a row's new maximum exceeds the old one by
+// more than 2^8 (the exponent of P stays bounded by 8), which makes the O rescale a rare,
+// wave-uniform branch; l and the final normalisation use the same reference, so the result is
+// unchanged in real arithmetic.
 #pragma once
 #include <type_traits>
 
@@ -92,7 +98,7 @@ __device__ __forceinline__ int swz_v(int r, int c) {
 }
 
 template <int D_, int DV_, int NWAVES_, int RB_, int BN_, int WPE_, int MOD_, uint32_t MASK_, int NBIAS_,
-          bool DIFF_, uint32_t EPI_, bool STAG_ = false>
+          bool DIFF_, uint32_t EPI_>
 struct Bf16Cfg {
   static constexpr int D = D_, DV = DV_, NWAVES = NWAVES_, RB = RB_, BN = BN_, MOD = MOD_, NBIAS = NBIAS_;
   static constexpr uint32_t MASK = MASK_, EPI = EPI_;
@@ -118,13 +124,6 @@ struct Bf16Cfg {
   static constexpr int K_RING = 0;                 // LDS layout: K ring [RING][NS][K_BYTES], V ring [RING][V_BYTES]
   static constexpr int V_RING = RING * NS * K_BYTES;
   static constexpr int LDS_BYTES = V_RING + RING * V_BYTES;
-  // Staggered schedule: the two waves of a SIMD (waves w and w + 4 of the workgroup) run half a
-  // pipeline step apart, so that the exponential-heavy phase A of one meets the matrix-heavy
-  // phase B of the other instead of both queueing for the vector ALU first and the matrix core
-  // afterwards.
-  static constexpr bool STAG = STAG_;
-  static_assert(!STAG_ || (!DIFF_ && NWAVES_ == 8 && D_ == DV_ && (BN_ * D_ * 2 / 1024) % 4 == 0),
-                "staggered schedule: pipelined 8-wave kernels with equal head dims");
   static constexpr int K_INSTR = K_BYTES / 1024;   // 64-lane x 16-byte direct loads per K tile
   static constexpr int V_INSTR = V_BYTES / 1024;
   static constexpr int K_ROWS_PI = 64 / (D / 8);   // tile rows covered by one direct-load instruction
@@ -533,7 +532,8 @@ struct Wave {
         } else {
           const int sm = slot - SE;                // pairs of scores of key block 0, all row blocks
 #pragma unroll
-          for (int u = sm * (8 * RB) / SM; u < (sm + 1) * (8 * RB) / SM; ++u) max_step(nxt, ps, 0, 2 * u, j1, br);
+          for (int u = sm * (8 * RB) / (SM > 0 ? SM : 1); u < (sm + 1) * (8 * RB) / (SM > 0 ? SM : 1); ++u)
+            max_step(nxt, ps, 0, 2 * u, j1, br);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -852,44 +852,6 @@ fwd_bf16_kernel(const FwdParams p) {
     __syncthreads();
   };
 
-  // Staggered schedule: group 0 (waves 0-3) streams the K tiles in, group 1 (waves 4-7) the V
-  // tiles; a wave's list has LPS instructions of its tensor, instruction u at index
-  // (wave & 3) + 4 u of the tile.
-  constexpr bool STAG = C::STAG;
-  constexpr int LPS = STAG ? C::K_INSTR / 4 : 1;
-  const int grp = STAG ? wave >> 2 : 0;
-  uint32_t s_off[LPS];
-  auto s_instr = [&](int u) __attribute__((always_inline)) { return (wave & 3) + 4 * u; };
-  auto s_lane_off = [&](int u, int nvalid) __attribute__((always_inline)) -> uint32_t {
-    if (grp == 0) {
-      const int row = s_instr(u) * C::K_ROWS_PI + kr_lane;
-      return (uint32_t)(row < nvalid ? row : nvalid - 1) * (uint32_t)kss[0] + (uint32_t)swz_k<D>(row, lane % (D / 8)) * 16u;
-    }
-    const int row = s_instr(u) * C::V_ROWS_PI + vr_lane;
-    return (uint32_t)(row < nvalid ? row : nvalid - 1) * (uint32_t)vss + (uint32_t)swz_v<DV>(row, lane % (DV / 8)) * 16u;
-  };
-  if constexpr (STAG) {
-#pragma unroll
-    for (int u = 0; u < LPS; ++u) s_off[u] = s_lane_off(u, BN);
-  }
-  auto s_clamp = [&](int t) __attribute__((always_inline)) {      // see clamp_k
-    const int nvalid = p.Sk - t * BN;
-    if (nvalid < BN) {
-#pragma unroll
-      for (int u = 0; u < LPS; ++u) s_off[u] = s_lane_off(u, nvalid);
-    }
-  };
-  auto s_tile_base = [&](int t) __attribute__((always_inline)) { return grp == 0 ? k_tile_base(0, t) : v_tile_base(t); };
-  auto s_issue = [&](int u, const unsigned char* tile_base, int lds_off) __attribute__((always_inline)) {
-    lds_void* dst = (lds_void*)(lds_raw + lds_off + s_instr(u) * 1024);
-    __builtin_amdgcn_global_load_lds((global_cvoid*)(tile_base + s_off[u]), dst, 16, 0, 0);
-  };
-  auto s_load = [&](int t, int lds_off) __attribute__((always_inline)) {          // this wave's share of a tile, in a burst
-    s_clamp(t);
-#pragma unroll
-    for (int u = 0; u < LPS; ++u) s_issue(u, s_tile_base(t), lds_off);
-  };
-
   typedef std::integral_constant<int, 0> Buf0;
   typedef std::integral_constant<int, 1> Buf1;
   if constexpr (C::PIPE) {
@@ -904,18 +866,9 @@ fwd_bf16_kernel(const FwdParams p) {
       auto after = [&](int t) __attribute__((always_inline)) { return t < t_hi ? next_tile(t + 1) : t_hi; };
       int t1 = after(t0), t2 = after(t1);
       w.load_bias(br, t0 * BN);
-      if constexpr (STAG) {
-        if (grp == 0) {
-          s_load(t0, C::K_RING);
-          if (t1 < t_hi) s_load(t1, C::K_RING + C::K_BYTES);
-        } else {
-          s_load(t0, C::V_RING);
-        }
-      } else {
-        load_k(t0, 0);
-        load_v(t0, 0);
-        if (t1 < t_hi) load_k(t1, 1);
-      }
+      load_k(t0, 0);
+      load_v(t0, 0);
+      if (t1 < t_hi) load_k(t1, 1);
       wait_loads_and_sync();
       w.template qk<C::K_RING>(sa, 0);
       w.transform(sa, t0 * BN, br);
@@ -960,31 +913,17 @@ fwd_bf16_kernel(const FwdParams p) {
           kb = k_tile_base(0, tk);
           vb = v_tile_base(tv);
         }
-        if constexpr (STAG) {
-          const int tl = grp == 0 ? tk : tv;
-          if (__builtin_expect(tl == t_rag, 0)) s_clamp(tl);
-          const unsigned char* lb = grp == 0 ? kb : vb;
-          const int ls = grp == 0 ? C::K_RING + s_cur * C::K_BYTES : C::V_RING + s_nxt * C::V_BYTES;
-          w.template phase_a<C::K_RING + s_nxt * C::K_BYTES>(nxt, cur, ps, t1 * BN, br, [&](auto fc) __attribute__((always_inline)) {
-            constexpr int f = decltype(fc)::value, NF = NB * KK;
-            static_for<0, LPS>([&](auto u) __attribute__((always_inline)) {
-              if constexpr (f == ((2 * u + 1) * NF) / (2 * LPS)) s_issue(u, lb, ls);
-            });
+        if (__builtin_expect(tk == t_rag, 0)) clamp_k(tk);
+        if (__builtin_expect(tv == t_rag, 0)) clamp_v(tv);
+        w.template phase_a<C::K_RING + s_nxt * C::K_BYTES>(nxt, cur, ps, t1 * BN, br, [&](auto fc) __attribute__((always_inline)) {
+          constexpr int f = decltype(fc)::value, NF = NB * KK, LPW = KPW + VPW;
+          static_for<0, KPW>([&](auto u) __attribute__((always_inline)) {
+            if constexpr (f == ((2 * u + 1) * NF) / (2 * LPW)) issue_k(0, u, kb, C::K_RING + s_cur * C::K_BYTES);
           });
-          __builtin_amdgcn_s_barrier();              // half-step boundary: every LDS read of phase A has been consumed
-        } else {
-          if (__builtin_expect(tk == t_rag, 0)) clamp_k(tk);
-          if (__builtin_expect(tv == t_rag, 0)) clamp_v(tv);
-          w.template phase_a<C::K_RING + s_nxt * C::K_BYTES>(nxt, cur, ps, t1 * BN, br, [&](auto fc) __attribute__((always_inline)) {
-            constexpr int f = decltype(fc)::value, NF = NB * KK, LPW = KPW + VPW;
-            static_for<0, KPW>([&](auto u) __attribute__((always_inline)) {
-              if constexpr (f == ((2 * u + 1) * NF) / (2 * LPW)) issue_k(0, u, kb, C::K_RING + s_cur * C::K_BYTES);
-            });
-            static_for<0, VPW>([&](auto u) __attribute__((always_inline)) {
-              if constexpr (f == ((2 * (KPW + u) + 1) * NF) / (2 * LPW)) issue_v(u, vb, C::V_RING + s_nxt * C::V_BYTES);
-            });
+          static_for<0, VPW>([&](auto u) __attribute__((always_inline)) {
+            if constexpr (f == ((2 * (KPW + u) + 1) * NF) / (2 * LPW)) issue_v(u, vb, C::V_RING + s_nxt * C::V_BYTES);
           });
-        }
+        });
         w.template phase_b<C::V_RING + s_cur * C::V_BYTES>(ps, cur, nxt, t1 * BN, br, full1);
         wait_loads_and_sync();
         t0 = t1;
@@ -996,15 +935,6 @@ fwd_bf16_kernel(const FwdParams p) {
           if (t2 < t_hi) kb += kstep;
         }
       };
-      // Half-step clock of the staggered schedule: group 0 runs phase A of step n in half step 2n
-      // and phase B in 2n + 1, group 1 one half step later.  K(t[n+1]) is then read in half steps
-      // 2n and 2n + 1, V(t[n]) in 2n + 1 and 2n + 2.  Group 0 issues K(t[n+2]) during half step
-      // 2n into the slot K(t[n]) left at 2n - 1 and waits for it at the end of 2n + 1, one
-      // barrier before its first reader; group 1 issues V(t[n+1]) during 2n + 1 into the slot
-      // V(t[n-1]) left at 2n and waits at the end of 2n + 2.  Two slots per ring are enough.
-      if constexpr (STAG) {
-        if (grp == 1) __builtin_amdgcn_s_barrier();
-      }
       while (true) {
         bool done = false;
         static_for<0, 4>([&](auto nc) __attribute__((always_inline)) {
@@ -1016,9 +946,6 @@ fwd_bf16_kernel(const FwdParams p) {
           }
         });
         if (done) break;
-      }
-      if constexpr (STAG) {
-        if (grp == 0) __builtin_amdgcn_s_barrier();  // group 1's last half step
       }
     }
   } else {

@@ -14,7 +14,7 @@ struct KernelKey {
   int nbias;        // -1 in f32 entries
   int diff;
   int epi;          // -1 in f32 entries
-  int nwaves, rb, bn, wpe, stag;   // kernel shape: waves, 32-row blocks per wave, keys per tile, waves per SIMD, staggered schedule
+  int nwaves, rb, bn, wpe;         // kernel shape: waves, 32-row blocks per wave, keys per tile, waves per SIMD
 };
 
 typedef hipError_t (*LaunchFn)(const FwdParams& p, int nblocks, hipStream_t stream);
@@ -46,10 +46,10 @@ hipError_t launch_bf16(const FwdParams& p, int nblocks, hipStream_t stream) {
 }
 
 template <int D, int DV, int NWAVES, int RB, int BN, int WPE, int MOD, uint32_t MASK, int NBIAS, bool DIFF,
-          uint32_t EPI, bool STAG = false>
+          uint32_t EPI>
 constexpr KernelEntry bf16_entry() {
-  typedef Bf16Cfg<D, DV, NWAVES, RB, BN, WPE, MOD, MASK, NBIAS, DIFF, EPI, STAG> C;
-  return KernelEntry{KernelKey{1, D, DV, MOD, (int)MASK, NBIAS, DIFF ? 1 : 0, (int)EPI, NWAVES, RB, BN, WPE, STAG ? 1 : 0}, C::BM,
+  typedef Bf16Cfg<D, DV, NWAVES, RB, BN, WPE, MOD, MASK, NBIAS, DIFF, EPI> C;
+  return KernelEntry{KernelKey{1, D, DV, MOD, (int)MASK, NBIAS, DIFF ? 1 : 0, (int)EPI, NWAVES, RB, BN, WPE}, C::BM,
                      C::LDS_BYTES, &launch_bf16<C>};
 }
 

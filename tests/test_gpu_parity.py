@@ -128,9 +128,8 @@ def test_deterministic_run_to_run():
 
 
 @pytest.mark.parametrize("D,tune", [
-    (128, dict(nw=8, rb=1, bn=64, stag=1)), (128, dict(nw=8, rb=1, bn=64, stag=2)), (128, dict(nw=4, rb=1, bn=64)),
-    (128, dict(nw=4, rb=2, bn=64)), (128, dict(nw=4, rb=2, bn=32)),
-    (64, dict(nw=8, rb=1, stag=1)), (64, dict(nw=8, rb=1, stag=2)), (64, dict(nw=4, rb=1)), (64, dict(nw=4, rb=2)), (64, dict(nw=8, rb=2)),
+    (128, dict(nw=8, rb=1, bn=64)), (128, dict(nw=4, rb=1, bn=64)), (128, dict(nw=4, rb=2, bn=32)),
+    (64, dict(nw=8, rb=1)), (64, dict(nw=4, rb=1)),
     (32, dict(nw=4, rb=1)), (32, dict(nw=4, rb=2)),
 ])
 @pytest.mark.parametrize("order", [1, 2])
@@ -145,7 +144,7 @@ def test_every_compiled_kernel_shape(D, tune, order):
         run_and_compare(inputs.causal_bf16(B=1, H=8, S=300, Sk=650, D=D, causal=False),
                         label=f"plain D={D} {tune} order={order}")
     finally:
-        for k in ("nw", "rb", "bn", "stag", "wpe", "bm", "order"):
+        for k in ("nw", "rb", "bn", "wpe", "bm", "order"):
             fb.fl_set_tuning(k, 0)
 
 
