@@ -27,7 +27,7 @@
 // the matrix cores busy at D = 128 (measured: with RB = 1 the LDS reads alone took 60% of the
 // kernel time).
 //
-// Software pipeline (single-stream variants).  Iteration n owns tile t0 (scores in registers,
+// Software pipeline.  Iteration n owns tile t0 (scores in registers,
 // transformed, row max folded into m) and its successor t1:
 //     phase A:  S1 = K(t1) Q^T on the matrix core   ||   P0 = exp2(S0 - m), first half, then the
 //               transform / row max of the first key block of S1
@@ -107,7 +107,6 @@ struct Bf16Cfg {
   // amplifies the bf16 rounding of the probabilities; there P is split into a bf16 high part
   // and a bf16 remainder and the second contraction runs on both.
   static constexpr bool PSPLIT = DIFF_ && (EPI_ & kEpiRms) != 0;
-  static constexpr bool PIPE = !DIFF_;             // two score tiles in flight (see header)
   static constexpr int WPE = WPE_;                 // waves per SIMD the register budget is set for
   static constexpr int GK = 2;                     // K fragments per LDS wait (read one group ahead)
   static constexpr int GV = 2;                     // V^T fragments (two reads each) per LDS wait
@@ -139,11 +138,6 @@ struct Wave {
   static constexpr int D = C::D, DV = C::DV, NB = C::NB, KK = C::KK, DVB = C::DVB, NS = C::NS, RB = C::RB;
   static constexpr bool kPlain = (C::MOD == kModNone && C::NBIAS == 0);
   typedef f32x16 Scores[C::RB][C::NB];
-  struct Probs {
-    bf16x8 hi[C::RB][C::NB][2];
-    bf16x8 lo[C::PSPLIT ? C::NB : 1][2];           // PSPLIT implies RB == 1
-  };
-
   // Raw bias values of one tile for this lane: for bias n, row block rb, key block nb and
   // register group r4, the four bf16 values of keys jb + 8*r4 .. +3 (loaded ahead of their use).
   struct BiasRegs {
@@ -261,7 +255,7 @@ struct Wave {
   }
 
   // ---- variant transform (Eq. 4 score_mod, additive biases) of one score register.
-  // Leaves the score in the domain exp_sum() expects: raw for the plain variants (the scale is
+  // Leaves the score in the domain exp_only() expects: raw for the plain variants (the scale is
   // folded into the exponent's FMA), log2-scaled otherwise.  j0 is the tile's first key.
   __device__ __forceinline__ float transform_one(float x, int j0, int rb, int nb, int r, const BiasRegs& br) const {
     if constexpr (kPlain) {
@@ -415,47 +409,7 @@ struct Wave {
     if constexpr (C::PSPLIT) wl = pack_bf16(p0 - __uint_as_float(w << 16), p1 - __uint_as_float(w & 0xFFFF0000u));
   }
 
-  // ---- P = exp2(S - m) rounded to bf16 operand fragments; l += row sum of the unrounded P
-  __device__ __forceinline__ void exp_sum(const Scores& sc, int s, Probs& pr) {
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      const float m_safe = m_run[s][rb] == -INFINITY ? 0.f : m_run[s][rb];
-      float psum = 0.f;
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        uint32_t w[8], wl[8];
-#pragma unroll
-        for (int r = 0; r < 16; r += 2) {
-          float p0, p1;
-          exp_only(sc[rb][nb][r], sc[rb][nb][r + 1], m_safe, p0, p1);
-          sum_pack(p0, p1, psum, w[r >> 1], wl[r >> 1]);
-        }
-        pr.hi[rb][nb][0] = __builtin_bit_cast(bf16x8, (i32x4){(int)w[0], (int)w[1], (int)w[2], (int)w[3]});
-        pr.hi[rb][nb][1] = __builtin_bit_cast(bf16x8, (i32x4){(int)w[4], (int)w[5], (int)w[6], (int)w[7]});
-        if constexpr (C::PSPLIT) {
-          pr.lo[nb][0] = __builtin_bit_cast(bf16x8, (i32x4){(int)wl[0], (int)wl[1], (int)wl[2], (int)wl[3]});
-          pr.lo[nb][1] = __builtin_bit_cast(bf16x8, (i32x4){(int)wl[4], (int)wl[5], (int)wl[6], (int)wl[7]});
-        }
-      }
-      l_run[s][rb] += psum;
-    }
-  }
-
-  // ---- second contraction of stream s: O^T += V^T P^T, V tile at LDS byte offset VOFF
-  template <int VOFF>
-  __device__ __forceinline__ void pv(const Probs& pr, int s) {
-    v_stream<VOFF>([&](auto fc, bf16x8 a) __attribute__((always_inline)) {
-      constexpr int f = fc, d = f % DVB, ks = (f / DVB) % 2, nb = f / (2 * DVB);
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb) {
-        oacc[s][rb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pr.hi[rb][nb][ks], oacc[s][rb][d], 0, 0, 0);
-        if constexpr (C::PSPLIT)
-          oacc[s][rb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pr.lo[nb][ks], oacc[s][rb][d], 0, 0, 0);
-      }
-    });
-  }
-
-  // ---- software pipeline of the single-stream variants.  A wave issues at most one vector or
+  // ---- software pipeline.  A wave issues at most one vector or
   // matrix instruction every few cycles, so what bounds a step is the number of instructions of
   // each phase; the softmax work of a tile is therefore cut in two halves of equal length:
   //   phase A:  QK MFMAs of the next tile  +  exponentials of the first half of the current tile
@@ -470,6 +424,7 @@ struct Wave {
   // conversion from being sunk out of the loop body.
   struct Pipe {
     uint32_t w[C::RB][C::NB][8];   // bf16 pairs of the current tile's probabilities
+    uint32_t wl[C::PSPLIT ? C::NB : 1][8];   // their bf16 remainders (PSPLIT implies RB == 1)
     float e0, e1;                  // the pair of exponentials whose sum / conversion is still due
     float psum[C::RB], m_safe[C::RB];
     float mx[C::RB];               // row maxima of the next tile so far
@@ -488,9 +443,14 @@ struct Wave {
   }
   __device__ __forceinline__ void finish_pair(Pipe& ps, int q) {
     const int h = q / (4 * RB), rb = (q / 4) % RB, nb = h / 2, r2 = (h % 2) * 4 + q % 4;
-    uint32_t unused = 0;
-    sum_pack(ps.e0, ps.e1, ps.psum[rb], ps.w[rb][nb][r2], unused);
-    asm volatile("" : "+v"(ps.w[rb][nb][r2]), "+v"(ps.psum[rb]));
+    if constexpr (C::PSPLIT) {
+      sum_pack(ps.e0, ps.e1, ps.psum[rb], ps.w[rb][nb][r2], ps.wl[nb][r2]);
+      asm volatile("" : "+v"(ps.w[rb][nb][r2]), "+v"(ps.wl[nb][r2]), "+v"(ps.psum[rb]));
+    } else {
+      uint32_t unused = 0;
+      sum_pack(ps.e0, ps.e1, ps.psum[rb], ps.w[rb][nb][r2], unused);
+      asm volatile("" : "+v"(ps.w[rb][nb][r2]), "+v"(ps.psum[rb]));
+    }
   }
   // two scores of key block nb of the next tile: variant transform in place, row max
   __device__ __forceinline__ void max_step(Scores& nxt, Pipe& ps, int nb, int L, int j1, const BiasRegs& br) {
@@ -503,17 +463,17 @@ struct Wave {
   }
 
   // hook(f) runs after the work of fragment f: the caller's tile loads.
-  template <int KOFF, class Hook>
+  // SC / SN: softmax stream of the current / next score tile (both 0 unless differential).
+  template <int KOFF, int SC, int SN, class Hook>
   __device__ __forceinline__ void phase_a(Scores& nxt, const Scores& cur, Pipe& ps, int j1, const BiasRegs& br,
                                           Hook&& hook) {
-    static_assert(!C::PSPLIT && NS == 1, "pipelined path is single-stream");
     constexpr int NF = NB * KK;
     constexpr int SE = (NB == 2 ? KK : NF) * RB;   // slots (fragment, row block) that carry exponentials
     constexpr int PA = NPAIR / 2;                  // pairs of the first half
     constexpr int SM = NF * RB - SE;               // slots that carry the max of key block 0 (NB == 2)
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      ps.m_safe[rb] = m_run[0][rb] == -INFINITY ? 0.f : m_run[0][rb];
+      ps.m_safe[rb] = m_run[SC][rb] == -INFINITY ? 0.f : m_run[SC][rb];
       ps.psum[rb] = 0.f;
       ps.mx[rb] = -INFINITY;
     }
@@ -523,7 +483,7 @@ struct Wave {
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
         if (kk == 0) acc[rb] = zero16();
-        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][rb][kk], acc[rb], 0, 0, 0);
+        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[SN][rb][kk], acc[rb], 0, 0, 0);
         if (kk == KK - 1) nxt[rb][nb] = acc[rb];
         const int slot = f * RB + rb;
         if (slot < SE) {
@@ -547,7 +507,7 @@ struct Wave {
 
   // `advance` (uniform) is false when the next tile still needs its mask: then the running-max
   // update is left to the start of the next step.  The O rescale is a rare branch at the end.
-  template <int VOFF>
+  template <int VOFF, int SC, int SN>
   __device__ __forceinline__ void phase_b(Pipe& ps, const Scores& cur, Scores& nxt, int j1, const BiasRegs& br,
                                           bool advance) {
     constexpr int NF = NB * 2 * DVB, HALF = NF / 2;
@@ -561,7 +521,12 @@ struct Wave {
         if (slot == SE) finish_pair(ps, NPAIR - 1);
         const bf16x8 pb = __builtin_bit_cast(bf16x8, (i32x4){(int)ps.w[rb][nb][4 * ks], (int)ps.w[rb][nb][4 * ks + 1],
                                                              (int)ps.w[rb][nb][4 * ks + 2], (int)ps.w[rb][nb][4 * ks + 3]});
-        oacc[0][rb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[0][rb][d], 0, 0, 0);
+        oacc[SC][rb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[SC][rb][d], 0, 0, 0);
+        if constexpr (C::PSPLIT) {
+          const bf16x8 pl = __builtin_bit_cast(bf16x8, (i32x4){(int)ps.wl[nb][4 * ks], (int)ps.wl[nb][4 * ks + 1],
+                                                               (int)ps.wl[nb][4 * ks + 2], (int)ps.wl[nb][4 * ks + 3]});
+          oacc[SC][rb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pl, oacc[SC][rb][d], 0, 0, 0);
+        }
         if (slot < SE) {
 #pragma unroll
           for (int q = PA + slot * PA / SE; q < PA + (slot + 1) * PA / SE; ++q) exp_step(cur, ps, q, PA);
@@ -578,16 +543,16 @@ struct Wave {
     bool any = false;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      l_run[0][rb] += ps.psum[rb];
+      l_run[SC][rb] += ps.psum[rb];
       float mxs = half_swap_max(ps.mx[rb]);
       if constexpr (kPlain) mxs *= c_scale;        // scale > 0 (checked on the host)
-      const float m_old = m_run[0][rb];
+      const float m_old = m_run[SN][rb];
       float m_new = (mxs - m_old > kLazyMaxLog2) ? mxs : m_old;   // false for NaN (-inf - -inf)
       m_new = advance ? m_new : m_old;
       const bool moved = m_new != m_old;
       alpha[rb] = moved ? fast_exp2(m_old - (m_new == -INFINITY ? 0.f : m_new)) : 1.f;
-      m_run[0][rb] = m_new;
-      l_run[0][rb] *= alpha[rb];
+      m_run[SN][rb] = m_new;
+      l_run[SN][rb] *= alpha[rb];
       any = any || moved;
     }
     if (__builtin_amdgcn_ballot_w64(any) != 0) {   // rare and wave-uniform
@@ -596,7 +561,7 @@ struct Wave {
 #pragma unroll
         for (int d = 0; d < DVB; ++d)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[0][rb][d][r] *= alpha[rb];
+          for (int r = 0; r < 16; ++r) oacc[SN][rb][d][r] *= alpha[rb];
     }
   }
 };
@@ -852,12 +817,12 @@ fwd_bf16_kernel(const FwdParams p) {
     __syncthreads();
   };
 
-  typedef std::integral_constant<int, 0> Buf0;
-  typedef std::integral_constant<int, 1> Buf1;
-  if constexpr (C::PIPE) {
-    // ============ pipelined single-stream loop (see the header comment) ============
-    // Inside the workgroup's tile list every wave processes every tile; a tile that a wave
-    // does not need is simply fully masked for it (its probabilities are exactly 0).
+  {
+    // ============ pipelined loop (see the header comment) ============
+    // The loop runs over work items: one item per key tile, or, for the differential variant, two
+    // per tile (stream 0, then stream 1, sharing the tile's V).  Inside the workgroup's tile list
+    // every wave processes every tile; a tile that a wave does not need is simply fully masked
+    // for it (its probabilities are exactly 0).
     typename W::Scores sa, sb;                     // the two score tiles in flight
     typename W::Pipe ps;
     typename W::BiasRegs br;
@@ -878,61 +843,77 @@ fwd_bf16_kernel(const FwdParams p) {
         w.rowmax(sa, mx);
         w.advance_max(0, mx);
       }
-      __syncthreads();                             // everyone is done with K ring slot 0
+      if constexpr (NS == 1) __syncthreads();      // everyone is done with K ring slot 0
       // uniform state of the tile stream: the ragged tile (if any) and the bases of the next K and
       // V tile to fetch, i.e. of tiles min(t2, t_hi - 1) and min(t1, t_hi - 1)
       const int t_rag = p.Sk % BN != 0 ? p.Sk / BN : -1;
-      const int64_t kstep = (int64_t)BN * kss[0], vstep = (int64_t)BN * vss;
-      const unsigned char* kb = k_tile_base(0, t2 < t_hi ? t2 : t_hi - 1);
+      const int64_t kstep[2] = {(int64_t)BN * kss[0], (int64_t)BN * kss[1]}, vstep = (int64_t)BN * vss;
+      const unsigned char* kb[NS];
+#pragma unroll
+      for (int s = 0; s < NS; ++s) kb[s] = k_tile_base(s, t2 < t_hi ? t2 : t_hi - 1);
       const unsigned char* vb = v_tile_base(t1 < t_hi ? t1 : t_hi - 1);
-      // Start of every step: finish the softmax bookkeeping of the current tile.  Only the
-      // (rare) mask branch and the (rare) rescale branch live outside the big basic block.
-      auto settle = [&](typename W::Scores& cur) __attribute__((always_inline)) {
+      // One pipeline step.  cur / nxt hold the scores of the current / next item.  Step number N
+      // (mod 4) fixes the roles at compile time.  One stream: K and V of the current tile sit in
+      // ring slot N % 2, K of the next tile in the other one; the step streams K(t2) into the slot
+      // K(t0) left in the previous step and V(t1) into the slot V(t-1) left.  Two streams: the
+      // tile's slot is (N / 2) % 2; the even step (stream 0) streams V(t1) in, the odd step
+      // (stream 1) both K tiles of t2, into the slot whose last reader was the even step.  These
+      // slots are free for the whole step, so the load instructions are spread over phase A (a
+      // burst of them right after the barrier stalls every wave of the workgroup in the memory
+      // pipeline while the matrix cores idle).  Past the end of the tile list the loads simply
+      // repeat the last tile, and the last item takes the same step: its "next item" contraction
+      // then runs on stale LDS contents and is never used.
+      auto step = [&](auto nc, typename W::Scores& cur, typename W::Scores& nxt) __attribute__((always_inline)) {
+        constexpr int N = decltype(nc)::value;
+        constexpr int SC = NS == 2 ? N % 2 : 0, SN = NS == 2 ? (N + 1) % 2 : 0;      // streams of cur / nxt
+        constexpr int slot_c = NS == 2 ? (N / 2) % 2 : N % 2;                         // ring slot of cur's tile
+        constexpr int slot_n = NS == 2 ? ((N + 1) / 2) % 2 : (N + 1) % 2;             // ... of nxt's tile
+        constexpr bool same_tile = NS == 2 && N % 2 == 0;                             // nxt is stream 1 of cur's tile
+        constexpr bool load_ks = NS == 1 || N % 2 == 1, load_vs = NS == 1 || N % 2 == 0;
+        const int tn = same_tile ? t0 : t1;
+        const bool fulln = same_tile ? full0 : wave_full(t1);
         if (!full0) {                              // fully visible tiles were settled in phase B
           w.mask(cur, t0 * BN);
           w.rowmax(cur, mx);
-          w.advance_max(0, mx);
+          w.advance_max(SC, mx);
         }
-      };
-      // One pipeline step.  cur / nxt hold the scores of t0 / t1.  Step number N (mod 4) fixes
-      // the roles at compile time: K(t0) and V(t0) sit in ring slot N % 2, K(t1) in the other
-      // one.  The step streams K(t2) into the slot K(t0) left in the previous step and V(t1) into
-      // the slot V(t-1) left; both are free for the whole step, so the load instructions are
-      // spread over phase A (a burst of them right after the barrier stalls every wave of the
-      // workgroup in the memory pipeline while the matrix cores idle).  Past the end of the tile
-      // list the loads simply repeat the last tile, and the last tile takes the same step: its
-      // "next tile" contraction then runs on stale LDS contents and is never used.
-      auto step = [&](auto nc, typename W::Scores& cur, typename W::Scores& nxt) __attribute__((always_inline)) {
-        constexpr int N = decltype(nc)::value;
-        constexpr int s_cur = N % 2, s_nxt = (N + 1) % 2;
-        const bool full1 = wave_full(t1);
-        settle(cur);
-        if (t1 < t_hi) w.load_bias(br, t1 * BN);   // before the tile loads: its wait then excludes them
+        if (tn < t_hi) w.load_bias(br, tn * BN);   // before the tile loads: its wait then excludes them
         const int tk = t2 < t_hi ? t2 : t_hi - 1, tv = t1 < t_hi ? t1 : t_hi - 1;
         if constexpr ((MASK & kMaskDoc) != 0) {    // tiles may be skipped: no fixed stride between them
-          kb = k_tile_base(0, tk);
+#pragma unroll
+          for (int s = 0; s < NS; ++s) kb[s] = k_tile_base(s, tk);
           vb = v_tile_base(tv);
         }
-        if (__builtin_expect(tk == t_rag, 0)) clamp_k(tk);
-        if (__builtin_expect(tv == t_rag, 0)) clamp_v(tv);
-        w.template phase_a<C::K_RING + s_nxt * C::K_BYTES>(nxt, cur, ps, t1 * BN, br, [&](auto fc) __attribute__((always_inline)) {
-          constexpr int f = decltype(fc)::value, NF = NB * KK, LPW = KPW + VPW;
-          static_for<0, KPW>([&](auto u) __attribute__((always_inline)) {
-            if constexpr (f == ((2 * u + 1) * NF) / (2 * LPW)) issue_k(0, u, kb, C::K_RING + s_cur * C::K_BYTES);
-          });
-          static_for<0, VPW>([&](auto u) __attribute__((always_inline)) {
-            if constexpr (f == ((2 * (KPW + u) + 1) * NF) / (2 * LPW)) issue_v(u, vb, C::V_RING + s_nxt * C::V_BYTES);
-          });
-        });
-        w.template phase_b<C::V_RING + s_cur * C::V_BYTES>(ps, cur, nxt, t1 * BN, br, full1);
+        if (load_ks && __builtin_expect(tk == t_rag, 0)) clamp_k(tk);
+        if (load_vs && __builtin_expect(tv == t_rag, 0)) clamp_v(tv);
+        w.template phase_a<C::K_RING + (slot_n * NS + SN) * C::K_BYTES, SC, SN>(
+            nxt, cur, ps, tn * BN, br, [&](auto fc) __attribute__((always_inline)) {
+              constexpr int f = decltype(fc)::value, NF = NB * KK;
+              constexpr int NK = load_ks ? NS * KPW : 0, NV = load_vs ? VPW : 0, LN = NK + NV;
+              static_for<0, NK>([&](auto ic) __attribute__((always_inline)) {
+                constexpr int i = decltype(ic)::value, ss = i / KPW, u = i % KPW;
+                if constexpr (f == ((2 * i + 1) * NF) / (2 * LN))
+                  issue_k(ss, u, kb[ss], C::K_RING + (slot_c * NS + ss) * C::K_BYTES);
+              });
+              static_for<0, NV>([&](auto uc) __attribute__((always_inline)) {
+                constexpr int u = decltype(uc)::value;
+                if constexpr (f == ((2 * (NK + u) + 1) * NF) / (2 * LN))
+                  issue_v(u, vb, C::V_RING + (NS == 2 ? 1 - slot_c : slot_n) * C::V_BYTES);
+              });
+            });
+        w.template phase_b<C::V_RING + slot_c * C::V_BYTES, SC, SN>(ps, cur, nxt, tn * BN, br, fulln);
         wait_loads_and_sync();
-        t0 = t1;
-        t1 = t2;
-        t2 = t2 < t_hi ? next_tile(t2 + 1) : t_hi;
-        full0 = full1;
-        if constexpr ((MASK & kMaskDoc) == 0) {    // consecutive tiles: advance the bases until the list ends
-          if (t1 < t_hi) vb += vstep;
-          if (t2 < t_hi) kb += kstep;
+        if constexpr (!same_tile) {                // the tile is done: move on in the tile list
+          t0 = t1;
+          t1 = t2;
+          t2 = t2 < t_hi ? next_tile(t2 + 1) : t_hi;
+          full0 = fulln;
+          if constexpr ((MASK & kMaskDoc) == 0) {  // consecutive tiles: advance the bases until the list ends
+            if (t1 < t_hi) vb += vstep;
+#pragma unroll
+            for (int s = 0; s < NS; ++s)
+              if (t2 < t_hi) kb[s] += kstep[s];
+          }
         }
       };
       while (true) {
@@ -947,51 +928,6 @@ fwd_bf16_kernel(const FwdParams p) {
         });
         if (done) break;
       }
-    }
-  } else {
-    // ============ two-stream (differential) loop: streams share V, one score tile at a time ====
-    typename W::Scores sc;
-    typename W::Probs pr;
-    typename W::BiasRegs br;
-    float mx[RB];
-    int t0 = next_tile(t_lo);
-    if (t0 < t_hi) {
-      load_k(t0, 0);
-      load_v(t0, 0);
-    }
-    wait_loads_and_sync();
-    auto step = [&](auto bufc) __attribute__((always_inline)) {
-      constexpr int BUF = decltype(bufc)::value;
-      const int t1 = next_tile(t0 + 1);
-      if (t1 < t_hi) {
-        load_k(t1, BUF ^ 1);
-        load_v(t1, BUF ^ 1);
-      }
-      const int c0 = wave_class(t0);
-      if (c0 != kTileSkip) {
-        w.load_bias(br, t0 * BN);
-        w.template qk<C::K_RING + (BUF * NS) * C::K_BYTES>(sc, 0);
-        w.transform(sc, t0 * BN, br);
-        if (c0 != kTileFull) w.mask(sc, t0 * BN);
-        w.rowmax(sc, mx);
-        w.advance_max(0, mx);
-        w.exp_sum(sc, 0, pr);
-        w.template pv<C::V_RING + BUF * C::V_BYTES>(pr, 0);
-        w.template qk<C::K_RING + (BUF * NS + NS - 1) * C::K_BYTES>(sc, NS - 1);
-        w.transform(sc, t0 * BN, br);
-        if (c0 != kTileFull) w.mask(sc, t0 * BN);
-        w.rowmax(sc, mx);
-        w.advance_max(NS - 1, mx);
-        w.exp_sum(sc, NS - 1, pr);
-        w.template pv<C::V_RING + BUF * C::V_BYTES>(pr, NS - 1);
-      }
-      wait_loads_and_sync();
-      t0 = t1;
-    };
-    while (t0 < t_hi) {
-      step(Buf0());
-      if (t0 >= t_hi) break;
-      step(Buf1());
     }
   }
 
