@@ -318,15 +318,30 @@ struct Wave {
     }
   }
 
-  // ---- masks of a partially visible tile: hidden scores become -inf (attention listing)
+  // ---- masks of a partially visible tile: hidden scores become -inf (attention listing).
+  // A lane holds one query row per row block, and register r of key block nb holds key
+  // j0 + 4*half + c with the compile-time offset c = 32*nb + 8*(r/4) + r%4.  The positional masks
+  // and the end of the key range are therefore two per-lane bounds on c: hidden iff c > d_hi
+  // (causal: j > i; PrefixLM: j > max(i, prefix - 1); always: j > Sk - 1) or c < d_lo (window:
+  // i - j > window) -- one or two compares per score instead of evaluating every mask on (i, j).
   __device__ __forceinline__ void mask(Scores& sc, int j0) const {
     constexpr uint32_t MASK = C::MASK;
+    const int jl = j0 + 4 * half;
+    int d_hi[RB], d_lo[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      int last = p.Sk - 1;                         // last visible key of the row
+      if constexpr ((MASK & kMaskPrefix) != 0) last = min(last, max(i[rb], p.prefix - 1));
+      else if constexpr ((MASK & (kMaskCausal | kMaskWindow)) != 0) last = min(last, i[rb]);
+      d_hi[rb] = last - jl;
+      d_lo[rb] = (MASK & kMaskWindow) != 0 ? i[rb] - p.window - jl : 0;
+    }
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-      const int jb = j0 + 32 * nb + 4 * half;
       int kd[16];
       if constexpr ((MASK & kMaskDoc) != 0) {
         const int32_t* kdoc = p.kv_doc + (int64_t)b * p.Sk;
+        const int jb = jl + 32 * nb;
         if (p.doc_vec && j0 + C::BN <= p.Sk) {     // uniform: four ids per load
 #pragma unroll
           for (int r4 = 0; r4 < 4; ++r4) {
@@ -345,8 +360,10 @@ struct Wave {
       for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int j = jb + 8 * (r >> 2) + (r & 3);
-          const bool hide = j >= p.Sk || is_masked(MASK, i[rb], j, p.window, p.prefix, qdoc[rb], (MASK & kMaskDoc) ? kd[r] : 0);
+          const int c = 32 * nb + 8 * (r >> 2) + (r & 3);
+          bool hide = c > d_hi[rb];
+          if constexpr ((MASK & kMaskWindow) != 0) hide = hide || c < d_lo[rb];
+          if constexpr ((MASK & kMaskDoc) != 0) hide = hide || kd[r] != qdoc[rb];
           if (hide) sc[rb][nb][r] = -INFINITY;
         }
     }
