@@ -161,6 +161,33 @@ def run_grid(steps, warmup):
                 print(f"# {variant:15s} {'gqa' if gqa else 'mha'} S={S:5d} B={w.dims['B']:2d}: {ms:.4f} ms  "
                       f"{rows[-1]['tflops']:.1f} TFLOP/s  {rows[-1]['gbs']:.0f} GB/s", file=sys.stderr, flush=True)
                 del dw
+    # the variants outside the 7 x 2 grid (Sec. 4.1): DiffAttn on the MHA grid and at head dim 128,
+    # Evoformer row-wise gated attention with two biases, plus column-wise gated attention
+    extra = [(f"diffattn_d64", "mha", S, lambda S=S: inputs.diffattn_paper_bf16(S=S, D=64)) for S in inputs.GRID_SEQ_LENS]
+    extra += [(f"diffattn_d128", "mha", S, lambda S=S: inputs.diffattn_paper_bf16(S=S, D=128)) for S in inputs.GRID_SEQ_LENS]
+    extra += [(f"evoformer_d{D}", f"b{B}", 256, lambda B=B, D=D: inputs.evoformer_paper_bf16(B=B, D=D))
+              for D in (64, 128) for B in (1, 4, 32)]
+    extra += [("columnwise_gated_d32", "b1", 128, lambda: inputs.columnwise_gated_bf16(B=1, Nseq=128, Nres=384, H=8, D=32))]
+    for variant, heads, S, make in extra:
+        w = make()
+        flops, byt = flops_and_bytes(w)
+        dw = runner.upload(w, out_dtype="same")
+        stream = torch.cuda.current_stream().cuda_stream
+        for _ in range(warmup):
+            dw.run_checked(stream)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            dw.run_checked(stream)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        rows.append(dict(variant=variant, heads=heads, S=S, B=w.dims["B"], ms=ms,
+                         tflops=flops / (ms * 1e-3) / 1e12, gbs=byt / (ms * 1e-3) / 1e9))
+        print(f"# {variant:15s} {heads} S={S:5d} B={w.dims['B']:2d}: {ms:.4f} ms  "
+              f"{rows[-1]['tflops']:.1f} TFLOP/s  {rows[-1]['gbs']:.0f} GB/s", file=sys.stderr, flush=True)
+        del dw
     os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
     with open(os.path.join(ROOT, "gpurun_out", "bench_grid.json"), "w") as f:
         json.dump(rows, f, indent=1)

@@ -7,6 +7,7 @@ static const KernelEntry kEntries[] = {
     E(64, 128, kMaskCausal, kEpiRms), E(64, 128, kMaskCausal, 0), E(64, 128, 0, kEpiRms), E(64, 128, 0, 0),
     E(128, 128, kMaskCausal, kEpiRms), E(128, 128, kMaskCausal, 0),
     E(64, 64, kMaskCausal, kEpiRms), E(64, 64, kMaskCausal, 0),
+    E(64, 64, 0, 0), E(128, 128, 0, 0),   // the paper's DiffAttn benchmark shapes: no mask, no normalisation
 };
 #undef E
 const KernelEntry* entries_diff(int* n) {

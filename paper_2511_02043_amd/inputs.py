@@ -170,7 +170,8 @@ def window_doc_bf16(B=8, H=16, S=2048, D=64, window=512, lo=64, hi=1024, salt=0)
                     window=window, q_doc=ids, kv_doc=ids)
 
 
-def differential_bf16(B=2, H=16, S=4096, D=64, Dv=128, lam=0.8, salt=0, dtype="bf16") -> Workload:
+def differential_bf16(B=2, H=16, S=4096, D=64, Dv=128, lam=0.8, salt=0, dtype="bf16", causal=True,
+                      rmsnorm=True) -> Workload:
     """Config 4: differential attention (two softmax streams sharing V), causal, RMSNorm.
 
     One allocation of 2H heads for q and for k; pair h is (head h, head H + h),
@@ -180,8 +181,8 @@ def differential_bf16(B=2, H=16, S=4096, D=64, Dv=128, lam=0.8, salt=0, dtype="b
     k_all = normal((B, 1, 2 * H, S, D), tensor_seed(4, 1, salt), dtype)
     v = normal((B, 1, H, S, Dv), tensor_seed(4, 2, salt), dtype)
     return Workload("differential_" + dtype, dtype, q_all[:, :, :H], k_all[:, :, :H], v,
-                    scale=D ** -0.5, causal=True, q2=q_all[:, :, H:], k2=k_all[:, :, H:],
-                    lam=np.full((H,), lam, dtype=np.float32), rmsnorm=True, rms_eps=1e-6)
+                    scale=D ** -0.5, causal=causal, q2=q_all[:, :, H:], k2=k_all[:, :, H:],
+                    lam=np.full((H,), lam, dtype=np.float32), rmsnorm=rmsnorm, rms_eps=1e-6)
 
 
 def evoformer_bf16(B=1, Nseq=128, Nres=384, H=8, D=32, two_biases=False, salt=0,
@@ -246,4 +247,33 @@ def grid_bf16(variant: str, S: int, gqa: bool = False, B: Optional[int] = None, 
     elif variant == "document_mask":
         ids = doc_ids_fixed_count(B, S, min(n_docs, S), tensor_seed(6, 3, salt))
         w.q_doc = w.kv_doc = ids
+    return w
+
+
+def columnwise_gated_bf16(B=1, Nseq=128, Nres=256, H=8, D=32, salt=0, dtype="bf16") -> Workload:
+    """Column-wise gated self-attention of the MSA stack (named in Sec. 1): attention runs over the
+    sequence axis independently for each residue column, no bias, sigmoid gate.  Activations are
+    stored [B, Nseq, Nres, H, D] as for the row-wise case; the arrays returned are the
+    [B, G=Nres, H, S=Nseq, D] views of that storage."""
+    def act(idx):
+        x = normal((B, Nseq, Nres, H, D), tensor_seed(5, idx, salt + 7), dtype)
+        return x.transpose(0, 2, 3, 1, 4)
+    q, k, v, gate = act(0), act(1), act(2), act(4)
+    return Workload("columnwise_gated_" + dtype, dtype, q, k, v, scale=D ** -0.5, gate=gate)
+
+
+def evoformer_paper_bf16(B=1, N=256, H=4, D=64, salt=0) -> Workload:
+    """The paper's Evoformer benchmark shape (Sec. 4.1): both sequence dimensions 256, 4 heads,
+    head dim 64 or 128, batch 1..32, two biases (one broadcast over the extra dimension), gate."""
+    w = evoformer_bf16(B=B, Nseq=N, Nres=N, H=H, D=D, two_biases=True, salt=salt + 11)
+    w.name = f"evoformer_paper_b{B}_d{D}"
+    return w
+
+
+def diffattn_paper_bf16(S=2048, D=64, B=None, H=16, tokens=16384, salt=0) -> Workload:
+    """The paper's DiffAttn benchmark shape (Sec. 4.1): the MHA grid (16 heads, head dim 64, batch * S =
+    16k tokens) and 16 heads with head dim 128; no mask, no normalisation, as in the listing."""
+    B = max(1, tokens // S) if B is None else B
+    w = differential_bf16(B=B, H=H, S=S, D=D, Dv=D, salt=salt + 13, causal=False, rmsnorm=False)
+    w.name = f"diffattn_paper_s{S}_d{D}"
     return w

@@ -18,3 +18,19 @@ def test_grid_cell_s512(variant, gqa):
 def test_grid_cell_s2048_gqa(variant):
     """Longer rows: several key tiles inside and outside the window / prefix / documents."""
     run_and_compare(inputs.grid_bf16(variant, 2048, gqa=True, B=1), label=f"grid {variant} gqa S=2048")
+
+
+@pytest.mark.parametrize("D", [32, 64, 128])
+def test_columnwise_gated(D):
+    """Attention over the sequence axis of [B, Nseq, Nres, H, D] storage (strided views), gate only."""
+    run_and_compare(inputs.columnwise_gated_bf16(B=1, Nseq=200, Nres=6, H=2, D=D), label=f"column-wise gated D={D}")
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_evoformer_paper_shape(D):
+    run_and_compare(inputs.evoformer_paper_bf16(B=1, N=256, H=4, D=D), label=f"Evoformer 256x256 H=4 D={D}")
+
+
+@pytest.mark.parametrize("S,D", [(512, 64), (1024, 128)])
+def test_diffattn_paper_shape(S, D):
+    run_and_compare(inputs.diffattn_paper_bf16(S=S, D=D, B=1, H=4), label=f"DiffAttn S={S} D={D}")
