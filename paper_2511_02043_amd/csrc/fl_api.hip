@@ -306,6 +306,9 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
       if (dtype == FL_BF16 && bv.is_f32) return fail(FL_ERR_DTYPE, "bias[%u]: bf16 inputs take bf16 biases", nb);
       bv.vec4 = bs[4] == 1 && Sk > 1 && ((uintptr_t)bt->ptr) % 8 == 0 && bs[0] % 4 == 0 && bs[1] % 4 == 0 &&
                 bs[2] % 4 == 0 && bs[3] % 4 == 0;
+      // per-query rows that start 16-byte aligned: whole tiles go through LDS (decided below, with the LDS budget)
+      bv.dma = dtype == FL_BF16 && bs[4] == 1 && bs[3] != 0 && ((uintptr_t)bt->ptr) % 16 == 0 && bs[0] % 8 == 0 &&
+               bs[1] % 8 == 0 && bs[2] % 8 == 0 && bs[3] % 8 == 0;
     }
   }
 
@@ -375,6 +378,17 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   p.n_bias = (int)desc->n_bias;
   p.epi = (int)desc->epilogue;
   p.n_qtiles = (int)((Sq + ke->bm - 1) / ke->bm);
+  if (dtype == FL_BF16) {
+    // dynamic LDS: the K/V rings, then two staging buffers per wave and bias for the bias tiles
+    // that are read through LDS
+    const int64_t kv = ke->lds_bytes;
+    const int64_t stage = (int64_t)ke->key.nwaves * ke->key.nbias * 2 * (32 * ke->key.rb * ke->key.bn * 2);
+    const bool any_dma = (ke->key.nbias > 0 && p.bias[0].dma) || (ke->key.nbias > 1 && p.bias[1].dma);
+    const bool staged = any_dma && kv + stage <= fl::kMaxLdsBytes;
+    if (!staged) p.bias[0].dma = p.bias[1].dma = 0;
+    p.bias_lds_base = (int)kv;
+    p.lds_bytes = (int)(kv + (staged ? stage : 0));
+  }
   const int64_t nbh = B * G * H;
   // bf16 kernels under a causal / prefix mask without a window: the work of a q-tile grows with
   // its index, so a workgroup takes a long and a short one -- when that still leaves every CU

@@ -146,6 +146,19 @@ struct Wave {
 
   const FwdParams& p;
   const uint16_t* brow[C::NBIAS > 0 ? C::NBIAS : 1][C::RB];   // this lane's bias rows (bias, row block)
+  // Bias tiles staged through LDS (BiasView::dma): a lane holds one query row, so reading its
+  // bias values straight from global memory touches one cache line per lane for 8 useful bytes.
+  // Instead each wave copies the [32 x BN] tile of its rows into a private LDS buffer with
+  // coalesced direct loads, one key tile ahead, and every lane picks its values up from there.
+  static constexpr int BROW_BYTES = C::BN * 2;                 // bytes of one staged bias row
+  static constexpr int BCH = BROW_BYTES / 16;                  // 16-byte chunks per row
+  static constexpr int BNI = 32 * BROW_BYTES / 1024;           // direct-load instructions per row block
+  static constexpr int BSTAGE = 32 * C::RB * BROW_BYTES;       // bytes of one staging buffer
+  const uint16_t* bsrc[C::NBIAS > 0 ? C::NBIAS : 1][C::RB][BNI];   // per-lane source of each load instruction (key 0)
+  uint32_t brd[C::RB];          // per-lane LDS address of its row in staging buffer 0 of bias 0
+  uint32_t bsw;                 // chunk swizzle of this lane's row
+  uint32_t bstage;              // LDS byte offset of this wave's staging area (uniform)
+  unsigned char* lds;           // the workgroup's LDS
   int lane, half, col;
   int b, g, h;
   int i[C::RB], ic[C::RB];      // this lane's query rows (unclamped / clamped), one per row block
@@ -203,7 +216,7 @@ struct Wave {
   // kind, so the loop is built to need few of them: fragments are read from LDS one group ahead
   // and one wait covers a whole group.  body(f, fragment) is called in fragment order.
   template <int KOFF, class Body>
-  __device__ __forceinline__ void k_stream(Body&& body) const {
+  __device__ __forceinline__ void k_stream(const uint32_t (&ka)[C::KK], Body&& body) const {
     constexpr int NF = NB * KK, G = C::GK < NF ? C::GK : NF, NG = NF / G;   // fragments (nb, kk)
     static_assert(NF % G == 0, "K fragment groups");
     i32x4 kf[NF];
@@ -219,7 +232,7 @@ struct Wave {
     });
   }
   template <int VOFF, class Body>
-  __device__ __forceinline__ void v_stream(Body&& body) const {
+  __device__ __forceinline__ void v_stream(const uint32_t (&va)[C::DVB], Body&& body) const {
     constexpr int NF = NB * 2 * DVB, G = C::GV < NF ? C::GV : NF, NG = NF / G;   // fragments (nb, ks, d)
     static_assert(NF % G == 0, "V fragment groups");
     i32x2 lo[NF], hi[NF];
@@ -241,9 +254,9 @@ struct Wave {
 
   // ---- first contraction of stream s: S^T = K Q^T for all row blocks, K tile at LDS offset KOFF
   template <int KOFF>
-  __device__ __forceinline__ void qk(Scores& sc, int s) const {
+  __device__ __forceinline__ void qk(Scores& sc, int s, const uint32_t (&ka)[C::KK]) const {
     f32x16 acc[RB];
-    k_stream<KOFF>([&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+    k_stream<KOFF>(ka, [&](auto fc, bf16x8 a) __attribute__((always_inline)) {
       constexpr int f = fc, kk = f % KK, nb = f / KK;
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
@@ -294,10 +307,46 @@ struct Wave {
 
   // ---- bias values of tile j0 for this lane, issued early so that their latency hides behind
   // the matrix work of the step.  Rows whose layout allows it are read four keys per load.
+  // chunk swizzle of staged row r: spreads the rows that share LDS banks over different chunks
+  static __device__ __forceinline__ uint32_t bias_swz(int r) { return (uint32_t)(BCH == 4 ? (r >> 2) : (r >> 1)) & (BCH - 1); }
+
+  // start the copy of the bias tiles of key tile j0 into staging buffer BUF (full tiles only)
+  template <int BUF>
+  __device__ __forceinline__ void bias_dma(int j0) const {
+#pragma unroll
+    for (int nbias = 0; nbias < C::NBIAS; ++nbias) {
+      if (p.bias[nbias].dma == 0 || j0 + C::BN > p.Sk) continue;   // uniform
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int u = 0; u < BNI; ++u) {
+          lds_void* dst = (lds_void*)(lds + bstage + (nbias * 2 + BUF) * BSTAGE + rb * (32 * BROW_BYTES) + u * 1024);
+          __builtin_amdgcn_global_load_lds((global_cvoid*)(bsrc[nbias][rb][u] + j0), dst, 16, 0, 0);
+        }
+    }
+  }
+
+  // bias values of tile j0 for this lane: from staging buffer BUF where the tile was staged, else
+  // straight from global memory (issued early so that the latency hides behind the matrix work)
+  template <int BUF>
   __device__ __forceinline__ void load_bias(BiasRegs& br, int j0) const {
 #pragma unroll
     for (int nbias = 0; nbias < C::NBIAS; ++nbias) {
       const BiasView& bv = p.bias[nbias];
+      if (bv.dma != 0 && j0 + C::BN <= p.Sk) {     // uniform
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+              const uint32_t a = brd[rb] + (((uint32_t)(4 * nb + r4) ^ bsw) << 4);
+              i32x2 v;
+              asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(v) : "v"(a), "n"((nbias * 2 + BUF) * BSTAGE) : "memory");
+              br.v[nbias][rb][nb][r4] = make_uint2((uint32_t)v[0], (uint32_t)v[1]);
+            }
+        continue;
+      }
       const bool vec = bv.vec4 != 0 && j0 + C::BN <= p.Sk;       // uniform
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
@@ -483,7 +532,7 @@ struct Wave {
   // SC / SN: softmax stream of the current / next score tile (both 0 unless differential).
   template <int KOFF, int SC, int SN, class Hook>
   __device__ __forceinline__ void phase_a(Scores& nxt, const Scores& cur, Pipe& ps, int j1, const BiasRegs& br,
-                                          Hook&& hook) {
+                                          const uint32_t (&ka)[C::KK], Hook&& hook) {
     constexpr int NF = NB * KK;
     constexpr int SE = (NB == 2 ? KK : NF) * RB;   // slots (fragment, row block) that carry exponentials
     constexpr int PA = NPAIR / 2;                  // pairs of the first half
@@ -495,7 +544,7 @@ struct Wave {
       ps.mx[rb] = -INFINITY;
     }
     f32x16 acc[RB];
-    k_stream<KOFF>([&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+    k_stream<KOFF>(ka, [&](auto fc, bf16x8 a) __attribute__((always_inline)) {
       constexpr int f = fc, kk = f % KK, nb = f / KK;
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
@@ -526,11 +575,11 @@ struct Wave {
   // update is left to the start of the next step.  The O rescale is a rare branch at the end.
   template <int VOFF, int SC, int SN>
   __device__ __forceinline__ void phase_b(Pipe& ps, const Scores& cur, Scores& nxt, int j1, const BiasRegs& br,
-                                          bool advance) {
+                                          const uint32_t (&va)[C::DVB], bool advance) {
     constexpr int NF = NB * 2 * DVB, HALF = NF / 2;
     constexpr int SE = HALF * RB, SM = NF * RB - SE, PA = NPAIR / 2;
     static_assert(NF % 2 == 0, "chunking");
-    v_stream<VOFF>([&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+    v_stream<VOFF>(va, [&](auto fc, bf16x8 a) __attribute__((always_inline)) {
       constexpr int f = fc, d = f % DVB, ks = (f / DVB) % 2, nb = f / (2 * DVB);
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
@@ -650,9 +699,20 @@ fwd_bf16_kernel(const FwdParams p) {
 #pragma unroll
     for (int nbias = 0; nbias < C::NBIAS; ++nbias) {
       const BiasView& bv = p.bias[nbias];
-      w.brow[nbias][rb] = (const uint16_t*)bv.ptr + b * bv.sb + g * bv.sg + h * bv.sh + (int64_t)w.ic[rb] * bv.si;
+      const uint16_t* bhead = (const uint16_t*)bv.ptr + b * bv.sb + g * bv.sg + h * bv.sh;
+      w.brow[nbias][rb] = bhead + (int64_t)w.ic[rb] * bv.si;
+#pragma unroll
+      for (int u = 0; u < W::BNI; ++u) {           // staging: this lane's source row and chunk of load instruction u
+        const int r = u * (64 / W::BCH) + lane / W::BCH;
+        const int ir = iw + 32 * rb + r < p.Sq ? iw + 32 * rb + r : p.Sq - 1;
+        w.bsrc[nbias][rb][u] = bhead + (int64_t)ir * bv.si + (((uint32_t)(lane % W::BCH) ^ W::bias_swz(r)) << 3);
+      }
     }
+    w.brd[rb] = p.bias_lds_base + wave * (C::NBIAS * 2 * W::BSTAGE) + rb * (32 * W::BROW_BYTES) + w.col * W::BROW_BYTES + w.half * 8;
   }
+  w.bsw = W::bias_swz(w.col);
+  w.bstage = p.bias_lds_base + wave * (C::NBIAS * 2 * W::BSTAGE);
+  w.lds = lds_raw;
 #pragma unroll
   for (int s = 0; s < NS; ++s)
 #pragma unroll
@@ -847,12 +907,15 @@ fwd_bf16_kernel(const FwdParams p) {
     if (t0 < t_hi) {
       auto after = [&](int t) __attribute__((always_inline)) { return t < t_hi ? next_tile(t + 1) : t_hi; };
       int t1 = after(t0), t2 = after(t1);
-      w.load_bias(br, t0 * BN);
+      w.template bias_dma<0>(t0 * BN);
+      if (t1 < t_hi) w.template bias_dma<1>(t1 * BN);
       load_k(t0, 0);
       load_v(t0, 0);
       if (t1 < t_hi) load_k(t1, 1);
       wait_loads_and_sync();
-      w.template qk<C::K_RING>(sa, 0);
+      w.template load_bias<0>(br, t0 * BN);
+      w.template qk<C::K_RING>(sa, 0, w.ka);
+      if constexpr (C::NBIAS > 0) W::template wait_lds<0>();     // staged bias values have arrived
       w.transform(sa, t0 * BN, br);
       float mx[RB];
       bool full0 = wave_full(t0);
@@ -894,7 +957,13 @@ fwd_bf16_kernel(const FwdParams p) {
           w.rowmax(cur, mx);
           w.advance_max(SC, mx);
         }
-        if (tn < t_hi) w.load_bias(br, tn * BN);   // before the tile loads: its wait then excludes them
+        if constexpr (C::NBIAS > 0) {
+          // bias of the next tile: staged one step ago into buffer (N + 1) % 2 (its values are
+          // first used behind the LDS waits of phase A, which cover these reads: LDS returns in
+          // order); the tile after it is staged now into the buffer this frees
+          if (tn < t_hi) w.template load_bias<(N + 1) % 2>(br, tn * BN);
+          if (t2 < t_hi) w.template bias_dma<N % 2>(t2 * BN);
+        }
         const int tk = t2 < t_hi ? t2 : t_hi - 1, tv = t1 < t_hi ? t1 : t_hi - 1;
         if constexpr ((MASK & kMaskDoc) != 0) {    // tiles may be skipped: no fixed stride between them
 #pragma unroll
@@ -904,7 +973,7 @@ fwd_bf16_kernel(const FwdParams p) {
         if (load_ks && __builtin_expect(tk == t_rag, 0)) clamp_k(tk);
         if (load_vs && __builtin_expect(tv == t_rag, 0)) clamp_v(tv);
         w.template phase_a<C::K_RING + (slot_n * NS + SN) * C::K_BYTES, SC, SN>(
-            nxt, cur, ps, tn * BN, br, [&](auto fc) __attribute__((always_inline)) {
+            nxt, cur, ps, tn * BN, br, w.ka, [&](auto fc) __attribute__((always_inline)) {
               constexpr int f = decltype(fc)::value, NF = NB * KK;
               constexpr int NK = load_ks ? NS * KPW : 0, NV = load_vs ? VPW : 0, LN = NK + NV;
               static_for<0, NK>([&](auto ic) __attribute__((always_inline)) {
@@ -918,7 +987,7 @@ fwd_bf16_kernel(const FwdParams p) {
                   issue_v(u, vb, C::V_RING + (NS == 2 ? 1 - slot_c : slot_n) * C::V_BYTES);
               });
             });
-        w.template phase_b<C::V_RING + slot_c * C::V_BYTES, SC, SN>(ps, cur, nxt, tn * BN, br, fulln);
+        w.template phase_b<C::V_RING + slot_c * C::V_BYTES, SC, SN>(ps, cur, nxt, tn * BN, br, w.va, fulln);
         wait_loads_and_sync();
         if constexpr (!same_tile) {                // the tile is done: move on in the tile list
           t0 = t1;

@@ -28,6 +28,7 @@ struct BiasView {        // logical [B, G, H, Sq, Sk]; any stride may be 0 (broa
   int64_t sb, sg, sh, si, sj;
   int32_t is_f32;
   int32_t vec4;          // 1: sj == 1 and every row start is 8-byte aligned -> 4 keys per load
+  int32_t dma;           // 1 (bf16 kernels): rows are 16-byte aligned and differ per query -> tiles staged through LDS
 };
 
 struct FwdParams {
@@ -52,6 +53,8 @@ struct FwdParams {
   int32_t n_qtiles;      // ceil(Sq / rows per workgroup)
   int32_t order;         // workgroup ordering scheme
   int32_t doc_vec;       // 1: kv_doc rows are 16-byte aligned and Sk % 4 == 0 -> 4 ids per load
+  int32_t lds_bytes;     // bf16 kernels: dynamic LDS size of this launch (K/V rings, then bias staging)
+  int32_t bias_lds_base; // byte offset of the per-wave bias staging buffers in LDS
   int32_t pair;          // bf16 kernels: 1 = a workgroup takes q-tiles nq - 1 - i and i (balanced causal work)
 };
 

@@ -22,26 +22,25 @@ typedef hipError_t (*LaunchFn)(const FwdParams& p, int nblocks, hipStream_t stre
 struct KernelEntry {
   KernelKey key;
   int bm;           // query rows per workgroup
-  int lds_bytes;
+  int lds_bytes;    // LDS of the K/V rings per workgroup
   LaunchFn launch;
 };
 
+constexpr int kMaxLdsBytes = 160 * 1024;           // LDS of a gfx950 compute unit
+
 template <class C>
 hipError_t launch_bf16(const FwdParams& p, int nblocks, hipStream_t stream) {
-  if (C::LDS_BYTES > 48 * 1024) {
-    // Raising the dynamic-LDS limit is per device and sticky; cheap enough to repeat per device.
-    static bool done[64] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
+  // Raising the dynamic-LDS limit is per device and sticky; cheap enough to repeat per device.
+  static bool done[64] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64 || !done[dev]) {
+    e = hipFuncSetAttribute((const void*)fwd_bf16_kernel<C>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
     if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= 64 || !done[dev]) {
-      e = hipFuncSetAttribute((const void*)fwd_bf16_kernel<C>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              C::LDS_BYTES);
-      if (e != hipSuccess) return e;
-      if (dev >= 0 && dev < 64) done[dev] = true;
-    }
+    if (dev >= 0 && dev < 64) done[dev] = true;
   }
-  hipLaunchKernelGGL(fwd_bf16_kernel<C>, dim3(nblocks), dim3(C::NT), C::LDS_BYTES, stream, p);
+  hipLaunchKernelGGL(fwd_bf16_kernel<C>, dim3(nblocks), dim3(C::NT), p.lds_bytes, stream, p);
   return hipGetLastError();
 }
 
