@@ -394,7 +394,7 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   // its index, so a workgroup takes a long and a short one -- when that still leaves every CU
   // several workgroups
   const bool tri = (mask & (FL_MASK_CAUSAL | FL_MASK_PREFIX)) != 0 && (mask & (FL_MASK_WINDOW | FL_MASK_DOC)) == 0;
-  p.pair = g_tuning.pair >= 0 ? g_tuning.pair : (dtype == FL_BF16 && tri && nbh * ((p.n_qtiles + 1) / 2) >= 1024);
+  p.pair = g_tuning.pair >= 0 ? g_tuning.pair : (dtype == FL_BF16 && tri && nbh * ((p.n_qtiles + 1) / 2) >= 512);
   if (dtype != FL_BF16) p.pair = 0;
   const int64_t nblocks = nbh * (p.pair ? (p.n_qtiles + 1) / 2 : p.n_qtiles);
   if (nblocks > 0x7fffffffLL || nbh * Sq > 0x7fffffff00LL) return fail(FL_ERR_SHAPE, "too many workgroups");
