@@ -114,6 +114,21 @@ def test_c5_evoformer():
     run_and_compare(inputs.evoformer_bf16(B=2, Nseq=3, Nres=70, H=2, D=32, two_biases=True))
 
 
+@pytest.mark.parametrize("D", [32, 64, 128])
+def test_bias_paths(D):
+    """Bias tiles reach the lanes three ways: staged through LDS (rows 16-byte aligned, full tiles),
+    four keys per load (8-byte aligned rows) and element by element (ragged last tile, odd row
+    stride).  Sizes here hit each of them, with one and with two per-query biases."""
+    import numpy as np
+    for nres, nseq in ((160, 2), (100, 3), (36, 2), (67, 2)):      # row bytes 320 / 200 / 72 / 134
+        w = inputs.evoformer_bf16(B=1, Nseq=nseq, Nres=nres, H=2, D=D, two_biases=True, salt=nres)
+        run_and_compare(w, label=f"bias D={D} Nres={nres} pair + row bias")
+        # second bias per query as well: both go through the staging buffers
+        full = inputs.normal((1, nseq, 2, nres, nres), inputs.tensor_seed(5, 6, nres), "bf16")
+        w.biases = (w.biases[0], np.ascontiguousarray(full))
+        run_and_compare(w, label=f"bias D={D} Nres={nres} two per-query biases")
+
+
 def test_deterministic_run_to_run():
     import torch
     from paper_2511_02043_amd import runner
