@@ -2,7 +2,8 @@
 // per-head RMSNorm (differential-attention listing, Sec. 3), bf16.
 #include "fl_registry.hpp"
 namespace fl {
-#define E(D, DV, MASK, EPI) bf16_entry<D, DV, 4, 1, 64, (DV > 64 ? 1 : 2), kModNone, MASK, 0, true, EPI>()
+// 8 waves: waves 0-3 run stream 0, waves 4-7 stream 1 of the same 128 query rows
+#define E(D, DV, MASK, EPI) bf16_entry<D, DV, 8, 1, (D == 128 ? 32 : 64), 2, kModNone, MASK, 0, true, EPI>()
 static const KernelEntry kEntries[] = {
     E(64, 128, kMaskCausal, kEpiRms), E(64, 128, kMaskCausal, 0), E(64, 128, 0, kEpiRms), E(64, 128, 0, 0),
     E(128, 128, kMaskCausal, kEpiRms), E(128, 128, kMaskCausal, 0),

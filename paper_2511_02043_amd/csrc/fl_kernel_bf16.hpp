@@ -112,17 +112,23 @@ struct Bf16Cfg {
   static constexpr int GV = 2;                     // V^T fragments (two reads each) per LDS wait
   static constexpr int NT = NWAVES * 64;
   static constexpr int WROWS = 32 * RB;            // query rows per wave
-  static constexpr int BM = NWAVES * WROWS;        // query rows per workgroup
+  static constexpr int NS = DIFF ? 2 : 1;          // softmax streams
+  // Differential: the two streams of a row block run in two different waves (wave w and wave
+  // w + NWAVES / 2, which share a SIMD), so that each keeps the register footprint of ordinary
+  // attention and two waves fit a SIMD; they share the V tiles and meet in the epilogue.
+  static constexpr int NROWG = NWAVES / NS;        // waves per stream = row groups of the workgroup
+  static constexpr int BM = NROWG * WROWS;         // query rows per workgroup
   static constexpr int NB = BN / 32;               // 32-key blocks per tile
   static constexpr int KK = D / 16;                // MFMA k-steps of the first contraction
   static constexpr int DVB = DV / 32;              // 32-channel blocks of the output
-  static constexpr int NS = DIFF ? 2 : 1;          // softmax streams
   static constexpr int K_BYTES = BN * D * 2;
   static constexpr int V_BYTES = BN * DV * 2;
   static constexpr int RING = 2;                   // slots of the K ring and of the V ring
   static constexpr int K_RING = 0;                 // LDS layout: K ring [RING][NS][K_BYTES], V ring [RING][V_BYTES]
   static constexpr int V_RING = RING * NS * K_BYTES;
-  static constexpr int LDS_BYTES = V_RING + RING * V_BYTES;
+  static constexpr int RING_BYTES = V_RING + RING * V_BYTES;
+  static constexpr int XCH_BYTES = DIFF ? NROWG * 64 * DVB * 16 * 4 : 0;   // epilogue exchange of the differential variant
+  static constexpr int LDS_BYTES = RING_BYTES > XCH_BYTES ? RING_BYTES : XCH_BYTES;
   static constexpr int K_INSTR = K_BYTES / 1024;   // 64-lane x 16-byte direct loads per K tile
   static constexpr int V_INSTR = V_BYTES / 1024;
   static constexpr int K_ROWS_PI = 64 / (D / 8);   // tile rows covered by one direct-load instruction
@@ -166,9 +172,9 @@ struct Wave {
   float c_scale, slope_l2;
   uint32_t ka[C::KK];           // per-lane byte offset of the K fragment of k-step kk (block 0)
   uint32_t va[C::DVB];          // per-lane byte offset of the V^T fragment of channel block d (key block 0)
-  bf16x8 qf[C::NS][C::RB][C::KK];
-  f32x16 oacc[C::NS][C::RB][C::DVB];
-  float m_run[C::NS][C::RB], l_run[C::NS][C::RB];  // log2-domain running max; per-lane partial sum
+  bf16x8 qf[1][C::RB][C::KK];   // (first index: softmax stream of the wave, always 0: one stream per wave)
+  f32x16 oacc[1][C::RB][C::DVB];
+  float m_run[1][C::RB], l_run[1][C::RB];          // log2-domain running max; per-lane partial sum
 
   __device__ __forceinline__ Wave(const FwdParams& p_) : p(p_) {}
 
@@ -529,8 +535,7 @@ struct Wave {
   }
 
   // hook(f) runs after the work of fragment f: the caller's tile loads.
-  // SC / SN: softmax stream of the current / next score tile (both 0 unless differential).
-  template <int KOFF, int SC, int SN, class Hook>
+  template <int KOFF, class Hook>
   __device__ __forceinline__ void phase_a(Scores& nxt, const Scores& cur, Pipe& ps, int j1, const BiasRegs& br,
                                           const uint32_t (&ka)[C::KK], Hook&& hook) {
     constexpr int NF = NB * KK;
@@ -539,7 +544,7 @@ struct Wave {
     constexpr int SM = NF * RB - SE;               // slots that carry the max of key block 0 (NB == 2)
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      ps.m_safe[rb] = m_run[SC][rb] == -INFINITY ? 0.f : m_run[SC][rb];
+      ps.m_safe[rb] = m_run[0][rb] == -INFINITY ? 0.f : m_run[0][rb];
       ps.psum[rb] = 0.f;
       ps.mx[rb] = -INFINITY;
     }
@@ -549,7 +554,7 @@ struct Wave {
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
         if (kk == 0) acc[rb] = zero16();
-        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[SN][rb][kk], acc[rb], 0, 0, 0);
+        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][rb][kk], acc[rb], 0, 0, 0);
         if (kk == KK - 1) nxt[rb][nb] = acc[rb];
         const int slot = f * RB + rb;
         if (slot < SE) {
@@ -573,7 +578,7 @@ struct Wave {
 
   // `advance` (uniform) is false when the next tile still needs its mask: then the running-max
   // update is left to the start of the next step.  The O rescale is a rare branch at the end.
-  template <int VOFF, int SC, int SN>
+  template <int VOFF>
   __device__ __forceinline__ void phase_b(Pipe& ps, const Scores& cur, Scores& nxt, int j1, const BiasRegs& br,
                                           const uint32_t (&va)[C::DVB], bool advance) {
     constexpr int NF = NB * 2 * DVB, HALF = NF / 2;
@@ -587,11 +592,11 @@ struct Wave {
         if (slot == SE) finish_pair(ps, NPAIR - 1);
         const bf16x8 pb = __builtin_bit_cast(bf16x8, (i32x4){(int)ps.w[rb][nb][4 * ks], (int)ps.w[rb][nb][4 * ks + 1],
                                                              (int)ps.w[rb][nb][4 * ks + 2], (int)ps.w[rb][nb][4 * ks + 3]});
-        oacc[SC][rb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[SC][rb][d], 0, 0, 0);
+        oacc[0][rb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[0][rb][d], 0, 0, 0);
         if constexpr (C::PSPLIT) {
           const bf16x8 pl = __builtin_bit_cast(bf16x8, (i32x4){(int)ps.wl[nb][4 * ks], (int)ps.wl[nb][4 * ks + 1],
                                                                (int)ps.wl[nb][4 * ks + 2], (int)ps.wl[nb][4 * ks + 3]});
-          oacc[SC][rb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pl, oacc[SC][rb][d], 0, 0, 0);
+          oacc[0][rb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pl, oacc[0][rb][d], 0, 0, 0);
         }
         if (slot < SE) {
 #pragma unroll
@@ -609,16 +614,16 @@ struct Wave {
     bool any = false;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      l_run[SC][rb] += ps.psum[rb];
+      l_run[0][rb] += ps.psum[rb];
       float mxs = half_swap_max(ps.mx[rb]);
       if constexpr (kPlain) mxs *= c_scale;        // scale > 0 (checked on the host)
-      const float m_old = m_run[SN][rb];
+      const float m_old = m_run[0][rb];
       float m_new = (mxs - m_old > kLazyMaxLog2) ? mxs : m_old;   // false for NaN (-inf - -inf)
       m_new = advance ? m_new : m_old;
       const bool moved = m_new != m_old;
       alpha[rb] = moved ? fast_exp2(m_old - (m_new == -INFINITY ? 0.f : m_new)) : 1.f;
-      m_run[SN][rb] = m_new;
-      l_run[SN][rb] *= alpha[rb];
+      m_run[0][rb] = m_new;
+      l_run[0][rb] *= alpha[rb];
       any = any || moved;
     }
     if (__builtin_amdgcn_ballot_w64(any) != 0) {   // rare and wave-uniform
@@ -627,7 +632,7 @@ struct Wave {
 #pragma unroll
         for (int d = 0; d < DVB; ++d)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[SN][rb][d][r] *= alpha[rb];
+          for (int r = 0; r < 16; ++r) oacc[0][rb][d][r] *= alpha[rb];
     }
   }
 };
@@ -679,21 +684,18 @@ fwd_bf16_kernel(const FwdParams p) {
   const int g = (bh / p.H) % p.G;
   const int b = bh / (p.H * p.G);
   const int hk = h / (p.H / p.Hkv);
+  const int stream = C::DIFF ? wave / C::NROWG : 0;   // softmax stream of this wave (uniform)
   const int i0 = qt * C::BM;                       // first query row of the workgroup
-  const int iw = i0 + wave * C::WROWS;             // first query row of the wave
+  const int iw = i0 + (wave % C::NROWG) * C::WROWS;   // first query row of the wave
   w.b = b; w.g = g; w.h = h;
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
     w.i[rb] = iw + 32 * rb + w.col;
     w.ic[rb] = w.i[rb] < p.Sq ? w.i[rb] : p.Sq - 1;
-    const uint16_t* qp = (const uint16_t*)p.q.ptr + b * p.q.sb + g * p.q.sg + h * p.q.sh + (int64_t)w.ic[rb] * p.q.ss;
+    const View& qv = stream == 0 ? p.q : p.q2;     // the wave's own stream
+    const uint16_t* qp = (const uint16_t*)qv.ptr + b * qv.sb + g * qv.sg + h * qv.sh + (int64_t)w.ic[rb] * qv.ss;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) w.qf[0][rb][kk] = *(const bf16x8*)(qp + 16 * kk + 8 * w.half);
-    if constexpr (C::DIFF) {
-      const uint16_t* q2 = (const uint16_t*)p.q2.ptr + b * p.q2.sb + g * p.q2.sg + h * p.q2.sh + (int64_t)w.ic[rb] * p.q2.ss;
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) w.qf[NS - 1][rb][kk] = *(const bf16x8*)(q2 + 16 * kk + 8 * w.half);
-    }
     w.qdoc[rb] = 0;
     if constexpr ((MASK & kMaskDoc) != 0) w.qdoc[rb] = p.q_doc[(int64_t)b * p.Sq + w.ic[rb]];
 #pragma unroll
@@ -714,21 +716,20 @@ fwd_bf16_kernel(const FwdParams p) {
   w.bstage = p.bias_lds_base + wave * (C::NBIAS * 2 * W::BSTAGE);
   w.lds = lds_raw;
 #pragma unroll
-  for (int s = 0; s < NS; ++s)
+  for (int rb = 0; rb < RB; ++rb) {
+    w.m_run[0][rb] = -INFINITY;
+    w.l_run[0][rb] = 0.f;
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      w.m_run[s][rb] = -INFINITY;
-      w.l_run[s][rb] = 0.f;
-#pragma unroll
-      for (int d = 0; d < DVB; ++d) w.oacc[s][rb][d] = W::zero16();
-    }
+    for (int d = 0; d < DVB; ++d) w.oacc[0][rb][d] = W::zero16();
+  }
   w.c_scale = p.scale * kLog2e;                    // raw score -> log2 domain
   w.slope_l2 = 0.f;
   if constexpr (C::MOD == kModAlibi) w.slope_l2 = p.alibi_slopes[h] * kLog2e;
 
   // ---- loop-invariant per-lane LDS offsets
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) w.ka[kk] = w.col * (D * 2) + swz_k<D>(w.col, 2 * kk + w.half) * 16;
+  for (int kk = 0; kk < KK; ++kk)                  // K ring slot layout: [stream][tile]; a wave reads its stream's tile
+    w.ka[kk] = stream * C::K_BYTES + w.col * (D * 2) + swz_k<D>(w.col, 2 * kk + w.half) * 16;
   {
     const int s16 = lane & 15;
     const int key0 = 4 * w.half + (s16 >> 2);      // row this lane addresses in the transposing read
@@ -896,10 +897,8 @@ fwd_bf16_kernel(const FwdParams p) {
 
   {
     // ============ pipelined loop (see the header comment) ============
-    // The loop runs over work items: one item per key tile, or, for the differential variant, two
-    // per tile (stream 0, then stream 1, sharing the tile's V).  Inside the workgroup's tile list
-    // every wave processes every tile; a tile that a wave does not need is simply fully masked
-    // for it (its probabilities are exactly 0).
+    // Inside the workgroup's tile list every wave processes every tile; a tile that a wave does
+    // not need is simply fully masked for it (its probabilities are exactly 0).
     typename W::Scores sa, sb;                     // the two score tiles in flight
     typename W::Pipe ps;
     typename W::BiasRegs br;
@@ -923,7 +922,7 @@ fwd_bf16_kernel(const FwdParams p) {
         w.rowmax(sa, mx);
         w.advance_max(0, mx);
       }
-      if constexpr (NS == 1) __syncthreads();      // everyone is done with K ring slot 0
+      __syncthreads();                             // everyone is done with K ring slot 0
       // uniform state of the tile stream: the ragged tile (if any) and the bases of the next K and
       // V tile to fetch, i.e. of tiles min(t2, t_hi - 1) and min(t1, t_hi - 1)
       const int t_rag = p.Sk % BN != 0 ? p.Sk / BN : -1;
@@ -932,30 +931,24 @@ fwd_bf16_kernel(const FwdParams p) {
 #pragma unroll
       for (int s = 0; s < NS; ++s) kb[s] = k_tile_base(s, t2 < t_hi ? t2 : t_hi - 1);
       const unsigned char* vb = v_tile_base(t1 < t_hi ? t1 : t_hi - 1);
-      // One pipeline step.  cur / nxt hold the scores of the current / next item.  Step number N
-      // (mod 4) fixes the roles at compile time.  One stream: K and V of the current tile sit in
-      // ring slot N % 2, K of the next tile in the other one; the step streams K(t2) into the slot
-      // K(t0) left in the previous step and V(t1) into the slot V(t-1) left.  Two streams: the
-      // tile's slot is (N / 2) % 2; the even step (stream 0) streams V(t1) in, the odd step
-      // (stream 1) both K tiles of t2, into the slot whose last reader was the even step.  These
-      // slots are free for the whole step, so the load instructions are spread over phase A (a
-      // burst of them right after the barrier stalls every wave of the workgroup in the memory
-      // pipeline while the matrix cores idle).  Past the end of the tile list the loads simply
-      // repeat the last tile, and the last item takes the same step: its "next item" contraction
-      // then runs on stale LDS contents and is never used.
+      // One pipeline step.  cur / nxt hold the scores of the current / next tile.  Step number N
+      // (mod 4) fixes the roles at compile time: K and V of the current tile sit in ring slot
+      // N % 2, K of the next tile in the other one; the step streams K(t2) (both streams' tiles
+      // for the differential variant) into the slot K(t0) left in the previous step and V(t1)
+      // into the slot V(t-1) left.  These slots are free for the whole step, so the load
+      // instructions are spread over phase A (a burst of them right after the barrier stalls
+      // every wave of the workgroup in the memory pipeline while the matrix cores idle).  Past the
+      // end of the tile list the loads simply repeat the last tile, and the last tile takes the
+      // same step: its "next tile" contraction then runs on stale LDS contents and is never used.
       auto step = [&](auto nc, typename W::Scores& cur, typename W::Scores& nxt) __attribute__((always_inline)) {
         constexpr int N = decltype(nc)::value;
-        constexpr int SC = NS == 2 ? N % 2 : 0, SN = NS == 2 ? (N + 1) % 2 : 0;      // streams of cur / nxt
-        constexpr int slot_c = NS == 2 ? (N / 2) % 2 : N % 2;                         // ring slot of cur's tile
-        constexpr int slot_n = NS == 2 ? ((N + 1) / 2) % 2 : (N + 1) % 2;             // ... of nxt's tile
-        constexpr bool same_tile = NS == 2 && N % 2 == 0;                             // nxt is stream 1 of cur's tile
-        constexpr bool load_ks = NS == 1 || N % 2 == 1, load_vs = NS == 1 || N % 2 == 0;
-        const int tn = same_tile ? t0 : t1;
-        const bool fulln = same_tile ? full0 : wave_full(t1);
+        constexpr int slot_c = N % 2, slot_n = (N + 1) % 2;   // ring slots of the current / next tile
+        const int tn = t1;
+        const bool fulln = wave_full(t1);
         if (!full0) {                              // fully visible tiles were settled in phase B
           w.mask(cur, t0 * BN);
           w.rowmax(cur, mx);
-          w.advance_max(SC, mx);
+          w.advance_max(0, mx);
         }
         if constexpr (C::NBIAS > 0) {
           // bias of the next tile: staged one step ago into buffer (N + 1) % 2 (its values are
@@ -970,12 +963,12 @@ fwd_bf16_kernel(const FwdParams p) {
           for (int s = 0; s < NS; ++s) kb[s] = k_tile_base(s, tk);
           vb = v_tile_base(tv);
         }
-        if (load_ks && __builtin_expect(tk == t_rag, 0)) clamp_k(tk);
-        if (load_vs && __builtin_expect(tv == t_rag, 0)) clamp_v(tv);
-        w.template phase_a<C::K_RING + (slot_n * NS + SN) * C::K_BYTES, SC, SN>(
+        if (__builtin_expect(tk == t_rag, 0)) clamp_k(tk);
+        if (__builtin_expect(tv == t_rag, 0)) clamp_v(tv);
+        w.template phase_a<C::K_RING + slot_n * NS * C::K_BYTES>(
             nxt, cur, ps, tn * BN, br, w.ka, [&](auto fc) __attribute__((always_inline)) {
               constexpr int f = decltype(fc)::value, NF = NB * KK;
-              constexpr int NK = load_ks ? NS * KPW : 0, NV = load_vs ? VPW : 0, LN = NK + NV;
+              constexpr int NK = NS * KPW, NV = VPW, LN = NK + NV;
               static_for<0, NK>([&](auto ic) __attribute__((always_inline)) {
                 constexpr int i = decltype(ic)::value, ss = i / KPW, u = i % KPW;
                 if constexpr (f == ((2 * i + 1) * NF) / (2 * LN))
@@ -984,22 +977,20 @@ fwd_bf16_kernel(const FwdParams p) {
               static_for<0, NV>([&](auto uc) __attribute__((always_inline)) {
                 constexpr int u = decltype(uc)::value;
                 if constexpr (f == ((2 * (NK + u) + 1) * NF) / (2 * LN))
-                  issue_v(u, vb, C::V_RING + (NS == 2 ? 1 - slot_c : slot_n) * C::V_BYTES);
+                  issue_v(u, vb, C::V_RING + slot_n * C::V_BYTES);
               });
             });
-        w.template phase_b<C::V_RING + slot_c * C::V_BYTES, SC, SN>(ps, cur, nxt, tn * BN, br, w.va, fulln);
+        w.template phase_b<C::V_RING + slot_c * C::V_BYTES>(ps, cur, nxt, tn * BN, br, w.va, fulln);
         wait_loads_and_sync();
-        if constexpr (!same_tile) {                // the tile is done: move on in the tile list
-          t0 = t1;
-          t1 = t2;
-          t2 = t2 < t_hi ? next_tile(t2 + 1) : t_hi;
-          full0 = fulln;
-          if constexpr ((MASK & kMaskDoc) == 0) {  // consecutive tiles: advance the bases until the list ends
-            if (t1 < t_hi) vb += vstep;
+        t0 = t1;
+        t1 = t2;
+        t2 = t2 < t_hi ? next_tile(t2 + 1) : t_hi;
+        full0 = fulln;
+        if constexpr ((MASK & kMaskDoc) == 0) {    // consecutive tiles: advance the bases until the list ends
+          if (t1 < t_hi) vb += vstep;
 #pragma unroll
-            for (int s = 0; s < NS; ++s)
-              if (t2 < t_hi) kb[s] += kstep[s];
-          }
+          for (int s = 0; s < NS; ++s)
+            if (t2 < t_hi) kb[s] += kstep[s];
         }
       };
       while (true) {
@@ -1021,30 +1012,52 @@ fwd_bf16_kernel(const FwdParams p) {
   const float lam = C::DIFF ? p.lambda[h] : 0.f;
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
-    float inv[NS], lse_v[NS];
+    const float lt = half_swap_sum(w.l_run[0][rb]);
+    const float inv = lt > 0.f ? 1.f / lt : 0.f;
+    const float lse_v = lt > 0.f ? w.m_run[0][rb] * kLn2 + __logf(lt) : -INFINITY;
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
-      const float lt = half_swap_sum(w.l_run[s][rb]);
-      inv[s] = lt > 0.f ? 1.f / lt : 0.f;
-      lse_v[s] = lt > 0.f ? w.m_run[s][rb] * kLn2 + __logf(lt) : -INFINITY;
+    for (int d = 0; d < DVB; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) w.oacc[0][rb][d][r] *= inv;
+    if constexpr (C::DIFF) {
+      // The wave of stream 1 hands its normalised rows to the wave of stream 0 that owns the same
+      // query rows (same lane, same registers) through LDS: the K/V rings are free by now (every
+      // wave has passed the barrier of the last step).  Layout [row group][register quad][lane][4].
+      float4* xch = (float4*)lds_raw + (wave % C::NROWG) * (DVB * 4 * 64) + lane;
+      if (stream == 1) {
+#pragma unroll
+        for (int d = 0; d < DVB; ++d)
+#pragma unroll
+          for (int r4 = 0; r4 < 4; ++r4)
+            xch[(d * 4 + r4) * 64] = make_float4(w.oacc[0][rb][d][4 * r4], w.oacc[0][rb][d][4 * r4 + 1],
+                                                 w.oacc[0][rb][d][4 * r4 + 2], w.oacc[0][rb][d][4 * r4 + 3]);
+      }
+      __syncthreads();
+      if (stream == 0) {
+#pragma unroll
+        for (int d = 0; d < DVB; ++d)
+#pragma unroll
+          for (int r4 = 0; r4 < 4; ++r4) {
+            const float4 o2 = xch[(d * 4 + r4) * 64];
+            w.oacc[0][rb][d][4 * r4] -= lam * o2.x;
+            w.oacc[0][rb][d][4 * r4 + 1] -= lam * o2.y;
+            w.oacc[0][rb][d][4 * r4 + 2] -= lam * o2.z;
+            w.oacc[0][rb][d][4 * r4 + 3] -= lam * o2.w;
+          }
+      }
     }
     float ssq = 0.f;
 #pragma unroll
     for (int d = 0; d < DVB; ++d)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float x = w.oacc[0][rb][d][r] * inv[0];
-        if constexpr (C::DIFF) x -= lam * (w.oacc[NS - 1][rb][d][r] * inv[NS - 1]);
-        w.oacc[0][rb][d][r] = x;
-        ssq = fmaf(x, x, ssq);
-      }
+      for (int r = 0; r < 16; ++r) ssq = fmaf(w.oacc[0][rb][d][r], w.oacc[0][rb][d][r], ssq);
     float rn = 1.f;
     if constexpr ((C::EPI & kEpiRms) != 0) {
       ssq = half_swap_sum(ssq);
       rn = 1.f / sqrtf(ssq * (1.f / DV) + p.rms_eps);
     }
     const int i = w.i[rb];
-    if (i < p.Sq) {
+    if (i < p.Sq && stream == 0) {
       const int64_t orow = b * p.out.sb + g * p.out.sg + h * p.out.sh + (int64_t)i * p.out.ss;
       const int64_t grow = b * p.gate.sb + g * p.gate.sg + h * p.gate.sh + (int64_t)i * p.gate.ss;
 #pragma unroll
@@ -1074,12 +1087,9 @@ fwd_bf16_kernel(const FwdParams p) {
             *(uint2*)((uint16_t*)p.out.ptr + orow + ch) = make_uint2(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]));
           }
         }
-      if (p.lse != nullptr && w.half == 0) {
-#pragma unroll
-        for (int s = 0; s < NS; ++s)
-          p.lse[b * p.lse_sb + (int64_t)(C::DIFF ? 2 * g + s : g) * p.lse_sg + h * p.lse_sh + i] = lse_v[s];
-      }
     }
+    if (i < p.Sq && p.lse != nullptr && w.half == 0)    // every wave writes the lse of its own stream
+      p.lse[b * p.lse_sb + (int64_t)(C::DIFF ? 2 * g + stream : g) * p.lse_sg + h * p.lse_sh + i] = lse_v;
   }
   }  // pass
 }
