@@ -170,6 +170,7 @@ struct Wave {
   int i[C::RB], ic[C::RB];      // this lane's query rows (unclamped / clamped), one per row block
   int qdoc[C::RB];
   float c_scale, slope_l2;
+  float alibi_c[16];            // ALiBi, uniform: slope * key offset of score register r inside its 32-key block
   uint32_t ka[C::KK];           // per-lane byte offset of the K fragment of k-step kk (block 0)
   uint32_t va[C::DVB];          // per-lane byte offset of the V^T fragment of channel block d (key block 0)
   bf16x8 qf[1][C::RB][C::KK];   // (first index: softmax stream of the wave, always 0: one stream per wave)
@@ -286,10 +287,16 @@ struct Wave {
         const float e = fast_exp2(x * (2.f * c_scale / p.softcap));
         const float cl = p.softcap * kLog2e;
         x = fmaf(fast_rcp(e + 1.f), -2.f * cl, cl);
+      } else if constexpr (C::MOD == kModAlibi) {
+        // slope * |i - j| with j = (j0 + 32*nb + 4*half) + c, c the register's compile-time key
+        // offset: one per-lane term per key block minus a uniform constant per register, then one FMA
+        // (all the integers involved are far below 2^24, so the float arithmetic is exact up
+        // to the final rounding of the products)
+        const float d = slope_l2 * (float)(i[rb] - j0 - 32 * nb - 4 * half);
+        x = fmaf(x, c_scale, -fabsf(d - alibi_c[r]));
       } else {
         x *= c_scale;
       }
-      if constexpr (C::MOD == kModAlibi) x -= slope_l2 * fabsf((float)(i[rb] - j));
 #pragma unroll
       for (int nbias = 0; nbias < C::NBIAS; ++nbias) {
         const uint2 q4 = br.v[nbias][rb][nb][r >> 2];
@@ -724,7 +731,14 @@ fwd_bf16_kernel(const FwdParams p) {
   }
   w.c_scale = p.scale * kLog2e;                    // raw score -> log2 domain
   w.slope_l2 = 0.f;
-  if constexpr (C::MOD == kModAlibi) w.slope_l2 = p.alibi_slopes[h] * kLog2e;
+  if constexpr (C::MOD == kModAlibi) {
+    w.slope_l2 = p.alibi_slopes[h] * kLog2e;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int c = 8 * (e >> 2) + (e & 3);
+      w.alibi_c[e] = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(w.slope_l2 * (float)c)));
+    }
+  }
 
   // ---- loop-invariant per-lane LDS offsets
 #pragma unroll
