@@ -382,11 +382,14 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
     // dynamic LDS: the K/V rings, then two staging buffers per wave and bias for the bias tiles
     // that are read through LDS
     const int64_t kv = ke->lds_bytes;
-    const int64_t stage = (int64_t)ke->key.nwaves * ke->key.nbias * 2 * (32 * ke->key.rb * ke->key.bn * 2);
-    const bool any_dma = (ke->key.nbias > 0 && p.bias[0].dma) || (ke->key.nbias > 1 && p.bias[1].dma);
-    const bool staged = any_dma && kv + stage <= fl::kMaxLdsBytes;
+    for (int nb = ke->key.nbias; nb < 2; ++nb) p.bias[nb].dma = 0;
+    const int n_stage = p.bias[1].dma ? 2 : (p.bias[0].dma ? 1 : 0);       // biases 0 .. n_stage-1 get buffers
+    const int64_t per_wave = (int64_t)n_stage * 2 * (32 * ke->key.rb * ke->key.bn * 2);
+    const int64_t stage = ke->key.nwaves * per_wave;
+    const bool staged = n_stage > 0 && kv + stage <= fl::kMaxLdsBytes;
     if (!staged) p.bias[0].dma = p.bias[1].dma = 0;
     p.bias_lds_base = (int)kv;
+    p.bias_lds_wave = staged ? (int)per_wave : 0;
     p.lds_bytes = (int)(kv + (staged ? stage : 0));
   }
   const int64_t nbh = B * G * H;

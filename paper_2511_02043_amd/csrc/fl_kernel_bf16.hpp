@@ -717,10 +717,10 @@ fwd_bf16_kernel(const FwdParams p) {
         w.bsrc[nbias][rb][u] = bhead + (int64_t)ir * bv.si + (((uint32_t)(lane % W::BCH) ^ W::bias_swz(r)) << 3);
       }
     }
-    w.brd[rb] = p.bias_lds_base + wave * (C::NBIAS * 2 * W::BSTAGE) + rb * (32 * W::BROW_BYTES) + w.col * W::BROW_BYTES + w.half * 8;
+    w.brd[rb] = p.bias_lds_base + wave * p.bias_lds_wave + rb * (32 * W::BROW_BYTES) + w.col * W::BROW_BYTES + w.half * 8;
   }
   w.bsw = W::bias_swz(w.col);
-  w.bstage = p.bias_lds_base + wave * (C::NBIAS * 2 * W::BSTAGE);
+  w.bstage = p.bias_lds_base + wave * p.bias_lds_wave;
   w.lds = lds_raw;
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {

@@ -55,6 +55,7 @@ struct FwdParams {
   int32_t doc_vec;       // 1: kv_doc rows are 16-byte aligned and Sk % 4 == 0 -> 4 ids per load
   int32_t lds_bytes;     // bf16 kernels: dynamic LDS size of this launch (K/V rings, then bias staging)
   int32_t bias_lds_base; // byte offset of the per-wave bias staging buffers in LDS
+  int32_t bias_lds_wave; // bytes of staging per wave (two buffers for every bias up to the last staged one)
   int32_t pair;          // bf16 kernels: 1 = a workgroup takes q-tiles nq - 1 - i and i (balanced causal work)
 };
 
