@@ -22,10 +22,9 @@
 //   * V^T as the A operand comes from row-major V in LDS through ds_read_b64_tr_b16.
 // Within one 16-key MFMA step the contraction index order is (half, element) -> key
 // 16*ks + 8*(e/4) + 4*half + e%4 for both operands.
-// Every K or V fragment read from LDS feeds the MFMAs of all RB row blocks of the wave: with
-// RB = 2 the LDS traffic per FLOP halves, which is what the LDS bandwidth of a CU needs to keep
-// the matrix cores busy at D = 128 (measured: with RB = 1 the LDS reads alone took 60% of the
-// kernel time).
+// Every K or V fragment read from LDS feeds the MFMAs of all RB row blocks of the wave (RB = 2
+// halves the LDS traffic per FLOP but needs a whole SIMD's registers for one wave; RB = 1 with two
+// waves per SIMD measured faster and is the default).
 //
 // Software pipeline.  Iteration n owns tile t0 (scores in registers,
 // transformed, row max folded into m) and its successor t1:
@@ -53,8 +52,6 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(2))) int i32x2;
 typedef __attribute__((address_space(3))) void lds_void;
@@ -173,9 +170,9 @@ struct Wave {
   float alibi_c[16];            // ALiBi, uniform: slope * key offset of score register r inside its 32-key block
   uint32_t ka[C::KK];           // per-lane byte offset of the K fragment of k-step kk (block 0)
   uint32_t va[C::DVB];          // per-lane byte offset of the V^T fragment of channel block d (key block 0)
-  bf16x8 qf[1][C::RB][C::KK];   // (first index: softmax stream of the wave, always 0: one stream per wave)
-  f32x16 oacc[1][C::RB][C::DVB];
-  float m_run[1][C::RB], l_run[1][C::RB];          // log2-domain running max; per-lane partial sum
+  bf16x8 qf[C::RB][C::KK];      // Q fragments of the wave's rows (of its own stream, differential variant)
+  f32x16 oacc[C::RB][C::DVB];
+  float m_run[C::RB], l_run[C::RB];                // log2-domain running max; per-lane partial sum
 
   __device__ __forceinline__ Wave(const FwdParams& p_) : p(p_) {}
 
@@ -223,7 +220,7 @@ struct Wave {
   // kind, so the loop is built to need few of them: fragments are read from LDS one group ahead
   // and one wait covers a whole group.  body(f, fragment) is called in fragment order.
   template <int KOFF, class Body>
-  __device__ __forceinline__ void k_stream(const uint32_t (&ka)[C::KK], Body&& body) const {
+  __device__ __forceinline__ void k_stream(Body&& body) const {
     constexpr int NF = NB * KK, G = C::GK < NF ? C::GK : NF, NG = NF / G;   // fragments (nb, kk)
     static_assert(NF % G == 0, "K fragment groups");
     i32x4 kf[NF];
@@ -239,7 +236,7 @@ struct Wave {
     });
   }
   template <int VOFF, class Body>
-  __device__ __forceinline__ void v_stream(const uint32_t (&va)[C::DVB], Body&& body) const {
+  __device__ __forceinline__ void v_stream(Body&& body) const {
     constexpr int NF = NB * 2 * DVB, G = C::GV < NF ? C::GV : NF, NG = NF / G;   // fragments (nb, ks, d)
     static_assert(NF % G == 0, "V fragment groups");
     i32x2 lo[NF], hi[NF];
@@ -259,16 +256,16 @@ struct Wave {
     });
   }
 
-  // ---- first contraction of stream s: S^T = K Q^T for all row blocks, K tile at LDS offset KOFF
+  // ---- first contraction: S^T = K Q^T for all row blocks, K tile at LDS offset KOFF
   template <int KOFF>
-  __device__ __forceinline__ void qk(Scores& sc, int s, const uint32_t (&ka)[C::KK]) const {
+  __device__ __forceinline__ void qk(Scores& sc) const {
     f32x16 acc[RB];
-    k_stream<KOFF>(ka, [&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+    k_stream<KOFF>([&](auto fc, bf16x8 a) __attribute__((always_inline)) {
       constexpr int f = fc, kk = f % KK, nb = f / KK;
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
         if (kk == 0) acc[rb] = zero16();
-        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s][rb][kk], acc[rb], 0, 0, 0);
+        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[rb][kk], acc[rb], 0, 0, 0);
         if (kk == KK - 1) sc[rb][nb] = acc[rb];
       }
     });
@@ -446,20 +443,20 @@ struct Wave {
     }
   }
 
-  // ---- running-max update of stream s with the next tile's row maxima (Alg. 2 / Sec. 3.4) and
+  // ---- running-max update with the next tile's row maxima (Alg. 2 / Sec. 3.4) and
   // the rescale of l and O that goes with it.  The max of a row only advances when it grows by
   // more than 2^kLazyMaxLog2, so the O rescale is a rare, wave-uniform branch.
-  __device__ __forceinline__ void advance_max(int s, const float (&mx)[C::RB]) {
+  __device__ __forceinline__ void advance_max(const float (&mx)[C::RB]) {
     float alpha[RB];
     bool any = false;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      const float m_old = m_run[s][rb];
+      const float m_old = m_run[rb];
       const float m_new = (mx[rb] - m_old > kLazyMaxLog2) ? mx[rb] : m_old;   // false for NaN (-inf - -inf)
       const bool moved = m_new != m_old;
       alpha[rb] = moved ? fast_exp2(m_old - (m_new == -INFINITY ? 0.f : m_new)) : 1.f;
-      m_run[s][rb] = m_new;
-      l_run[s][rb] *= alpha[rb];
+      m_run[rb] = m_new;
+      l_run[rb] *= alpha[rb];
       any = any || moved;
     }
     if (__builtin_amdgcn_ballot_w64(any) != 0) {
@@ -468,7 +465,7 @@ struct Wave {
 #pragma unroll
         for (int d = 0; d < DVB; ++d)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[s][rb][d][r] *= alpha[rb];
+          for (int r = 0; r < 16; ++r) oacc[rb][d][r] *= alpha[rb];
     }
   }
 
@@ -544,24 +541,24 @@ struct Wave {
   // hook(f) runs after the work of fragment f: the caller's tile loads.
   template <int KOFF, class Hook>
   __device__ __forceinline__ void phase_a(Scores& nxt, const Scores& cur, Pipe& ps, int j1, const BiasRegs& br,
-                                          const uint32_t (&ka)[C::KK], Hook&& hook) {
+                                          Hook&& hook) {
     constexpr int NF = NB * KK;
     constexpr int SE = (NB == 2 ? KK : NF) * RB;   // slots (fragment, row block) that carry exponentials
     constexpr int PA = NPAIR / 2;                  // pairs of the first half
     constexpr int SM = NF * RB - SE;               // slots that carry the max of key block 0 (NB == 2)
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      ps.m_safe[rb] = m_run[0][rb] == -INFINITY ? 0.f : m_run[0][rb];
+      ps.m_safe[rb] = m_run[rb] == -INFINITY ? 0.f : m_run[rb];
       ps.psum[rb] = 0.f;
       ps.mx[rb] = -INFINITY;
     }
     f32x16 acc[RB];
-    k_stream<KOFF>(ka, [&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+    k_stream<KOFF>([&](auto fc, bf16x8 a) __attribute__((always_inline)) {
       constexpr int f = fc, kk = f % KK, nb = f / KK;
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
         if (kk == 0) acc[rb] = zero16();
-        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][rb][kk], acc[rb], 0, 0, 0);
+        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[rb][kk], acc[rb], 0, 0, 0);
         if (kk == KK - 1) nxt[rb][nb] = acc[rb];
         const int slot = f * RB + rb;
         if (slot < SE) {
@@ -587,11 +584,11 @@ struct Wave {
   // update is left to the start of the next step.  The O rescale is a rare branch at the end.
   template <int VOFF>
   __device__ __forceinline__ void phase_b(Pipe& ps, const Scores& cur, Scores& nxt, int j1, const BiasRegs& br,
-                                          const uint32_t (&va)[C::DVB], bool advance) {
+                                          bool advance) {
     constexpr int NF = NB * 2 * DVB, HALF = NF / 2;
     constexpr int SE = HALF * RB, SM = NF * RB - SE, PA = NPAIR / 2;
     static_assert(NF % 2 == 0, "chunking");
-    v_stream<VOFF>(va, [&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+    v_stream<VOFF>([&](auto fc, bf16x8 a) __attribute__((always_inline)) {
       constexpr int f = fc, d = f % DVB, ks = (f / DVB) % 2, nb = f / (2 * DVB);
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
@@ -599,11 +596,11 @@ struct Wave {
         if (slot == SE) finish_pair(ps, NPAIR - 1);
         const bf16x8 pb = __builtin_bit_cast(bf16x8, (i32x4){(int)ps.w[rb][nb][4 * ks], (int)ps.w[rb][nb][4 * ks + 1],
                                                              (int)ps.w[rb][nb][4 * ks + 2], (int)ps.w[rb][nb][4 * ks + 3]});
-        oacc[0][rb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[0][rb][d], 0, 0, 0);
+        oacc[rb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, oacc[rb][d], 0, 0, 0);
         if constexpr (C::PSPLIT) {
           const bf16x8 pl = __builtin_bit_cast(bf16x8, (i32x4){(int)ps.wl[nb][4 * ks], (int)ps.wl[nb][4 * ks + 1],
                                                                (int)ps.wl[nb][4 * ks + 2], (int)ps.wl[nb][4 * ks + 3]});
-          oacc[0][rb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pl, oacc[0][rb][d], 0, 0, 0);
+          oacc[rb][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pl, oacc[rb][d], 0, 0, 0);
         }
         if (slot < SE) {
 #pragma unroll
@@ -621,16 +618,16 @@ struct Wave {
     bool any = false;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-      l_run[0][rb] += ps.psum[rb];
+      l_run[rb] += ps.psum[rb];
       float mxs = half_swap_max(ps.mx[rb]);
       if constexpr (kPlain) mxs *= c_scale;        // scale > 0 (checked on the host)
-      const float m_old = m_run[0][rb];
+      const float m_old = m_run[rb];
       float m_new = (mxs - m_old > kLazyMaxLog2) ? mxs : m_old;   // false for NaN (-inf - -inf)
       m_new = advance ? m_new : m_old;
       const bool moved = m_new != m_old;
       alpha[rb] = moved ? fast_exp2(m_old - (m_new == -INFINITY ? 0.f : m_new)) : 1.f;
-      m_run[0][rb] = m_new;
-      l_run[0][rb] *= alpha[rb];
+      m_run[rb] = m_new;
+      l_run[rb] *= alpha[rb];
       any = any || moved;
     }
     if (__builtin_amdgcn_ballot_w64(any) != 0) {   // rare and wave-uniform
@@ -639,7 +636,7 @@ struct Wave {
 #pragma unroll
         for (int d = 0; d < DVB; ++d)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[0][rb][d][r] *= alpha[rb];
+          for (int r = 0; r < 16; ++r) oacc[rb][d][r] *= alpha[rb];
     }
   }
 };
@@ -702,7 +699,7 @@ fwd_bf16_kernel(const FwdParams p) {
     const View& qv = stream == 0 ? p.q : p.q2;     // the wave's own stream
     const uint16_t* qp = (const uint16_t*)qv.ptr + b * qv.sb + g * qv.sg + h * qv.sh + (int64_t)w.ic[rb] * qv.ss;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) w.qf[0][rb][kk] = *(const bf16x8*)(qp + 16 * kk + 8 * w.half);
+    for (int kk = 0; kk < KK; ++kk) w.qf[rb][kk] = *(const bf16x8*)(qp + 16 * kk + 8 * w.half);
     w.qdoc[rb] = 0;
     if constexpr ((MASK & kMaskDoc) != 0) w.qdoc[rb] = p.q_doc[(int64_t)b * p.Sq + w.ic[rb]];
 #pragma unroll
@@ -724,10 +721,10 @@ fwd_bf16_kernel(const FwdParams p) {
   w.lds = lds_raw;
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
-    w.m_run[0][rb] = -INFINITY;
-    w.l_run[0][rb] = 0.f;
+    w.m_run[rb] = -INFINITY;
+    w.l_run[rb] = 0.f;
 #pragma unroll
-    for (int d = 0; d < DVB; ++d) w.oacc[0][rb][d] = W::zero16();
+    for (int d = 0; d < DVB; ++d) w.oacc[rb][d] = W::zero16();
   }
   w.c_scale = p.scale * kLog2e;                    // raw score -> log2 domain
   w.slope_l2 = 0.f;
@@ -927,14 +924,14 @@ fwd_bf16_kernel(const FwdParams p) {
       if (t1 < t_hi) load_k(t1, 1);
       wait_loads_and_sync();
       w.template load_bias<0>(br, t0 * BN);
-      w.template qk<C::K_RING>(sa, 0, w.ka);
+      w.template qk<C::K_RING>(sa);
       if constexpr (C::NBIAS > 0) W::template wait_lds<0>();     // staged bias values have arrived
       w.transform(sa, t0 * BN, br);
       float mx[RB];
       bool full0 = wave_full(t0);
       if (full0) {
         w.rowmax(sa, mx);
-        w.advance_max(0, mx);
+        w.advance_max(mx);
       }
       __syncthreads();                             // everyone is done with K ring slot 0
       // uniform state of the tile stream: the ragged tile (if any) and the bases of the next K and
@@ -962,7 +959,7 @@ fwd_bf16_kernel(const FwdParams p) {
         if (!full0) {                              // fully visible tiles were settled in phase B
           w.mask(cur, t0 * BN);
           w.rowmax(cur, mx);
-          w.advance_max(0, mx);
+          w.advance_max(mx);
         }
         if constexpr (C::NBIAS > 0) {
           // bias of the next tile: staged one step ago into buffer (N + 1) % 2 (its values are
@@ -980,7 +977,7 @@ fwd_bf16_kernel(const FwdParams p) {
         if (__builtin_expect(tk == t_rag, 0)) clamp_k(tk);
         if (__builtin_expect(tv == t_rag, 0)) clamp_v(tv);
         w.template phase_a<C::K_RING + slot_n * NS * C::K_BYTES>(
-            nxt, cur, ps, tn * BN, br, w.ka, [&](auto fc) __attribute__((always_inline)) {
+            nxt, cur, ps, tn * BN, br, [&](auto fc) __attribute__((always_inline)) {
               constexpr int f = decltype(fc)::value, NF = NB * KK;
               constexpr int NK = NS * KPW, NV = VPW, LN = NK + NV;
               static_for<0, NK>([&](auto ic) __attribute__((always_inline)) {
@@ -994,7 +991,7 @@ fwd_bf16_kernel(const FwdParams p) {
                   issue_v(u, vb, C::V_RING + slot_n * C::V_BYTES);
               });
             });
-        w.template phase_b<C::V_RING + slot_c * C::V_BYTES>(ps, cur, nxt, tn * BN, br, w.va, fulln);
+        w.template phase_b<C::V_RING + slot_c * C::V_BYTES>(ps, cur, nxt, tn * BN, br, fulln);
         wait_loads_and_sync();
         t0 = t1;
         t1 = t2;
@@ -1026,13 +1023,13 @@ fwd_bf16_kernel(const FwdParams p) {
   const float lam = C::DIFF ? p.lambda[h] : 0.f;
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
-    const float lt = half_swap_sum(w.l_run[0][rb]);
+    const float lt = half_swap_sum(w.l_run[rb]);
     const float inv = lt > 0.f ? 1.f / lt : 0.f;
-    const float lse_v = lt > 0.f ? w.m_run[0][rb] * kLn2 + __logf(lt) : -INFINITY;
+    const float lse_v = lt > 0.f ? w.m_run[rb] * kLn2 + __logf(lt) : -INFINITY;
 #pragma unroll
     for (int d = 0; d < DVB; ++d)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) w.oacc[0][rb][d][r] *= inv;
+      for (int r = 0; r < 16; ++r) w.oacc[rb][d][r] *= inv;
     if constexpr (C::DIFF) {
       // The wave of stream 1 hands its normalised rows to the wave of stream 0 that owns the same
       // query rows (same lane, same registers) through LDS: the K/V rings are free by now (every
@@ -1043,8 +1040,8 @@ fwd_bf16_kernel(const FwdParams p) {
         for (int d = 0; d < DVB; ++d)
 #pragma unroll
           for (int r4 = 0; r4 < 4; ++r4)
-            xch[(d * 4 + r4) * 64] = make_float4(w.oacc[0][rb][d][4 * r4], w.oacc[0][rb][d][4 * r4 + 1],
-                                                 w.oacc[0][rb][d][4 * r4 + 2], w.oacc[0][rb][d][4 * r4 + 3]);
+            xch[(d * 4 + r4) * 64] = make_float4(w.oacc[rb][d][4 * r4], w.oacc[rb][d][4 * r4 + 1],
+                                                 w.oacc[rb][d][4 * r4 + 2], w.oacc[rb][d][4 * r4 + 3]);
       }
       __syncthreads();
       if (stream == 0) {
@@ -1053,10 +1050,10 @@ fwd_bf16_kernel(const FwdParams p) {
 #pragma unroll
           for (int r4 = 0; r4 < 4; ++r4) {
             const float4 o2 = xch[(d * 4 + r4) * 64];
-            w.oacc[0][rb][d][4 * r4] -= lam * o2.x;
-            w.oacc[0][rb][d][4 * r4 + 1] -= lam * o2.y;
-            w.oacc[0][rb][d][4 * r4 + 2] -= lam * o2.z;
-            w.oacc[0][rb][d][4 * r4 + 3] -= lam * o2.w;
+            w.oacc[rb][d][4 * r4] -= lam * o2.x;
+            w.oacc[rb][d][4 * r4 + 1] -= lam * o2.y;
+            w.oacc[rb][d][4 * r4 + 2] -= lam * o2.z;
+            w.oacc[rb][d][4 * r4 + 3] -= lam * o2.w;
           }
       }
     }
@@ -1064,7 +1061,7 @@ fwd_bf16_kernel(const FwdParams p) {
 #pragma unroll
     for (int d = 0; d < DVB; ++d)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) ssq = fmaf(w.oacc[0][rb][d][r], w.oacc[0][rb][d][r], ssq);
+      for (int r = 0; r < 16; ++r) ssq = fmaf(w.oacc[rb][d][r], w.oacc[rb][d][r], ssq);
     float rn = 1.f;
     if constexpr ((C::EPI & kEpiRms) != 0) {
       ssq = half_swap_sum(ssq);
@@ -1081,7 +1078,7 @@ fwd_bf16_kernel(const FwdParams p) {
           const int ch = 32 * d + 8 * r4 + 4 * w.half;   // 4 consecutive channels ch..ch+3
           float x[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) x[e] = w.oacc[0][rb][d][4 * r4 + e];
+          for (int e = 0; e < 4; ++e) x[e] = w.oacc[rb][d][4 * r4 + e];
           if constexpr ((C::EPI & kEpiRms) != 0) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) x[e] *= rn * (p.rms_weight ? p.rms_weight[ch + e] : 1.f);
