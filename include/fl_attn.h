@@ -1,5 +1,6 @@
 /*
- * fl_attn.h -- C ABI of the fused attention-variant forward library for AMD MI355X (gfx950).
+ * fl_attn.h -- C ABI of the fused attention-variant library for AMD MI355X (gfx950): the forward
+ * pass of every variant and the backward pass of the variants without bias, gate and second stream.
  *
  * One call computes, for every (b, g, h) and every query row i, without ever writing the
  * [Sq, Sk] score matrix to device memory:
@@ -143,6 +144,37 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
  * that the paper's own kernels do not skip masked blocks -- this goes beyond it).           */
 size_t fl_attn_fwd_workspace_size(const fl_tensor* q, const fl_tensor* k,
                                   const fl_variant_desc* desc);
+
+/* Gradient of fl_attn_fwd with respect to q, k and v, for the variants without bias, second
+ * stream and epilogue (score_mod and every mask are covered).  The paper's conclusion names
+ * training support as the extension it leaves open; this is the derivative of Eq. 3 with the
+ * score_mod of Eq. 4 and the masks of the attention listing, evaluated like the forward pass
+ * without materialising anything of size [Sq, Sk]: per score tile P = exp(s - lse) is recomputed
+ * from the saved lse, dP = dout V^T, dS = P * (dP - rowsum(dout * out)) (times 1 - tanh^2 under a
+ * soft-cap), and dv = P^T dout, dk = scale * dS^T q, dq = scale * dS k.
+ *
+ *   q, k, v      as given to fl_attn_fwd (bf16; D == Dv in {64, 128})
+ *   out, lse     what fl_attn_fwd wrote for them: out [B, G, H, Sq, Dv] bf16, lse [B, G, H, Sq, 1] f32
+ *   dout         [B, G, H, Sq, Dv] bf16, the gradient arriving at out
+ *   dq           [B, G, H,   Sq, D ] bf16 or f32, written
+ *   dk, dv       [B, G, Hkv, Sk, D ] bf16 or f32 (one dtype for both), written; with grouped
+ *                query heads they hold the sum over the query heads of the group
+ *   aux          required: aux->workspace of fl_attn_bwd_workspace_size bytes, 16-byte aligned
+ *                (row statistics and tile-skipper summaries; contents undefined afterwards),
+ *                plus alibi_slopes / doc ids as for the forward pass
+ *
+ * Rows without a visible key get dq = 0; keys that no row sees get dk = dv = 0.  Results are
+ * bitwise reproducible (no atomics).  Same stream, ownership and error rules as fl_attn_fwd:
+ * on an error code nothing was launched.                                                    */
+fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v, const fl_tensor* out,
+                      const fl_tensor* dout, const fl_tensor* lse, const fl_variant_desc* desc,
+                      const fl_aux* aux, fl_tensor* dq, fl_tensor* dk, fl_tensor* dv, void* stream);
+
+/* Bytes of aux->workspace that fl_attn_bwd needs for these shapes and this descriptor. */
+size_t fl_attn_bwd_workspace_size(const fl_tensor* q, const fl_tensor* k, const fl_variant_desc* desc);
+
+/* 1 if fl_attn_bwd has a kernel specialisation for (descriptor, dtype, D, Dv), else 0. */
+int fl_bwd_supported(const fl_variant_desc* desc, int dtype, int D, int Dv);
 
 /* 1 if a kernel specialisation exists for (descriptor, dtype, D, Dv), else 0. */
 int fl_variant_supported(const fl_variant_desc* desc, int dtype, int D, int Dv);

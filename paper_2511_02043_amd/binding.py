@@ -68,6 +68,13 @@ def lib() -> C.CDLL:
                                   C.c_void_p]
         L.fl_attn_fwd_workspace_size.restype = C.c_size_t
         L.fl_attn_fwd_workspace_size.argtypes = [TP, TP, C.POINTER(fl_variant_desc)]
+        L.fl_attn_bwd.restype = C.c_int
+        L.fl_attn_bwd.argtypes = [TP, TP, TP, TP, TP, TP, C.POINTER(fl_variant_desc), C.POINTER(fl_aux),
+                                  TP, TP, TP, C.c_void_p]
+        L.fl_attn_bwd_workspace_size.restype = C.c_size_t
+        L.fl_attn_bwd_workspace_size.argtypes = [TP, TP, C.POINTER(fl_variant_desc)]
+        L.fl_bwd_supported.restype = C.c_int
+        L.fl_bwd_supported.argtypes = [C.POINTER(fl_variant_desc), C.c_int, C.c_int, C.c_int]
         L.fl_variant_supported.restype = C.c_int
         L.fl_variant_supported.argtypes = [C.POINTER(fl_variant_desc), C.c_int, C.c_int, C.c_int]
         L.fl_strerror.restype = C.c_char_p
@@ -82,7 +89,8 @@ def lib() -> C.CDLL:
     return _lib
 
 
-EXPORTS = ["fl_attn_fwd", "fl_attn_fwd_workspace_size", "fl_variant_supported", "fl_strerror",
+EXPORTS = ["fl_attn_fwd", "fl_attn_fwd_workspace_size", "fl_attn_bwd", "fl_attn_bwd_workspace_size",
+           "fl_bwd_supported", "fl_variant_supported", "fl_strerror",
            "fl_last_error_detail", "fl_set_tuning", "fl_version"]
 
 
@@ -148,6 +156,22 @@ def fl_attn_fwd(q: fl_tensor, k: fl_tensor, v: fl_tensor, desc: fl_variant_desc,
 
 def fl_attn_fwd_workspace_size(q: fl_tensor, k: fl_tensor, desc: fl_variant_desc) -> int:
     return lib().fl_attn_fwd_workspace_size(_ref(q), _ref(k), _ref(desc))
+
+
+def fl_attn_bwd(q: fl_tensor, k: fl_tensor, v: fl_tensor, out: fl_tensor, dout: fl_tensor, lse: fl_tensor,
+                desc: fl_variant_desc, aux: Optional[fl_aux], dq: fl_tensor, dk: fl_tensor, dv: fl_tensor,
+                stream: int = 0) -> int:
+    """Raw call; returns the fl_status code."""
+    return lib().fl_attn_bwd(_ref(q), _ref(k), _ref(v), _ref(out), _ref(dout), _ref(lse), _ref(desc), _ref(aux),
+                             _ref(dq), _ref(dk), _ref(dv), C.c_void_p(stream))
+
+
+def fl_attn_bwd_workspace_size(q: fl_tensor, k: fl_tensor, desc: fl_variant_desc) -> int:
+    return lib().fl_attn_bwd_workspace_size(_ref(q), _ref(k), _ref(desc))
+
+
+def fl_bwd_supported(desc: fl_variant_desc, dtype: int, D: int, Dv: int) -> bool:
+    return bool(lib().fl_bwd_supported(_ref(desc), dtype, D, Dv))
 
 
 def fl_variant_supported(desc: fl_variant_desc, dtype: int, D: int, Dv: int) -> bool:

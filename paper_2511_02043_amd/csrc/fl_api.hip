@@ -8,6 +8,7 @@
 #include <cstring>
 
 #include "../../include/fl_attn.h"
+#include "fl_bwd_registry.hpp"
 #include "fl_registry.hpp"
 
 static_assert(FL_MASK_CAUSAL == fl::kMaskCausal && FL_MASK_WINDOW == fl::kMaskWindow &&
@@ -178,6 +179,38 @@ __global__ void empty_keys_kernel(fl::View out, int out_f32, float* lse, int64_t
   if (lse != nullptr)
     for (int s = 0; s < n_lse_g; ++s)
       lse[b * lse_sb + (int64_t)(g * n_lse_g + s) * lse_sg + h * lse_sh + i] = -INFINITY;
+}
+
+const fl::BwdEntry* find_bwd_entry(const fl_variant_desc* d, int D) {
+  static const fl::BwdEntry* tab[2];
+  static int n[2];
+  static bool init = false;
+  if (!init) {
+    tab[0] = fl::entries_bwd64(&n[0]);
+    tab[1] = fl::entries_bwd128(&n[1]);
+    init = true;
+  }
+  const int mask = (int)canonical_mask(d->mask);
+  for (int t = 0; t < 2; ++t)
+    for (int e = 0; e < n[t]; ++e) {
+      const fl::BwdEntry& k = tab[t][e];
+      if (k.key.D == D && k.key.mod == (int)d->score_mod && k.key.mask == mask) return &k;
+    }
+  return nullptr;
+}
+
+bool bwd_desc_ok(const fl_variant_desc* d) { return d->n_bias == 0 && d->combine == FL_SINGLE && d->epilogue == 0; }
+
+// Workspace of the backward pass: delta, lse2 ([B, G, H, Sq] floats each, 256-byte aligned), then
+// the document-id summaries of the tile skipper.
+struct BwdWorkspace {
+  size_t stat_bytes, total;
+};
+BwdWorkspace bwd_workspace(int64_t B, int64_t G, int64_t H, int64_t Sq, int64_t Sk, uint32_t mask) {
+  BwdWorkspace w;
+  w.stat_bytes = ((size_t)(B * G * H * Sq) * sizeof(float) + 255) / 256 * 256;
+  w.total = 2 * w.stat_bytes + workspace_bytes(B, Sq, Sk, mask);
+  return w;
 }
 
 }  // namespace
@@ -428,6 +461,142 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   }
   hipError_t e = ke->launch(p, (int)nblocks, stream);
   if (e != hipSuccess) return fail(FL_ERR_LAUNCH, "kernel launch: %s", hipGetErrorString(e));
+  return FL_OK;
+}
+
+size_t fl_attn_bwd_workspace_size(const fl_tensor* q, const fl_tensor* k, const fl_variant_desc* desc) {
+  if (q == nullptr || k == nullptr || desc == nullptr) return 0;
+  return bwd_workspace(q->size[0], q->size[1], q->size[2], q->size[3], k->size[3], desc->mask).total;
+}
+
+int fl_bwd_supported(const fl_variant_desc* desc, int dtype, int D, int Dv) {
+  if (check_desc(desc) != FL_OK || dtype != FL_BF16 || D != Dv || !bwd_desc_ok(desc)) return 0;
+  return find_bwd_entry(desc, D) != nullptr ? 1 : 0;
+}
+
+fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v, const fl_tensor* out,
+                      const fl_tensor* dout, const fl_tensor* lse, const fl_variant_desc* desc, const fl_aux* aux,
+                      fl_tensor* dq, fl_tensor* dk, fl_tensor* dv, void* stream_v) {
+  g_detail[0] = 0;
+  fl_status st = check_desc(desc);
+  if (st != FL_OK) return st;
+  if (q == nullptr || k == nullptr || v == nullptr || out == nullptr || dout == nullptr || lse == nullptr ||
+      dq == nullptr || dk == nullptr || dv == nullptr)
+    return fail(FL_ERR_NULL, "a tensor descriptor is NULL");
+  if (aux != nullptr && aux->struct_size != sizeof(fl_aux))
+    return fail(FL_ERR_DESC, "aux->struct_size = %u, expected %zu", aux->struct_size, sizeof(fl_aux));
+  if (!bwd_desc_ok(desc))
+    return fail(FL_ERR_UNSUPPORTED, "the backward pass covers variants without bias, second stream and epilogue");
+  if (q->dtype != FL_BF16) return fail(FL_ERR_DTYPE, "the backward pass takes bf16 inputs (q dtype %d)", q->dtype);
+
+  const int64_t B = q->size[0], G = q->size[1], H = q->size[2], Sq = q->size[3], D = q->size[4];
+  const int64_t Hkv = k->size[2], Sk = k->size[3], Dv = v->size[4];
+  if (B < 0 || G < 0 || H < 0 || Sq < 0 || Sk < 0 || D <= 0 || Dv <= 0) return fail(FL_ERR_SHAPE, "negative size");
+  if (Sq > 0x7fffff00LL || Sk > 0x7fffff00LL || B * G * H > 0x7fffffffLL) return fail(FL_ERR_SHAPE, "size too large");
+  if (Hkv <= 0 || H % (Hkv > 0 ? Hkv : 1) != 0)
+    if (H != 0) return fail(FL_ERR_SHAPE, "k heads (%lld) must divide q heads (%lld)", (long long)Hkv, (long long)H);
+  const uint32_t mask = canonical_mask(desc->mask);
+  const fl::BwdEntry* be = D == Dv ? find_bwd_entry(desc, (int)D) : nullptr;
+  if (be == nullptr)
+    return fail(FL_ERR_UNSUPPORTED, "no backward specialisation for D=%lld Dv=%lld score_mod=%u mask=0x%x", (long long)D,
+                (long long)Dv, desc->score_mod, mask);
+  const bool no_rows = (B == 0 || G == 0 || H == 0 || Sq == 0);       // dq is empty; dk, dv are all zero
+  const bool no_keys = (B == 0 || G == 0 || H == 0 || Sk == 0);       // dk, dv are empty; dq is all zero
+
+  const int64_t qsz[5] = {B, G, H, Sq, D}, ksz[5] = {B, G, Hkv, Sk, D}, osz[5] = {B, G, H, Sq, Dv};
+  if (!no_rows) {
+    if ((st = check_data_tensor(q, "q", FL_BF16, qsz)) != FL_OK) return st;
+    if ((st = check_data_tensor(out, "out", FL_BF16, osz)) != FL_OK) return st;
+    if ((st = check_data_tensor(dout, "dout", FL_BF16, osz)) != FL_OK) return st;
+    if (dq->dtype != FL_BF16 && dq->dtype != FL_F32) return fail(FL_ERR_DTYPE, "dq dtype %d", dq->dtype);
+    if ((st = check_data_tensor(dq, "dq", dq->dtype, qsz)) != FL_OK) return st;
+    if (lse->ptr == nullptr) return fail(FL_ERR_NULL, "lse is NULL");
+    if (lse->dtype != FL_F32) return fail(FL_ERR_DTYPE, "lse must be f32");
+    const int64_t lsz[5] = {B, G, H, Sq, 1};
+    for (int a = 0; a < 5; ++a)
+      if (lse->size[a] != lsz[a])
+        return fail(FL_ERR_SHAPE, "lse size[%d] = %lld, expected %lld", a, (long long)lse->size[a], (long long)lsz[a]);
+    if (Sq > 1 && lse->stride[3] != 1) return fail(FL_ERR_STRIDE, "lse must be contiguous along Sq");
+    for (int a = 0; a < 3; ++a)
+      if (lse->stride[a] < 0) return fail(FL_ERR_STRIDE, "lse stride[%d] negative", a);
+  }
+  if (!no_keys) {
+    if ((st = check_data_tensor(k, "k", FL_BF16, ksz)) != FL_OK) return st;
+    if ((st = check_data_tensor(v, "v", FL_BF16, ksz)) != FL_OK) return st;
+    if (dk->dtype != FL_BF16 && dk->dtype != FL_F32) return fail(FL_ERR_DTYPE, "dk dtype %d", dk->dtype);
+    if (dv->dtype != dk->dtype) return fail(FL_ERR_DTYPE, "dk and dv must share one dtype");
+    if ((st = check_data_tensor(dk, "dk", dk->dtype, ksz)) != FL_OK) return st;
+    if ((st = check_data_tensor(dv, "dv", dv->dtype, ksz)) != FL_OK) return st;
+  }
+  const bool need_aux = desc->score_mod == FL_MOD_ALIBI || (mask & FL_MASK_DOC) || !(no_rows && no_keys);
+  if (need_aux && aux == nullptr) return fail(FL_ERR_AUX_MISSING, "the backward pass needs aux (workspace)");
+  if (desc->score_mod == FL_MOD_ALIBI && aux->alibi_slopes == nullptr) return fail(FL_ERR_AUX_MISSING, "alibi_slopes");
+  if ((mask & FL_MASK_DOC) && (aux->q_doc_ids == nullptr || aux->kv_doc_ids == nullptr))
+    return fail(FL_ERR_AUX_MISSING, "q_doc_ids / kv_doc_ids");
+  if (no_rows && no_keys) return FL_OK;
+  const BwdWorkspace wsz = bwd_workspace(B, G, H, Sq, Sk, mask);
+  if (aux->workspace == nullptr || aux->workspace_bytes < wsz.total)
+    return fail(FL_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", wsz.total, aux->workspace ? aux->workspace_bytes : (size_t)0);
+  if (((uintptr_t)aux->workspace) % 16 != 0) return fail(FL_ERR_ALIGN, "workspace not 16-byte aligned");
+
+  fl::BwdParams p;
+  memset(&p, 0, sizeof(p));
+  if (!no_rows) {
+    p.q = make_view(q);
+    p.o = make_view(out);
+    p.dout = make_view(dout);
+    p.dq = make_view(dq);
+    p.lse = (const float*)lse->ptr;
+    p.lse_sb = lse->size[0] > 1 ? lse->stride[0] : 0;
+    p.lse_sg = lse->size[1] > 1 ? lse->stride[1] : 0;
+    p.lse_sh = lse->size[2] > 1 ? lse->stride[2] : 0;
+  }
+  if (!no_keys) {
+    p.k = make_view(k);
+    p.v = make_view(v);
+    p.dk = make_view(dk);
+    p.dv = make_view(dv);
+  }
+  p.delta = (float*)aux->workspace;
+  p.lse2 = (float*)((unsigned char*)aux->workspace + wsz.stat_bytes);
+  p.alibi_slopes = aux->alibi_slopes;
+  p.q_doc = aux->q_doc_ids;
+  p.kv_doc = aux->kv_doc_ids;
+  p.B = (int)B; p.G = (int)G; p.H = (int)H; p.Hkv = (int)Hkv; p.Sq = (int)Sq; p.Sk = (int)Sk;
+  p.window = desc->window;
+  p.prefix = desc->prefix_len;
+  p.scale = desc->scale;
+  p.softcap = desc->softcap;
+  p.dq_f32 = dq->dtype == FL_F32;
+  p.dkv_f32 = dk->dtype == FL_F32;
+  p.n_qtiles = (int)((Sq + be->bm - 1) / be->bm);
+  p.n_ktiles = (int)((Sk + be->bm - 1) / be->bm);
+  const int64_t nb_q = B * G * H * p.n_qtiles, nb_k = B * G * Hkv * p.n_ktiles;
+  const int64_t rows = B * G * H * Sq;
+  if (nb_q > 0x7fffffffLL || nb_k > 0x7fffffffLL || rows > 0x7fffffff00LL) return fail(FL_ERR_SHAPE, "too many workgroups");
+
+  hipStream_t stream = (hipStream_t)stream_v;
+  hipError_t e = hipSuccess;
+  if ((mask & FL_MASK_DOC) && !no_rows && !no_keys) {
+    const int nqs = (int)((Sq + fl::kSumBlock - 1) / fl::kSumBlock), nks = (int)((Sk + fl::kSumBlock - 1) / fl::kSumBlock);
+    p.q_sum = (int2*)((unsigned char*)aux->workspace + 2 * wsz.stat_bytes);
+    p.kv_sum = p.q_sum + B * nqs;
+    const int tq = (int)(B * nqs), tk = (int)(B * nks);
+    hipLaunchKernelGGL(doc_summary_kernel, dim3((tq + 3) / 4), dim3(256), 0, stream, aux->q_doc_ids, p.q_sum, (int)Sq, nqs, tq);
+    hipLaunchKernelGGL(doc_summary_kernel, dim3((tk + 3) / 4), dim3(256), 0, stream, aux->kv_doc_ids, p.kv_sum, (int)Sk, nks, tk);
+    if ((e = hipGetLastError()) != hipSuccess) return fail(FL_ERR_LAUNCH, "doc summary launch: %s", hipGetErrorString(e));
+  }
+  if (!no_rows) {
+    const int lanes_per_row = (int)Dv / 8;
+    const int64_t nb_prep = (rows * lanes_per_row + 255) / 256;
+    if ((e = be->prep(p, (int)nb_prep, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "pre-pass launch: %s", hipGetErrorString(e));
+    // Sk == 0: the key loop is empty and dq comes out as zeros
+    if ((e = be->dq(p, (int)nb_q, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dq launch: %s", hipGetErrorString(e));
+  }
+  if (!no_keys) {
+    // Sq == 0: the query loop is empty and dk, dv come out as zeros
+    if ((e = be->dkdv(p, (int)nb_k, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dk/dv launch: %s", hipGetErrorString(e));
+  }
   return FL_OK;
 }
 

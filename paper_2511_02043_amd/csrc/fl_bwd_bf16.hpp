@@ -1,0 +1,684 @@
+// bf16 backward kernels of the attention variants for gfx950: gradients of the fused forward
+// pass (Eq. 3 with the score_mod of Eq. 4 and the masks of the attention listing) with respect
+// to Q, K and V, from the saved log-sum-exp -- the training extension the paper's conclusion
+// leaves open.  Like the forward pass, nothing of size [Sq, Sk] ever reaches device memory: each
+// score tile is recomputed on the matrix cores, turned into probabilities with the saved
+// row statistics and consumed at once.
+//
+//     P  = exp(s - lse)                 s: the transformed, masked score of the forward pass
+//     dP = dO V^T
+//     dS = P * (dP - delta)             delta_i = sum_c dO_ic O_ic  (= rowsum(P * dP))
+//     dZ = dS * (1 - tanh^2)            soft-cap only
+//     dV = P^T dO,   dK = scale * dZ^T Q,   dQ = scale * dZ K
+//
+// Two kernels, both without atomics (bitwise reproducible results):
+//   * bwd_dq_kernel: a workgroup owns 128 query rows (one per lane, as in the forward kernel)
+//     and walks the key tiles; per tile S^T = K Q^T and dP^T = V dO^T land in the 32x32
+//     accumulator layout with the query in the lane, dS^T rounded to bf16 is the B operand of
+//     dQ^T += K^T dS^T, whose A operand is the same K tile read through the transposing LDS load.
+//   * bwd_dkdv_kernel: a workgroup owns 128 keys (one per lane, K and V fragments in registers)
+//     and walks the query tiles of every query head of its group; S = Q K^T and dP = dO V^T have
+//     the key in the lane and the query row in the register index, so P and dS are the B
+//     operands of dV^T += dO^T P and dK^T += Q^T dS with dO^T / Q^T read transposed from LDS.
+// A small pre-pass writes delta and the log2-scaled lse (+inf for rows without a visible key, so
+// that their probabilities come out as exactly 0).
+//
+// LDS tiles are row-major [rows][D] bf16 with one 16-byte-chunk swizzle that serves both access
+// patterns without bank conflicts: the row read (32 consecutive rows, one chunk per lane) and
+// the transposing read (4 rows x 4 chunks per 32 lanes).
+#pragma once
+#include "fl_kernel_bf16.hpp"
+
+namespace fl {
+
+struct BwdParams {
+  View q, k, v, o, dout;           // inputs  [B, G, H | Hkv, S, D]
+  View dq, dk, dv;                 // outputs (ptr is written)
+  const float* lse;                // [B, G, H, Sq] from the forward pass
+  int64_t lse_sb, lse_sg, lse_sh;
+  float* delta;                    // workspace [B, G, H, Sq]: rowsum(dO * O)
+  float* lse2;                     // workspace [B, G, H, Sq]: lse * log2(e), +inf for dead rows
+  const float* alibi_slopes;
+  const int32_t* q_doc;            // [B, Sq]
+  const int32_t* kv_doc;           // [B, Sk]
+  int2* q_sum;                     // (min, max) document id per block of 32 rows / keys
+  int2* kv_sum;
+  int32_t B, G, H, Hkv, Sq, Sk;
+  int32_t window, prefix;
+  float scale, softcap;
+  int32_t dq_f32, dkv_f32;         // 1: that output is float, 0: bf16
+  int32_t n_qtiles, n_ktiles;      // workgroups per (b, g, h) of the dQ kernel / per (b, g, hkv) of the dK/dV kernel
+};
+
+// chunk swizzle of a tile row (see the header comment): an XOR on the 16-byte chunk index that
+// depends on row % 16 only.
+template <int D>
+__device__ __forceinline__ int swz_u(int r) {
+  if constexpr (D == 128) return ((r & 3) << 2) | ((r >> 2) & 3);
+  else return (((r >> 1) & 1) << 2) | ((r >> 2) & 3);
+}
+
+// Query rows [lo, hi) that can see any key in [j_lo, j_hi] under the positional masks.
+__device__ __forceinline__ void query_range(const uint32_t MASK, int j_lo, int j_hi, int Sq, int window, int prefix,
+                                            int& lo, int& hi) {
+  lo = 0;
+  hi = Sq;
+  if ((MASK & kMaskPrefix) != 0) {
+    if (j_lo >= prefix) lo = j_lo;
+  } else if ((MASK & (kMaskCausal | kMaskWindow)) != 0) {
+    lo = j_lo;
+  }
+  if ((MASK & kMaskWindow) != 0) hi = min(Sq, j_hi + window + 1);
+  lo = min(lo, hi);
+}
+
+template <int D_, int MOD_, uint32_t MASK_, int BN_, int WPE_>
+struct BwdCfg {
+  static constexpr int D = D_, MOD = MOD_, BN = BN_, WPE = WPE_;
+  static constexpr uint32_t MASK = MASK_;
+  static constexpr int NW = 4, NT = NW * 64;
+  static constexpr int BM = NW * 32;               // rows (dQ kernel) or keys (dK/dV kernel) per workgroup
+  static constexpr int NB = BN / 32;               // 32-row blocks of a streamed tile
+  static constexpr int KK = D / 16;                // k-steps over the head dim
+  static constexpr int DB = D / 32;                // 32-channel blocks of the head dim
+  static constexpr int ROW = D * 2;                // bytes of a tile row
+  static constexpr int TILE = BN * ROW;            // bytes of one streamed tile
+  static constexpr int STAT = BN * 4;              // bytes of one per-row statistic of a tile (dK/dV kernel)
+  static constexpr int STAGE_DQ = 2 * TILE;        // K, V
+  static constexpr int STAGE_KV = 2 * TILE + 2 * STAT;   // Q, dO, lse2, delta
+  static constexpr int TILE_INSTR = TILE / 1024;   // 64-lane x 16-byte direct loads per tile
+  static constexpr int RPI = 1024 / ROW;           // tile rows per load instruction
+  static_assert(D == 64 || D == 128, "head dims of the backward kernels");
+  static_assert(TILE_INSTR % NW == 0, "every wave issues the same number of loads");
+  static_assert((NW * RPI) % 16 == 0, "a lane's destination row keeps its residue mod 16");
+};
+
+template <class C>
+struct BwdWave {
+  static constexpr int D = C::D, KK = C::KK, DB = C::DB, ROW = C::ROW;
+  static constexpr uint32_t MASK = C::MASK;
+
+  int lane, half, col;
+  uint32_t ra[C::KK];              // per-lane byte offset of the row-read fragment of k-step kk (row block 0)
+  uint32_t ta[C::DB][2];           // per-lane byte offsets of the transposing read of channel block d (rows +0 / +8)
+
+  __device__ __forceinline__ void init(int lane_) {
+    lane = lane_;
+    half = lane >> 5;
+    col = lane & 31;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) ra[kk] = col * ROW + ((2 * kk + half) ^ swz_u<D>(col)) * 16;
+    const int s16 = lane & 15;
+    const int r0 = 4 * half + (s16 >> 2);          // row this lane addresses in the transposing read
+#pragma unroll
+    for (int d = 0; d < DB; ++d) {
+      const int ch = 32 * d + 16 * ((lane >> 4) & 1) + 4 * (s16 & 3);   // first of its 4 channels
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int r = r0 + 8 * u;
+        ta[d][u] = r * ROW + ((ch >> 3) ^ swz_u<D>(r)) * 16 + (ch & 7) * 2;
+      }
+    }
+  }
+
+  static __device__ __forceinline__ f32x16 zero16() {
+    return f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  }
+
+  // LDS reads are issued by hand with explicit lgkmcnt waits (LDS returns in order): the compiler
+  // then sees no LDS read in the loop and cannot tie one to the direct global->LDS loads of the
+  // next tile that are in flight.
+  template <int OFF>
+  static __device__ __forceinline__ void read_b128(i32x4& dst, uint32_t addr) {
+    if constexpr (OFF <= 65535) {
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
+    } else {
+      const uint32_t a = addr + (uint32_t)OFF;
+      asm volatile("ds_read_b128 %0, %1" : "=v"(dst) : "v"(a) : "memory");
+    }
+  }
+  template <int OFF>
+  static __device__ __forceinline__ void read_tr(i32x2& dst, uint32_t addr) {
+    if constexpr (OFF <= 65535) {
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF) : "memory");
+    } else {
+      const uint32_t a = addr + (uint32_t)OFF;
+      asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(dst) : "v"(a) : "memory");
+    }
+  }
+  template <int N>
+  static __device__ __forceinline__ void wait_lds() {
+    static_assert(N >= 0 && N <= 15, "lgkmcnt is a 4-bit counter");
+    asm volatile("s_waitcnt lgkmcnt(%0)" : : "n"(N) : "memory");
+    __builtin_amdgcn_sched_barrier(0);
+  }
+
+  // KK row-read fragments (A operand, 32 tile rows x 16 channels each) of the 32-row block at
+  // LDS byte offset OFF, read two ahead; body(kk, fragment).
+  template <int OFF, class Body>
+  __device__ __forceinline__ void row_stream(Body&& body) const {
+    constexpr int G = 2, NG = KK / G;
+    i32x4 fr[KK];
+    static_for<0, G>([&](auto f) __attribute__((always_inline)) { read_b128<OFF>(fr[f], ra[f]); });
+    static_for<0, NG>([&](auto gc) __attribute__((always_inline)) {
+      constexpr int g = gc;
+      if constexpr (g + 1 < NG)
+        static_for<(g + 1) * G, (g + 2) * G>([&](auto f) __attribute__((always_inline)) { read_b128<OFF>(fr[f], ra[f]); });
+      wait_lds<(g + 1 < NG) ? G : 0>();
+      static_for<g * G, (g + 1) * G>([&](auto f) __attribute__((always_inline)) { body(f, __builtin_bit_cast(bf16x8, fr[f])); });
+    });
+  }
+  // 2 * DB transposed fragments (A operand, 32 channels x 16 tile rows each) of the 32-row block
+  // at OFF: fragment f = ks * DB + d covers rows 16 * ks .. + 15 and channels 32 * d .. + 31, with
+  // the contraction index order of the accumulator registers (element e <-> row 8*(e/4) + 4*half + e%4).
+  template <int OFF, class Body>
+  __device__ __forceinline__ void tr_stream(Body&& body) const {
+    constexpr int NF = 2 * DB, G = 2, NG = NF / G;
+    i32x2 lo[NF], hi[NF];
+    static_for<0, G>([&](auto f) __attribute__((always_inline)) {
+      read_tr<OFF + (f / DB) * 16 * ROW>(lo[f], ta[f % DB][0]);
+      read_tr<OFF + (f / DB) * 16 * ROW>(hi[f], ta[f % DB][1]);
+    });
+    static_for<0, NG>([&](auto gc) __attribute__((always_inline)) {
+      constexpr int g = gc;
+      if constexpr (g + 1 < NG)
+        static_for<(g + 1) * G, (g + 2) * G>([&](auto f) __attribute__((always_inline)) {
+          read_tr<OFF + (f / DB) * 16 * ROW>(lo[f], ta[f % DB][0]);
+          read_tr<OFF + (f / DB) * 16 * ROW>(hi[f], ta[f % DB][1]);
+        });
+      wait_lds<(g + 1 < NG) ? 2 * G : 0>();
+      static_for<g * G, (g + 1) * G>([&](auto f) __attribute__((always_inline)) {
+        body(f, __builtin_bit_cast(bf16x8, (i32x4){lo[f][0], lo[f][1], hi[f][0], hi[f][1]}));
+      });
+    });
+  }
+};
+
+// One 64-lane x 16-byte direct load instruction `inst` of a [rows][D] tile whose row 0 is at
+// `base` (row stride `row_bytes`); rows at or past n_valid are replaced by row n_valid - 1.
+template <class C>
+__device__ __forceinline__ void tile_load_instr(const unsigned char* base, int64_t row_bytes, int n_valid, int inst,
+                                                int lane, unsigned char* lds_tile) {
+  const int dst_row = inst * C::RPI + lane / (C::D / 8);
+  const int chunk = (lane % (C::D / 8)) ^ swz_u<C::D>(dst_row);
+  const int row = dst_row < n_valid ? dst_row : n_valid - 1;
+  lds_void* dst = (lds_void*)(lds_tile + inst * 1024);
+  __builtin_amdgcn_global_load_lds((global_cvoid*)(base + (int64_t)row * row_bytes + chunk * 16), dst, 16, 0, 0);
+}
+
+// The score pipeline of the forward pass replayed on one raw dot product x = <q_i, k_j>:
+// returns the log2-domain exponent argument a (P = exp2(a)) and the soft-cap derivative factor.
+//   rel = i - j;  slope2 = slope * log2(e);  lse2 = lse * log2(e).
+template <int MOD>
+__device__ __forceinline__ float replay_score(float x, float c_scale, float lse2, float softcap, float slope2,
+                                              float rel, float& fac) {
+  fac = 1.f;
+  if constexpr (MOD == kModSoftcap) {
+    const float e = fast_exp2(x * (2.f * c_scale / softcap));     // exp(2 z / cap)
+    const float t = fmaf(fast_rcp(e + 1.f), -2.f, 1.f);           // tanh(z / cap)
+    fac = fmaf(-t, t, 1.f);
+    return fmaf(t, softcap * kLog2e, -lse2);
+  } else if constexpr (MOD == kModAlibi) {
+    return fmaf(x, c_scale, -lse2) - slope2 * fabsf(rel);
+  } else {
+    return fmaf(x, c_scale, -lse2);
+  }
+}
+
+template <uint32_t MASK>
+__device__ __forceinline__ bool hidden(int i, int j, int Sq, int Sk, int window, int prefix, int qdoc, int kdoc) {
+  return i >= Sq || j >= Sk || is_masked(MASK, i, j, window, prefix, qdoc, kdoc);
+}
+
+// ------------------------------------------------------------------------------------------------
+// pre-pass: delta = rowsum(dO * O), lse2 = lse * log2(e) (+inf where lse = -inf)
+// ------------------------------------------------------------------------------------------------
+template <int DV>
+__global__ void __launch_bounds__(256) bwd_prep_kernel(const BwdParams p) {
+  constexpr int LPR = DV / 8;                      // lanes per row, 16 bytes each
+  const int64_t rows = (int64_t)p.B * p.G * p.H * p.Sq;
+  const int64_t row = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPR;
+  const int part = threadIdx.x % LPR;
+  const int64_t rc = row < rows ? row : rows - 1;
+  const int i = (int)(rc % p.Sq);
+  const int h = (int)((rc / p.Sq) % p.H);
+  const int g = (int)((rc / ((int64_t)p.Sq * p.H)) % p.G);
+  const int b = (int)(rc / ((int64_t)p.Sq * p.H * p.G));
+  const uint16_t* op = (const uint16_t*)p.o.ptr + b * p.o.sb + g * p.o.sg + h * p.o.sh + (int64_t)i * p.o.ss + 8 * part;
+  const uint16_t* dp = (const uint16_t*)p.dout.ptr + b * p.dout.sb + g * p.dout.sg + h * p.dout.sh + (int64_t)i * p.dout.ss + 8 * part;
+  const uint4 ov = *(const uint4*)op, dv = *(const uint4*)dp;
+  const uint32_t ow[4] = {ov.x, ov.y, ov.z, ov.w}, dw[4] = {dv.x, dv.y, dv.z, dv.w};
+  float s = 0.f;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    s = fmaf(__uint_as_float(ow[e] << 16), __uint_as_float(dw[e] << 16), s);
+    s = fmaf(__uint_as_float(ow[e] & 0xFFFF0000u), __uint_as_float(dw[e] & 0xFFFF0000u), s);
+  }
+#pragma unroll
+  for (int o = LPR / 2; o >= 1; o >>= 1) s += __shfl_xor(s, o);
+  if (part == 0 && row < rows) {
+    p.delta[row] = s;
+    const float l = p.lse[b * p.lse_sb + g * p.lse_sg + h * p.lse_sh + i];
+    p.lse2[row] = l == -INFINITY ? INFINITY : l * kLog2e;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// dQ
+// ------------------------------------------------------------------------------------------------
+template <class C>
+__global__ void __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE)))
+bwd_dq_kernel(const BwdParams p) {
+  constexpr int D = C::D, BN = C::BN, NB = C::NB, KK = C::KK, DB = C::DB, ROW = C::ROW;
+  constexpr uint32_t MASK = C::MASK;
+  constexpr uint32_t POS = MASK & ~kMaskDoc;
+  typedef BwdWave<C> W;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  W w;
+  w.init(tid & 63);
+  const int lane = w.lane;
+
+  // grid decode: longest q-tiles (under a causal mask) first
+  const int nq = p.n_qtiles;
+  const int qt = nq - 1 - (int)(blockIdx.x % nq);
+  const int bh = blockIdx.x / nq;
+  const int h = bh % p.H, g = (bh / p.H) % p.G, b = bh / (p.H * p.G);
+  const int hk = h / (p.H / p.Hkv);
+  const int i0 = qt * C::BM, iw = i0 + 32 * wave;
+  const int i = iw + w.col, ic = i < p.Sq ? i : p.Sq - 1;
+  const int64_t srow = ((int64_t)(b * p.G + g) * p.H + h) * p.Sq + ic;
+
+  // per-lane operands: Q and dO rows as B fragments, row statistics
+  bf16x8 qf[KK], dof[KK];
+  {
+    const uint16_t* qp = (const uint16_t*)p.q.ptr + b * p.q.sb + g * p.q.sg + h * p.q.sh + (int64_t)ic * p.q.ss;
+    const uint16_t* dp = (const uint16_t*)p.dout.ptr + b * p.dout.sb + g * p.dout.sg + h * p.dout.sh + (int64_t)ic * p.dout.ss;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      qf[kk] = *(const bf16x8*)(qp + 16 * kk + 8 * w.half);
+      dof[kk] = *(const bf16x8*)(dp + 16 * kk + 8 * w.half);
+    }
+  }
+  const float lse2 = p.lse2[srow], delta = p.delta[srow];
+  const float c_scale = p.scale * kLog2e;
+  const float slope2 = C::MOD == kModAlibi ? p.alibi_slopes[h] * kLog2e : 0.f;
+  int qdoc = 0;
+  if constexpr ((MASK & kMaskDoc) != 0) qdoc = p.q_doc[(int64_t)b * p.Sq + ic];
+
+  f32x16 acc[DB];
+#pragma unroll
+  for (int d = 0; d < DB; ++d) acc[d] = W::zero16();
+
+  // visible key range and tile skipping
+  const int i_last = (i0 + C::BM < p.Sq ? i0 + C::BM : p.Sq) - 1;
+  int k_lo, k_hi;
+  key_range(MASK, i0, i_last, p.Sk, p.window, p.prefix, k_lo, k_hi);
+  const int t_lo = k_lo / BN, t_hi = (k_hi + BN - 1) / BN;
+  const int nks = (p.Sk + kSumBlock - 1) / kSumBlock;
+  int2 qs_wg = make_int2(0, 0);
+  if constexpr ((MASK & kMaskDoc) != 0) {
+    const int nqs = (p.Sq + kSumBlock - 1) / kSumBlock;
+    const int2* qsum = p.q_sum + (int64_t)b * nqs;
+    qs_wg = qsum[i0 / kSumBlock];
+    for (int u = 1; u < C::BM / kSumBlock; ++u)
+      if (i0 / kSumBlock + u < nqs) {
+        const int2 t = qsum[i0 / kSumBlock + u];
+        qs_wg.x = min(qs_wg.x, t.x);
+        qs_wg.y = max(qs_wg.y, t.y);
+      }
+  }
+  auto next_tile = [&](int t) __attribute__((always_inline)) -> int {
+    if constexpr ((MASK & kMaskDoc) != 0) {
+      const int2* ksum = p.kv_sum + (int64_t)b * nks;
+      while (t < t_hi) {
+        int2 ks = ksum[min(t * NB, nks - 1)];
+        for (int u = 1; u < NB; ++u)
+          if (t * NB + u < nks) {
+            const int2 x = ksum[t * NB + u];
+            ks.x = min(ks.x, x.x);
+            ks.y = max(ks.y, x.y);
+          }
+        if (classify_block(MASK, i0, i_last, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg, ks) != kSkip) break;
+        ++t;
+      }
+    }
+    return t;
+  };
+
+  const unsigned char* kbase = (const unsigned char*)((const uint16_t*)p.k.ptr + b * p.k.sb + g * p.k.sg + hk * p.k.sh);
+  const unsigned char* vbase = (const unsigned char*)((const uint16_t*)p.v.ptr + b * p.v.sb + g * p.v.sg + hk * p.v.sh);
+  const int64_t kss = p.k.ss * 2, vss = p.v.ss * 2;
+  auto load_tile = [&](int t, int stage) __attribute__((always_inline)) {
+    const int nvalid = min(BN, p.Sk - t * BN);
+    unsigned char* st = lds_raw + stage * C::STAGE_DQ;
+#pragma unroll
+    for (int u = 0; u < C::TILE_INSTR / C::NW; ++u) {
+      tile_load_instr<C>(kbase + (int64_t)(t * BN) * kss, kss, nvalid, wave + u * C::NW, lane, st);
+      tile_load_instr<C>(vbase + (int64_t)(t * BN) * vss, vss, nvalid, wave + u * C::NW, lane, st + C::TILE);
+    }
+  };
+
+  auto compute = [&](auto stage_c, int t) __attribute__((always_inline)) {
+    constexpr int ST = decltype(stage_c)::value * C::STAGE_DQ;
+    const int j0 = t * BN;
+    static_for<0, NB>([&](auto nbc) __attribute__((always_inline)) {
+      constexpr int nb = decltype(nbc)::value;
+      // the wave's 32 rows against this block's 32 keys under the positional masks (uniform)
+      const int cls = classify_block(POS, iw, iw + 31, j0 + 32 * nb, j0 + 32 * nb + 31, p.Sk, p.window, p.prefix,
+                                     make_int2(0, 0), make_int2(0, 0));
+      if (cls == kSkip) return;                    // nothing visible: dS = 0
+      const bool need_mask = (MASK & kMaskDoc) != 0 || iw + 31 >= p.Sq || cls != kFull;
+      f32x16 s = W::zero16(), dp = W::zero16();
+      w.template row_stream<ST + nb * 32 * ROW>([&](auto kk, bf16x8 a) __attribute__((always_inline)) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s, 0, 0, 0);
+      });
+      w.template row_stream<ST + C::TILE + nb * 32 * ROW>([&](auto kk, bf16x8 a) __attribute__((always_inline)) {
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, dof[kk], dp, 0, 0, 0);
+      });
+      const int jb = j0 + 32 * nb + 4 * w.half;    // key of register 0
+      int kd[16];
+      if constexpr ((MASK & kMaskDoc) != 0) {
+        const int32_t* kdoc = p.kv_doc + (int64_t)b * p.Sk;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int j = jb + 8 * (r >> 2) + (r & 3);
+          kd[r] = kdoc[j < p.Sk ? j : p.Sk - 1];
+        }
+      }
+      uint32_t dsw[8];
+#pragma unroll
+      for (int r2 = 0; r2 < 8; ++r2) {
+        float dsv[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const int r = 2 * r2 + e;
+          const int j = jb + 8 * (r >> 2) + (r & 3);
+          float fac;
+          const float a = replay_score<C::MOD>(s[r], c_scale, lse2, p.softcap, slope2, (float)(i - j), fac);
+          float pr = fast_exp2(a);
+          if (need_mask && hidden<MASK>(i, j, p.Sq, p.Sk, p.window, p.prefix, qdoc, (MASK & kMaskDoc) ? kd[r] : 0)) pr = 0.f;
+          dsv[e] = pr * (dp[r] - delta);
+          if constexpr (C::MOD == kModSoftcap) dsv[e] *= fac;
+        }
+        dsw[r2] = pack_bf16(dsv[0], dsv[1]);
+      }
+      w.template tr_stream<ST + nb * 32 * ROW>([&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+        constexpr int f = decltype(fc)::value, d = f % DB, ks = f / DB;
+        const bf16x8 bop = __builtin_bit_cast(
+            bf16x8, (i32x4){(int)dsw[4 * ks], (int)dsw[4 * ks + 1], (int)dsw[4 * ks + 2], (int)dsw[4 * ks + 3]});
+        acc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bop, acc[d], 0, 0, 0);
+      });
+    });
+  };
+
+  int t = next_tile(t_lo);
+  if (t < t_hi) {
+    load_tile(t, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0)
+    __syncthreads();
+    while (true) {
+      bool done = false;
+      static_for<0, 2>([&](auto sc) __attribute__((always_inline)) {
+        if (!done) {
+          const int tn = next_tile(t + 1);
+          if (tn < t_hi) load_tile(tn, 1 - decltype(sc)::value);
+          compute(sc, t);
+          __builtin_amdgcn_s_waitcnt(0x0F70);
+          __syncthreads();
+          t = tn;
+          done = t >= t_hi;
+        }
+      });
+      if (done) break;
+    }
+  }
+
+  if (i < p.Sq) {
+    const int64_t orow = b * p.dq.sb + g * p.dq.sg + h * p.dq.sh + (int64_t)i * p.dq.ss;
+#pragma unroll
+    for (int d = 0; d < DB; ++d)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int ch = 32 * d + 8 * r4 + 4 * w.half;
+        const float x0 = acc[d][4 * r4] * p.scale, x1 = acc[d][4 * r4 + 1] * p.scale;
+        const float x2 = acc[d][4 * r4 + 2] * p.scale, x3 = acc[d][4 * r4 + 3] * p.scale;
+        if (p.dq_f32) *(float4*)((float*)p.dq.ptr + orow + ch) = make_float4(x0, x1, x2, x3);
+        else *(uint2*)((uint16_t*)p.dq.ptr + orow + ch) = make_uint2(pack_bf16(x0, x1), pack_bf16(x2, x3));
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// dK, dV
+// ------------------------------------------------------------------------------------------------
+template <class C>
+__global__ void __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE)))
+bwd_dkdv_kernel(const BwdParams p) {
+  constexpr int D = C::D, BN = C::BN, NB = C::NB, KK = C::KK, DB = C::DB, ROW = C::ROW;
+  constexpr uint32_t MASK = C::MASK;
+  constexpr uint32_t POS = MASK & ~kMaskDoc;
+  typedef BwdWave<C> W;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  W w;
+  w.init(tid & 63);
+  const int lane = w.lane;
+
+  // grid decode: key tiles in increasing order (under a causal mask the first ones see the most rows)
+  const int nk = p.n_ktiles;
+  const int kt = blockIdx.x % nk;
+  const int bh = blockIdx.x / nk;
+  const int hk = bh % p.Hkv, g = (bh / p.Hkv) % p.G, b = bh / (p.Hkv * p.G);
+  const int group = p.H / p.Hkv;
+  const int j0 = kt * C::BM, jw = j0 + 32 * wave;
+  const int j = jw + w.col, jc = j < p.Sk ? j : p.Sk - 1;
+
+  bf16x8 kf[KK], vf[KK];
+  {
+    const uint16_t* kp = (const uint16_t*)p.k.ptr + b * p.k.sb + g * p.k.sg + hk * p.k.sh + (int64_t)jc * p.k.ss;
+    const uint16_t* vp = (const uint16_t*)p.v.ptr + b * p.v.sb + g * p.v.sg + hk * p.v.sh + (int64_t)jc * p.v.ss;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      kf[kk] = *(const bf16x8*)(kp + 16 * kk + 8 * w.half);
+      vf[kk] = *(const bf16x8*)(vp + 16 * kk + 8 * w.half);
+    }
+  }
+  const float c_scale = p.scale * kLog2e;
+  int kdoc = 0;
+  if constexpr ((MASK & kMaskDoc) != 0) kdoc = p.kv_doc[(int64_t)b * p.Sk + jc];
+
+  f32x16 dk[DB], dv[DB];
+#pragma unroll
+  for (int d = 0; d < DB; ++d) {
+    dk[d] = W::zero16();
+    dv[d] = W::zero16();
+  }
+
+  // query rows that can see the workgroup's keys; q-tile skipping for document masks
+  const int j_last = (j0 + C::BM < p.Sk ? j0 + C::BM : p.Sk) - 1;
+  int q_lo, q_hi;
+  query_range(MASK, j0, j_last, p.Sq, p.window, p.prefix, q_lo, q_hi);
+  const int t_lo = q_lo / BN, t_hi = (q_hi + BN - 1) / BN;
+  const int nt = t_hi - t_lo;                      // q-tiles per head
+  const int n_items = nt > 0 ? nt * group : 0;     // (head of the group, q-tile), head-major
+  const int nqs = (p.Sq + kSumBlock - 1) / kSumBlock;
+  int2 ks_wg = make_int2(0, 0);
+  if constexpr ((MASK & kMaskDoc) != 0) {
+    const int nks = (p.Sk + kSumBlock - 1) / kSumBlock;
+    const int2* ksum = p.kv_sum + (int64_t)b * nks;
+    ks_wg = ksum[j0 / kSumBlock];
+    for (int u = 1; u < C::BM / kSumBlock; ++u)
+      if (j0 / kSumBlock + u < nks) {
+        const int2 x = ksum[j0 / kSumBlock + u];
+        ks_wg.x = min(ks_wg.x, x.x);
+        ks_wg.y = max(ks_wg.y, x.y);
+      }
+  }
+  auto next_item = [&](int it) __attribute__((always_inline)) -> int {
+    if constexpr ((MASK & kMaskDoc) != 0) {
+      const int2* qsum = p.q_sum + (int64_t)b * nqs;
+      while (it < n_items) {
+        const int t = t_lo + it % nt;
+        int2 qs = qsum[min(t * NB, nqs - 1)];
+        for (int u = 1; u < NB; ++u)
+          if (t * NB + u < nqs) {
+            const int2 x = qsum[t * NB + u];
+            qs.x = min(qs.x, x.x);
+            qs.y = max(qs.y, x.y);
+          }
+        const int q_last = (t * BN + BN < p.Sq ? t * BN + BN : p.Sq) - 1;
+        if (classify_block(MASK, t * BN, q_last, j0, j0 + C::BM - 1, p.Sk, p.window, p.prefix, qs, ks_wg) != kSkip) break;
+        ++it;
+      }
+    }
+    return it;
+  };
+
+  auto load_item = [&](int it, int stage) __attribute__((always_inline)) {
+    const int t = t_lo + it % nt, h = hk * group + it / nt;
+    const int nvalid = min(BN, p.Sq - t * BN);
+    unsigned char* st = lds_raw + stage * C::STAGE_KV;
+    const unsigned char* qb = (const unsigned char*)((const uint16_t*)p.q.ptr + b * p.q.sb + g * p.q.sg + h * p.q.sh + (int64_t)(t * BN) * p.q.ss);
+    const unsigned char* db = (const unsigned char*)((const uint16_t*)p.dout.ptr + b * p.dout.sb + g * p.dout.sg + h * p.dout.sh + (int64_t)(t * BN) * p.dout.ss);
+#pragma unroll
+    for (int u = 0; u < C::TILE_INSTR / C::NW; ++u) {
+      tile_load_instr<C>(qb, p.q.ss * 2, nvalid, wave + u * C::NW, lane, st);
+      tile_load_instr<C>(db, p.dout.ss * 2, nvalid, wave + u * C::NW, lane, st + C::TILE);
+    }
+    // row statistics: 64 rows per instruction, 4 bytes per lane
+    const int64_t srow = ((int64_t)(b * p.G + g) * p.H + h) * p.Sq;
+    for (int u = wave; u < 2 * (BN / 64 > 0 ? BN / 64 : 1); u += C::NW) {
+      const int which = u % 2, blk = u / 2;        // 0: lse2, 1: delta
+      const int r = blk * 64 + lane;
+      const int row = t * BN + (r < nvalid ? r : nvalid - 1);
+      const float* src = (which == 0 ? p.lse2 : p.delta) + srow + row;
+      if (BN >= 64 || lane < BN) {
+        lds_void* dst = (lds_void*)(st + 2 * C::TILE + which * C::STAT + blk * 256);
+        __builtin_amdgcn_global_load_lds((global_cvoid*)src, dst, 4, 0, 0);
+      }
+    }
+  };
+
+  auto compute = [&](auto stage_c, int it) __attribute__((always_inline)) {
+    constexpr int ST = decltype(stage_c)::value * C::STAGE_KV;
+    const int t = t_lo + it % nt, h = hk * group + it / nt;
+    const int i0 = t * BN;
+    const float slope2 = C::MOD == kModAlibi ? p.alibi_slopes[h] * kLog2e : 0.f;
+    const uint32_t stat_addr = (uint32_t)(4 * w.half) * 4;     // this half's first row of a register quad
+    static_for<0, NB>([&](auto qbc) __attribute__((always_inline)) {
+      constexpr int qb = decltype(qbc)::value;
+      const int ib = i0 + 32 * qb;
+      // this block's 32 rows against the wave's 32 keys under the positional masks (uniform)
+      const int cls = classify_block(POS, ib, ib + 31, jw, jw + 31, p.Sk, p.window, p.prefix, make_int2(0, 0),
+                                     make_int2(0, 0));
+      if (cls == kSkip || ib >= p.Sq) return;      // nothing visible: P = dS = 0
+      const bool need_mask = (MASK & kMaskDoc) != 0 || ib + 31 >= p.Sq || cls != kFull;
+      // row statistics of the block's 16 rows of this half: four quads of lse2, four of delta
+      i32x4 st_l[4], st_d[4];
+      static_for<0, 4>([&](auto qc) __attribute__((always_inline)) {
+        constexpr int q4 = decltype(qc)::value;
+        W::template read_b128<ST + 2 * C::TILE + (32 * qb + 8 * q4) * 4>(st_l[q4], stat_addr);
+        W::template read_b128<ST + 2 * C::TILE + C::STAT + (32 * qb + 8 * q4) * 4>(st_d[q4], stat_addr);
+      });
+      f32x16 s = W::zero16(), dp = W::zero16();
+      w.template row_stream<ST + qb * 32 * ROW>([&](auto kk, bf16x8 a) __attribute__((always_inline)) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[kk], s, 0, 0, 0);
+      });
+      w.template row_stream<ST + C::TILE + qb * 32 * ROW>([&](auto kk, bf16x8 a) __attribute__((always_inline)) {
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, vf[kk], dp, 0, 0, 0);
+      });
+      const int irow = ib + 4 * w.half;            // query row of register 0
+      int qd[16];
+      if constexpr ((MASK & kMaskDoc) != 0) {
+        const int32_t* qdoc = p.q_doc + (int64_t)b * p.Sq;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int i = irow + 8 * (r >> 2) + (r & 3);
+          qd[r] = qdoc[i < p.Sq ? i : p.Sq - 1];
+        }
+      }
+      uint32_t pw[8], dsw[8];
+#pragma unroll
+      for (int r2 = 0; r2 < 8; ++r2) {
+        float pv[2], dsv[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const int r = 2 * r2 + e;
+          const int i = irow + 8 * (r >> 2) + (r & 3);
+          const float lse2 = __int_as_float(st_l[r >> 2][r & 3]), delta = __int_as_float(st_d[r >> 2][r & 3]);
+          float fac;
+          const float a = replay_score<C::MOD>(s[r], c_scale, lse2, p.softcap, slope2, (float)(i - j), fac);
+          float pr = fast_exp2(a);
+          if (need_mask && hidden<MASK>(i, j, p.Sq, p.Sk, p.window, p.prefix, (MASK & kMaskDoc) ? qd[r] : 0, kdoc)) pr = 0.f;
+          pv[e] = pr;
+          dsv[e] = pr * (dp[r] - delta);
+          if constexpr (C::MOD == kModSoftcap) dsv[e] *= fac;
+        }
+        pw[r2] = pack_bf16(pv[0], pv[1]);
+        dsw[r2] = pack_bf16(dsv[0], dsv[1]);
+      }
+      w.template tr_stream<ST + C::TILE + qb * 32 * ROW>([&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+        constexpr int f = decltype(fc)::value, d = f % DB, ks = f / DB;
+        const bf16x8 bop = __builtin_bit_cast(
+            bf16x8, (i32x4){(int)pw[4 * ks], (int)pw[4 * ks + 1], (int)pw[4 * ks + 2], (int)pw[4 * ks + 3]});
+        dv[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bop, dv[d], 0, 0, 0);
+      });
+      w.template tr_stream<ST + qb * 32 * ROW>([&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+        constexpr int f = decltype(fc)::value, d = f % DB, ks = f / DB;
+        const bf16x8 bop = __builtin_bit_cast(
+            bf16x8, (i32x4){(int)dsw[4 * ks], (int)dsw[4 * ks + 1], (int)dsw[4 * ks + 2], (int)dsw[4 * ks + 3]});
+        dk[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bop, dk[d], 0, 0, 0);
+      });
+    });
+  };
+
+  int it = next_item(0);
+  if (it < n_items) {
+    load_item(it, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0)
+    __syncthreads();
+    while (true) {
+      bool done = false;
+      static_for<0, 2>([&](auto sc) __attribute__((always_inline)) {
+        if (!done) {
+          const int in = next_item(it + 1);
+          if (in < n_items) load_item(in, 1 - decltype(sc)::value);
+          compute(sc, it);
+          __builtin_amdgcn_s_waitcnt(0x0F70);
+          __syncthreads();
+          it = in;
+          done = it >= n_items;
+        }
+      });
+      if (done) break;
+    }
+  }
+
+  if (j < p.Sk) {
+    const int64_t krow = b * p.dk.sb + g * p.dk.sg + hk * p.dk.sh + (int64_t)j * p.dk.ss;
+    const int64_t vrow = b * p.dv.sb + g * p.dv.sg + hk * p.dv.sh + (int64_t)j * p.dv.ss;
+#pragma unroll
+    for (int d = 0; d < DB; ++d)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int ch = 32 * d + 8 * r4 + 4 * w.half;
+        const float k0 = dk[d][4 * r4] * p.scale, k1 = dk[d][4 * r4 + 1] * p.scale;
+        const float k2 = dk[d][4 * r4 + 2] * p.scale, k3 = dk[d][4 * r4 + 3] * p.scale;
+        const float v0 = dv[d][4 * r4], v1 = dv[d][4 * r4 + 1], v2 = dv[d][4 * r4 + 2], v3 = dv[d][4 * r4 + 3];
+        if (p.dkv_f32) {
+          *(float4*)((float*)p.dk.ptr + krow + ch) = make_float4(k0, k1, k2, k3);
+          *(float4*)((float*)p.dv.ptr + vrow + ch) = make_float4(v0, v1, v2, v3);
+        } else {
+          *(uint2*)((uint16_t*)p.dk.ptr + krow + ch) = make_uint2(pack_bf16(k0, k1), pack_bf16(k2, k3));
+          *(uint2*)((uint16_t*)p.dv.ptr + vrow + ch) = make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3));
+        }
+      }
+  }
+}
+
+}  // namespace fl

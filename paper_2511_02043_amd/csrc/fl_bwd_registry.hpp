@@ -1,0 +1,66 @@
+// Table of compiled backward specialisations (one dQ kernel and one dK/dV kernel per entry).
+#pragma once
+#include "fl_bwd_bf16.hpp"
+#include "fl_registry.hpp"
+
+namespace fl {
+
+struct BwdKey {
+  int D;            // head dim (D == Dv)
+  int mod, mask;
+};
+
+typedef hipError_t (*BwdLaunchFn)(const BwdParams& p, int nblocks, hipStream_t stream);
+
+struct BwdEntry {
+  BwdKey key;
+  int bm;           // query rows per workgroup of the dQ kernel = keys per workgroup of the dK/dV kernel
+  BwdLaunchFn prep, dq, dkdv;
+};
+
+template <class K>
+hipError_t raise_lds_limit(K kernel) {
+  static bool done[64] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64 || !done[dev]) {
+    e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64) done[dev] = true;
+  }
+  return hipSuccess;
+}
+
+template <int DV>
+hipError_t launch_bwd_prep(const BwdParams& p, int nblocks, hipStream_t stream) {
+  hipLaunchKernelGGL(bwd_prep_kernel<DV>, dim3(nblocks), dim3(256), 0, stream, p);
+  return hipGetLastError();
+}
+template <class C>
+hipError_t launch_bwd_dq(const BwdParams& p, int nblocks, hipStream_t stream) {
+  hipError_t e = raise_lds_limit(bwd_dq_kernel<C>);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(bwd_dq_kernel<C>, dim3(nblocks), dim3(C::NT), 2 * C::STAGE_DQ, stream, p);
+  return hipGetLastError();
+}
+template <class C>
+hipError_t launch_bwd_dkdv(const BwdParams& p, int nblocks, hipStream_t stream) {
+  hipError_t e = raise_lds_limit(bwd_dkdv_kernel<C>);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(bwd_dkdv_kernel<C>, dim3(nblocks), dim3(C::NT), 2 * C::STAGE_KV, stream, p);
+  return hipGetLastError();
+}
+
+// CQ / CK: the shapes of the dQ kernel and of the dK/dV kernel (streamed tile rows, waves per SIMD).
+template <int D, int MOD, uint32_t MASK, int BN_Q, int WPE_Q, int BN_K, int WPE_K>
+constexpr BwdEntry bwd_entry() {
+  typedef BwdCfg<D, MOD, MASK, BN_Q, WPE_Q> CQ;
+  typedef BwdCfg<D, MOD, MASK, BN_K, WPE_K> CK;
+  return BwdEntry{BwdKey{D, MOD, (int)MASK}, CQ::BM, &launch_bwd_prep<D>, &launch_bwd_dq<CQ>, &launch_bwd_dkdv<CK>};
+}
+
+const BwdEntry* entries_bwd64(int* n);
+const BwdEntry* entries_bwd128(int* n);
+
+}  // namespace fl

@@ -130,6 +130,13 @@ def _qkv(cfg, B, G, H, Sq, Sk, D, Dv, dtype, Hkv=None, salt=0, qscale=1.0):
     return q, k, v
 
 
+def dout_for(w: "Workload", salt: int = 0) -> np.ndarray:
+    """Seeded N(0,1) gradient arriving at the output of `w` ([B, G, H, Sq, Dv], rounded to the
+    storage dtype), for the backward pass.  Tensor index 9 of configuration 7 in the seed recipe."""
+    B, G, H, Sq, _ = w.q.shape
+    return normal((B, G, H, Sq, w.v.shape[4]), tensor_seed(7, 9, salt), w.dtype)
+
+
 # --- the five benchmark configurations, each shrinkable for parity tests -----------------
 
 def plain_f32(B=1, H=2, S=128, D=64, Sk=None, salt=0) -> Workload:

@@ -1,4 +1,4 @@
-"""Upload an inputs.Workload to the GPU and call fl_attn_fwd on it (marshalling only).
+"""Upload an inputs.Workload to the GPU and call fl_attn_fwd / fl_attn_bwd on it (marshalling only).
 
 Used by the GPU tests, the smoke check and the benchmark.  The NumPy layouts of the
 workload (including the Evoformer [B, Nseq, Nres, H, D] storage viewed as [B,G,H,S,D])
@@ -131,3 +131,53 @@ def lse_to_oracle_layout(dw: DeviceWorkload) -> np.ndarray:
         B, G2, H, Sq = l.shape
         return l.reshape(B, G2 // 2, 2, H, Sq).transpose(0, 2, 1, 3, 4)
     return l
+
+
+@dataclasses.dataclass
+class DeviceBackward:
+    """Device tensors of one fl_attn_bwd call on top of a forward DeviceWorkload (bf16 out + lse)."""
+    fwd: DeviceWorkload
+    dout: torch.Tensor
+    dq: torch.Tensor
+    dk: torch.Tensor
+    dv: torch.Tensor
+    aux: fb.fl_aux
+    keep: List[torch.Tensor]
+    tdout: fb.fl_tensor = None
+    tdq: fb.fl_tensor = None
+    tdk: fb.fl_tensor = None
+    tdv: fb.fl_tensor = None
+
+    def run(self, stream: int = 0) -> int:
+        f = self.fwd
+        return fb.fl_attn_bwd(f.tq, f.tk, f.tv, f.tout, self.tdout, f.tlse, f.desc, self.aux,
+                              self.tdq, self.tdk, self.tdv, stream)
+
+    def run_checked(self, stream: int = 0) -> None:
+        fb.check(self.run(stream))
+
+
+def upload_backward(w, dout: np.ndarray, grad_dtype: str = "f32", device="cuda:0") -> DeviceBackward:
+    """Forward tensors (bf16 out, lse) plus dout, the gradient outputs and the backward workspace.
+    The forward pass has to be run (fwd.run_checked()) before the backward call."""
+    fwd = upload(w, out_dtype="bf16", device=device, want_lse=True)
+    tdt = torch.bfloat16
+    gdt = torch.float32 if grad_dtype == "f32" else tdt
+    d_out = to_device(dout, tdt, device)
+    dq = empty_like_layout(fwd.q, fwd.q.shape[4], gdt)
+    dk = empty_like_layout(fwd.k, fwd.k.shape[4], gdt)
+    dv = empty_like_layout(fwd.v, fwd.v.shape[4], gdt)
+    nbytes = fb.fl_attn_bwd_workspace_size(fwd.tq, fwd.tk, fwd.desc)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)
+    keep = [ws] + list(fwd.keep)
+    slopes = qd = kd = None
+    # the aux tensors of the forward upload, by the order upload() appended them
+    it = iter(fwd.keep)
+    if w.alibi is not None:
+        slopes = next(it)
+    if w.q_doc is not None:
+        qd = next(it)
+        kd = qd if (w.kv_doc is w.q_doc) else next(it)
+    aux = fb.aux_desc(alibi_slopes=slopes, q_doc_ids=qd, kv_doc_ids=kd, workspace=ws)
+    return DeviceBackward(fwd, d_out, dq, dk, dv, aux, keep, fb.tensor_desc(d_out), fb.tensor_desc(dq),
+                          fb.tensor_desc(dk), fb.tensor_desc(dv))

@@ -1,0 +1,143 @@
+"""GPU parity of fl_attn_bwd (through the C-ABI) against the fp64 backward oracle.
+
+Tolerance.  The kernels recompute P and dS in fp32 from bf16 inputs and round both to bf16
+(relative error 2^-9 per element) before the fp32-accumulating contractions; the bf16 `out`
+that enters delta = rowsum(dout * out) carries the same relative rounding.  With fp32 gradient
+outputs the error of an element is therefore a sum of independently rounded terms: relative
+L2 error about 2^-9 ~ 2e-3 (measured 1.5e-3 .. 2.0e-3; bound used: 1e-2), and no element off by
+more than 2e-2 of the tensor's largest magnitude (measured: below 4e-3 of it).  bf16 gradient outputs add half a bf16 ulp of the value.
+"""
+import numpy as np
+import pytest
+
+from oracle import attention_backward_oracle as bo
+from paper_2511_02043_amd import inputs, runner
+
+pytestmark = pytest.mark.gpu
+
+REL_L2 = 1e-2
+MAX_REL = 2e-2
+
+
+def run_backward(w, grad_dtype="f32", salt=0):
+    import torch
+    dout = inputs.dout_for(w, salt)
+    db = runner.upload_backward(w, dout, grad_dtype=grad_dtype)
+    db.fwd.run_checked()
+    for t in (db.dq, db.dk, db.dv):
+        t.fill_(float("nan"))
+    db.run_checked()
+    torch.cuda.synchronize()
+    return dout, [t.float().cpu().numpy() for t in (db.dq, db.dk, db.dv)]
+
+
+def compare(w, grad_dtype="f32", label=None):
+    dout, got = run_backward(w, grad_dtype)
+    ref = bo.run_workload_backward(w, dout)
+    res = {}
+    for name, g, r in zip(("dq", "dk", "dv"), got, ref):
+        assert np.all(np.isfinite(g)), f"{label or w.name} {name}: non-finite gradient"
+        diff = g - r
+        # a gradient that is exactly zero in real arithmetic (one visible key: P = 1, dS = 0) comes out
+        # as fp32 rounding noise; the floors below keep the relative measures meaningful there
+        scale = max(float(np.max(np.abs(r))), 1e-3)
+        rel = float(np.sqrt(np.sum(diff * diff)) / max(np.sqrt(np.sum(r * r)), 1e-3 * np.sqrt(r.size)))
+        mx = float(np.max(np.abs(diff)))
+        print(f"{label or w.name} {name}: rel_l2={rel:.3e} max_abs={mx:.3e} (max |ref| {scale:.3e})", flush=True)
+        slack = 2.0 ** -8 * np.abs(r) if grad_dtype == "bf16" else 0.0
+        assert rel <= REL_L2, (name, rel)
+        assert np.all(np.abs(diff) <= MAX_REL * scale + slack), (name, mx, scale)
+        res[name] = (rel, mx)
+    return res
+
+
+CASES = {
+    # several tiles of 64 / 128 plus a ragged tail, both head dims
+    "plain_d64": lambda: inputs.causal_bf16(B=1, H=2, S=333, D=64, causal=False),
+    "plain_d128": lambda: inputs.causal_bf16(B=1, H=2, S=333, D=128, causal=False),
+    "causal_d64": lambda: inputs.causal_bf16(B=2, H=2, S=427, D=64),
+    "causal_d128": lambda: inputs.causal_bf16(B=1, H=3, S=427, D=128),
+    "causal_gqa_d64": lambda: inputs.causal_bf16(B=1, H=8, Hkv=2, S=300, D=64),
+    "causal_gqa_d128": lambda: inputs.causal_bf16(B=1, H=4, Hkv=1, S=257, D=128),
+    "rect_more_keys": lambda: inputs.causal_bf16(B=1, H=2, S=150, Sk=401, D=64, causal=False),
+    "rect_more_rows_causal": lambda: inputs.causal_bf16(B=1, H=2, S=401, Sk=150, D=64),
+    "alibi_d64": lambda: inputs.alibi_bf16(B=1, H=4, S=300, D=64),
+    "alibi_d128": lambda: inputs.alibi_bf16(B=1, H=2, S=200, D=128),
+    "softcap_d64": lambda: inputs.softcap_bf16(B=1, H=2, S=300, D=64, cap=5.0, qscale=3.0),
+    "softcap_d128": lambda: inputs.softcap_bf16(B=1, H=2, S=200, D=128, cap=30.0),
+    "window_doc_d64": lambda: inputs.window_doc_bf16(B=2, H=2, S=500, D=64, window=100, lo=20, hi=150),
+    "window_doc_d128": lambda: inputs.window_doc_bf16(B=1, H=2, S=400, D=128, window=70, lo=20, hi=150),
+    "window_d64": lambda: inputs.grid_bf16("sliding_window", 512, B=1, H=2, window=100),
+    "prefix_d64": lambda: inputs.grid_bf16("prefix_lm", 400, B=1, H=2, prefix=100),
+    "doc_d64": lambda: inputs.grid_bf16("document_mask", 512, B=2, H=2, n_docs=5),
+    "doc_gqa_d64": lambda: inputs.grid_bf16("document_mask", 384, gqa=True, B=1, H=4, n_docs=4),
+    "tiny": lambda: inputs.causal_bf16(B=1, H=1, S=1, D=64),
+    "one_key_many_rows": lambda: inputs.causal_bf16(B=1, H=1, S=70, Sk=1, D=64, causal=False),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_backward_matches_oracle(name):
+    compare(CASES[name](), "f32", label=name)
+
+
+def test_alibi_causal_and_softcap_causal():
+    w = inputs.alibi_bf16(B=1, H=4, S=260, D=64)
+    w.causal = True
+    compare(w, "f32", label="alibi_causal_d64")
+    w = inputs.softcap_bf16(B=1, H=2, S=260, D=64, cap=8.0, qscale=2.0)
+    w.causal = True
+    compare(w, "f32", label="softcap_causal_d64")
+
+
+def test_bf16_gradient_outputs():
+    compare(inputs.causal_bf16(B=1, H=2, S=300, D=128), "bf16", label="causal_d128_bf16_grads")
+    compare(inputs.causal_bf16(B=1, H=4, Hkv=2, S=300, D=64), "bf16", label="causal_gqa_d64_bf16_grads")
+
+
+def test_dead_rows_and_unseen_keys():
+    """Document ids that never match: rows without a visible key get dq = 0 exactly, keys nobody
+    sees get dk = dv = 0 exactly."""
+    w = inputs.causal_bf16(B=1, H=2, S=200, D=64, causal=False)
+    w.q_doc = np.zeros((1, 200), dtype=np.int32)
+    w.q_doc[0, 120:] = 7
+    w.kv_doc = np.zeros((1, 200), dtype=np.int32)
+    w.kv_doc[0, 90:] = 9
+    w.name = "doc_disjoint"
+    dout, (dq, dk, dv) = run_backward(w)
+    assert np.all(dq[0, 0, :, 120:] == 0) and np.any(dq[0, 0, :, :120] != 0)
+    assert np.all(dk[0, 0, :, 90:] == 0) and np.all(dv[0, 0, :, 90:] == 0)
+    compare(w, "f32", label="doc_disjoint")
+
+
+def test_backward_is_reproducible():
+    w = inputs.causal_bf16(B=1, H=4, Hkv=2, S=500, D=64)
+    _, a = run_backward(w)
+    _, b = run_backward(w)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+
+
+def test_backward_error_paths():
+    from paper_2511_02043_amd import binding as fb
+    import torch
+    w = inputs.causal_bf16(B=1, H=1, S=64, D=64)
+    db = runner.upload_backward(w, inputs.dout_for(w))
+    db.fwd.run_checked()
+    f = db.fwd
+    # workspace too small
+    small_ws = torch.empty(16, dtype=torch.uint8, device="cuda:0")
+    aux = fb.aux_desc(workspace=small_ws)
+    st = fb.fl_attn_bwd(f.tq, f.tk, f.tv, f.tout, db.tdout, f.tlse, f.desc, aux, db.tdq, db.tdk, db.tdv)
+    assert st == fb.FL_ERR_WORKSPACE
+    # a variant without a backward specialisation
+    desc = fb.variant_desc(scale=0.125, epilogue=fb.FL_EPI_GATE_SIGMOID)
+    st = fb.fl_attn_bwd(f.tq, f.tk, f.tv, f.tout, db.tdout, f.tlse, desc, db.aux, db.tdq, db.tdk, db.tdv)
+    assert st == fb.FL_ERR_UNSUPPORTED
+    assert not fb.fl_bwd_supported(desc, fb.FL_BF16, 64, 64)
+    assert fb.fl_bwd_supported(f.desc, fb.FL_BF16, 64, 64)
+    assert not fb.fl_bwd_supported(f.desc, fb.FL_BF16, 32, 32)
+    # missing aux
+    st = fb.fl_attn_bwd(f.tq, f.tk, f.tv, f.tout, db.tdout, f.tlse, f.desc, None, db.tdq, db.tdk, db.tdv)
+    assert st == fb.FL_ERR_AUX_MISSING
+    torch.cuda.synchronize()
