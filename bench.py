@@ -118,6 +118,35 @@ def time_config(name, steps, warmup, out_dtype="same", rotate=1):
                 gbs=byt / (ev_ms * 1e-3) / 1e9, dims=w.dims), w
 
 
+BWD_CONFIGS = ["c2_d128", "c2_d64", "c3a_alibi", "c3b_softcap", "c3c_window_doc"]
+
+
+def time_backward(name, steps, warmup):
+    """One fl_attn_bwd call (pre-pass + dQ kernel + dK/dV kernel) per step on the configuration's
+    inputs, bf16 gradients; out and lse come from one untimed forward call.  FLOPs are the five
+    contractions of the backward pass on unmasked pairs (2.5 x the forward count); the kernels
+    recompute the score and dP tiles in both passes, which is not counted."""
+    import torch
+    from paper_2511_02043_amd import inputs, runner
+    w = make_workload(name)
+    flops, _ = flops_and_bytes(w)
+    flops = flops * 5 // 2
+    db = runner.upload_backward(w, inputs.dout_for(w), grad_dtype="bf16")
+    stream = torch.cuda.current_stream().cuda_stream
+    db.fwd.run_checked(stream)
+    for _ in range(warmup):
+        db.run_checked(stream)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        db.run_checked(stream)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    return dict(config=name, flops=flops, ms_per_step=ms, tflops=flops / (ms * 1e-3) / 1e12, dims=w.dims)
+
+
 def gemm_reference(n=8192, reps=50):
     """TFLOP/s of torch.matmul on random bf16 data of size n^3: what the matrix cores sustain under the
     board's power limit with nothing but a contraction to run (context for roofline.frac, not a target)."""
@@ -245,6 +274,8 @@ def main():
     ap.add_argument("--grid", action="store_true",
                     help="time the paper's benchmark grid (7 variants x MHA/GQA x S = 512..16k, 16k tokens, D = 64); "
                          "table on stderr, gpurun_out/bench_grid.json")
+    ap.add_argument("--backward", action="store_true",
+                    help="time fl_attn_bwd on the configurations it covers (table on stderr, gpurun_out/bench_bwd.json)")
     ap.add_argument("--no-gemm-reference", action="store_true",
                     help="skip the bf16 GEMM that shows what the matrix cores sustain on random data")
     ap.add_argument("--tune", default="", help="comma list key=value passed to fl_set_tuning (sweeps)")
@@ -274,6 +305,21 @@ def main():
 
     if args.grid:
         run_grid(args.steps, args.warmup)
+        return
+    if args.backward:
+        names = BWD_CONFIGS if args.all else [args.config]
+        res = []
+        for name in names:
+            r = time_backward(name, args.steps, args.warmup)
+            res.append(r)
+            print(f"# bwd {name}: {r['ms_per_step']:.4f} ms  {r['tflops']:.1f} TFLOP/s  "
+                  f"{100 * r['tflops'] / PEAK_BF16_TFLOPS:.1f}% of bf16 peak", file=sys.stderr, flush=True)
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "bench_bwd.json"), "w") as f:
+            json.dump(res, f, indent=1)
+        print(json.dumps({"metric": "attention bwd TFLOP/s (5 contractions on unmasked pairs)", "unit": "TFLOP/s",
+                          "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "dtype": "bf16",
+                          "data": "synthetic", "results": res}), flush=True)
         return
     results = []
     if args.all:
