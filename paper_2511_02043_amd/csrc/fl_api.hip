@@ -571,6 +571,9 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   p.dkv_f32 = dk->dtype == FL_F32;
   p.n_qtiles = (int)((Sq + be->bm - 1) / be->bm);
   p.n_ktiles = (int)((Sk + be->bm - 1) / be->bm);
+  const int order = g_tuning.order >= 0 ? g_tuning.order : 1;
+  p.order_q = order == 1 && (B * G * H) % 8 == 0;
+  p.order_k = order == 1 && (B * G * Hkv) % 8 == 0;
   const int64_t nb_q = B * G * H * p.n_qtiles, nb_k = B * G * Hkv * p.n_ktiles;
   const int64_t rows = B * G * H * Sq;
   if (nb_q > 0x7fffffffLL || nb_k > 0x7fffffffLL || rows > 0x7fffffff00LL) return fail(FL_ERR_SHAPE, "too many workgroups");

@@ -48,6 +48,7 @@ struct BwdParams {
   float scale, softcap;
   int32_t dq_f32, dkv_f32;         // 1: that output is float, 0: bf16
   int32_t n_qtiles, n_ktiles;      // workgroups per (b, g, h) of the dQ kernel / per (b, g, hkv) of the dK/dV kernel
+  int32_t order_q, order_k;        // 1: XCD-aware workgroup order (whole (b, g, h) problems per XCD) in that kernel
 };
 
 // chunk swizzle of a tile row (see the header comment): an XOR on the 16-byte chunk index that
@@ -91,6 +92,18 @@ struct BwdCfg {
   static_assert(D == 64 || D == 128, "head dims of the backward kernels");
   static_assert(TILE_INSTR % NW == 0, "every wave issues the same number of loads");
   static_assert((NW * RPI) % 16 == 0, "a lane's destination row keeps its residue mod 16");
+};
+
+// Fragment -> LDS offset maps of the pipelined loops.  RowPair: KK row fragments of the block at
+// OFF0, then KK of the block at OFF1.  TrQuad: DB transposed fragments each of (block at OFF0,
+// rows 0..15), (block at OFF1, rows 0..15), (OFF0, rows 16..31), (OFF1, rows 16..31).
+template <int OFF0, int OFF1, int KK>
+struct RowPair {
+  static constexpr int off(int f) { return f < KK ? OFF0 : OFF1; }
+};
+template <int OFF0, int OFF1, int DB, int ROW>
+struct TrQuad {
+  static constexpr int off(int f) { return (((f / DB) % 2) == 0 ? OFF0 : OFF1) + ((f / DB) / 2) * 16 * ROW; }
 };
 
 template <class C>
@@ -192,6 +205,45 @@ struct BwdWave {
       });
     });
   }
+
+  // Generic forms for the software-pipelined loops: O::off(f) is the LDS byte offset of fragment
+  // f (a compile-time function), fragments are read G ahead, body(f, fragment) runs in order.
+  template <class O, int NF, int G, class Body>
+  __device__ __forceinline__ void row_stream_g(const uint32_t (&ra)[C::KK], Body&& body) const {
+    constexpr int NG = NF / G;
+    static_assert(NF % G == 0 && G <= 15, "fragment groups");
+    i32x4 fr[NF];
+    static_for<0, G>([&](auto f) __attribute__((always_inline)) { read_b128<O::off(f)>(fr[f], ra[f % KK]); });
+    static_for<0, NG>([&](auto gc) __attribute__((always_inline)) {
+      constexpr int g = gc;
+      if constexpr (g + 1 < NG)
+        static_for<(g + 1) * G, (g + 2) * G>([&](auto f) __attribute__((always_inline)) { read_b128<O::off(f)>(fr[f], ra[f % KK]); });
+      wait_lds<(g + 1 < NG) ? G : 0>();
+      static_for<g * G, (g + 1) * G>([&](auto f) __attribute__((always_inline)) { body(f, __builtin_bit_cast(bf16x8, fr[f])); });
+    });
+  }
+  template <class O, int NF, int G, class Body>
+  __device__ __forceinline__ void tr_stream_g(const uint32_t (&ta)[C::DB][2], Body&& body) const {
+    constexpr int NG = NF / G;
+    static_assert(NF % G == 0 && 2 * G <= 15, "fragment groups");
+    i32x2 lo[NF], hi[NF];
+    static_for<0, G>([&](auto f) __attribute__((always_inline)) {
+      read_tr<O::off(f)>(lo[f], ta[f % DB][0]);
+      read_tr<O::off(f)>(hi[f], ta[f % DB][1]);
+    });
+    static_for<0, NG>([&](auto gc) __attribute__((always_inline)) {
+      constexpr int g = gc;
+      if constexpr (g + 1 < NG)
+        static_for<(g + 1) * G, (g + 2) * G>([&](auto f) __attribute__((always_inline)) {
+          read_tr<O::off(f)>(lo[f], ta[f % DB][0]);
+          read_tr<O::off(f)>(hi[f], ta[f % DB][1]);
+        });
+      wait_lds<(g + 1 < NG) ? 2 * G : 0>();
+      static_for<g * G, (g + 1) * G>([&](auto f) __attribute__((always_inline)) {
+        body(f, __builtin_bit_cast(bf16x8, (i32x4){lo[f][0], lo[f][1], hi[f][0], hi[f][1]}));
+      });
+    });
+  }
 };
 
 // One 64-lane x 16-byte direct load instruction `inst` of a [rows][D] tile whose row 0 is at
@@ -283,8 +335,17 @@ bwd_dq_kernel(const BwdParams p) {
 
   // grid decode: longest q-tiles (under a causal mask) first
   const int nq = p.n_qtiles;
-  const int qt = nq - 1 - (int)(blockIdx.x % nq);
-  const int bh = blockIdx.x / nq;
+  int qt, bh;
+  if (p.order_q == 1) {
+    // consecutive workgroup ids go round-robin to the 8 XCDs: give each XCD whole heads, so that a
+    // head's K / V tiles stay in one L2 (the host checks that the head count is a multiple of 8)
+    const int idx = blockIdx.x >> 3;
+    bh = (idx / nq) * 8 + (blockIdx.x & 7);
+    qt = nq - 1 - idx % nq;
+  } else {
+    qt = nq - 1 - (int)(blockIdx.x % nq);
+    bh = blockIdx.x / nq;
+  }
   const int h = bh % p.H, g = (bh / p.H) % p.G, b = bh / (p.H * p.G);
   const int hk = h / (p.H / p.Hkv);
   const int i0 = qt * C::BM, iw = i0 + 32 * wave;
@@ -391,18 +452,28 @@ bwd_dq_kernel(const BwdParams p) {
       uint32_t dsw[8];
 #pragma unroll
       for (int r2 = 0; r2 < 8; ++r2) {
-        float dsv[2];
+        float dsv[2], pr[2];
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
           const int r = 2 * r2 + e;
           const int j = jb + 8 * (r >> 2) + (r & 3);
           float fac;
           const float a = replay_score<C::MOD>(s[r], c_scale, lse2, p.softcap, slope2, (float)(i - j), fac);
-          float pr = fast_exp2(a);
-          if (need_mask && hidden<MASK>(i, j, p.Sq, p.Sk, p.window, p.prefix, qdoc, (MASK & kMaskDoc) ? kd[r] : 0)) pr = 0.f;
-          dsv[e] = pr * (dp[r] - delta);
+          pr[e] = fast_exp2(a);
+          dsv[e] = dp[r] - delta;
           if constexpr (C::MOD == kModSoftcap) dsv[e] *= fac;
         }
+        if (need_mask) {                           // uniform; kept a branch: most tiles need no mask
+          asm volatile("");
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            const int r = 2 * r2 + e;
+            const int j = jb + 8 * (r >> 2) + (r & 3);
+            if (hidden<MASK>(i, j, p.Sq, p.Sk, p.window, p.prefix, qdoc, (MASK & kMaskDoc) ? kd[r] : 0)) pr[e] = 0.f;
+          }
+        }
+        dsv[0] *= pr[0];
+        dsv[1] *= pr[1];
         dsw[r2] = pack_bf16(dsv[0], dsv[1]);
       }
       w.template tr_stream<ST + nb * 32 * ROW>([&](auto fc, bf16x8 a) __attribute__((always_inline)) {
@@ -471,8 +542,15 @@ bwd_dkdv_kernel(const BwdParams p) {
 
   // grid decode: key tiles in increasing order (under a causal mask the first ones see the most rows)
   const int nk = p.n_ktiles;
-  const int kt = blockIdx.x % nk;
-  const int bh = blockIdx.x / nk;
+  int kt, bh;
+  if (p.order_k == 1) {                            // whole key/value heads per XCD: their Q / dO tiles stay in one L2
+    const int idx = blockIdx.x >> 3;
+    bh = (idx / nk) * 8 + (blockIdx.x & 7);
+    kt = idx % nk;
+  } else {
+    kt = blockIdx.x % nk;
+    bh = blockIdx.x / nk;
+  }
   const int hk = bh % p.Hkv, g = (bh / p.Hkv) % p.G, b = bh / (p.Hkv * p.G);
   const int group = p.H / p.Hkv;
   const int j0 = kt * C::BM, jw = j0 + 32 * wave;
@@ -564,98 +642,156 @@ bwd_dkdv_kernel(const BwdParams p) {
     }
   };
 
-  auto compute = [&](auto stage_c, int it) __attribute__((always_inline)) {
-    constexpr int ST = decltype(stage_c)::value * C::STAGE_KV;
+  // ---- software pipeline over 32-row query blocks.  Step n owns block n (scores and dP in
+  // registers) and its successor:
+  //   phase A:  S, dP of block n + 1 on the matrix core   ||   P, dS of the first 16 rows of block n
+  //   phase B:  dV += dO^T P, dK += Q^T dS of block n, rows 0..15 first   ||   P, dS of rows 16..31
+  // so the matrix core and the vector ALU of a wave have independent work at the same time.  The
+  // Q / dO tiles cycle through a ring of three LDS stages: the tile after next is requested when
+  // every wave has left the tile before the current one.
+  struct Blk {
+    f32x16 s, dp;
+  };
+  constexpr int NSTAGE = 3;
+  // one step: block QB of the tile in the LDS stage at byte offset base_c is current, block QN of
+  // the tile at base_n is next (the same tile, or row block 0 of the following one)
+  auto step = [&](auto qb_c, auto qn_c, uint32_t base_c, uint32_t base_n, int it, bool first, Blk& cur, Blk& nxt) __attribute__((always_inline)) {
+    constexpr int QB = decltype(qb_c)::value, QN = decltype(qn_c)::value;
     const int t = t_lo + it % nt, h = hk * group + it / nt;
-    const int i0 = t * BN;
+    const int ib = t * BN + 32 * QB;
     const float slope2 = C::MOD == kModAlibi ? p.alibi_slopes[h] * kLog2e : 0.f;
-    const uint32_t stat_addr = (uint32_t)(4 * w.half) * 4;     // this half's first row of a register quad
-    static_for<0, NB>([&](auto qbc) __attribute__((always_inline)) {
-      constexpr int qb = decltype(qbc)::value;
-      const int ib = i0 + 32 * qb;
-      // this block's 32 rows against the wave's 32 keys under the positional masks (uniform)
-      const int cls = classify_block(POS, ib, ib + 31, jw, jw + 31, p.Sk, p.window, p.prefix, make_int2(0, 0),
-                                     make_int2(0, 0));
-      if (cls == kSkip || ib >= p.Sq) return;      // nothing visible: P = dS = 0
-      const bool need_mask = (MASK & kMaskDoc) != 0 || ib + 31 >= p.Sq || cls != kFull;
-      // row statistics of the block's 16 rows of this half: four quads of lse2, four of delta
-      i32x4 st_l[4], st_d[4];
-      static_for<0, 4>([&](auto qc) __attribute__((always_inline)) {
+    const int cls = classify_block(POS, ib, ib + 31, jw, jw + 31, p.Sk, p.window, p.prefix, make_int2(0, 0), make_int2(0, 0));
+    const bool need_mask = (MASK & kMaskDoc) != 0 || ib + 31 >= p.Sq || cls != kFull;
+    uint32_t ra_n[KK], ta_c[DB][2];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) ra_n[kk] = w.ra[kk] + base_n;
+#pragma unroll
+    for (int d = 0; d < DB; ++d) {
+      ta_c[d][0] = w.ta[d][0] + base_c;
+      ta_c[d][1] = w.ta[d][1] + base_c;
+    }
+    // row statistics of the current block's 16 rows of this half: quads of lse2 and of delta, read
+    // shortly before the element pairs that use them
+    const uint32_t stat_addr = (uint32_t)(4 * w.half) * 4 + base_c;
+    i32x4 st_l[4], st_d[4];
+    auto read_stats = [&](auto q_lo, auto q_hi) __attribute__((always_inline)) {   // quads [q_lo, q_hi): rows 8*q .. 8*q + 3 (+ 4*half)
+      static_for<decltype(q_lo)::value, decltype(q_hi)::value>([&](auto qc) __attribute__((always_inline)) {
         constexpr int q4 = decltype(qc)::value;
-        W::template read_b128<ST + 2 * C::TILE + (32 * qb + 8 * q4) * 4>(st_l[q4], stat_addr);
-        W::template read_b128<ST + 2 * C::TILE + C::STAT + (32 * qb + 8 * q4) * 4>(st_d[q4], stat_addr);
+        W::template read_b128<2 * C::TILE + (32 * QB + 8 * q4) * 4>(st_l[q4], stat_addr);
+        W::template read_b128<2 * C::TILE + C::STAT + (32 * QB + 8 * q4) * 4>(st_d[q4], stat_addr);
       });
-      f32x16 s = W::zero16(), dp = W::zero16();
-      w.template row_stream<ST + qb * 32 * ROW>([&](auto kk, bf16x8 a) __attribute__((always_inline)) {
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[kk], s, 0, 0, 0);
-      });
-      w.template row_stream<ST + C::TILE + qb * 32 * ROW>([&](auto kk, bf16x8 a) __attribute__((always_inline)) {
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, vf[kk], dp, 0, 0, 0);
-      });
-      const int irow = ib + 4 * w.half;            // query row of register 0
-      int qd[16];
-      if constexpr ((MASK & kMaskDoc) != 0) {
-        const int32_t* qdoc = p.q_doc + (int64_t)b * p.Sq;
+    };
+    if (first) {                                   // the very first block: its scores are not there yet
+      uint32_t ra_c[KK];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int i = irow + 8 * (r >> 2) + (r & 3);
-          qd[r] = qdoc[i < p.Sq ? i : p.Sq - 1];
-        }
+      for (int kk = 0; kk < KK; ++kk) ra_c[kk] = w.ra[kk] + base_c;
+      cur.s = W::zero16();
+      cur.dp = W::zero16();
+      w.template row_stream_g<RowPair<QB * 32 * ROW, C::TILE + QB * 32 * ROW, KK>, 2 * KK, 2>(
+          ra_c, [&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+            constexpr int f = decltype(fc)::value;
+            if constexpr (f < KK) cur.s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[f], cur.s, 0, 0, 0);
+            else cur.dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, vf[f - KK], cur.dp, 0, 0, 0);
+          });
+    }
+    read_stats(std::integral_constant<int, 0>(), std::integral_constant<int, 2>());   // for the pairs of phase A
+    const int irow = ib + 4 * w.half;              // query row of register 0
+    int qd[16];
+    if constexpr ((MASK & kMaskDoc) != 0) {
+      const int32_t* qdoc = p.q_doc + (int64_t)b * p.Sq;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int i = irow + 8 * (r >> 2) + (r & 3);
+        qd[r] = qdoc[i < p.Sq ? i : p.Sq - 1];
       }
-      uint32_t pw[8], dsw[8];
+    }
+    uint32_t pw[8], dsw[8];
+    auto ew_pair = [&](int r2) __attribute__((always_inline)) {      // P and dS of registers 2*r2, 2*r2 + 1
+      float pv[2], dsv[2];
 #pragma unroll
-      for (int r2 = 0; r2 < 8; ++r2) {
-        float pv[2], dsv[2];
+      for (int e = 0; e < 2; ++e) {
+        const int r = 2 * r2 + e;
+        const int i = irow + 8 * (r >> 2) + (r & 3);
+        const float lse2 = __int_as_float(st_l[r >> 2][r & 3]), delta = __int_as_float(st_d[r >> 2][r & 3]);
+        float fac;
+        const float a = replay_score<C::MOD>(cur.s[r], c_scale, lse2, p.softcap, slope2, (float)(i - j), fac);
+        pv[e] = fast_exp2(a);
+        dsv[e] = cur.dp[r] - delta;
+        if constexpr (C::MOD == kModSoftcap) dsv[e] *= fac;
+      }
+      if (need_mask) {                             // uniform; kept a branch: most blocks need no mask
+        asm volatile("");
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
           const int r = 2 * r2 + e;
           const int i = irow + 8 * (r >> 2) + (r & 3);
-          const float lse2 = __int_as_float(st_l[r >> 2][r & 3]), delta = __int_as_float(st_d[r >> 2][r & 3]);
-          float fac;
-          const float a = replay_score<C::MOD>(s[r], c_scale, lse2, p.softcap, slope2, (float)(i - j), fac);
-          float pr = fast_exp2(a);
-          if (need_mask && hidden<MASK>(i, j, p.Sq, p.Sk, p.window, p.prefix, (MASK & kMaskDoc) ? qd[r] : 0, kdoc)) pr = 0.f;
-          pv[e] = pr;
-          dsv[e] = pr * (dp[r] - delta);
-          if constexpr (C::MOD == kModSoftcap) dsv[e] *= fac;
+          if (hidden<MASK>(i, j, p.Sq, p.Sk, p.window, p.prefix, (MASK & kMaskDoc) ? qd[r] : 0, kdoc)) pv[e] = 0.f;
         }
-        pw[r2] = pack_bf16(pv[0], pv[1]);
-        dsw[r2] = pack_bf16(dsv[0], dsv[1]);
       }
-      w.template tr_stream<ST + C::TILE + qb * 32 * ROW>([&](auto fc, bf16x8 a) __attribute__((always_inline)) {
-        constexpr int f = decltype(fc)::value, d = f % DB, ks = f / DB;
-        const bf16x8 bop = __builtin_bit_cast(
-            bf16x8, (i32x4){(int)pw[4 * ks], (int)pw[4 * ks + 1], (int)pw[4 * ks + 2], (int)pw[4 * ks + 3]});
-        dv[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bop, dv[d], 0, 0, 0);
-      });
-      w.template tr_stream<ST + qb * 32 * ROW>([&](auto fc, bf16x8 a) __attribute__((always_inline)) {
-        constexpr int f = decltype(fc)::value, d = f % DB, ks = f / DB;
-        const bf16x8 bop = __builtin_bit_cast(
-            bf16x8, (i32x4){(int)dsw[4 * ks], (int)dsw[4 * ks + 1], (int)dsw[4 * ks + 2], (int)dsw[4 * ks + 3]});
-        dk[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bop, dk[d], 0, 0, 0);
-      });
-    });
+      dsv[0] *= pv[0];
+      dsv[1] *= pv[1];
+      pw[r2] = pack_bf16(pv[0], pv[1]);
+      dsw[r2] = pack_bf16(dsv[0], dsv[1]);
+      asm volatile("" : "+v"(pw[r2]), "+v"(dsw[r2]));               // stays where it is scheduled
+    };
+    // phase A
+    nxt.s = W::zero16();
+    nxt.dp = W::zero16();
+    w.template row_stream_g<RowPair<QN * 32 * ROW, C::TILE + QN * 32 * ROW, KK>, 2 * KK, 2>(
+        ra_n, [&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+          constexpr int f = decltype(fc)::value;
+          if constexpr (f < KK) nxt.s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[f], nxt.s, 0, 0, 0);
+          else nxt.dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, vf[f - KK], nxt.dp, 0, 0, 0);
+          constexpr int per = (2 * KK) / 4;        // MFMAs per element pair (pairs 0..3 in this phase)
+          if constexpr (f % per == per - 1) ew_pair(f / per);
+          __builtin_amdgcn_sched_barrier(0);
+        });
+    // phase B
+    read_stats(std::integral_constant<int, 2>(), std::integral_constant<int, 4>());   // covered by the first wait below
+    w.template tr_stream_g<TrQuad<C::TILE + QB * 32 * ROW, QB * 32 * ROW, DB, ROW>, 4 * DB, 2>(
+        ta_c, [&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+          constexpr int f = decltype(fc)::value, d = f % DB, grp = f / DB, ks = grp / 2;
+          if constexpr (grp % 2 == 0) {
+            const bf16x8 bop = __builtin_bit_cast(
+                bf16x8, (i32x4){(int)pw[4 * ks], (int)pw[4 * ks + 1], (int)pw[4 * ks + 2], (int)pw[4 * ks + 3]});
+            dv[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bop, dv[d], 0, 0, 0);
+          } else {
+            const bf16x8 bop = __builtin_bit_cast(
+                bf16x8, (i32x4){(int)dsw[4 * ks], (int)dsw[4 * ks + 1], (int)dsw[4 * ks + 2], (int)dsw[4 * ks + 3]});
+            dk[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bop, dk[d], 0, 0, 0);
+          }
+          constexpr int per = (2 * DB) / 4;        // MFMAs per element pair (pairs 4..7 during the rows-0..15 half)
+          if constexpr (f < 2 * DB && f % per == per - 1) ew_pair(4 + f / per);
+          __builtin_amdgcn_sched_barrier(0);
+        });
   };
+  static_assert(NB == 2, "a tile is two row blocks: the two score register sets swap roles twice per tile");
 
-  int it = next_item(0);
-  if (it < n_items) {
-    load_item(it, 0);
+  int it0 = next_item(0);
+  if (it0 < n_items) {
+    int it1 = next_item(it0 + 1);
+    int it2 = it1 < n_items ? next_item(it1 + 1) : n_items;
+    load_item(it0, 0);
+    if (it1 < n_items) load_item(it1, 1);
     __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0)
     __syncthreads();
-    while (true) {
-      bool done = false;
-      static_for<0, 2>([&](auto sc) __attribute__((always_inline)) {
-        if (!done) {
-          const int in = next_item(it + 1);
-          if (in < n_items) load_item(in, 1 - decltype(sc)::value);
-          compute(sc, it);
-          __builtin_amdgcn_s_waitcnt(0x0F70);
-          __syncthreads();
-          it = in;
-          done = it >= n_items;
-        }
-      });
-      if (done) break;
+    if (it2 < n_items) load_item(it2, 2);
+    Blk ba, bb;
+    int stage = 0;                                 // ring stage of the current tile
+    bool first = true;
+    while (it0 < n_items) {
+      const int stage_n = stage + 1 == NSTAGE ? 0 : stage + 1;
+      const uint32_t base_c = stage * C::STAGE_KV, base_n = stage_n * C::STAGE_KV;
+      step(std::integral_constant<int, 0>(), std::integral_constant<int, 1>(), base_c, base_c, it0, first, ba, bb);
+      step(std::integral_constant<int, 1>(), std::integral_constant<int, 0>(), base_c, base_n, it0, false, bb, ba);
+      first = false;
+      __builtin_amdgcn_s_waitcnt(0x0F70);          // the tile after next has landed ...
+      __syncthreads();                             // ... for everyone, and everyone has left this tile
+      it0 = it1;
+      it1 = it2;
+      it2 = it2 < n_items ? next_item(it2 + 1) : n_items;
+      if (it2 < n_items) load_item(it2, stage);
+      stage = stage_n;
     }
   }
 

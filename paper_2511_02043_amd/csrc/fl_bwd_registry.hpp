@@ -48,7 +48,7 @@ template <class C>
 hipError_t launch_bwd_dkdv(const BwdParams& p, int nblocks, hipStream_t stream) {
   hipError_t e = raise_lds_limit(bwd_dkdv_kernel<C>);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(bwd_dkdv_kernel<C>, dim3(nblocks), dim3(C::NT), 2 * C::STAGE_KV, stream, p);
+  hipLaunchKernelGGL(bwd_dkdv_kernel<C>, dim3(nblocks), dim3(C::NT), 3 * C::STAGE_KV, stream, p);
   return hipGetLastError();
 }
 
