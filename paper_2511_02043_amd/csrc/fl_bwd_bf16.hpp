@@ -89,6 +89,8 @@ struct BwdCfg {
   static constexpr int STAGE_KV = 2 * TILE + 2 * STAT;   // Q, dO, lse2, delta
   static constexpr int TILE_INSTR = TILE / 1024;   // 64-lane x 16-byte direct loads per tile
   static constexpr int RPI = 1024 / ROW;           // tile rows per load instruction
+  static constexpr int GR = WPE == 1 ? 4 : 2;      // dK/dV pipeline: row fragments read ahead (a lone wave per SIMD hides LDS latency itself)
+  static constexpr int GT = WPE == 1 ? 4 : 2;      // dK/dV pipeline: transposed fragments read ahead
   static_assert(D == 64 || D == 128, "head dims of the backward kernels");
   static_assert(TILE_INSTR % NW == 0, "every wave issues the same number of loads");
   static_assert((NW * RPI) % 16 == 0, "a lane's destination row keeps its residue mod 16");
@@ -737,7 +739,7 @@ bwd_dkdv_kernel(const BwdParams p) {
     // phase A
     nxt.s = W::zero16();
     nxt.dp = W::zero16();
-    w.template row_stream_g<RowPair<QN * 32 * ROW, C::TILE + QN * 32 * ROW, KK>, 2 * KK, 2>(
+    w.template row_stream_g<RowPair<QN * 32 * ROW, C::TILE + QN * 32 * ROW, KK>, 2 * KK, C::GR>(
         ra_n, [&](auto fc, bf16x8 a) __attribute__((always_inline)) {
           constexpr int f = decltype(fc)::value;
           if constexpr (f < KK) nxt.s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[f], nxt.s, 0, 0, 0);
@@ -748,7 +750,7 @@ bwd_dkdv_kernel(const BwdParams p) {
         });
     // phase B
     read_stats(std::integral_constant<int, 2>(), std::integral_constant<int, 4>());   // covered by the first wait below
-    w.template tr_stream_g<TrQuad<C::TILE + QB * 32 * ROW, QB * 32 * ROW, DB, ROW>, 4 * DB, 2>(
+    w.template tr_stream_g<TrQuad<C::TILE + QB * 32 * ROW, QB * 32 * ROW, DB, ROW>, 4 * DB, C::GT>(
         ta_c, [&](auto fc, bf16x8 a) __attribute__((always_inline)) {
           constexpr int f = decltype(fc)::value, d = f % DB, grp = f / DB, ks = grp / 2;
           if constexpr (grp % 2 == 0) {
