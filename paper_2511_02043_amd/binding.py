@@ -61,6 +61,9 @@ def lib() -> C.CDLL:
             raise FileNotFoundError(
                 f"{LIB_PATH} not found: build it with __graft_entry__.build() "
                 "(or make -C paper_2511_02043_amd/csrc); there is no fallback path")
+        # PyTorch ships its own HIP runtime; load it first, so that this process has one runtime
+        # (the library's launches and torch's allocations must see the same devices and streams)
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         TP = C.POINTER(fl_tensor)
         L.fl_attn_fwd.restype = C.c_int

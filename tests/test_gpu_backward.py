@@ -110,6 +110,33 @@ def test_dead_rows_and_unseen_keys():
     compare(w, "f32", label="doc_disjoint")
 
 
+def test_full_size_c2_one_head():
+    """The benchmark's default workload (causal bf16 B=4 H=16 S=8192 D=128) in the launch
+    configuration bench.py times, bf16 gradients; one (batch, head) problem is checked element
+    by element against the oracle (the oracle's fp64 [8192, 8192] matrices for all 64 heads
+    would take minutes), and every gradient has to be finite."""
+    import torch
+    w = inputs.causal_bf16()
+    dout = inputs.dout_for(w)
+    db = runner.upload_backward(w, dout, grad_dtype="bf16")
+    db.fwd.run_checked()
+    db.run_checked()
+    torch.cuda.synchronize()
+    for t in (db.dq, db.dk, db.dv):
+        assert bool(torch.isfinite(t).all())
+    b, h = 2, 13
+    sl = lambda x: np.ascontiguousarray(x[b:b + 1, :, h:h + 1])
+    ref = bo.attention_backward(sl(w.q), sl(w.k), sl(w.v), sl(dout), scale=w.scale, causal=True)
+    for name, t, r in zip(("dq", "dk", "dv"), (db.dq, db.dk, db.dv), ref):
+        g = t[b:b + 1, :, h:h + 1].float().cpu().numpy()
+        diff = g - r
+        rel = float(np.sqrt(np.sum(diff * diff) / np.sum(r * r)))
+        scale = float(np.max(np.abs(r)))
+        print(f"c2 full size {name}: rel_l2={rel:.3e} max_abs={np.max(np.abs(diff)):.3e} (max |ref| {scale:.3e})", flush=True)
+        assert rel <= REL_L2
+        assert np.all(np.abs(diff) <= MAX_REL * scale + 2.0 ** -8 * np.abs(r))
+
+
 def test_backward_is_reproducible():
     w = inputs.causal_bf16(B=1, H=4, Hkv=2, S=500, D=64)
     _, a = run_backward(w)
