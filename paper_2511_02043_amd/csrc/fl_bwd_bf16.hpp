@@ -108,6 +108,15 @@ struct TrQuad {
   static constexpr int off(int f) { return (((f / DB) % 2) == 0 ? OFF0 : OFF1) + ((f / DB) / 2) * 16 * ROW; }
 };
 
+template <int OFF>
+struct RowOne {                                    // KK row fragments of the block at OFF
+  static constexpr int off(int) { return OFF; }
+};
+template <int OFF, int DB, int ROW>
+struct TrOne {                                     // DB transposed fragments of rows 0..15, then DB of rows 16..31
+  static constexpr int off(int f) { return OFF + (f / DB) * 16 * ROW; }
+};
+
 template <class C>
 struct BwdWave {
   static constexpr int D = C::D, KK = C::KK, DB = C::DB, ROW = C::ROW;
@@ -160,6 +169,10 @@ struct BwdWave {
       const uint32_t a = addr + (uint32_t)OFF;
       asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(dst) : "v"(a) : "memory");
     }
+  }
+  template <int OFF>
+  static __device__ __forceinline__ void write_b128(uint32_t addr, i32x4 v) {
+    asm volatile("ds_write_b128 %0, %1 offset:%2" : : "v"(addr), "v"(v), "n"(OFF) : "memory");
   }
   template <int N>
   static __device__ __forceinline__ void wait_lds() {
@@ -816,6 +829,372 @@ bwd_dkdv_kernel(const BwdParams p) {
           *(uint2*)((uint16_t*)p.dv.ptr + vrow + ch) = make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3));
         }
       }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// dK, dV with specialised waves: the same contractions as bwd_dkdv_kernel, for head dims whose
+// accumulators (32 keys x D channels x two gradients in fp32) leave no room for a second wave on
+// the SIMD.  Eight waves per workgroup; waves w and w + 4 own the same 32 keys and share a SIMD:
+//   wave w     ("P wave"):   S = Q K^T, P = exp2(..), dV += dO^T P; hands P (times the soft-cap
+//                            derivative) to its partner through LDS, fp32
+//   wave w + 4 ("dS wave"):  dP = dO V^T, dS = P * (dP - delta) one block later, dK += Q^T dS
+// Each does half of the matrix work of a block and holds one accumulator set, so both fit the
+// register budget of two waves per SIMD and fill each other's stalls.  One workgroup barrier per
+// 32-row block hands the P blocks over (two exchange buffers per wave pair).
+// ------------------------------------------------------------------------------------------------
+template <class C>
+__global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+bwd_dkdv_ws_kernel(const BwdParams p) {
+  constexpr int D = C::D, BN = C::BN, NB = C::NB, KK = C::KK, DB = C::DB, ROW = C::ROW;
+  constexpr uint32_t MASK = C::MASK;
+  constexpr uint32_t POS = MASK & ~kMaskDoc;
+  constexpr int NWS = 8;                           // waves of the workgroup
+  constexpr int NSTAGE = 3;
+  constexpr int XBUF = 64 * 16 * 4;                // one exchange buffer: 16 floats per lane, [quad][lane][4]
+  constexpr int XCH = NSTAGE * C::STAGE_KV;        // exchange buffers [key group][2] follow the tile ring
+  constexpr int PPM = 8 / KK;                      // element pairs per MFMA of phase 1
+  static_assert(NB == 2 && BN == 64, "two row blocks per tile");
+  static_assert(C::TILE_INSTR % NWS == 0, "every wave issues the same number of loads");
+  typedef BwdWave<C> W;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int role = wave >> 2, kg = wave & 3;       // 0: P wave, 1: dS wave; key group
+  W w;
+  w.init(tid & 63);
+  const int lane = w.lane;
+
+  const int nk = p.n_ktiles;
+  int kt, bh;
+  if (p.order_k == 1) {                            // whole key/value heads per XCD: their Q / dO tiles stay in one L2
+    const int idx = blockIdx.x >> 3;
+    bh = (idx / nk) * 8 + (blockIdx.x & 7);
+    kt = idx % nk;
+  } else {
+    kt = blockIdx.x % nk;
+    bh = blockIdx.x / nk;
+  }
+  const int hk = bh % p.Hkv, g = (bh / p.Hkv) % p.G, b = bh / (p.Hkv * p.G);
+  const int group = p.H / p.Hkv;
+  const int j0 = kt * C::BM, jw = j0 + 32 * kg;
+  const int j = jw + w.col, jc = j < p.Sk ? j : p.Sk - 1;
+  const float c_scale = p.scale * kLog2e;
+
+  // query rows that can see the workgroup's keys; q-tile skipping for document masks
+  const int j_last = (j0 + C::BM < p.Sk ? j0 + C::BM : p.Sk) - 1;
+  int q_lo, q_hi;
+  query_range(MASK, j0, j_last, p.Sq, p.window, p.prefix, q_lo, q_hi);
+  const int t_lo = q_lo / BN, t_hi = (q_hi + BN - 1) / BN;
+  const int nt = t_hi - t_lo;                      // q-tiles per head
+  const int n_items = nt > 0 ? nt * group : 0;     // (head of the group, q-tile), head-major
+  const int nqs = (p.Sq + kSumBlock - 1) / kSumBlock;
+  int2 ks_wg = make_int2(0, 0);
+  if constexpr ((MASK & kMaskDoc) != 0) {
+    const int nks = (p.Sk + kSumBlock - 1) / kSumBlock;
+    const int2* ksum = p.kv_sum + (int64_t)b * nks;
+    ks_wg = ksum[j0 / kSumBlock];
+    for (int u = 1; u < C::BM / kSumBlock; ++u)
+      if (j0 / kSumBlock + u < nks) {
+        const int2 x = ksum[j0 / kSumBlock + u];
+        ks_wg.x = min(ks_wg.x, x.x);
+        ks_wg.y = max(ks_wg.y, x.y);
+      }
+  }
+  auto next_item = [&](int it) __attribute__((always_inline)) -> int {
+    if constexpr ((MASK & kMaskDoc) != 0) {
+      const int2* qsum = p.q_sum + (int64_t)b * nqs;
+      while (it < n_items) {
+        const int t = t_lo + it % nt;
+        int2 qs = qsum[min(t * NB, nqs - 1)];
+        for (int u = 1; u < NB; ++u)
+          if (t * NB + u < nqs) {
+            const int2 x = qsum[t * NB + u];
+            qs.x = min(qs.x, x.x);
+            qs.y = max(qs.y, x.y);
+          }
+        const int q_last = (t * BN + BN < p.Sq ? t * BN + BN : p.Sq) - 1;
+        if (classify_block(MASK, t * BN, q_last, j0, j0 + C::BM - 1, p.Sk, p.window, p.prefix, qs, ks_wg) != kSkip) break;
+        ++it;
+      }
+    }
+    return it;
+  };
+  auto load_item = [&](int it, int stage) __attribute__((always_inline)) {
+    const int t = t_lo + it % nt, h = hk * group + it / nt;
+    const int nvalid = min(BN, p.Sq - t * BN);
+    unsigned char* st = lds_raw + stage * C::STAGE_KV;
+    const unsigned char* qb = (const unsigned char*)((const uint16_t*)p.q.ptr + b * p.q.sb + g * p.q.sg + h * p.q.sh + (int64_t)(t * BN) * p.q.ss);
+    const unsigned char* db = (const unsigned char*)((const uint16_t*)p.dout.ptr + b * p.dout.sb + g * p.dout.sg + h * p.dout.sh + (int64_t)(t * BN) * p.dout.ss);
+#pragma unroll
+    for (int u = 0; u < C::TILE_INSTR / NWS; ++u) {
+      tile_load_instr<C>(qb, p.q.ss * 2, nvalid, wave + u * NWS, lane, st);
+      tile_load_instr<C>(db, p.dout.ss * 2, nvalid, wave + u * NWS, lane, st + C::TILE);
+    }
+    if (wave < 2) {                                // row statistics, 4 bytes per lane: wave 0 lse2, wave 1 delta
+      const int64_t srow = ((int64_t)(b * p.G + g) * p.H + h) * p.Sq;
+      const int row = t * BN + (lane < nvalid ? lane : nvalid - 1);
+      const float* src = (wave == 0 ? p.lse2 : p.delta) + srow + row;
+      lds_void* dst = (lds_void*)(st + 2 * C::TILE + wave * C::STAT);
+      __builtin_amdgcn_global_load_lds((global_cvoid*)src, dst, 4, 0, 0);
+    }
+  };
+  // end of an iteration: this wave's LDS traffic (and, when `loads`, its tile loads) is complete, then
+  // the workgroup barrier.  No fence beyond that: every LDS access of the loop is issued by hand.
+  auto iteration_end = [&](bool loads) __attribute__((always_inline)) {
+    if (loads) __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
+    else __builtin_amdgcn_s_waitcnt(0xC07F);         // lgkmcnt(0)
+    asm volatile("" ::: "memory");                   // no memory access moves across the barrier at compile time
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
+
+  // window of the tile list: items at list positions P - 1, P, P + 1, P + 2 (n_items = none)
+  int itm1 = n_items, it0 = next_item(0);
+  int itp1 = it0 < n_items ? next_item(it0 + 1) : n_items;
+  int itp2 = itp1 < n_items ? next_item(itp1 + 1) : n_items;
+  if (it0 < n_items) load_item(it0, 0);
+  if (itp1 < n_items) load_item(itp1, 1);
+  if (itp2 < n_items) load_item(itp2, 2);
+  iteration_end(true);
+  int s0 = 0;                                      // ring stage of position P
+  const uint32_t xaddr = XCH + kg * (2 * XBUF) + lane * 16;   // this lane's slot in exchange buffer 0 of its wave pair
+  const uint32_t stat_addr = (uint32_t)(4 * w.half) * 4;
+
+  if (role == 0) {
+    // ================= P wave =================
+    bf16x8 kf[KK];
+    {
+      const uint16_t* kp = (const uint16_t*)p.k.ptr + b * p.k.sb + g * p.k.sg + hk * p.k.sh + (int64_t)jc * p.k.ss;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) kf[kk] = *(const bf16x8*)(kp + 16 * kk + 8 * w.half);
+    }
+    int kdoc = 0;
+    if constexpr ((MASK & kMaskDoc) != 0) kdoc = p.kv_doc[(int64_t)b * p.Sk + jc];
+    f32x16 dv[DB];
+#pragma unroll
+    for (int d = 0; d < DB; ++d) dv[d] = W::zero16();
+    f32x16 sa = W::zero16(), sb = W::zero16();
+    auto scores = [&](auto off_c, uint32_t base, f32x16& dst) __attribute__((always_inline)) {   // S of one block, no overlap
+      uint32_t ra_b[KK];
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) ra_b[kk] = w.ra[kk] + base;
+      dst = W::zero16();
+      w.template row_stream_g<RowOne<decltype(off_c)::value>, KK, 2>(ra_b, [&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+        dst = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[decltype(fc)::value], dst, 0, 0, 0);
+      });
+    };
+    // block QB of item `it` (stage offset base_c) is current (scores in cur); the scores of block QN at
+    // base_n go to nxt; P of the current block goes to exchange buffer XB
+    auto p_iter = [&](auto qb_c, auto qn_c, auto xb_c, uint32_t base_c, uint32_t base_n, int it, f32x16& cur, f32x16& nxt) __attribute__((always_inline)) {
+      constexpr int QB = decltype(qb_c)::value, QN = decltype(qn_c)::value, XB = decltype(xb_c)::value;
+      const int t = t_lo + it % nt, h = hk * group + it / nt;
+      const int ib = t * BN + 32 * QB;
+      const float slope2 = C::MOD == kModAlibi ? p.alibi_slopes[h] * kLog2e : 0.f;
+      const int cls = classify_block(POS, ib, ib + 31, jw, jw + 31, p.Sk, p.window, p.prefix, make_int2(0, 0), make_int2(0, 0));
+      const bool need_mask = (MASK & kMaskDoc) != 0 || ib + 31 >= p.Sq || cls != kFull;
+      uint32_t ra_n[KK], ta_c[DB][2];
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) ra_n[kk] = w.ra[kk] + base_n;
+#pragma unroll
+      for (int d = 0; d < DB; ++d) {
+        ta_c[d][0] = w.ta[d][0] + base_c;
+        ta_c[d][1] = w.ta[d][1] + base_c;
+      }
+      i32x4 st_l[4];                               // lse2 of the block's 16 rows of this half
+      static_for<0, 4>([&](auto qc) __attribute__((always_inline)) {
+        W::template read_b128<2 * C::TILE + (32 * QB + 8 * decltype(qc)::value) * 4>(st_l[decltype(qc)::value], stat_addr + base_c);
+      });
+      const int irow = ib + 4 * w.half;            // query row of register 0
+      int qd[16];
+      if constexpr ((MASK & kMaskDoc) != 0) {
+        const int32_t* qdoc = p.q_doc + (int64_t)b * p.Sq;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int i = irow + 8 * (r >> 2) + (r & 3);
+          qd[r] = qdoc[i < p.Sq ? i : p.Sq - 1];
+        }
+      }
+      uint32_t pw[8];
+      float pf[4];
+      auto ew_pair = [&](auto r2c) __attribute__((always_inline)) {
+        constexpr int r2 = decltype(r2c)::value;
+        float pv[2], fc2[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const int r = 2 * r2 + e;
+          const int i = irow + 8 * (r >> 2) + (r & 3);
+          const float lse2 = __int_as_float(st_l[r >> 2][r & 3]);
+          const float a = replay_score<C::MOD>(cur[r], c_scale, lse2, p.softcap, slope2, (float)(i - j), fc2[e]);
+          pv[e] = fast_exp2(a);
+        }
+        if (need_mask) {                           // uniform; kept a branch: most blocks need no mask
+          asm volatile("");
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            const int r = 2 * r2 + e;
+            const int i = irow + 8 * (r >> 2) + (r & 3);
+            if (hidden<MASK>(i, j, p.Sq, p.Sk, p.window, p.prefix, (MASK & kMaskDoc) ? qd[r] : 0, kdoc)) pv[e] = 0.f;
+          }
+        }
+        pw[r2] = pack_bf16(pv[0], pv[1]);
+        asm volatile("" : "+v"(pw[r2]));
+        pf[2 * (r2 & 1)] = C::MOD == kModSoftcap ? pv[0] * fc2[0] : pv[0];
+        pf[2 * (r2 & 1) + 1] = C::MOD == kModSoftcap ? pv[1] * fc2[1] : pv[1];
+        if constexpr (r2 % 2 == 1)                 // registers 4q .. 4q + 3 are complete: quad q = r2 / 2
+          W::template write_b128<XB * XBUF + (r2 / 2) * 1024>(
+              xaddr, (i32x4){__float_as_int(pf[0]), __float_as_int(pf[1]), __float_as_int(pf[2]), __float_as_int(pf[3])});
+      };
+      // phase 1: scores of the next block  ||  P of the current block
+      nxt = W::zero16();
+      w.template row_stream_g<RowOne<QN * 32 * ROW>, KK, 2>(ra_n, [&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+        constexpr int f = decltype(fc)::value;
+        nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[f], nxt, 0, 0, 0);
+        static_for<f * PPM, (f + 1) * PPM>([&](auto r2c) __attribute__((always_inline)) { ew_pair(r2c); });
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      // phase 2: dV += dO^T P
+      w.template tr_stream_g<TrOne<C::TILE + QB * 32 * ROW, DB, ROW>, 2 * DB, 2>(ta_c, [&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+        constexpr int f = decltype(fc)::value, d = f % DB, ks = f / DB;
+        const bf16x8 bop = __builtin_bit_cast(
+            bf16x8, (i32x4){(int)pw[4 * ks], (int)pw[4 * ks + 1], (int)pw[4 * ks + 2], (int)pw[4 * ks + 3]});
+        dv[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bop, dv[d], 0, 0, 0);
+      });
+    };
+    if (it0 < n_items) scores(std::integral_constant<int, 0>(), 0u, sa);
+    while (true) {
+      const bool vp = it0 < n_items, vm = itm1 < n_items;
+      if (!vp && !vm) break;
+      const uint32_t b0 = s0 * C::STAGE_KV, b1 = (s0 + 1 == NSTAGE ? 0 : s0 + 1) * C::STAGE_KV;
+      const int s2 = s0 + 2 >= NSTAGE ? s0 + 2 - NSTAGE : s0 + 2;
+      // even iteration: block (P, 0) current, (P, 1) next
+      if (vp) p_iter(std::integral_constant<int, 0>(), std::integral_constant<int, 1>(), std::integral_constant<int, 0>(), b0, b0, it0, sa, sb);
+      iteration_end(true);
+      if (!vp) break;
+      // odd iteration: block (P, 1) current, (P + 1, 0) next; the tile at P + 2 replaces the one at P - 1
+      if (vm && itp2 < n_items) load_item(itp2, s2);
+      p_iter(std::integral_constant<int, 1>(), std::integral_constant<int, 0>(), std::integral_constant<int, 1>(), b0, b1, it0, sb, sa);
+      iteration_end(false);
+      itm1 = it0;
+      it0 = itp1;
+      itp1 = itp2;
+      itp2 = itp2 < n_items ? next_item(itp2 + 1) : n_items;
+      s0 = s0 + 1 == NSTAGE ? 0 : s0 + 1;
+    }
+    if (j < p.Sk) {
+      const int64_t vrow = b * p.dv.sb + g * p.dv.sg + hk * p.dv.sh + (int64_t)j * p.dv.ss;
+#pragma unroll
+      for (int d = 0; d < DB; ++d)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int ch = 32 * d + 8 * r4 + 4 * w.half;
+          const float v0 = dv[d][4 * r4], v1 = dv[d][4 * r4 + 1], v2 = dv[d][4 * r4 + 2], v3 = dv[d][4 * r4 + 3];
+          if (p.dkv_f32) *(float4*)((float*)p.dv.ptr + vrow + ch) = make_float4(v0, v1, v2, v3);
+          else *(uint2*)((uint16_t*)p.dv.ptr + vrow + ch) = make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3));
+        }
+    }
+  } else {
+    // ================= dS wave =================
+    bf16x8 vf[KK];
+    {
+      const uint16_t* vp = (const uint16_t*)p.v.ptr + b * p.v.sb + g * p.v.sg + hk * p.v.sh + (int64_t)jc * p.v.ss;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) vf[kk] = *(const bf16x8*)(vp + 16 * kk + 8 * w.half);
+    }
+    f32x16 dk[DB];
+#pragma unroll
+    for (int d = 0; d < DB; ++d) dk[d] = W::zero16();
+    f32x16 da = W::zero16(), db = W::zero16();
+    auto dscores = [&](auto off_c, uint32_t base, f32x16& dst) __attribute__((always_inline)) {  // dP of one block, no overlap
+      uint32_t ra_b[KK];
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) ra_b[kk] = w.ra[kk] + base;
+      dst = W::zero16();
+      w.template row_stream_g<RowOne<decltype(off_c)::value>, KK, 2>(ra_b, [&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+        dst = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, vf[decltype(fc)::value], dst, 0, 0, 0);
+      });
+    };
+    // block QP at stage offset base_p was handed over in exchange buffer XB (its dP in cur); the dP of
+    // block QN at base_n goes to nxt
+    auto ds_iter = [&](auto qp_c, auto qn_c, auto xb_c, uint32_t base_p, uint32_t base_n, f32x16& cur, f32x16& nxt) __attribute__((always_inline)) {
+      constexpr int QP = decltype(qp_c)::value, QN = decltype(qn_c)::value, XB = decltype(xb_c)::value;
+      uint32_t ra_n[KK], ta_p[DB][2];
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) ra_n[kk] = w.ra[kk] + base_n;
+#pragma unroll
+      for (int d = 0; d < DB; ++d) {
+        ta_p[d][0] = w.ta[d][0] + base_p;
+        ta_p[d][1] = w.ta[d][1] + base_p;
+      }
+      i32x4 pq[4], st_d[4];                        // P of the block (fp32) and delta of its rows, by register quad
+      static_for<0, 4>([&](auto qc) __attribute__((always_inline)) {
+        constexpr int q4 = decltype(qc)::value;
+        W::template read_b128<XB * XBUF + q4 * 1024>(pq[q4], xaddr);
+        W::template read_b128<2 * C::TILE + C::STAT + (32 * QP + 8 * q4) * 4>(st_d[q4], stat_addr + base_p);
+      });
+      uint32_t dsw[8];
+      auto ew_pair = [&](auto r2c) __attribute__((always_inline)) {
+        constexpr int r2 = decltype(r2c)::value;
+        float dsv[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const int r = 2 * r2 + e;
+          dsv[e] = __int_as_float(pq[r >> 2][r & 3]) * (cur[r] - __int_as_float(st_d[r >> 2][r & 3]));
+        }
+        dsw[r2] = pack_bf16(dsv[0], dsv[1]);
+        asm volatile("" : "+v"(dsw[r2]));
+      };
+      // phase 1: dP of the next block  ||  dS of the handed-over block
+      nxt = W::zero16();
+      w.template row_stream_g<RowOne<C::TILE + QN * 32 * ROW>, KK, 2>(ra_n, [&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+        constexpr int f = decltype(fc)::value;
+        nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, vf[f], nxt, 0, 0, 0);
+        static_for<f * PPM, (f + 1) * PPM>([&](auto r2c) __attribute__((always_inline)) { ew_pair(r2c); });
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      // phase 2: dK += Q^T dS
+      w.template tr_stream_g<TrOne<QP * 32 * ROW, DB, ROW>, 2 * DB, 2>(ta_p, [&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+        constexpr int f = decltype(fc)::value, d = f % DB, ks = f / DB;
+        const bf16x8 bop = __builtin_bit_cast(
+            bf16x8, (i32x4){(int)dsw[4 * ks], (int)dsw[4 * ks + 1], (int)dsw[4 * ks + 2], (int)dsw[4 * ks + 3]});
+        dk[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bop, dk[d], 0, 0, 0);
+      });
+    };
+    if (it0 < n_items) dscores(std::integral_constant<int, C::TILE>(), 0u, da);
+    while (true) {
+      const bool vp = it0 < n_items, vm = itm1 < n_items;
+      if (!vp && !vm) break;
+      const uint32_t b0 = s0 * C::STAGE_KV;
+      const int s2 = s0 + 2 >= NSTAGE ? s0 + 2 - NSTAGE : s0 + 2;
+      const uint32_t b2 = s2 * C::STAGE_KV;        // stage of position P - 1
+      // even iteration: block (P - 1, 1) was handed over in buffer 1; dP of block (P, 0) is next
+      if (vm) ds_iter(std::integral_constant<int, 1>(), std::integral_constant<int, 0>(), std::integral_constant<int, 1>(), b2, b0, db, da);
+      iteration_end(true);
+      if (!vp) break;
+      // odd iteration: block (P, 0) was handed over in buffer 0; dP of block (P, 1) is next
+      if (vm && itp2 < n_items) load_item(itp2, s2);
+      ds_iter(std::integral_constant<int, 0>(), std::integral_constant<int, 1>(), std::integral_constant<int, 0>(), b0, b0, da, db);
+      iteration_end(false);
+      itm1 = it0;
+      it0 = itp1;
+      itp1 = itp2;
+      itp2 = itp2 < n_items ? next_item(itp2 + 1) : n_items;
+      s0 = s0 + 1 == NSTAGE ? 0 : s0 + 1;
+    }
+    if (j < p.Sk) {
+      const int64_t krow = b * p.dk.sb + g * p.dk.sg + hk * p.dk.sh + (int64_t)j * p.dk.ss;
+#pragma unroll
+      for (int d = 0; d < DB; ++d)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int ch = 32 * d + 8 * r4 + 4 * w.half;
+          const float k0 = dk[d][4 * r4] * p.scale, k1 = dk[d][4 * r4 + 1] * p.scale;
+          const float k2 = dk[d][4 * r4 + 2] * p.scale, k3 = dk[d][4 * r4 + 3] * p.scale;
+          if (p.dkv_f32) *(float4*)((float*)p.dk.ptr + krow + ch) = make_float4(k0, k1, k2, k3);
+          else *(uint2*)((uint16_t*)p.dk.ptr + krow + ch) = make_uint2(pack_bf16(k0, k1), pack_bf16(k2, k3));
+        }
+    }
   }
 }
 

@@ -52,12 +52,26 @@ hipError_t launch_bwd_dkdv(const BwdParams& p, int nblocks, hipStream_t stream) 
   return hipGetLastError();
 }
 
+template <class C>
+hipError_t launch_bwd_dkdv_ws(const BwdParams& p, int nblocks, hipStream_t stream) {
+  hipError_t e = raise_lds_limit(bwd_dkdv_ws_kernel<C>);
+  if (e != hipSuccess) return e;
+  constexpr int lds = 3 * C::STAGE_KV + 4 * 2 * (64 * 16 * 4);   // tile ring, then two exchange buffers per wave pair
+  static_assert(lds <= kMaxLdsBytes, "LDS of the wave-specialised dK/dV kernel");
+  hipLaunchKernelGGL(bwd_dkdv_ws_kernel<C>, dim3(nblocks), dim3(512), lds, stream, p);
+  return hipGetLastError();
+}
+
 // CQ / CK: the shapes of the dQ kernel and of the dK/dV kernel (streamed tile rows, waves per SIMD).
-template <int D, int MOD, uint32_t MASK, int BN_Q, int WPE_Q, int BN_K, int WPE_K>
+// WS: the dK/dV kernel with specialised waves (eight waves, two per SIMD) instead of the plain one.
+template <int D, int MOD, uint32_t MASK, int BN_Q, int WPE_Q, int BN_K, int WPE_K, bool WS>
 constexpr BwdEntry bwd_entry() {
   typedef BwdCfg<D, MOD, MASK, BN_Q, WPE_Q> CQ;
   typedef BwdCfg<D, MOD, MASK, BN_K, WPE_K> CK;
-  return BwdEntry{BwdKey{D, MOD, (int)MASK}, CQ::BM, &launch_bwd_prep<D>, &launch_bwd_dq<CQ>, &launch_bwd_dkdv<CK>};
+  if constexpr (WS)
+    return BwdEntry{BwdKey{D, MOD, (int)MASK}, CQ::BM, &launch_bwd_prep<D>, &launch_bwd_dq<CQ>, &launch_bwd_dkdv_ws<CK>};
+  else
+    return BwdEntry{BwdKey{D, MOD, (int)MASK}, CQ::BM, &launch_bwd_prep<D>, &launch_bwd_dq<CQ>, &launch_bwd_dkdv<CK>};
 }
 
 const BwdEntry* entries_bwd64(int* n);

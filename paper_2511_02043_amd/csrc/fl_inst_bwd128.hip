@@ -2,7 +2,7 @@
 // keys in registers and runs one wave per SIMD.
 #include "fl_bwd_registry.hpp"
 namespace fl {
-#define E(MOD, MASK) bwd_entry<128, MOD, MASK, 64, 2, 64, 1>()
+#define E(MOD, MASK) bwd_entry<128, MOD, MASK, 64, 2, 64, 2, true>()
 constexpr uint32_t CW = kMaskCausal | kMaskWindow;
 static const BwdEntry kEntries[] = {
     E(kModNone, 0),  E(kModNone, kMaskCausal), E(kModAlibi, 0), E(kModSoftcap, 0), E(kModNone, CW),

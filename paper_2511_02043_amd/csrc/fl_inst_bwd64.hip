@@ -2,7 +2,7 @@
 // second softmax stream.
 #include "fl_bwd_registry.hpp"
 namespace fl {
-#define E(MOD, MASK) bwd_entry<64, MOD, MASK, 64, 2, 64, 2>()
+#define E(MOD, MASK) bwd_entry<64, MOD, MASK, 64, 2, 64, 2, false>()
 constexpr uint32_t CW = kMaskCausal | kMaskWindow;
 static const BwdEntry kEntries[] = {
     E(kModNone, 0),        E(kModNone, kMaskCausal),        E(kModAlibi, 0),       E(kModAlibi, kMaskCausal),
