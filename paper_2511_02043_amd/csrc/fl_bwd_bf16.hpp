@@ -836,8 +836,8 @@ bwd_dkdv_kernel(const BwdParams p) {
 // dK, dV with specialised waves: the same contractions as bwd_dkdv_kernel, for head dims whose
 // accumulators (32 keys x D channels x two gradients in fp32) leave no room for a second wave on
 // the SIMD.  Eight waves per workgroup; waves w and w + 4 own the same 32 keys and share a SIMD:
-//   wave w     ("P wave"):   S = Q K^T, P = exp2(..), dV += dO^T P; hands P (times the soft-cap
-//                            derivative) to its partner through LDS, fp32
+//   wave w     ("P wave"):   S = Q K^T, P = exp2(..), dV += dO^T P one block later; hands P (times
+//                            the soft-cap derivative) to its partner through LDS, fp32
 //   wave w + 4 ("dS wave"):  dP = dO V^T, dS = P * (dP - delta) one block later, dK += Q^T dS
 // Each does half of the matrix work of a block and holds one accumulator set, so both fit the
 // register budget of two waves per SIMD and fill each other's stalls.  One workgroup barrier per
@@ -976,6 +976,7 @@ bwd_dkdv_ws_kernel(const BwdParams p) {
 #pragma unroll
     for (int d = 0; d < DB; ++d) dv[d] = W::zero16();
     f32x16 sa = W::zero16(), sb = W::zero16();
+    uint32_t pw[8] = {0, 0, 0, 0, 0, 0, 0, 0};     // bf16 pairs of the last block's P, consumed one iteration later
     auto scores = [&](auto off_c, uint32_t base, f32x16& dst) __attribute__((always_inline)) {   // S of one block, no overlap
       uint32_t ra_b[KK];
 #pragma unroll
@@ -994,14 +995,9 @@ bwd_dkdv_ws_kernel(const BwdParams p) {
       const float slope2 = C::MOD == kModAlibi ? p.alibi_slopes[h] * kLog2e : 0.f;
       const int cls = classify_block(POS, ib, ib + 31, jw, jw + 31, p.Sk, p.window, p.prefix, make_int2(0, 0), make_int2(0, 0));
       const bool need_mask = (MASK & kMaskDoc) != 0 || ib + 31 >= p.Sq || cls != kFull;
-      uint32_t ra_n[KK], ta_c[DB][2];
+      uint32_t ra_n[KK];
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) ra_n[kk] = w.ra[kk] + base_n;
-#pragma unroll
-      for (int d = 0; d < DB; ++d) {
-        ta_c[d][0] = w.ta[d][0] + base_c;
-        ta_c[d][1] = w.ta[d][1] + base_c;
-      }
       i32x4 st_l[4];                               // lse2 of the block's 16 rows of this half
       static_for<0, 4>([&](auto qc) __attribute__((always_inline)) {
         W::template read_b128<2 * C::TILE + (32 * QB + 8 * decltype(qc)::value) * 4>(st_l[decltype(qc)::value], stat_addr + base_c);
@@ -1016,7 +1012,6 @@ bwd_dkdv_ws_kernel(const BwdParams p) {
           qd[r] = qdoc[i < p.Sq ? i : p.Sq - 1];
         }
       }
-      uint32_t pw[8];
       float pf[4];
       auto ew_pair = [&](auto r2c) __attribute__((always_inline)) {
         constexpr int r2 = decltype(r2c)::value;
@@ -1054,7 +1049,18 @@ bwd_dkdv_ws_kernel(const BwdParams p) {
         static_for<f * PPM, (f + 1) * PPM>([&](auto r2c) __attribute__((always_inline)) { ew_pair(r2c); });
         __builtin_amdgcn_sched_barrier(0);
       });
-      // phase 2: dV += dO^T P
+    };
+    // dV += dO^T P for the block whose P (bf16 pairs in pw) the previous iteration formed: it runs
+    // first in an iteration, while the partner wave is in its mixed phase, and the mixed phase above
+    // runs while the partner is in its pure matrix phase
+    auto dv_phase = [&](auto qb_c, uint32_t base_c) __attribute__((always_inline)) {
+      constexpr int QB = decltype(qb_c)::value;
+      uint32_t ta_c[DB][2];
+#pragma unroll
+      for (int d = 0; d < DB; ++d) {
+        ta_c[d][0] = w.ta[d][0] + base_c;
+        ta_c[d][1] = w.ta[d][1] + base_c;
+      }
       w.template tr_stream_g<TrOne<C::TILE + QB * 32 * ROW, DB, ROW>, 2 * DB, 2>(ta_c, [&](auto fc, bf16x8 a) __attribute__((always_inline)) {
         constexpr int f = decltype(fc)::value, d = f % DB, ks = f / DB;
         const bf16x8 bop = __builtin_bit_cast(
@@ -1068,12 +1074,15 @@ bwd_dkdv_ws_kernel(const BwdParams p) {
       if (!vp && !vm) break;
       const uint32_t b0 = s0 * C::STAGE_KV, b1 = (s0 + 1 == NSTAGE ? 0 : s0 + 1) * C::STAGE_KV;
       const int s2 = s0 + 2 >= NSTAGE ? s0 + 2 - NSTAGE : s0 + 2;
-      // even iteration: block (P, 0) current, (P, 1) next
+      // even iteration: dV of block (P - 1, 1); block (P, 0) current, (P, 1) next
+      if (vm) dv_phase(std::integral_constant<int, 1>(), (uint32_t)(s2 * C::STAGE_KV));
       if (vp) p_iter(std::integral_constant<int, 0>(), std::integral_constant<int, 1>(), std::integral_constant<int, 0>(), b0, b0, it0, sa, sb);
       iteration_end(true);
       if (!vp) break;
-      // odd iteration: block (P, 1) current, (P + 1, 0) next; the tile at P + 2 replaces the one at P - 1
+      // odd iteration: dV of block (P, 0); block (P, 1) current, (P + 1, 0) next; the tile at P + 2
+      // replaces the one at P - 1
       if (vm && itp2 < n_items) load_item(itp2, s2);
+      dv_phase(std::integral_constant<int, 0>(), b0);
       p_iter(std::integral_constant<int, 1>(), std::integral_constant<int, 0>(), std::integral_constant<int, 1>(), b0, b1, it0, sb, sa);
       iteration_end(false);
       itm1 = it0;
