@@ -147,6 +147,40 @@ def time_backward(name, steps, warmup):
     return dict(config=name, flops=flops, ms_per_step=ms, tflops=flops / (ms * 1e-3) / 1e12, dims=w.dims)
 
 
+def run_grid_backward(steps, warmup):
+    """fl_attn_bwd on the paper's benchmark grid (Sec. 4.1 shapes; the paper itself times no backward pass)."""
+    import torch
+    from paper_2511_02043_amd import inputs, runner
+    rows = []
+    for variant in inputs.GRID_VARIANTS:
+        for gqa in (False, True):
+            for S in inputs.GRID_SEQ_LENS:
+                w = inputs.grid_bf16(variant, S, gqa=gqa)
+                flops = flops_and_bytes(w)[0] * 5 // 2
+                db = runner.upload_backward(w, inputs.dout_for(w), grad_dtype="bf16")
+                stream = torch.cuda.current_stream().cuda_stream
+                db.fwd.run_checked(stream)
+                for _ in range(warmup):
+                    db.run_checked(stream)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(steps):
+                    db.run_checked(stream)
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1) / steps
+                rows.append(dict(variant=variant, heads="gqa" if gqa else "mha", S=S, B=w.dims["B"], ms=ms,
+                                 tflops=flops / (ms * 1e-3) / 1e12))
+                print(f"# bwd {variant:15s} {'gqa' if gqa else 'mha'} S={S:5d} B={w.dims['B']:2d}: {ms:.4f} ms  "
+                      f"{rows[-1]['tflops']:.1f} TFLOP/s", file=sys.stderr, flush=True)
+                del db
+    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+    with open(os.path.join(ROOT, "gpurun_out", "bench_grid_bwd.json"), "w") as f:
+        json.dump(rows, f, indent=1)
+    print(json.dumps({"grid_cells": len(rows), "file": "gpurun_out/bench_grid_bwd.json"}), flush=True)
+
+
 def gemm_reference(n=8192, reps=50):
     """TFLOP/s of torch.matmul on random bf16 data of size n^3: what the matrix cores sustain under the
     board's power limit with nothing but a contraction to run (context for roofline.frac, not a target)."""
@@ -303,6 +337,9 @@ def main():
         k, v = kv.split("=")
         fb.check(fb.fl_set_tuning(k, int(v)))
 
+    if args.grid and args.backward:
+        run_grid_backward(args.steps, args.warmup)
+        return
     if args.grid:
         run_grid(args.steps, args.warmup)
         return

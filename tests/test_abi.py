@@ -100,3 +100,49 @@ def test_validation_errors_need_no_gpu():
     k.stride[:] = [768, 768, 256, 64, 1]
     d = fb.variant_desc(scale=0.125)
     assert fb.fl_attn_fwd(t, k, k, d, None, t, None) == fb.FL_ERR_SHAPE      # 3 kv heads vs 1 q head
+
+
+def test_backward_validation_paths_return_before_any_launch():
+    """fl_attn_bwd: every failed check returns its code without touching the device."""
+    t = fb.fl_tensor()
+    t.ptr, t.dtype = 0x1000, fb.FL_BF16
+    t.size[:] = [1, 1, 2, 64, 64]
+    t.stride[:] = [8192, 8192, 4096, 64, 1]
+    lse = fb.fl_tensor()
+    lse.ptr, lse.dtype = 0x3000, fb.FL_F32
+    lse.size[:] = [1, 1, 2, 64, 1]
+    lse.stride[:] = [128, 128, 64, 1, 1]
+    d = fb.variant_desc(scale=0.125, mask=fb.FL_MASK_CAUSAL)
+    assert fb.fl_bwd_supported(d, fb.FL_BF16, 64, 64) and fb.fl_bwd_supported(d, fb.FL_BF16, 128, 128)
+    assert not fb.fl_bwd_supported(d, fb.FL_F32, 64, 64)
+    assert not fb.fl_bwd_supported(d, fb.FL_BF16, 64, 128)
+    assert not fb.fl_bwd_supported(fb.variant_desc(scale=0.125, n_bias=1), fb.FL_BF16, 64, 64)
+    assert not fb.fl_bwd_supported(fb.variant_desc(scale=0.125, combine=fb.FL_DIFFERENTIAL), fb.FL_BF16, 64, 64)
+    # workspace: two float rows statistics per query row, each array padded to 256 bytes
+    assert fb.fl_attn_bwd_workspace_size(t, t, d) == 2 * 512
+    dd = fb.variant_desc(scale=0.125, mask=fb.FL_MASK_DOC)
+    assert fb.fl_attn_bwd_workspace_size(t, t, dd) == 2 * 512 + 8 * (2 + 2)
+    a = fb.aux_desc()
+    assert fb.fl_attn_bwd(t, t, t, t, t, lse, d, None, t, t, t) == fb.FL_ERR_AUX_MISSING
+    assert fb.fl_attn_bwd(t, t, t, t, t, lse, d, a, t, t, t) == fb.FL_ERR_WORKSPACE
+    assert fb.fl_attn_bwd(t, t, t, t, t, None, d, a, t, t, t) == fb.FL_ERR_NULL
+    g = fb.variant_desc(scale=0.125, epilogue=fb.FL_EPI_GATE_SIGMOID)
+    assert fb.fl_attn_bwd(t, t, t, t, t, lse, g, a, t, t, t) == fb.FL_ERR_UNSUPPORTED
+    f32 = fb.fl_tensor()
+    f32.ptr, f32.dtype = 0x1000, fb.FL_F32
+    f32.size[:] = t.size[:]
+    f32.stride[:] = t.stride[:]
+    assert fb.fl_attn_bwd(f32, t, t, t, t, lse, d, a, t, t, t) == fb.FL_ERR_DTYPE
+    bad = fb.fl_tensor()
+    bad.ptr, bad.dtype = 0x1000, fb.FL_BF16
+    bad.size[:] = [1, 1, 2, 32, 64]
+    bad.stride[:] = t.stride[:]
+    assert fb.fl_attn_bwd(t, t, t, t, bad, lse, d, a, t, t, t) == fb.FL_ERR_SHAPE      # dout rows
+    lse.dtype = fb.FL_BF16
+    assert fb.fl_attn_bwd(t, t, t, t, t, lse, d, a, t, t, t) == fb.FL_ERR_DTYPE
+    lse.dtype = fb.FL_F32
+    t96 = fb.fl_tensor()
+    t96.ptr, t96.dtype = 0x1000, fb.FL_BF16
+    t96.size[:] = [1, 1, 2, 64, 96]
+    t96.stride[:] = [12288, 12288, 6144, 96, 1]
+    assert fb.fl_attn_bwd(t96, t96, t96, t96, t96, lse, d, a, t96, t96, t96) == fb.FL_ERR_UNSUPPORTED
