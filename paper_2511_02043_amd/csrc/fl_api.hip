@@ -204,12 +204,30 @@ bool bwd_desc_ok(const fl_variant_desc* d) { return d->n_bias == 0 && d->combine
 // Workspace of the backward pass: delta, lse2 ([B, G, H, Sq] floats each, 256-byte aligned), then
 // the document-id summaries of the tile skipper.
 struct BwdWorkspace {
-  size_t stat_bytes, total;
+  size_t stat_bytes, sum_bytes, part_bytes, total;
+  int hsplit;
 };
-BwdWorkspace bwd_workspace(int64_t B, int64_t G, int64_t H, int64_t Sq, int64_t Sk, uint32_t mask) {
+constexpr int kBwdKeysPerWg = 128;                 // keys per workgroup of the dK/dV kernels (BwdCfg::BM)
+
+// Grouped-query heads: a dK/dV workgroup sums over the query heads of its group.  When that leaves
+// the launch with too few workgroups, the group is cut into hsplit subsets whose fp32 partial
+// sums a small kernel adds up afterwards.
+int choose_hsplit(int64_t B, int64_t G, int64_t H, int64_t Hkv, int64_t Sk) {
+  if (Hkv <= 0 || H <= Hkv || Sk <= 0) return 1;
+  const int64_t group = H / Hkv, wgs = B * G * Hkv * ((Sk + kBwdKeysPerWg - 1) / kBwdKeysPerWg);
+  int hs = 1;
+  while (hs < group && wgs * hs < 1024 && group % (hs * 2) == 0) hs *= 2;
+  return hs;
+}
+
+BwdWorkspace bwd_workspace(int64_t B, int64_t G, int64_t H, int64_t Hkv, int64_t Sq, int64_t Sk, int64_t D,
+                           uint32_t mask) {
   BwdWorkspace w;
   w.stat_bytes = ((size_t)(B * G * H * Sq) * sizeof(float) + 255) / 256 * 256;
-  w.total = 2 * w.stat_bytes + workspace_bytes(B, Sq, Sk, mask);
+  w.sum_bytes = (workspace_bytes(B, Sq, Sk, mask) + 255) / 256 * 256;
+  w.hsplit = choose_hsplit(B, G, H, Hkv, Sk);
+  w.part_bytes = w.hsplit > 1 ? (size_t)w.hsplit * (size_t)(B * G * Hkv * Sk * D) * sizeof(float) : 0;
+  w.total = 2 * w.stat_bytes + w.sum_bytes + 2 * w.part_bytes;
   return w;
 }
 
@@ -466,7 +484,7 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
 
 size_t fl_attn_bwd_workspace_size(const fl_tensor* q, const fl_tensor* k, const fl_variant_desc* desc) {
   if (q == nullptr || k == nullptr || desc == nullptr) return 0;
-  return bwd_workspace(q->size[0], q->size[1], q->size[2], q->size[3], k->size[3], desc->mask).total;
+  return bwd_workspace(q->size[0], q->size[1], q->size[2], k->size[2], q->size[3], k->size[3], q->size[4], desc->mask).total;
 }
 
 int fl_bwd_supported(const fl_variant_desc* desc, int dtype, int D, int Dv) {
@@ -534,7 +552,7 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   if ((mask & FL_MASK_DOC) && (aux->q_doc_ids == nullptr || aux->kv_doc_ids == nullptr))
     return fail(FL_ERR_AUX_MISSING, "q_doc_ids / kv_doc_ids");
   if (no_rows && no_keys) return FL_OK;
-  const BwdWorkspace wsz = bwd_workspace(B, G, H, Sq, Sk, mask);
+  const BwdWorkspace wsz = bwd_workspace(B, G, H, Hkv, Sq, Sk, D, mask);
   if (aux->workspace == nullptr || aux->workspace_bytes < wsz.total)
     return fail(FL_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", wsz.total, aux->workspace ? aux->workspace_bytes : (size_t)0);
   if (((uintptr_t)aux->workspace) % 16 != 0) return fail(FL_ERR_ALIGN, "workspace not 16-byte aligned");
@@ -571,10 +589,14 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   p.dkv_f32 = dk->dtype == FL_F32;
   p.n_qtiles = (int)((Sq + be->bm - 1) / be->bm);
   p.n_ktiles = (int)((Sk + be->bm - 1) / be->bm);
+  static_assert(fl::BwdCfg<64, 0, 0, 64, 2>::BM == kBwdKeysPerWg, "keys per dK/dV workgroup");
+  p.hsplit = no_keys || no_rows ? 1 : wsz.hsplit;
+  p.part_dk = (float*)((unsigned char*)aux->workspace + 2 * wsz.stat_bytes + wsz.sum_bytes);
+  p.part_dv = (float*)((unsigned char*)p.part_dk + wsz.part_bytes);
   const int order = g_tuning.order >= 0 ? g_tuning.order : 1;
   p.order_q = order == 1 && (B * G * H) % 8 == 0;
-  p.order_k = order == 1 && (B * G * Hkv) % 8 == 0;
-  const int64_t nb_q = B * G * H * p.n_qtiles, nb_k = B * G * Hkv * p.n_ktiles;
+  p.order_k = order == 1 && (B * G * Hkv * p.hsplit) % 8 == 0;
+  const int64_t nb_q = B * G * H * p.n_qtiles, nb_k = B * G * Hkv * p.hsplit * p.n_ktiles;
   const int64_t rows = B * G * H * Sq;
   if (nb_q > 0x7fffffffLL || nb_k > 0x7fffffffLL || rows > 0x7fffffff00LL) return fail(FL_ERR_SHAPE, "too many workgroups");
 
@@ -599,6 +621,11 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   if (!no_keys) {
     // Sq == 0: the query loop is empty and dk, dv come out as zeros
     if ((e = be->dkdv(p, (int)nb_k, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dk/dv launch: %s", hipGetErrorString(e));
+    if (p.hsplit > 1) {
+      const int64_t chunks = B * G * Hkv * Sk * (D / 4);
+      if ((e = be->reduce(p, (int)((chunks + 255) / 256), stream)) != hipSuccess)
+        return fail(FL_ERR_LAUNCH, "dk/dv reduction launch: %s", hipGetErrorString(e));
+    }
   }
   return FL_OK;
 }

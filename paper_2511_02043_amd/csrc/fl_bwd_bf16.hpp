@@ -49,6 +49,9 @@ struct BwdParams {
   int32_t dq_f32, dkv_f32;         // 1: that output is float, 0: bf16
   int32_t n_qtiles, n_ktiles;      // workgroups per (b, g, h) of the dQ kernel / per (b, g, hkv) of the dK/dV kernel
   int32_t order_q, order_k;        // 1: XCD-aware workgroup order (whole (b, g, h) problems per XCD) in that kernel
+  int32_t hsplit;                  // dK/dV kernel: the query heads of a group are cut into hsplit subsets, one workgroup each
+  float* part_dk;                  // hsplit > 1: fp32 partial sums [hsplit][B, G, Hkv, Sk, D], summed by bwd_reduce_kv_kernel
+  float* part_dv;
 };
 
 // chunk swizzle of a tile row (see the header comment): an XOR on the 16-byte chunk index that
@@ -295,6 +298,51 @@ __device__ __forceinline__ float replay_score(float x, float c_scale, float lse2
 template <uint32_t MASK>
 __device__ __forceinline__ bool hidden(int i, int j, int Sq, int Sk, int window, int prefix, int qdoc, int kdoc) {
   return i >= Sq || j >= Sk || is_masked(MASK, i, j, window, prefix, qdoc, kdoc);
+}
+
+// Four consecutive channels of a dK or dV row: to the output tensor, or (grouped-query heads cut
+// over several workgroups) to this workgroup's fp32 partial.
+__device__ __forceinline__ void store_kv_grad(const BwdParams& p, const View& out, float* part, int split, int b, int g,
+                                              int hk, int j, int ch, int D, float x0, float x1, float x2, float x3) {
+  if (p.hsplit > 1) {
+    const int64_t row = ((((int64_t)split * p.B + b) * p.G + g) * p.Hkv + hk) * p.Sk + j;
+    *(float4*)(part + row * D + ch) = make_float4(x0, x1, x2, x3);
+  } else {
+    const int64_t row = b * out.sb + g * out.sg + hk * out.sh + (int64_t)j * out.ss;
+    if (p.dkv_f32) *(float4*)((float*)out.ptr + row + ch) = make_float4(x0, x1, x2, x3);
+    else *(uint2*)((uint16_t*)out.ptr + row + ch) = make_uint2(pack_bf16(x0, x1), pack_bf16(x2, x3));
+  }
+}
+
+// Sum of the hsplit partials of dK and dV, in a fixed order (reproducible), written in the output dtype.
+template <int D>
+__global__ void __launch_bounds__(256) bwd_reduce_kv_kernel(const BwdParams p) {
+  constexpr int cpr = D / 4;                       // float4 chunks per row
+  const int64_t rows = (int64_t)p.B * p.G * p.Hkv * p.Sk;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= rows * cpr) return;
+  const int64_t row = idx / cpr;
+  const int ch = (int)(idx % cpr) * 4;
+  const int j = (int)(row % p.Sk);
+  const int hk = (int)((row / p.Sk) % p.Hkv);
+  const int g = (int)((row / ((int64_t)p.Sk * p.Hkv)) % p.G);
+  const int b = (int)(row / ((int64_t)p.Sk * p.Hkv * p.G));
+  float4 k = make_float4(0.f, 0.f, 0.f, 0.f), v = k;
+  for (int s = 0; s < p.hsplit; ++s) {
+    const float4 a = *(const float4*)(p.part_dk + ((int64_t)s * rows + row) * D + ch);
+    const float4 c = *(const float4*)(p.part_dv + ((int64_t)s * rows + row) * D + ch);
+    k.x += a.x; k.y += a.y; k.z += a.z; k.w += a.w;
+    v.x += c.x; v.y += c.y; v.z += c.z; v.w += c.w;
+  }
+  const int64_t krow = b * p.dk.sb + g * p.dk.sg + hk * p.dk.sh + (int64_t)j * p.dk.ss;
+  const int64_t vrow = b * p.dv.sb + g * p.dv.sg + hk * p.dv.sh + (int64_t)j * p.dv.ss;
+  if (p.dkv_f32) {
+    *(float4*)((float*)p.dk.ptr + krow + ch) = k;
+    *(float4*)((float*)p.dv.ptr + vrow + ch) = v;
+  } else {
+    *(uint2*)((uint16_t*)p.dk.ptr + krow + ch) = make_uint2(pack_bf16(k.x, k.y), pack_bf16(k.z, k.w));
+    *(uint2*)((uint16_t*)p.dv.ptr + vrow + ch) = make_uint2(pack_bf16(v.x, v.y), pack_bf16(v.z, v.w));
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -566,8 +614,11 @@ bwd_dkdv_kernel(const BwdParams p) {
     kt = blockIdx.x % nk;
     bh = blockIdx.x / nk;
   }
-  const int hk = bh % p.Hkv, g = (bh / p.Hkv) % p.G, b = bh / (p.Hkv * p.G);
-  const int group = p.H / p.Hkv;
+  // bh counts (b, g, kv head, subset of the group's query heads)
+  const int split = bh % p.hsplit, bhk = bh / p.hsplit;
+  const int hk = bhk % p.Hkv, g = (bhk / p.Hkv) % p.G, b = bhk / (p.Hkv * p.G);
+  const int group = p.H / p.Hkv / p.hsplit;        // query heads this workgroup sums over
+  const int h_first = hk * (p.H / p.Hkv) + split * group;
   const int j0 = kt * C::BM, jw = j0 + 32 * wave;
   const int j = jw + w.col, jc = j < p.Sk ? j : p.Sk - 1;
 
@@ -633,7 +684,7 @@ bwd_dkdv_kernel(const BwdParams p) {
   };
 
   auto load_item = [&](int it, int stage) __attribute__((always_inline)) {
-    const int t = t_lo + it % nt, h = hk * group + it / nt;
+    const int t = t_lo + it % nt, h = h_first + it / nt;
     const int nvalid = min(BN, p.Sq - t * BN);
     unsigned char* st = lds_raw + stage * C::STAGE_KV;
     const unsigned char* qb = (const unsigned char*)((const uint16_t*)p.q.ptr + b * p.q.sb + g * p.q.sg + h * p.q.sh + (int64_t)(t * BN) * p.q.ss);
@@ -672,7 +723,7 @@ bwd_dkdv_kernel(const BwdParams p) {
   // the tile at base_n is next (the same tile, or row block 0 of the following one)
   auto step = [&](auto qb_c, auto qn_c, uint32_t base_c, uint32_t base_n, int it, bool first, Blk& cur, Blk& nxt) __attribute__((always_inline)) {
     constexpr int QB = decltype(qb_c)::value, QN = decltype(qn_c)::value;
-    const int t = t_lo + it % nt, h = hk * group + it / nt;
+    const int t = t_lo + it % nt, h = h_first + it / nt;
     const int ib = t * BN + 32 * QB;
     const float slope2 = C::MOD == kModAlibi ? p.alibi_slopes[h] * kLog2e : 0.f;
     const int cls = classify_block(POS, ib, ib + 31, jw, jw + 31, p.Sk, p.window, p.prefix, make_int2(0, 0), make_int2(0, 0));
@@ -811,23 +862,15 @@ bwd_dkdv_kernel(const BwdParams p) {
   }
 
   if (j < p.Sk) {
-    const int64_t krow = b * p.dk.sb + g * p.dk.sg + hk * p.dk.sh + (int64_t)j * p.dk.ss;
-    const int64_t vrow = b * p.dv.sb + g * p.dv.sg + hk * p.dv.sh + (int64_t)j * p.dv.ss;
 #pragma unroll
     for (int d = 0; d < DB; ++d)
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
         const int ch = 32 * d + 8 * r4 + 4 * w.half;
-        const float k0 = dk[d][4 * r4] * p.scale, k1 = dk[d][4 * r4 + 1] * p.scale;
-        const float k2 = dk[d][4 * r4 + 2] * p.scale, k3 = dk[d][4 * r4 + 3] * p.scale;
-        const float v0 = dv[d][4 * r4], v1 = dv[d][4 * r4 + 1], v2 = dv[d][4 * r4 + 2], v3 = dv[d][4 * r4 + 3];
-        if (p.dkv_f32) {
-          *(float4*)((float*)p.dk.ptr + krow + ch) = make_float4(k0, k1, k2, k3);
-          *(float4*)((float*)p.dv.ptr + vrow + ch) = make_float4(v0, v1, v2, v3);
-        } else {
-          *(uint2*)((uint16_t*)p.dk.ptr + krow + ch) = make_uint2(pack_bf16(k0, k1), pack_bf16(k2, k3));
-          *(uint2*)((uint16_t*)p.dv.ptr + vrow + ch) = make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3));
-        }
+        store_kv_grad(p, p.dk, p.part_dk, split, b, g, hk, j, ch, D, dk[d][4 * r4] * p.scale, dk[d][4 * r4 + 1] * p.scale,
+                      dk[d][4 * r4 + 2] * p.scale, dk[d][4 * r4 + 3] * p.scale);
+        store_kv_grad(p, p.dv, p.part_dv, split, b, g, hk, j, ch, D, dv[d][4 * r4], dv[d][4 * r4 + 1], dv[d][4 * r4 + 2],
+                      dv[d][4 * r4 + 3]);
       }
   }
 }
@@ -876,8 +919,11 @@ bwd_dkdv_ws_kernel(const BwdParams p) {
     kt = blockIdx.x % nk;
     bh = blockIdx.x / nk;
   }
-  const int hk = bh % p.Hkv, g = (bh / p.Hkv) % p.G, b = bh / (p.Hkv * p.G);
-  const int group = p.H / p.Hkv;
+  // bh counts (b, g, kv head, subset of the group's query heads)
+  const int split = bh % p.hsplit, bhk = bh / p.hsplit;
+  const int hk = bhk % p.Hkv, g = (bhk / p.Hkv) % p.G, b = bhk / (p.Hkv * p.G);
+  const int group = p.H / p.Hkv / p.hsplit;        // query heads this workgroup sums over
+  const int h_first = hk * (p.H / p.Hkv) + split * group;
   const int j0 = kt * C::BM, jw = j0 + 32 * kg;
   const int j = jw + w.col, jc = j < p.Sk ? j : p.Sk - 1;
   const float c_scale = p.scale * kLog2e;
@@ -922,7 +968,7 @@ bwd_dkdv_ws_kernel(const BwdParams p) {
     return it;
   };
   auto load_item = [&](int it, int stage) __attribute__((always_inline)) {
-    const int t = t_lo + it % nt, h = hk * group + it / nt;
+    const int t = t_lo + it % nt, h = h_first + it / nt;
     const int nvalid = min(BN, p.Sq - t * BN);
     unsigned char* st = lds_raw + stage * C::STAGE_KV;
     const unsigned char* qb = (const unsigned char*)((const uint16_t*)p.q.ptr + b * p.q.sb + g * p.q.sg + h * p.q.sh + (int64_t)(t * BN) * p.q.ss);
@@ -990,7 +1036,7 @@ bwd_dkdv_ws_kernel(const BwdParams p) {
     // base_n go to nxt; P of the current block goes to exchange buffer XB
     auto p_iter = [&](auto qb_c, auto qn_c, auto xb_c, uint32_t base_c, uint32_t base_n, int it, f32x16& cur, f32x16& nxt) __attribute__((always_inline)) {
       constexpr int QB = decltype(qb_c)::value, QN = decltype(qn_c)::value, XB = decltype(xb_c)::value;
-      const int t = t_lo + it % nt, h = hk * group + it / nt;
+      const int t = t_lo + it % nt, h = h_first + it / nt;
       const int ib = t * BN + 32 * QB;
       const float slope2 = C::MOD == kModAlibi ? p.alibi_slopes[h] * kLog2e : 0.f;
       const int cls = classify_block(POS, ib, ib + 31, jw, jw + 31, p.Sk, p.window, p.prefix, make_int2(0, 0), make_int2(0, 0));
@@ -1092,16 +1138,12 @@ bwd_dkdv_ws_kernel(const BwdParams p) {
       s0 = s0 + 1 == NSTAGE ? 0 : s0 + 1;
     }
     if (j < p.Sk) {
-      const int64_t vrow = b * p.dv.sb + g * p.dv.sg + hk * p.dv.sh + (int64_t)j * p.dv.ss;
 #pragma unroll
       for (int d = 0; d < DB; ++d)
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const int ch = 32 * d + 8 * r4 + 4 * w.half;
-          const float v0 = dv[d][4 * r4], v1 = dv[d][4 * r4 + 1], v2 = dv[d][4 * r4 + 2], v3 = dv[d][4 * r4 + 3];
-          if (p.dkv_f32) *(float4*)((float*)p.dv.ptr + vrow + ch) = make_float4(v0, v1, v2, v3);
-          else *(uint2*)((uint16_t*)p.dv.ptr + vrow + ch) = make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3));
-        }
+        for (int r4 = 0; r4 < 4; ++r4)
+          store_kv_grad(p, p.dv, p.part_dv, split, b, g, hk, j, 32 * d + 8 * r4 + 4 * w.half, D, dv[d][4 * r4],
+                        dv[d][4 * r4 + 1], dv[d][4 * r4 + 2], dv[d][4 * r4 + 3]);
     }
   } else {
     // ================= dS wave =================
@@ -1192,17 +1234,12 @@ bwd_dkdv_ws_kernel(const BwdParams p) {
       s0 = s0 + 1 == NSTAGE ? 0 : s0 + 1;
     }
     if (j < p.Sk) {
-      const int64_t krow = b * p.dk.sb + g * p.dk.sg + hk * p.dk.sh + (int64_t)j * p.dk.ss;
 #pragma unroll
       for (int d = 0; d < DB; ++d)
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const int ch = 32 * d + 8 * r4 + 4 * w.half;
-          const float k0 = dk[d][4 * r4] * p.scale, k1 = dk[d][4 * r4 + 1] * p.scale;
-          const float k2 = dk[d][4 * r4 + 2] * p.scale, k3 = dk[d][4 * r4 + 3] * p.scale;
-          if (p.dkv_f32) *(float4*)((float*)p.dk.ptr + krow + ch) = make_float4(k0, k1, k2, k3);
-          else *(uint2*)((uint16_t*)p.dk.ptr + krow + ch) = make_uint2(pack_bf16(k0, k1), pack_bf16(k2, k3));
-        }
+        for (int r4 = 0; r4 < 4; ++r4)
+          store_kv_grad(p, p.dk, p.part_dk, split, b, g, hk, j, 32 * d + 8 * r4 + 4 * w.half, D, dk[d][4 * r4] * p.scale,
+                        dk[d][4 * r4 + 1] * p.scale, dk[d][4 * r4 + 2] * p.scale, dk[d][4 * r4 + 3] * p.scale);
     }
   }
 }

@@ -15,7 +15,7 @@ typedef hipError_t (*BwdLaunchFn)(const BwdParams& p, int nblocks, hipStream_t s
 struct BwdEntry {
   BwdKey key;
   int bm;           // query rows per workgroup of the dQ kernel = keys per workgroup of the dK/dV kernel
-  BwdLaunchFn prep, dq, dkdv;
+  BwdLaunchFn prep, dq, dkdv, reduce;   // reduce: sum of the head-subset partials of dK / dV (nblocks of 256 threads)
 };
 
 template <class K>
@@ -35,6 +35,11 @@ hipError_t raise_lds_limit(K kernel) {
 template <int DV>
 hipError_t launch_bwd_prep(const BwdParams& p, int nblocks, hipStream_t stream) {
   hipLaunchKernelGGL(bwd_prep_kernel<DV>, dim3(nblocks), dim3(256), 0, stream, p);
+  return hipGetLastError();
+}
+template <int D>
+hipError_t launch_bwd_reduce(const BwdParams& p, int nblocks, hipStream_t stream) {
+  hipLaunchKernelGGL(bwd_reduce_kv_kernel<D>, dim3(nblocks), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 template <class C>
@@ -69,9 +74,9 @@ constexpr BwdEntry bwd_entry() {
   typedef BwdCfg<D, MOD, MASK, BN_Q, WPE_Q> CQ;
   typedef BwdCfg<D, MOD, MASK, BN_K, WPE_K> CK;
   if constexpr (WS)
-    return BwdEntry{BwdKey{D, MOD, (int)MASK}, CQ::BM, &launch_bwd_prep<D>, &launch_bwd_dq<CQ>, &launch_bwd_dkdv_ws<CK>};
+    return BwdEntry{BwdKey{D, MOD, (int)MASK}, CQ::BM, &launch_bwd_prep<D>, &launch_bwd_dq<CQ>, &launch_bwd_dkdv_ws<CK>, &launch_bwd_reduce<D>};
   else
-    return BwdEntry{BwdKey{D, MOD, (int)MASK}, CQ::BM, &launch_bwd_prep<D>, &launch_bwd_dq<CQ>, &launch_bwd_dkdv<CK>};
+    return BwdEntry{BwdKey{D, MOD, (int)MASK}, CQ::BM, &launch_bwd_prep<D>, &launch_bwd_dq<CQ>, &launch_bwd_dkdv<CK>, &launch_bwd_reduce<D>};
 }
 
 const BwdEntry* entries_bwd64(int* n);

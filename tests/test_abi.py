@@ -121,7 +121,13 @@ def test_backward_validation_paths_return_before_any_launch():
     # workspace: two float rows statistics per query row, each array padded to 256 bytes
     assert fb.fl_attn_bwd_workspace_size(t, t, d) == 2 * 512
     dd = fb.variant_desc(scale=0.125, mask=fb.FL_MASK_DOC)
-    assert fb.fl_attn_bwd_workspace_size(t, t, dd) == 2 * 512 + 8 * (2 + 2)
+    assert fb.fl_attn_bwd_workspace_size(t, t, dd) == 2 * 512 + 256      # summaries padded to 256 bytes
+    kv1 = fb.fl_tensor()                                                   # one kv head for the two query heads
+    kv1.ptr, kv1.dtype = 0x1000, fb.FL_BF16
+    kv1.size[:] = [1, 1, 1, 64, 64]
+    kv1.stride[:] = [4096, 4096, 4096, 64, 1]
+    # few workgroups: the group is cut in two, each half writes fp32 partials of dk and dv
+    assert fb.fl_attn_bwd_workspace_size(t, kv1, d) == 2 * 512 + 2 * 2 * (64 * 64 * 4)
     a = fb.aux_desc()
     assert fb.fl_attn_bwd(t, t, t, t, t, lse, d, None, t, t, t) == fb.FL_ERR_AUX_MISSING
     assert fb.fl_attn_bwd(t, t, t, t, t, lse, d, a, t, t, t) == fb.FL_ERR_WORKSPACE

@@ -59,6 +59,9 @@ CASES = {
     "causal_d128": lambda: inputs.causal_bf16(B=1, H=3, S=427, D=128),
     "causal_gqa_d64": lambda: inputs.causal_bf16(B=1, H=8, Hkv=2, S=300, D=64),
     "causal_gqa_d128": lambda: inputs.causal_bf16(B=1, H=4, Hkv=1, S=257, D=128),
+    # enough workgroups that each dK/dV workgroup sums over its whole group of query heads
+    # (the small grouped cases above cut the group over several workgroups plus a reduction)
+    "causal_gqa_many_workgroups": lambda: inputs.causal_bf16(B=16, H=16, Hkv=8, S=1024, D=64),
     "rect_more_keys": lambda: inputs.causal_bf16(B=1, H=2, S=150, Sk=401, D=64, causal=False),
     "rect_more_rows_causal": lambda: inputs.causal_bf16(B=1, H=2, S=401, Sk=150, D=64),
     "alibi_d64": lambda: inputs.alibi_bf16(B=1, H=4, S=300, D=64),
