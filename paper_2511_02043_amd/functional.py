@@ -1,0 +1,103 @@
+"""PyTorch-facing call of the library: `attention(q, k, v, ...)` with autograd support.
+
+Marshalling only: the forward pass is fl_attn_fwd, the backward pass fl_attn_bwd, both through
+the C-ABI binding; no attention arithmetic happens here and there is no fallback path.  Tensors
+are [B, H, S, D] (or [B, G, H, S, D] with an extra independent row axis) bf16 CUDA tensors;
+strided views are passed as they are.
+
+Differentiable variants: scale, causal / sliding-window / PrefixLM / document masks, ALiBi,
+tanh soft-cap, grouped-query heads (the variants fl_attn_bwd covers).  Biases, the sigmoid gate
+and differential attention are forward-only here: use runner.upload / fl_attn_fwd for those.
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import torch
+
+from . import binding as fb
+
+
+def _as5(x: torch.Tensor) -> torch.Tensor:
+    if x.dim() == 4:
+        return x.unsqueeze(1)
+    if x.dim() != 5:
+        raise ValueError(f"expected [B, H, S, D] or [B, G, H, S, D], got {tuple(x.shape)}")
+    return x
+
+
+def _desc(scale, causal, window, prefix, softcap, alibi_slopes, q_doc_ids):
+    mask = 0
+    if causal:
+        mask |= fb.FL_MASK_CAUSAL
+    if window is not None:
+        mask |= fb.FL_MASK_WINDOW | fb.FL_MASK_CAUSAL
+    if prefix is not None:
+        mask |= fb.FL_MASK_PREFIX
+    if q_doc_ids is not None:
+        mask |= fb.FL_MASK_DOC
+    if softcap is not None and alibi_slopes is not None:
+        raise ValueError("one score_mod at a time")
+    mod = fb.FL_MOD_SOFTCAP if softcap is not None else (fb.FL_MOD_ALIBI if alibi_slopes is not None else fb.FL_MOD_NONE)
+    return fb.variant_desc(scale=float(scale), score_mod=mod, softcap=float(softcap or 0.0), mask=mask,
+                           window=int(window or 0), prefix_len=int(prefix or 0))
+
+
+class _Attention(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, q, k, v, scale, causal, window, prefix, softcap, alibi_slopes, q_doc_ids, kv_doc_ids):
+        q5, k5, v5 = _as5(q), _as5(k), _as5(v)
+        B, G, H, Sq, _ = q5.shape
+        desc = _desc(scale, causal, window, prefix, softcap, alibi_slopes, q_doc_ids)
+        out = torch.empty((B, G, H, Sq, v5.shape[4]), dtype=q.dtype, device=q.device)
+        lse = torch.empty((B, G, H, Sq, 1), dtype=torch.float32, device=q.device)
+        tq, tk, tv, tout, tlse = (fb.tensor_desc(x) for x in (q5, k5, v5, out, lse))
+        ws = None
+        nbytes = fb.fl_attn_fwd_workspace_size(tq, tk, desc)
+        if nbytes:
+            ws = torch.empty(nbytes, dtype=torch.uint8, device=q.device)
+        aux = fb.aux_desc(alibi_slopes=alibi_slopes, q_doc_ids=q_doc_ids, kv_doc_ids=kv_doc_ids, workspace=ws)
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+        fb.check(fb.fl_attn_fwd(tq, tk, tv, desc, aux, tout, tlse, stream))
+        ctx.save_for_backward(q, k, v, out, lse)
+        ctx.variant = (scale, causal, window, prefix, softcap)
+        ctx.aux_tensors = (alibi_slopes, q_doc_ids, kv_doc_ids)
+        return out if q.dim() == 5 else out.squeeze(1)
+
+    @staticmethod
+    def backward(ctx, dout):
+        q, k, v, out, lse = ctx.saved_tensors
+        scale, causal, window, prefix, softcap = ctx.variant
+        alibi_slopes, q_doc_ids, kv_doc_ids = ctx.aux_tensors
+        q5, k5, v5, d5 = _as5(q), _as5(k), _as5(v), _as5(dout)
+        if d5.stride(-1) != 1 or any(st % 8 for st in d5.stride()[:-1]):
+            d5 = d5.contiguous()                   # the kernels need unit inner stride and 16-byte aligned rows
+        desc = _desc(scale, causal, window, prefix, softcap, alibi_slopes, q_doc_ids)
+        dq, dk, dv = torch.empty_like(q5), torch.empty_like(k5), torch.empty_like(v5)
+        tq, tk, tv, tout, tdo, tlse, tdq, tdk, tdv = (fb.tensor_desc(x) for x in (q5, k5, v5, out, d5, lse, dq, dk, dv))
+        nbytes = fb.fl_attn_bwd_workspace_size(tq, tk, desc)
+        ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=q.device)
+        aux = fb.aux_desc(alibi_slopes=alibi_slopes, q_doc_ids=q_doc_ids, kv_doc_ids=kv_doc_ids, workspace=ws)
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+        fb.check(fb.fl_attn_bwd(tq, tk, tv, tout, tdo, tlse, desc, aux, tdq, tdk, tdv, stream))
+        if q.dim() == 4:
+            dq, dk, dv = dq.squeeze(1), dk.squeeze(1), dv.squeeze(1)
+        return (dq, dk, dv) + (None,) * 8
+
+
+def attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, scale: Optional[float] = None,
+              causal: bool = False, window: Optional[int] = None, prefix: Optional[int] = None,
+              softcap: Optional[float] = None, alibi_slopes: Optional[torch.Tensor] = None,
+              q_doc_ids: Optional[torch.Tensor] = None, kv_doc_ids: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """softmax(mask(score_mod(scale * q k^T))) v on the library's fused kernels, differentiable in
+    q, k and v.  q [B, (G,) H, Sq, D], k and v [B, (G,) Hkv, Sk, D] with Hkv dividing H; bf16.
+
+    alibi_slopes: float32 [H]; q_doc_ids / kv_doc_ids: int32 [B, Sq] / [B, Sk] (kv defaults to q's).
+    """
+    if not q.is_cuda or q.dtype != torch.bfloat16:
+        raise ValueError("attention() takes bf16 CUDA tensors (there is no CPU or fallback path)")
+    if scale is None:
+        scale = q.shape[-1] ** -0.5
+    if q_doc_ids is not None and kv_doc_ids is None:
+        kv_doc_ids = q_doc_ids
+    return _Attention.apply(q, k, v, scale, causal, window, prefix, softcap, alibi_slopes, q_doc_ids, kv_doc_ids)

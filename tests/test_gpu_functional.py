@@ -1,0 +1,67 @@
+"""attention() (autograd wrapper over fl_attn_fwd / fl_attn_bwd) against the oracles."""
+import numpy as np
+import pytest
+
+from oracle import attention_backward_oracle as bo
+from oracle import attention_oracle as ao
+from paper_2511_02043_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def rel_l2(got, ref):
+    d = got - ref
+    return float(np.sqrt(np.sum(d * d) / np.sum(ref * ref)))
+
+
+@pytest.mark.parametrize("case", ["causal_gqa", "window_doc", "alibi", "softcap_strided"])
+def test_autograd_matches_oracles(case):
+    import torch
+    from paper_2511_02043_amd.functional import attention
+    if case == "causal_gqa":
+        w = inputs.causal_bf16(B=2, H=4, Hkv=2, S=200, D=64)
+    elif case == "window_doc":
+        w = inputs.window_doc_bf16(B=2, H=2, S=300, D=128, window=64, lo=20, hi=120)
+    elif case == "alibi":
+        w = inputs.alibi_bf16(B=1, H=4, S=260, D=64)
+    else:
+        w = inputs.softcap_bf16(B=1, H=2, S=260, D=128, cap=10.0, qscale=2.0)
+    dout = inputs.dout_for(w)
+    dev = "cuda:0"
+
+    def leaf(x, strided=False):
+        t = torch.from_numpy(np.ascontiguousarray(x[:, 0])).to(dev, torch.bfloat16)      # [B, H, S, D]
+        if strided:                                 # stored [B, S, H, D], viewed [B, H, S, D]
+            t = t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+        return t.requires_grad_(True)
+
+    strided = case == "softcap_strided"
+    q, k, v = leaf(w.q, strided), leaf(w.k, strided), leaf(w.v, strided)
+    kw = dict(scale=w.scale, causal=w.causal, window=w.window, prefix=w.prefix, softcap=w.softcap)
+    if w.alibi is not None:
+        kw["alibi_slopes"] = torch.from_numpy(w.alibi).to(dev)
+    if w.q_doc is not None:
+        kw["q_doc_ids"] = torch.from_numpy(w.q_doc).to(dev)
+    out = attention(q, k, v, **kw)
+    out.backward(torch.from_numpy(np.ascontiguousarray(dout[:, 0])).to(dev, torch.bfloat16))
+    torch.cuda.synchronize()
+    ref_out, _ = ao.run_workload(w)
+    ref = bo.run_workload_backward(w, dout)
+    got_out = out.detach().float().cpu().numpy()[:, None]
+    assert np.all(np.abs(got_out - ref_out) <= 1e-2 + 2.0 ** -8 * np.abs(ref_out))
+    for name, t, r in zip(("dq", "dk", "dv"), (q.grad, k.grad, v.grad), ref):
+        g = t.float().cpu().numpy()[:, None]
+        e = rel_l2(g, r)
+        print(f"{case} {name}: rel_l2={e:.3e}", flush=True)
+        assert e <= 1e-2, (name, e)
+
+
+def test_rejects_what_it_cannot_run():
+    import torch
+    from paper_2511_02043_amd.functional import attention
+    x = torch.zeros(1, 2, 16, 64)
+    with pytest.raises(ValueError):
+        attention(x, x, x)                          # CPU tensors: there is no fallback
+    y = torch.zeros(1, 2, 16, 64, device="cuda:0", dtype=torch.float32)
+    with pytest.raises(ValueError):
+        attention(y, y, y)
