@@ -284,3 +284,48 @@ def diffattn_paper_bf16(S=2048, D=64, B=None, H=16, tokens=16384, salt=0) -> Wor
     w = differential_bf16(B=B, H=H, S=S, D=D, Dv=D, salt=salt + 13, causal=False, rmsnorm=False)
     w.name = f"diffattn_paper_s{S}_d{D}"
     return w
+
+
+# --- decode step over a paged key/value cache (the serving experiment of Sec. 4.1) -----------
+
+@dataclasses.dataclass
+class DecodeWorkload:
+    """One decode step: a query per sequence against that sequence's cached keys / values."""
+    name: str
+    q: np.ndarray                   # [B, H, D]
+    k_cache: np.ndarray             # [num_pages, page_size, Hkv, D]
+    v_cache: np.ndarray             # [num_pages, page_size, Hkv, D]
+    block_table: np.ndarray         # [B, max_pages] int32
+    seq_lens: np.ndarray            # [B] int32
+    scale: float
+    window: Optional[int] = None
+    softcap: Optional[float] = None
+    alibi: Optional[np.ndarray] = None
+
+
+def decode_bf16(B=4, H=8, Hkv=2, D=128, page_size=16, seq_lens=None, max_len=512, salt=0, shuffle_pages=True,
+                spare_pages=3) -> DecodeWorkload:
+    """Paged-cache decode step.  Sequence lengths (if not given) are uniform on [1, max_len]; every
+    sequence owns ceil(len / page_size) pages drawn from one shuffled pool, so the physical order
+    of a sequence's pages is arbitrary (as in a serving system's allocator).  Configuration 8 in
+    the seed recipe.  Unused slots of the cache hold NaN-free random values like the used ones."""
+    rng = np.random.Generator(np.random.PCG64(tensor_seed(8, 5, salt)))
+    if seq_lens is None:
+        seq_lens = rng.integers(1, max_len + 1, size=B)
+    seq_lens = np.asarray(seq_lens, dtype=np.int32)
+    B = len(seq_lens)
+    pages_per_seq = [(int(n) + page_size - 1) // page_size for n in seq_lens]
+    max_pages = max(1, max(pages_per_seq))
+    n_pages = sum(pages_per_seq) + spare_pages
+    pool = np.arange(n_pages, dtype=np.int32)
+    if shuffle_pages:
+        rng.shuffle(pool)
+    table = np.zeros((B, max_pages), dtype=np.int32)
+    pos = 0
+    for b, npg in enumerate(pages_per_seq):
+        table[b, :npg] = pool[pos:pos + npg]
+        pos += npg
+    q = normal((B, H, D), tensor_seed(8, 0, salt))
+    k_cache = normal((n_pages, page_size, Hkv, D), tensor_seed(8, 1, salt))
+    v_cache = normal((n_pages, page_size, Hkv, D), tensor_seed(8, 2, salt))
+    return DecodeWorkload(f"decode_bf16_d{D}_p{page_size}", q, k_cache, v_cache, table, seq_lens, scale=D ** -0.5)
