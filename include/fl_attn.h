@@ -1,6 +1,7 @@
 /*
  * fl_attn.h -- C ABI of the fused attention-variant library for AMD MI355X (gfx950): the forward
- * pass of every variant and the backward pass of the variants without bias, gate and second stream.
+ * pass of every variant, the backward pass of the variants without bias, gate and second stream, and the
+ * decode step (one query per sequence over a paged key/value cache).
  *
  * One call computes, for every (b, g, h) and every query row i, without ever writing the
  * [Sq, Sk] score matrix to device memory:
@@ -175,6 +176,44 @@ size_t fl_attn_bwd_workspace_size(const fl_tensor* q, const fl_tensor* k, const 
 
 /* 1 if fl_attn_bwd has a kernel specialisation for (descriptor, dtype, D, Dv), else 0. */
 int fl_bwd_supported(const fl_variant_desc* desc, int dtype, int D, int Dv);
+
+/* Where the cached keys and values of each sequence live (decode step). */
+typedef struct {
+  uint32_t       struct_size;   /* sizeof(fl_paged_kv) */
+  uint32_t       reserved;
+  const int32_t* block_table;   /* [B, table_stride] device: page holding tokens p*page_size .. of sequence b;
+                                   NULL: no paging, sequence b is page b of the cache                         */
+  int32_t        table_stride;  /* elements between the rows of block_table                                  */
+  int32_t        page_size;     /* tokens per page (size[3] of the cache tensors); with a block table a
+                                   power of two >= 8                                                         */
+  const int32_t* seq_lens;      /* [B] device: cached tokens of each sequence, 0 <= len <= pages * page_size */
+  int32_t        max_seq_len;   /* host-side upper bound of seq_lens: sizes the launch and the workspace     */
+  int32_t        reserved2;
+} fl_paged_kv;
+
+/* One decode step: for every sequence b, attention of its single query row (the token at position
+ * len_b - 1) over its len_b cached keys and values -- the per-token call of the serving experiment
+ * in Sec. 4.1.  Same arithmetic as fl_attn_fwd for that row (Eq. 3, score_mod of Eq. 4, online
+ * softmax of Sec. 3.4); a causal mask is implied and changes nothing, FL_MASK_WINDOW keeps the last
+ * window + 1 keys; other masks, biases, the second stream and epilogues are FL_ERR_UNSUPPORTED.
+ *
+ *   q        [B, 1, H, 1, D]  bf16, D in {64, 128}
+ *   k_cache  [pages, 1, Hkv, page_size, D]  bf16, any strides with unit inner stride and 16-byte
+ *   v_cache  [pages, 1, Hkv, page_size, D]  aligned rows (e.g. a view of [pages, page_size, Hkv, D]);
+ *                                           Hkv divides H, H / Hkv <= 32
+ *   out      [B, 1, H, 1, D]  bf16 or f32;  lse [B, 1, H, 1, 1] f32 or NULL
+ *   aux      alibi_slopes for FL_MOD_ALIBI, and aux->workspace of fl_attn_decode_workspace_size bytes
+ *            (per-split partial results; 16-byte aligned; contents undefined afterwards)
+ *
+ * A sequence with len = 0 gets out = 0 and lse = -inf.  The key range of a sequence is cut into
+ * splits so that the launch fills the chip; the split count depends on B, Hkv and max_seq_len only,
+ * and results are bitwise reproducible.  Stream, ownership and error rules as for fl_attn_fwd.   */
+fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_tensor* v_cache,
+                         const fl_paged_kv* kv, const fl_variant_desc* desc, const fl_aux* aux,
+                         fl_tensor* out, fl_tensor* lse, void* stream);
+
+/* Bytes of aux->workspace that fl_attn_decode needs. */
+size_t fl_attn_decode_workspace_size(const fl_tensor* q, const fl_tensor* k_cache, const fl_paged_kv* kv);
 
 /* 1 if a kernel specialisation exists for (descriptor, dtype, D, Dv), else 0. */
 int fl_variant_supported(const fl_variant_desc* desc, int dtype, int D, int Dv);

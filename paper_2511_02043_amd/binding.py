@@ -43,6 +43,12 @@ class fl_aux(C.Structure):
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
 
 
+class fl_paged_kv(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("reserved", C.c_uint32), ("block_table", C.c_void_p),
+                ("table_stride", C.c_int32), ("page_size", C.c_int32), ("seq_lens", C.c_void_p),
+                ("max_seq_len", C.c_int32), ("reserved2", C.c_int32)]
+
+
 class FlError(RuntimeError):
     def __init__(self, status: int, text: str, detail: str):
         super().__init__(f"fl_attn status {status} ({text}): {detail}")
@@ -78,6 +84,11 @@ def lib() -> C.CDLL:
         L.fl_attn_bwd_workspace_size.argtypes = [TP, TP, C.POINTER(fl_variant_desc)]
         L.fl_bwd_supported.restype = C.c_int
         L.fl_bwd_supported.argtypes = [C.POINTER(fl_variant_desc), C.c_int, C.c_int, C.c_int]
+        L.fl_attn_decode.restype = C.c_int
+        L.fl_attn_decode.argtypes = [TP, TP, TP, C.POINTER(fl_paged_kv), C.POINTER(fl_variant_desc), C.POINTER(fl_aux),
+                                     TP, TP, C.c_void_p]
+        L.fl_attn_decode_workspace_size.restype = C.c_size_t
+        L.fl_attn_decode_workspace_size.argtypes = [TP, TP, C.POINTER(fl_paged_kv)]
         L.fl_variant_supported.restype = C.c_int
         L.fl_variant_supported.argtypes = [C.POINTER(fl_variant_desc), C.c_int, C.c_int, C.c_int]
         L.fl_strerror.restype = C.c_char_p
@@ -93,7 +104,7 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ["fl_attn_fwd", "fl_attn_fwd_workspace_size", "fl_attn_bwd", "fl_attn_bwd_workspace_size",
-           "fl_bwd_supported", "fl_variant_supported", "fl_strerror",
+           "fl_bwd_supported", "fl_attn_decode", "fl_attn_decode_workspace_size", "fl_variant_supported", "fl_strerror",
            "fl_last_error_detail", "fl_set_tuning", "fl_version"]
 
 
@@ -175,6 +186,28 @@ def fl_attn_bwd_workspace_size(q: fl_tensor, k: fl_tensor, desc: fl_variant_desc
 
 def fl_bwd_supported(desc: fl_variant_desc, dtype: int, D: int, Dv: int) -> bool:
     return bool(lib().fl_bwd_supported(_ref(desc), dtype, D, Dv))
+
+
+def paged_kv(*, block_table=None, page_size: int, seq_lens, max_seq_len: int) -> fl_paged_kv:
+    kv = fl_paged_kv()
+    kv.struct_size = C.sizeof(fl_paged_kv)
+    kv.block_table = None if block_table is None else block_table.data_ptr()
+    kv.table_stride = 0 if block_table is None else block_table.stride(0)
+    kv.page_size = page_size
+    kv.seq_lens = seq_lens.data_ptr()
+    kv.max_seq_len = max_seq_len
+    return kv
+
+
+def fl_attn_decode(q: fl_tensor, k_cache: fl_tensor, v_cache: fl_tensor, kv: fl_paged_kv, desc: fl_variant_desc,
+                   aux: Optional[fl_aux], out: fl_tensor, lse: Optional[fl_tensor], stream: int = 0) -> int:
+    """Raw call; returns the fl_status code."""
+    return lib().fl_attn_decode(_ref(q), _ref(k_cache), _ref(v_cache), _ref(kv), _ref(desc), _ref(aux), _ref(out),
+                                _ref(lse), C.c_void_p(stream))
+
+
+def fl_attn_decode_workspace_size(q: fl_tensor, k_cache: fl_tensor, kv: fl_paged_kv) -> int:
+    return lib().fl_attn_decode_workspace_size(_ref(q), _ref(k_cache), _ref(kv))
 
 
 def fl_variant_supported(desc: fl_variant_desc, dtype: int, D: int, Dv: int) -> bool:

@@ -9,6 +9,7 @@
 
 #include "../../include/fl_attn.h"
 #include "fl_bwd_registry.hpp"
+#include "fl_decode_registry.hpp"
 #include "fl_registry.hpp"
 
 static_assert(FL_MASK_CAUSAL == fl::kMaskCausal && FL_MASK_WINDOW == fl::kMaskWindow &&
@@ -229,6 +230,26 @@ BwdWorkspace bwd_workspace(int64_t B, int64_t G, int64_t H, int64_t Hkv, int64_t
   w.part_bytes = w.hsplit > 1 ? (size_t)w.hsplit * (size_t)(B * G * Hkv * Sk * D) * sizeof(float) : 0;
   w.total = 2 * w.stat_bytes + w.sum_bytes + 2 * w.part_bytes;
   return w;
+}
+
+const fl::DecodeEntry* find_decode_entry(int D, int mod) {
+  int n = 0;
+  const fl::DecodeEntry* tab = fl::entries_decode(&n);
+  for (int e = 0; e < n; ++e)
+    if (tab[e].D == D && tab[e].mod == mod) return &tab[e];
+  return nullptr;
+}
+
+// Splits of a sequence's key range: enough workgroups to fill the chip (one workgroup per CU fits),
+// at least 8 tiles of 32 keys per split.  A function of the shapes and the host-side length bound only.
+int decode_splits(int64_t B, int64_t Hkv, int64_t max_seq_len) {
+  const int64_t tiles = (max_seq_len + 31) / 32;
+  int64_t want = (512 + B * Hkv - 1) / (B * Hkv > 0 ? B * Hkv : 1);
+  const int64_t cap = tiles / 8 > 1 ? tiles / 8 : 1;
+  if (want > cap) want = cap;
+  if (want < 1) want = 1;
+  if (want > 64) want = 64;
+  return (int)want;
 }
 
 }  // namespace
@@ -627,6 +648,122 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
         return fail(FL_ERR_LAUNCH, "dk/dv reduction launch: %s", hipGetErrorString(e));
     }
   }
+  return FL_OK;
+}
+
+size_t fl_attn_decode_workspace_size(const fl_tensor* q, const fl_tensor* k_cache, const fl_paged_kv* kv) {
+  if (q == nullptr || k_cache == nullptr || kv == nullptr) return 0;
+  const int64_t B = q->size[0], H = q->size[2], D = q->size[4];
+  const int ns = decode_splits(B, k_cache->size[2], kv->max_seq_len);
+  return (size_t)(B * H * ns) * (size_t)(D + 2) * sizeof(float);
+}
+
+fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_tensor* v_cache, const fl_paged_kv* kv,
+                         const fl_variant_desc* desc, const fl_aux* aux, fl_tensor* out, fl_tensor* lse, void* stream_v) {
+  g_detail[0] = 0;
+  fl_status st = check_desc(desc);
+  if (st != FL_OK) return st;
+  if (q == nullptr || k_cache == nullptr || v_cache == nullptr || kv == nullptr || out == nullptr)
+    return fail(FL_ERR_NULL, "q, k_cache, v_cache, kv or out is NULL");
+  if (kv->struct_size != sizeof(fl_paged_kv))
+    return fail(FL_ERR_DESC, "kv->struct_size = %u, expected %zu", kv->struct_size, sizeof(fl_paged_kv));
+  if (aux != nullptr && aux->struct_size != sizeof(fl_aux))
+    return fail(FL_ERR_DESC, "aux->struct_size = %u, expected %zu", aux->struct_size, sizeof(fl_aux));
+  const uint32_t mask = canonical_mask(desc->mask);
+  if ((mask & (FL_MASK_DOC | FL_MASK_PREFIX)) || desc->n_bias != 0 || desc->combine != FL_SINGLE || desc->epilogue != 0)
+    return fail(FL_ERR_UNSUPPORTED, "the decode step covers scale, score_mod and the sliding window only");
+  if (q->dtype != FL_BF16) return fail(FL_ERR_DTYPE, "the decode step takes bf16 inputs (q dtype %d)", q->dtype);
+
+  const int64_t B = q->size[0], H = q->size[2], D = q->size[4];
+  const int64_t pages = k_cache->size[0], Hkv = k_cache->size[2], page_size = k_cache->size[3];
+  if (B < 0 || H < 0 || D <= 0 || pages < 0 || page_size <= 0) return fail(FL_ERR_SHAPE, "negative size");
+  if (q->size[1] != 1 || q->size[3] != 1) return fail(FL_ERR_SHAPE, "q must be [B, 1, H, 1, D]");
+  if (Hkv <= 0 || H % Hkv != 0 || H / Hkv > 32)
+    if (H != 0) return fail(FL_ERR_SHAPE, "kv heads (%lld) must divide q heads (%lld), at most 32 q heads per kv head", (long long)Hkv, (long long)H);
+  if (kv->page_size != page_size) return fail(FL_ERR_SHAPE, "kv->page_size = %d, cache size[3] = %lld", kv->page_size, (long long)page_size);
+  if (kv->max_seq_len < 0) return fail(FL_ERR_SHAPE, "max_seq_len negative");
+  int page_shift = 0;
+  if (kv->block_table != nullptr) {
+    if (page_size < 8 || (page_size & (page_size - 1)) != 0)
+      return fail(FL_ERR_SHAPE, "with a block table the page size (%lld) must be a power of two >= 8", (long long)page_size);
+    while ((1LL << page_shift) < page_size) ++page_shift;
+    if (kv->table_stride < (kv->max_seq_len + page_size - 1) / page_size)
+      return fail(FL_ERR_SHAPE, "table_stride %d is less than the pages of max_seq_len", kv->table_stride);
+  } else {
+    if (pages < B) return fail(FL_ERR_SHAPE, "without a block table the cache needs a page per sequence");
+    if (kv->max_seq_len > page_size) return fail(FL_ERR_SHAPE, "max_seq_len exceeds the page size");
+  }
+  const fl::DecodeEntry* de = find_decode_entry((int)D, (int)desc->score_mod);
+  if (de == nullptr || v_cache->size[4] != D)
+    return fail(FL_ERR_UNSUPPORTED, "no decode specialisation for D=%lld Dv=%lld score_mod=%u", (long long)D,
+                (long long)v_cache->size[4], desc->score_mod);
+  const bool empty = (B == 0 || H == 0);
+  const int64_t qsz[5] = {B, 1, H, 1, D}, csz[5] = {pages, 1, Hkv, page_size, D};
+  if (!empty) {
+    if ((st = check_data_tensor(q, "q", FL_BF16, qsz)) != FL_OK) return st;
+    if (kv->max_seq_len > 0) {
+      if ((st = check_data_tensor(k_cache, "k_cache", FL_BF16, csz)) != FL_OK) return st;
+      if ((st = check_data_tensor(v_cache, "v_cache", FL_BF16, csz)) != FL_OK) return st;
+    }
+    if (out->dtype != FL_BF16 && out->dtype != FL_F32) return fail(FL_ERR_DTYPE, "out dtype %d", out->dtype);
+    if ((st = check_data_tensor(out, "out", out->dtype, qsz)) != FL_OK) return st;
+    if (kv->seq_lens == nullptr) return fail(FL_ERR_NULL, "seq_lens is NULL");
+  }
+  const bool want_lse = lse != nullptr && lse->ptr != nullptr;
+  if (want_lse && !empty) {
+    if (lse->dtype != FL_F32) return fail(FL_ERR_DTYPE, "lse must be f32");
+    const int64_t lsz[5] = {B, 1, H, 1, 1};
+    for (int a = 0; a < 5; ++a)
+      if (lse->size[a] != lsz[a])
+        return fail(FL_ERR_SHAPE, "lse size[%d] = %lld, expected %lld", a, (long long)lse->size[a], (long long)lsz[a]);
+  }
+  if (empty) return FL_OK;
+  if (aux == nullptr) return fail(FL_ERR_AUX_MISSING, "the decode step needs aux (workspace)");
+  if (desc->score_mod == FL_MOD_ALIBI && aux->alibi_slopes == nullptr) return fail(FL_ERR_AUX_MISSING, "alibi_slopes");
+  const int ns = decode_splits(B, Hkv, kv->max_seq_len);
+  const size_t ws_need = (size_t)(B * H * ns) * (size_t)(D + 2) * sizeof(float);
+  if (aux->workspace == nullptr || aux->workspace_bytes < ws_need)
+    return fail(FL_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", ws_need, aux->workspace ? aux->workspace_bytes : (size_t)0);
+  if (((uintptr_t)aux->workspace) % 16 != 0) return fail(FL_ERR_ALIGN, "workspace not 16-byte aligned");
+  if (B * Hkv * ns > 0x7fffffffLL || B * H > 0x7fffffffLL) return fail(FL_ERR_SHAPE, "too many workgroups");
+
+  fl::DecodeParams p;
+  memset(&p, 0, sizeof(p));
+  p.q = (const uint16_t*)q->ptr;
+  p.q_sb = B > 1 ? q->stride[0] : 0;
+  p.q_sh = H > 1 ? q->stride[2] : 0;
+  p.k = (const uint16_t*)k_cache->ptr;
+  p.v = (const uint16_t*)v_cache->ptr;
+  p.k_sp = pages > 1 ? k_cache->stride[0] : 0;
+  p.k_st = page_size > 1 ? k_cache->stride[3] : 0;
+  p.k_sh = Hkv > 1 ? k_cache->stride[2] : 0;
+  p.v_sp = pages > 1 ? v_cache->stride[0] : 0;
+  p.v_st = page_size > 1 ? v_cache->stride[3] : 0;
+  p.v_sh = Hkv > 1 ? v_cache->stride[2] : 0;
+  p.block_table = kv->block_table;
+  p.table_stride = kv->table_stride;
+  p.page_shift = page_shift;
+  p.seq_lens = kv->seq_lens;
+  p.out = out->ptr;
+  p.o_sb = B > 1 ? out->stride[0] : 0;
+  p.o_sh = H > 1 ? out->stride[2] : 0;
+  p.out_f32 = out->dtype == FL_F32;
+  if (want_lse) {
+    p.lse = (float*)lse->ptr;
+    p.lse_sb = B > 1 ? lse->stride[0] : 0;
+    p.lse_sh = H > 1 ? lse->stride[2] : 0;
+  }
+  p.part_o = (float*)aux->workspace;
+  p.part_ml = p.part_o + B * H * ns * D;
+  p.alibi_slopes = aux->alibi_slopes;
+  p.B = (int)B; p.H = (int)H; p.Hkv = (int)Hkv; p.nsplit = ns;
+  p.window = (mask & FL_MASK_WINDOW) ? desc->window : -1;
+  p.scale = desc->scale;
+  p.softcap = desc->softcap;
+  hipStream_t stream = (hipStream_t)stream_v;
+  hipError_t e = de->main(p, (int)(B * Hkv * ns), stream);
+  if (e != hipSuccess) return fail(FL_ERR_LAUNCH, "decode launch: %s", hipGetErrorString(e));
+  if ((e = de->combine(p, (int)(B * H), stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "decode merge launch: %s", hipGetErrorString(e));
   return FL_OK;
 }
 

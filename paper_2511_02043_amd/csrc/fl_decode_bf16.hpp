@@ -1,0 +1,291 @@
+// Decode-step attention over a paged key/value cache for gfx950: one query per sequence (the
+// token being generated) against that sequence's cached keys and values -- the shape the
+// serving experiment of the paper's Sec. 4.1 runs once per generated token.  The arithmetic is
+// the forward pass (Eq. 3, score_mod of Eq. 4, online softmax of Sec. 3.4) for the single query
+// row at position len - 1; the work is reading the cache once, so the kernel is built around
+// HBM: every wave streams its own key/value tiles into a private LDS ring with direct
+// global->LDS loads, several tiles ahead, and never meets another wave inside the loop.
+//
+//   * a workgroup owns one (sequence, kv head, split of the key range); its four waves take the
+//     tiles of that range round-robin;
+//   * the query heads that share the kv head are the 32 columns of the MFMA tile (lane = head),
+//     so a K / V tile is read once for the whole group: S^T = K Q^T and O^T += V^T P^T exactly
+//     as in the forward kernel, with the running max / sum per lane;
+//   * a page table is followed per tile row when the direct loads are issued;
+//   * waves, then splits, are merged with the rescale rule of Sec. 3.3 / 3.4 (the partial
+//     (m, l, O) of each split goes through the caller's workspace to a small second kernel).
+#pragma once
+#include "fl_bwd_bf16.hpp"
+
+namespace fl {
+
+struct DecodeParams {
+  const uint16_t* q;               // [B, H, D], strides in elements
+  int64_t q_sb, q_sh;
+  const uint16_t* k;               // cache: page, token in page, kv head strides in elements
+  const uint16_t* v;
+  int64_t k_sp, k_st, k_sh, v_sp, v_st, v_sh;
+  const int32_t* block_table;      // [B, table_stride], or null: sequence b is page b
+  int32_t table_stride;
+  int32_t page_shift;              // log2(tokens per page) when block_table is given
+  const int32_t* seq_lens;         // [B]
+  void* out;                       // [B, H, D]
+  int64_t o_sb, o_sh;
+  int32_t out_f32;
+  float* lse;                      // [B, H] or null
+  int64_t lse_sb, lse_sh;
+  float* part_o;                   // workspace [B, H, nsplit, D]
+  float* part_ml;                  // workspace [B, H, nsplit, 2]: running max (log2 domain), sum
+  const float* alibi_slopes;       // [H]
+  int32_t B, H, Hkv, nsplit;
+  int32_t window;                  // < 0: no window
+  float scale, softcap;
+};
+
+template <int D_, int MOD_>
+struct DecodeCfg : BwdCfg<D_, MOD_, 0, 32, 1> {
+  static constexpr int NSTG = D_ == 128 ? 2 : 4;   // ring stages per wave (16 / 8 KiB each)
+  static constexpr int STAGE = 2 * BwdCfg<D_, MOD_, 0, 32, 1>::TILE;                 // K tile, V tile
+  static constexpr int WAVE_LDS = NSTG * STAGE;
+  static constexpr int LDS = 4 * WAVE_LDS;
+  static constexpr int IPT = 2 * BwdCfg<D_, MOD_, 0, 32, 1>::TILE_INSTR;             // load instructions per tile
+  static_assert((NSTG - 1) * IPT < 64, "vmcnt is a 6-bit counter");
+};
+
+template <int N>
+__device__ __forceinline__ void wait_vm() {          // at most N vector-memory operations still in flight
+  __builtin_amdgcn_s_waitcnt((N & 15) | 0x0F70 | ((N >> 4) << 14));
+}
+
+template <class C>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+decode_kernel(const DecodeParams p) {
+  constexpr int D = C::D, KK = C::KK, DB = C::DB, ROW = C::ROW, BN = 32;
+  typedef BwdWave<C> W;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  W w;
+  w.init(tid & 63);
+  const int lane = w.lane;
+
+  const int split = blockIdx.x % p.nsplit;
+  const int bhk = blockIdx.x / p.nsplit;
+  const int hk = bhk % p.Hkv, b = bhk / p.Hkv;
+  const int group = p.H / p.Hkv;                   // query heads per kv head (<= 32)
+  const int hq = hk * group + (w.col < group ? w.col : group - 1);   // this lane's query head (clamped copies beyond the group)
+  const int len = p.seq_lens[b];
+
+  // key tiles of this workgroup, then of this wave
+  const int first_key = p.window >= 0 ? max(0, len - 1 - p.window) : 0;
+  const int t_lo = first_key / BN, t_hi = (len + BN - 1) / BN;
+  const int per_split = (t_hi - t_lo + p.nsplit - 1) / p.nsplit;
+  const int t_begin = t_lo + split * per_split, t_end = min(t_hi, t_begin + per_split);
+
+  bf16x8 qf[KK];
+  {
+    const uint16_t* qp = p.q + b * p.q_sb + hq * p.q_sh;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) qf[kk] = *(const bf16x8*)(qp + 16 * kk + 8 * w.half);
+  }
+  const float c_scale = p.scale * kLog2e;
+  const float slope2 = C::MOD == kModAlibi ? p.alibi_slopes[hq] * kLog2e : 0.f;
+  float m_run = -INFINITY, l_run = 0.f;            // log2-domain running max (same in both halves), per-lane partial sum
+  f32x16 oacc[DB];
+#pragma unroll
+  for (int d = 0; d < DB; ++d) oacc[d] = W::zero16();
+
+  unsigned char* ring = lds_raw + wave * C::WAVE_LDS;
+  // all load instructions of tile t (32 keys of K, then of V) into ring stage `stage`; rows past
+  // the sequence end repeat its last key (their scores are masked)
+  auto load_tile = [&](int t, int stage) __attribute__((always_inline)) {
+    unsigned char* st = ring + stage * C::STAGE;
+#pragma unroll
+    for (int inst = 0; inst < C::TILE_INSTR; ++inst) {
+      const int dst_row = inst * C::RPI + lane / (D / 8);
+      const int chunk = (lane % (D / 8)) ^ swz_u<D>(dst_row);
+      // the rows of one instruction share a page (pages hold at least 8 tokens and tiles are aligned),
+      // so the page index is uniform: a scalar table lookup that does not wait for the loads in flight
+      const int j_first = min(t * BN + inst * C::RPI, len - 1);
+      const int j = min(t * BN + dst_row, len - 1);
+      int64_t page, off;
+      if (p.block_table != nullptr) {
+        page = p.block_table[(int64_t)b * p.table_stride + (j_first >> p.page_shift)];
+        off = j & ((1 << p.page_shift) - 1);
+      } else {
+        page = b;
+        off = j;
+      }
+      const uint16_t* kr = p.k + page * p.k_sp + off * p.k_st + hk * p.k_sh + chunk * 8;
+      const uint16_t* vr = p.v + page * p.v_sp + off * p.v_st + hk * p.v_sh + chunk * 8;
+      __builtin_amdgcn_global_load_lds((global_cvoid*)kr, (lds_void*)(st + inst * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((global_cvoid*)vr, (lds_void*)(st + C::TILE + inst * 1024), 16, 0, 0);
+    }
+  };
+
+  // this wave's tiles: t_begin + wave, + 4, ...; NSTG - 1 of them in flight ahead of the one in use
+  int t_issue = t_begin + wave;
+#pragma unroll
+  for (int s = 0; s < C::NSTG - 1; ++s) {
+    if (t_issue < t_end) load_tile(t_issue, s);
+    t_issue += 4;
+  }
+  int stage = 0;
+  for (int t = t_begin + wave; t < t_end; t += 4) {
+    const int stage_ld = stage == 0 ? C::NSTG - 1 : stage - 1;      // the stage the previous tile used
+    if (t_issue < t_end) {
+      load_tile(t_issue, stage_ld);
+      wait_vm<(C::NSTG - 1) * C::IPT>();           // everything but the NSTG - 1 younger tiles has landed
+    } else {
+      wait_vm<0>();
+    }
+    t_issue += 4;
+    const uint32_t base = (uint32_t)(wave * C::WAVE_LDS + stage * C::STAGE);
+    uint32_t ra_b[KK], ta_b[DB][2];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) ra_b[kk] = w.ra[kk] + base;
+#pragma unroll
+    for (int d = 0; d < DB; ++d) {
+      ta_b[d][0] = w.ta[d][0] + base;
+      ta_b[d][1] = w.ta[d][1] + base;
+    }
+    // scores of the tile's 32 keys for the group's heads: lane = head, register r = key 8*(r/4) + 4*half + r%4
+    f32x16 s = W::zero16();
+    w.template row_stream_g<RowOne<0>, KK, 2>(ra_b, [&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[decltype(fc)::value], s, 0, 0, 0);
+    });
+    const int jb = t * BN + 4 * w.half;            // key of register 0
+    const bool partial = t * BN + BN > len || t * BN < first_key;     // uniform
+    float x[16];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int j = jb + 8 * (r >> 2) + (r & 3);
+      float a;
+      if constexpr (C::MOD == kModSoftcap) {
+        const float e = fast_exp2(s[r] * (2.f * c_scale / p.softcap));
+        a = fmaf(fast_rcp(e + 1.f), -2.f * p.softcap * kLog2e, p.softcap * kLog2e);
+      } else if constexpr (C::MOD == kModAlibi) {
+        a = fmaf(s[r], c_scale, -slope2 * (float)(len - 1 - j));
+      } else {
+        a = s[r] * c_scale;
+      }
+      if (partial && (j >= len || j < first_key)) a = -INFINITY;
+      x[r] = a;
+      mx = fmaxf(mx, a);
+    }
+    mx = half_swap_max(mx);
+    const float m_new = fmaxf(m_run, mx);
+    const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = fast_exp2(m_run - m_safe);               // exp2(-inf) = 0 on the first tile
+    m_run = m_new;
+    float psum = 0.f;
+    uint32_t pw[8];
+#pragma unroll
+    for (int r2 = 0; r2 < 8; ++r2) {
+      const float p0 = fast_exp2(x[2 * r2] - m_safe), p1 = fast_exp2(x[2 * r2 + 1] - m_safe);
+      psum += p0 + p1;
+      pw[r2] = pack_bf16(p0, p1);
+    }
+    l_run = fmaf(l_run, alpha, psum);
+#pragma unroll
+    for (int d = 0; d < DB; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[d][r] *= alpha;
+    w.template tr_stream_g<TrOne<C::TILE, DB, ROW>, 2 * DB, 2>(ta_b, [&](auto fc, bf16x8 a) __attribute__((always_inline)) {
+      constexpr int f = decltype(fc)::value, d = f % DB, ks = f / DB;
+      const bf16x8 bop = __builtin_bit_cast(
+          bf16x8, (i32x4){(int)pw[4 * ks], (int)pw[4 * ks + 1], (int)pw[4 * ks + 2], (int)pw[4 * ks + 3]});
+      oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bop, oacc[d], 0, 0, 0);
+    });
+    stage = stage + 1 == C::NSTG ? 0 : stage + 1;
+  }
+
+  // ---- merge the four waves (Sec. 3.3 / 3.4 rescale rule): everyone parks (m, l, O) in its own
+  // ring region, wave 0 folds them and writes the split's partial result
+  const float l_wave = half_swap_sum(l_run);
+  float4* park = (float4*)(lds_raw + wave * C::WAVE_LDS) + lane;       // [quad][lane] float4, then (m, l)
+  static_assert((DB * 4 + 1) * 64 * 16 <= C::WAVE_LDS, "parking area");
+  W::template wait_lds<0>();
+#pragma unroll
+  for (int d = 0; d < DB; ++d)
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4)
+      park[(d * 4 + r4) * 64] = make_float4(oacc[d][4 * r4], oacc[d][4 * r4 + 1], oacc[d][4 * r4 + 2], oacc[d][4 * r4 + 3]);
+  park[DB * 4 * 64] = make_float4(m_run, l_wave, 0.f, 0.f);
+  __syncthreads();
+  if (wave == 0) {
+    float m_all = m_run;
+#pragma unroll
+    for (int u = 1; u < 4; ++u) {
+      const float4* other = (const float4*)(lds_raw + u * C::WAVE_LDS) + lane;
+      m_all = fmaxf(m_all, other[DB * 4 * 64].x);
+    }
+    const float m_safe = m_all == -INFINITY ? 0.f : m_all;
+    float l_all = 0.f;
+    f32x16 o[DB];
+#pragma unroll
+    for (int d = 0; d < DB; ++d) o[d] = W::zero16();
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float4* other = (const float4*)(lds_raw + u * C::WAVE_LDS) + lane;
+      const float4 ml = other[DB * 4 * 64];
+      const float wgt = fast_exp2(ml.x - m_safe);                 // 0 for a wave that saw no key
+      l_all = fmaf(ml.y, wgt, l_all);
+#pragma unroll
+      for (int d = 0; d < DB; ++d)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const float4 q4 = other[(d * 4 + r4) * 64];
+          o[d][4 * r4] = fmaf(q4.x, wgt, o[d][4 * r4]);
+          o[d][4 * r4 + 1] = fmaf(q4.y, wgt, o[d][4 * r4 + 1]);
+          o[d][4 * r4 + 2] = fmaf(q4.z, wgt, o[d][4 * r4 + 2]);
+          o[d][4 * r4 + 3] = fmaf(q4.w, wgt, o[d][4 * r4 + 3]);
+        }
+    }
+    if (w.col < group) {
+      const int64_t slot = ((int64_t)b * p.H + hq) * p.nsplit + split;
+      float* po = p.part_o + slot * D;
+#pragma unroll
+      for (int d = 0; d < DB; ++d)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4)
+          *(float4*)(po + 32 * d + 8 * r4 + 4 * w.half) = make_float4(o[d][4 * r4], o[d][4 * r4 + 1], o[d][4 * r4 + 2], o[d][4 * r4 + 3]);
+      if (w.half == 0) *(float2*)(p.part_ml + slot * 2) = make_float2(m_all, l_all);
+    }
+  }
+}
+
+// Merge of the splits of one (sequence, head): out = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M).
+template <int D>
+__global__ void __launch_bounds__(64) decode_combine_kernel(const DecodeParams p) {
+  const int bh = blockIdx.x;
+  const int h = bh % p.H, b = bh / p.H;
+  constexpr int CPT = D / 64;
+  const float* ml = p.part_ml + (int64_t)bh * p.nsplit * 2;
+  float m_all = -INFINITY;
+  for (int s = 0; s < p.nsplit; ++s) m_all = fmaxf(m_all, ml[2 * s]);
+  const float m_safe = m_all == -INFINITY ? 0.f : m_all;
+  float l_all = 0.f, acc[CPT];
+#pragma unroll
+  for (int e = 0; e < CPT; ++e) acc[e] = 0.f;
+  for (int s = 0; s < p.nsplit; ++s) {
+    const float wgt = fast_exp2(ml[2 * s] - m_safe);
+    l_all = fmaf(ml[2 * s + 1], wgt, l_all);
+    const float* po = p.part_o + ((int64_t)bh * p.nsplit + s) * D + threadIdx.x * CPT;
+#pragma unroll
+    for (int e = 0; e < CPT; ++e) acc[e] = fmaf(po[e], wgt, acc[e]);
+  }
+  const float inv = l_all > 0.f ? 1.f / l_all : 0.f;
+  const int64_t o = b * p.o_sb + h * p.o_sh + threadIdx.x * CPT;
+#pragma unroll
+  for (int e = 0; e < CPT; ++e) {
+    if (p.out_f32) ((float*)p.out)[o + e] = acc[e] * inv;
+    else ((uint16_t*)p.out)[o + e] = (uint16_t)(pack_bf16(acc[e] * inv, 0.f) & 0xFFFFu);
+  }
+  if (threadIdx.x == 0 && p.lse != nullptr)
+    p.lse[b * p.lse_sb + h * p.lse_sh] = l_all > 0.f ? (m_all + __log2f(l_all)) * kLn2 : -INFINITY;
+}
+
+}  // namespace fl

@@ -181,3 +181,53 @@ def upload_backward(w, dout: np.ndarray, grad_dtype: str = "f32", device="cuda:0
     aux = fb.aux_desc(alibi_slopes=slopes, q_doc_ids=qd, kv_doc_ids=kd, workspace=ws)
     return DeviceBackward(fwd, d_out, dq, dk, dv, aux, keep, fb.tensor_desc(d_out), fb.tensor_desc(dq),
                           fb.tensor_desc(dk), fb.tensor_desc(dv))
+
+
+@dataclasses.dataclass
+class DeviceDecode:
+    """Device tensors of one fl_attn_decode call (an inputs.DecodeWorkload)."""
+    q: torch.Tensor
+    k_cache: torch.Tensor
+    v_cache: torch.Tensor
+    out: torch.Tensor
+    lse: torch.Tensor
+    desc: fb.fl_variant_desc
+    kv: fb.fl_paged_kv
+    aux: fb.fl_aux
+    keep: List[torch.Tensor]
+    tq: fb.fl_tensor = None
+    tk: fb.fl_tensor = None
+    tv: fb.fl_tensor = None
+    tout: fb.fl_tensor = None
+    tlse: fb.fl_tensor = None
+
+    def run(self, stream: int = 0) -> int:
+        return fb.fl_attn_decode(self.tq, self.tk, self.tv, self.kv, self.desc, self.aux, self.tout, self.tlse, stream)
+
+    def run_checked(self, stream: int = 0) -> None:
+        fb.check(self.run(stream))
+
+
+def upload_decode(w, out_dtype: str = "f32", device="cuda:0", paged: bool = True) -> DeviceDecode:
+    """Cache stored [pages, page_size, Hkv, D] (the serving layout) and viewed [pages, 1, Hkv, page_size, D];
+    paged=False passes no block table (the workload's table must then be the identity)."""
+    tdt = torch.bfloat16
+    q = torch.from_numpy(np.ascontiguousarray(w.q)).to(device, tdt)[:, None, :, None, :]       # [B, 1, H, 1, D]
+    kc = torch.from_numpy(np.ascontiguousarray(w.k_cache)).to(device, tdt).permute(0, 2, 1, 3)[:, None]
+    vc = torch.from_numpy(np.ascontiguousarray(w.v_cache)).to(device, tdt).permute(0, 2, 1, 3)[:, None]
+    B, _, H, _, D = q.shape
+    out = torch.empty((B, 1, H, 1, D), dtype=torch.float32 if out_dtype == "f32" else tdt, device=device)
+    lse = torch.empty((B, 1, H, 1, 1), dtype=torch.float32, device=device)
+    table = torch.from_numpy(w.block_table).to(device) if paged else None
+    lens = torch.from_numpy(w.seq_lens).to(device)
+    mod = fb.FL_MOD_SOFTCAP if w.softcap is not None else (fb.FL_MOD_ALIBI if w.alibi is not None else fb.FL_MOD_NONE)
+    desc = fb.variant_desc(scale=float(w.scale), score_mod=mod, softcap=float(w.softcap or 0.0),
+                           mask=(fb.FL_MASK_WINDOW | fb.FL_MASK_CAUSAL) if w.window is not None else fb.FL_MASK_CAUSAL,
+                           window=int(w.window or 0))
+    kv = fb.paged_kv(block_table=table, page_size=w.k_cache.shape[1], seq_lens=lens,
+                     max_seq_len=int(w.seq_lens.max()) if len(w.seq_lens) else 0)
+    tq, tk, tv, tout, tlse = (fb.tensor_desc(x) for x in (q, kc, vc, out, lse))
+    ws = torch.empty(max(fb.fl_attn_decode_workspace_size(tq, tk, kv), 16), dtype=torch.uint8, device=device)
+    slopes = None if w.alibi is None else torch.from_numpy(np.asarray(w.alibi, np.float32)).to(device)
+    aux = fb.aux_desc(alibi_slopes=slopes, workspace=ws)
+    return DeviceDecode(q, kc, vc, out, lse, desc, kv, aux, [table, lens, ws, slopes], tq, tk, tv, tout, tlse)

@@ -1,0 +1,104 @@
+"""GPU parity of fl_attn_decode (through the C-ABI) against the fp64 decode oracle.
+
+Tolerance: the forward pass's (bf16 inputs, bf16 probabilities into an fp32-accumulating
+contraction): max-abs <= 1e-2 on fp32 outputs, lse <= 1e-3."""
+import numpy as np
+import pytest
+
+from oracle import decode_oracle as do
+from paper_2511_02043_amd import inputs, runner
+
+pytestmark = pytest.mark.gpu
+
+
+def run(w, out_dtype="f32", paged=True):
+    import torch
+    dd = runner.upload_decode(w, out_dtype=out_dtype, paged=paged)
+    dd.out.fill_(float("nan"))
+    dd.lse.fill_(float("nan"))
+    dd.run_checked()
+    torch.cuda.synchronize()
+    return dd.out.float().cpu().numpy()[:, 0, :, 0], dd.lse.cpu().numpy()[:, 0, :, 0, 0]
+
+
+def compare(w, label, out_dtype="f32", paged=True):
+    got, got_lse = run(w, out_dtype, paged)
+    ref, ref_lse = do.decode_attention(w.q, w.k_cache, w.v_cache, w.block_table, w.seq_lens, scale=w.scale,
+                                       window=w.window, softcap_value=w.softcap, alibi_slopes=w.alibi)
+    assert np.all(np.isfinite(got)), label
+    err = float(np.max(np.abs(got - ref)))
+    dead = np.isneginf(ref_lse)
+    assert np.array_equal(np.isneginf(got_lse), dead), label
+    le = float(np.max(np.abs(got_lse[~dead] - ref_lse[~dead]))) if np.any(~dead) else 0.0
+    print(f"{label}: max_abs={err:.3e} lse={le:.3e}", flush=True)
+    slack = 2.0 ** -8 * np.abs(ref) if out_dtype == "bf16" else 0.0
+    assert np.all(np.abs(got - ref) <= 1e-2 + slack), (label, err)
+    assert le <= 1e-3, (label, le)
+
+
+CASES = {
+    # ragged lengths around tile (32) and page boundaries, several splits' worth of keys, both head dims
+    "gqa4_d128_p16": lambda: inputs.decode_bf16(H=8, Hkv=2, D=128, page_size=16, seq_lens=[1, 31, 32, 33, 500, 1027]),
+    "gqa8_d64_p32": lambda: inputs.decode_bf16(H=16, Hkv=2, D=64, page_size=32, seq_lens=[7, 64, 65, 900, 2049]),
+    "mha_d128_p8": lambda: inputs.decode_bf16(H=4, Hkv=4, D=128, page_size=8, seq_lens=[15, 16, 17, 300]),
+    "gqa32_d64_p128": lambda: inputs.decode_bf16(H=32, Hkv=1, D=64, page_size=128, seq_lens=[129, 1000, 3]),
+    "long_many_splits": lambda: inputs.decode_bf16(H=8, Hkv=1, D=128, page_size=16, seq_lens=[8191, 4097]),
+    "empty_and_one": lambda: inputs.decode_bf16(H=4, Hkv=2, D=64, page_size=16, seq_lens=[0, 1, 0, 40]),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_decode_matches_oracle(name):
+    compare(CASES[name](), name)
+
+
+def test_decode_variants():
+    w = inputs.decode_bf16(H=8, Hkv=2, D=128, page_size=16, seq_lens=[5, 100, 700, 1500], salt=1)
+    w.window = 255
+    compare(w, "window_255")
+    w.window = 0
+    compare(w, "window_0")
+    w.window = None
+    w.softcap = 2.0
+    compare(w, "softcap")
+    w.softcap = None
+    w.alibi = inputs.alibi_slopes(8)
+    compare(w, "alibi")
+    w.window = 300
+    compare(w, "alibi_window")
+
+
+def test_decode_bf16_output_and_contiguous_cache():
+    w = inputs.decode_bf16(H=8, Hkv=2, D=64, page_size=16, seq_lens=[33, 500, 77], salt=2)
+    compare(w, "bf16_out", out_dtype="bf16")
+    # no block table: sequence b is page b of a cache whose pages hold a whole sequence
+    c = inputs.decode_bf16(H=8, Hkv=4, D=128, page_size=1024, seq_lens=[1000, 17, 513], salt=3, shuffle_pages=False,
+                           spare_pages=0)
+    assert np.array_equal(c.block_table[:, 0], np.arange(3))
+    compare(c, "contiguous", paged=False)
+
+
+def test_decode_is_reproducible_and_page_placement_does_not_matter():
+    w = inputs.decode_bf16(H=8, Hkv=2, D=128, page_size=16, seq_lens=[100, 900, 2500], salt=4)
+    a, la = run(w)
+    b, lb = run(w)
+    assert np.array_equal(a, b) and np.array_equal(la, lb)
+    perm = np.random.Generator(np.random.PCG64(5)).permutation(w.k_cache.shape[0])
+    inv = np.argsort(perm)
+    import dataclasses
+    w2 = dataclasses.replace(w, k_cache=w.k_cache[perm], v_cache=w.v_cache[perm], block_table=inv[w.block_table].astype(np.int32))
+    c, lc = run(w2)
+    assert np.array_equal(a, c) and np.array_equal(la, lc)
+
+
+def test_decode_error_paths():
+    from paper_2511_02043_amd import binding as fb
+    w = inputs.decode_bf16(H=8, Hkv=2, D=128, page_size=16, seq_lens=[40, 50])
+    dd = runner.upload_decode(w)
+    bad = fb.variant_desc(scale=0.1, mask=fb.FL_MASK_DOC)
+    assert fb.fl_attn_decode(dd.tq, dd.tk, dd.tv, dd.kv, bad, dd.aux, dd.tout, dd.tlse) == fb.FL_ERR_UNSUPPORTED
+    assert fb.fl_attn_decode(dd.tq, dd.tk, dd.tv, dd.kv, dd.desc, None, dd.tout, dd.tlse) == fb.FL_ERR_AUX_MISSING
+    small = fb.aux_desc(workspace=dd.keep[2][:16])
+    assert fb.fl_attn_decode(dd.tq, dd.tk, dd.tv, dd.kv, dd.desc, small, dd.tout, dd.tlse) == fb.FL_ERR_WORKSPACE
+    kv = fb.paged_kv(block_table=dd.keep[0], page_size=32, seq_lens=dd.keep[1], max_seq_len=50)
+    assert fb.fl_attn_decode(dd.tq, dd.tk, dd.tv, kv, dd.desc, dd.aux, dd.tout, dd.tlse) == fb.FL_ERR_SHAPE
