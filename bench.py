@@ -181,6 +181,53 @@ def run_grid_backward(steps, warmup):
     print(json.dumps({"grid_cells": len(rows), "file": "gpurun_out/bench_grid_bwd.json"}), flush=True)
 
 
+def time_decode(steps, warmup, B=64, H=32, Hkv=8, D=128, ctx=8192, page_size=16):
+    """One fl_attn_decode call per step: B sequences with lengths uniform on [ctx / 2, ctx], a paged cache in the
+    serving layout [pages, page_size, Hkv, D] with shuffled page placement, bf16.  The cache is drawn on the
+    device (seeded N(0,1)); the algorithmic bytes are the visible keys and values read once plus q and out."""
+    import torch
+    from paper_2511_02043_amd import binding as fb
+    g = torch.Generator(device="cuda").manual_seed(251102043)
+    rng = np.random.Generator(np.random.PCG64(251102043))
+    lens = rng.integers(ctx // 2, ctx + 1, size=B).astype(np.int32)
+    pages_per_seq = (lens + page_size - 1) // page_size
+    n_pages = int(pages_per_seq.sum())
+    pool = rng.permutation(n_pages).astype(np.int32)
+    table = np.zeros((B, int(pages_per_seq.max())), dtype=np.int32)
+    pos = 0
+    for b in range(B):
+        table[b, :pages_per_seq[b]] = pool[pos:pos + pages_per_seq[b]]
+        pos += pages_per_seq[b]
+    dev = "cuda:0"
+    kc = torch.randn((n_pages, page_size, Hkv, D), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    vc = torch.randn((n_pages, page_size, Hkv, D), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    q = torch.randn((B, H, D), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    out = torch.empty((B, 1, H, 1, D), dtype=torch.bfloat16, device=dev)
+    t_table, t_lens = torch.from_numpy(table).to(dev), torch.from_numpy(lens).to(dev)
+    tq = fb.tensor_desc(q[:, None, :, None, :])
+    tk = fb.tensor_desc(kc.permute(0, 2, 1, 3)[:, None])
+    tv = fb.tensor_desc(vc.permute(0, 2, 1, 3)[:, None])
+    tout = fb.tensor_desc(out)
+    kv = fb.paged_kv(block_table=t_table, page_size=page_size, seq_lens=t_lens, max_seq_len=int(lens.max()))
+    desc = fb.variant_desc(scale=D ** -0.5, mask=fb.FL_MASK_CAUSAL)
+    ws = torch.empty(max(fb.fl_attn_decode_workspace_size(tq, tk, kv), 16), dtype=torch.uint8, device=dev)
+    aux = fb.aux_desc(workspace=ws)
+    stream = torch.cuda.current_stream().cuda_stream
+    for _ in range(warmup):
+        fb.check(fb.fl_attn_decode(tq, tk, tv, kv, desc, aux, tout, None, stream))
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        fb.check(fb.fl_attn_decode(tq, tk, tv, kv, desc, aux, tout, None, stream))
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    byt = int(lens.sum()) * Hkv * D * 2 * 2 + 2 * B * H * D * 2
+    return dict(ms_per_step=ms, bytes=byt, gbs=byt / (ms * 1e-3) / 1e9, tokens=int(lens.sum()),
+                dims=dict(B=B, H=H, Hkv=Hkv, D=D, ctx=ctx, page_size=page_size))
+
+
 def gemm_reference(n=8192, reps=50):
     """TFLOP/s of torch.matmul on random bf16 data of size n^3: what the matrix cores sustain under the
     board's power limit with nothing but a contraction to run (context for roofline.frac, not a target)."""
@@ -310,6 +357,8 @@ def main():
                          "table on stderr, gpurun_out/bench_grid.json")
     ap.add_argument("--backward", action="store_true",
                     help="time fl_attn_bwd on the configurations it covers (table on stderr, gpurun_out/bench_bwd.json)")
+    ap.add_argument("--decode", action="store_true",
+                    help="time fl_attn_decode (64 sequences of 4k-8k cached tokens, 32 / 8 heads, D = 128, 16-token pages)")
     ap.add_argument("--no-gemm-reference", action="store_true",
                     help="skip the bf16 GEMM that shows what the matrix cores sustain on random data")
     ap.add_argument("--tune", default="", help="comma list key=value passed to fl_set_tuning (sweeps)")
@@ -337,6 +386,17 @@ def main():
         k, v = kv.split("=")
         fb.check(fb.fl_set_tuning(k, int(v)))
 
+    if args.decode:
+        r = time_decode(args.steps, args.warmup)
+        print(f"# decode: {r['ms_per_step']:.4f} ms  {r['gbs']:.0f} GB/s  {100 * r['gbs'] / PEAK_HBM_GBS:.1f}% of the HBM peak",
+              file=sys.stderr, flush=True)
+        print(json.dumps({"metric": "decode-step attention over a paged KV cache, GB/s of cache read", "value": r["gbs"],
+                          "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                          "ms_per_step": r["ms_per_step"], "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": "decode_b64_h32_kv8_d128_ctx4k-8k_page16", **r["dims"], "cached_tokens": r["tokens"]},
+                          "roofline": {"bound": "hbm", "achieved": r["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                       "frac": r["gbs"] / PEAK_HBM_GBS, "traffic": None}}), flush=True)
+        return
     if args.grid and args.backward:
         run_grid_backward(args.steps, args.warmup)
         return

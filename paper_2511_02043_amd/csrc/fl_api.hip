@@ -240,11 +240,11 @@ const fl::DecodeEntry* find_decode_entry(int D, int mod) {
   return nullptr;
 }
 
-// Splits of a sequence's key range: enough workgroups to fill the chip (one workgroup per CU fits),
-// at least 8 tiles of 32 keys per split.  A function of the shapes and the host-side length bound only.
+// Splits of a sequence's key range: several workgroups per CU over the launch (one is resident at a time,
+// and sequences differ in length), at least 8 tiles of 32 keys per split.  A function of the shapes and the host-side length bound only.
 int decode_splits(int64_t B, int64_t Hkv, int64_t max_seq_len) {
   const int64_t tiles = (max_seq_len + 31) / 32;
-  int64_t want = (512 + B * Hkv - 1) / (B * Hkv > 0 ? B * Hkv : 1);
+  int64_t want = (2048 + B * Hkv - 1) / (B * Hkv > 0 ? B * Hkv : 1);
   const int64_t cap = tiles / 8 > 1 ? tiles / 8 : 1;
   if (want > cap) want = cap;
   if (want < 1) want = 1;

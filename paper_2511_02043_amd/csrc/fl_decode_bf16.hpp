@@ -97,21 +97,41 @@ decode_kernel(const DecodeParams p) {
   for (int d = 0; d < DB; ++d) oacc[d] = W::zero16();
 
   unsigned char* ring = lds_raw + wave * C::WAVE_LDS;
+  // Pages of a tile: a tile of 32 keys touches at most four pages (pages hold at least 8 tokens and
+  // tiles are aligned to them).  They are looked up with scalar loads one tile ahead of the direct
+  // loads that need them, so that neither waits for the other.
+  struct Pages {
+    int64_t pg[4];
+  };
+  auto lookup = [&](int t) __attribute__((always_inline)) -> Pages {
+    Pages r;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (p.block_table != nullptr) {
+        const int j = min(t * BN + (u << p.page_shift), len - 1);           // first token of the tile's u-th page, clamped
+        r.pg[u] = p.block_table[(int64_t)b * p.table_stride + (j >> p.page_shift)];
+      } else {
+        r.pg[u] = b;
+      }
+    }
+    return r;
+  };
   // all load instructions of tile t (32 keys of K, then of V) into ring stage `stage`; rows past
   // the sequence end repeat its last key (their scores are masked)
-  auto load_tile = [&](int t, int stage) __attribute__((always_inline)) {
+  auto load_tile = [&](int t, int stage, const Pages& pages) __attribute__((always_inline)) {
     unsigned char* st = ring + stage * C::STAGE;
+    const int tile_page0 = (t * BN) >> p.page_shift;
 #pragma unroll
     for (int inst = 0; inst < C::TILE_INSTR; ++inst) {
       const int dst_row = inst * C::RPI + lane / (D / 8);
       const int chunk = (lane % (D / 8)) ^ swz_u<D>(dst_row);
-      // the rows of one instruction share a page (pages hold at least 8 tokens and tiles are aligned),
-      // so the page index is uniform: a scalar table lookup that does not wait for the loads in flight
+      // the rows of one instruction share a page, so its index is uniform
       const int j_first = min(t * BN + inst * C::RPI, len - 1);
       const int j = min(t * BN + dst_row, len - 1);
       int64_t page, off;
       if (p.block_table != nullptr) {
-        page = p.block_table[(int64_t)b * p.table_stride + (j_first >> p.page_shift)];
+        const int u = (j_first >> p.page_shift) - tile_page0;                // 0..3, uniform
+        page = u == 0 ? pages.pg[0] : (u == 1 ? pages.pg[1] : (u == 2 ? pages.pg[2] : pages.pg[3]));
         off = j & ((1 << p.page_shift) - 1);
       } else {
         page = b;
@@ -128,19 +148,21 @@ decode_kernel(const DecodeParams p) {
   int t_issue = t_begin + wave;
 #pragma unroll
   for (int s = 0; s < C::NSTG - 1; ++s) {
-    if (t_issue < t_end) load_tile(t_issue, s);
+    if (t_issue < t_end) load_tile(t_issue, s, lookup(t_issue));
     t_issue += 4;
   }
+  Pages next_pages = lookup(t_issue < t_end ? t_issue : t_begin);            // of the next tile to request
   int stage = 0;
   for (int t = t_begin + wave; t < t_end; t += 4) {
     const int stage_ld = stage == 0 ? C::NSTG - 1 : stage - 1;      // the stage the previous tile used
     if (t_issue < t_end) {
-      load_tile(t_issue, stage_ld);
+      load_tile(t_issue, stage_ld, next_pages);
       wait_vm<(C::NSTG - 1) * C::IPT>();           // everything but the NSTG - 1 younger tiles has landed
     } else {
       wait_vm<0>();
     }
     t_issue += 4;
+    if (t_issue < t_end) next_pages = lookup(t_issue);
     const uint32_t base = (uint32_t)(wave * C::WAVE_LDS + stage * C::STAGE);
     uint32_t ra_b[KK], ta_b[DB][2];
 #pragma unroll
