@@ -181,7 +181,7 @@ def run_grid_backward(steps, warmup):
     print(json.dumps({"grid_cells": len(rows), "file": "gpurun_out/bench_grid_bwd.json"}), flush=True)
 
 
-def time_decode(steps, warmup, B=64, H=32, Hkv=8, D=128, ctx=8192, page_size=16):
+def time_decode(steps, warmup, B=64, H=32, Hkv=8, D=128, ctx=8192, page_size=16, layout="NHD"):
     """One fl_attn_decode call per step: B sequences with lengths uniform on [ctx / 2, ctx], a paged cache in the
     serving layout [pages, page_size, Hkv, D] with shuffled page placement, bf16.  The cache is drawn on the
     device (seeded N(0,1)); the algorithmic bytes are the visible keys and values read once plus q and out."""
@@ -199,14 +199,16 @@ def time_decode(steps, warmup, B=64, H=32, Hkv=8, D=128, ctx=8192, page_size=16)
         table[b, :pages_per_seq[b]] = pool[pos:pos + pages_per_seq[b]]
         pos += pages_per_seq[b]
     dev = "cuda:0"
-    kc = torch.randn((n_pages, page_size, Hkv, D), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
-    vc = torch.randn((n_pages, page_size, Hkv, D), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    # NHD: [pages, page_size, Hkv, D] (a token's heads are adjacent); HND: [pages, Hkv, page_size, D] (a head's page is one block)
+    shape = (n_pages, page_size, Hkv, D) if layout == "NHD" else (n_pages, Hkv, page_size, D)
+    kc = torch.randn(shape, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    vc = torch.randn(shape, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
     q = torch.randn((B, H, D), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
     out = torch.empty((B, 1, H, 1, D), dtype=torch.bfloat16, device=dev)
     t_table, t_lens = torch.from_numpy(table).to(dev), torch.from_numpy(lens).to(dev)
     tq = fb.tensor_desc(q[:, None, :, None, :])
-    tk = fb.tensor_desc(kc.permute(0, 2, 1, 3)[:, None])
-    tv = fb.tensor_desc(vc.permute(0, 2, 1, 3)[:, None])
+    tk = fb.tensor_desc((kc.permute(0, 2, 1, 3) if layout == "NHD" else kc)[:, None])
+    tv = fb.tensor_desc((vc.permute(0, 2, 1, 3) if layout == "NHD" else vc)[:, None])
     tout = fb.tensor_desc(out)
     kv = fb.paged_kv(block_table=t_table, page_size=page_size, seq_lens=t_lens, max_seq_len=int(lens.max()))
     desc = fb.variant_desc(scale=D ** -0.5, mask=fb.FL_MASK_CAUSAL)
@@ -225,7 +227,7 @@ def time_decode(steps, warmup, B=64, H=32, Hkv=8, D=128, ctx=8192, page_size=16)
     ms = e0.elapsed_time(e1) / steps
     byt = int(lens.sum()) * Hkv * D * 2 * 2 + 2 * B * H * D * 2
     return dict(ms_per_step=ms, bytes=byt, gbs=byt / (ms * 1e-3) / 1e9, tokens=int(lens.sum()),
-                dims=dict(B=B, H=H, Hkv=Hkv, D=D, ctx=ctx, page_size=page_size))
+                dims=dict(B=B, H=H, Hkv=Hkv, D=D, ctx=ctx, page_size=page_size, cache_layout=layout))
 
 
 def gemm_reference(n=8192, reps=50):
@@ -357,6 +359,9 @@ def main():
                          "table on stderr, gpurun_out/bench_grid.json")
     ap.add_argument("--backward", action="store_true",
                     help="time fl_attn_bwd on the configurations it covers (table on stderr, gpurun_out/bench_bwd.json)")
+    ap.add_argument("--decode-layout", default="NHD", choices=["NHD", "HND"],
+                    help="cache storage order for --decode: [pages, page_size, Hkv, D] or [pages, Hkv, page_size, D]")
+    ap.add_argument("--decode-page", type=int, default=16, help="tokens per page for --decode")
     ap.add_argument("--decode", action="store_true",
                     help="time fl_attn_decode (64 sequences of 4k-8k cached tokens, 32 / 8 heads, D = 128, 16-token pages)")
     ap.add_argument("--no-gemm-reference", action="store_true",
@@ -387,7 +392,7 @@ def main():
         fb.check(fb.fl_set_tuning(k, int(v)))
 
     if args.decode:
-        r = time_decode(args.steps, args.warmup)
+        r = time_decode(args.steps, args.warmup, page_size=args.decode_page, layout=args.decode_layout)
         print(f"# decode: {r['ms_per_step']:.4f} ms  {r['gbs']:.0f} GB/s  {100 * r['gbs'] / PEAK_HBM_GBS:.1f}% of the HBM peak",
               file=sys.stderr, flush=True)
         print(json.dumps({"metric": "decode-step attention over a paged KV cache, GB/s of cache read", "value": r["gbs"],

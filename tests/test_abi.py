@@ -152,3 +152,42 @@ def test_backward_validation_paths_return_before_any_launch():
     t96.size[:] = [1, 1, 2, 64, 96]
     t96.stride[:] = [12288, 12288, 6144, 96, 1]
     assert fb.fl_attn_bwd(t96, t96, t96, t96, t96, lse, d, a, t96, t96, t96) == fb.FL_ERR_UNSUPPORTED
+
+
+def test_decode_validation_paths_return_before_any_launch():
+    q = fb.fl_tensor()
+    q.ptr, q.dtype = 0x1000, fb.FL_BF16
+    q.size[:] = [2, 1, 8, 1, 128]
+    q.stride[:] = [1024, 1024, 128, 128, 1]
+    c = fb.fl_tensor()
+    c.ptr, c.dtype = 0x100000, fb.FL_BF16
+    c.size[:] = [10, 1, 2, 16, 128]
+    c.stride[:] = [4096, 4096, 128, 256, 1]              # stored [pages, page_size, Hkv, D]
+    kv = fb.fl_paged_kv()
+    kv.struct_size = fb.C.sizeof(fb.fl_paged_kv)
+    kv.block_table, kv.table_stride, kv.page_size, kv.seq_lens, kv.max_seq_len = 0x2000, 5, 16, 0x3000, 80
+    d = fb.variant_desc(scale=0.1, mask=fb.FL_MASK_CAUSAL)
+    # one split for 80 tokens: per (sequence, head) D + 2 floats
+    assert fb.fl_attn_decode_workspace_size(q, c, kv) == 2 * 8 * (128 + 2) * 4
+    assert fb.fl_attn_decode(q, c, c, kv, d, None, q, None) == fb.FL_ERR_AUX_MISSING
+    a = fb.aux_desc()
+    assert fb.fl_attn_decode(q, c, c, kv, d, a, q, None) == fb.FL_ERR_WORKSPACE
+    assert fb.fl_attn_decode(q, c, c, None, d, a, q, None) == fb.FL_ERR_NULL
+    assert fb.fl_attn_decode(q, c, c, kv, fb.variant_desc(scale=0.1, n_bias=1), a, q, None) == fb.FL_ERR_UNSUPPORTED
+    assert fb.fl_attn_decode(q, c, c, kv, fb.variant_desc(scale=0.1, mask=fb.FL_MASK_PREFIX), a, q, None) == fb.FL_ERR_UNSUPPORTED
+    kv.page_size = 32
+    assert fb.fl_attn_decode(q, c, c, kv, d, a, q, None) == fb.FL_ERR_SHAPE              # page size vs cache shape
+    kv.page_size = 16
+    kv.table_stride = 4
+    assert fb.fl_attn_decode(q, c, c, kv, d, a, q, None) == fb.FL_ERR_SHAPE              # table too narrow for 80 tokens
+    kv.table_stride = 5
+    c.size[3] = 12
+    kv.page_size = 12
+    assert fb.fl_attn_decode(q, c, c, kv, d, a, q, None) == fb.FL_ERR_SHAPE              # not a power of two
+    c.size[3] = 16
+    kv.page_size = 16
+    c.size[2] = 3
+    assert fb.fl_attn_decode(q, c, c, kv, d, a, q, None) == fb.FL_ERR_SHAPE              # 3 kv heads vs 8 q heads
+    c.size[2] = 2
+    q.size[4] = 96
+    assert fb.fl_attn_decode(q, c, c, kv, d, a, q, None) == fb.FL_ERR_UNSUPPORTED
