@@ -215,6 +215,30 @@ fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_
 /* Bytes of aux->workspace that fl_attn_decode needs. */
 size_t fl_attn_decode_workspace_size(const fl_tensor* q, const fl_tensor* k_cache, const fl_paged_kv* kv);
 
+/* A variant compiled at run time from user expressions (opaque; owned by the caller until released). */
+typedef struct fl_custom_variant fl_custom_variant;
+
+/* Compiles (hipRTC, a few seconds) the forward kernel for a variant that the descriptor cannot
+ * name -- the library's stand-in for the paper's compiler accepting an arbitrary attention program:
+ *   score_mod_expr  C expression for the new score, of: float s (the scaled score, Eq. 4),
+ *                   int b, g, h (batch, row axis, query head), int i, j (query and key index);
+ *                   e.g. "s - 0.25f * fabsf((float)(i - j))".  NULL: s.
+ *   mask_expr       C expression, nonzero where the score is replaced by -inf (the mask_mod of
+ *                   Sec. 2.2, inverted), of int b, g, h, i, j; e.g. "j > i || (i - j) % 4 != 0".
+ *                   NULL: nothing masked.  It is evaluated on every score: no tile is skipped.
+ *   D               head dim (= Dv), 64 or 128; bf16 inputs.
+ * An expression is one C expression (no ; { } # quotes or backslashes).  FL_ERR_DESC with the
+ * compiler's first error in fl_last_error_detail() if it does not compile.  Needs no GPU.       */
+fl_status fl_compile_variant(const char* score_mod_expr, const char* mask_expr, int D, fl_custom_variant** handle);
+
+/* The forward pass of a compiled variant: q, k, v, out, lse, stream as for fl_attn_fwd (grouped
+ * heads included); the code object is loaded on the current device at the first call there.     */
+fl_status fl_attn_fwd_custom(fl_custom_variant* variant, const fl_tensor* q, const fl_tensor* k, const fl_tensor* v,
+                             float scale, fl_tensor* out, fl_tensor* lse, void* stream);
+
+/* Unloads and frees a compiled variant (no launch of it may be in flight). */
+void fl_release_variant(fl_custom_variant* variant);
+
 /* 1 if a kernel specialisation exists for (descriptor, dtype, D, Dv), else 0. */
 int fl_variant_supported(const fl_variant_desc* desc, int dtype, int D, int Dv);
 

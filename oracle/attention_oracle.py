@@ -39,7 +39,8 @@ PyTorch on every mask / bias kind; a pure-Python brute force written separately
 (oracle/brute_force.py); closed forms for Q = 0 (prefix means, ln(count), geometric
 ALiBi sums); single-visible-key rows; constant-V rows; row sums of P; a scalar run
 of Alg. 2; key-permutation and bias-shift invariances; differential with lambda = 0
-and with identical streams; gate = +40 / -40.  RMSNorm (not in the paper; defined by
+and with identical streams; gate = +40 / -40; attention_custom against attention() with
+ALiBi / window written as callables and against SDPA with an arbitrary predicate.  RMSNorm (not in the paper; defined by
 the benchmark configuration) is pinned only by its definition written out in the
 brute force, unit mean square, and scale invariance: parity unpinned beyond that.
 """
@@ -166,6 +167,36 @@ def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, *, scale: float,
                     probs[b, g, h] = p
     if return_probs:
         return out, lse, probs
+    return out, lse
+
+
+def attention_custom(q: np.ndarray, k: np.ndarray, v: np.ndarray, *, scale: float, score_mod=None, mask=None):
+    """Attention with an arbitrary score_mod (Eq. 4) and mask predicate (the mask_mod of Sec. 2.2,
+    inverted: True = hidden), given as callables on NumPy arrays:
+
+        score_mod(s, b, g, h, i, j) -> new scores     s [Sq, Sk] scaled scores, i [Sq, 1], j [1, Sk]
+        mask(b, g, h, i, j)         -> bool [Sq, Sk]
+
+    Same unfused program as attention(): scores, score_mod, mask -> -inf, stable softmax, P V.
+    Returns out [B,G,H,Sq,Dv] and lse [B,G,H,Sq] (float64)."""
+    B, G, H, Sq, D = q.shape
+    Hkv, Sk = k.shape[2], k.shape[3]
+    group = H // Hkv
+    i = np.arange(Sq, dtype=np.int64)[:, None]
+    j = np.arange(Sk, dtype=np.int64)[None, :]
+    out = np.zeros((B, G, H, Sq, v.shape[4]))
+    lse = np.zeros((B, G, H, Sq))
+    for b in range(B):
+        for g in range(G):
+            for h in range(H):
+                s = scaled_scores(np.asarray(q[b, g, h], np.float64), np.asarray(k[b, g, h // group], np.float64), scale)
+                if score_mod is not None:
+                    s = np.asarray(score_mod(s, b, g, h, i, j), dtype=np.float64)
+                if mask is not None:
+                    s = np.where(np.broadcast_to(mask(b, g, h, i, j), s.shape), NEG_INF, s)
+                p, row_lse = stable_softmax(s)
+                out[b, g, h] = p @ np.asarray(v[b, g, h // group], np.float64)
+                lse[b, g, h] = row_lse
     return out, lse
 
 

@@ -89,6 +89,12 @@ def lib() -> C.CDLL:
                                      TP, TP, C.c_void_p]
         L.fl_attn_decode_workspace_size.restype = C.c_size_t
         L.fl_attn_decode_workspace_size.argtypes = [TP, TP, C.POINTER(fl_paged_kv)]
+        L.fl_compile_variant.restype = C.c_int
+        L.fl_compile_variant.argtypes = [C.c_char_p, C.c_char_p, C.c_int, C.POINTER(C.c_void_p)]
+        L.fl_attn_fwd_custom.restype = C.c_int
+        L.fl_attn_fwd_custom.argtypes = [C.c_void_p, TP, TP, TP, C.c_float, TP, TP, C.c_void_p]
+        L.fl_release_variant.restype = None
+        L.fl_release_variant.argtypes = [C.c_void_p]
         L.fl_variant_supported.restype = C.c_int
         L.fl_variant_supported.argtypes = [C.POINTER(fl_variant_desc), C.c_int, C.c_int, C.c_int]
         L.fl_strerror.restype = C.c_char_p
@@ -104,7 +110,8 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ["fl_attn_fwd", "fl_attn_fwd_workspace_size", "fl_attn_bwd", "fl_attn_bwd_workspace_size",
-           "fl_bwd_supported", "fl_attn_decode", "fl_attn_decode_workspace_size", "fl_variant_supported", "fl_strerror",
+           "fl_bwd_supported", "fl_attn_decode", "fl_attn_decode_workspace_size", "fl_compile_variant", "fl_attn_fwd_custom",
+           "fl_release_variant", "fl_variant_supported", "fl_strerror",
            "fl_last_error_detail", "fl_set_tuning", "fl_version"]
 
 
@@ -208,6 +215,49 @@ def fl_attn_decode(q: fl_tensor, k_cache: fl_tensor, v_cache: fl_tensor, kv: fl_
 
 def fl_attn_decode_workspace_size(q: fl_tensor, k_cache: fl_tensor, kv: fl_paged_kv) -> int:
     return lib().fl_attn_decode_workspace_size(_ref(q), _ref(k_cache), _ref(kv))
+
+
+def fl_compile_variant(score_mod: Optional[str], mask: Optional[str], D: int):
+    """Returns (status, handle); handle is a ctypes void pointer (NULL on failure)."""
+    h = C.c_void_p()
+    st = lib().fl_compile_variant(None if score_mod is None else score_mod.encode(),
+                                  None if mask is None else mask.encode(), D, C.byref(h))
+    return st, h
+
+
+def fl_attn_fwd_custom(handle, q: fl_tensor, k: fl_tensor, v: fl_tensor, scale: float, out: fl_tensor,
+                       lse: Optional[fl_tensor] = None, stream: int = 0) -> int:
+    """Raw call; returns the fl_status code."""
+    return lib().fl_attn_fwd_custom(handle, _ref(q), _ref(k), _ref(v), C.c_float(scale), _ref(out), _ref(lse),
+                                    C.c_void_p(stream))
+
+
+def fl_release_variant(handle) -> None:
+    lib().fl_release_variant(handle)
+
+
+class CustomVariant:
+    """A variant compiled at run time from a score_mod and / or a mask expression (C syntax)."""
+
+    def __init__(self, score_mod: Optional[str], mask: Optional[str], D: int):
+        st, h = fl_compile_variant(score_mod, mask, D)
+        check(st)
+        self.handle = h
+
+    def forward(self, q: fl_tensor, k: fl_tensor, v: fl_tensor, scale: float, out: fl_tensor,
+                lse: Optional[fl_tensor] = None, stream: int = 0) -> int:
+        return fl_attn_fwd_custom(self.handle, q, k, v, scale, out, lse, stream)
+
+    def release(self) -> None:
+        if self.handle is not None and self.handle.value:
+            fl_release_variant(self.handle)
+        self.handle = None
+
+    def __del__(self):
+        try:
+            self.release()
+        except Exception:
+            pass
 
 
 def fl_variant_supported(desc: fl_variant_desc, dtype: int, D: int, Dv: int) -> bool:

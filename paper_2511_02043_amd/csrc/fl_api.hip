@@ -9,6 +9,7 @@
 
 #include "../../include/fl_attn.h"
 #include "fl_bwd_registry.hpp"
+#include "fl_host.hpp"
 #include "fl_decode_registry.hpp"
 #include "fl_registry.hpp"
 
@@ -21,54 +22,14 @@ static_assert(FL_EPI_RMSNORM == fl::kEpiRms && FL_EPI_GATE_SIGMOID == fl::kEpiGa
 
 namespace {
 
-thread_local char g_detail[384] = "";
-
-fl_status fail(fl_status st, const char* fmt, ...) {
-  va_list ap;
-  va_start(ap, fmt);
-  vsnprintf(g_detail, sizeof(g_detail), fmt, ap);
-  va_end(ap);
-  return st;
-}
+using fl::host::check_data_tensor;
+using fl::host::fail;
+using fl::host::g_detail;
+using fl::host::make_view;
 
 struct Tuning {
   int bm = 0, bn = 0, rb = 0, nw = 0, wpe = 0, order = -1, pair = -1;
 } g_tuning;
-
-int elem_size(int dtype) { return dtype == FL_BF16 ? 2 : 4; }
-
-// Common checks of a [B, G, H, S, D] data tensor (q, k, v, out, gate, q2, k2).
-fl_status check_data_tensor(const fl_tensor* t, const char* name, int want_dtype, const int64_t want[5]) {
-  if (t == nullptr || t->ptr == nullptr) return fail(FL_ERR_NULL, "%s is NULL", name);
-  if (t->dtype != want_dtype) return fail(FL_ERR_DTYPE, "%s has dtype %d, expected %d", name, t->dtype, want_dtype);
-  for (int a = 0; a < 5; ++a)
-    if (t->size[a] != want[a])
-      return fail(FL_ERR_SHAPE, "%s size[%d] = %lld, expected %lld", name, a, (long long)t->size[a],
-                  (long long)want[a]);
-  if (t->stride[4] != 1) return fail(FL_ERR_STRIDE, "%s innermost stride must be 1", name);
-  const int es = elem_size(t->dtype);
-  if (((uintptr_t)t->ptr) % 16 != 0) return fail(FL_ERR_ALIGN, "%s base pointer not 16-byte aligned", name);
-  for (int a = 0; a < 4; ++a) {
-    if (t->stride[a] < 0) return fail(FL_ERR_STRIDE, "%s stride[%d] negative", name, a);
-    if (t->size[a] > 1 && t->stride[a] == 0) return fail(FL_ERR_STRIDE, "%s stride[%d] is 0 (no broadcast here)", name, a);
-    if (t->size[a] > 1 && (t->stride[a] * es) % 16 != 0)
-      return fail(FL_ERR_ALIGN, "%s stride[%d] not a multiple of 16 bytes", name, a);
-  }
-  // the kernels address the rows of one key tile with 32-bit byte offsets from the tile's base
-  if (t->size[3] > 1 && t->stride[3] >= (int64_t)1 << 23)
-    return fail(FL_ERR_STRIDE, "%s row stride %lld is not below 2^23 elements", name, (long long)t->stride[3]);
-  return FL_OK;
-}
-
-fl::View make_view(const fl_tensor* t) {
-  fl::View v;
-  v.ptr = t->ptr;
-  v.sb = t->size[0] > 1 ? t->stride[0] : 0;
-  v.sg = t->size[1] > 1 ? t->stride[1] : 0;
-  v.sh = t->size[2] > 1 ? t->stride[2] : 0;
-  v.ss = t->size[3] > 1 ? t->stride[3] : 0;
-  return v;
-}
 
 struct Registry {
   const fl::KernelEntry* tab[5];

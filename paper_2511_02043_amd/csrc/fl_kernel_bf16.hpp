@@ -42,8 +42,6 @@
 // wave-uniform branch; l and the final normalisation use the same reference, so the result is
 // unchanged in real arithmetic.
 #pragma once
-#include <type_traits>
-
 #include "fl_params.hpp"
 
 namespace fl {
@@ -291,6 +289,8 @@ struct Wave {
         // to the final rounding of the products)
         const float d = slope_l2 * (float)(i[rb] - j0 - 32 * nb - 4 * half);
         x = fmaf(x, c_scale, -fabsf(d - alibi_c[r]));
+      } else if constexpr (C::MOD == kModCustom) {
+        x = fl_user_score_mod(x * p.scale, b, g, h, i[rb], j) * kLog2e;
       } else {
         x *= c_scale;
       }
@@ -423,6 +423,7 @@ struct Wave {
           bool hide = c > d_hi[rb];
           if constexpr ((MASK & kMaskWindow) != 0) hide = hide || c < d_lo[rb];
           if constexpr ((MASK & kMaskDoc) != 0) hide = hide || kd[r] != qdoc[rb];
+          if constexpr ((MASK & kMaskCustom) != 0) hide = hide || fl_user_mask(b, g, h, i[rb], jl + c);
           if (hide) sc[rb][nb][r] = -INFINITY;
         }
     }
@@ -814,6 +815,7 @@ fwd_bf16_kernel(const FwdParams p) {
   };
 
   auto wave_full = [&](int t) __attribute__((always_inline)) -> bool {            // is tile t fully visible to the wave?
+    if constexpr ((MASK & kMaskCustom) != 0) return false;   // an arbitrary predicate: evaluated on every score
     if constexpr ((MASK & kMaskDoc) != 0) return wave_class(t) == kTileFull;
     else return t >= tf_lo && t < tf_hi;
   };

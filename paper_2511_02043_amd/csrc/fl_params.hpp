@@ -1,15 +1,45 @@
 // Kernel-side parameter block and small device helpers shared by every kernel of the library.
 #pragma once
+// Under hipRTC (run-time compilation of a custom variant) the HIP built-ins are already there and
+// no system header is reachable: the one library facility the kernels use is declared here.
+#ifdef __HIPCC_RTC__
+typedef signed char int8_t;
+typedef unsigned char uint8_t;
+typedef short int16_t;
+typedef unsigned short uint16_t;
+typedef int int32_t;
+typedef unsigned int uint32_t;
+typedef long long int64_t;
+typedef unsigned long long uint64_t;
+#ifndef INFINITY
+#define INFINITY __builtin_huge_valf()
+#endif
+namespace std {
+template <class T, T v>
+struct integral_constant {
+  static constexpr T value = v;
+  typedef T value_type;
+  constexpr operator value_type() const noexcept { return value; }
+  constexpr value_type operator()() const noexcept { return value; }
+};
+}  // namespace std
+#else
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include <type_traits>
+#endif
 
 namespace fl {
 
 // Mask bits / enums mirror include/fl_attn.h (kept numerically identical; checked in fl_api.hip).
 constexpr uint32_t kMaskCausal = 1, kMaskWindow = 2, kMaskDoc = 4, kMaskPrefix = 8;
 constexpr int kModNone = 0, kModAlibi = 1, kModSoftcap = 2;
+// Variants compiled at run time from user expressions (fl_compile_variant): the score_mod and the
+// mask predicate are the two functions below, defined by the generated translation unit.  The
+// library's own kernels never instantiate these values, so the functions need no definition there.
+constexpr int kModCustom = 3;
+constexpr uint32_t kMaskCustom = 16;
 constexpr uint32_t kEpiRms = 1, kEpiGate = 2;
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -58,6 +88,13 @@ struct FwdParams {
   int32_t bias_lds_wave; // bytes of staging per wave (two buffers for every bias up to the last staged one)
   int32_t pair;          // bf16 kernels: 1 = a workgroup takes q-tiles nq - 1 - i and i (balanced causal work)
 };
+
+}  // namespace fl
+// new score from the scaled score s of query i and key j (Eq. 4's score_mod)
+__device__ float fl_user_score_mod(float s, int b, int g, int h, int i, int j);
+// true where the score of (i, j) is to be replaced by -inf (the mask_mod of Sec. 2.2, inverted)
+__device__ bool fl_user_mask(int b, int g, int h, int i, int j);
+namespace fl {
 
 // Compile-time loop: f(std::integral_constant<int, I>) for I in [B, E).
 template <int B, int E, class F>

@@ -1,0 +1,190 @@
+// Run-time compilation of attention variants that no compiled specialisation covers: the caller
+// gives the score_mod (Eq. 4) and the mask predicate (the mask_mod of Sec. 2.2) as C expressions,
+// and the forward kernel template is instantiated around them with hipRTC -- the nearest
+// equivalent, in a hand-written library, of the paper's compiler taking an arbitrary attention
+// program.  The generated kernel is the same software-pipelined bf16 kernel as the built-in
+// variants; a custom mask is evaluated on every score (no tile is skipped, as in the paper's
+// own kernels, Sec. 3.8).
+#include <hip/hip_runtime.h>
+#include <hip/hiprtc.h>
+
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "../../include/fl_attn.h"
+#include "fl_host.hpp"
+#include "fl_registry.hpp"
+
+namespace {
+#include "_build/fl_embedded.inc"   // kParamsHpp, kKernelHpp: the two kernel headers as strings
+}
+
+struct fl_custom_variant {
+  int D = 0;
+  std::vector<char> code;          // the compiled code object
+  std::string kernel_name;         // lowered name of the instantiated kernel
+  std::mutex mu;
+  hipModule_t module[64] = {};     // loaded lazily, once per device
+  hipFunction_t func[64] = {};
+};
+
+namespace {
+
+// Kernel shape of the generated variants: 4 waves x 32 query rows, 64-key tiles, two waves per SIMD.
+constexpr int kWaves = 4, kBN = 64, kBM = 128;
+
+bool expression_ok(const char* e) {
+  // one C expression: no statement separators, braces, preprocessor lines or string literals
+  for (const char* c = e; *c; ++c)
+    if (*c == ';' || *c == '{' || *c == '}' || *c == '#' || *c == '"' || *c == '\\' || *c == '\n') return false;
+  return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+fl_status fl_compile_variant(const char* score_mod_expr, const char* mask_expr, int D, fl_custom_variant** handle) {
+  fl::host::clear_detail();
+  if (handle == nullptr) return fl::host::fail(FL_ERR_NULL, "handle is NULL");
+  *handle = nullptr;
+  if (D != 64 && D != 128) return fl::host::fail(FL_ERR_UNSUPPORTED, "custom variants are built for head dims 64 and 128");
+  if (score_mod_expr == nullptr && mask_expr == nullptr) return fl::host::fail(FL_ERR_DESC, "neither a score_mod nor a mask expression");
+  if ((score_mod_expr && !expression_ok(score_mod_expr)) || (mask_expr && !expression_ok(mask_expr)))
+    return fl::host::fail(FL_ERR_DESC, "an expression may not contain ; { } # \" \\ or a line break");
+
+  const int mod = score_mod_expr ? fl::kModCustom : fl::kModNone;
+  const unsigned mask = mask_expr ? fl::kMaskCustom : 0u;
+  char inst[256];
+  snprintf(inst, sizeof(inst), "fl::fwd_bf16_kernel<fl::Bf16Cfg<%d, %d, %d, 1, %d, 2, %d, %uu, 0, false, 0u>>", D, D, kWaves, kBN, mod, mask);
+  std::string src = "#include \"fl_kernel_bf16.hpp\"\n";
+  src += "__device__ float fl_user_score_mod(float s, int b, int g, int h, int i, int j) { return (";
+  src += score_mod_expr ? score_mod_expr : "s";
+  src += "); }\n__device__ bool fl_user_mask(int b, int g, int h, int i, int j) { return (";
+  src += mask_expr ? mask_expr : "false";
+  src += "); }\ntemplate __global__ void ";
+  src += inst;
+  src += "(const fl::FwdParams);\n";
+
+  const char* headers[] = {kParamsHpp, kKernelHpp};
+  const char* names[] = {"fl_params.hpp", "fl_kernel_bf16.hpp"};
+  hiprtcProgram prog;
+  if (hiprtcCreateProgram(&prog, src.c_str(), "fl_custom_variant.hip", 2, headers, names) != HIPRTC_SUCCESS)
+    return fl::host::fail(FL_ERR_LAUNCH, "hiprtcCreateProgram failed");
+  std::string expr = std::string("&") + inst;
+  hiprtcAddNameExpression(prog, expr.c_str());
+  // the library's own flags: gfx950 only, packed fp32 instructions off
+  const char* opts[] = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
+  const hiprtcResult r = hiprtcCompileProgram(prog, (int)(sizeof(opts) / sizeof(opts[0])), opts);
+  if (r != HIPRTC_SUCCESS) {
+    size_t n = 0;
+    hiprtcGetProgramLogSize(prog, &n);
+    std::string log(n, 0);
+    if (n) hiprtcGetProgramLog(prog, &log[0]);
+    // the first error line is what the caller needs; the detail buffer keeps its head
+    const size_t at = log.find("error:");
+    fl_status st = fl::host::fail(FL_ERR_DESC, "expression does not compile: %.300s", at == std::string::npos ? log.c_str() : log.c_str() + at);
+    hiprtcDestroyProgram(&prog);
+    return st;
+  }
+  fl_custom_variant* v = new fl_custom_variant;
+  v->D = D;
+  size_t cs = 0;
+  hiprtcGetCodeSize(prog, &cs);
+  v->code.resize(cs);
+  hiprtcGetCode(prog, v->code.data());
+  const char* lowered = nullptr;
+  if (hiprtcGetLoweredName(prog, expr.c_str(), &lowered) != HIPRTC_SUCCESS || lowered == nullptr) {
+    hiprtcDestroyProgram(&prog);
+    delete v;
+    return fl::host::fail(FL_ERR_LAUNCH, "no lowered kernel name");
+  }
+  v->kernel_name = lowered;
+  hiprtcDestroyProgram(&prog);
+  *handle = v;
+  return FL_OK;
+}
+
+void fl_release_variant(fl_custom_variant* v) {
+  if (v == nullptr) return;
+  for (int d = 0; d < 64; ++d)
+    if (v->module[d] != nullptr) (void)hipModuleUnload(v->module[d]);
+  delete v;
+}
+
+fl_status fl_attn_fwd_custom(fl_custom_variant* v, const fl_tensor* q, const fl_tensor* k, const fl_tensor* vv, float scale,
+                             fl_tensor* out, fl_tensor* lse, void* stream_v) {
+  fl::host::clear_detail();
+  if (v == nullptr || q == nullptr || k == nullptr || vv == nullptr || out == nullptr)
+    return fl::host::fail(FL_ERR_NULL, "handle, q, k, v or out is NULL");
+  if (!(scale > 0.f) || scale != scale || scale > 3.0e38f) return fl::host::fail(FL_ERR_DESC, "scale must be finite and > 0");
+  if (q->dtype != FL_BF16) return fl::host::fail(FL_ERR_DTYPE, "custom variants take bf16 inputs");
+  const int64_t B = q->size[0], G = q->size[1], H = q->size[2], Sq = q->size[3], D = q->size[4];
+  const int64_t Hkv = k->size[2], Sk = k->size[3];
+  if (D != v->D || vv->size[4] != v->D) return fl::host::fail(FL_ERR_SHAPE, "this variant was compiled for head dim %d", v->D);
+  if (B < 0 || G < 0 || H < 0 || Sq < 0 || Sk <= 0) return fl::host::fail(FL_ERR_SHAPE, "negative size or no keys");
+  if (Sq > 0x7fffff00LL || Sk > 0x7fffff00LL || B * G * H > 0x7fffffffLL) return fl::host::fail(FL_ERR_SHAPE, "size too large");
+  if (Hkv <= 0 || H % Hkv != 0)
+    if (H != 0) return fl::host::fail(FL_ERR_SHAPE, "k heads must divide q heads");
+  if (B == 0 || G == 0 || H == 0 || Sq == 0) return FL_OK;
+  const int64_t qsz[5] = {B, G, H, Sq, D}, ksz[5] = {B, G, Hkv, Sk, D};
+  fl_status st;
+  if ((st = fl::host::check_data_tensor(q, "q", FL_BF16, qsz)) != FL_OK) return st;
+  if ((st = fl::host::check_data_tensor(k, "k", FL_BF16, ksz)) != FL_OK) return st;
+  if ((st = fl::host::check_data_tensor(vv, "v", FL_BF16, ksz)) != FL_OK) return st;
+  if (out->dtype != FL_BF16 && out->dtype != FL_F32) return fl::host::fail(FL_ERR_DTYPE, "out dtype %d", out->dtype);
+  if ((st = fl::host::check_data_tensor(out, "out", out->dtype, qsz)) != FL_OK) return st;
+  const bool want_lse = lse != nullptr && lse->ptr != nullptr;
+  if (want_lse) {
+    if (lse->dtype != FL_F32) return fl::host::fail(FL_ERR_DTYPE, "lse must be f32");
+    const int64_t lsz[5] = {B, G, H, Sq, 1};
+    for (int a = 0; a < 5; ++a)
+      if (lse->size[a] != lsz[a]) return fl::host::fail(FL_ERR_SHAPE, "lse size[%d]", a);
+    if (Sq > 1 && lse->stride[3] != 1) return fl::host::fail(FL_ERR_STRIDE, "lse must be contiguous along Sq");
+  }
+
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= 64) return fl::host::fail(FL_ERR_LAUNCH, "hipGetDevice: %s", hipGetErrorString(e));
+  {
+    std::lock_guard<std::mutex> lock(v->mu);
+    if (v->func[dev] == nullptr) {
+      if ((e = hipModuleLoadData(&v->module[dev], v->code.data())) != hipSuccess)
+        return fl::host::fail(FL_ERR_LAUNCH, "hipModuleLoadData: %s", hipGetErrorString(e));
+      if ((e = hipModuleGetFunction(&v->func[dev], v->module[dev], v->kernel_name.c_str())) != hipSuccess)
+        return fl::host::fail(FL_ERR_LAUNCH, "hipModuleGetFunction(%s): %s", v->kernel_name.c_str(), hipGetErrorString(e));
+    }
+  }
+
+  fl::FwdParams p;
+  memset(&p, 0, sizeof(p));
+  p.q = fl::host::make_view(q);
+  p.k = fl::host::make_view(k);
+  p.v = fl::host::make_view(vv);
+  p.out = fl::host::make_view(out);
+  if (want_lse) {
+    p.lse = (float*)lse->ptr;
+    p.lse_sb = lse->size[0] > 1 ? lse->stride[0] : 0;
+    p.lse_sg = lse->size[1] > 1 ? lse->stride[1] : 0;
+    p.lse_sh = lse->size[2] > 1 ? lse->stride[2] : 0;
+  }
+  p.B = (int)B; p.G = (int)G; p.H = (int)H; p.Hkv = (int)Hkv; p.Sq = (int)Sq; p.Sk = (int)Sk;
+  p.D = (int)D; p.Dv = (int)D;
+  p.scale = scale;
+  p.out_f32 = out->dtype == FL_F32;
+  p.n_qtiles = (int)((Sq + kBM - 1) / kBM);
+  p.lds_bytes = 4 * kBN * (int)D * 2;              // K ring and V ring of two 64-key tiles each
+  const int64_t nbh = B * G * H;
+  p.order = nbh % 8 == 0 ? 1 : 0;
+  const int64_t nblocks = nbh * p.n_qtiles;
+  if (nblocks > 0x7fffffffLL) return fl::host::fail(FL_ERR_SHAPE, "too many workgroups");
+  void* args[] = {&p};
+  e = hipModuleLaunchKernel(v->func[dev], (unsigned)nblocks, 1, 1, kWaves * 64, 1, 1, (unsigned)p.lds_bytes, (hipStream_t)stream_v, args, nullptr);
+  if (e != hipSuccess) return fl::host::fail(FL_ERR_LAUNCH, "custom variant launch: %s", hipGetErrorString(e));
+  return FL_OK;
+}
+
+}  // extern "C"

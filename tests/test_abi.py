@@ -191,3 +191,21 @@ def test_decode_validation_paths_return_before_any_launch():
     c.size[2] = 2
     q.size[4] = 96
     assert fb.fl_attn_decode(q, c, c, kv, d, a, q, None) == fb.FL_ERR_UNSUPPORTED
+
+
+def test_custom_variant_compiles_without_a_gpu_and_reports_errors():
+    st, h = fb.fl_compile_variant("s - 0.5f * fabsf((float)(i - j))", "j > i || (i - j) % 2 != 0", 64)
+    assert st == fb.FL_OK and h.value
+    t = fb.fl_tensor()
+    assert fb.fl_attn_fwd_custom(h, t, t, t, -1.0, t) == fb.FL_ERR_DESC           # scale
+    t.dtype = fb.FL_F32
+    assert fb.fl_attn_fwd_custom(h, t, t, t, 0.1, t) == fb.FL_ERR_DTYPE
+    t.dtype = fb.FL_BF16
+    t.size[:] = [1, 1, 1, 8, 128]
+    assert fb.fl_attn_fwd_custom(h, t, t, t, 0.1, t) == fb.FL_ERR_SHAPE           # compiled for D = 64
+    fb.fl_release_variant(h)
+    st, h = fb.fl_compile_variant("s + oops", None, 128)
+    assert st == fb.FL_ERR_DESC and "oops" in fb.fl_last_error_detail() and not h.value
+    assert fb.fl_compile_variant("s } {", None, 64)[0] == fb.FL_ERR_DESC
+    assert fb.fl_compile_variant(None, None, 64)[0] == fb.FL_ERR_DESC
+    assert fb.fl_compile_variant("s", None, 32)[0] == fb.FL_ERR_UNSUPPORTED

@@ -386,3 +386,33 @@ def test_row_sampling_agrees_with_full_evaluation():
             np.testing.assert_allclose(o, out[b, g, h, i], atol=1e-13)
             full = lse[b, :, g, h, i] if w.q2 is not None else lse[b, g, h, i]
             np.testing.assert_allclose(l, full, atol=1e-13)
+
+
+# ---------------------------------------------------------------------------------------
+# attention_custom: callables for score_mod and mask
+# ---------------------------------------------------------------------------------------
+
+def test_custom_callables_reproduce_the_named_variants():
+    q, k, v = rand((2, 1, 4, 29, 8), 91), rand((2, 1, 2, 29, 8), 92), rand((2, 1, 2, 29, 6), 93)
+    slopes = inputs.alibi_slopes(4).astype(np.float64)
+    ref, ref_lse = ao.attention(q, k, v, scale=0.3, window=6, alibi_slopes=slopes)
+    out, lse = ao.attention_custom(q, k, v, scale=0.3,
+                                   score_mod=lambda s, b, g, h, i, j: s - slopes[h] * np.abs(i - j),
+                                   mask=lambda b, g, h, i, j: (j > i) | (i - j > 6))
+    np.testing.assert_allclose(out, ref, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(lse, ref_lse, rtol=0, atol=1e-13)
+    ref, _ = ao.attention(q, k, v, scale=0.3, softcap_value=0.8, causal=True)
+    out, _ = ao.attention_custom(q, k, v, scale=0.3, score_mod=lambda s, b, g, h, i, j: 0.8 * np.tanh(s / 0.8),
+                                 mask=lambda b, g, h, i, j: j > i)
+    np.testing.assert_allclose(out, ref, rtol=0, atol=1e-13)
+
+
+def test_custom_predicate_matches_sdpa():
+    q, k, v = rand((1, 1, 2, 21, 8), 94), rand((1, 1, 2, 21, 8), 95), rand((1, 1, 2, 21, 8), 96)
+    i = np.arange(21)[:, None]
+    j = np.arange(21)[None, :]
+    hidden = (j > i) | (((i ^ j) & 4) != 0)
+    bias = 0.05 * ((i - j) % 5)
+    out, _ = ao.attention_custom(q, k, v, scale=0.4, score_mod=lambda s, b, g, h, ii, jj: s + 0.05 * ((ii - jj) % 5),
+                                 mask=lambda b, g, h, ii, jj: (jj > ii) | (((ii ^ jj) & 4) != 0))
+    np.testing.assert_allclose(out, sdpa(q, k, v, 0.4, allowed=~hidden, bias=bias.astype(np.float64)), rtol=0, atol=1e-12)
