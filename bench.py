@@ -230,6 +230,52 @@ def time_decode(steps, warmup, B=64, H=32, Hkv=8, D=128, ctx=8192, page_size=16,
                 dims=dict(B=B, H=H, Hkv=Hkv, D=D, ctx=ctx, page_size=page_size, cache_layout=layout))
 
 
+def time_custom(steps, warmup):
+    """Variants compiled at run time, on the shapes of the ALiBi configuration (B=8 H=16 S=2048 D=64): the ALiBi
+    score_mod as an expression (same arithmetic as the built-in variant, for comparison), and two variants no
+    descriptor names.  FLOPs on unmasked pairs, as everywhere."""
+    import torch
+    from paper_2511_02043_amd import binding as fb, inputs, runner
+    w = inputs.alibi_bf16()
+    d = w.dims
+    dw = runner.upload(w, out_dtype="same")
+    stream = torch.cuda.current_stream().cuda_stream
+    S = d["Sq"]
+    i = np.arange(S, dtype=np.int64)[:, None]
+    j = np.arange(S, dtype=np.int64)[None, :]
+    cases = [
+        ("built-in ALiBi (descriptor)", None, None, 0, S * S),
+        ("ALiBi as an expression", "s - exp2f(-0.5f * (float)(h + 1)) * fabsf((float)(i - j))", None, 0, S * S),
+        ("bucketed relative bias, causal as an expression (every tile computed)", "s + 0.05f * (float)((i - j) % 7)", "j > i", 0,
+         int((j <= i).sum())),
+        ("bucketed relative bias, causal as base mask", "s + 0.05f * (float)((i - j) % 7)", None, fb.FL_MASK_CAUSAL,
+         int((j <= i).sum())),
+        ("dilated window 768: base window + expression", None, "(i - j) % 3 != 0", fb.FL_MASK_WINDOW,
+         int(((j <= i) & ((i - j) % 3 == 0) & (i - j <= 768)).sum())),
+    ]
+    res = []
+    for name, mod, mask, base, pairs in cases:
+        t0 = time.perf_counter()
+        var = None if (mod is None and mask is None) else fb.CustomVariant(mod, mask, d["D"], base_mask=base)
+        compile_s = time.perf_counter() - t0
+        call = (lambda: dw.run_checked(stream)) if var is None else \
+            (lambda: fb.check(var.forward(dw.tq, dw.tk, dw.tv, float(w.scale), dw.tout, dw.tlse, stream, window=768)))
+        for _ in range(warmup):
+            call()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        flops = pairs * d["B"] * d["H"] * 4 * d["D"]
+        res.append(dict(variant=name, ms=ms, tflops=flops / (ms * 1e-3) / 1e12, compile_s=compile_s))
+        print(f"# {name}: {ms:.4f} ms  {res[-1]['tflops']:.1f} TFLOP/s  (compiled in {compile_s:.1f} s)", file=sys.stderr, flush=True)
+    return res
+
+
 def gemm_reference(n=8192, reps=50):
     """TFLOP/s of torch.matmul on random bf16 data of size n^3: what the matrix cores sustain under the
     board's power limit with nothing but a contraction to run (context for roofline.frac, not a target)."""
@@ -362,6 +408,7 @@ def main():
     ap.add_argument("--decode-layout", default="NHD", choices=["NHD", "HND"],
                     help="cache storage order for --decode: [pages, page_size, Hkv, D] or [pages, Hkv, page_size, D]")
     ap.add_argument("--decode-page", type=int, default=16, help="tokens per page for --decode")
+    ap.add_argument("--custom", action="store_true", help="time variants compiled at run time from expressions (ALiBi shapes)")
     ap.add_argument("--decode", action="store_true",
                     help="time fl_attn_decode (64 sequences of 4k-8k cached tokens, 32 / 8 heads, D = 128, 16-token pages)")
     ap.add_argument("--no-gemm-reference", action="store_true",
@@ -391,6 +438,11 @@ def main():
         k, v = kv.split("=")
         fb.check(fb.fl_set_tuning(k, int(v)))
 
+    if args.custom:
+        res = time_custom(args.steps, args.warmup)
+        print(json.dumps({"metric": "attention fwd TFLOP/s of run-time compiled variants", "unit": "TFLOP/s", "n_gpus": 1,
+                          "steps": args.steps, "warmup": args.warmup, "dtype": "bf16", "data": "synthetic", "results": res}), flush=True)
+        return
     if args.decode:
         r = time_decode(args.steps, args.warmup, page_size=args.decode_page, layout=args.decode_layout)
         print(f"# decode: {r['ms_per_step']:.4f} ms  {r['gbs']:.0f} GB/s  {100 * r['gbs'] / PEAK_HBM_GBS:.1f}% of the HBM peak",

@@ -226,15 +226,21 @@ typedef struct fl_custom_variant fl_custom_variant;
  *   mask_expr       C expression, nonzero where the score is replaced by -inf (the mask_mod of
  *                   Sec. 2.2, inverted), of int b, g, h, i, j; e.g. "j > i || (i - j) % 4 != 0".
  *                   NULL: nothing masked.  It is evaluated on every score: no tile is skipped.
+ *   base_mask       FL_MASK_CAUSAL / FL_MASK_WINDOW / FL_MASK_PREFIX bits OR-ed into the mask: these the
+ *                   kernel knows in closed form, so tiles they hide are skipped and tiles they leave
+ *                   fully visible skip the mask arithmetic (when there is no mask_expr).
  *   D               head dim (= Dv), 64 or 128; bf16 inputs.
  * An expression is one C expression (no ; { } # quotes or backslashes).  FL_ERR_DESC with the
  * compiler's first error in fl_last_error_detail() if it does not compile.  Needs no GPU.       */
-fl_status fl_compile_variant(const char* score_mod_expr, const char* mask_expr, int D, fl_custom_variant** handle);
+fl_status fl_compile_variant(const char* score_mod_expr, const char* mask_expr, uint32_t base_mask, int D,
+                             fl_custom_variant** handle);
 
 /* The forward pass of a compiled variant: q, k, v, out, lse, stream as for fl_attn_fwd (grouped
- * heads included); the code object is loaded on the current device at the first call there.     */
+ * heads included); window / prefix_len belong to the base mask (ignored without it).  The code
+ * object is loaded on the current device at the first call there.                              */
 fl_status fl_attn_fwd_custom(fl_custom_variant* variant, const fl_tensor* q, const fl_tensor* k, const fl_tensor* v,
-                             float scale, fl_tensor* out, fl_tensor* lse, void* stream);
+                             float scale, int32_t window, int32_t prefix_len, fl_tensor* out, fl_tensor* lse,
+                             void* stream);
 
 /* Unloads and frees a compiled variant (no launch of it may be in flight). */
 void fl_release_variant(fl_custom_variant* variant);

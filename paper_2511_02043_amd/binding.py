@@ -90,9 +90,9 @@ def lib() -> C.CDLL:
         L.fl_attn_decode_workspace_size.restype = C.c_size_t
         L.fl_attn_decode_workspace_size.argtypes = [TP, TP, C.POINTER(fl_paged_kv)]
         L.fl_compile_variant.restype = C.c_int
-        L.fl_compile_variant.argtypes = [C.c_char_p, C.c_char_p, C.c_int, C.POINTER(C.c_void_p)]
+        L.fl_compile_variant.argtypes = [C.c_char_p, C.c_char_p, C.c_uint32, C.c_int, C.POINTER(C.c_void_p)]
         L.fl_attn_fwd_custom.restype = C.c_int
-        L.fl_attn_fwd_custom.argtypes = [C.c_void_p, TP, TP, TP, C.c_float, TP, TP, C.c_void_p]
+        L.fl_attn_fwd_custom.argtypes = [C.c_void_p, TP, TP, TP, C.c_float, C.c_int32, C.c_int32, TP, TP, C.c_void_p]
         L.fl_release_variant.restype = None
         L.fl_release_variant.argtypes = [C.c_void_p]
         L.fl_variant_supported.restype = C.c_int
@@ -217,19 +217,19 @@ def fl_attn_decode_workspace_size(q: fl_tensor, k_cache: fl_tensor, kv: fl_paged
     return lib().fl_attn_decode_workspace_size(_ref(q), _ref(k_cache), _ref(kv))
 
 
-def fl_compile_variant(score_mod: Optional[str], mask: Optional[str], D: int):
+def fl_compile_variant(score_mod: Optional[str], mask: Optional[str], D: int, base_mask: int = 0):
     """Returns (status, handle); handle is a ctypes void pointer (NULL on failure)."""
     h = C.c_void_p()
     st = lib().fl_compile_variant(None if score_mod is None else score_mod.encode(),
-                                  None if mask is None else mask.encode(), D, C.byref(h))
+                                  None if mask is None else mask.encode(), base_mask, D, C.byref(h))
     return st, h
 
 
 def fl_attn_fwd_custom(handle, q: fl_tensor, k: fl_tensor, v: fl_tensor, scale: float, out: fl_tensor,
-                       lse: Optional[fl_tensor] = None, stream: int = 0) -> int:
+                       lse: Optional[fl_tensor] = None, stream: int = 0, window: int = 0, prefix_len: int = 0) -> int:
     """Raw call; returns the fl_status code."""
-    return lib().fl_attn_fwd_custom(handle, _ref(q), _ref(k), _ref(v), C.c_float(scale), _ref(out), _ref(lse),
-                                    C.c_void_p(stream))
+    return lib().fl_attn_fwd_custom(handle, _ref(q), _ref(k), _ref(v), C.c_float(scale), window, prefix_len, _ref(out),
+                                    _ref(lse), C.c_void_p(stream))
 
 
 def fl_release_variant(handle) -> None:
@@ -239,14 +239,14 @@ def fl_release_variant(handle) -> None:
 class CustomVariant:
     """A variant compiled at run time from a score_mod and / or a mask expression (C syntax)."""
 
-    def __init__(self, score_mod: Optional[str], mask: Optional[str], D: int):
-        st, h = fl_compile_variant(score_mod, mask, D)
+    def __init__(self, score_mod: Optional[str], mask: Optional[str], D: int, base_mask: int = 0):
+        st, h = fl_compile_variant(score_mod, mask, D, base_mask)
         check(st)
         self.handle = h
 
     def forward(self, q: fl_tensor, k: fl_tensor, v: fl_tensor, scale: float, out: fl_tensor,
-                lse: Optional[fl_tensor] = None, stream: int = 0) -> int:
-        return fl_attn_fwd_custom(self.handle, q, k, v, scale, out, lse, stream)
+                lse: Optional[fl_tensor] = None, stream: int = 0, window: int = 0, prefix_len: int = 0) -> int:
+        return fl_attn_fwd_custom(self.handle, q, k, v, scale, out, lse, stream, window, prefix_len)
 
     def release(self) -> None:
         if self.handle is not None and self.handle.value:

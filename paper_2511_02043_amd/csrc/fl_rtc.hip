@@ -24,6 +24,7 @@ namespace {
 
 struct fl_custom_variant {
   int D = 0;
+  unsigned mask = 0;               // mask bits the kernel was instantiated with
   std::vector<char> code;          // the compiled code object
   std::string kernel_name;         // lowered name of the instantiated kernel
   std::mutex mu;
@@ -47,17 +48,23 @@ bool expression_ok(const char* e) {
 
 extern "C" {
 
-fl_status fl_compile_variant(const char* score_mod_expr, const char* mask_expr, int D, fl_custom_variant** handle) {
+fl_status fl_compile_variant(const char* score_mod_expr, const char* mask_expr, uint32_t base_mask, int D,
+                             fl_custom_variant** handle) {
   fl::host::clear_detail();
   if (handle == nullptr) return fl::host::fail(FL_ERR_NULL, "handle is NULL");
   *handle = nullptr;
   if (D != 64 && D != 128) return fl::host::fail(FL_ERR_UNSUPPORTED, "custom variants are built for head dims 64 and 128");
   if (score_mod_expr == nullptr && mask_expr == nullptr) return fl::host::fail(FL_ERR_DESC, "neither a score_mod nor a mask expression");
+  if (base_mask & ~(uint32_t)(FL_MASK_CAUSAL | FL_MASK_WINDOW | FL_MASK_PREFIX))
+    return fl::host::fail(FL_ERR_DESC, "base_mask takes FL_MASK_CAUSAL, FL_MASK_WINDOW and FL_MASK_PREFIX");
+  if ((base_mask & FL_MASK_PREFIX) && (base_mask & (FL_MASK_CAUSAL | FL_MASK_WINDOW)))
+    return fl::host::fail(FL_ERR_DESC, "FL_MASK_PREFIX excludes FL_MASK_CAUSAL and FL_MASK_WINDOW");
+  if (base_mask & FL_MASK_WINDOW) base_mask |= FL_MASK_CAUSAL;
   if ((score_mod_expr && !expression_ok(score_mod_expr)) || (mask_expr && !expression_ok(mask_expr)))
     return fl::host::fail(FL_ERR_DESC, "an expression may not contain ; { } # \" \\ or a line break");
 
   const int mod = score_mod_expr ? fl::kModCustom : fl::kModNone;
-  const unsigned mask = mask_expr ? fl::kMaskCustom : 0u;
+  const unsigned mask = (mask_expr ? fl::kMaskCustom : 0u) | base_mask;
   char inst[256];
   snprintf(inst, sizeof(inst), "fl::fwd_bf16_kernel<fl::Bf16Cfg<%d, %d, %d, 1, %d, 2, %d, %uu, 0, false, 0u>>", D, D, kWaves, kBN, mod, mask);
   std::string src = "#include \"fl_kernel_bf16.hpp\"\n";
@@ -92,6 +99,7 @@ fl_status fl_compile_variant(const char* score_mod_expr, const char* mask_expr, 
   }
   fl_custom_variant* v = new fl_custom_variant;
   v->D = D;
+  v->mask = mask;
   size_t cs = 0;
   hiprtcGetCodeSize(prog, &cs);
   v->code.resize(cs);
@@ -116,12 +124,14 @@ void fl_release_variant(fl_custom_variant* v) {
 }
 
 fl_status fl_attn_fwd_custom(fl_custom_variant* v, const fl_tensor* q, const fl_tensor* k, const fl_tensor* vv, float scale,
-                             fl_tensor* out, fl_tensor* lse, void* stream_v) {
+                             int32_t window, int32_t prefix_len, fl_tensor* out, fl_tensor* lse, void* stream_v) {
   fl::host::clear_detail();
   if (v == nullptr || q == nullptr || k == nullptr || vv == nullptr || out == nullptr)
     return fl::host::fail(FL_ERR_NULL, "handle, q, k, v or out is NULL");
   if (!(scale > 0.f) || scale != scale || scale > 3.0e38f) return fl::host::fail(FL_ERR_DESC, "scale must be finite and > 0");
   if (q->dtype != FL_BF16) return fl::host::fail(FL_ERR_DTYPE, "custom variants take bf16 inputs");
+  if ((v->mask & FL_MASK_WINDOW) && window < 0) return fl::host::fail(FL_ERR_DESC, "window must be >= 0");
+  if ((v->mask & FL_MASK_PREFIX) && prefix_len < 0) return fl::host::fail(FL_ERR_DESC, "prefix_len must be >= 0");
   const int64_t B = q->size[0], G = q->size[1], H = q->size[2], Sq = q->size[3], D = q->size[4];
   const int64_t Hkv = k->size[2], Sk = k->size[3];
   if (D != v->D || vv->size[4] != v->D) return fl::host::fail(FL_ERR_SHAPE, "this variant was compiled for head dim %d", v->D);
@@ -174,12 +184,17 @@ fl_status fl_attn_fwd_custom(fl_custom_variant* v, const fl_tensor* q, const fl_
   p.B = (int)B; p.G = (int)G; p.H = (int)H; p.Hkv = (int)Hkv; p.Sq = (int)Sq; p.Sk = (int)Sk;
   p.D = (int)D; p.Dv = (int)D;
   p.scale = scale;
+  p.window = window;
+  p.prefix = prefix_len;
   p.out_f32 = out->dtype == FL_F32;
   p.n_qtiles = (int)((Sq + kBM - 1) / kBM);
   p.lds_bytes = 4 * kBN * (int)D * 2;              // K ring and V ring of two 64-key tiles each
   const int64_t nbh = B * G * H;
   p.order = nbh % 8 == 0 ? 1 : 0;
-  const int64_t nblocks = nbh * p.n_qtiles;
+  // under a causal / prefix base mask without a window a workgroup takes a long and a short q-tile
+  const bool tri = (v->mask & (FL_MASK_CAUSAL | FL_MASK_PREFIX)) != 0 && (v->mask & FL_MASK_WINDOW) == 0;
+  p.pair = tri && nbh * ((p.n_qtiles + 1) / 2) >= 512;
+  const int64_t nblocks = nbh * (p.pair ? (p.n_qtiles + 1) / 2 : p.n_qtiles);
   if (nblocks > 0x7fffffffLL) return fl::host::fail(FL_ERR_SHAPE, "too many workgroups");
   void* args[] = {&p};
   e = hipModuleLaunchKernel(v->func[dev], (unsigned)nblocks, 1, 1, kWaves * 64, 1, 1, (unsigned)p.lds_bytes, (hipStream_t)stream_v, args, nullptr);

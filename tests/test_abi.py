@@ -208,4 +208,8 @@ def test_custom_variant_compiles_without_a_gpu_and_reports_errors():
     assert st == fb.FL_ERR_DESC and "oops" in fb.fl_last_error_detail() and not h.value
     assert fb.fl_compile_variant("s } {", None, 64)[0] == fb.FL_ERR_DESC
     assert fb.fl_compile_variant(None, None, 64)[0] == fb.FL_ERR_DESC
+    assert fb.fl_compile_variant("s", None, 64, base_mask=fb.FL_MASK_DOC)[0] == fb.FL_ERR_DESC
+    st, h2 = fb.fl_compile_variant("s * 0.5f", None, 128, base_mask=fb.FL_MASK_WINDOW)
+    assert st == fb.FL_OK
+    fb.fl_release_variant(h2)
     assert fb.fl_compile_variant("s", None, 32)[0] == fb.FL_ERR_UNSUPPORTED

@@ -61,6 +61,29 @@ def test_custom_variant_equals_the_built_in_kernel_on_a_named_variant():
     assert float(np.max(np.abs(dw.out.cpu().numpy() - ref))) <= 1e-2
 
 
+def test_base_mask_with_expressions():
+    """Structural masks the kernel knows (tile skipping) combined with an expression mask and score_mod."""
+    import torch
+    w = inputs.causal_bf16(B=1, H=8, Hkv=2, S=700, D=64, causal=False, salt=5)
+    dw = runner.upload(w, out_dtype="f32")
+    # causal base, score_mod only: full tiles skip the mask arithmetic
+    var = fb.CustomVariant("s + 0.05f * (float)((i - j) % 7)", None, 64, base_mask=fb.FL_MASK_CAUSAL)
+    fb.check(var.forward(dw.tq, dw.tk, dw.tv, float(w.scale), dw.tout, dw.tlse))
+    torch.cuda.synchronize()
+    ref, ref_lse = ao.attention_custom(w.q, w.k, w.v, scale=w.scale, score_mod=lambda s, b, g, h, i, j: s + np.float32(0.05) * ((i - j) % 7),
+                                       mask=lambda b, g, h, i, j: j > i)
+    assert float(np.max(np.abs(dw.out.cpu().numpy() - ref))) <= 1e-2
+    assert float(np.max(np.abs(dw.lse.cpu().numpy()[..., 0] - ref_lse))) <= 1e-3
+    # window base + dilation expression
+    var2 = fb.CustomVariant(None, "(i - j) % 3 != 0", 64, base_mask=fb.FL_MASK_WINDOW)
+    fb.check(var2.forward(dw.tq, dw.tk, dw.tv, float(w.scale), dw.tout, dw.tlse, window=200))
+    torch.cuda.synchronize()
+    ref, ref_lse = ao.attention_custom(w.q, w.k, w.v, scale=w.scale,
+                                       mask=lambda b, g, h, i, j: (j > i) | (i - j > 200) | ((i - j) % 3 != 0))
+    assert float(np.max(np.abs(dw.out.cpu().numpy() - ref))) <= 1e-2
+    assert float(np.max(np.abs(dw.lse.cpu().numpy()[..., 0] - ref_lse))) <= 1e-3
+
+
 def test_compile_errors_are_reported():
     with pytest.raises(fb.FlError) as e:
         fb.CustomVariant("s + no_such_name", None, 64)
