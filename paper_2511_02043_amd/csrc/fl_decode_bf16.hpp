@@ -6,7 +6,7 @@
 // HBM: every wave streams its own key/value tiles into a private LDS ring with direct
 // global->LDS loads, several tiles ahead, and never meets another wave inside the loop.
 //
-//   * a workgroup owns one (sequence, kv head, split of the key range); its four waves take the
+//   * a workgroup owns one (sequence, kv head, split of the key range); its waves take the
 //     tiles of that range round-robin;
 //   * the query heads that share the kv head are the 32 columns of the MFMA tile (lane = head),
 //     so a K / V tile is read once for the whole group: S^T = K Q^T and O^T += V^T P^T exactly
@@ -44,10 +44,14 @@ struct DecodeParams {
 
 template <int D_, int MOD_>
 struct DecodeCfg : BwdCfg<D_, MOD_, 0, 32, 1> {
-  static constexpr int NSTG = D_ == 128 ? 2 : 4;   // ring stages per wave (16 / 8 KiB each)
+  // D = 128: four waves (one per SIMD) with 16 KiB stages; D = 64: eight waves (two per SIMD) with 8 KiB
+  // stages -- a tile carries half the bytes there, and a second wave on the SIMD hides the first one's
+  // per-tile chain of waits (load, LDS read, matrix core, exponentials)
+  static constexpr int NWV = D_ == 128 ? 4 : 8;    // waves per workgroup
+  static constexpr int NSTG = 2;                   // ring stages per wave
   static constexpr int STAGE = 2 * BwdCfg<D_, MOD_, 0, 32, 1>::TILE;                 // K tile, V tile
   static constexpr int WAVE_LDS = NSTG * STAGE;
-  static constexpr int LDS = 4 * WAVE_LDS;
+  static constexpr int LDS = NWV * WAVE_LDS;
   static constexpr int IPT = 2 * BwdCfg<D_, MOD_, 0, 32, 1>::TILE_INSTR;             // load instructions per tile
   static_assert((NSTG - 1) * IPT < 64, "vmcnt is a 6-bit counter");
 };
@@ -58,7 +62,7 @@ __device__ __forceinline__ void wait_vm() {          // at most N vector-memory 
 }
 
 template <class C>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__global__ void __launch_bounds__(C::NWV * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 decode_kernel(const DecodeParams p) {
   constexpr int D = C::D, KK = C::KK, DB = C::DB, ROW = C::ROW, BN = 32;
   typedef BwdWave<C> W;
@@ -144,16 +148,16 @@ decode_kernel(const DecodeParams p) {
     }
   };
 
-  // this wave's tiles: t_begin + wave, + 4, ...; NSTG - 1 of them in flight ahead of the one in use
+  // this wave's tiles: t_begin + wave, + NWV, ...; NSTG - 1 of them in flight ahead of the one in use
   int t_issue = t_begin + wave;
 #pragma unroll
   for (int s = 0; s < C::NSTG - 1; ++s) {
     if (t_issue < t_end) load_tile(t_issue, s, lookup(t_issue));
-    t_issue += 4;
+    t_issue += C::NWV;
   }
   Pages next_pages = lookup(t_issue < t_end ? t_issue : t_begin);            // of the next tile to request
   int stage = 0;
-  for (int t = t_begin + wave; t < t_end; t += 4) {
+  for (int t = t_begin + wave; t < t_end; t += C::NWV) {
     const int stage_ld = stage == 0 ? C::NSTG - 1 : stage - 1;      // the stage the previous tile used
     if (t_issue < t_end) {
       load_tile(t_issue, stage_ld, next_pages);
@@ -161,7 +165,7 @@ decode_kernel(const DecodeParams p) {
     } else {
       wait_vm<0>();
     }
-    t_issue += 4;
+    t_issue += C::NWV;
     if (t_issue < t_end) next_pages = lookup(t_issue);
     const uint32_t base = (uint32_t)(wave * C::WAVE_LDS + stage * C::STAGE);
     uint32_t ra_b[KK], ta_b[DB][2];
@@ -198,9 +202,13 @@ decode_kernel(const DecodeParams p) {
       mx = fmaxf(mx, a);
     }
     mx = half_swap_max(mx);
-    const float m_new = fmaxf(m_run, mx);
+    // the running max only advances when the tile's max exceeds it by more than 2^8 (P stays
+    // bounded by 2^8; l and the final division use the same reference, so nothing changes in real
+    // arithmetic): the O rescale becomes a rare, wave-uniform branch
+    const float m_new = (mx - m_run > kLazyMaxLog2) ? mx : m_run;   // false for NaN (-inf - -inf)
     const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-    const float alpha = fast_exp2(m_run - m_safe);               // exp2(-inf) = 0 on the first tile
+    const bool moved = m_new != m_run;
+    const float alpha = moved ? fast_exp2(m_run - m_safe) : 1.f;  // exp2(-inf) = 0 on the first tile
     m_run = m_new;
     float psum = 0.f;
     uint32_t pw[8];
@@ -211,10 +219,12 @@ decode_kernel(const DecodeParams p) {
       pw[r2] = pack_bf16(p0, p1);
     }
     l_run = fmaf(l_run, alpha, psum);
+    if (__builtin_amdgcn_ballot_w64(moved) != 0) {
 #pragma unroll
-    for (int d = 0; d < DB; ++d)
+      for (int d = 0; d < DB; ++d)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[d][r] *= alpha;
+        for (int r = 0; r < 16; ++r) oacc[d][r] *= alpha;
+    }
     w.template tr_stream_g<TrOne<C::TILE, DB, ROW>, 2 * DB, 2>(ta_b, [&](auto fc, bf16x8 a) __attribute__((always_inline)) {
       constexpr int f = decltype(fc)::value, d = f % DB, ks = f / DB;
       const bf16x8 bop = __builtin_bit_cast(
@@ -224,7 +234,7 @@ decode_kernel(const DecodeParams p) {
     stage = stage + 1 == C::NSTG ? 0 : stage + 1;
   }
 
-  // ---- merge the four waves (Sec. 3.3 / 3.4 rescale rule): everyone parks (m, l, O) in its own
+  // ---- merge the waves (Sec. 3.3 / 3.4 rescale rule): everyone parks (m, l, O) in its own
   // ring region, wave 0 folds them and writes the split's partial result
   const float l_wave = half_swap_sum(l_run);
   float4* park = (float4*)(lds_raw + wave * C::WAVE_LDS) + lane;       // [quad][lane] float4, then (m, l)
@@ -240,7 +250,7 @@ decode_kernel(const DecodeParams p) {
   if (wave == 0) {
     float m_all = m_run;
 #pragma unroll
-    for (int u = 1; u < 4; ++u) {
+    for (int u = 1; u < C::NWV; ++u) {
       const float4* other = (const float4*)(lds_raw + u * C::WAVE_LDS) + lane;
       m_all = fmaxf(m_all, other[DB * 4 * 64].x);
     }
@@ -250,7 +260,7 @@ decode_kernel(const DecodeParams p) {
 #pragma unroll
     for (int d = 0; d < DB; ++d) o[d] = W::zero16();
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < C::NWV; ++u) {
       const float4* other = (const float4*)(lds_raw + u * C::WAVE_LDS) + lane;
       const float4 ml = other[DB * 4 * 64];
       const float wgt = fast_exp2(ml.x - m_safe);                 // 0 for a wave that saw no key

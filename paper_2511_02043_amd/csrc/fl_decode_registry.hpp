@@ -17,7 +17,7 @@ hipError_t launch_decode(const DecodeParams& p, int nblocks, hipStream_t stream)
   hipError_t e = raise_lds_limit(decode_kernel<C>);
   if (e != hipSuccess) return e;
   static_assert(C::LDS <= kMaxLdsBytes, "LDS of the decode kernel");
-  hipLaunchKernelGGL(decode_kernel<C>, dim3(nblocks), dim3(256), C::LDS, stream, p);
+  hipLaunchKernelGGL(decode_kernel<C>, dim3(nblocks), dim3(C::NWV * 64), C::LDS, stream, p);
   return hipGetLastError();
 }
 template <int D>
