@@ -7,6 +7,9 @@ namespace fl {
 constexpr uint32_t CW = kMaskCausal | kMaskWindow;
 static const KernelEntry kEntries[] = {
     E(64, kModAlibi, 0),   E(64, kModAlibi, kMaskCausal),   E(64, kModSoftcap, 0), E(64, kModSoftcap, kMaskCausal),
+    // sliding window: short key loops, most tiles partly masked; 32-key tiles at four waves per SIMD (four
+    // resident workgroups per CU) measured 10 % faster than the common shape, which stays selectable
+    bf16_entry<64, 64, 4, 1, 32, 4, kModNone, CW, 0, false, 0>(),
     E(64, kModNone, CW),   E(64, kModNone, CW | kMaskDoc),  E(64, kModNone, kMaskDoc),
     E(64, kModNone, kMaskCausal | kMaskDoc), E(64, kModNone, kMaskPrefix), E(64, kModNone, kMaskPrefix | kMaskDoc),
     E(128, kModAlibi, 0),  E(128, kModSoftcap, 0), E(128, kModNone, CW), E(128, kModNone, CW | kMaskDoc),
