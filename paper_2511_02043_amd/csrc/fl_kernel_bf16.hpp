@@ -795,9 +795,26 @@ fwd_bf16_kernel(const FwdParams p) {
   };
   auto next_tile = [&](int t) __attribute__((always_inline)) -> int {             // uniform over the workgroup
     if constexpr ((MASK & kMaskDoc) != 0) {
-      while (t < t_hi && classify_block(MASK, i0, i_last, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg,
-                                        tile_keys(t)) == kSkip)
+      // the usual case first: tile t itself has something visible (one uniform check)
+      if (t < t_hi && classify_block(MASK, i0, i_last, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg,
+                                     tile_keys(t)) == kSkip) {
+        // a run of hidden tiles (the other documents of a long sequence): 64 tiles per round, one per lane
         ++t;
+        while (t < t_hi) {
+          const int tt = t + w.lane;
+          bool keep = false;
+          if (tt < t_hi)
+            keep = classify_block(MASK, i0, i_last, tt * BN, tt * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg,
+                                  tile_keys(tt)) != kSkip;
+          const unsigned long long found = __builtin_amdgcn_ballot_w64(keep);
+          if (found != 0) {
+            t += __builtin_ctzll(found);
+            break;
+          }
+          t += 64;
+        }
+        t = __builtin_amdgcn_readfirstlane(t < t_hi ? t : t_hi);
+      }
     }
     return t;                                      // positional masks are already in [t_lo, t_hi)
   };
