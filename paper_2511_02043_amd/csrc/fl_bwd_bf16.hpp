@@ -454,19 +454,32 @@ bwd_dq_kernel(const BwdParams p) {
         qs_wg.y = max(qs_wg.y, t.y);
       }
   }
+  // does key tile t hold anything visible to the workgroup's rows?  (document-id summaries)
+  auto tile_visible = [&](int t) __attribute__((always_inline)) -> bool {
+    const int2* ksum = p.kv_sum + (int64_t)b * nks;
+    int2 ks = ksum[min(t * NB, nks - 1)];
+    for (int u = 1; u < NB; ++u)
+      if (t * NB + u < nks) {
+        const int2 x = ksum[t * NB + u];
+        ks.x = min(ks.x, x.x);
+        ks.y = max(ks.y, x.y);
+      }
+    return classify_block(MASK, i0, i_last, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg, ks) != kSkip;
+  };
   auto next_tile = [&](int t) __attribute__((always_inline)) -> int {
     if constexpr ((MASK & kMaskDoc) != 0) {
-      const int2* ksum = p.kv_sum + (int64_t)b * nks;
-      while (t < t_hi) {
-        int2 ks = ksum[min(t * NB, nks - 1)];
-        for (int u = 1; u < NB; ++u)
-          if (t * NB + u < nks) {
-            const int2 x = ksum[t * NB + u];
-            ks.x = min(ks.x, x.x);
-            ks.y = max(ks.y, x.y);
-          }
-        if (classify_block(MASK, i0, i_last, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg, ks) != kSkip) break;
+      if (t < t_hi && !tile_visible(t)) {            // a run of hidden tiles: 64 per round, one per lane
         ++t;
+        while (t < t_hi) {
+          const int tt = t + lane;
+          const unsigned long long found = __builtin_amdgcn_ballot_w64(tt < t_hi && tile_visible(tt));
+          if (found != 0) {
+            t += __builtin_ctzll(found);
+            break;
+          }
+          t += 64;
+        }
+        t = __builtin_amdgcn_readfirstlane(t < t_hi ? t : t_hi);
       }
     }
     return t;
@@ -663,21 +676,34 @@ bwd_dkdv_kernel(const BwdParams p) {
         ks_wg.y = max(ks_wg.y, x.y);
       }
   }
+  // does the q-tile of item `it` hold a row that sees any of the workgroup's keys?  (document-id summaries)
+  auto item_visible = [&](int it) __attribute__((always_inline)) -> bool {
+    const int2* qsum = p.q_sum + (int64_t)b * nqs;
+    const int t = t_lo + it % nt;
+    int2 qs = qsum[min(t * NB, nqs - 1)];
+    for (int u = 1; u < NB; ++u)
+      if (t * NB + u < nqs) {
+        const int2 x = qsum[t * NB + u];
+        qs.x = min(qs.x, x.x);
+        qs.y = max(qs.y, x.y);
+      }
+    const int q_last = (t * BN + BN < p.Sq ? t * BN + BN : p.Sq) - 1;
+    return classify_block(MASK, t * BN, q_last, j0, j0 + C::BM - 1, p.Sk, p.window, p.prefix, qs, ks_wg) != kSkip;
+  };
   auto next_item = [&](int it) __attribute__((always_inline)) -> int {
     if constexpr ((MASK & kMaskDoc) != 0) {
-      const int2* qsum = p.q_sum + (int64_t)b * nqs;
-      while (it < n_items) {
-        const int t = t_lo + it % nt;
-        int2 qs = qsum[min(t * NB, nqs - 1)];
-        for (int u = 1; u < NB; ++u)
-          if (t * NB + u < nqs) {
-            const int2 x = qsum[t * NB + u];
-            qs.x = min(qs.x, x.x);
-            qs.y = max(qs.y, x.y);
-          }
-        const int q_last = (t * BN + BN < p.Sq ? t * BN + BN : p.Sq) - 1;
-        if (classify_block(MASK, t * BN, q_last, j0, j0 + C::BM - 1, p.Sk, p.window, p.prefix, qs, ks_wg) != kSkip) break;
+      if (it < n_items && !item_visible(it)) {       // a run of hidden q-tiles: 64 per round, one per lane
         ++it;
+        while (it < n_items) {
+          const int ii = it + lane;
+          const unsigned long long found = __builtin_amdgcn_ballot_w64(ii < n_items && item_visible(ii));
+          if (found != 0) {
+            it += __builtin_ctzll(found);
+            break;
+          }
+          it += 64;
+        }
+        it = __builtin_amdgcn_readfirstlane(it < n_items ? it : n_items);
       }
     }
     return it;
@@ -948,21 +974,34 @@ bwd_dkdv_ws_kernel(const BwdParams p) {
         ks_wg.y = max(ks_wg.y, x.y);
       }
   }
+  // does the q-tile of item `it` hold a row that sees any of the workgroup's keys?  (document-id summaries)
+  auto item_visible = [&](int it) __attribute__((always_inline)) -> bool {
+    const int2* qsum = p.q_sum + (int64_t)b * nqs;
+    const int t = t_lo + it % nt;
+    int2 qs = qsum[min(t * NB, nqs - 1)];
+    for (int u = 1; u < NB; ++u)
+      if (t * NB + u < nqs) {
+        const int2 x = qsum[t * NB + u];
+        qs.x = min(qs.x, x.x);
+        qs.y = max(qs.y, x.y);
+      }
+    const int q_last = (t * BN + BN < p.Sq ? t * BN + BN : p.Sq) - 1;
+    return classify_block(MASK, t * BN, q_last, j0, j0 + C::BM - 1, p.Sk, p.window, p.prefix, qs, ks_wg) != kSkip;
+  };
   auto next_item = [&](int it) __attribute__((always_inline)) -> int {
     if constexpr ((MASK & kMaskDoc) != 0) {
-      const int2* qsum = p.q_sum + (int64_t)b * nqs;
-      while (it < n_items) {
-        const int t = t_lo + it % nt;
-        int2 qs = qsum[min(t * NB, nqs - 1)];
-        for (int u = 1; u < NB; ++u)
-          if (t * NB + u < nqs) {
-            const int2 x = qsum[t * NB + u];
-            qs.x = min(qs.x, x.x);
-            qs.y = max(qs.y, x.y);
-          }
-        const int q_last = (t * BN + BN < p.Sq ? t * BN + BN : p.Sq) - 1;
-        if (classify_block(MASK, t * BN, q_last, j0, j0 + C::BM - 1, p.Sk, p.window, p.prefix, qs, ks_wg) != kSkip) break;
+      if (it < n_items && !item_visible(it)) {       // a run of hidden q-tiles: 64 per round, one per lane
         ++it;
+        while (it < n_items) {
+          const int ii = it + lane;
+          const unsigned long long found = __builtin_amdgcn_ballot_w64(ii < n_items && item_visible(ii));
+          if (found != 0) {
+            it += __builtin_ctzll(found);
+            break;
+          }
+          it += 64;
+        }
+        it = __builtin_amdgcn_readfirstlane(it < n_items ? it : n_items);
       }
     }
     return it;
