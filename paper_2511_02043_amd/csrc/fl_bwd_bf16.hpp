@@ -11,15 +11,19 @@
 //     dZ = dS * (1 - tanh^2)            soft-cap only
 //     dV = P^T dO,   dK = scale * dZ^T Q,   dQ = scale * dZ K
 //
-// Two kernels, both without atomics (bitwise reproducible results):
+// Two passes, both without atomics (bitwise reproducible results):
 //   * bwd_dq_kernel: a workgroup owns 128 query rows (one per lane, as in the forward kernel)
 //     and walks the key tiles; per tile S^T = K Q^T and dP^T = V dO^T land in the 32x32
 //     accumulator layout with the query in the lane, dS^T rounded to bf16 is the B operand of
 //     dQ^T += K^T dS^T, whose A operand is the same K tile read through the transposing LDS load.
-//   * bwd_dkdv_kernel: a workgroup owns 128 keys (one per lane, K and V fragments in registers)
-//     and walks the query tiles of every query head of its group; S = Q K^T and dP = dO V^T have
-//     the key in the lane and the query row in the register index, so P and dS are the B
-//     operands of dV^T += dO^T P and dK^T += Q^T dS with dO^T / Q^T read transposed from LDS.
+//   * dK / dV: a workgroup owns 128 keys (one per lane) and walks the query tiles of the query
+//     heads of its group; S = Q K^T and dP = dO V^T have the key in the lane and the query row in
+//     the register index, so P and dS are the B operands of dV^T += dO^T P and dK^T += Q^T dS with
+//     dO^T / Q^T read transposed from LDS.  bwd_dkdv_kernel (D = 64) does all of it in every wave,
+//     software-pipelined over 32-row blocks; bwd_dkdv_ws_kernel (D = 128, where one wave's
+//     accumulators fill a SIMD's registers) splits it over two specialised waves per SIMD.
+//     With grouped heads and few workgroups, the group's heads are cut over several workgroups
+//     whose fp32 partials bwd_reduce_kv_kernel adds in a fixed order.
 // A small pre-pass writes delta and the log2-scaled lse (+inf for rows without a visible key, so
 // that their probabilities come out as exactly 0).
 //
