@@ -782,7 +782,7 @@ fwd_bf16_kernel(const FwdParams p) {
   }
   const int2* ksum = (MASK & kMaskDoc) ? p.kv_sum + (int64_t)b * nks : nullptr;
 
-  auto tile_keys = [&](int t) __attribute__((always_inline)) -> int2 {            // document-id range of the keys of tile t
+  auto tile_keys_lane = [&](int t) __attribute__((always_inline)) -> int2 {       // document-id range of the keys of tile t (t per lane)
     int2 ks = ksum[min(t * NB, nks - 1)];
 #pragma unroll
     for (int u = 1; u < NB; ++u)
@@ -791,6 +791,26 @@ fwd_bf16_kernel(const FwdParams p) {
         ks.x = min(ks.x, x.x);
         ks.y = max(ks.y, x.y);
       }
+    return ks;
+  };
+  // The same for a uniform t, once per step of the loop: read through the scalar cache.  A vector
+  // load there would have to wait for the tile loads in flight (vector memory operations complete
+  // in order); the summaries were written by an earlier kernel, so the scalar cache sees them.
+  // The lane-read built-in returns a signed int: both address halves go through uint32_t, or a low
+  // half with bit 31 set would be sign-extended over the high half.
+  auto tile_keys = [&](int t) __attribute__((always_inline)) -> int2 {
+    int2 ks = make_int2(0, 0);
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+      const uint64_t a = (uint64_t)(ksum + min(t * NB + u, nks - 1));
+      const uint64_t au = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(a >> 32)) << 32) |
+                          (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)a);
+      unsigned long long r;
+      // (the idle cycles keep the load clear of the vector instruction that has just written its address registers)
+      asm volatile("s_nop 4\n\ts_load_dwordx2 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(r) : "s"(au) : "memory");
+      const int x = (int)(uint32_t)r, y = (int)(uint32_t)(r >> 32);
+      ks = u == 0 ? make_int2(x, y) : make_int2(min(ks.x, x), max(ks.y, y));
+    }
     return ks;
   };
   auto next_tile = [&](int t) __attribute__((always_inline)) -> int {             // uniform over the workgroup
@@ -805,7 +825,7 @@ fwd_bf16_kernel(const FwdParams p) {
           bool keep = false;
           if (tt < t_hi)
             keep = classify_block(MASK, i0, i_last, tt * BN, tt * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg,
-                                  tile_keys(tt)) != kSkip;
+                                  tile_keys_lane(tt)) != kSkip;
           const unsigned long long found = __builtin_amdgcn_ballot_w64(keep);
           if (found != 0) {
             t += __builtin_ctzll(found);
