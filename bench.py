@@ -113,7 +113,18 @@ def time_config(name, steps, warmup, out_dtype="same", rotate=1):
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / steps
     ev_ms = e0.elapsed_time(e1) / steps
-    return dict(config=name, flops=flops, bytes=byt, ms_per_step=wall_ms, kernel_ms=ev_ms,
+    # spread of single launches (the paper's protocol, Sec. 4.1: 20 timed launches), each between
+    # its own pair of events; the clock cannot be pinned here, so min and std-dev go with the median
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+    for n, (a, b) in enumerate(evs):
+        a.record()
+        dws[n % rotate].run_checked(stream)
+        b.record()
+    torch.cuda.synchronize()
+    one = np.array([a.elapsed_time(b) * 1e3 for a, b in evs])
+    launch_us = dict(n=len(one), median=float(np.median(one)), mean=float(one.mean()), min=float(one.min()),
+                     std=float(one.std()))
+    return dict(config=name, flops=flops, bytes=byt, ms_per_step=wall_ms, kernel_ms=ev_ms, launch_us=launch_us,
                 tflops=flops / (wall_ms * 1e-3) / 1e12, kernel_tflops=flops / (ev_ms * 1e-3) / 1e12,
                 gbs=byt / (ev_ms * 1e-3) / 1e9, dims=w.dims), w
 
@@ -512,7 +523,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.config, **r["dims"], "variant": w.name, "out_dtype": "bf16",
                    "flops_per_step": r["flops"], "pct_of_bf16_mfma_peak": 100 * r["tflops"] / PEAK_BF16_TFLOPS,
-                   "hbm_gb_per_s_algorithmic": r["gbs"]},
+                   "hbm_gb_per_s_algorithmic": r["gbs"], "single_launch_us": r["launch_us"]},
         "roofline": {"bound": "mfma", "achieved": r["kernel_tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": r["kernel_tflops"] / PEAK_BF16_TFLOPS, "traffic": traffic},
     }
