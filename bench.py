@@ -8,7 +8,7 @@ K/V tiles through LDS, score tile, variant transform, online softmax, P.V, epilo
 batch of synthetic inputs that are already resident in HBM.  The default workload is the
 configuration the metric is quoted on: causal bf16, B=4 H=16 S=8192 D=128.  One JSON line is
 printed on stdout.  `--config NAME` times another benchmark configuration, `--all` times every
-configuration and writes gpurun_out/bench_all.json as well.
+configuration and writes bench_all.json into --out-dir as well.
 """
 import argparse
 import json
@@ -19,6 +19,7 @@ import time
 import numpy as np
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
+OUT_DIR = os.path.join(ROOT, "bench_out")          # --out-dir: where --all / --grid / --backward leave their tables
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
@@ -186,10 +187,10 @@ def run_grid_backward(steps, warmup):
                 print(f"# bwd {variant:15s} {'gqa' if gqa else 'mha'} S={S:5d} B={w.dims['B']:2d}: {ms:.4f} ms  "
                       f"{rows[-1]['tflops']:.1f} TFLOP/s", file=sys.stderr, flush=True)
                 del db
-    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-    with open(os.path.join(ROOT, "gpurun_out", "bench_grid_bwd.json"), "w") as f:
+    os.makedirs(OUT_DIR, exist_ok=True)
+    with open(os.path.join(OUT_DIR, "bench_grid_bwd.json"), "w") as f:
         json.dump(rows, f, indent=1)
-    print(json.dumps({"grid_cells": len(rows), "file": "gpurun_out/bench_grid_bwd.json"}), flush=True)
+    print(json.dumps({"grid_cells": len(rows), "file": os.path.join(OUT_DIR, "bench_grid_bwd.json")}), flush=True)
 
 
 def time_decode(steps, warmup, B=64, H=32, Hkv=8, D=128, ctx=8192, page_size=16, layout="NHD"):
@@ -359,10 +360,10 @@ def run_grid(steps, warmup):
         print(f"# {variant:15s} {heads} S={S:5d} B={w.dims['B']:2d}: {ms:.4f} ms  "
               f"{rows[-1]['tflops']:.1f} TFLOP/s  {rows[-1]['gbs']:.0f} GB/s", file=sys.stderr, flush=True)
         del dw
-    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-    with open(os.path.join(ROOT, "gpurun_out", "bench_grid.json"), "w") as f:
+    os.makedirs(OUT_DIR, exist_ok=True)
+    with open(os.path.join(OUT_DIR, "bench_grid.json"), "w") as f:
         json.dump(rows, f, indent=1)
-    print(json.dumps({"grid_cells": len(rows), "file": "gpurun_out/bench_grid.json"}))
+    print(json.dumps({"grid_cells": len(rows), "file": os.path.join(OUT_DIR, "bench_grid.json")}))
 
 
 def cpu_baseline(w, budget_s=15.0):
@@ -409,13 +410,14 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", default="c2_d128", choices=CONFIGS)
-    ap.add_argument("--all", action="store_true", help="time every configuration (results in gpurun_out/bench_all.json)")
+    ap.add_argument("--out-dir", default=None, help="folder for the JSON tables of --all / --grid / --backward (default: bench_out/)")
+    ap.add_argument("--all", action="store_true", help="time every configuration (results in bench_all.json under --out-dir)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--grid", action="store_true",
                     help="time the paper's benchmark grid (7 variants x MHA/GQA x S = 512..16k, 16k tokens, D = 64); "
-                         "table on stderr, gpurun_out/bench_grid.json")
+                         "table on stderr, bench_grid.json under --out-dir")
     ap.add_argument("--backward", action="store_true",
-                    help="time fl_attn_bwd on the configurations it covers (table on stderr, gpurun_out/bench_bwd.json)")
+                    help="time fl_attn_bwd on the configurations it covers (table on stderr, bench_bwd.json under --out-dir)")
     ap.add_argument("--decode-layout", default="NHD", choices=["NHD", "HND"],
                     help="cache storage order for --decode: [pages, page_size, Hkv, D] or [pages, Hkv, page_size, D]")
     ap.add_argument("--decode-page", type=int, default=16, help="tokens per page for --decode")
@@ -430,6 +432,9 @@ def main():
                     help="only run a plain device-to-device copy of MIB MiB a few times (scale factor of the "
                          "FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
     args = ap.parse_args()
+    if args.out_dir:
+        global OUT_DIR
+        OUT_DIR = os.path.abspath(args.out_dir)
     if args.gpus != 1:
         raise SystemExit("this build runs on one GPU only: no sharding or collectives are part of it (use --gpus 1)")
     import torch
@@ -480,8 +485,8 @@ def main():
             res.append(r)
             print(f"# bwd {name}: {r['ms_per_step']:.4f} ms  {r['tflops']:.1f} TFLOP/s  "
                   f"{100 * r['tflops'] / PEAK_BF16_TFLOPS:.1f}% of bf16 peak", file=sys.stderr, flush=True)
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "bench_bwd.json"), "w") as f:
+        os.makedirs(OUT_DIR, exist_ok=True)
+        with open(os.path.join(OUT_DIR, "bench_bwd.json"), "w") as f:
             json.dump(res, f, indent=1)
         print(json.dumps({"metric": "attention bwd TFLOP/s (5 contractions on unmasked pairs)", "unit": "TFLOP/s",
                           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "dtype": "bf16",
@@ -507,8 +512,8 @@ def main():
     r, w = time_config(args.config, args.steps, args.warmup)
     results.append(r)
     if args.all:
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "bench_all.json"), "w") as f:
+        os.makedirs(OUT_DIR, exist_ok=True)
+        with open(os.path.join(OUT_DIR, "bench_all.json"), "w") as f:
             json.dump(results, f, indent=1)
 
     traffic = None
