@@ -80,3 +80,12 @@ def test_long_document_causal_forward_backward(D, H, Hkv):
             rel = float(np.sqrt(np.sum(diff * diff)) / max(np.sqrt(np.sum(r * r)), 1e-3 * np.sqrt(r.size)))
             print(f"D={D} document {d} {name}: rel_l2={rel:.3e}", flush=True)
             assert rel <= 1e-2, (d, name, rel)
+
+
+@pytest.mark.parametrize("D", [128, 64])
+def test_long_decode(D):
+    """One query against 131072 cached tokens (8192 pages of 16, shuffled; the key axis is cut into the
+    maximum number of splits), next to a shorter and a tiny sequence in the same call."""
+    from tests.test_gpu_decode import compare
+    w = inputs.decode_bf16(H=8, Hkv=2, D=D, page_size=16, seq_lens=[S_LONG, 100001, 5])
+    compare(w, f"decode_long_d{D}")
