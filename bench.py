@@ -422,6 +422,8 @@ def main():
                     help="cache storage order for --decode: [pages, page_size, Hkv, D] or [pages, Hkv, page_size, D]")
     ap.add_argument("--decode-page", type=int, default=16, help="tokens per page for --decode")
     ap.add_argument("--decode-dim", type=int, default=128, choices=[64, 128], help="head dim for --decode")
+    ap.add_argument("--decode-batch", type=int, default=64, help="sequences for --decode")
+    ap.add_argument("--decode-ctx", type=int, default=8192, help="longest cached sequence for --decode (lengths are uniform on [ctx / 2, ctx])")
     ap.add_argument("--custom", action="store_true", help="time variants compiled at run time from expressions (ALiBi shapes)")
     ap.add_argument("--decode", action="store_true",
                     help="time fl_attn_decode (64 sequences of 4k-8k cached tokens, 32 / 8 heads, D = 128, 16-token pages)")
@@ -461,13 +463,15 @@ def main():
                           "steps": args.steps, "warmup": args.warmup, "dtype": "bf16", "data": "synthetic", "results": res}), flush=True)
         return
     if args.decode:
-        r = time_decode(args.steps, args.warmup, D=args.decode_dim, page_size=args.decode_page, layout=args.decode_layout)
+        r = time_decode(args.steps, args.warmup, B=args.decode_batch, ctx=args.decode_ctx, D=args.decode_dim, page_size=args.decode_page,
+                        layout=args.decode_layout)
         print(f"# decode: {r['ms_per_step']:.4f} ms  {r['gbs']:.0f} GB/s  {100 * r['gbs'] / PEAK_HBM_GBS:.1f}% of the HBM peak",
               file=sys.stderr, flush=True)
         print(json.dumps({"metric": "decode-step attention over a paged KV cache, GB/s of cache read", "value": r["gbs"],
                           "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
                           "ms_per_step": r["ms_per_step"], "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
-                          "config": {"workload": f"decode_b64_h32_kv8_d{args.decode_dim}_ctx4k-8k_page{args.decode_page}", **r["dims"], "cached_tokens": r["tokens"]},
+                          "config": {"workload": f"decode_b{args.decode_batch}_h32_kv8_d{args.decode_dim}_ctx{args.decode_ctx // 2}-{args.decode_ctx}_page{args.decode_page}",
+                                     **r["dims"], "cached_tokens": r["tokens"]},
                           "roofline": {"bound": "hbm", "achieved": r["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                        "frac": r["gbs"] / PEAK_HBM_GBS, "traffic": None}}), flush=True)
         return

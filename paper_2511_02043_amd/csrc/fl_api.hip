@@ -29,6 +29,7 @@ using fl::host::make_view;
 
 struct Tuning {
   int bm = 0, bn = 0, rb = 0, nw = 0, wpe = 0, order = -1, pair = -1;
+  int decode_splits = 0;           // 0: chosen by decode_splits() from the shapes
 } g_tuning;
 
 struct Registry {
@@ -201,16 +202,27 @@ const fl::DecodeEntry* find_decode_entry(int D, int mod) {
   return nullptr;
 }
 
-// Splits of a sequence's key range: several workgroups per CU over the launch (one is resident at a time,
-// and sequences differ in length), at least 8 tiles of 32 keys per split.  A function of the shapes and the host-side length bound only.
-int decode_splits(int64_t B, int64_t Hkv, int64_t max_seq_len) {
+// Splits of a sequence's key range, a function of the shapes and the host-side length bound only.
+// Measured on (sequences x kv heads) = 8 ... 2048 units and 1k ... 128k cached tokens: few units want
+// about 512 workgroups in all and tolerate splits as short as 16 tiles of 32 keys; with hundreds of
+// units three or four splits (by head dim) of at least 32 tiles even out the different sequence lengths; more than
+// 32 splits never paid (every workgroup pays its start-up: length, first page lookups, first tiles).
+int decode_splits(int64_t B, int64_t Hkv, int64_t D, int64_t max_seq_len) {
   const int64_t tiles = (max_seq_len + 31) / 32;
-  int64_t want = (2048 + B * Hkv - 1) / (B * Hkv > 0 ? B * Hkv : 1);
-  const int64_t cap = tiles / 8 > 1 ? tiles / 8 : 1;
-  if (want > cap) want = cap;
-  if (want < 1) want = 1;
-  if (want > 64) want = 64;
-  return (int)want;
+  const int64_t units = B * Hkv > 0 ? B * Hkv : 1;
+  int64_t ns;
+  if (g_tuning.decode_splits > 0) {
+    ns = g_tuning.decode_splits;
+    if (ns > tiles) ns = tiles;
+  } else {
+    int64_t fill = (512 + units - 1) / units;
+    if (fill > tiles / 16) fill = tiles / 16;
+    int64_t even = units >= 192 && units < 768 ? (D >= 128 ? 4 : 3) : (units >= 768 && units < 1536 ? 3 : 1);
+    if (even > tiles / 32) even = tiles / 32;
+    ns = fill > even ? fill : even;
+    if (ns > 32) ns = 32;
+  }
+  return (int)(ns < 1 ? 1 : ns);
 }
 
 }  // namespace
@@ -248,6 +260,7 @@ fl_status fl_set_tuning(const char* key, int value) {
   else if (!strcmp(key, "wpe")) g_tuning.wpe = value;
   else if (!strcmp(key, "order")) g_tuning.order = value == 0 ? -1 : value - 1;
   else if (!strcmp(key, "pair")) g_tuning.pair = value == 0 ? -1 : value - 1;
+  else if (!strcmp(key, "decode_splits")) g_tuning.decode_splits = value;
   else return fail(FL_ERR_UNSUPPORTED, "unknown tuning key '%s'", key);
   return FL_OK;
 }
@@ -615,7 +628,7 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
 size_t fl_attn_decode_workspace_size(const fl_tensor* q, const fl_tensor* k_cache, const fl_paged_kv* kv) {
   if (q == nullptr || k_cache == nullptr || kv == nullptr) return 0;
   const int64_t B = q->size[0], H = q->size[2], D = q->size[4];
-  const int ns = decode_splits(B, k_cache->size[2], kv->max_seq_len);
+  const int ns = decode_splits(B, k_cache->size[2], D, kv->max_seq_len);
   return (size_t)(B * H * ns) * (size_t)(D + 2) * sizeof(float);
 }
 
@@ -681,7 +694,7 @@ fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_
   if (empty) return FL_OK;
   if (aux == nullptr) return fail(FL_ERR_AUX_MISSING, "the decode step needs aux (workspace)");
   if (desc->score_mod == FL_MOD_ALIBI && aux->alibi_slopes == nullptr) return fail(FL_ERR_AUX_MISSING, "alibi_slopes");
-  const int ns = decode_splits(B, Hkv, kv->max_seq_len);
+  const int ns = decode_splits(B, Hkv, D, kv->max_seq_len);
   const size_t ws_need = (size_t)(B * H * ns) * (size_t)(D + 2) * sizeof(float);
   if (aux->workspace == nullptr || aux->workspace_bytes < ws_need)
     return fail(FL_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", ws_need, aux->workspace ? aux->workspace_bytes : (size_t)0);

@@ -290,33 +290,51 @@ decode_kernel(const DecodeParams p) {
 }
 
 // Merge of the splits of one (sequence, head): out = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M).
+// One wave per (sequence, head).  The statistics are read one split per lane (maximum and sum by
+// wave reductions); the partial outputs are then accumulated with each lane on its D / 64 channels,
+// the weight of split s taken from lane s, several loads in flight (a loop that waited for every
+// split's load in turn cost more than the attention itself on a long single sequence).
 template <int D>
 __global__ void __launch_bounds__(64) decode_combine_kernel(const DecodeParams p) {
   const int bh = blockIdx.x;
   const int h = bh % p.H, b = bh / p.H;
+  const int lane = threadIdx.x;
   constexpr int CPT = D / 64;
   const float* ml = p.part_ml + (int64_t)bh * p.nsplit * 2;
   float m_all = -INFINITY;
-  for (int s = 0; s < p.nsplit; ++s) m_all = fmaxf(m_all, ml[2 * s]);
+  for (int s = lane; s < p.nsplit; s += 64) m_all = fmaxf(m_all, ml[2 * s]);
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) m_all = fmaxf(m_all, __shfl_xor(m_all, o));
   const float m_safe = m_all == -INFINITY ? 0.f : m_all;
   float l_all = 0.f, acc[CPT];
 #pragma unroll
   for (int e = 0; e < CPT; ++e) acc[e] = 0.f;
-  for (int s = 0; s < p.nsplit; ++s) {
-    const float wgt = fast_exp2(ml[2 * s] - m_safe);
-    l_all = fmaf(ml[2 * s + 1], wgt, l_all);
-    const float* po = p.part_o + ((int64_t)bh * p.nsplit + s) * D + threadIdx.x * CPT;
+  for (int c = 0; c < p.nsplit; c += 64) {         // 64 splits per round, one per lane
+    const int s = c + lane;
+    float wgt = 0.f;
+    if (s < p.nsplit) {
+      wgt = fast_exp2(ml[2 * s] - m_safe);
+      l_all = fmaf(ml[2 * s + 1], wgt, l_all);
+    }
+    const int n = min(64, p.nsplit - c);           // uniform
+    const float* po = p.part_o + ((int64_t)bh * p.nsplit + c) * D + lane * CPT;
+#pragma unroll 8
+    for (int u = 0; u < n; ++u) {
+      const float wu = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(wgt), u));
 #pragma unroll
-    for (int e = 0; e < CPT; ++e) acc[e] = fmaf(po[e], wgt, acc[e]);
+      for (int e = 0; e < CPT; ++e) acc[e] = fmaf(po[(int64_t)u * D + e], wu, acc[e]);
+    }
   }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) l_all += __shfl_xor(l_all, o);
   const float inv = l_all > 0.f ? 1.f / l_all : 0.f;
-  const int64_t o = b * p.o_sb + h * p.o_sh + threadIdx.x * CPT;
+  const int64_t o = b * p.o_sb + h * p.o_sh + lane * CPT;
 #pragma unroll
   for (int e = 0; e < CPT; ++e) {
     if (p.out_f32) ((float*)p.out)[o + e] = acc[e] * inv;
     else ((uint16_t*)p.out)[o + e] = (uint16_t)(pack_bf16(acc[e] * inv, 0.f) & 0xFFFFu);
   }
-  if (threadIdx.x == 0 && p.lse != nullptr)
+  if (lane == 0 && p.lse != nullptr)
     p.lse[b * p.lse_sb + h * p.lse_sh] = l_all > 0.f ? (m_all + __log2f(l_all)) * kLn2 : -INFINITY;
 }
 
