@@ -1,4 +1,5 @@
-"""PyTorch-facing call of the library: `attention(q, k, v, ...)` with autograd support.
+"""PyTorch-facing calls of the library: `attention(q, k, v, ...)` with autograd support and
+`decode_attention(...)` for one decode step over a paged cache.
 
 Marshalling only: the forward pass is fl_attn_fwd, the backward pass fl_attn_bwd, both through
 the C-ABI binding; no attention arithmetic happens here and there is no fallback path.  Tensors
@@ -101,3 +102,50 @@ def attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, scale: Optio
     if q_doc_ids is not None and kv_doc_ids is None:
         kv_doc_ids = q_doc_ids
     return _Attention.apply(q, k, v, scale, causal, window, prefix, softcap, alibi_slopes, q_doc_ids, kv_doc_ids)
+
+
+def decode_attention(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, seq_lens: torch.Tensor,
+                     block_table: Optional[torch.Tensor] = None, *, max_seq_len: Optional[int] = None,
+                     scale: Optional[float] = None, window: Optional[int] = None, softcap: Optional[float] = None,
+                     alibi_slopes: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                     return_lse: bool = False):
+    """One decode step (fl_attn_decode): the last token of every sequence against its cached keys.
+
+    q [B, H, D] bf16; k_cache, v_cache [pages, page_size, Hkv, D] bf16 (any strides with unit inner
+    stride, e.g. a permuted [pages, Hkv, page_size, D] buffer); seq_lens int32 [B] on the device;
+    block_table int32 [B, max_pages] or None for a contiguous cache (sequence b in "page" b).
+    max_seq_len is a host-side bound on seq_lens (it fixes the launch shape; default: the capacity
+    of the table, so no device value is read back).  workspace: a uint8 tensor of at least
+    decode_workspace_size(...) bytes to reuse across steps; allocated here when omitted.
+    Returns out [B, H, D] bf16 (and lse [B, H] float32 with return_lse).  Not differentiable.
+    """
+    if not q.is_cuda or q.dtype != torch.bfloat16 or q.dim() != 3:
+        raise ValueError("decode_attention() takes a bf16 CUDA q of shape [B, H, D]")
+    B, H, D = q.shape
+    page_size = k_cache.shape[1]
+    if max_seq_len is None:
+        max_seq_len = (block_table.shape[1] if block_table is not None else 1) * page_size
+    if scale is None:
+        scale = D ** -0.5
+    if softcap is not None and alibi_slopes is not None:
+        raise ValueError("one score_mod at a time")
+    mod = fb.FL_MOD_SOFTCAP if softcap is not None else (fb.FL_MOD_ALIBI if alibi_slopes is not None else fb.FL_MOD_NONE)
+    desc = fb.variant_desc(scale=float(scale), score_mod=mod, softcap=float(softcap or 0.0),
+                           mask=(fb.FL_MASK_WINDOW | fb.FL_MASK_CAUSAL) if window is not None else fb.FL_MASK_CAUSAL,
+                           window=int(window or 0))
+    q5 = q[:, None, :, None, :]
+    k5, v5 = k_cache.permute(0, 2, 1, 3)[:, None], v_cache.permute(0, 2, 1, 3)[:, None]    # [pages, 1, Hkv, page_size, D]
+    out = torch.empty((B, 1, H, 1, D), dtype=torch.bfloat16, device=q.device)
+    lse = torch.empty((B, 1, H, 1, 1), dtype=torch.float32, device=q.device) if return_lse else None
+    kv = fb.paged_kv(block_table=block_table, page_size=page_size, seq_lens=seq_lens, max_seq_len=int(max_seq_len))
+    tq, tk, tv, tout = (fb.tensor_desc(x) for x in (q5, k5, v5, out))
+    tlse = fb.tensor_desc(lse) if return_lse else None
+    need = max(fb.fl_attn_decode_workspace_size(tq, tk, kv), 16)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    elif workspace.numel() * workspace.element_size() < need:
+        raise ValueError(f"workspace holds {workspace.numel() * workspace.element_size()} bytes, {need} needed")
+    aux = fb.aux_desc(alibi_slopes=alibi_slopes, workspace=workspace)
+    fb.check(fb.fl_attn_decode(tq, tk, tv, kv, desc, aux, tout, tlse, torch.cuda.current_stream(q.device).cuda_stream))
+    out = out[:, 0, :, 0, :]
+    return (out, lse[:, 0, :, 0, 0]) if return_lse else out

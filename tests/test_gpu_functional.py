@@ -65,3 +65,28 @@ def test_rejects_what_it_cannot_run():
     y = torch.zeros(1, 2, 16, 64, device="cuda:0", dtype=torch.float32)
     with pytest.raises(ValueError):
         attention(y, y, y)
+
+
+def test_decode_wrapper_matches_oracle():
+    import torch
+    from oracle import decode_oracle as do
+    from paper_2511_02043_amd.functional import decode_attention
+    w = inputs.decode_bf16(H=8, Hkv=2, D=128, page_size=16, seq_lens=[1, 47, 600, 1025])
+    dev = "cuda:0"
+    q = torch.from_numpy(w.q).to(dev, torch.bfloat16)
+    kc = torch.from_numpy(w.k_cache).to(dev, torch.bfloat16)
+    vc = torch.from_numpy(w.v_cache).to(dev, torch.bfloat16)
+    table, lens = torch.from_numpy(w.block_table).to(dev), torch.from_numpy(w.seq_lens).to(dev)
+    ref, ref_lse = do.decode_attention(w.q, w.k_cache, w.v_cache, w.block_table, w.seq_lens, scale=w.scale, window=300)
+    out, lse = decode_attention(q, kc, vc, lens, table, window=300, return_lse=True)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()
+    assert np.all(np.abs(got - ref) <= 1e-2 + 2.0 ** -8 * np.abs(ref))
+    assert np.max(np.abs(lse.cpu().numpy() - ref_lse)) <= 1e-3
+    # a reused workspace and a tight length bound give the same result
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device=dev)
+    out2 = decode_attention(q, kc, vc, lens, table, window=300, max_seq_len=1025, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.all(np.abs(out2.float().cpu().numpy() - ref) <= 1e-2 + 2.0 ** -8 * np.abs(ref))
+    with pytest.raises(ValueError):
+        decode_attention(q, kc, vc, lens, table, workspace=torch.empty(8, dtype=torch.uint8, device=dev))

@@ -1,4 +1,4 @@
-"""The library under HIP graph capture: fl_attn_fwd and fl_attn_bwd allocate nothing, never
+"""The library under HIP graph capture: fl_attn_fwd, fl_attn_bwd and fl_attn_decode allocate nothing, never
 synchronise and launch only on the caller's stream, so a captured call sequence can be replayed.
 Every replay is compared bit for bit with the eager result, with eager work and synchronisations
 between the replays."""
@@ -42,3 +42,45 @@ def test_forward_and_backward_replay_from_a_graph(case):
         torch.cuda.synchronize()
         for name, t, r in zip(("out", "lse", "dq", "dk", "dv"), outs, ref):
             assert torch.equal(t, r), f"{case}: replay {rep} differs in {name}"
+
+
+def test_decode_replays_from_a_graph_while_sequences_grow():
+    """A serving loop captures one decode step and replays it as the sequences grow: seq_lens and the
+    block table are device data, the launch shape depends on the host-side bound max_seq_len only."""
+    import torch
+    from oracle import decode_oracle as do
+    final = np.array([131, 741, 53, 1], dtype=np.int32)
+    w = inputs.decode_bf16(H=8, Hkv=2, D=128, page_size=16, seq_lens=final)
+    dd = runner.upload_decode(w)                    # pages, table and max_seq_len sized for the final lengths
+    lens = dd.keep[1]
+    outs = (dd.out, dd.lse)
+
+    def eager(cur):
+        lens.copy_(torch.from_numpy(cur))
+        dd.run_checked()
+        torch.cuda.synchronize()
+        return [t.clone() for t in outs]
+
+    steps = [np.maximum(final - 20, 0).astype(np.int32), np.maximum(final - 7, 0).astype(np.int32), final]
+    refs = [eager(cur) for cur in steps]
+    ref_out, ref_lse = do.decode_attention(w.q, w.k_cache, w.v_cache, w.block_table, final, scale=w.scale)
+    got_out, got_lse = refs[-1][0].float().cpu().numpy()[:, 0, :, 0], refs[-1][1].cpu().numpy()[:, 0, :, 0, 0]
+    assert np.max(np.abs(got_out - ref_out)) <= 1e-2 and np.max(np.abs(got_lse - ref_lse)) <= 1e-3
+
+    lens.copy_(torch.from_numpy(steps[0]))
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        dd.run_checked(torch.cuda.current_stream().cuda_stream)
+        graph.capture_end()
+    torch.cuda.synchronize()
+    for rep, (cur, ref) in enumerate(zip(steps, refs)):
+        lens.copy_(torch.from_numpy(cur))           # eager work between the replays
+        for t in outs:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, t, r in zip(("out", "lse"), outs, ref):
+            assert torch.equal(t, r), f"decode replay {rep} differs in {name}"
