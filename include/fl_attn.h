@@ -187,7 +187,8 @@ typedef struct {
   int32_t        page_size;     /* tokens per page (size[3] of the cache tensors); with a block table a
                                    power of two >= 8                                                         */
   const int32_t* seq_lens;      /* [B] device: cached tokens of each sequence, 0 <= len <= pages * page_size */
-  int32_t        max_seq_len;   /* host-side upper bound of seq_lens: sizes the launch and the workspace     */
+  int32_t        max_seq_len;   /* host-side upper bound of seq_lens: sizes the launch and the workspace;
+                                   a device length outside [0, max_seq_len] is cut to that range           */
   int32_t        reserved2;
 } fl_paged_kv;
 

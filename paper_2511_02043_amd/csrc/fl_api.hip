@@ -731,6 +731,7 @@ fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_
   p.part_ml = p.part_o + B * H * ns * D;
   p.alibi_slopes = aux->alibi_slopes;
   p.B = (int)B; p.H = (int)H; p.Hkv = (int)Hkv; p.nsplit = ns;
+  p.max_len = kv->max_seq_len;
   p.window = (mask & FL_MASK_WINDOW) ? desc->window : -1;
   p.scale = desc->scale;
   p.softcap = desc->softcap;

@@ -38,6 +38,7 @@ struct DecodeParams {
   float* part_ml;                  // workspace [B, H, nsplit, 2]: running max (log2 domain), sum
   const float* alibi_slopes;       // [H]
   int32_t B, H, Hkv, nsplit;
+  int32_t max_len;                 // the host-side bound of seq_lens that sized the launch, the table and the workspace
   int32_t window;                  // < 0: no window
   float scale, softcap;
 };
@@ -79,7 +80,8 @@ decode_kernel(const DecodeParams p) {
   const int hk = bhk % p.Hkv, b = bhk / p.Hkv;
   const int group = p.H / p.Hkv;                   // query heads per kv head (<= 32)
   const int hq = hk * group + (w.col < group ? w.col : group - 1);   // this lane's query head (clamped copies beyond the group)
-  const int len = p.seq_lens[b];
+  // a length outside [0, max_len] would walk past the block table: such a sequence is cut to the bound
+  const int len = min(max(p.seq_lens[b], 0), p.max_len);
 
   // key tiles of this workgroup, then of this wave
   const int first_key = p.window >= 0 ? max(0, len - 1 - p.window) : 0;

@@ -148,3 +148,22 @@ def test_decode_full_size_sampled():
         le = float(np.max(np.abs(lse[b, 0, :, 0, 0].cpu().numpy() - ref_lse[0])))
         print(f"decode full size, sequence {b} (len {lens[b]}): max_abs={err:.3e} lse={le:.3e}", flush=True)
         assert err <= 1e-2 and le <= 1e-3
+
+
+def test_lengths_outside_the_host_bound_are_cut_to_it():
+    """seq_lens is device data the host cannot check; a value beyond max_seq_len (or negative) must not
+    walk past the block table: the kernel cuts it to [0, max_seq_len]."""
+    import torch
+    w = inputs.decode_bf16(H=8, Hkv=2, D=128, page_size=16, seq_lens=[100, 500, 37])
+    dd = runner.upload_decode(w)                    # max_seq_len = 500, table 32 pages wide
+    lens = dd.keep[1]
+    lens.copy_(torch.tensor([100, 1 << 30, -5], dtype=torch.int32))
+    dd.run_checked()
+    torch.cuda.synchronize()
+    got, got_lse = dd.out.float().cpu().numpy()[:, 0, :, 0], dd.lse.cpu().numpy()[:, 0, :, 0, 0]
+    cut = np.array([100, 500, 0], dtype=np.int32)
+    # sequence 1 owns 32 pages (500 tokens -> 32 pages of 16): all 500 positions of the cut length are its own
+    ref, ref_lse = do.decode_attention(w.q, w.k_cache, w.v_cache, w.block_table, cut, scale=w.scale)
+    assert np.max(np.abs(got - ref)) <= 1e-2
+    assert np.all(np.isneginf(got_lse[2])) and np.all(got[2] == 0.0)
+    assert np.max(np.abs(got_lse[:2] - ref_lse[:2])) <= 1e-3
