@@ -182,7 +182,8 @@ typedef struct {
   uint32_t       struct_size;   /* sizeof(fl_paged_kv) */
   uint32_t       reserved;
   const int32_t* block_table;   /* [B, table_stride] device: page holding tokens p*page_size .. of sequence b;
-                                   NULL: no paging, sequence b is page b of the cache                         */
+                                   NULL: no paging, sequence b is page b of the cache; an entry outside
+                                   [0, pages) is cut to that range (wrong data, never a wild address)       */
   int32_t        table_stride;  /* elements between the rows of block_table                                  */
   int32_t        page_size;     /* tokens per page (size[3] of the cache tensors); with a block table a
                                    power of two >= 8                                                         */

@@ -651,6 +651,8 @@ fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_
   const int64_t B = q->size[0], H = q->size[2], D = q->size[4];
   const int64_t pages = k_cache->size[0], Hkv = k_cache->size[2], page_size = k_cache->size[3];
   if (B < 0 || H < 0 || D <= 0 || pages < 0 || page_size <= 0) return fail(FL_ERR_SHAPE, "negative size");
+  if (pages > 0x7fffffffLL) return fail(FL_ERR_SHAPE, "more pages than an int32 table entry can name");
+  if (pages == 0 && kv->max_seq_len > 0) return fail(FL_ERR_SHAPE, "max_seq_len = %d with an empty cache", kv->max_seq_len);
   if (q->size[1] != 1 || q->size[3] != 1) return fail(FL_ERR_SHAPE, "q must be [B, 1, H, 1, D]");
   if (Hkv <= 0 || H % Hkv != 0 || H / Hkv > 32)
     if (H != 0) return fail(FL_ERR_SHAPE, "kv heads (%lld) must divide q heads (%lld), at most 32 q heads per kv head", (long long)Hkv, (long long)H);
@@ -732,6 +734,7 @@ fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_
   p.alibi_slopes = aux->alibi_slopes;
   p.B = (int)B; p.H = (int)H; p.Hkv = (int)Hkv; p.nsplit = ns;
   p.max_len = kv->max_seq_len;
+  p.num_pages = (int)pages;
   p.window = (mask & FL_MASK_WINDOW) ? desc->window : -1;
   p.scale = desc->scale;
   p.softcap = desc->softcap;

@@ -38,6 +38,7 @@ struct DecodeParams {
   float* part_ml;                  // workspace [B, H, nsplit, 2]: running max (log2 domain), sum
   const float* alibi_slopes;       // [H]
   int32_t B, H, Hkv, nsplit;
+  int32_t num_pages;               // size[0] of the caches: table entries are cut to [0, num_pages)
   int32_t max_len;                 // the host-side bound of seq_lens that sized the launch, the table and the workspace
   int32_t window;                  // < 0: no window
   float scale, softcap;
@@ -115,7 +116,7 @@ decode_kernel(const DecodeParams p) {
     for (int u = 0; u < 4; ++u) {
       if (p.block_table != nullptr) {
         const int j = min(t * BN + (u << p.page_shift), len - 1);           // first token of the tile's u-th page, clamped
-        r.pg[u] = p.block_table[(int64_t)b * p.table_stride + (j >> p.page_shift)];
+        r.pg[u] = min(max(p.block_table[(int64_t)b * p.table_stride + (j >> p.page_shift)], 0), p.num_pages - 1);
       } else {
         r.pg[u] = b;
       }

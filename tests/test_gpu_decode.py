@@ -167,3 +167,20 @@ def test_lengths_outside_the_host_bound_are_cut_to_it():
     assert np.max(np.abs(got - ref)) <= 1e-2
     assert np.all(np.isneginf(got_lse[2])) and np.all(got[2] == 0.0)
     assert np.max(np.abs(got_lse[:2] - ref_lse[:2])) <= 1e-3
+
+
+def test_table_entries_outside_the_cache_are_cut_to_it():
+    """A corrupt block table must not turn into a wild address: entries are cut to [0, pages)."""
+    import torch
+    w = inputs.decode_bf16(H=4, Hkv=2, D=64, page_size=16, seq_lens=[40, 90], shuffle_pages=False)
+    n_pages = w.k_cache.shape[0]
+    bad = w.block_table.copy()
+    bad[0, 1], bad[1, 2] = 1 << 30, -7               # read as pages n_pages - 1 and 0
+    cut = np.clip(bad, 0, n_pages - 1)
+    dd = runner.upload_decode(w)
+    dd.keep[0].copy_(torch.from_numpy(bad))
+    dd.run_checked()
+    torch.cuda.synchronize()
+    got = dd.out.float().cpu().numpy()[:, 0, :, 0]
+    ref, _ = do.decode_attention(w.q, w.k_cache, w.v_cache, cut, w.seq_lens, scale=w.scale)
+    assert np.max(np.abs(got - ref)) <= 1e-2
