@@ -74,10 +74,12 @@ fl_status check_desc(const fl_variant_desc* d) {
   return FL_OK;
 }
 
-const fl::KernelEntry* find_entry(const fl_variant_desc* d, int dtype, int D, int Dv) {
+// Sk > 0: the key length of the call, for the shape preference; <= 0: any shape of the variant will do.
+const fl::KernelEntry* find_entry(const fl_variant_desc* d, int dtype, int D, int Dv, int64_t Sk = 0) {
   const Registry& r = registry();
   const int mask = (int)canonical_mask(d->mask);
   const fl::KernelEntry* best = nullptr;
+  const fl::KernelEntry* short_loop = nullptr;    // the variant's 32-key-tile, four-waves-per-SIMD shape, if listed
   for (int t = 0; t < 5; ++t)
     for (int e = 0; e < r.n[t]; ++e) {
       const fl::KernelEntry& k = r.tab[t][e];
@@ -97,7 +99,13 @@ const fl::KernelEntry* find_entry(const fl_variant_desc* d, int dtype, int D, in
                (g_tuning.wpe == 0 || e.key.wpe == g_tuning.wpe);
       };
       if (best == nullptr || (wanted(k) && !wanted(*best))) best = &k;
+      if (short_loop == nullptr && k.key.bn == 32 && k.key.wpe == 4) short_loop = &k;
     }
+  // Short key loops: start-up and drain of a workgroup weigh more than the per-tile cost, and four
+  // small workgroups per CU hide them better than two large ones (measured on the paper's grid at
+  // head dim 64; the crossover is at a few dozen key tiles per query tile).
+  const bool tuned = g_tuning.bm || g_tuning.bn || g_tuning.rb || g_tuning.nw || g_tuning.wpe;
+  if (!tuned && best != nullptr && short_loop != nullptr && Sk > 0 && Sk <= (mask == 0 ? 4096 : 2048)) best = short_loop;
   return best;
 }
 
@@ -377,7 +385,7 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
     if (D % 4 != 0 || Dv % 4 != 0) return fail(FL_ERR_UNSUPPORTED, "f32 head dims must be multiples of 4");
     if (!empty && out->dtype != FL_F32) return fail(FL_ERR_DTYPE, "f32 inputs need f32 out");
   }
-  const fl::KernelEntry* ke = find_entry(desc, dtype, (int)D, (int)Dv);
+  const fl::KernelEntry* ke = find_entry(desc, dtype, (int)D, (int)Dv, Sk);
   if (ke == nullptr)
     return fail(FL_ERR_UNSUPPORTED,
                 "no specialisation for dtype=%d D=%lld Dv=%lld score_mod=%u mask=0x%x n_bias=%u combine=%u epilogue=0x%x",

@@ -14,6 +14,21 @@ def test_grid_cell_s512(variant, gqa):
     run_and_compare(inputs.grid_bf16(variant, 512, gqa=gqa, B=2), label=f"grid {variant} gqa={gqa} S=512")
 
 
+@pytest.mark.parametrize("variant", ["vanilla", "causal", "softcap", "prefix_lm", "sliding_window"])
+def test_grid_cell_s512_both_tile_shapes(variant):
+    """Short key loops run the 32-key-tile shape by default; the 64-key-tile shape of the same variant
+    (the default of long sequences) is forced here on the same cell."""
+    from paper_2511_02043_amd import binding as fb
+    try:
+        for bn, wpe in ((64, 2), (32, 4)):
+            fb.check(fb.fl_set_tuning("bn", bn))
+            fb.check(fb.fl_set_tuning("wpe", wpe))
+            run_and_compare(inputs.grid_bf16(variant, 512, B=2), label=f"grid {variant} S=512 bn={bn} wpe={wpe}")
+    finally:
+        fb.fl_set_tuning("bn", 0)
+        fb.fl_set_tuning("wpe", 0)
+
+
 @pytest.mark.parametrize("variant", ["sliding_window", "prefix_lm", "document_mask", "causal"])
 def test_grid_cell_s2048_gqa(variant):
     """Longer rows: several key tiles inside and outside the window / prefix / documents."""
