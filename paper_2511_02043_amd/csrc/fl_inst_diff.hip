@@ -9,6 +9,7 @@ static const KernelEntry kEntries[] = {
     E(128, 128, kMaskCausal, kEpiRms), E(128, 128, kMaskCausal, 0),
     E(64, 64, kMaskCausal, kEpiRms), E(64, 64, kMaskCausal, 0),
     E(64, 64, 0, 0), E(128, 128, 0, 0),   // the paper's DiffAttn benchmark shapes: no mask, no normalisation
+    bf16_entry<64, 64, 8, 1, 32, 4, kModNone, 0, 0, true, 0>(),   // short key loops: two workgroups per CU
 };
 #undef E
 const KernelEntry* entries_diff(int* n) {

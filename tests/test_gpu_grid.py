@@ -49,3 +49,15 @@ def test_evoformer_paper_shape(D):
 @pytest.mark.parametrize("S,D", [(512, 64), (1024, 128)])
 def test_diffattn_paper_shape(S, D):
     run_and_compare(inputs.diffattn_paper_bf16(S=S, D=D, B=1, H=4), label=f"DiffAttn S={S} D={D}")
+
+
+def test_diffattn_s512_both_tile_shapes():
+    from paper_2511_02043_amd import binding as fb
+    try:
+        for bn, wpe in ((64, 2), (32, 4)):
+            fb.check(fb.fl_set_tuning("bn", bn))
+            fb.check(fb.fl_set_tuning("wpe", wpe))
+            run_and_compare(inputs.diffattn_paper_bf16(S=512, D=64, B=1, H=4), label=f"DiffAttn S=512 D=64 bn={bn} wpe={wpe}")
+    finally:
+        fb.fl_set_tuning("bn", 0)
+        fb.fl_set_tuning("wpe", 0)
