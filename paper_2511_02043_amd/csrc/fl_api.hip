@@ -79,7 +79,7 @@ const fl::KernelEntry* find_entry(const fl_variant_desc* d, int dtype, int D, in
   const Registry& r = registry();
   const int mask = (int)canonical_mask(d->mask);
   const fl::KernelEntry* best = nullptr;
-  const fl::KernelEntry* short_loop = nullptr;    // the variant's 32-key-tile, four-waves-per-SIMD shape, if listed
+  const fl::KernelEntry* short_loop = nullptr;    // the variant's 32-key-tile shape at three or four waves per SIMD, if listed
   for (int t = 0; t < 5; ++t)
     for (int e = 0; e < r.n[t]; ++e) {
       const fl::KernelEntry& k = r.tab[t][e];
@@ -99,7 +99,7 @@ const fl::KernelEntry* find_entry(const fl_variant_desc* d, int dtype, int D, in
                (g_tuning.wpe == 0 || e.key.wpe == g_tuning.wpe);
       };
       if (best == nullptr || (wanted(k) && !wanted(*best))) best = &k;
-      if (short_loop == nullptr && k.key.bn == 32 && k.key.wpe == 4) short_loop = &k;
+      if (short_loop == nullptr && k.key.bn == 32 && k.key.wpe >= 3) short_loop = &k;
     }
   // Short key loops: start-up and drain of a workgroup weigh more than the per-tile cost, and four
   // small workgroups per CU hide them better than two large ones (measured on the paper's grid at

@@ -61,3 +61,15 @@ def test_diffattn_s512_both_tile_shapes():
     finally:
         fb.fl_set_tuning("bn", 0)
         fb.fl_set_tuning("wpe", 0)
+
+
+def test_evoformer_d64_both_tile_shapes():
+    from paper_2511_02043_amd import binding as fb
+    try:
+        for bn, wpe in ((64, 2), (32, 3)):
+            fb.check(fb.fl_set_tuning("bn", bn))
+            fb.check(fb.fl_set_tuning("wpe", wpe))
+            run_and_compare(inputs.evoformer_paper_bf16(B=1, N=256, H=4, D=64), label=f"Evoformer 256x256 D=64 bn={bn} wpe={wpe}")
+    finally:
+        fb.fl_set_tuning("bn", 0)
+        fb.fl_set_tuning("wpe", 0)
