@@ -10,11 +10,15 @@ static const KernelEntry kEntries[] = {
     // sliding window: short key loops, most tiles partly masked; 32-key tiles at four waves per SIMD (four
     // resident workgroups per CU) measured 10 % faster than the common shape, which stays selectable
     bf16_entry<64, 64, 4, 1, 32, 4, kModNone, CW, 0, false, 0>(),
+    // window and document mask: three waves per SIMD (the document ids do not fit four), 7 % faster at every length
+    bf16_entry<64, 64, 4, 1, 32, 3, kModNone, CW | kMaskDoc, 0, false, 0>(),
     E(64, kModNone, CW),   E(64, kModNone, CW | kMaskDoc),  E(64, kModNone, kMaskDoc),
     E(64, kModNone, kMaskCausal | kMaskDoc), E(64, kModNone, kMaskPrefix), E(64, kModNone, kMaskPrefix | kMaskDoc),
-    // the same shape for the short key loops of other variants (chosen by the host for Sk <= 2048, where it
-    // measured 2 - 8 % faster; ALiBi spills at this register budget and document masks gain nothing)
+    // 32-key tiles for the short key loops of other variants (chosen by the host for Sk <= 2048, where they
+    // measured 2 - 11 % faster): four waves per SIMD, or three where the document ids need the registers.
+    // ALiBi gains only at S = 512 and keeps one shape.
     bf16_entry<64, 64, 4, 1, 32, 4, kModSoftcap, 0, 0, false, 0>(), bf16_entry<64, 64, 4, 1, 32, 4, kModNone, kMaskPrefix, 0, false, 0>(),
+    bf16_entry<64, 64, 4, 1, 32, 3, kModNone, kMaskDoc, 0, false, 0>(), bf16_entry<64, 64, 4, 1, 32, 3, kModNone, kMaskCausal | kMaskDoc, 0, false, 0>(),
     E(128, kModAlibi, 0),  E(128, kModSoftcap, 0), E(128, kModNone, CW), E(128, kModNone, CW | kMaskDoc),
     E(128, kModNone, kMaskDoc), E(128, kModNone, kMaskCausal | kMaskDoc), E(128, kModNone, kMaskPrefix),
 };

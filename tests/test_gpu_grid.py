@@ -14,16 +14,22 @@ def test_grid_cell_s512(variant, gqa):
     run_and_compare(inputs.grid_bf16(variant, 512, gqa=gqa, B=2), label=f"grid {variant} gqa={gqa} S=512")
 
 
-@pytest.mark.parametrize("variant", ["vanilla", "causal", "softcap", "prefix_lm", "sliding_window"])
+@pytest.mark.parametrize("variant", ["vanilla", "causal", "softcap", "prefix_lm", "sliding_window", "document_mask"])
 def test_grid_cell_s512_both_tile_shapes(variant):
     """Short key loops run the 32-key-tile shape by default; the 64-key-tile shape of the same variant
     (the default of long sequences) is forced here on the same cell."""
     from paper_2511_02043_amd import binding as fb
     try:
-        for bn, wpe in ((64, 2), (32, 4)):
+        for bn, wpe in ((64, 2), (32, 3 if variant == "document_mask" else 4)):
             fb.check(fb.fl_set_tuning("bn", bn))
             fb.check(fb.fl_set_tuning("wpe", wpe))
             run_and_compare(inputs.grid_bf16(variant, 512, B=2), label=f"grid {variant} S=512 bn={bn} wpe={wpe}")
+            if variant == "document_mask":          # the same two shapes under window + document and causal + document masks
+                run_and_compare(inputs.window_doc_bf16(B=2, H=2, S=700, D=64, window=100, lo=20, hi=300),
+                                label=f"window + document bn={bn} wpe={wpe}")
+                w = inputs.causal_bf16(B=2, H=2, S=600, D=64)
+                w.q_doc = w.kv_doc = inputs.doc_ids(2, 600, seed=5, lo=20, hi=300)
+                run_and_compare(w, label=f"causal + document bn={bn} wpe={wpe}")
     finally:
         fb.fl_set_tuning("bn", 0)
         fb.fl_set_tuning("wpe", 0)
