@@ -94,3 +94,22 @@ def test_compile_errors_are_reported():
     with pytest.raises(fb.FlError) as e:
         fb.CustomVariant("s", None, 96)
     assert e.value.status == fb.FL_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_chunked_prefill_offset_as_a_custom_mask(D):
+    """Sq new tokens against a longer cache (bottom-right causal alignment: query row i sits at position
+    i + Sk - Sq), with ALiBi measured from those positions: the offset is a literal in the expressions."""
+    import torch
+    Sq, Sk = 200, 1000
+    off = Sk - Sq
+    w = inputs.causal_bf16(B=2, H=4, Hkv=2, S=Sq, Sk=Sk, D=D, causal=False, salt=9)
+    var = fb.CustomVariant(f"s - 0.0625f * (float)(i + {off} - j)", f"j > i + {off}", D)
+    dw = runner.upload(w, out_dtype="f32")
+    fb.check(var.forward(dw.tq, dw.tk, dw.tv, float(w.scale), dw.tout, dw.tlse))
+    torch.cuda.synchronize()
+    ref, ref_lse = ao.attention_custom(w.q, w.k, w.v, scale=w.scale, score_mod=lambda s, b, g, h, i, j: s - 0.0625 * (i + off - j),
+                                       mask=lambda b, g, h, i, j: j > i + off)
+    assert float(np.max(np.abs(dw.out.cpu().numpy() - ref))) <= 1e-2
+    assert float(np.max(np.abs(dw.lse.cpu().numpy()[..., 0] - ref_lse))) <= 1e-3
+    var.release()
