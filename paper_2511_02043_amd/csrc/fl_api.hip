@@ -30,6 +30,7 @@ using fl::host::make_view;
 struct Tuning {
   int bm = 0, bn = 0, rb = 0, nw = 0, wpe = 0, order = -1, pair = -1;
   int decode_splits = 0;           // 0: chosen by decode_splits() from the shapes
+  int bwd_wg_target = 0;           // 0: the default of choose_hsplit
 } g_tuning;
 
 struct Registry {
@@ -182,21 +183,32 @@ constexpr int kBwdKeysPerWg = 128;                 // keys per workgroup of the 
 
 // Grouped-query heads: a dK/dV workgroup sums over the query heads of its group.  When that leaves
 // the launch with too few workgroups, the group is cut into hsplit subsets whose fp32 partial
-// sums a small kernel adds up afterwards.
-int choose_hsplit(int64_t B, int64_t G, int64_t H, int64_t Hkv, int64_t Sk) {
+// sums a small kernel adds up afterwards.  Cutting pays while a workgroup keeps enough (head, 64-row
+// query tile) items to amortise its partial sums: up to 1024 workgroups if at least 24 items remain
+// each, up to 2048 if at least 256 remain (fitted to a sweep over the paper's grouped-head shapes).
+int choose_hsplit(int64_t B, int64_t G, int64_t H, int64_t Hkv, int64_t Sq, int64_t Sk, uint32_t mask, int64_t window) {
   if (Hkv <= 0 || H <= Hkv || Sk <= 0) return 1;
   const int64_t group = H / Hkv, wgs = B * G * Hkv * ((Sk + kBwdKeysPerWg - 1) / kBwdKeysPerWg);
+  int64_t rows = Sq;                               // query rows that can see a workgroup's keys
+  if ((mask & FL_MASK_WINDOW) && window + kBwdKeysPerWg < rows) rows = window + kBwdKeysPerWg;
+  const int64_t items = group * ((rows + 63) / 64);
   int hs = 1;
-  while (hs < group && wgs * hs < 1024 && group % (hs * 2) == 0) hs *= 2;
+  if (g_tuning.bwd_wg_target > 0) {
+    while (hs < group && wgs * hs < g_tuning.bwd_wg_target && group % (hs * 2) == 0) hs *= 2;
+    return hs;
+  }
+  while (hs < group && group % (hs * 2) == 0 &&
+         ((wgs * hs < 1024 && items / (2 * hs) >= 24) || (wgs * hs < 2048 && items / (2 * hs) >= 256)))
+    hs *= 2;
   return hs;
 }
 
 BwdWorkspace bwd_workspace(int64_t B, int64_t G, int64_t H, int64_t Hkv, int64_t Sq, int64_t Sk, int64_t D,
-                           uint32_t mask) {
+                           uint32_t mask, int64_t window) {
   BwdWorkspace w;
   w.stat_bytes = ((size_t)(B * G * H * Sq) * sizeof(float) + 255) / 256 * 256;
   w.sum_bytes = (workspace_bytes(B, Sq, Sk, mask) + 255) / 256 * 256;
-  w.hsplit = choose_hsplit(B, G, H, Hkv, Sk);
+  w.hsplit = choose_hsplit(B, G, H, Hkv, Sq, Sk, mask, window);
   w.part_bytes = w.hsplit > 1 ? (size_t)w.hsplit * (size_t)(B * G * Hkv * Sk * D) * sizeof(float) : 0;
   w.total = 2 * w.stat_bytes + w.sum_bytes + 2 * w.part_bytes;
   return w;
@@ -269,6 +281,7 @@ fl_status fl_set_tuning(const char* key, int value) {
   else if (!strcmp(key, "order")) g_tuning.order = value == 0 ? -1 : value - 1;
   else if (!strcmp(key, "pair")) g_tuning.pair = value == 0 ? -1 : value - 1;
   else if (!strcmp(key, "decode_splits")) g_tuning.decode_splits = value;
+  else if (!strcmp(key, "bwd_wg_target")) g_tuning.bwd_wg_target = value;
   else return fail(FL_ERR_UNSUPPORTED, "unknown tuning key '%s'", key);
   return FL_OK;
 }
@@ -487,7 +500,8 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
 
 size_t fl_attn_bwd_workspace_size(const fl_tensor* q, const fl_tensor* k, const fl_variant_desc* desc) {
   if (q == nullptr || k == nullptr || desc == nullptr) return 0;
-  return bwd_workspace(q->size[0], q->size[1], q->size[2], k->size[2], q->size[3], k->size[3], q->size[4], desc->mask).total;
+  return bwd_workspace(q->size[0], q->size[1], q->size[2], k->size[2], q->size[3], k->size[3], q->size[4], canonical_mask(desc->mask),
+                       desc->window).total;
 }
 
 int fl_bwd_supported(const fl_variant_desc* desc, int dtype, int D, int Dv) {
@@ -555,7 +569,7 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   if ((mask & FL_MASK_DOC) && (aux->q_doc_ids == nullptr || aux->kv_doc_ids == nullptr))
     return fail(FL_ERR_AUX_MISSING, "q_doc_ids / kv_doc_ids");
   if (no_rows && no_keys) return FL_OK;
-  const BwdWorkspace wsz = bwd_workspace(B, G, H, Hkv, Sq, Sk, D, mask);
+  const BwdWorkspace wsz = bwd_workspace(B, G, H, Hkv, Sq, Sk, D, mask, desc->window);
   if (aux->workspace == nullptr || aux->workspace_bytes < wsz.total)
     return fail(FL_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", wsz.total, aux->workspace ? aux->workspace_bytes : (size_t)0);
   if (((uintptr_t)aux->workspace) % 16 != 0) return fail(FL_ERR_ALIGN, "workspace not 16-byte aligned");

@@ -126,8 +126,13 @@ def test_backward_validation_paths_return_before_any_launch():
     kv1.ptr, kv1.dtype = 0x1000, fb.FL_BF16
     kv1.size[:] = [1, 1, 1, 64, 64]
     kv1.stride[:] = [4096, 4096, 4096, 64, 1]
-    # few workgroups: the group is cut in two, each half writes fp32 partials of dk and dv
-    assert fb.fl_attn_bwd_workspace_size(t, kv1, d) == 2 * 512 + 2 * 2 * (64 * 64 * 4)
+    # a tiny problem keeps the group in one piece; cut in two (forced here), each half writes fp32 partials of dk and dv
+    assert fb.fl_attn_bwd_workspace_size(t, kv1, d) == 2 * 512
+    try:
+        fb.check(fb.fl_set_tuning("bwd_wg_target", 1024))
+        assert fb.fl_attn_bwd_workspace_size(t, kv1, d) == 2 * 512 + 2 * 2 * (64 * 64 * 4)
+    finally:
+        fb.fl_set_tuning("bwd_wg_target", 0)
     a = fb.aux_desc()
     assert fb.fl_attn_bwd(t, t, t, t, t, lse, d, None, t, t, t) == fb.FL_ERR_AUX_MISSING
     assert fb.fl_attn_bwd(t, t, t, t, t, lse, d, a, t, t, t) == fb.FL_ERR_WORKSPACE

@@ -171,3 +171,24 @@ def test_backward_error_paths():
     st = fb.fl_attn_bwd(f.tq, f.tk, f.tv, f.tout, db.tdout, f.tlse, f.desc, None, db.tdq, db.tdk, db.tdv)
     assert st == fb.FL_ERR_AUX_MISSING
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("name", ["causal_gqa_d64", "causal_gqa_d128", "doc_gqa_d64"])
+def test_grouped_heads_cut_over_several_workgroups(name):
+    """The head group of a dK/dV workgroup cut into subsets (fp32 partial sums + reduction kernel): forced
+    here on small shapes, which the host would leave in one piece."""
+    from paper_2511_02043_amd import binding as fb
+    try:
+        fb.check(fb.fl_set_tuning("bwd_wg_target", 4096))
+        compare(CASES[name](), label=f"{name} head subsets")
+    finally:
+        fb.fl_set_tuning("bwd_wg_target", 0)
+
+
+def test_grouped_heads_cut_by_the_host_rule():
+    """16 query heads on 2 kv heads at S = 512: enough (head, query tile) items per workgroup for the host to cut the group."""
+    from paper_2511_02043_amd import binding as fb
+    w = inputs.grid_bf16("causal", 512, gqa=True, B=1)
+    dw = runner.upload(w)
+    assert fb.fl_attn_bwd_workspace_size(dw.tq, dw.tk, dw.desc) > 2 * 256 * ((16 * 512 * 4 + 255) // 256)   # partials are part of it
+    compare(w, label="grid causal gqa S=512")
