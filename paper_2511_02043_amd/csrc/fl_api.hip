@@ -153,15 +153,19 @@ __global__ void empty_keys_kernel(fl::View out, int out_f32, float* lse, int64_t
       lse[b * lse_sb + (int64_t)(g * n_lse_g + s) * lse_sg + h * lse_sh + i] = -INFINITY;
 }
 
-const fl::BwdEntry* find_bwd_entry(const fl_variant_desc* d, int D) {
-  static const fl::BwdEntry* tab[2];
-  static int n[2];
-  static bool init = false;
-  if (!init) {
+struct BwdRegistry {
+  const fl::BwdEntry* tab[2];
+  int n[2];
+  BwdRegistry() {
     tab[0] = fl::entries_bwd64(&n[0]);
     tab[1] = fl::entries_bwd128(&n[1]);
-    init = true;
   }
+};
+
+const fl::BwdEntry* find_bwd_entry(const fl_variant_desc* d, int D) {
+  static const BwdRegistry reg;                    // initialised once, also under concurrent first calls
+  const fl::BwdEntry* const* tab = reg.tab;
+  const int* n = reg.n;
   const int mask = (int)canonical_mask(d->mask);
   for (int t = 0; t < 2; ++t)
     for (int e = 0; e < n[t]; ++e) {

@@ -1,6 +1,7 @@
 // Table of compiled backward specialisations (one dQ kernel and one dK/dV kernel per entry).
 #pragma once
 #include "fl_bwd_bf16.hpp"
+#include <atomic>
 #include "fl_registry.hpp"
 
 namespace fl {
@@ -20,14 +21,14 @@ struct BwdEntry {
 
 template <class K>
 hipError_t raise_lds_limit(K kernel) {
-  static bool done[64] = {};
+  static std::atomic<bool> done[64];              // zero-initialised; a repeated call from a second thread is harmless
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
-  if (dev < 0 || dev >= 64 || !done[dev]) {
+  if (dev < 0 || dev >= 64 || !done[dev].load(std::memory_order_acquire)) {
     e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
     if (e != hipSuccess) return e;
-    if (dev >= 0 && dev < 64) done[dev] = true;
+    if (dev >= 0 && dev < 64) done[dev].store(true, std::memory_order_release);
   }
   return hipSuccess;
 }

@@ -3,6 +3,7 @@
 // up in the concatenation of those arrays.  There is deliberately no generic fallback kernel.
 #pragma once
 #include "fl_kernel_bf16.hpp"
+#include <atomic>
 
 namespace fl {
 
@@ -31,14 +32,14 @@ constexpr int kMaxLdsBytes = 160 * 1024;           // LDS of a gfx950 compute un
 template <class C>
 hipError_t launch_bf16(const FwdParams& p, int nblocks, hipStream_t stream) {
   // Raising the dynamic-LDS limit is per device and sticky; cheap enough to repeat per device.
-  static bool done[64] = {};
+  static std::atomic<bool> done[64];              // zero-initialised; a repeated call from a second thread is harmless
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
-  if (dev < 0 || dev >= 64 || !done[dev]) {
+  if (dev < 0 || dev >= 64 || !done[dev].load(std::memory_order_acquire)) {
     e = hipFuncSetAttribute((const void*)fwd_bf16_kernel<C>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes);
     if (e != hipSuccess) return e;
-    if (dev >= 0 && dev < 64) done[dev] = true;
+    if (dev >= 0 && dev < 64) done[dev].store(true, std::memory_order_release);
   }
   hipLaunchKernelGGL(fwd_bf16_kernel<C>, dim3(nblocks), dim3(C::NT), p.lds_bytes, stream, p);
   return hipGetLastError();
