@@ -842,6 +842,17 @@ fwd_bf16_kernel(const FwdParams p) {
   full_tile_range(MASK, iw, iw + C::WROWS - 1, p.Sk, p.window, p.prefix, BN, tf_lo, tf_hi);
   tf_lo = __builtin_amdgcn_readfirstlane(tf_lo);
   tf_hi = __builtin_amdgcn_readfirstlane(min(tf_hi, t_hi));
+  // Tiles that hold a visible key of some row of this wave (positional masks): outside of
+  // [tv_lo, tv_hi) every score of the wave is hidden, which needs no per-score mask arithmetic.
+  constexpr bool kWaveSkip = (MASK & (kMaskCausal | kMaskWindow | kMaskPrefix)) != 0 &&
+                             (MASK & (kMaskDoc | kMaskCustom)) == 0;
+  int tv_lo = 0, tv_hi = 0;
+  if constexpr (kWaveSkip) {
+    int lo, hi;
+    key_range(MASK, iw, iw + C::WROWS - 1, p.Sk, p.window, p.prefix, lo, hi);
+    tv_lo = __builtin_amdgcn_readfirstlane(lo / BN);
+    tv_hi = __builtin_amdgcn_readfirstlane((hi + BN - 1) / BN);
+  }
   auto wave_class = [&](int t) __attribute__((always_inline)) -> int {            // uniform over the wave
     if (t >= t_hi) return kTileSkip;
     int2 ks = make_int2(0, 0);
@@ -996,9 +1007,19 @@ fwd_bf16_kernel(const FwdParams p) {
         const int tn = t1;
         const bool fulln = wave_full(t1);
         if (!full0) {                              // fully visible tiles were settled in phase B
-          w.mask(cur, t0 * BN);
-          w.rowmax(cur, mx);
-          w.advance_max(mx);
+          if (kWaveSkip && (t0 < tv_lo || t0 >= tv_hi)) {
+            // nothing of the tile is visible to this wave's rows: all -inf, the running max stays
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+              for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) cur[rb][nb][r] = -INFINITY;
+          } else {
+            w.mask(cur, t0 * BN);
+            w.rowmax(cur, mx);
+            w.advance_max(mx);
+          }
         }
         if constexpr (C::NBIAS > 0) {
           // bias of the next tile: staged one step ago into buffer (N + 1) % 2 (its values are
