@@ -228,7 +228,7 @@ const fl::DecodeEntry* find_decode_entry(int D, int mod) {
 
 // Splits of a sequence's key range, a function of the shapes and the host-side length bound only.
 // Measured on (sequences x kv heads) = 8 ... 2048 units and 1k ... 128k cached tokens: few units want
-// about 512 workgroups in all and tolerate splits as short as 16 tiles of 32 keys; with hundreds of
+// about 512 workgroups in all and tolerate splits as short as 16 (a sequence or two: 8) tiles of 32 keys; with hundreds of
 // units three or four splits (by head dim) of at least 32 tiles even out the different sequence lengths; more than
 // 32 splits never paid (every workgroup pays its start-up: length, first page lookups, first tiles).
 int decode_splits(int64_t B, int64_t Hkv, int64_t D, int64_t max_seq_len) {
@@ -240,7 +240,8 @@ int decode_splits(int64_t B, int64_t Hkv, int64_t D, int64_t max_seq_len) {
     if (ns > tiles) ns = tiles;
   } else {
     int64_t fill = (512 + units - 1) / units;
-    if (fill > tiles / 16) fill = tiles / 16;
+    const int64_t least = units <= 16 ? 8 : 16;    // tiles a split must keep
+    if (fill > tiles / least) fill = tiles / least;
     int64_t even = units >= 192 && units < 768 ? (D >= 128 ? 4 : 3) : (units >= 768 && units < 1536 ? 3 : 1);
     if (even > tiles / 32) even = tiles / 32;
     ns = fill > even ? fill : even;

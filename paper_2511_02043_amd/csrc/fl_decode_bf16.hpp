@@ -321,11 +321,20 @@ __global__ void __launch_bounds__(64) decode_combine_kernel(const DecodeParams p
     }
     const int n = min(64, p.nsplit - c);           // uniform
     const float* po = p.part_o + ((int64_t)bh * p.nsplit + c) * D + lane * CPT;
-#pragma unroll 8
-    for (int u = 0; u < n; ++u) {
-      const float wu = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(wgt), u));
+    for (int u0 = 0; u0 < n; u0 += 8) {            // eight loads in flight; past n: the last split again, weight 0
+      float x[8][CPT];
 #pragma unroll
-      for (int e = 0; e < CPT; ++e) acc[e] = fmaf(po[(int64_t)u * D + e], wu, acc[e]);
+      for (int k = 0; k < 8; ++k) {
+        const int u = min(u0 + k, n - 1);
+#pragma unroll
+        for (int e = 0; e < CPT; ++e) x[k][e] = po[(int64_t)u * D + e];
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const float wu = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(wgt), u0 + k));
+#pragma unroll
+        for (int e = 0; e < CPT; ++e) acc[e] = fmaf(x[k][e], wu, acc[e]);
+      }
     }
   }
 #pragma unroll
