@@ -192,3 +192,11 @@ def test_grouped_heads_cut_by_the_host_rule():
     dw = runner.upload(w)
     assert fb.fl_attn_bwd_workspace_size(dw.tq, dw.tk, dw.desc) > 2 * 256 * ((16 * 512 * 4 + 255) // 256)   # partials are part of it
     compare(w, label="grid causal gqa S=512")
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_large_logits_backward(D):
+    """Queries scaled by 16: P = exp(s - lse) must be formed from the saved lse without overflow."""
+    w = inputs.causal_bf16(B=1, H=4, Hkv=2, S=400, D=D)
+    w.q = w.q * 16.0
+    compare(w, label=f"large logits D={D}")
