@@ -7,9 +7,11 @@ namespace fl {
 static const KernelEntry kEntries[] = {
     // first entry of a head dim = default shape; the others are selectable with fl_set_tuning
     BOTH(128, 8, 1, 64, 2), BOTH(128, 4, 1, 64, 2), BOTH(128, 4, 2, 32, 1),
+    // D = 64, long key loops: two row blocks per wave on 32-key tiles (every K / V fragment read from LDS feeds
+    // two MFMAs; 225 registers, two waves per SIMD) measured 2 - 4 % faster than one row block on 64-key tiles.
     // (64, 4, 1, 32, 4): 32-key tiles at four waves per SIMD, four resident workgroups per CU: the host picks
     // it for short key loops (Sk <= 4096 unmasked, <= 2048 causal), where it measured 3 - 12 % faster
-    BOTH(64, 4, 1, 64, 2),  BOTH(64, 8, 1, 64, 2),  BOTH(64, 4, 1, 32, 4),
+    BOTH(64, 4, 2, 32, 2),  BOTH(64, 4, 1, 64, 2),  BOTH(64, 8, 1, 64, 2),  BOTH(64, 4, 1, 32, 4),
     BOTH(32, 4, 1, 64, 2),  BOTH(32, 4, 2, 64, 2),
 };
 #undef BOTH

@@ -144,7 +144,7 @@ def test_deterministic_run_to_run():
 
 @pytest.mark.parametrize("D,tune", [
     (128, dict(nw=8, rb=1, bn=64)), (128, dict(nw=4, rb=1, bn=64)), (128, dict(nw=4, rb=2, bn=32)),
-    (64, dict(nw=8, rb=1)), (64, dict(nw=4, rb=1, bn=64)), (64, dict(nw=4, rb=1, bn=32, wpe=4)),
+    (64, dict(nw=8, rb=1)), (64, dict(nw=4, rb=1, bn=64)), (64, dict(nw=4, rb=1, bn=32, wpe=4)), (64, dict(nw=4, rb=2, bn=32)),
     (32, dict(nw=4, rb=1)), (32, dict(nw=4, rb=2)),
 ])
 @pytest.mark.parametrize("order", [1, 2])
