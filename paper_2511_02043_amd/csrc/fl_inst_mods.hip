@@ -13,7 +13,9 @@ static const KernelEntry kEntries[] = {
     // window and document mask: three waves per SIMD (the document ids do not fit four), 7 % faster at every length
     bf16_entry<64, 64, 4, 1, 32, 3, kModNone, CW | kMaskDoc, 0, false, 0>(),
     E(64, kModNone, CW),   E(64, kModNone, CW | kMaskDoc),  E(64, kModNone, kMaskDoc),
-    E(64, kModNone, kMaskCausal | kMaskDoc), E(64, kModNone, kMaskPrefix), E(64, kModNone, kMaskPrefix | kMaskDoc),
+    E(64, kModNone, kMaskCausal | kMaskDoc),
+    bf16_entry<64, 64, 4, 2, 32, 2, kModNone, kMaskPrefix, 0, false, 0>(),   // long key loops: two row blocks per wave, as for plain / causal
+    E(64, kModNone, kMaskPrefix), E(64, kModNone, kMaskPrefix | kMaskDoc),
     // 32-key tiles for the short key loops of other variants (chosen by the host for Sk <= 2048, where they
     // measured 2 - 11 % faster): four waves per SIMD, or three where the document ids need the registers.
     // ALiBi gains only at S = 512 and keeps one shape.

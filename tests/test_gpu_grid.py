@@ -79,3 +79,9 @@ def test_evoformer_d64_both_tile_shapes():
     finally:
         fb.fl_set_tuning("bn", 0)
         fb.fl_set_tuning("wpe", 0)
+
+
+@pytest.mark.parametrize("variant", ["vanilla", "causal", "prefix_lm"])
+def test_grid_cell_s4160_default_long_loop_shape(variant):
+    """Past the short-loop lengths the host picks the two-row-block shape at head dim 64 (ragged length: 4160 = 16 * 256 + 64)."""
+    run_and_compare(inputs.grid_bf16(variant, 4160, B=1, H=2), label=f"grid {variant} S=4160 H=2")
