@@ -228,7 +228,8 @@ const fl::DecodeEntry* find_decode_entry(int D, int mod) {
 
 // Splits of a sequence's key range, a function of the shapes and the host-side length bound only.
 // Measured on (sequences x kv heads) = 8 ... 2048 units and 1k ... 128k cached tokens: few units want
-// about 512 workgroups in all and tolerate splits as short as 16 (a sequence or two: 8) tiles of 32 keys; with hundreds of
+// about 512 workgroups in all (256 when tiles are scarce: a wave has one tile in flight, so more waves are what
+// hides the latency of a tile on a nearly empty chip, down to 4 tiles per split); with hundreds of
 // units three or four splits (by head dim) of at least 32 tiles even out the different sequence lengths; more than
 // 32 splits never paid (every workgroup pays its start-up: length, first page lookups, first tiles).
 int decode_splits(int64_t B, int64_t Hkv, int64_t D, int64_t max_seq_len) {
@@ -239,9 +240,14 @@ int decode_splits(int64_t B, int64_t Hkv, int64_t D, int64_t max_seq_len) {
     ns = g_tuning.decode_splits;
     if (ns > tiles) ns = tiles;
   } else {
+    // enough tiles: about 512 workgroups in all; otherwise about 256, with splits as short as 4 tiles (one per
+    // wave) while the chip is nearly empty (<= 64 units), 16 beyond
     int64_t fill = (512 + units - 1) / units;
-    const int64_t least = units <= 16 ? 8 : 16;    // tiles a split must keep
-    if (fill > tiles / least) fill = tiles / least;
+    if (tiles / fill < 16) {
+      fill = (256 + units - 1) / units;
+      const int64_t least = units <= 64 ? 4 : 16;
+      if (fill > tiles / least) fill = tiles / least;
+    }
     int64_t even = units >= 192 && units < 768 ? (D >= 128 ? 4 : 3) : (units >= 768 && units < 1536 ? 3 : 1);
     if (even > tiles / 32) even = tiles / 32;
     ns = fill > even ? fill : even;
@@ -768,7 +774,8 @@ fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_
   hipStream_t stream = (hipStream_t)stream_v;
   hipError_t e = de->main(p, (int)(B * Hkv * ns), stream);
   if (e != hipSuccess) return fail(FL_ERR_LAUNCH, "decode launch: %s", hipGetErrorString(e));
-  if ((e = de->combine(p, (int)(B * H), stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "decode merge launch: %s", hipGetErrorString(e));
+  if (ns > 1 && (e = de->combine(p, (int)(B * H), stream)) != hipSuccess)   // a single split writes the result itself
+    return fail(FL_ERR_LAUNCH, "decode merge launch: %s", hipGetErrorString(e));
   return FL_OK;
 }
 

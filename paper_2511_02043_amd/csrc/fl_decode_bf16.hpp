@@ -279,7 +279,22 @@ decode_kernel(const DecodeParams p) {
           o[d][4 * r4 + 3] = fmaf(q4.w, wgt, o[d][4 * r4 + 3]);
         }
     }
-    if (w.col < group) {
+    if (w.col < group && p.nsplit == 1) {
+      // the only split of its sequence: this is the result, no partials and no merge kernel
+      const float inv = l_all > 0.f ? 1.f / l_all : 0.f;
+      const int64_t ob = b * p.o_sb + hq * p.o_sh;
+#pragma unroll
+      for (int d = 0; d < DB; ++d)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int ch = 32 * d + 8 * r4 + 4 * w.half;
+          const float x0 = o[d][4 * r4] * inv, x1 = o[d][4 * r4 + 1] * inv, x2 = o[d][4 * r4 + 2] * inv, x3 = o[d][4 * r4 + 3] * inv;
+          if (p.out_f32) *(float4*)((float*)p.out + ob + ch) = make_float4(x0, x1, x2, x3);
+          else *(uint2*)((uint16_t*)p.out + ob + ch) = make_uint2(pack_bf16(x0, x1), pack_bf16(x2, x3));
+        }
+      if (w.half == 0 && p.lse != nullptr)
+        p.lse[b * p.lse_sb + hq * p.lse_sh] = l_all > 0.f ? (m_all + __log2f(l_all)) * kLn2 : -INFINITY;
+    } else if (w.col < group) {
       const int64_t slot = ((int64_t)b * p.H + hq) * p.nsplit + split;
       float* po = p.part_o + slot * D;
 #pragma unroll
