@@ -4,10 +4,8 @@ calls); every result must equal the one the same call gives alone.  The library 
 state outside its arguments (the error detail is per thread)."""
 import threading
 
-import numpy as np
 import pytest
 
-from paper_2511_02043_amd import binding as fb
 from paper_2511_02043_amd import inputs, runner
 
 pytestmark = pytest.mark.gpu
