@@ -83,5 +83,15 @@ def test_evoformer_d64_both_tile_shapes():
 
 @pytest.mark.parametrize("variant", ["vanilla", "causal", "prefix_lm"])
 def test_grid_cell_s4160_default_long_loop_shape(variant):
-    """Past the short-loop lengths the host picks the two-row-block shape at head dim 64 (ragged length: 4160 = 16 * 256 + 64)."""
-    run_and_compare(inputs.grid_bf16(variant, 4160, B=1, H=2), label=f"grid {variant} S=4160 H=2")
+    """The two-row-block shape at head dim 64, the host's choice for long key loops on large launches (forced here:
+    this launch is small), at a ragged length (4160 = 16 * 256 + 64); then the host's own choice for this launch."""
+    from paper_2511_02043_amd import binding as fb
+    w = inputs.grid_bf16(variant, 4160, B=1, H=2)
+    try:
+        fb.check(fb.fl_set_tuning("rb", 2))
+        fb.check(fb.fl_set_tuning("bn", 32))
+        run_and_compare(w, label=f"grid {variant} S=4160 H=2 two row blocks")
+    finally:
+        fb.fl_set_tuning("rb", 0)
+        fb.fl_set_tuning("bn", 0)
+    run_and_compare(w, label=f"grid {variant} S=4160 H=2")
