@@ -49,6 +49,13 @@ const Registry& registry() {
   return r;
 }
 
+// A window that reaches past both sequence ends changes nothing; cutting it there keeps the kernels'
+// int32 arithmetic on i - window and j + window far from overflow (callers pass INT_MAX for "no limit").
+int32_t clamp_window(int32_t window, int64_t Sq, int64_t Sk) {
+  const int64_t lim = Sq > Sk ? Sq : Sk;
+  return (int64_t)window > lim ? (int32_t)lim : window;
+}
+
 // Canonical mask bits: WINDOW implies CAUSAL.
 uint32_t canonical_mask(uint32_t m) { return (m & FL_MASK_WINDOW) ? (m | FL_MASK_CAUSAL) : m; }
 
@@ -459,7 +466,7 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   }
   p.B = (int)B; p.G = (int)G; p.H = (int)H; p.Hkv = (int)Hkv; p.Sq = (int)Sq; p.Sk = (int)Sk;
   p.D = (int)D; p.Dv = (int)Dv;
-  p.window = desc->window;
+  p.window = clamp_window(desc->window, Sq, Sk);
   p.prefix = desc->prefix_len;
   p.scale = desc->scale;
   p.softcap = desc->softcap;
@@ -526,7 +533,7 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
 size_t fl_attn_bwd_workspace_size(const fl_tensor* q, const fl_tensor* k, const fl_variant_desc* desc) {
   if (q == nullptr || k == nullptr || desc == nullptr) return 0;
   return bwd_workspace(q->size[0], q->size[1], q->size[2], k->size[2], q->size[3], k->size[3], q->size[4], canonical_mask(desc->mask),
-                       desc->window).total;
+                       clamp_window(desc->window, q->size[3], k->size[3])).total;
 }
 
 int fl_bwd_supported(const fl_variant_desc* desc, int dtype, int D, int Dv) {
@@ -594,7 +601,7 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   if ((mask & FL_MASK_DOC) && (aux->q_doc_ids == nullptr || aux->kv_doc_ids == nullptr))
     return fail(FL_ERR_AUX_MISSING, "q_doc_ids / kv_doc_ids");
   if (no_rows && no_keys) return FL_OK;
-  const BwdWorkspace wsz = bwd_workspace(B, G, H, Hkv, Sq, Sk, D, mask, desc->window);
+  const BwdWorkspace wsz = bwd_workspace(B, G, H, Hkv, Sq, Sk, D, mask, clamp_window(desc->window, Sq, Sk));
   if (aux->workspace == nullptr || aux->workspace_bytes < wsz.total)
     return fail(FL_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", wsz.total, aux->workspace ? aux->workspace_bytes : (size_t)0);
   if (((uintptr_t)aux->workspace) % 16 != 0) return fail(FL_ERR_ALIGN, "workspace not 16-byte aligned");
@@ -623,7 +630,7 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   p.q_doc = aux->q_doc_ids;
   p.kv_doc = aux->kv_doc_ids;
   p.B = (int)B; p.G = (int)G; p.H = (int)H; p.Hkv = (int)Hkv; p.Sq = (int)Sq; p.Sk = (int)Sk;
-  p.window = desc->window;
+  p.window = clamp_window(desc->window, Sq, Sk);
   p.prefix = desc->prefix_len;
   p.scale = desc->scale;
   p.softcap = desc->softcap;
@@ -782,7 +789,7 @@ fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_
   p.B = (int)B; p.H = (int)H; p.Hkv = (int)Hkv; p.nsplit = ns;
   p.max_len = kv->max_seq_len;
   p.num_pages = (int)pages;
-  p.window = (mask & FL_MASK_WINDOW) ? desc->window : -1;
+  p.window = (mask & FL_MASK_WINDOW) ? clamp_window(desc->window, kv->max_seq_len, kv->max_seq_len) : -1;
   p.scale = desc->scale;
   p.softcap = desc->softcap;
   hipStream_t stream = (hipStream_t)stream_v;

@@ -115,7 +115,9 @@ decode_kernel(const DecodeParams p) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       if (p.block_table != nullptr) {
-        const int j = min(t * BN + (u << p.page_shift), len - 1);           // first token of the tile's u-th page, clamped
+        // first token of the tile's u-th page, clamped into the sequence; never below token 0, although
+        // only workgroups that own a tile (so len >= 1) look anything up
+        const int j = max(min(t * BN + (u << p.page_shift), len - 1), 0);
         r.pg[u] = min(max(p.block_table[(int64_t)b * p.table_stride + (j >> p.page_shift)], 0), p.num_pages - 1);
       } else {
         r.pg[u] = b;
@@ -133,8 +135,8 @@ decode_kernel(const DecodeParams p) {
       const int dst_row = inst * C::RPI + lane / (D / 8);
       const int chunk = (lane % (D / 8)) ^ swz_u<D>(dst_row);
       // the rows of one instruction share a page, so its index is uniform
-      const int j_first = min(t * BN + inst * C::RPI, len - 1);
-      const int j = min(t * BN + dst_row, len - 1);
+      const int j_first = max(min(t * BN + inst * C::RPI, len - 1), 0);
+      const int j = max(min(t * BN + dst_row, len - 1), 0);
       int64_t page, off;
       if (p.block_table != nullptr) {
         const int u = (j_first >> p.page_shift) - tile_page0;                // 0..3, uniform
@@ -158,7 +160,9 @@ decode_kernel(const DecodeParams p) {
     if (t_issue < t_end) load_tile(t_issue, s, lookup(t_issue));
     t_issue += C::NWV;
   }
-  Pages next_pages = lookup(t_issue < t_end ? t_issue : t_begin);            // of the next tile to request
+  // pages of the next tile to request (a workgroup without tiles, e.g. of an empty sequence, looks nothing up)
+  Pages next_pages = {{0, 0, 0, 0}};
+  if (t_begin < t_end) next_pages = lookup(t_issue < t_end ? t_issue : t_begin);
   int stage = 0;
   for (int t = t_begin + wave; t < t_end; t += C::NWV) {
     const int stage_ld = stage == 0 ? C::NSTG - 1 : stage - 1;      // the stage the previous tile used

@@ -184,7 +184,7 @@ fl_status fl_attn_fwd_custom(fl_custom_variant* v, const fl_tensor* q, const fl_
   p.B = (int)B; p.G = (int)G; p.H = (int)H; p.Hkv = (int)Hkv; p.Sq = (int)Sq; p.Sk = (int)Sk;
   p.D = (int)D; p.Dv = (int)D;
   p.scale = scale;
-  p.window = window;
+  p.window = (int64_t)window > (Sq > Sk ? Sq : Sk) ? (int32_t)(Sq > Sk ? Sq : Sk) : window;   // keeps i - window clear of int32 overflow
   p.prefix = prefix_len;
   p.out_f32 = out->dtype == FL_F32;
   p.n_qtiles = (int)((Sq + kBM - 1) / kBM);

@@ -27,6 +27,27 @@ def _as5(x: torch.Tensor) -> torch.Tensor:
     return x
 
 
+def _check_aux(name: str, t: Optional[torch.Tensor], dtype: torch.dtype, shape, device, *, contiguous: bool = True,
+               inner_unit: bool = False) -> None:
+    """The C ABI reads these arrays as raw int32 / float32 memory of a fixed shape: anything else
+    (torch's default int64 ids, a sliced view, a tensor on another device) would be reinterpreted
+    silently, so it is refused here."""
+    if t is None:
+        return
+    if not isinstance(t, torch.Tensor):
+        raise ValueError(f"{name} must be a torch.Tensor")
+    if t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    if t.device != device:
+        raise ValueError(f"{name} is on {t.device}, expected {device}")
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+    if contiguous and not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if inner_unit and t.dim() >= 2 and t.shape[-1] > 1 and t.stride(-1) != 1:
+        raise ValueError(f"{name} must have unit stride along its last axis")
+
+
 def _desc(scale, causal, window, prefix, softcap, alibi_slopes, q_doc_ids):
     mask = 0
     if causal:
@@ -101,6 +122,12 @@ def attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, scale: Optio
         scale = q.shape[-1] ** -0.5
     if q_doc_ids is not None and kv_doc_ids is None:
         kv_doc_ids = q_doc_ids
+    if kv_doc_ids is not None and q_doc_ids is None:
+        raise ValueError("kv_doc_ids needs q_doc_ids")
+    q5, k5 = _as5(q), _as5(k)
+    _check_aux("alibi_slopes", alibi_slopes, torch.float32, (q5.shape[2],), q.device)
+    _check_aux("q_doc_ids", q_doc_ids, torch.int32, (q5.shape[0], q5.shape[3]), q.device)
+    _check_aux("kv_doc_ids", kv_doc_ids, torch.int32, (k5.shape[0], k5.shape[3]), q.device)
     return _Attention.apply(q, k, v, scale, causal, window, prefix, softcap, alibi_slopes, q_doc_ids, kv_doc_ids)
 
 
@@ -123,6 +150,13 @@ def decode_attention(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tens
         raise ValueError("decode_attention() takes a bf16 CUDA q of shape [B, H, D]")
     B, H, D = q.shape
     page_size = k_cache.shape[1]
+    _check_aux("seq_lens", seq_lens, torch.int32, (B,), q.device)
+    if block_table is not None:
+        if block_table.dim() != 2:
+            raise ValueError("block_table must be [B, max_pages]")
+        _check_aux("block_table", block_table, torch.int32, (B, block_table.shape[1]), q.device, contiguous=False,
+                   inner_unit=True)
+    _check_aux("alibi_slopes", alibi_slopes, torch.float32, (H,), q.device)
     if max_seq_len is None:
         max_seq_len = (block_table.shape[1] if block_table is not None else 1) * page_size
     if scale is None:

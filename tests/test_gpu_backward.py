@@ -200,3 +200,25 @@ def test_large_logits_backward(D):
     w = inputs.causal_bf16(B=1, H=4, Hkv=2, S=400, D=D)
     w.q = w.q * 16.0
     compare(w, label=f"large logits D={D}")
+
+
+def test_unbounded_window_equals_causal():
+    """window = INT_MAX (the usual "no limit" value) is the causal mask: the host cuts the window to the
+    sequence length, so no kernel forms i - window or j + window beyond int32.  Forward, dq, dk and dv
+    have to equal the causal result (dk / dv came out as zeros when the key-side query range overflowed)."""
+    import dataclasses
+    import torch
+    w = inputs.causal_bf16(B=1, H=2, S=300, D=64)
+    ww = dataclasses.replace(w, window=2 ** 31 - 1, name="window_intmax")
+    compare(ww, "f32", label="window_intmax_d64")
+    dout = inputs.dout_for(w)
+    res = []
+    for x in (w, ww):
+        db = runner.upload_backward(x, dout, grad_dtype="f32")
+        db.fwd.run_checked()
+        db.run_checked()
+        torch.cuda.synchronize()
+        res.append([t.float().cpu().numpy() for t in (db.fwd.out, db.dq, db.dk, db.dv)])
+    for a, b in zip(*res):
+        assert np.max(np.abs(a - b)) <= 1e-2 * max(1.0, float(np.max(np.abs(a))))
+    assert float(np.max(np.abs(res[1][2]))) > 0 and float(np.max(np.abs(res[1][3]))) > 0

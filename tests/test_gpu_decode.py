@@ -184,3 +184,21 @@ def test_table_entries_outside_the_cache_are_cut_to_it():
     got = dd.out.float().cpu().numpy()[:, 0, :, 0]
     ref, _ = do.decode_attention(w.q, w.k_cache, w.v_cache, cut, w.seq_lens, scale=w.scale)
     assert np.max(np.abs(got - ref)) <= 1e-2
+
+
+def test_all_sequences_empty_without_table_columns():
+    """max_seq_len = 0 with a block table that has no columns (table_stride = 0): no workgroup owns a
+    tile, so nothing may be looked up in the table; every output is 0 and every lse is -inf."""
+    import torch
+    from paper_2511_02043_amd import binding as fb
+    w = inputs.decode_bf16(H=4, Hkv=2, D=64, page_size=16, seq_lens=[0, 0, 0])
+    dd = runner.upload_decode(w)
+    empty_table = torch.empty((3, 0), dtype=torch.int32, device="cuda:0")
+    kv = fb.paged_kv(block_table=dd.keep[0], page_size=16, seq_lens=dd.keep[1], max_seq_len=0)
+    kv.block_table = empty_table.data_ptr() or dd.keep[0].data_ptr()   # a zero-size tensor may have no storage
+    kv.table_stride = 0
+    dd.out.fill_(float("nan"))
+    dd.lse.fill_(float("nan"))
+    fb.check(fb.fl_attn_decode(dd.tq, dd.tk, dd.tv, kv, dd.desc, dd.aux, dd.tout, dd.tlse))
+    torch.cuda.synchronize()
+    assert bool((dd.out == 0).all()) and bool(torch.isneginf(dd.lse).all())

@@ -90,3 +90,31 @@ def test_decode_wrapper_matches_oracle():
     assert np.all(np.abs(out2.float().cpu().numpy() - ref) <= 1e-2 + 2.0 ** -8 * np.abs(ref))
     with pytest.raises(ValueError):
         decode_attention(q, kc, vc, lens, table, workspace=torch.empty(8, dtype=torch.uint8, device=dev))
+
+
+def test_wrapper_refuses_arrays_the_abi_would_misread():
+    """int64 document ids (torch's default integer type), sliced id views, slopes on the CPU and
+    int64 lengths would be reinterpreted as int32 / float32 memory by the C ABI: the wrapper raises."""
+    import torch
+    from paper_2511_02043_amd.functional import attention, decode_attention
+    dev = "cuda:0"
+    q = torch.zeros(2, 4, 64, 64, dtype=torch.bfloat16, device=dev)
+    ids = torch.zeros(2, 64, dtype=torch.int64, device=dev)
+    with pytest.raises(ValueError):
+        attention(q, q, q, q_doc_ids=ids)
+    with pytest.raises(ValueError):
+        attention(q, q, q, q_doc_ids=torch.zeros(2, 128, dtype=torch.int32, device=dev)[:, ::2])
+    with pytest.raises(ValueError):
+        attention(q, q, q, alibi_slopes=torch.ones(4))
+    with pytest.raises(ValueError):
+        attention(q, q, q, alibi_slopes=torch.ones(3, device=dev))
+    kc = torch.zeros(8, 16, 2, 64, dtype=torch.bfloat16, device=dev)
+    with pytest.raises(ValueError):
+        decode_attention(q[:, :, 0], kc, kc, torch.tensor([3, 4], device=dev),
+                         torch.zeros(2, 4, dtype=torch.int32, device=dev))
+    with pytest.raises(ValueError):
+        decode_attention(q[:, :, 0], kc, kc, torch.tensor([3, 4], dtype=torch.int32, device=dev),
+                         torch.zeros(2, 4, dtype=torch.int64, device=dev))
+    # the accepted forms still run
+    out = attention(q, q, q, q_doc_ids=ids.to(torch.int32))
+    assert out.shape == q.shape
