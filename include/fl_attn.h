@@ -146,6 +146,22 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
 size_t fl_attn_fwd_workspace_size(const fl_tensor* q, const fl_tensor* k,
                                   const fl_variant_desc* desc);
 
+/* fl_attn_fwd for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments, same kernels, same results, but the
+ * tile skipper's document-id summaries (the only scratch of the forward pass, FL_MASK_DOC) go to a
+ * buffer built into the library, 1 MiB per GPU, instead of aux->workspace; aux->workspace and
+ * aux->workspace_bytes are ignored.  The call allocates and frees nothing.
+ *
+ *   limit   B * (ceil(Sq / 32) + ceil(Sk / 32)) * 8 bytes <= 1 MiB (e.g. B * (Sq + Sk) <= 4 Mi tokens);
+ *           beyond it FL_ERR_WORKSPACE and nothing is launched.
+ *   sharing every call on a GPU uses that GPU's one buffer: two such calls whose kernels may overlap
+ *           in time (different streams, different host threads) race on it; calls on one stream are safe.
+ *           The buffer is rewritten by every call, nothing in it has to be cleared in between.
+ * Variants without FL_MASK_DOC need no scratch and behave exactly like fl_attn_fwd.          */
+fl_status fl_attn_fwd_noalloc(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v,
+                              const fl_variant_desc* desc, const fl_aux* aux,
+                              fl_tensor* out, fl_tensor* lse, void* stream);
+
 /* Gradient of fl_attn_fwd with respect to q, k and v, for the variants without bias, second
  * stream and epilogue (score_mod and every mask are covered).  The paper's conclusion names
  * training support as the extension it leaves open; this is the derivative of Eq. 3 with the

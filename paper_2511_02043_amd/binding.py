@@ -75,6 +75,8 @@ def lib() -> C.CDLL:
         L.fl_attn_fwd.restype = C.c_int
         L.fl_attn_fwd.argtypes = [TP, TP, TP, C.POINTER(fl_variant_desc), C.POINTER(fl_aux), TP, TP,
                                   C.c_void_p]
+        L.fl_attn_fwd_noalloc.restype = C.c_int
+        L.fl_attn_fwd_noalloc.argtypes = L.fl_attn_fwd.argtypes
         L.fl_attn_fwd_workspace_size.restype = C.c_size_t
         L.fl_attn_fwd_workspace_size.argtypes = [TP, TP, C.POINTER(fl_variant_desc)]
         L.fl_attn_bwd.restype = C.c_int
@@ -109,7 +111,7 @@ def lib() -> C.CDLL:
     return _lib
 
 
-EXPORTS = ["fl_attn_fwd", "fl_attn_fwd_workspace_size", "fl_attn_bwd", "fl_attn_bwd_workspace_size",
+EXPORTS = ["fl_attn_fwd", "fl_attn_fwd_noalloc", "fl_attn_fwd_workspace_size", "fl_attn_bwd", "fl_attn_bwd_workspace_size",
            "fl_bwd_supported", "fl_attn_decode", "fl_attn_decode_workspace_size", "fl_compile_variant", "fl_attn_fwd_custom",
            "fl_release_variant", "fl_variant_supported", "fl_strerror",
            "fl_last_error_detail", "fl_set_tuning", "fl_version"]
@@ -173,6 +175,13 @@ def fl_attn_fwd(q: fl_tensor, k: fl_tensor, v: fl_tensor, desc: fl_variant_desc,
     """Raw call; returns the fl_status code."""
     return lib().fl_attn_fwd(_ref(q), _ref(k), _ref(v), _ref(desc), _ref(aux), _ref(out), _ref(lse),
                              C.c_void_p(stream))
+
+
+def fl_attn_fwd_noalloc(q: fl_tensor, k: fl_tensor, v: fl_tensor, desc: fl_variant_desc, aux: Optional[fl_aux],
+                        out: fl_tensor, lse: Optional[fl_tensor], stream: int = 0) -> int:
+    """Raw call; returns the fl_status code.  aux.workspace is ignored (the library's built-in scratch is used)."""
+    return lib().fl_attn_fwd_noalloc(_ref(q), _ref(k), _ref(v), _ref(desc), _ref(aux), _ref(out), _ref(lse),
+                                     C.c_void_p(stream))
 
 
 def fl_attn_fwd_workspace_size(q: fl_tensor, k: fl_tensor, desc: fl_variant_desc) -> int:

@@ -6,6 +6,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 #include "../../include/fl_attn.h"
 #include "fl_bwd_registry.hpp"
@@ -19,6 +20,12 @@ static_assert(FL_MASK_CAUSAL == fl::kMaskCausal && FL_MASK_WINDOW == fl::kMaskWi
 static_assert(FL_MOD_NONE == fl::kModNone && FL_MOD_ALIBI == fl::kModAlibi && FL_MOD_SOFTCAP == fl::kModSoftcap,
               "score_mod values");
 static_assert(FL_EPI_RMSNORM == fl::kEpiRms && FL_EPI_GATE_SIGMOID == fl::kEpiGate, "epilogue bits");
+
+// Built-in scratch of fl_attn_fwd_noalloc: the tile skipper's document-id summaries live here instead
+// of in a caller-supplied workspace.  One copy per GPU, held until the process ends.  In host code
+// the array's name is only a handle for hipGetSymbolAddress; kernels get the device address it returns.
+constexpr size_t kScratchBytes = 1u << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 namespace {
 
@@ -528,6 +535,49 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   hipError_t e = ke->launch(p, (int)nblocks, stream);
   if (e != hipSuccess) return fail(FL_ERR_LAUNCH, "kernel launch: %s", hipGetErrorString(e));
   return FL_OK;
+}
+
+// Device address of this GPU's copy of `scratch`, looked up once per device with that device current.
+static fl_status scratch_address(void** out) {
+  static std::mutex mu;
+  static void* ptrs[64];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= 64) return fail(FL_ERR_LAUNCH, "hipGetDevice: %s", hipGetErrorString(e));
+  std::lock_guard<std::mutex> lock(mu);
+  if (ptrs[dev] == nullptr) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || ptr == nullptr)
+      return fail(FL_ERR_LAUNCH, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+    ptrs[dev] = ptr;
+  }
+  *out = ptrs[dev];
+  return FL_OK;
+}
+
+fl_status fl_attn_fwd_noalloc(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v, const fl_variant_desc* desc,
+                              const fl_aux* aux, fl_tensor* out, fl_tensor* lse, void* stream_v) {
+  g_detail[0] = 0;
+  fl_status st = check_desc(desc);
+  if (st != FL_OK) return st;
+  if (q == nullptr || k == nullptr) return fail(FL_ERR_NULL, "q or k is NULL");
+  const size_t need = workspace_bytes(q->size[0], q->size[3], k->size[3], canonical_mask(desc->mask));
+  // variants without a workspace, and calls that fl_attn_fwd refuses for their aux block anyway
+  if (need == 0 || aux == nullptr || aux->struct_size != sizeof(fl_aux))
+    return fl_attn_fwd(q, k, v, desc, aux, out, lse, stream_v);
+  if (q->size[0] < 0 || q->size[3] < 0 || k->size[3] < 0) return fail(FL_ERR_SHAPE, "negative size");
+  if (need > kScratchBytes)
+    return fail(FL_ERR_WORKSPACE,
+                "the document-id summaries of this call need %zu bytes, the built-in scratch buffer holds %zu "
+                "(B * (ceil(Sq / 32) + ceil(Sk / 32)) <= %zu); use fl_attn_fwd with a workspace",
+                need, kScratchBytes, kScratchBytes / sizeof(int2));
+  void* ptr = nullptr;
+  if ((st = scratch_address(&ptr)) != FL_OK) return st;
+  fl_aux a = *aux;
+  a.workspace = ptr;
+  a.workspace_bytes = kScratchBytes;
+  return fl_attn_fwd(q, k, v, desc, &a, out, lse, stream_v);
 }
 
 size_t fl_attn_bwd_workspace_size(const fl_tensor* q, const fl_tensor* k, const fl_variant_desc* desc) {

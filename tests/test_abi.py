@@ -218,3 +218,17 @@ def test_custom_variant_compiles_without_a_gpu_and_reports_errors():
     assert st == fb.FL_OK
     fb.fl_release_variant(h2)
     assert fb.fl_compile_variant("s", None, 32)[0] == fb.FL_ERR_UNSUPPORTED
+
+
+def test_noalloc_entry_point_rejects_sizes_beyond_its_built_in_buffer():
+    """fl_attn_fwd_noalloc checks the size of the document-id summaries against its 1 MiB buffer before
+    any HIP call (the pointers below are never used)."""
+    d = fb.variant_desc(scale=0.125, mask=fb.FL_MASK_DOC)
+    t = fb.fl_tensor()
+    t.ptr = 4096
+    t.dtype = fb.FL_BF16
+    t.size[:] = [64, 1, 1, 1 << 20, 64]
+    t.stride[:] = [1 << 26, 1 << 26, 1 << 26, 64, 1]
+    assert fb.fl_attn_fwd_noalloc(t, t, t, d, fb.aux_desc(), t, None) == fb.FL_ERR_WORKSPACE
+    assert "scratch" in fb.fl_last_error_detail()
+    assert fb.fl_attn_fwd_noalloc(t, t, t, None, None, t, None) == fb.FL_ERR_NULL
