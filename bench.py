@@ -46,6 +46,7 @@ def make_workload(name):
     raise SystemExit(f"unknown config {name!r}")
 
 
+HBM_BOUND = ("c3c_window_doc", "c5_evoformer")    # configurations whose roofline is HBM bandwidth (algorithmic bytes)
 CONFIGS = ["c2_d128", "c2_d64", "c3a_alibi", "c3b_softcap", "c3c_window_doc", "c4_differential", "c5_evoformer"]
 
 
@@ -93,15 +94,19 @@ def flops_and_bytes(w):
     return flops, byt
 
 
-def time_config(name, steps, warmup, out_dtype="same", rotate=1):
+def time_config(name, steps, warmup, out_dtype="same", rotate=1, before=None):
     """rotate > 1: cycle over that many independent copies of every buffer, so that a workload
-    smaller than the 256 MB Infinity Cache is timed from HBM ("cold") rather than from cache."""
+    smaller than the 256 MB Infinity Cache is timed from HBM ("cold") rather than from cache.
+    before: called once the inputs are resident, right before the warm-up steps (the reference
+    measurements of the default run: no idle gap between them and the timed region)."""
     import torch
     from paper_2511_02043_amd import runner
     w = make_workload(name)
     flops, byt = flops_and_bytes(w)
     dws = [runner.upload(w, out_dtype=out_dtype) for _ in range(rotate)]
     stream = torch.cuda.current_stream().cuda_stream
+    if before is not None:
+        before()
     for n in range(warmup):
         dws[n % rotate].run_checked(stream)
     torch.cuda.synchronize()
@@ -127,10 +132,11 @@ def time_config(name, steps, warmup, out_dtype="same", rotate=1):
                      std=float(one.std()))
     return dict(config=name, flops=flops, bytes=byt, ms_per_step=wall_ms, kernel_ms=ev_ms, launch_us=launch_us,
                 tflops=flops / (wall_ms * 1e-3) / 1e12, kernel_tflops=flops / (ev_ms * 1e-3) / 1e12,
-                gbs=byt / (ev_ms * 1e-3) / 1e9, dims=w.dims), w
+                gbs=byt / (ev_ms * 1e-3) / 1e9, dims=w.dims, device_workload=dws[0]), w
 
 
-BWD_CONFIGS = ["c2_d128", "c2_d64", "c3a_alibi", "c3b_softcap", "c3c_window_doc"]
+BWD_HBM_BOUND = ("c3c_window_doc", "c5_evoformer")    # configurations whose roofline is HBM bandwidth (algorithmic bytes)
+CONFIGS = ["c2_d128", "c2_d64", "c3a_alibi", "c3b_softcap", "c3c_window_doc"]
 
 
 def time_backward(name, steps, warmup):
@@ -306,6 +312,146 @@ def gemm_reference(n=8192, reps=50):
     return 2.0 * n ** 3 * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12
 
 
+def _bench_lib():
+    """libflbench.so: the two measurement kernels of csrc/fl_bench_kernels.hip (no attention code)."""
+    import ctypes as C
+    path = os.path.join(ROOT, "paper_2511_02043_amd", "libflbench.so")
+    L = C.CDLL(path)
+    L.flb_mfma_peak.restype = C.c_double
+    L.flb_mfma_peak.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
+    L.flb_copy.restype = C.c_int
+    L.flb_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    return L
+
+
+def mfma_peak_reference(zero_data=False, blocks=2048, iters=4000, reps=10):
+    """TFLOP/s of a pure chain of v_mfma_f32_32x32x16_bf16 (two waves per SIMD, no memory traffic) on
+    pseudo-random operands: the peak the matrix cores reach on this board at the clock its power limit allows."""
+    import torch
+    L = _bench_lib()
+    sink = torch.empty(blocks * 512, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    for _ in range(3):
+        L.flb_mfma_peak(sink.data_ptr(), blocks, iters, int(zero_data), stream)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    flops = 0.0
+    for _ in range(reps):
+        f = L.flb_mfma_peak(sink.data_ptr(), blocks, iters, int(zero_data), stream)
+        if f < 0:
+            raise RuntimeError("flb_mfma_peak failed")
+        flops += f
+    e1.record()
+    torch.cuda.synchronize()
+    return flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
+def copy_reference(mib=1024, reps=10):
+    """GB/s (bytes read + bytes written) of a plain device copy kernel of `mib` MiB: the HBM reference."""
+    import torch
+    L = _bench_lib()
+    n = mib << 20
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
+    dst = torch.empty_like(src)
+    stream = torch.cuda.current_stream().cuda_stream
+    for _ in range(3):
+        L.flb_copy(dst.data_ptr(), src.data_ptr(), n, stream)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        if L.flb_copy(dst.data_ptr(), src.data_ptr(), n, stream) != 0:
+            raise RuntimeError("flb_copy failed")
+    e1.record()
+    torch.cuda.synchronize()
+    return 2.0 * n * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
+def _read_sysfs_power():
+    """(socket power in W, power cap in W) from the amdgpu hwmon files, or (None, None)."""
+    import glob
+    for d in glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*"):
+        try:
+            for name in ("power1_average", "power1_input"):
+                f = os.path.join(d, name)
+                if os.path.exists(f):
+                    cap = None
+                    if os.path.exists(os.path.join(d, "power1_cap")):
+                        cap = int(open(os.path.join(d, "power1_cap")).read()) / 1e6
+                    return int(open(f).read()) / 1e6, cap
+        except (OSError, ValueError):
+            continue
+    return None, None
+
+
+def _read_smi_clock():
+    """Mean shader clock in MHz over the gfx_N entries of `amd-smi metric -c --json` (and its socket power), or None."""
+    import subprocess
+    try:
+        out = subprocess.run(["amd-smi", "metric", "-p", "-c", "--json"], capture_output=True, text=True, timeout=10).stdout
+        data = json.loads(out[out.index("{"):])
+        g = data["gpu_data"][0] if "gpu_data" in data else data[0]
+        clks = [v["clk"]["value"] for k, v in g.get("clock", {}).items()
+                if k.startswith("gfx_") and isinstance(v, dict) and isinstance(v.get("clk"), dict)
+                and isinstance(v["clk"].get("value"), (int, float))]
+        pw = g.get("power", {}).get("socket_power", {})
+        pw = pw.get("value") if isinstance(pw, dict) else None
+        return (float(np.mean(clks)) if clks else None), (float(pw) if isinstance(pw, (int, float)) else None)
+    except Exception:
+        return None, None
+
+
+def sustained_power_clock(dw, flops, seconds=1.5, max_seconds=6.0):
+    """Runs the workload back to back for `seconds` (until the clock query has returned, at most
+    max_seconds) while a thread samples the socket power (hwmon, every 20 ms) and asks amd-smi once for
+    the shader clocks.  The clock cannot be pinned from user space: under this kernel the board sits at its
+    power limit and lowers the clock, so both numbers go into the record next to the throughput."""
+    import threading
+    import torch
+    stream = torch.cuda.current_stream().cuda_stream
+    samples, smi = [], {}
+    stop = threading.Event()
+
+    def sampler():
+        t0 = time.perf_counter()
+        asked = False
+        while not stop.is_set():
+            pw, cap = _read_sysfs_power()
+            if pw is not None:
+                samples.append((time.perf_counter() - t0, pw, cap))
+            if not asked and time.perf_counter() - t0 > 0.5:
+                asked = True
+                smi["clk"], smi["power"] = _read_smi_clock()
+                smi["done"] = True
+            time.sleep(0.02)
+
+    th = threading.Thread(target=sampler, daemon=True)
+    th.start()
+    t0 = time.perf_counter()
+    n = 0
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    while True:
+        for _ in range(50):
+            dw.run_checked(stream)
+        n += 50
+        torch.cuda.synchronize()
+        t = time.perf_counter() - t0
+        if (t >= seconds and smi.get("done")) or t >= max_seconds:
+            break
+    e1.record()
+    torch.cuda.synchronize()
+    stop.set()
+    th.join(timeout=15)
+    late = [pw for (t, pw, cap) in samples if t > 0.3]
+    cap = next((c for (_, _, c) in samples if c is not None), None)
+    return {"socket_power_w": float(np.mean(late)) if late else smi.get("power"),
+            "power_cap_w": cap, "sclk_mhz": smi.get("clk"), "sclk_max_mhz": 2400,
+            "launches": n, "tflops_sustained": flops * n / (e0.elapsed_time(e1) * 1e-3) / 1e12,
+            "source": "hwmon power1_input sampled every 20 ms; amd-smi metric -c once, both during a back-to-back run of the same launch"}
+
+
 def run_grid(steps, warmup):
     """The paper's benchmark grid (Sec. 4.1): every cell timed like the default workload."""
     import torch
@@ -429,6 +575,9 @@ def main():
                     help="time fl_attn_decode (64 sequences of 4k-8k cached tokens, 32 / 8 heads, D = 128, 16-token pages)")
     ap.add_argument("--no-gemm-reference", action="store_true",
                     help="skip the bf16 GEMM that shows what the matrix cores sustain on random data")
+    ap.add_argument("--rotate", type=int, default=1,
+                    help="cycle the timed launches over this many independent buffer sets (a workload smaller than the "
+                         "256 MB Infinity Cache is then timed from HBM)")
     ap.add_argument("--tune", default="", help="comma list key=value passed to fl_set_tuning (sweeps)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run a plain device-to-device copy of MIB MiB a few times (scale factor of the "
@@ -496,12 +645,26 @@ def main():
                           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "dtype": "bf16",
                           "data": "synthetic", "results": res}), flush=True)
         return
+    # Reference measurements (what the matrix cores and the HBM of this board sustain, in this run).  They
+    # run once the workload is resident, right before its warm-up steps: the board is then in its sustained
+    # power state, and the timed steps see the clock a long-running job sees rather than the transient of
+    # the first launches after an idle period (the host-side input generation is such a period).
+    refs = {}
+
+    def references():
+        if args.no_gemm_reference:
+            return
+        refs["mfma_only_bf16_zeros_tflops"] = mfma_peak_reference(zero_data=True, reps=4)
+        refs["device_copy_gb_per_s"] = copy_reference()
+        refs["gemm_bf16_random_tflops"] = gemm_reference()
+        refs["mfma_only_bf16_random_tflops"] = mfma_peak_reference()
     results = []
     if args.all:
         for name in CONFIGS:
             if name == args.config:
                 continue
             r, _ = time_config(name, args.steps, args.warmup)
+            r.pop("device_workload")
             results.append(r)
             print(f"# {name}: {r['kernel_ms']:.4f} ms  {r['kernel_tflops']:.1f} TFLOP/s  "
                   f"{100 * r['kernel_tflops'] / PEAK_BF16_TFLOPS:.1f}% of bf16 peak  {r['gbs']:.0f} GB/s",
@@ -509,11 +672,13 @@ def main():
             if r["bytes"] < 256e6 and name in ("c3c_window_doc", "c5_evoformer"):
                 # small enough to live in the Infinity Cache between calls: also time it from HBM
                 rc, _ = time_config(name, args.steps, args.warmup, rotate=6)
+                rc.pop("device_workload")
                 rc["config"] = name + "_cold"
                 results.append(rc)
                 print(f"# {name} over 6 rotating buffer sets: {rc['kernel_ms']:.4f} ms  {rc['gbs']:.0f} GB/s "
                       f"({100 * rc['gbs'] / PEAK_HBM_GBS:.1f}% of the HBM peak)", file=sys.stderr, flush=True)
-    r, w = time_config(args.config, args.steps, args.warmup)
+    r, w = time_config(args.config, args.steps, args.warmup, before=references, rotate=args.rotate)
+    dw0 = r.pop("device_workload")
     results.append(r)
     if args.all:
         os.makedirs(OUT_DIR, exist_ok=True)
@@ -530,14 +695,18 @@ def main():
         "value": r["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": args.config, **r["dims"], "variant": w.name, "out_dtype": "bf16",
+        "config": {"workload": args.config, **r["dims"], "variant": w.name, "out_dtype": "bf16", "buffer_sets": args.rotate,
                    "flops_per_step": r["flops"], "pct_of_bf16_mfma_peak": 100 * r["tflops"] / PEAK_BF16_TFLOPS,
                    "hbm_gb_per_s_algorithmic": r["gbs"], "single_launch_us": r["launch_us"]},
         "roofline": {"bound": "mfma", "achieved": r["kernel_tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": r["kernel_tflops"] / PEAK_BF16_TFLOPS, "traffic": traffic},
     }
+    if args.config in HBM_BOUND:                   # below the ridge of 315 FLOP per byte once masked tiles are skipped
+        line["roofline"] = {"bound": "hbm", "achieved": r["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                            "frac": r["gbs"] / PEAK_HBM_GBS, "traffic": traffic}
+    line["config"].update(refs)
     if not args.no_gemm_reference:
-        line["config"]["gemm_bf16_random_tflops"] = gemm_reference()
+        line["config"]["power_clock"] = sustained_power_clock(dw0, r["flops"])
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(line), flush=True)

@@ -35,7 +35,7 @@ using fl::host::g_detail;
 using fl::host::make_view;
 
 struct Tuning {
-  int bm = 0, bn = 0, rb = 0, nw = 0, wpe = 0, order = -1, pair = -1;
+  int bm = 0, bn = 0, rb = 0, nw = 0, wpe = 0, ring = 0, order = -1, pair = -1;
   int decode_splits = 0;           // 0: chosen by decode_splits() from the shapes
   int bwd_wg_target = 0;           // 0: the default of choose_hsplit
 } g_tuning;
@@ -98,6 +98,7 @@ const fl::KernelEntry* find_entry(const fl_variant_desc* d, int dtype, int D, in
   const fl::KernelEntry* best = nullptr;
   const fl::KernelEntry* short_loop = nullptr;    // the variant's 32-key-tile shape at three or four waves per SIMD, if listed
   const fl::KernelEntry* four_waves = nullptr;    // a 4-wave, one-row-block shape of the variant (128 query rows per workgroup)
+  const fl::KernelEntry* deep_ring = nullptr;     // the default shape with four-slot K / V rings (a barrier per two tiles)
   for (int t = 0; t < 5; ++t)
     for (int e = 0; e < r.n[t]; ++e) {
       const fl::KernelEntry& k = r.tab[t][e];
@@ -114,16 +115,17 @@ const fl::KernelEntry* find_entry(const fl_variant_desc* d, int dtype, int D, in
       auto wanted = [](const fl::KernelEntry& e) {
         return (g_tuning.bm == 0 || e.bm == g_tuning.bm) && (g_tuning.bn == 0 || e.key.bn == g_tuning.bn) &&
                (g_tuning.rb == 0 || e.key.rb == g_tuning.rb) && (g_tuning.nw == 0 || e.key.nwaves == g_tuning.nw) &&
-               (g_tuning.wpe == 0 || e.key.wpe == g_tuning.wpe);
+               (g_tuning.wpe == 0 || e.key.wpe == g_tuning.wpe) && (g_tuning.ring == 0 || e.key.ring == g_tuning.ring);
       };
       if (best == nullptr || (wanted(k) && !wanted(*best))) best = &k;
       if (short_loop == nullptr && k.key.bn == 32 && k.key.wpe >= 3) short_loop = &k;
       if (four_waves == nullptr && k.key.nwaves == 4 && k.key.rb == 1 && k.key.wpe == 2) four_waves = &k;
+      if (deep_ring == nullptr && k.key.ring == 4) deep_ring = &k;
     }
   // Short key loops: start-up and drain of a workgroup weigh more than the per-tile cost, and four
   // small workgroups per CU hide them better than two large ones (measured on the paper's grid at
   // head dim 64; the crossover is at a few dozen key tiles per query tile).
-  const bool tuned = g_tuning.bm || g_tuning.bn || g_tuning.rb || g_tuning.nw || g_tuning.wpe;
+  const bool tuned = g_tuning.bm || g_tuning.bn || g_tuning.rb || g_tuning.nw || g_tuning.wpe || g_tuning.ring;
   // (it needs a launch that fills the CUs four workgroups deep: on a small launch the fewer, larger tiles win)
   const bool known = heads > 0 && Sq > 0;
   if (!tuned && best != nullptr && short_loop != nullptr && Sk > 0 && Sk <= (mask == 0 ? 4096 : 2048) &&
@@ -135,6 +137,13 @@ const fl::KernelEntry* find_entry(const fl_variant_desc* d, int dtype, int D, in
   else if (!tuned && best != nullptr && four_waves != nullptr && best->bm == 256 && known &&
            heads * ((Sq + 255) / 256) < (mask == 0 ? 512 : 1024))
     best = four_waves;
+  // Long key loops at the default shape: with four ring slots the workgroup meets at a barrier once per two
+  // tiles, which measured 1.7 % faster on the causal S = 8192 benchmark shape; short loops would only pay the
+  // longer prologue (three K tiles and two V tiles in flight before the first contraction).
+  if (!tuned && best != nullptr && deep_ring != nullptr && best->key.ring == 2 && best->key.nwaves == deep_ring->key.nwaves &&
+      best->key.rb == deep_ring->key.rb && best->key.bn == deep_ring->key.bn && best->key.wpe == deep_ring->key.wpe &&
+      Sk >= 2048)
+    best = deep_ring;
   return best;
 }
 
@@ -317,6 +326,7 @@ fl_status fl_set_tuning(const char* key, int value) {
   else if (!strcmp(key, "rb")) g_tuning.rb = value;
   else if (!strcmp(key, "nw")) g_tuning.nw = value;
   else if (!strcmp(key, "wpe")) g_tuning.wpe = value;
+  else if (!strcmp(key, "ring")) g_tuning.ring = value;
   else if (!strcmp(key, "order")) g_tuning.order = value == 0 ? -1 : value - 1;
   else if (!strcmp(key, "pair")) g_tuning.pair = value == 0 ? -1 : value - 1;
   else if (!strcmp(key, "decode_splits")) g_tuning.decode_splits = value;

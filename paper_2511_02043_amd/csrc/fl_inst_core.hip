@@ -4,9 +4,11 @@
 namespace fl {
 #define E(D, NW, RB, BN, WPE, MASK) bf16_entry<D, D, NW, RB, BN, WPE, kModNone, MASK, 0, false, 0>()
 #define BOTH(D, NW, RB, BN, WPE) E(D, NW, RB, BN, WPE, 0), E(D, NW, RB, BN, WPE, kMaskCausal)
+#define R4(D, NW, RB, BN, WPE, MASK) bf16_entry<D, D, NW, RB, BN, WPE, kModNone, MASK, 0, false, 0, 4>()
+#define BOTH4(D, NW, RB, BN, WPE) R4(D, NW, RB, BN, WPE, 0), R4(D, NW, RB, BN, WPE, kMaskCausal)
 static const KernelEntry kEntries[] = {
     // first entry of a head dim = default shape; the others are selectable with fl_set_tuning
-    BOTH(128, 8, 1, 64, 2), BOTH(128, 4, 1, 64, 2), BOTH(128, 4, 2, 32, 1),
+    BOTH(128, 8, 1, 64, 2), BOTH4(128, 8, 1, 64, 2), BOTH(128, 4, 1, 64, 2), BOTH(128, 4, 2, 32, 1),
     // D = 64, long key loops: two row blocks per wave on 32-key tiles (every K / V fragment read from LDS feeds
     // two MFMAs; 225 registers, two waves per SIMD) measured 2 - 4 % faster than one row block on 64-key tiles.
     // (64, 4, 1, 32, 4): 32-key tiles at four waves per SIMD, four resident workgroups per CU: the host picks
@@ -15,6 +17,8 @@ static const KernelEntry kEntries[] = {
     BOTH(32, 4, 1, 64, 2),  BOTH(32, 4, 2, 64, 2),
 };
 #undef BOTH
+#undef BOTH4
+#undef R4
 #undef E
 const KernelEntry* entries_core(int* n) {
   *n = (int)(sizeof(kEntries) / sizeof(kEntries[0]));

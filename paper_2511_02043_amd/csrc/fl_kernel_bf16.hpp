@@ -93,7 +93,7 @@ __device__ __forceinline__ int swz_v(int r, int c) {
 }
 
 template <int D_, int DV_, int NWAVES_, int RB_, int BN_, int WPE_, int MOD_, uint32_t MASK_, int NBIAS_,
-          bool DIFF_, uint32_t EPI_>
+          bool DIFF_, uint32_t EPI_, int RING_ = 2>
 struct Bf16Cfg {
   static constexpr int D = D_, DV = DV_, NWAVES = NWAVES_, RB = RB_, BN = BN_, MOD = MOD_, NBIAS = NBIAS_;
   static constexpr uint32_t MASK = MASK_, EPI = EPI_;
@@ -118,7 +118,13 @@ struct Bf16Cfg {
   static constexpr int DVB = DV / 32;              // 32-channel blocks of the output
   static constexpr int K_BYTES = BN * D * 2;
   static constexpr int V_BYTES = BN * DV * 2;
-  static constexpr int RING = 2;                   // slots of the K ring and of the V ring
+  // Slots of the K ring and of the V ring.  The workgroup meets at a barrier once per RING / 2 tiles:
+  // a step reads K of the next tile and V of the current one while it streams K of the tile
+  // RING / 2 + 1 ahead and V of the tile RING / 2 ahead into slots that nobody reads before the next barrier.
+  static constexpr int RING = RING_;
+  static constexpr int SPB = RING / 2;             // pipeline steps (tiles) per barrier
+  static_assert(RING_ == 2 || RING_ == 4, "ring depth");
+  static_assert(RING_ == 2 || (NBIAS_ == 0 && !DIFF_), "bias staging and the two-stream loop wait for their loads every step");
   static constexpr int K_RING = 0;                 // LDS layout: K ring [RING][NS][K_BYTES], V ring [RING][V_BYTES]
   static constexpr int V_RING = RING * NS * K_BYTES;
   static constexpr int RING_BYTES = V_RING + RING * V_BYTES;
@@ -748,7 +754,8 @@ fwd_bf16_kernel(const FwdParams p) {
 #pragma unroll
     for (int d = 0; d < DVB; ++d) {
       const int ch = 32 * d + 16 * ((lane >> 4) & 1) + 4 * (s16 & 3);   // first of its 4 channels
-      w.va[d] = key0 * (DV * 2) + swz_v<DV>(key0, ch >> 3) * 16 + (ch & 7) * 2;
+      // (the ring's base is part of the address register, so that the immediate offsets of the reads stay below 64 KiB)
+      w.va[d] = C::V_RING + key0 * (DV * 2) + swz_v<DV>(key0, ch >> 3) * 16 + (ch & 7) * 2;
     }
   }
 
@@ -963,47 +970,63 @@ fwd_bf16_kernel(const FwdParams p) {
     typename W::Scores sa, sb;                     // the two score tiles in flight
     typename W::Pipe ps;
     typename W::BiasRegs br;
-    int t0 = next_tile(t_lo);
-    if (t0 < t_hi) {
+    // tl[0] is the current tile, tl[1] the next, ...; tl[SPB] is the tile whose V and tl[SPB + 1] the tile
+    // whose K the current step streams into the rings (t_hi past the end of the list)
+    constexpr int SPB = C::SPB, RING = C::RING, NTL = SPB + 2;
+    int tl[NTL];
+    tl[0] = next_tile(t_lo);
+    if (tl[0] < t_hi) {
       auto after = [&](int t) __attribute__((always_inline)) { return t < t_hi ? next_tile(t + 1) : t_hi; };
-      int t1 = after(t0), t2 = after(t1);
-      w.template bias_dma<0>(t0 * BN);
-      if (t1 < t_hi) w.template bias_dma<1>(t1 * BN);
-      load_k(t0, 0);
-      load_v(t0, 0);
-      if (t1 < t_hi) load_k(t1, 1);
+#pragma unroll
+      for (int u = 1; u < NTL; ++u) tl[u] = after(tl[u - 1]);
+      w.template bias_dma<0>(tl[0] * BN);
+      if (tl[1] < t_hi) w.template bias_dma<1>(tl[1] * BN);
+      // K of tiles tl[0 .. SPB] into slots 0 .. SPB, V of tiles tl[0 .. SPB - 1] into slots 0 .. SPB - 1
+      load_k(tl[0], 0);
+      load_v(tl[0], 0);
+#pragma unroll
+      for (int u = 1; u <= SPB; ++u) {
+        if (tl[u] < t_hi) load_k(tl[u], u);
+        if (u < SPB && tl[u] < t_hi) load_v(tl[u], u);
+      }
       wait_loads_and_sync();
-      w.template load_bias<0>(br, t0 * BN);
+      w.template load_bias<0>(br, tl[0] * BN);
       w.template qk<C::K_RING>(sa);
       if constexpr (C::NBIAS > 0) W::template wait_lds<0>();     // staged bias values have arrived
-      w.transform(sa, t0 * BN, br);
+      w.transform(sa, tl[0] * BN, br);
       float mx[RB];
-      bool full0 = wave_full(t0);
+      bool full0 = wave_full(tl[0]);
       if (full0) {
         w.rowmax(sa, mx);
         w.advance_max(mx);
       }
       __syncthreads();                             // everyone is done with K ring slot 0
       // uniform state of the tile stream: the ragged tile (if any) and the bases of the next K and
-      // V tile to fetch, i.e. of tiles min(t2, t_hi - 1) and min(t1, t_hi - 1)
+      // V tile to fetch, i.e. of tiles min(tl[SPB + 1], t_hi - 1) and min(tl[SPB], t_hi - 1)
       const int t_rag = p.Sk % BN != 0 ? p.Sk / BN : -1;
       const int64_t kstep[2] = {(int64_t)BN * kss[0], (int64_t)BN * kss[1]}, vstep = (int64_t)BN * vss;
       const unsigned char* kb[NS];
 #pragma unroll
-      for (int s = 0; s < NS; ++s) kb[s] = k_tile_base(s, t2 < t_hi ? t2 : t_hi - 1);
-      const unsigned char* vb = v_tile_base(t1 < t_hi ? t1 : t_hi - 1);
+      for (int s = 0; s < NS; ++s) kb[s] = k_tile_base(s, tl[SPB + 1] < t_hi ? tl[SPB + 1] : t_hi - 1);
+      const unsigned char* vb = v_tile_base(tl[SPB] < t_hi ? tl[SPB] : t_hi - 1);
       // One pipeline step.  cur / nxt hold the scores of the current / next tile.  Step number N
-      // (mod 4) fixes the roles at compile time: K and V of the current tile sit in ring slot
-      // N % 2, K of the next tile in the other one; the step streams K(t2) (both streams' tiles
-      // for the differential variant) into the slot K(t0) left in the previous step and V(t1)
-      // into the slot V(t-1) left.  These slots are free for the whole step, so the load
-      // instructions are spread over phase A (a burst of them right after the barrier stalls
-      // every wave of the workgroup in the memory pipeline while the matrix cores idle).  Past the
-      // end of the tile list the loads simply repeat the last tile, and the last tile takes the
-      // same step: its "next tile" contraction then runs on stale LDS contents and is never used.
+      // (mod 4) fixes the roles at compile time: tile number n of the list lives in ring slot
+      // n % RING, so V of the current tile sits in slot N % RING and K of the next tile in slot
+      // (N + 1) % RING; the step streams K of the tile SPB + 1 ahead (both streams' tiles for the
+      // differential variant) into slot (N + SPB + 1) % RING and V of the tile SPB ahead into slot
+      // (N + SPB) % RING.  Between two barriers (SPB steps) the slots read -- K: N + 1 .. N + SPB,
+      // V: N .. N + SPB - 1 -- and the slots written -- K: N + SPB + 1 .. N + 2 SPB, V: N + SPB ..
+      // N + 2 SPB - 1 -- are disjoint modulo RING = 2 SPB, and everything read was written before
+      // the previous barrier; so the waves only meet once per SPB tiles.  The load instructions
+      // are spread over phase A (a burst of them right after the barrier stalls every wave of the
+      // workgroup in the memory pipeline while the matrix cores idle).  Past the end of the tile
+      // list the loads simply repeat the last tile, and the last tile takes the same step: its
+      // "next tile" contraction then runs on stale LDS contents and is never used.
       auto step = [&](auto nc, typename W::Scores& cur, typename W::Scores& nxt) __attribute__((always_inline)) {
         constexpr int N = decltype(nc)::value;
-        constexpr int slot_c = N % 2, slot_n = (N + 1) % 2;   // ring slots of the current / next tile
+        constexpr int slot_vc = N % RING, slot_kn = (N + 1) % RING;            // read: V current, K next
+        constexpr int slot_kl = (N + SPB + 1) % RING, slot_vl = (N + SPB) % RING;   // written by this step's loads
+        const int t0 = tl[0], t1 = tl[1];
         const int tn = t1;
         const bool fulln = wave_full(t1);
         if (!full0) {                              // fully visible tiles were settled in phase B
@@ -1026,9 +1049,9 @@ fwd_bf16_kernel(const FwdParams p) {
           // first used behind the LDS waits of phase A, which cover these reads: LDS returns in
           // order); the tile after it is staged now into the buffer this frees
           if (tn < t_hi) w.template load_bias<(N + 1) % 2>(br, tn * BN);
-          if (t2 < t_hi) w.template bias_dma<N % 2>(t2 * BN);
+          if (tl[2] < t_hi) w.template bias_dma<N % 2>(tl[2] * BN);
         }
-        const int tk = t2 < t_hi ? t2 : t_hi - 1, tv = t1 < t_hi ? t1 : t_hi - 1;
+        const int tk = tl[SPB + 1] < t_hi ? tl[SPB + 1] : t_hi - 1, tv = tl[SPB] < t_hi ? tl[SPB] : t_hi - 1;
         if constexpr ((MASK & kMaskDoc) != 0) {    // tiles may be skipped: no fixed stride between them
 #pragma unroll
           for (int s = 0; s < NS; ++s) kb[s] = k_tile_base(s, tk);
@@ -1036,32 +1059,32 @@ fwd_bf16_kernel(const FwdParams p) {
         }
         if (__builtin_expect(tk == t_rag, 0)) clamp_k(tk);
         if (__builtin_expect(tv == t_rag, 0)) clamp_v(tv);
-        w.template phase_a<C::K_RING + slot_n * NS * C::K_BYTES>(
+        w.template phase_a<C::K_RING + slot_kn * NS * C::K_BYTES>(
             nxt, cur, ps, tn * BN, br, [&](auto fc) __attribute__((always_inline)) {
               constexpr int f = decltype(fc)::value, NF = NB * KK;
               constexpr int NK = NS * KPW, NV = VPW, LN = NK + NV;
               static_for<0, NK>([&](auto ic) __attribute__((always_inline)) {
                 constexpr int i = decltype(ic)::value, ss = i / KPW, u = i % KPW;
                 if constexpr (f == ((2 * i + 1) * NF) / (2 * LN))
-                  issue_k(ss, u, kb[ss], C::K_RING + (slot_c * NS + ss) * C::K_BYTES);
+                  issue_k(ss, u, kb[ss], C::K_RING + (slot_kl * NS + ss) * C::K_BYTES);
               });
               static_for<0, NV>([&](auto uc) __attribute__((always_inline)) {
                 constexpr int u = decltype(uc)::value;
                 if constexpr (f == ((2 * (NK + u) + 1) * NF) / (2 * LN))
-                  issue_v(u, vb, C::V_RING + slot_n * C::V_BYTES);
+                  issue_v(u, vb, C::V_RING + slot_vl * C::V_BYTES);
               });
             });
-        w.template phase_b<C::V_RING + slot_c * C::V_BYTES>(ps, cur, nxt, tn * BN, br, fulln);
-        wait_loads_and_sync();
-        t0 = t1;
-        t1 = t2;
-        t2 = t2 < t_hi ? next_tile(t2 + 1) : t_hi;
+        w.template phase_b<slot_vc * C::V_BYTES>(ps, cur, nxt, tn * BN, br, fulln);
+        if constexpr (N % SPB == SPB - 1) wait_loads_and_sync();
+#pragma unroll
+        for (int u = 0; u + 1 < NTL; ++u) tl[u] = tl[u + 1];
+        tl[NTL - 1] = tl[NTL - 1] < t_hi ? next_tile(tl[NTL - 1] + 1) : t_hi;
         full0 = fulln;
         if constexpr ((MASK & kMaskDoc) == 0) {    // consecutive tiles: advance the bases until the list ends
-          if (t1 < t_hi) vb += vstep;
+          if (tl[SPB] < t_hi) vb += vstep;
 #pragma unroll
           for (int s = 0; s < NS; ++s)
-            if (t2 < t_hi) kb[s] += kstep[s];
+            if (tl[SPB + 1] < t_hi) kb[s] += kstep[s];
         }
       };
       while (true) {
@@ -1071,11 +1094,14 @@ fwd_bf16_kernel(const FwdParams p) {
           if (!done) {
             if constexpr (N % 2 == 0) step(nc, sa, sb);
             else step(nc, sb, sa);
-            done = t0 >= t_hi;
+            done = tl[0] >= t_hi;
           }
         });
         if (done) break;
       }
+      // the loop may end between two barriers: this wave's last loads have to land, and every wave has to
+      // be done reading, before the rings are used again (second q-tile of a pair, epilogue exchange)
+      if constexpr (SPB > 1) wait_loads_and_sync();
     }
   }
 

@@ -143,7 +143,7 @@ def test_deterministic_run_to_run():
 
 
 @pytest.mark.parametrize("D,tune", [
-    (128, dict(nw=8, rb=1, bn=64)), (128, dict(nw=4, rb=1, bn=64)), (128, dict(nw=4, rb=2, bn=32)),
+    (128, dict(nw=8, rb=1, bn=64, ring=2)), (128, dict(nw=8, rb=1, bn=64, ring=4)), (128, dict(nw=4, rb=1, bn=64)), (128, dict(nw=4, rb=2, bn=32)),
     (64, dict(nw=8, rb=1)), (64, dict(nw=4, rb=1, bn=64)), (64, dict(nw=4, rb=1, bn=32, wpe=4)), (64, dict(nw=4, rb=2, bn=32)),
     (32, dict(nw=4, rb=1)), (32, dict(nw=4, rb=2)),
 ])
@@ -159,7 +159,24 @@ def test_every_compiled_kernel_shape(D, tune, order):
         run_and_compare(inputs.causal_bf16(B=1, H=8, S=300, Sk=650, D=D, causal=False),
                         label=f"plain D={D} {tune} order={order}")
     finally:
-        for k in ("nw", "rb", "bn", "wpe", "bm", "order"):
+        for k in ("nw", "rb", "bn", "wpe", "bm", "order", "ring"):
+            fb.fl_set_tuning(k, 0)
+
+
+@pytest.mark.parametrize("S,Sk,causal", [(257, 257, True), (300, 64, False), (300, 65, False), (900, 130, False),
+                                         (1500, 1500, True), (256, 4096 + 33, False)])
+def test_four_slot_ring_every_loop_length(S, Sk, causal):
+    """The four-slot K / V rings (one barrier per two key tiles): loops of one, two, three and many tiles,
+    odd and even tile counts, ragged last tiles, with the long + short q-tile pairing and without."""
+    from paper_2511_02043_amd import binding as fb
+    try:
+        fb.check(fb.fl_set_tuning("ring", 4))
+        for pair in (1, 2):
+            fb.check(fb.fl_set_tuning("pair", pair))
+            run_and_compare(inputs.causal_bf16(B=1, H=8, S=S, Sk=Sk, D=128, causal=causal),
+                            label=f"ring 4 S={S} Sk={Sk} causal={causal} pair={pair}")
+    finally:
+        for k in ("ring", "pair"):
             fb.fl_set_tuning(k, 0)
 
 
