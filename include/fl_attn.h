@@ -275,13 +275,15 @@ const char* fl_last_error_detail(void);
 
 /* Tuning knobs for benchmarking sweeps: choose a non-default kernel shape among the compiled
  * ones.  `key` is one of "bm" (query rows per workgroup), "bn" (keys per tile), "nw" (waves per
- * workgroup), "rb" (32-row blocks per wave), "wpe" (waves per SIMD the kernel is built for),
+ * workgroup), "rb" (32-row blocks per wave), "wpe" (waves per SIMD the kernel is built for), "ring" (slots of
+ * the K / V rings in LDS: 2 = a workgroup barrier per key tile, 4 = one per two tiles),
  * "order" (1 = plain, 2 = XCD-aware workgroup order), "pair" (1 = one q-tile per workgroup,
  * 2 = a long and a short q-tile per workgroup), "decode_splits" (key-range splits per sequence and
  * kv head of fl_attn_decode), "bwd_wg_target" (workgroups up to which fl_attn_bwd cuts a group of
  * query heads into subsets; both change the workspace size the matching *_workspace_size reports).
- * Value 0 restores the built-in choice.  Returns FL_OK or FL_ERR_UNSUPPORTED.  Not thread-safe
- * with respect to concurrent calls of the other entry points (everything else is).           */
+ * Value 0 restores the built-in choice.  Returns FL_OK or FL_ERR_UNSUPPORTED.  The requests are kept
+ * per host thread: they change the later calls of the calling thread only, so this call is as
+ * thread-safe as the others and no state is shared between threads.                          */
 fl_status fl_set_tuning(const char* key, int value);
 
 /* ABI version: major << 16 | minor. */

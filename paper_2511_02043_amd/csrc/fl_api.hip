@@ -34,11 +34,14 @@ using fl::host::fail;
 using fl::host::g_detail;
 using fl::host::make_view;
 
+// Shape requests of fl_set_tuning.  Per host thread: a request changes the calls of the thread that made it
+// and nothing else, so the entry points share no mutable state (the error detail is per thread as well).
 struct Tuning {
   int bm = 0, bn = 0, rb = 0, nw = 0, wpe = 0, ring = 0, order = -1, pair = -1;
   int decode_splits = 0;           // 0: chosen by decode_splits() from the shapes
   int bwd_wg_target = 0;           // 0: the default of choose_hsplit
-} g_tuning;
+};
+thread_local Tuning g_tuning;
 
 struct Registry {
   const fl::KernelEntry* tab[5];
@@ -145,6 +148,11 @@ const fl::KernelEntry* find_entry(const fl_variant_desc* d, int dtype, int D, in
       Sk >= 2048)
     best = deep_ring;
   return best;
+}
+
+// Head dims the bf16 kernel template can be instantiated for at run time.
+bool jit_dims_ok(int64_t D, int64_t Dv) {
+  return (D == 32 || D == 64 || D == 128) && (Dv == 32 || Dv == 64 || Dv == 128);
 }
 
 size_t workspace_bytes(int64_t B, int64_t Sq, int64_t Sk, uint32_t mask) {
@@ -338,7 +346,8 @@ fl_status fl_set_tuning(const char* key, int value) {
 int fl_variant_supported(const fl_variant_desc* desc, int dtype, int D, int Dv) {
   if (check_desc(desc) != FL_OK) return 0;
   if (dtype == FL_F32 && (D % 4 != 0 || Dv % 4 != 0 || D <= 0 || Dv <= 0)) return 0;
-  return find_entry(desc, dtype, D, Dv) != nullptr ? 1 : 0;
+  if (find_entry(desc, dtype, D, Dv) != nullptr) return 1;
+  return dtype == FL_BF16 && jit_dims_ok(D, Dv) ? 1 : 0;     // instantiated from the kernel template on first use
 }
 
 size_t fl_attn_fwd_workspace_size(const fl_tensor* q, const fl_tensor* k, const fl_variant_desc* desc) {
@@ -448,6 +457,15 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
     if (!empty && out->dtype != FL_F32) return fail(FL_ERR_DTYPE, "f32 inputs need f32 out");
   }
   const fl::KernelEntry* ke = find_entry(desc, dtype, (int)D, (int)Dv, Sk, B * G * H, Sq);
+  if (ke == nullptr && dtype == FL_BF16 && jit_dims_ok(D, Dv)) {
+    // not in the compiled table: the same kernel template, instantiated for this descriptor on first use
+    ke = fl::jit_forward_entry(fl::JitRequest{(int)D, (int)Dv, (int)desc->score_mod, mask, (int)desc->n_bias, diff, desc->epilogue});
+    if (ke == nullptr) {
+      char why[300];
+      snprintf(why, sizeof(why), "%s", g_detail);
+      return fail(FL_ERR_UNSUPPORTED, "run-time specialisation failed: %.290s", why);
+    }
+  }
   if (ke == nullptr)
     return fail(FL_ERR_UNSUPPORTED,
                 "no specialisation for dtype=%d D=%lld Dv=%lld score_mod=%u mask=0x%x n_bias=%u combine=%u epilogue=0x%x",
@@ -502,7 +520,7 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
     const int n_stage = p.bias[1].dma ? 2 : (p.bias[0].dma ? 1 : 0);       // biases 0 .. n_stage-1 get buffers
     const int64_t per_wave = (int64_t)n_stage * 2 * (32 * ke->key.rb * ke->key.bn * 2);
     const int64_t stage = ke->key.nwaves * per_wave;
-    const bool staged = n_stage > 0 && kv + stage <= fl::kMaxLdsBytes;
+    const bool staged = n_stage > 0 && kv + stage <= (ke->max_lds > 0 ? ke->max_lds : fl::kMaxLdsBytes);
     if (!staged) p.bias[0].dma = p.bias[1].dma = 0;
     p.bias_lds_base = (int)kv;
     p.bias_lds_wave = staged ? (int)per_wave : 0;
@@ -542,7 +560,7 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(FL_ERR_LAUNCH, "doc summary launch: %s", hipGetErrorString(e));
   }
-  hipError_t e = ke->launch(p, (int)nblocks, stream);
+  hipError_t e = ke->jit != nullptr ? fl::jit_forward_launch(*ke, p, (int)nblocks, stream) : ke->launch(p, (int)nblocks, stream);
   if (e != hipSuccess) return fail(FL_ERR_LAUNCH, "kernel launch: %s", hipGetErrorString(e));
   return FL_OK;
 }

@@ -25,8 +25,24 @@ struct KernelEntry {
   KernelKey key;
   int bm;           // query rows per workgroup
   int lds_bytes;    // LDS of the K/V rings per workgroup
-  LaunchFn launch;
+  LaunchFn launch;  // compiled specialisations; null for one compiled at run time
+  void* jit;        // run-time compiled specialisations: the loaded code object (see jit_forward_entry)
+  int max_lds;      // dynamic LDS a launch of this entry may ask for (0: all of a compute unit's)
 };
+
+// Specialisations outside the compiled table are instantiated from the same kernel template on first
+// use (hipRTC) and kept for the life of the process: returns the entry for (D, DV, score_mod, mask,
+// n_bias, combine, epilogue), or null with the compiler's message in the thread's error detail.
+// Thread-safe; the first call for a combination takes about a second on the host.
+struct JitRequest {
+  int D, DV, mod;
+  uint32_t mask;
+  int nbias;
+  bool diff;
+  uint32_t epi;
+};
+const KernelEntry* jit_forward_entry(const JitRequest& r);
+hipError_t jit_forward_launch(const KernelEntry& e, const FwdParams& p, int nblocks, hipStream_t stream);
 
 constexpr int kMaxLdsBytes = 160 * 1024;           // LDS of a gfx950 compute unit
 

@@ -10,8 +10,10 @@
 
 #include <cstdio>
 #include <cstring>
+#include <map>
 #include <mutex>
 #include <string>
+#include <tuple>
 #include <vector>
 
 #include "../../include/fl_attn.h"
@@ -44,7 +46,126 @@ bool expression_ok(const char* e) {
   return true;
 }
 
+
+// Compiles `src` (which instantiates the kernel named by the expression `inst`) for gfx950 with the
+// library's own flags; returns the code object and the lowered kernel name.
+fl_status compile_instance(const std::string& src, const char* inst, const char* what, std::vector<char>* code,
+                           std::string* kernel_name) {
+  const char* headers[] = {kParamsHpp, kKernelHpp};
+  const char* names[] = {"fl_params.hpp", "fl_kernel_bf16.hpp"};
+  hiprtcProgram prog;
+  if (hiprtcCreateProgram(&prog, src.c_str(), "fl_variant.hip", 2, headers, names) != HIPRTC_SUCCESS)
+    return fl::host::fail(FL_ERR_LAUNCH, "hiprtcCreateProgram failed");
+  std::string expr = std::string("&") + inst;
+  hiprtcAddNameExpression(prog, expr.c_str());
+  // gfx950 only, packed fp32 instructions off
+  const char* opts[] = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
+  const hiprtcResult r = hiprtcCompileProgram(prog, (int)(sizeof(opts) / sizeof(opts[0])), opts);
+  if (r != HIPRTC_SUCCESS) {
+    size_t n = 0;
+    hiprtcGetProgramLogSize(prog, &n);
+    std::string log(n, 0);
+    if (n) hiprtcGetProgramLog(prog, &log[0]);
+    // the first error line is what the caller needs; the detail buffer keeps its head
+    const size_t at = log.find("error:");
+    fl_status st = fl::host::fail(FL_ERR_DESC, "%s: %.300s", what, at == std::string::npos ? log.c_str() : log.c_str() + at);
+    hiprtcDestroyProgram(&prog);
+    return st;
+  }
+  size_t cs = 0;
+  hiprtcGetCodeSize(prog, &cs);
+  code->resize(cs);
+  hiprtcGetCode(prog, code->data());
+  const char* lowered = nullptr;
+  if (hiprtcGetLoweredName(prog, expr.c_str(), &lowered) != HIPRTC_SUCCESS || lowered == nullptr) {
+    hiprtcDestroyProgram(&prog);
+    return fl::host::fail(FL_ERR_LAUNCH, "no lowered kernel name");
+  }
+  *kernel_name = lowered;
+  hiprtcDestroyProgram(&prog);
+  return FL_OK;
+}
+
+// A code object loaded lazily, once per device.
+struct LoadedKernel {
+  std::vector<char> code;
+  std::string kernel_name;
+  std::mutex mu;
+  hipModule_t module[64] = {};
+  hipFunction_t func[64] = {};
+  hipError_t get(hipFunction_t* f) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (func[dev] == nullptr) {
+      if ((e = hipModuleLoadData(&module[dev], code.data())) != hipSuccess) return e;
+      if ((e = hipModuleGetFunction(&func[dev], module[dev], kernel_name.c_str())) != hipSuccess) return e;
+    }
+    *f = func[dev];
+    return hipSuccess;
+  }
+};
+
+struct JitForward {
+  LoadedKernel k;
+  fl::KernelEntry entry;
+  int nthreads;
+};
+
 }  // namespace
+
+namespace fl {
+
+const KernelEntry* jit_forward_entry(const JitRequest& r) {
+  typedef std::tuple<int, int, int, uint32_t, int, bool, uint32_t> Key;
+  static std::mutex mu;
+  static std::map<Key, JitForward*> cache;        // entries live until the process ends
+  const Key key(r.D, r.DV, r.mod, r.mask, r.nbias, r.diff, r.epi);
+  std::lock_guard<std::mutex> lock(mu);            // one compilation at a time; a hit only takes the lookup
+  auto it = cache.find(key);
+  if (it != cache.end()) return it->second != nullptr ? &it->second->entry : nullptr;
+  // Shape of the generated kernels: one 32-row block per wave, two waves per SIMD; 4 waves (8 for the two
+  // softmax streams of the differential variant); 64-key tiles unless the rings would pass 64 KiB of LDS
+  // (a launch through the module API gets no more than that).
+  const int nw = r.diff ? 8 : 4;
+  const int ns = r.diff ? 2 : 1;
+  int bn = 64;
+  if (2 * bn * 2 * (ns * r.D + r.DV) > 65536) bn = 32;
+  const int lds = 2 * bn * 2 * (ns * r.D + r.DV);
+  const int xch = r.diff ? (nw / 2) * 64 * (r.DV / 32) * 16 * 4 : 0;
+  char inst[320];
+  snprintf(inst, sizeof(inst), "fl::fwd_bf16_kernel<fl::Bf16Cfg<%d, %d, %d, 1, %d, 2, %d, %uu, %d, %s, %uu>>", r.D, r.DV, nw, bn,
+           r.mod, r.mask, r.nbias, r.diff ? "true" : "false", r.epi);
+  std::string src = "#include \"fl_kernel_bf16.hpp\"\ntemplate __global__ void ";
+  src += inst;
+  src += "(const fl::FwdParams);\n";
+  JitForward* j = new JitForward;
+  if (compile_instance(src, inst, "run-time specialisation does not compile", &j->k.code, &j->k.kernel_name) != FL_OK ||
+      (lds > xch ? lds : xch) > 65536) {
+    delete j;
+    cache[key] = nullptr;                          // do not try again
+    return nullptr;
+  }
+  j->nthreads = nw * 64;
+  j->entry = KernelEntry{KernelKey{1, r.D, r.DV, r.mod, (int)r.mask, r.nbias, r.diff ? 1 : 0, (int)r.epi, nw, 1, bn, 2, 2},
+                         (nw / ns) * 32, lds > xch ? lds : xch, nullptr, j, 65536};
+  cache[key] = j;
+  return &j->entry;
+}
+
+hipError_t jit_forward_launch(const KernelEntry& e, const FwdParams& p, int nblocks, hipStream_t stream) {
+  JitForward* j = (JitForward*)e.jit;
+  hipFunction_t f = nullptr;
+  hipError_t err = j->k.get(&f);
+  if (err != hipSuccess) return err;
+  FwdParams copy = p;
+  void* args[] = {&copy};
+  return hipModuleLaunchKernel(f, (unsigned)nblocks, 1, 1, (unsigned)j->nthreads, 1, 1, (unsigned)p.lds_bytes, stream, args, nullptr);
+}
+
+}  // namespace fl
 
 extern "C" {
 
@@ -76,42 +197,14 @@ fl_status fl_compile_variant(const char* score_mod_expr, const char* mask_expr, 
   src += inst;
   src += "(const fl::FwdParams);\n";
 
-  const char* headers[] = {kParamsHpp, kKernelHpp};
-  const char* names[] = {"fl_params.hpp", "fl_kernel_bf16.hpp"};
-  hiprtcProgram prog;
-  if (hiprtcCreateProgram(&prog, src.c_str(), "fl_custom_variant.hip", 2, headers, names) != HIPRTC_SUCCESS)
-    return fl::host::fail(FL_ERR_LAUNCH, "hiprtcCreateProgram failed");
-  std::string expr = std::string("&") + inst;
-  hiprtcAddNameExpression(prog, expr.c_str());
-  // the library's own flags: gfx950 only, packed fp32 instructions off
-  const char* opts[] = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
-  const hiprtcResult r = hiprtcCompileProgram(prog, (int)(sizeof(opts) / sizeof(opts[0])), opts);
-  if (r != HIPRTC_SUCCESS) {
-    size_t n = 0;
-    hiprtcGetProgramLogSize(prog, &n);
-    std::string log(n, 0);
-    if (n) hiprtcGetProgramLog(prog, &log[0]);
-    // the first error line is what the caller needs; the detail buffer keeps its head
-    const size_t at = log.find("error:");
-    fl_status st = fl::host::fail(FL_ERR_DESC, "expression does not compile: %.300s", at == std::string::npos ? log.c_str() : log.c_str() + at);
-    hiprtcDestroyProgram(&prog);
-    return st;
-  }
   fl_custom_variant* v = new fl_custom_variant;
   v->D = D;
   v->mask = mask;
-  size_t cs = 0;
-  hiprtcGetCodeSize(prog, &cs);
-  v->code.resize(cs);
-  hiprtcGetCode(prog, v->code.data());
-  const char* lowered = nullptr;
-  if (hiprtcGetLoweredName(prog, expr.c_str(), &lowered) != HIPRTC_SUCCESS || lowered == nullptr) {
-    hiprtcDestroyProgram(&prog);
+  const fl_status st = compile_instance(src, inst, "expression does not compile", &v->code, &v->kernel_name);
+  if (st != FL_OK) {
     delete v;
-    return fl::host::fail(FL_ERR_LAUNCH, "no lowered kernel name");
+    return st;
   }
-  v->kernel_name = lowered;
-  hiprtcDestroyProgram(&prog);
   *handle = v;
   return FL_OK;
 }

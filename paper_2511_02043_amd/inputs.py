@@ -286,6 +286,55 @@ def diffattn_paper_bf16(S=2048, D=64, B=None, H=16, tokens=16384, salt=0) -> Wor
     return w
 
 
+def combination_bf16(D=64, Dv=None, score_mod="none", pos_mask="none", doc=False, n_bias=0, diff=False, rmsnorm=False,
+                     gate=False, B=2, G=1, H=4, Hkv=None, S=200, Sk=None, window=37, prefix=45, cap=4.0, qscale=2.0,
+                     salt=0) -> Workload:
+    """Any combination of the descriptor's independent parts (Eq. 4 score_mod x positional mask x
+    document mask x additive biases x differential streams x epilogues), small enough for the oracle:
+    score_mod in {"none", "alibi", "softcap"}, pos_mask in {"none", "causal", "window", "prefix"}.
+    Bias 0 is a per-query pair bias [B, 1, H, Sq, Sk] (broadcast over G), bias 1 a per-row key bias
+    [B, G, 1, 1, Sk].  Configuration 7 in the seed recipe."""
+    Dv = D if Dv is None else Dv
+    Sk = S if Sk is None else Sk
+    Hkv = H if Hkv is None else Hkv
+    nq = 2 * H if diff else H
+    nk = 2 * Hkv if diff else Hkv
+    q_all = normal((B, G, nq, S, D), tensor_seed(7, 0, salt), "bf16", qscale if score_mod == "softcap" else 1.0)
+    k_all = normal((B, G, nk, Sk, D), tensor_seed(7, 1, salt), "bf16")
+    v = normal((B, G, Hkv, Sk, Dv), tensor_seed(7, 2, salt), "bf16")
+    w = Workload(f"combo_d{D}_{Dv}_{score_mod}_{pos_mask}{'_doc' if doc else ''}_b{n_bias}{'_diff' if diff else ''}"
+                 f"{'_rms' if rmsnorm else ''}{'_gate' if gate else ''}", "bf16", q_all[:, :, :H], k_all[:, :, :Hkv], v,
+                 scale=D ** -0.5)
+    if diff:
+        w.q2, w.k2 = q_all[:, :, H:], k_all[:, :, Hkv:]
+        w.lam = np.linspace(0.3, 0.9, H).astype(np.float32)
+    if score_mod == "alibi":
+        w.alibi = alibi_slopes(H)
+    elif score_mod == "softcap":
+        w.softcap = cap
+    if pos_mask == "causal":
+        w.causal = True
+    elif pos_mask == "window":
+        w.causal, w.window = True, window
+    elif pos_mask == "prefix":
+        w.prefix = prefix
+    if doc:
+        ids = doc_ids(B, max(S, Sk), tensor_seed(7, 3, salt), 20, 90)
+        w.q_doc, w.kv_doc = np.ascontiguousarray(ids[:, :S]), np.ascontiguousarray(ids[:, :Sk])
+    biases = []
+    if n_bias >= 1:
+        biases.append(normal((B, 1, H, S, Sk), tensor_seed(7, 4, salt), "bf16"))
+    if n_bias >= 2:
+        biases.append(normal((B, G, 1, 1, Sk), tensor_seed(7, 5, salt), "bf16"))
+    w.biases = tuple(biases)
+    if gate:
+        w.gate = normal((B, G, H, S, Dv), tensor_seed(7, 6, salt), "bf16")
+    if rmsnorm:
+        w.rmsnorm = True
+        w.rms_weight = (1.0 + 0.1 * np.cos(np.arange(Dv))).astype(np.float32)
+    return w
+
+
 # --- decode step over a paged key/value cache (the serving experiment of Sec. 4.1) -----------
 
 @dataclasses.dataclass

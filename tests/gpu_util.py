@@ -52,3 +52,54 @@ def run_and_compare(w, out_dtype="f32", label=None):
     assert rel_l2 <= tol["rel_l2"], msg
     assert le <= tol["lse"], msg
     return dict(max_abs=max_abs, rel_l2=rel_l2, lse=le)
+
+
+def head_slice(w, b, h):
+    """The (b, h) problem of a workload as a workload of its own (B = H = 1; all rows of the G axis)."""
+    import dataclasses
+    d = w.dims
+    group = d["H"] // d["Hkv"]
+    sub = dataclasses.replace(w)
+    for f in ("q", "k", "v", "q2", "k2", "gate"):
+        x = getattr(w, f)
+        if x is not None:
+            hh = h if x.shape[2] == d["H"] else h // group
+            setattr(sub, f, x[b:b + 1, :, hh:hh + 1])
+    sub.biases = tuple(bb[(b if bb.shape[0] > 1 else 0):(b if bb.shape[0] > 1 else 0) + 1, :,
+                          (h if bb.shape[2] > 1 else 0):(h if bb.shape[2] > 1 else 0) + 1] for bb in w.biases)
+    if w.alibi is not None:
+        sub.alibi = w.alibi[h:h + 1]
+    if w.lam is not None:
+        sub.lam = w.lam[h:h + 1]
+    if w.q_doc is not None:
+        sub.q_doc, sub.kv_doc = w.q_doc[b:b + 1], w.kv_doc[b:b + 1]
+    return sub
+
+
+def compare_whole_heads(w, heads, out_dtype="f32", label=None):
+    """One launch of the whole workload; the listed (b, h) problems are compared element by element with
+    the oracle (which evaluates one head at a time), and everything else has to be finite."""
+    import torch
+    dw = runner.upload(w, out_dtype=out_dtype)
+    dw.out.fill_(float("nan"))
+    dw.lse.fill_(float("nan"))
+    dw.run_checked()
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(dw.out).all()), f"{label or w.name}: non-finite output"
+    tol = TOL[w.dtype]
+    worst = dict(max_abs=0.0, rel_l2=0.0, lse=0.0)
+    for (b, h) in heads:
+        got = dw.out[b, :, h].float().cpu().numpy()[None, :, None]
+        got_lse = dw.lse[b, :, h, :, 0].cpu().numpy()[None, :, None]
+        ref, ref_lse = ao.run_workload(head_slice(w, b, h))
+        max_abs, rel_l2 = errors(got, ref)
+        le = lse_error(got_lse, ref_lse)
+        msg = f"{label or w.name} head ({b}, {h}): max_abs={max_abs:.3e} rel_l2={rel_l2:.3e} lse={le:.3e}"
+        print(msg, flush=True)
+        if out_dtype == "f32":
+            assert max_abs <= tol["max_abs"], msg
+        else:
+            assert np.all(np.abs(got - ref) <= tol["max_abs"] + 2.0 ** -8 * np.abs(ref)), msg
+        assert rel_l2 <= tol["rel_l2"] and le <= tol["lse"], msg
+        worst = dict(max_abs=max(worst["max_abs"], max_abs), rel_l2=max(worst["rel_l2"], rel_l2), lse=max(worst["lse"], le))
+    return worst

@@ -4,8 +4,8 @@ Tolerance.  The kernels recompute P and dS in fp32 from bf16 inputs and round bo
 (relative error 2^-9 per element) before the fp32-accumulating contractions; the bf16 `out`
 that enters delta = rowsum(dout * out) carries the same relative rounding.  With fp32 gradient
 outputs the error of an element is therefore a sum of independently rounded terms: relative
-L2 error about 2^-9 ~ 2e-3 (measured 1.5e-3 .. 2.0e-3; bound used: 1e-2), and no element off by
-more than 2e-2 of the tensor's largest magnitude (measured: below 4e-3 of it).  bf16 gradient outputs add half a bf16 ulp of the value.
+L2 error about 2^-9 ~ 2e-3 (measured 1.5e-3 .. 2.5e-3; bound used: 5e-3, the forward contract's), and
+no element off by more than 1e-2 of the tensor's largest magnitude (measured: below 4e-3 of it).  bf16 gradient outputs add half a bf16 ulp of the value.
 """
 import numpy as np
 import pytest
@@ -15,8 +15,8 @@ from paper_2511_02043_amd import inputs, runner
 
 pytestmark = pytest.mark.gpu
 
-REL_L2 = 1e-2
-MAX_REL = 2e-2
+REL_L2 = 5e-3
+MAX_REL = 1e-2
 
 
 def run_backward(w, grad_dtype="f32", salt=0):
@@ -31,7 +31,7 @@ def run_backward(w, grad_dtype="f32", salt=0):
     return dout, [t.float().cpu().numpy() for t in (db.dq, db.dk, db.dv)]
 
 
-def compare(w, grad_dtype="f32", label=None):
+def compare(w, grad_dtype="f32", label=None, rel_l2=REL_L2, max_rel=MAX_REL):
     dout, got = run_backward(w, grad_dtype)
     ref = bo.run_workload_backward(w, dout)
     res = {}
@@ -45,8 +45,8 @@ def compare(w, grad_dtype="f32", label=None):
         mx = float(np.max(np.abs(diff)))
         print(f"{label or w.name} {name}: rel_l2={rel:.3e} max_abs={mx:.3e} (max |ref| {scale:.3e})", flush=True)
         slack = 2.0 ** -8 * np.abs(r) if grad_dtype == "bf16" else 0.0
-        assert rel <= REL_L2, (name, rel)
-        assert np.all(np.abs(diff) <= MAX_REL * scale + slack), (name, mx, scale)
+        assert rel <= rel_l2, (name, rel)
+        assert np.all(np.abs(diff) <= max_rel * scale + slack), (name, mx, scale)
         res[name] = (rel, mx)
     return res
 
@@ -196,10 +196,13 @@ def test_grouped_heads_cut_by_the_host_rule():
 
 @pytest.mark.parametrize("D", [64, 128])
 def test_large_logits_backward(D):
-    """Queries scaled by 16: P = exp(s - lse) must be formed from the saved lse without overflow."""
+    """Queries scaled by 16: P = exp(s - lse) must be formed from the saved lse without overflow.
+    Outside the benchmark's input range: the rows are nearly one-hot, so the bf16 rounding of the one
+    large P and dS of a row (relative 2^-8 at worst) reaches the gradient without averaging over keys;
+    the bound is therefore twice the contract's (measured 6.5e-3 relative L2)."""
     w = inputs.causal_bf16(B=1, H=4, Hkv=2, S=400, D=D)
     w.q = w.q * 16.0
-    compare(w, label=f"large logits D={D}")
+    compare(w, label=f"large logits D={D}", rel_l2=1e-2, max_rel=2e-2)
 
 
 def test_unbounded_window_equals_causal():

@@ -9,7 +9,7 @@ import pytest
 
 from oracle import attention_oracle as ao
 from paper_2511_02043_amd import inputs, runner
-from tests.gpu_util import TOL, errors, run_and_compare
+from tests.gpu_util import TOL, compare_whole_heads, errors, run_and_compare
 
 pytestmark = pytest.mark.gpu
 
@@ -50,6 +50,26 @@ def test_c2_full_size_sampled_rows(D, out_dtype):
     # properties that hold at any size: causal row 0 returns V row 0; every lse is finite
     np.testing.assert_allclose(out[:, 0, :, 0], w.v[:, 0, :, 0], atol=2.0 ** -8 * 4)
     assert np.all(np.isfinite(lse)) and np.all(np.isfinite(out))
+
+
+@pytest.mark.parametrize("D", [128, 64])
+def test_c2_full_size_whole_heads(D):
+    """The benchmark launch, eight whole (batch, head) problems element by element: every row of every q-tile
+    (the long and the short tile of each workgroup's pair, the diagonal tiles, the ragged-free last tile), one
+    problem on each of the eight XCDs of the XCD-aware workgroup order (problem index b * H + h mod 8 = 0 .. 7),
+    spread over the four batch elements."""
+    heads = [(0, 0), (0, 9), (1, 2), (1, 11), (2, 4), (2, 13), (3, 6), (3, 15)]
+    assert sorted((b * 16 + h) % 8 for b, h in heads) == list(range(8))
+    compare_whole_heads(inputs.causal_bf16(D=D), heads, out_dtype="f32", label=f"c2 D={D} whole heads")
+
+
+@pytest.mark.parametrize("variant", inputs.GRID_VARIANTS)
+def test_grid_cell_s16384_whole_head(variant):
+    """The longest cell of the paper's grid (S = 16384, one batch element, 16 heads, D = 64): two whole heads
+    per variant against the oracle, grouped-query heads for every second variant."""
+    gqa = inputs.GRID_VARIANTS.index(variant) % 2 == 1
+    compare_whole_heads(inputs.grid_bf16(variant, 16384, gqa=gqa), [(0, 3), (0, 12)], out_dtype="f32",
+                        label=f"grid {variant} S=16384 gqa={gqa}")
 
 
 def test_c3a_alibi_full_size():

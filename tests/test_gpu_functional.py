@@ -53,7 +53,7 @@ def test_autograd_matches_oracles(case):
         g = t.float().cpu().numpy()[:, None]
         e = rel_l2(g, r)
         print(f"{case} {name}: rel_l2={e:.3e}", flush=True)
-        assert e <= 1e-2, (name, e)
+        assert e <= 5e-3, (name, e)          # bf16 gradients: P and dS rounding plus half an ulp of the stored value
 
 
 def test_rejects_what_it_cannot_run():

@@ -46,7 +46,7 @@ def test_forward_backward_past_4gib():
         for name, t, r in zip(("dq", "dk", "dv"), (q.grad, k.grad, v.grad), ref):
             e = rel_l2(head(t), r)
             print(f"head ({b}, {h}) {name}: rel_l2={e:.3e}", flush=True)
-            assert e <= 1e-2, (b, h, name, e)
+            assert e <= 5e-3, (b, h, name, e)
 
 
 def test_decode_cache_past_4gib():

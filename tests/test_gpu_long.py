@@ -79,7 +79,7 @@ def test_long_document_causal_forward_backward(D, H, Hkv):
             diff = g[:, :, :, a:b] - r
             rel = float(np.sqrt(np.sum(diff * diff)) / max(np.sqrt(np.sum(r * r)), 1e-3 * np.sqrt(r.size)))
             print(f"D={D} document {d} {name}: rel_l2={rel:.3e}", flush=True)
-            assert rel <= 1e-2, (d, name, rel)
+            assert rel <= 5e-3, (d, name, rel)
 
 
 @pytest.mark.parametrize("D", [128, 64])
