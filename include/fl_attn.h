@@ -69,6 +69,7 @@ typedef struct {
 enum { FL_MOD_NONE = 0, FL_MOD_ALIBI = 1, FL_MOD_SOFTCAP = 2 };
 
 /* mask bits (True = masked, combined by OR), i = query index, j = key index:
+ * (with q_offset != 0 read i as the query's position i + q_offset in the three positional masks)
  *   CAUSAL  masked iff j > i                                   (attention listing + causal)
  *   WINDOW  masked iff j > i or i - j > window                 (sliding-window listings);
  *           implies CAUSAL, so window + 1 keys are visible including j = i
@@ -96,7 +97,11 @@ typedef struct {
   uint32_t combine;        /* FL_SINGLE | FL_DIFFERENTIAL                                     */
   uint32_t epilogue;       /* bit-or of FL_EPI_*                                              */
   float    rms_eps;
-  uint32_t reserved;
+  int32_t  q_offset;       /* >= 0: query row i sits at sequence position i + q_offset (key j at
+                              position j): the positional masks and ALiBi use positions, so e.g.
+                              q_offset = Sk - Sq aligns a causal mask bottom-right (a chunk of new
+                              queries against a longer key/value cache, Sec. 4.1 serving).  Document
+                              ids stay per row.  Forward pass only.                               */
 } fl_variant_desc;
 
 typedef struct {

@@ -244,6 +244,9 @@ def run_workload(w, q_rows=None):
     variant = dict(causal=w.causal, window=w.window, prefix=w.prefix,
                    softcap_value=w.softcap, alibi_slopes=w.alibi, biases=w.biases,
                    q_doc=w.q_doc, kv_doc=w.kv_doc)
+    off = int(getattr(w, "q_offset", 0) or 0)
+    if off:                                                # query row i sits at position i + q_offset
+        variant["q_pos"] = np.arange(w.q.shape[3], dtype=np.int64) + off
     if w.q2 is not None:
         out, lse = differential_attention(w.q, w.k, w.q2, w.k2, w.v, w.lam, scale=w.scale,
                                           rms=w.rmsnorm, rms_eps=w.rms_eps,
@@ -288,7 +291,7 @@ def run_workload_rows(w, picks):
                        biases=biases,
                        q_doc=None if w.q_doc is None else w.q_doc[b:b + 1, i:i + 1],
                        kv_doc=None if w.kv_doc is None else w.kv_doc[b:b + 1],
-                       q_pos=np.array([i]))
+                       q_pos=np.array([i + int(getattr(w, "q_offset", 0) or 0)]))
         q = one(w.q, b, g, h)[:, :, :, i:i + 1]
         k, v = one(w.k, b, g, hk), one(w.v, b, g, hk)
         if w.q2 is not None:

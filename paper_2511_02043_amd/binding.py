@@ -32,7 +32,7 @@ class fl_variant_desc(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("scale", C.c_float), ("score_mod", C.c_uint32),
                 ("softcap", C.c_float), ("mask", C.c_uint32), ("window", C.c_int32),
                 ("prefix_len", C.c_int32), ("n_bias", C.c_uint32), ("combine", C.c_uint32),
-                ("epilogue", C.c_uint32), ("rms_eps", C.c_float), ("reserved", C.c_uint32)]
+                ("epilogue", C.c_uint32), ("rms_eps", C.c_float), ("q_offset", C.c_int32)]
 
 
 class fl_aux(C.Structure):
@@ -139,12 +139,12 @@ def tensor_desc(t, sizes: Optional[Sequence[int]] = None) -> fl_tensor:
 
 def variant_desc(*, scale: float, score_mod: int = FL_MOD_NONE, softcap: float = 0.0, mask: int = 0,
                  window: int = 0, prefix_len: int = 0, n_bias: int = 0, combine: int = FL_SINGLE,
-                 epilogue: int = 0, rms_eps: float = 0.0) -> fl_variant_desc:
+                 epilogue: int = 0, rms_eps: float = 0.0, q_offset: int = 0) -> fl_variant_desc:
     d = fl_variant_desc()
     d.struct_size = C.sizeof(fl_variant_desc)
     d.scale, d.score_mod, d.softcap, d.mask = scale, score_mod, softcap, mask
     d.window, d.prefix_len, d.n_bias, d.combine = window, prefix_len, n_bias, combine
-    d.epilogue, d.rms_eps = epilogue, rms_eps
+    d.epilogue, d.rms_eps, d.q_offset = epilogue, rms_eps, q_offset
     return d
 
 

@@ -89,6 +89,7 @@ fl_status check_desc(const fl_variant_desc* d) {
     return fail(FL_ERR_DESC, "unknown epilogue bits 0x%x", d->epilogue);
   if ((d->epilogue & FL_EPI_RMSNORM) && (!(d->rms_eps >= 0.f) || !std::isfinite(d->rms_eps)))
     return fail(FL_ERR_DESC, "rms_eps must be finite and >= 0");
+  if (d->q_offset < 0 || d->q_offset > 0x3fffffff) return fail(FL_ERR_DESC, "q_offset must be in [0, 2^30)");
   return FL_OK;
 }
 
@@ -220,7 +221,9 @@ const fl::BwdEntry* find_bwd_entry(const fl_variant_desc* d, int D) {
   return nullptr;
 }
 
-bool bwd_desc_ok(const fl_variant_desc* d) { return d->n_bias == 0 && d->combine == FL_SINGLE && d->epilogue == 0; }
+bool bwd_desc_ok(const fl_variant_desc* d) {
+  return d->n_bias == 0 && d->combine == FL_SINGLE && d->epilogue == 0 && d->q_offset == 0;
+}
 
 // Workspace of the backward pass: delta, lse2 ([B, G, H, Sq] floats each, 256-byte aligned), then
 // the document-id summaries of the tile skipper.
@@ -501,8 +504,10 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   }
   p.B = (int)B; p.G = (int)G; p.H = (int)H; p.Hkv = (int)Hkv; p.Sq = (int)Sq; p.Sk = (int)Sk;
   p.D = (int)D; p.Dv = (int)Dv;
-  p.window = clamp_window(desc->window, Sq, Sk);
+  p.window = clamp_window(desc->window, Sq + desc->q_offset, Sk);
   p.prefix = desc->prefix_len;
+  p.q_off = desc->q_offset;
+  if ((int64_t)desc->q_offset + Sq > 0x7fffff00LL) return fail(FL_ERR_SHAPE, "q_offset + Sq too large");
   p.scale = desc->scale;
   p.softcap = desc->softcap;
   p.rms_eps = desc->rms_eps;
@@ -631,7 +636,7 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   if (aux != nullptr && aux->struct_size != sizeof(fl_aux))
     return fail(FL_ERR_DESC, "aux->struct_size = %u, expected %zu", aux->struct_size, sizeof(fl_aux));
   if (!bwd_desc_ok(desc))
-    return fail(FL_ERR_UNSUPPORTED, "the backward pass covers variants without bias, second stream and epilogue");
+    return fail(FL_ERR_UNSUPPORTED, "the backward pass covers variants without bias, second stream, epilogue and query offset");
   if (q->dtype != FL_BF16) return fail(FL_ERR_DTYPE, "the backward pass takes bf16 inputs (q dtype %d)", q->dtype);
 
   const int64_t B = q->size[0], G = q->size[1], H = q->size[2], Sq = q->size[3], D = q->size[4];
@@ -776,7 +781,8 @@ fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_
   if (aux != nullptr && aux->struct_size != sizeof(fl_aux))
     return fail(FL_ERR_DESC, "aux->struct_size = %u, expected %zu", aux->struct_size, sizeof(fl_aux));
   const uint32_t mask = canonical_mask(desc->mask);
-  if ((mask & (FL_MASK_DOC | FL_MASK_PREFIX)) || desc->n_bias != 0 || desc->combine != FL_SINGLE || desc->epilogue != 0)
+  if ((mask & (FL_MASK_DOC | FL_MASK_PREFIX)) || desc->n_bias != 0 || desc->combine != FL_SINGLE || desc->epilogue != 0 ||
+      desc->q_offset != 0)
     return fail(FL_ERR_UNSUPPORTED, "the decode step covers scale, score_mod and the sliding window only");
   if (q->dtype != FL_BF16) return fail(FL_ERR_DTYPE, "the decode step takes bf16 inputs (q dtype %d)", q->dtype);
 

@@ -293,10 +293,10 @@ struct Wave {
         // offset: one per-lane term per key block minus a uniform constant per register, then one FMA
         // (all the integers involved are far below 2^24, so the float arithmetic is exact up
         // to the final rounding of the products)
-        const float d = slope_l2 * (float)(i[rb] - j0 - 32 * nb - 4 * half);
+        const float d = slope_l2 * (float)(i[rb] + p.q_off - j0 - 32 * nb - 4 * half);
         x = fmaf(x, c_scale, -fabsf(d - alibi_c[r]));
       } else if constexpr (C::MOD == kModCustom) {
-        x = fl_user_score_mod(x * p.scale, b, g, h, i[rb], j) * kLog2e;
+        x = fl_user_score_mod(x * p.scale, b, g, h, i[rb] + p.q_off, j) * kLog2e;
       } else {
         x *= c_scale;
       }
@@ -395,11 +395,12 @@ struct Wave {
     int d_hi[RB], d_lo[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
+      const int ip = i[rb] + p.q_off;              // the row's sequence position
       int last = p.Sk - 1;                         // last visible key of the row
-      if constexpr ((MASK & kMaskPrefix) != 0) last = min(last, max(i[rb], p.prefix - 1));
-      else if constexpr ((MASK & (kMaskCausal | kMaskWindow)) != 0) last = min(last, i[rb]);
+      if constexpr ((MASK & kMaskPrefix) != 0) last = min(last, max(ip, p.prefix - 1));
+      else if constexpr ((MASK & (kMaskCausal | kMaskWindow)) != 0) last = min(last, ip);
       d_hi[rb] = last - jl;
-      d_lo[rb] = (MASK & kMaskWindow) != 0 ? i[rb] - p.window - jl : 0;
+      d_lo[rb] = (MASK & kMaskWindow) != 0 ? ip - p.window - jl : 0;
     }
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
@@ -429,7 +430,7 @@ struct Wave {
           bool hide = c > d_hi[rb];
           if constexpr ((MASK & kMaskWindow) != 0) hide = hide || c < d_lo[rb];
           if constexpr ((MASK & kMaskDoc) != 0) hide = hide || kd[r] != qdoc[rb];
-          if constexpr ((MASK & kMaskCustom) != 0) hide = hide || fl_user_mask(b, g, h, i[rb], jl + c);
+          if constexpr ((MASK & kMaskCustom) != 0) hide = hide || fl_user_mask(b, g, h, i[rb] + p.q_off, jl + c);
           if (hide) sc[rb][nb][r] = -INFINITY;
         }
     }
@@ -761,8 +762,10 @@ fwd_bf16_kernel(const FwdParams p) {
 
   // ---- tile skipper (a0): visible key range and document-id summaries
   const int i_last = (i0 + C::BM - 1 < p.Sq ? i0 + C::BM : p.Sq) - 1;
+  // positions of the workgroup's / the wave's first and last query row: what the positional masks compare with keys
+  const int pos0 = i0 + p.q_off, pos_last = i_last + p.q_off, posw = iw + p.q_off;
   int k_lo, k_hi;
-  key_range(MASK, i0, i_last, p.Sk, p.window, p.prefix, k_lo, k_hi);
+  key_range(MASK, pos0, pos_last, p.Sk, p.window, p.prefix, k_lo, k_hi);
   const int t_lo = k_lo / BN;
   const int t_hi = (k_hi + BN - 1) / BN;
   const int nks = (p.Sk + kSumBlock - 1) / kSumBlock;
@@ -823,7 +826,7 @@ fwd_bf16_kernel(const FwdParams p) {
   auto next_tile = [&](int t) __attribute__((always_inline)) -> int {             // uniform over the workgroup
     if constexpr ((MASK & kMaskDoc) != 0) {
       // the usual case first: tile t itself has something visible (one uniform check)
-      if (t < t_hi && classify_block(MASK, i0, i_last, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg,
+      if (t < t_hi && classify_block(MASK, pos0, pos_last, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg,
                                      tile_keys(t)) == kSkip) {
         // a run of hidden tiles (the other documents of a long sequence): 64 tiles per round, one per lane
         ++t;
@@ -831,7 +834,7 @@ fwd_bf16_kernel(const FwdParams p) {
           const int tt = t + w.lane;
           bool keep = false;
           if (tt < t_hi)
-            keep = classify_block(MASK, i0, i_last, tt * BN, tt * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg,
+            keep = classify_block(MASK, pos0, pos_last, tt * BN, tt * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg,
                                   tile_keys_lane(tt)) != kSkip;
           const unsigned long long found = __builtin_amdgcn_ballot_w64(keep);
           if (found != 0) {
@@ -846,7 +849,7 @@ fwd_bf16_kernel(const FwdParams p) {
     return t;                                      // positional masks are already in [t_lo, t_hi)
   };
   int tf_lo = 0, tf_hi = 0;                        // tiles fully visible to this wave's rows (positional masks)
-  full_tile_range(MASK, iw, iw + C::WROWS - 1, p.Sk, p.window, p.prefix, BN, tf_lo, tf_hi);
+  full_tile_range(MASK, posw, posw + C::WROWS - 1, p.Sk, p.window, p.prefix, BN, tf_lo, tf_hi);
   tf_lo = __builtin_amdgcn_readfirstlane(tf_lo);
   tf_hi = __builtin_amdgcn_readfirstlane(min(tf_hi, t_hi));
   // Tiles that hold a visible key of some row of this wave (positional masks): outside of
@@ -856,7 +859,7 @@ fwd_bf16_kernel(const FwdParams p) {
   int tv_lo = 0, tv_hi = 0;
   if constexpr (kWaveSkip) {
     int lo, hi;
-    key_range(MASK, iw, iw + C::WROWS - 1, p.Sk, p.window, p.prefix, lo, hi);
+    key_range(MASK, posw, posw + C::WROWS - 1, p.Sk, p.window, p.prefix, lo, hi);
     tv_lo = __builtin_amdgcn_readfirstlane(lo / BN);
     tv_hi = __builtin_amdgcn_readfirstlane((hi + BN - 1) / BN);
   }
@@ -864,7 +867,7 @@ fwd_bf16_kernel(const FwdParams p) {
     if (t >= t_hi) return kTileSkip;
     int2 ks = make_int2(0, 0);
     if constexpr ((MASK & kMaskDoc) != 0) ks = tile_keys(t);
-    const int c = classify_block(MASK, iw, iw + C::WROWS - 1, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix,
+    const int c = classify_block(MASK, posw, posw + C::WROWS - 1, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix,
                                  qs_wave, ks);
     return __builtin_amdgcn_readfirstlane(c);
   };

@@ -90,7 +90,7 @@ fwd_f32_kernel(const FwdParams p) {
   // ---- visible key range of this workgroup (positional masks) and tile walk
   int k_lo, k_hi;
   const int i_max = (i0 + kF32Rows - 1 < p.Sq ? i0 + kF32Rows - 1 : p.Sq - 1);
-  key_range(MASK, i0, i_max, p.Sk, p.window, p.prefix, k_lo, k_hi);
+  key_range(MASK, i0 + p.q_off, i_max + p.q_off, p.Sk, p.window, p.prefix, k_lo, k_hi);   // row i sits at position i + q_off
   const int t_lo = k_lo / kF32Keys;
   const int t_hi = (k_hi + kF32Keys - 1) / kF32Keys;
 
@@ -112,7 +112,7 @@ fwd_f32_kernel(const FwdParams p) {
     int2 ks = make_int2(0, 0);
     if ((MASK & kMaskDoc) != 0)
       ks = p.kv_sum[(int64_t)b * ((p.Sk + kSumBlock - 1) / kSumBlock) + t];   // kF32Keys == kSumBlock
-    const int cls = classify_block(MASK, i0, i_max, j0, j0 + kF32Keys - 1, p.Sk, p.window, p.prefix, qs, ks);
+    const int cls = classify_block(MASK, i0 + p.q_off, i_max + p.q_off, j0, j0 + kF32Keys - 1, p.Sk, p.window, p.prefix, qs, ks);
     if (cls == kSkip) continue;                    // uniform over the workgroup
 
     __syncthreads();                               // previous tile fully consumed
@@ -166,7 +166,7 @@ fwd_f32_kernel(const FwdParams p) {
           const int j = j0 + r;
           float x = acc * p.scale;                                   // Eq. 3
           if (MOD == kModSoftcap) x = p.softcap * tanhf(x / p.softcap);   // Eq. 4
-          if (MOD == kModAlibi) x -= slope * fabsf((float)(i - j));       // Eq. 4
+          if (MOD == kModAlibi) x -= slope * fabsf((float)(i + p.q_off - j));       // Eq. 4
           for (int nb = 0; nb < NBIAS; ++nb) {
             const BiasView& bv = p.bias[nb];
             const int64_t off = b * bv.sb + g * bv.sg + h * bv.sh + (int64_t)ic * bv.si +
@@ -177,7 +177,7 @@ fwd_f32_kernel(const FwdParams p) {
           bool hide = j >= p.Sk;
           if (cls == kPartial) {
             const int kd = (MASK & kMaskDoc) ? p.kv_doc[(int64_t)b * p.Sk + (j < p.Sk ? j : 0)] : 0;
-            hide = hide || is_masked(MASK, i, j, p.window, p.prefix, qdoc, kd);
+            hide = hide || is_masked(MASK, i + p.q_off, j, p.window, p.prefix, qdoc, kd);
           }
           sc[u] = hide ? -INFINITY : x * kLog2e;                     // log2 domain from here on
         }

@@ -87,6 +87,7 @@ struct FwdParams {
   int32_t bias_lds_base; // byte offset of the per-wave bias staging buffers in LDS
   int32_t bias_lds_wave; // bytes of staging per wave (two buffers for every bias up to the last staged one)
   int32_t pair;          // bf16 kernels: 1 = a workgroup takes q-tiles nq - 1 - i and i (balanced causal work)
+  int32_t q_off;         // query row i sits at sequence position i + q_off (positional masks, ALiBi); >= 0
 };
 
 }  // namespace fl

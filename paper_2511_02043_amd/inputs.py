@@ -114,6 +114,7 @@ class Workload:
     rmsnorm: bool = False
     rms_eps: float = 1e-6
     rms_weight: Optional[np.ndarray] = None  # [Dv] float32
+    q_offset: int = 0               # query row i sits at sequence position i + q_offset (keys: j at j)
 
     @property
     def dims(self) -> Dict[str, int]:

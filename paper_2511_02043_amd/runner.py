@@ -91,7 +91,7 @@ def upload(w, out_dtype: str = "f32", device="cuda:0", want_lse: bool = True) ->
     desc = fb.variant_desc(scale=float(w.scale), score_mod=mod, softcap=float(w.softcap or 0.0), mask=mask,
                            window=int(w.window or 0), prefix_len=int(w.prefix or 0), n_bias=len(w.biases),
                            combine=fb.FL_DIFFERENTIAL if diff else fb.FL_SINGLE, epilogue=epi,
-                           rms_eps=float(w.rms_eps) if w.rmsnorm else 0.0)
+                           rms_eps=float(w.rms_eps) if w.rmsnorm else 0.0, q_offset=int(getattr(w, "q_offset", 0) or 0))
 
     def dev(x, dt):
         t = None if x is None else to_device(np.asarray(x), dt, device)

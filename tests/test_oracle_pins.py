@@ -416,3 +416,46 @@ def test_custom_predicate_matches_sdpa():
     out, _ = ao.attention_custom(q, k, v, scale=0.4, score_mod=lambda s, b, g, h, ii, jj: s + 0.05 * ((ii - jj) % 5),
                                  mask=lambda b, g, h, ii, jj: (jj > ii) | (((ii ^ jj) & 4) != 0))
     np.testing.assert_allclose(out, sdpa(q, k, v, 0.4, allowed=~hidden, bias=bias.astype(np.float64)), rtol=0, atol=1e-12)
+
+
+# ---------------------------------------------------------------------------------------
+# Query-position offset (chunked prefill / bottom-right aligned masks: query row i sits at
+# position i + q_offset): run_workload against SDPA with the mask written out explicitly,
+# and against the rows of the square problem the chunk is cut from.
+# ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("kind", ["causal", "window", "prefix", "alibi_causal"])
+def test_query_offset_matches_sdpa_explicit_mask(kind):
+    Sq, Sk, off = 13, 40, 27
+    w = inputs.causal_bf16(B=2, H=2, S=Sq, Sk=Sk, D=64, causal=kind in ("causal", "alibi_causal"))
+    w.q_offset = off
+    i = np.arange(Sq)[:, None] + off
+    j = np.arange(Sk)[None, :]
+    bias = None
+    if kind == "causal":
+        allowed = j <= i
+    elif kind == "window":
+        w.causal, w.window = True, 9
+        allowed = (j <= i) & (i - j <= 9)
+    elif kind == "prefix":
+        w.prefix = 31
+        allowed = (j <= i) | (j < 31)
+    else:
+        w.alibi = inputs.alibi_slopes(2)
+        allowed = j <= i
+        bias = -w.alibi.astype(np.float64)[None, None, :, None, None] * np.abs(i - j)[None, None, None]
+    out, lse = ao.run_workload(w)
+    ref = sdpa(w.q.astype(np.float64), w.k.astype(np.float64), w.v.astype(np.float64), w.scale,
+               allowed=np.broadcast_to(allowed, (2, 1, 2, Sq, Sk)), bias=bias)
+    np.testing.assert_allclose(out, ref, rtol=0, atol=1e-12)
+    # the last Sq rows of the square causal problem over the same keys are these rows
+    if kind == "causal":
+        full = inputs.causal_bf16(B=2, H=2, S=Sk, D=64)
+        full.k, full.v = w.k, w.v
+        full.q = np.concatenate([np.zeros((2, 1, 2, off, 64), w.q.dtype), w.q], axis=3)
+        out_full, lse_full = ao.run_workload(full)
+        np.testing.assert_allclose(out, out_full[:, :, :, off:], rtol=0, atol=1e-12)
+        np.testing.assert_allclose(lse, lse_full[:, :, :, off:], rtol=0, atol=1e-12)
+        rows = ao.run_workload_rows(w, [(1, 0, 1, 5), (0, 0, 0, 12)])
+        np.testing.assert_allclose(rows[0][0], out[1, 0, 1, 5], rtol=0, atol=1e-12)
+        np.testing.assert_allclose(rows[1][1], lse[0, 0, 0, 12], rtol=0, atol=1e-12)
