@@ -291,6 +291,31 @@ def time_custom(steps, warmup):
         flops = pairs * d["B"] * d["H"] * 4 * d["D"]
         res.append(dict(variant=name, ms=ms, tflops=flops / (ms * 1e-3) / 1e12, compile_s=compile_s))
         print(f"# {name}: {ms:.4f} ms  {res[-1]['tflops']:.1f} TFLOP/s  (compiled in {compile_s:.1f} s)", file=sys.stderr, flush=True)
+    # the document mask of the paper's grid (12 documents, S = 4096, B = 4, 16 heads, D = 64): through the
+    # descriptor (per-token ids in aux, tiles of other documents skipped) and as an expression over the same
+    # id arrays captured by the variant (every tile computed, the paper's own behaviour)
+    wd = inputs.grid_bf16("document_mask", 4096)
+    dd = runner.upload(wd, out_dtype="same")
+    ids = dd.keep[0]
+    pairs = unmasked_pairs(wd)
+    for name, var in (("document mask (descriptor, tile skipper)", None),
+                      ("document mask as an expression over captured id arrays",
+                       fb.CustomVariant(None, "aux0[b * Sq + i] != aux1[b * Sk + j]", wd.dims["D"], aux=[ids, ids]))):
+        call = (lambda: dd.run_checked(stream)) if var is None else \
+            (lambda: fb.check(var.forward(dd.tq, dd.tk, dd.tv, float(wd.scale), dd.tout, dd.tlse, stream)))
+        for _ in range(warmup):
+            call()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        flops = pairs * wd.dims["H"] * 4 * wd.dims["D"]
+        res.append(dict(variant=name, ms=ms, tflops=flops / (ms * 1e-3) / 1e12, compile_s=0.0))
+        print(f"# {name}: {ms:.4f} ms  {res[-1]['tflops']:.1f} TFLOP/s", file=sys.stderr, flush=True)
     return res
 
 

@@ -252,7 +252,8 @@ typedef struct fl_custom_variant fl_custom_variant;
  *   base_mask       FL_MASK_CAUSAL / FL_MASK_WINDOW / FL_MASK_PREFIX bits OR-ed into the mask: these the
  *                   kernel knows in closed form, so tiles they hide are skipped and tiles they leave
  *                   fully visible skip the mask arithmetic (when there is no mask_expr).
- *   D               head dim (= Dv), 64 or 128; bf16 inputs.
+ *   D               head dim (= Dv), 64 or 128; bf16 inputs.  (At 128 the kernel takes 256 query rows per
+ *                   workgroup on eight waves, at 64 it takes 128 rows on four.)
  * An expression is one C expression (no ; { } # quotes or backslashes).  FL_ERR_DESC with the
  * compiler's first error in fl_last_error_detail() if it does not compile.  Needs no GPU.       */
 fl_status fl_compile_variant(const char* score_mod_expr, const char* mask_expr, uint32_t base_mask, int D,
@@ -264,6 +265,25 @@ fl_status fl_compile_variant(const char* score_mod_expr, const char* mask_expr, 
 fl_status fl_attn_fwd_custom(fl_custom_variant* variant, const fl_tensor* q, const fl_tensor* k, const fl_tensor* v,
                              float scale, int32_t window, int32_t prefix_len, fl_tensor* out, fl_tensor* lse,
                              void* stream);
+
+/* fl_compile_variant for expressions that read caller-supplied device arrays, as the score_mod / mask_mod
+ * closures of Sec. 2.2 capture tensors (the per-token document ids of the document mask of Sec. 4.1, a
+ * learned relative-position bias table, per-head slopes): inside both expressions
+ *   aux0 .. aux3   are pointers to the arrays given at call time, typed by aux_dtypes[n]:
+ *                  FL_I32 -> const int*, FL_F32 -> const float*, FL_BF16 -> elements that read as float;
+ *                  0 -> that name does not exist.  Index arithmetic is the expression's own, e.g.
+ *                  mask_expr "aux0[b * Sq + i] != aux1[b * Sk + j]", score_mod_expr "s + aux2[h * 64 + min(i - j, 63)]".
+ *   B, G, H, Sq, Sk  are the sizes of the call.
+ * aux_dtypes may be NULL (no arrays: the same as fl_compile_variant).  The library cannot check what an
+ * expression indexes: an out-of-range index is the caller's error, as in any kernel the caller writes.  */
+fl_status fl_compile_variant_aux(const char* score_mod_expr, const char* mask_expr, uint32_t base_mask, int D,
+                                 const int32_t* aux_dtypes, fl_custom_variant** handle);
+
+/* fl_attn_fwd_custom with the arrays the variant's expressions read: aux_ptrs[n] is a DEVICE pointer for every
+ * n whose dtype was given at compile time (FL_ERR_AUX_MISSING otherwise); the other entries are ignored.  */
+fl_status fl_attn_fwd_custom_aux(fl_custom_variant* variant, const fl_tensor* q, const fl_tensor* k, const fl_tensor* v,
+                                 float scale, int32_t window, int32_t prefix_len, const void* const* aux_ptrs,
+                                 fl_tensor* out, fl_tensor* lse, void* stream);
 
 /* Unloads and frees a compiled variant (no launch of it may be in flight). */
 void fl_release_variant(fl_custom_variant* variant);

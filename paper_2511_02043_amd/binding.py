@@ -95,6 +95,12 @@ def lib() -> C.CDLL:
         L.fl_compile_variant.argtypes = [C.c_char_p, C.c_char_p, C.c_uint32, C.c_int, C.POINTER(C.c_void_p)]
         L.fl_attn_fwd_custom.restype = C.c_int
         L.fl_attn_fwd_custom.argtypes = [C.c_void_p, TP, TP, TP, C.c_float, C.c_int32, C.c_int32, TP, TP, C.c_void_p]
+        L.fl_compile_variant_aux.restype = C.c_int
+        L.fl_compile_variant_aux.argtypes = [C.c_char_p, C.c_char_p, C.c_uint32, C.c_int, C.POINTER(C.c_int32),
+                                             C.POINTER(C.c_void_p)]
+        L.fl_attn_fwd_custom_aux.restype = C.c_int
+        L.fl_attn_fwd_custom_aux.argtypes = [C.c_void_p, TP, TP, TP, C.c_float, C.c_int32, C.c_int32,
+                                             C.POINTER(C.c_void_p), TP, TP, C.c_void_p]
         L.fl_release_variant.restype = None
         L.fl_release_variant.argtypes = [C.c_void_p]
         L.fl_variant_supported.restype = C.c_int
@@ -112,7 +118,7 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ["fl_attn_fwd", "fl_attn_fwd_noalloc", "fl_attn_fwd_workspace_size", "fl_attn_bwd", "fl_attn_bwd_workspace_size",
-           "fl_bwd_supported", "fl_attn_decode", "fl_attn_decode_workspace_size", "fl_compile_variant", "fl_attn_fwd_custom",
+           "fl_bwd_supported", "fl_attn_decode", "fl_attn_decode_workspace_size", "fl_compile_variant", "fl_attn_fwd_custom", "fl_compile_variant_aux", "fl_attn_fwd_custom_aux",
            "fl_release_variant", "fl_variant_supported", "fl_strerror",
            "fl_last_error_detail", "fl_set_tuning", "fl_version"]
 
@@ -241,6 +247,24 @@ def fl_attn_fwd_custom(handle, q: fl_tensor, k: fl_tensor, v: fl_tensor, scale: 
                                     _ref(lse), C.c_void_p(stream))
 
 
+def fl_compile_variant_aux(score_mod: Optional[str], mask: Optional[str], D: int, aux=(), base_mask: int = 0):
+    """aux: up to four torch tensors (or dtype codes) that the expressions read as aux0 .. aux3.
+    Returns (status, handle)."""
+    h = C.c_void_p()
+    codes = (C.c_int32 * 4)(*([(_dtype_code(a) if hasattr(a, "dtype") else int(a or 0)) for a in aux] + [0] * (4 - len(aux))))
+    st = lib().fl_compile_variant_aux(None if score_mod is None else score_mod.encode(),
+                                      None if mask is None else mask.encode(), base_mask, D, codes, C.byref(h))
+    return st, h
+
+
+def fl_attn_fwd_custom_aux(handle, q: fl_tensor, k: fl_tensor, v: fl_tensor, scale: float, aux, out: fl_tensor,
+                           lse: Optional[fl_tensor] = None, stream: int = 0, window: int = 0, prefix_len: int = 0) -> int:
+    """aux: the device tensors for aux0 .. aux3 (None for unused slots).  Returns the fl_status code."""
+    ptrs = (C.c_void_p * 4)(*([(None if a is None else a.data_ptr()) for a in aux] + [None] * (4 - len(aux))))
+    return lib().fl_attn_fwd_custom_aux(handle, _ref(q), _ref(k), _ref(v), C.c_float(scale), window, prefix_len, ptrs,
+                                        _ref(out), _ref(lse), C.c_void_p(stream))
+
+
 def fl_release_variant(handle) -> None:
     lib().fl_release_variant(handle)
 
@@ -248,13 +272,20 @@ def fl_release_variant(handle) -> None:
 class CustomVariant:
     """A variant compiled at run time from a score_mod and / or a mask expression (C syntax)."""
 
-    def __init__(self, score_mod: Optional[str], mask: Optional[str], D: int, base_mask: int = 0):
-        st, h = fl_compile_variant(score_mod, mask, D, base_mask)
+    def __init__(self, score_mod: Optional[str], mask: Optional[str], D: int, base_mask: int = 0, aux=()):
+        """aux: up to four device tensors the expressions read as aux0 .. aux3 (kept alive by this object)."""
+        self.aux = list(aux)
+        if self.aux:
+            st, h = fl_compile_variant_aux(score_mod, mask, D, self.aux, base_mask)
+        else:
+            st, h = fl_compile_variant(score_mod, mask, D, base_mask)
         check(st)
         self.handle = h
 
     def forward(self, q: fl_tensor, k: fl_tensor, v: fl_tensor, scale: float, out: fl_tensor,
                 lse: Optional[fl_tensor] = None, stream: int = 0, window: int = 0, prefix_len: int = 0) -> int:
+        if self.aux:
+            return fl_attn_fwd_custom_aux(self.handle, q, k, v, scale, self.aux, out, lse, stream, window, prefix_len)
         return fl_attn_fwd_custom(self.handle, q, k, v, scale, out, lse, stream, window, prefix_len)
 
     def release(self) -> None:

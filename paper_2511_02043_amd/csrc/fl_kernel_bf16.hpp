@@ -296,7 +296,7 @@ struct Wave {
         const float d = slope_l2 * (float)(i[rb] + p.q_off - j0 - 32 * nb - 4 * half);
         x = fmaf(x, c_scale, -fabsf(d - alibi_c[r]));
       } else if constexpr (C::MOD == kModCustom) {
-        x = fl_user_score_mod(x * p.scale, b, g, h, i[rb] + p.q_off, j) * kLog2e;
+        x = fl_user_score_mod(x * p.scale, b, g, h, i[rb] + p.q_off, j, p) * kLog2e;
       } else {
         x *= c_scale;
       }
@@ -430,7 +430,7 @@ struct Wave {
           bool hide = c > d_hi[rb];
           if constexpr ((MASK & kMaskWindow) != 0) hide = hide || c < d_lo[rb];
           if constexpr ((MASK & kMaskDoc) != 0) hide = hide || kd[r] != qdoc[rb];
-          if constexpr ((MASK & kMaskCustom) != 0) hide = hide || fl_user_mask(b, g, h, i[rb] + p.q_off, jl + c);
+          if constexpr ((MASK & kMaskCustom) != 0) hide = hide || fl_user_mask(b, g, h, i[rb] + p.q_off, jl + c, p);
           if (hide) sc[rb][nb][r] = -INFINITY;
         }
     }

@@ -88,13 +88,15 @@ struct FwdParams {
   int32_t bias_lds_wave; // bytes of staging per wave (two buffers for every bias up to the last staged one)
   int32_t pair;          // bf16 kernels: 1 = a workgroup takes q-tiles nq - 1 - i and i (balanced causal work)
   int32_t q_off;         // query row i sits at sequence position i + q_off (positional masks, ALiBi); >= 0
+  const void* user_aux[4];   // run-time compiled variants: the caller's device arrays that the expressions read
 };
 
 }  // namespace fl
-// new score from the scaled score s of query i and key j (Eq. 4's score_mod)
-__device__ float fl_user_score_mod(float s, int b, int g, int h, int i, int j);
+// new score from the scaled score s of query i and key j (Eq. 4's score_mod); p gives the expression
+// the call's sizes and the caller's captured arrays
+__device__ float fl_user_score_mod(float s, int b, int g, int h, int i, int j, const fl::FwdParams& p);
 // true where the score of (i, j) is to be replaced by -inf (the mask_mod of Sec. 2.2, inverted)
-__device__ bool fl_user_mask(int b, int g, int h, int i, int j);
+__device__ bool fl_user_mask(int b, int g, int h, int i, int j, const fl::FwdParams& p);
 namespace fl {
 
 // Compile-time loop: f(std::integral_constant<int, I>) for I in [B, E).

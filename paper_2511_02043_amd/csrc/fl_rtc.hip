@@ -26,6 +26,8 @@ namespace {
 
 struct fl_custom_variant {
   int D = 0;
+  int waves = 4;                   // waves per workgroup of the instantiated kernel shape
+  int aux_dtype[4] = {0, 0, 0, 0}; // element types of the arrays the expressions read (0: not used)
   unsigned mask = 0;               // mask bits the kernel was instantiated with
   std::vector<char> code;          // the compiled code object
   std::string kernel_name;         // lowered name of the instantiated kernel
@@ -36,8 +38,10 @@ struct fl_custom_variant {
 
 namespace {
 
-// Kernel shape of the generated variants: 4 waves x 32 query rows, 64-key tiles, two waves per SIMD.
-constexpr int kWaves = 4, kBN = 64, kBM = 128;
+// Kernel shape of the generated variants: 32 query rows per wave, 64-key tiles, two waves per SIMD; eight
+// waves per workgroup at head dim 128 (the shape the compiled causal / plain kernels default to), four at 64.
+constexpr int kBN = 64;
+constexpr int waves_for(int D) { return D == 128 ? 8 : 4; }
 
 bool expression_ok(const char* e) {
   // one C expression: no statement separators, braces, preprocessor lines or string literals
@@ -171,6 +175,11 @@ extern "C" {
 
 fl_status fl_compile_variant(const char* score_mod_expr, const char* mask_expr, uint32_t base_mask, int D,
                              fl_custom_variant** handle) {
+  return fl_compile_variant_aux(score_mod_expr, mask_expr, base_mask, D, nullptr, handle);
+}
+
+fl_status fl_compile_variant_aux(const char* score_mod_expr, const char* mask_expr, uint32_t base_mask, int D,
+                                 const int32_t* aux_dtypes, fl_custom_variant** handle) {
   fl::host::clear_detail();
   if (handle == nullptr) return fl::host::fail(FL_ERR_NULL, "handle is NULL");
   *handle = nullptr;
@@ -184,14 +193,32 @@ fl_status fl_compile_variant(const char* score_mod_expr, const char* mask_expr, 
   if ((score_mod_expr && !expression_ok(score_mod_expr)) || (mask_expr && !expression_ok(mask_expr)))
     return fl::host::fail(FL_ERR_DESC, "an expression may not contain ; { } # \" \\ or a line break");
 
+  int adt[4] = {0, 0, 0, 0};
+  for (int n = 0; n < 4 && aux_dtypes != nullptr; ++n) {
+    adt[n] = aux_dtypes[n];
+    if (adt[n] != 0 && adt[n] != FL_BF16 && adt[n] != FL_F32 && adt[n] != FL_I32)
+      return fl::host::fail(FL_ERR_DTYPE, "aux_dtypes[%d] = %d: 0 (unused), FL_BF16, FL_F32 or FL_I32", n, adt[n]);
+  }
+
   const int mod = score_mod_expr ? fl::kModCustom : fl::kModNone;
   const unsigned mask = (mask_expr ? fl::kMaskCustom : 0u) | base_mask;
   char inst[256];
-  snprintf(inst, sizeof(inst), "fl::fwd_bf16_kernel<fl::Bf16Cfg<%d, %d, %d, 1, %d, 2, %d, %uu, 0, false, 0u>>", D, D, kWaves, kBN, mod, mask);
+  snprintf(inst, sizeof(inst), "fl::fwd_bf16_kernel<fl::Bf16Cfg<%d, %d, %d, 1, %d, 2, %d, %uu, 0, false, 0u>>", D, D, waves_for(D), kBN, mod, mask);
+  // what an expression sees besides its arguments: the call's sizes and the captured arrays aux0 .. aux3
+  // (bf16 arrays read as float through a one-field wrapper)
+  std::string scope = "  const int B = fl_p.B, G = fl_p.G, H = fl_p.H, Sq = fl_p.Sq, Sk = fl_p.Sk; (void)B; (void)G; (void)H; (void)Sq; (void)Sk;\n";
+  for (int n = 0; n < 4; ++n) {
+    if (adt[n] == 0) continue;
+    const char* ty = adt[n] == FL_I32 ? "int" : (adt[n] == FL_F32 ? "float" : "fl_bf16_elem");
+    char line[160];
+    snprintf(line, sizeof(line), "  const %s* aux%d = (const %s*)fl_p.user_aux[%d]; (void)aux%d;\n", ty, n, ty, n, n);
+    scope += line;
+  }
   std::string src = "#include \"fl_kernel_bf16.hpp\"\n";
-  src += "__device__ float fl_user_score_mod(float s, int b, int g, int h, int i, int j) { return (";
+  src += "struct fl_bf16_elem { unsigned short u; __device__ operator float() const { return __uint_as_float((unsigned)u << 16); } };\n";
+  src += "__device__ float fl_user_score_mod(float s, int b, int g, int h, int i, int j, const fl::FwdParams& fl_p) {\n" + scope + "  return (";
   src += score_mod_expr ? score_mod_expr : "s";
-  src += "); }\n__device__ bool fl_user_mask(int b, int g, int h, int i, int j) { return (";
+  src += "); }\n__device__ bool fl_user_mask(int b, int g, int h, int i, int j, const fl::FwdParams& fl_p) {\n" + scope + "  return (";
   src += mask_expr ? mask_expr : "false";
   src += "); }\ntemplate __global__ void ";
   src += inst;
@@ -199,6 +226,8 @@ fl_status fl_compile_variant(const char* score_mod_expr, const char* mask_expr, 
 
   fl_custom_variant* v = new fl_custom_variant;
   v->D = D;
+  v->waves = waves_for(D);
+  for (int n = 0; n < 4; ++n) v->aux_dtype[n] = adt[n];
   v->mask = mask;
   const fl_status st = compile_instance(src, inst, "expression does not compile", &v->code, &v->kernel_name);
   if (st != FL_OK) {
@@ -218,11 +247,20 @@ void fl_release_variant(fl_custom_variant* v) {
 
 fl_status fl_attn_fwd_custom(fl_custom_variant* v, const fl_tensor* q, const fl_tensor* k, const fl_tensor* vv, float scale,
                              int32_t window, int32_t prefix_len, fl_tensor* out, fl_tensor* lse, void* stream_v) {
+  return fl_attn_fwd_custom_aux(v, q, k, vv, scale, window, prefix_len, nullptr, out, lse, stream_v);
+}
+
+fl_status fl_attn_fwd_custom_aux(fl_custom_variant* v, const fl_tensor* q, const fl_tensor* k, const fl_tensor* vv, float scale,
+                                 int32_t window, int32_t prefix_len, const void* const* aux_ptrs, fl_tensor* out, fl_tensor* lse,
+                                 void* stream_v) {
   fl::host::clear_detail();
   if (v == nullptr || q == nullptr || k == nullptr || vv == nullptr || out == nullptr)
     return fl::host::fail(FL_ERR_NULL, "handle, q, k, v or out is NULL");
   if (!(scale > 0.f) || scale != scale || scale > 3.0e38f) return fl::host::fail(FL_ERR_DESC, "scale must be finite and > 0");
   if (q->dtype != FL_BF16) return fl::host::fail(FL_ERR_DTYPE, "custom variants take bf16 inputs");
+  for (int n = 0; n < 4; ++n)
+    if (v->aux_dtype[n] != 0 && (aux_ptrs == nullptr || aux_ptrs[n] == nullptr))
+      return fl::host::fail(FL_ERR_AUX_MISSING, "this variant reads aux%d, which was not given", n);
   if ((v->mask & FL_MASK_WINDOW) && window < 0) return fl::host::fail(FL_ERR_DESC, "window must be >= 0");
   if ((v->mask & FL_MASK_PREFIX) && prefix_len < 0) return fl::host::fail(FL_ERR_DESC, "prefix_len must be >= 0");
   const int64_t B = q->size[0], G = q->size[1], H = q->size[2], Sq = q->size[3], D = q->size[4];
@@ -280,6 +318,8 @@ fl_status fl_attn_fwd_custom(fl_custom_variant* v, const fl_tensor* q, const fl_
   p.window = (int64_t)window > (Sq > Sk ? Sq : Sk) ? (int32_t)(Sq > Sk ? Sq : Sk) : window;   // keeps i - window clear of int32 overflow
   p.prefix = prefix_len;
   p.out_f32 = out->dtype == FL_F32;
+  for (int n = 0; n < 4; ++n) p.user_aux[n] = (aux_ptrs != nullptr && v->aux_dtype[n] != 0) ? aux_ptrs[n] : nullptr;
+  const int kBM = 32 * v->waves;
   p.n_qtiles = (int)((Sq + kBM - 1) / kBM);
   p.lds_bytes = 4 * kBN * (int)D * 2;              // K ring and V ring of two 64-key tiles each
   const int64_t nbh = B * G * H;
@@ -290,7 +330,7 @@ fl_status fl_attn_fwd_custom(fl_custom_variant* v, const fl_tensor* q, const fl_
   const int64_t nblocks = nbh * (p.pair ? (p.n_qtiles + 1) / 2 : p.n_qtiles);
   if (nblocks > 0x7fffffffLL) return fl::host::fail(FL_ERR_SHAPE, "too many workgroups");
   void* args[] = {&p};
-  e = hipModuleLaunchKernel(v->func[dev], (unsigned)nblocks, 1, 1, kWaves * 64, 1, 1, (unsigned)p.lds_bytes, (hipStream_t)stream_v, args, nullptr);
+  e = hipModuleLaunchKernel(v->func[dev], (unsigned)nblocks, 1, 1, (unsigned)v->waves * 64, 1, 1, (unsigned)p.lds_bytes, (hipStream_t)stream_v, args, nullptr);
   if (e != hipSuccess) return fl::host::fail(FL_ERR_LAUNCH, "custom variant launch: %s", hipGetErrorString(e));
   return FL_OK;
 }

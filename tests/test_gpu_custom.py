@@ -113,3 +113,49 @@ def test_chunked_prefill_offset_as_a_custom_mask(D):
     assert float(np.max(np.abs(dw.out.cpu().numpy() - ref))) <= 1e-2
     assert float(np.max(np.abs(dw.lse.cpu().numpy()[..., 0] - ref_lse))) <= 1e-3
     var.release()
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_expressions_that_capture_tensors(D):
+    """The closures of Sec. 2.2 capture tensors: a document mask written as an expression over the per-token
+    id arrays (Sec. 4.1), on top of a causal base mask, and a learned relative-position bias read from a
+    bf16 table per head plus per-head fp32 slopes; against the oracle's callable form with the same arrays."""
+    import torch
+    dev = "cuda:0"
+    B, H, S = 2, 4, 333
+    w = inputs.causal_bf16(B=B, H=H, Hkv=2, S=S, D=D, causal=False, salt=9)
+    ids = inputs.doc_ids(B, S, seed=77, lo=20, hi=120)
+    table = inputs.normal((H, 64), inputs.tensor_seed(9, 7), "bf16")          # bias by clipped distance, per head
+    slopes = (0.01 * (1 + np.arange(H))).astype(np.float32)
+    t_ids = torch.from_numpy(ids).to(dev)
+    t_table = torch.from_numpy(table.astype(np.float32)).to(dev, torch.bfloat16)
+    t_slopes = torch.from_numpy(slopes).to(dev)
+    var = fb.CustomVariant("s + aux2[h * 64 + min(abs(i - j), 63)] - aux3[h] * (float)(i - j)",
+                           "aux0[b * Sq + i] != aux1[b * Sk + j]", D, base_mask=fb.FL_MASK_CAUSAL,
+                           aux=[t_ids, t_ids, t_table, t_slopes])
+    dw = runner.upload(w, out_dtype="f32")
+    dw.out.fill_(float("nan"))
+    fb.check(var.forward(dw.tq, dw.tk, dw.tv, float(w.scale), dw.tout, dw.tlse))
+    torch.cuda.synchronize()
+    tab64 = table.astype(np.float64)
+    ref, ref_lse = ao.attention_custom(
+        w.q, w.k, w.v, scale=w.scale,
+        score_mod=lambda s, b, g, h, i, j: s + tab64[h][np.minimum(np.abs(i - j), 63)] - np.float64(slopes[h]) * (i - j),
+        mask=lambda b, g, h, i, j: (j > i) | (ids[b][:, None] != ids[b][None, :]))
+    got, got_lse = dw.out.cpu().numpy(), dw.lse.cpu().numpy()[..., 0]
+    err = float(np.max(np.abs(got - ref)))
+    le = float(np.max(np.abs(got_lse - ref_lse)))
+    print(f"captured tensors D={D}: max_abs={err:.3e} lse={le:.3e}", flush=True)
+    assert err <= 1e-2 and le <= 1e-3
+    # the same document mask through the descriptor (ids in aux, tile skipping): the same result up to the
+    # bf16 rounding of the probabilities (the two kernels differ in tile shape and running-max reference)
+    wd = inputs.causal_bf16(B=B, H=H, Hkv=2, S=S, D=D, causal=True, salt=9)
+    wd.q_doc = wd.kv_doc = ids
+    var2 = fb.CustomVariant(None, "aux0[b * Sq + i] != aux1[b * Sk + j]", D, base_mask=fb.FL_MASK_CAUSAL, aux=[t_ids, t_ids])
+    dd = runner.upload(wd, out_dtype="f32")
+    dd.run_checked()
+    fb.check(var2.forward(dw.tq, dw.tk, dw.tv, float(w.scale), dw.tout, dw.tlse))
+    torch.cuda.synchronize()
+    assert float((dd.out - dw.out).abs().max()) <= 1e-2
+    # a variant that reads an array refuses a call without it
+    assert fb.fl_attn_fwd_custom(var2.handle, dw.tq, dw.tk, dw.tv, float(w.scale), dw.tout, dw.tlse) == fb.FL_ERR_AUX_MISSING
