@@ -26,6 +26,18 @@ With grouped-query attention the dK / dV of a key/value head are the sums over t
 heads that read it.  Masked positions have P = 0 and therefore dS = 0; a row whose keys are
 all masked contributes nothing.
 
+Additive biases enter s after the score_mod and before the mask, so dBias = dS summed over the
+axes the bias broadcasts along.  The epilogues and the second softmax stream (variant_backward):
+
+    x  = O1 - lambda_h O2                       differential listing (x = O for one stream)
+    y  = w * x / r,  r = sqrt(mean_c x_c^2 + eps)        RMSNorm (benchmark configuration)
+    out = sigmoid(g) * y                        gate
+
+    dy = dout * sigmoid(g),   dg = dout * y * sigmoid(g) (1 - sigmoid(g))
+    dx = w dy / r - x (sum_c w_c dy_c x_c) / (Dv r^3)
+    dO1 = dx,  dO2 = -lambda_h dx,  dlambda_h = - sum_{rows, c} dx * O2
+    then the softmax / contraction derivative above per stream; dV is the sum of both streams'.
+
 Pins (tests/test_oracle_backward_pins.py): central finite differences of the forward oracle
 on every variant; autograd through PyTorch's fp64 CPU scaled_dot_product_attention;
 closed forms for Q = 0; the identities sum_j dV_j = sum_i dO_i and rowsum(dS) = 0;
@@ -69,12 +81,14 @@ def attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray, dout: np.nda
                        prefix: Optional[int] = None, softcap_value: Optional[float] = None,
                        alibi_slopes: Optional[np.ndarray] = None,
                        q_doc: Optional[np.ndarray] = None, kv_doc: Optional[np.ndarray] = None,
-                       return_delta: bool = False):
+                       return_delta: bool = False, biases=(), return_dbias: bool = False):
     """Gradients of sum(out * dout) with respect to q, k, v.
 
-    q [B,G,H,Sq,D], k [B,G,Hkv,Sk,D], v [B,G,Hkv,Sk,Dv], dout [B,G,H,Sq,Dv].
+    q [B,G,H,Sq,D], k [B,G,Hkv,Sk,D], v [B,G,Hkv,Sk,Dv], dout [B,G,H,Sq,Dv]; biases: arrays that
+    broadcast to [B,G,H,Sq,Sk], added to the score after the score_mod (forward pipeline order).
     Returns dq, dk, dv (float64, shapes of q, k, v); with return_delta also
-    delta [B,G,H,Sq] = rowsum(P * dP).
+    delta [B,G,H,Sq] = rowsum(P * dP); with return_dbias also a list with the gradient of each
+    bias in the bias's own shape (dS summed over the axes it broadcasts along).
     """
     B, G, H, Sq, D = q.shape
     Hkv, Sk, Dv = k.shape[2], k.shape[3], v.shape[4]
@@ -84,6 +98,8 @@ def attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray, dout: np.nda
     dk = np.zeros((B, G, Hkv, Sk, D))
     dv = np.zeros((B, G, Hkv, Sk, Dv))
     delta = np.zeros((B, G, H, Sq))
+    full_biases = [np.broadcast_to(np.asarray(bb, dtype=np.float64), (B, G, H, Sq, Sk)) for bb in biases]
+    ds_all = np.zeros((B, G, H, Sq, Sk)) if (return_dbias and biases) else None
     dist = np.abs(np.arange(Sq)[:, None] - np.arange(Sk)[None, :]).astype(np.float64)
     for b in range(B):
         masked = mask_matrix(Sq, Sk, causal=causal, window=window, prefix=prefix,
@@ -104,20 +120,85 @@ def attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray, dout: np.nda
                     s = z
                 if alibi_slopes is not None:
                     s = s - float(alibi_slopes[h]) * dist
+                for fb_ in full_biases:
+                    s = s + fb_[b, g, h]
                 s = np.where(masked, -np.inf, s)
                 p = softmax_rows(s)
                 dv[b, g, hk] += p.T @ do
                 dp = do @ vh.T
                 row = np.sum(p * dp, axis=1)
                 ds = p * (dp - row[:, None])
+                if ds_all is not None:
+                    ds_all[b, g, h] = ds               # gradient of the score after the score_mod
                 if softcap_value is not None:
                     ds = ds * (1.0 - t * t)
                 dq[b, g, h] = scale * (ds @ kh)
                 dk[b, g, hk] += scale * (ds.T @ qh)
                 delta[b, g, h] = row
+    res = (dq, dk, dv)
     if return_delta:
-        return dq, dk, dv, delta
-    return dq, dk, dv
+        res = res + (delta,)
+    if return_dbias:
+        dbs = []
+        for bb in biases:
+            axes = tuple(a for a in range(5) if np.asarray(bb).shape[a] == 1 and (B, G, H, Sq, Sk)[a] != 1)
+            dbs.append(np.sum(ds_all, axis=axes, keepdims=True) if axes else ds_all.copy())
+        res = res + (dbs,)
+    return res
+
+
+def variant_backward(w, dout):
+    """Gradients of sum(out * dout) for every part of an inputs.Workload (duck-typed): biases, the second
+    softmax stream with lambda, RMSNorm and the sigmoid gate included.  Returns a dict with dq, dk, dv and,
+    where the workload has them, dq2, dk2, dlambda [H], dbias (list), dgate, drms_weight [Dv]."""
+    from oracle import attention_oracle as ao            # the pinned forward oracle gives the intermediates
+    variant = dict(scale=w.scale, causal=w.causal, window=w.window, prefix=w.prefix, softcap_value=w.softcap,
+                   alibi_slopes=w.alibi, q_doc=w.q_doc, kv_doc=w.kv_doc)
+    fwd = dict(variant)
+    fwd["biases"] = w.biases
+    dout = np.asarray(dout, dtype=np.float64)
+    B, G, H, Sq, _ = w.q.shape
+    Dv = w.v.shape[4]
+    o1, _ = ao.attention(w.q, w.k, w.v, **fwd)
+    diff = w.q2 is not None
+    if diff:
+        o2, _ = ao.attention(w.q2, w.k2, w.v, **fwd)
+        lam = np.asarray(w.lam, dtype=np.float64)[None, None, :, None, None]
+        x = o1 - lam * o2
+    else:
+        x = o1
+    y = x
+    if w.rmsnorm:
+        wt = np.ones(Dv) if w.rms_weight is None else np.asarray(w.rms_weight, dtype=np.float64)
+        r = np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + w.rms_eps)
+        y = wt * x / r
+    out = {}
+    dy = dout
+    if w.gate is not None:
+        sg = 1.0 / (1.0 + np.exp(-np.asarray(w.gate, dtype=np.float64)))
+        out["dgate"] = dout * y * sg * (1.0 - sg)
+        dy = dout * sg
+    dx = dy
+    if w.rmsnorm:
+        out["drms_weight"] = np.sum(dy * x / r, axis=(0, 1, 2, 3))
+        dot = np.sum(wt * dy * x, axis=-1, keepdims=True)
+        dx = wt * dy / r - x * dot / (Dv * r ** 3)
+    do1 = dx
+    if diff:
+        out["dlambda"] = -np.sum(dx * o2, axis=(0, 1, 3, 4))
+        do2 = -lam * dx
+    need_db = len(w.biases) > 0
+    r1 = attention_backward(w.q, w.k, w.v, do1, biases=w.biases, return_dbias=need_db, **variant)
+    out["dq"], out["dk"], out["dv"] = r1[0], r1[1], r1[2]
+    if need_db:
+        out["dbias"] = r1[3]
+    if diff:
+        r2 = attention_backward(w.q2, w.k2, w.v, do2, biases=w.biases, return_dbias=need_db, **variant)
+        out["dq2"], out["dk2"] = r2[0], r2[1]
+        out["dv"] = out["dv"] + r2[2]
+        if need_db:
+            out["dbias"] = [a + b for a, b in zip(out["dbias"], r2[3])]
+    return out
 
 
 def run_workload_backward(w, dout):

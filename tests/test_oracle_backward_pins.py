@@ -212,3 +212,147 @@ def test_gqa_sums_over_the_group():
     np.testing.assert_allclose(dq, dq_r, atol=1e-14)
     np.testing.assert_allclose(dk, dk_r.reshape(1, 1, 2, 2, S, D).sum(axis=3), atol=1e-14)
     np.testing.assert_allclose(dv, dv_r.reshape(1, 1, 2, 2, S, D).sum(axis=3), atol=1e-14)
+
+
+# ---------------------------------------------------------------------------------------
+# 6. Biases, gate, differential streams and RMSNorm (variant_backward): central finite differences of
+#    the pinned forward oracle in every input, and autograd through an fp64 torch program built from
+#    the library routine scaled_dot_product_attention (float mask = bias), sigmoid and elementwise ops.
+# ---------------------------------------------------------------------------------------
+
+def small_combo(diff, rms, gate, n_bias, mods, seed):
+    w = inputs.combination_bf16(D=8, Dv=6, score_mod=mods[0], pos_mask=mods[1], doc=mods[2], n_bias=n_bias, diff=diff,
+                                rmsnorm=rms, gate=gate, B=2, G=2, H=2, S=11, window=4, prefix=5, cap=1.3, salt=seed)
+    # full-precision random values instead of bf16-rounded ones: the finite differences need smooth inputs
+    for n, f in enumerate(("q", "k", "v", "q2", "k2", "gate")):
+        x = getattr(w, f)
+        if x is not None:
+            setattr(w, f, rand(x.shape, seed * 31 + n))
+    w.biases = tuple(rand(b.shape, seed * 7 + n) for n, b in enumerate(w.biases))
+    if w.lam is not None:
+        w.lam = np.array([0.35, 0.8])
+    return w
+
+
+COMBOS = {
+    "bias1": dict(diff=False, rms=False, gate=False, n_bias=1, mods=("none", "none", False)),
+    "bias2_gate_causal": dict(diff=False, rms=False, gate=True, n_bias=2, mods=("none", "causal", False)),
+    "gate_softcap_window": dict(diff=False, rms=False, gate=True, n_bias=0, mods=("softcap", "window", False)),
+    "rms_alone_prefix": dict(diff=False, rms=True, gate=False, n_bias=0, mods=("none", "prefix", False)),
+    "diff_causal": dict(diff=True, rms=False, gate=False, n_bias=0, mods=("none", "causal", False)),
+    "diff_rms_causal": dict(diff=True, rms=True, gate=False, n_bias=0, mods=("none", "causal", False)),
+    "diff_rms_gate_bias_alibi_doc": dict(diff=True, rms=True, gate=True, n_bias=1, mods=("alibi", "causal", True)),
+}
+
+
+@pytest.mark.parametrize("name", list(COMBOS))
+def test_variant_backward_finite_differences(name):
+    w = small_combo(seed=3, **COMBOS[name])
+    dout = rand(w.q.shape[:4] + (w.v.shape[4],), 99)
+    g = bo.variant_backward(w, dout)
+
+    def loss():
+        out, _ = ao.run_workload(w)
+        return float(np.sum(out * dout))
+
+    fields = [("q", "dq"), ("k", "dk"), ("v", "dv")]
+    if w.q2 is not None:
+        fields += [("q2", "dq2"), ("k2", "dk2"), ("lam", "dlambda")]
+    if w.gate is not None:
+        fields.append(("gate", "dgate"))
+    if w.rmsnorm:
+        fields.append(("rms_weight", "drms_weight"))
+    r = np.random.Generator(np.random.PCG64(17))
+    eps = 1e-6
+
+    def check(arr, grad, label):
+        assert grad.shape == arr.shape, (label, grad.shape, arr.shape)
+        for _ in range(8):
+            idx = tuple(int(r.integers(0, n)) for n in arr.shape)
+            keep = arr[idx]
+            arr[idx] = keep + eps
+            lp = loss()
+            arr[idx] = keep - eps
+            lm = loss()
+            arr[idx] = keep
+            fd = (lp - lm) / (2 * eps)
+            assert abs(fd - grad[idx]) <= 2e-6 * max(1.0, abs(fd)), (label, idx, fd, grad[idx])
+
+    for field, gname in fields:
+        arr = np.array(getattr(w, field), dtype=np.float64)
+        setattr(w, field, arr)
+        check(arr, g[gname], gname)
+    biases = [np.array(b, dtype=np.float64) for b in w.biases]
+    w.biases = tuple(biases)
+    for n, b in enumerate(biases):
+        check(b, g["dbias"][n], f"dbias[{n}]")
+
+
+@pytest.mark.parametrize("name", ["bias2_gate_causal", "diff_rms_causal", "diff_rms_gate_bias_alibi_doc"])
+def test_variant_backward_matches_torch_autograd(name):
+    w = small_combo(seed=5, **COMBOS[name])
+    dout = rand(w.q.shape[:4] + (w.v.shape[4],), 98)
+    g = bo.variant_backward(w, dout)
+    B, G, H, S, D = w.q.shape
+    t = lambda x: torch.tensor(np.asarray(x, dtype=np.float64), requires_grad=True)
+    q, k, v = t(w.q), t(w.k), t(w.v)
+    biases = [t(b) for b in w.biases]
+    i = np.arange(S)[:, None]
+    j = np.arange(S)[None, :]
+    hidden = np.zeros((B, 1, 1, S, S), dtype=bool)
+    if w.causal:
+        hidden |= (j > i)
+    if w.q_doc is not None:
+        hidden |= (w.q_doc[:, None, None, :, None] != w.kv_doc[:, None, None, None, :])
+    mask = torch.zeros(B, G, H, S, S, dtype=torch.float64)
+    if w.alibi is not None:
+        mask = mask - torch.tensor(w.alibi.astype(np.float64))[None, None, :, None, None] * torch.tensor(np.abs(i - j).astype(np.float64))
+    for b in biases:
+        mask = mask + b
+    mask = mask.masked_fill(torch.tensor(np.broadcast_to(hidden, (B, G, H, S, S)).copy()), float("-inf"))
+
+    def sdpa(q_, k_):
+        f = lambda x: x.reshape(B * G, H, S, -1)
+        return torch.nn.functional.scaled_dot_product_attention(f(q_), f(k_), f(v), attn_mask=mask.reshape(B * G, H, S, S),
+                                                                scale=w.scale).reshape(B, G, H, S, -1)
+    x = sdpa(q, k)
+    extra = {}
+    if w.q2 is not None:
+        q2, k2, lam = t(w.q2), t(w.k2), t(w.lam)
+        x = x - lam[None, None, :, None, None] * sdpa(q2, k2)
+        extra = dict(dq2=q2, dk2=k2, dlambda=lam)
+    if w.rmsnorm:
+        wt = t(w.rms_weight)
+        x = wt * x / torch.sqrt(torch.mean(x * x, dim=-1, keepdim=True) + w.rms_eps)
+        extra["drms_weight"] = wt
+    if w.gate is not None:
+        gt = t(w.gate)
+        x = torch.sigmoid(gt) * x
+        extra["dgate"] = gt
+    (x * torch.tensor(dout)).sum().backward()
+    for name_, leaf in dict(dq=q, dk=k, dv=v, **extra).items():
+        np.testing.assert_allclose(g[name_], leaf.grad.numpy(), rtol=0, atol=1e-10, err_msg=name_)
+    for n, b in enumerate(biases):
+        np.testing.assert_allclose(g["dbias"][n], b.grad.numpy(), rtol=0, atol=1e-10, err_msg=f"dbias[{n}]")
+
+
+def test_variant_backward_reduces_to_the_plain_one_and_identities():
+    w = small_combo(seed=8, diff=False, rms=False, gate=False, n_bias=0, mods=("none", "causal", False))
+    dout = rand(w.q.shape[:4] + (w.v.shape[4],), 97)
+    g = bo.variant_backward(w, dout)
+    ref = bo.attention_backward(w.q, w.k, w.v, dout, scale=w.scale, causal=True)
+    for a, b in zip((g["dq"], g["dk"], g["dv"]), ref):
+        np.testing.assert_allclose(a, b, rtol=0, atol=1e-13)
+    # a bias row-constant shift does not change the output, so the gradient of a [.., Sq, 1]-shaped bias is 0;
+    # dbias of a full bias sums to zero over keys (rowsum(dS) = 0)
+    wb = small_combo(seed=8, diff=False, rms=False, gate=True, n_bias=1, mods=("none", "none", False))
+    gb = bo.variant_backward(wb, dout)
+    np.testing.assert_allclose(np.sum(gb["dbias"][0], axis=-1), 0.0, atol=1e-12)
+    # lambda = 0: the second stream gets no gradient; identical streams: dq2 = -lambda dq / (1 - lambda) ... checked by FD above
+    wd = small_combo(seed=8, diff=True, rms=False, gate=False, n_bias=0, mods=("none", "none", False))
+    wd.lam = np.zeros(2)
+    gd = bo.variant_backward(wd, dout)
+    assert np.all(gd["dq2"] == 0) and np.all(gd["dk2"] == 0)
+    single = bo.attention_backward(wd.q, wd.k, wd.v, dout, scale=wd.scale)
+    np.testing.assert_allclose(gd["dq"], single[0], rtol=0, atol=1e-13)
+    np.testing.assert_allclose(gd["dv"], single[2], rtol=0, atol=1e-13)
