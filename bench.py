@@ -135,8 +135,7 @@ def time_config(name, steps, warmup, out_dtype="same", rotate=1, before=None):
                 gbs=byt / (ev_ms * 1e-3) / 1e9, dims=w.dims, device_workload=dws[0]), w
 
 
-BWD_HBM_BOUND = ("c3c_window_doc", "c5_evoformer")    # configurations whose roofline is HBM bandwidth (algorithmic bytes)
-CONFIGS = ["c2_d128", "c2_d64", "c3a_alibi", "c3b_softcap", "c3c_window_doc"]
+BWD_CONFIGS = ["c2_d128", "c2_d64", "c3a_alibi", "c3b_softcap", "c3c_window_doc", "c4_differential", "c5_evoformer"]
 
 
 def time_backward(name, steps, warmup):
@@ -149,7 +148,10 @@ def time_backward(name, steps, warmup):
     w = make_workload(name)
     flops, _ = flops_and_bytes(w)
     flops = flops * 5 // 2
-    db = runner.upload_backward(w, inputs.dout_for(w), grad_dtype="bf16")
+    composed = bool(w.biases) or w.gate is not None or w.q2 is not None or w.rmsnorm or w.dims["D"] != w.dims["Dv"] \
+        or w.dims["D"] not in (64, 128)
+    # biases, gate, RMSNorm, second stream, other head dims: fl_attn_bwd_ex (every gradient the variant has)
+    db = (runner.upload_backward_ex if composed else runner.upload_backward)(w, inputs.dout_for(w), grad_dtype="bf16")
     stream = torch.cuda.current_stream().cuda_stream
     db.fwd.run_checked(stream)
     for _ in range(warmup):

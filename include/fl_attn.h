@@ -192,10 +192,53 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
                       const fl_tensor* dout, const fl_tensor* lse, const fl_variant_desc* desc,
                       const fl_aux* aux, fl_tensor* dq, fl_tensor* dk, fl_tensor* dv, void* stream);
 
-/* Bytes of aux->workspace that fl_attn_bwd needs for these shapes and this descriptor. */
+/* Bytes of aux->workspace that fl_attn_bwd needs for these shapes and this descriptor (variants without
+ * bias, second stream and epilogue; for the others ask fl_attn_bwd_ex_workspace_size). */
 size_t fl_attn_bwd_workspace_size(const fl_tensor* q, const fl_tensor* k, const fl_variant_desc* desc);
 
-/* 1 if fl_attn_bwd has a kernel specialisation for (descriptor, dtype, D, Dv), else 0. */
+/* Gradient outputs beyond dq, dk, dv, for the variants whose forward pass reads more than q, k, v. */
+typedef struct {
+  uint32_t  struct_size;   /* sizeof(fl_bwd_extra) */
+  uint32_t  reserved;
+  fl_tensor dq2, dk2;      /* FL_DIFFERENTIAL: gradients of aux->q2 / aux->k2; shapes and dtypes as dq / dk; required */
+  fl_tensor dbias[2];      /* gradient of aux->bias[n]: f32 with the sizes of aux->bias[n] (an axis of size 1 that
+                              broadcasts holds the sum over that axis; those sums use atomic adds, so they are
+                              reproducible only up to fp32 summation order); ptr NULL: not computed            */
+  fl_tensor dgate;         /* FL_EPI_GATE_SIGMOID: gradient of aux->gate, shape of out, bf16 or f32; ptr NULL: not computed */
+  float*    dlambda;       /* FL_DIFFERENTIAL: [H] f32 device (atomic sums over rows); NULL: not computed      */
+} fl_bwd_extra;
+
+/* fl_attn_bwd for every variant of the forward pass: additive biases (with their gradients), the sigmoid
+ * gate, RMSNorm and the differential second stream, and the head dims the plain backward kernels do not
+ * take (D = 32, D != Dv).  The derivative is that of the forward definition (differential listing; Evoformer
+ * description in Sec. 4.1):
+ *     dy = dout * sigmoid(g),  dg = dout * y * sigmoid(g) (1 - sigmoid(g))           gate
+ *     dx = w dy / r - x (sum_c w_c dy_c x_c) / (Dv r^3),  r = sqrt(mean(x^2) + eps)  RMSNorm
+ *     dO1 = dx,  dO2 = -lambda_h dx,  dlambda_h = -sum dx * O2                       x = O1 - lambda_h O2
+ *     dbias = dS summed over the axes the bias broadcasts along
+ * and then the softmax / contraction derivative of fl_attn_bwd per stream (dv sums both streams).
+ * It is composed from the same kernels: the streams' outputs O1, O2 are recomputed with the forward kernel
+ * where RMSNorm or the second stream need them, one elementwise kernel turns dout into the per-stream dO,
+ * delta and the epilogue gradients, tensors whose head dim the backward kernels do not take are zero-padded
+ * into the workspace (D = 32 -> 64, D = 64 with Dv = 128 -> 128), and the backward kernels run once per stream.
+ *
+ *   out, lse   what fl_attn_fwd wrote (lse [B, 2G, H, Sq, 1] for FL_DIFFERENTIAL)
+ *   aux        as for fl_attn_fwd, with aux->workspace of fl_attn_bwd_ex_workspace_size bytes (16-byte aligned)
+ *   extra      may be NULL when the variant has nothing beyond dq, dk, dv to write
+ * Covered: everything fl_attn_bwd covers, plus biases with score_mod = FL_MOD_NONE under no mask or
+ * FL_MASK_CAUSAL, plus any epilogue / FL_DIFFERENTIAL on top of those; q_offset must be 0.  The gradient of
+ * rms_weight is not computed.  Same stream, ownership and error rules as fl_attn_fwd.                     */
+fl_status fl_attn_bwd_ex(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v, const fl_tensor* out,
+                         const fl_tensor* dout, const fl_tensor* lse, const fl_variant_desc* desc,
+                         const fl_aux* aux, fl_tensor* dq, fl_tensor* dk, fl_tensor* dv,
+                         const fl_bwd_extra* extra, void* stream);
+
+/* Bytes of aux->workspace that fl_attn_bwd_ex needs. */
+size_t fl_attn_bwd_ex_workspace_size(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v,
+                                     const fl_variant_desc* desc);
+
+/* 1 if fl_attn_bwd_ex (for the variants without bias, second stream and epilogue at D == Dv in {64, 128}:
+ * also fl_attn_bwd) covers (descriptor, dtype, D, Dv), else 0. */
 int fl_bwd_supported(const fl_variant_desc* desc, int dtype, int D, int Dv);
 
 /* Where the cached keys and values of each sequence live (decode step). */

@@ -43,6 +43,11 @@ class fl_aux(C.Structure):
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
 
 
+class fl_bwd_extra(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("reserved", C.c_uint32), ("dq2", fl_tensor), ("dk2", fl_tensor),
+                ("dbias", fl_tensor * 2), ("dgate", fl_tensor), ("dlambda", C.c_void_p)]
+
+
 class fl_paged_kv(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("reserved", C.c_uint32), ("block_table", C.c_void_p),
                 ("table_stride", C.c_int32), ("page_size", C.c_int32), ("seq_lens", C.c_void_p),
@@ -84,6 +89,11 @@ def lib() -> C.CDLL:
                                   TP, TP, TP, C.c_void_p]
         L.fl_attn_bwd_workspace_size.restype = C.c_size_t
         L.fl_attn_bwd_workspace_size.argtypes = [TP, TP, C.POINTER(fl_variant_desc)]
+        L.fl_attn_bwd_ex.restype = C.c_int
+        L.fl_attn_bwd_ex.argtypes = [TP, TP, TP, TP, TP, TP, C.POINTER(fl_variant_desc), C.POINTER(fl_aux),
+                                     TP, TP, TP, C.POINTER(fl_bwd_extra), C.c_void_p]
+        L.fl_attn_bwd_ex_workspace_size.restype = C.c_size_t
+        L.fl_attn_bwd_ex_workspace_size.argtypes = [TP, TP, TP, C.POINTER(fl_variant_desc)]
         L.fl_bwd_supported.restype = C.c_int
         L.fl_bwd_supported.argtypes = [C.POINTER(fl_variant_desc), C.c_int, C.c_int, C.c_int]
         L.fl_attn_decode.restype = C.c_int
@@ -117,7 +127,7 @@ def lib() -> C.CDLL:
     return _lib
 
 
-EXPORTS = ["fl_attn_fwd", "fl_attn_fwd_noalloc", "fl_attn_fwd_workspace_size", "fl_attn_bwd", "fl_attn_bwd_workspace_size",
+EXPORTS = ["fl_attn_fwd", "fl_attn_fwd_noalloc", "fl_attn_fwd_workspace_size", "fl_attn_bwd", "fl_attn_bwd_workspace_size", "fl_attn_bwd_ex", "fl_attn_bwd_ex_workspace_size",
            "fl_bwd_supported", "fl_attn_decode", "fl_attn_decode_workspace_size", "fl_compile_variant", "fl_attn_fwd_custom", "fl_compile_variant_aux", "fl_attn_fwd_custom_aux",
            "fl_release_variant", "fl_variant_supported", "fl_strerror",
            "fl_last_error_detail", "fl_set_tuning", "fl_version"]
@@ -200,6 +210,28 @@ def fl_attn_bwd(q: fl_tensor, k: fl_tensor, v: fl_tensor, out: fl_tensor, dout: 
     """Raw call; returns the fl_status code."""
     return lib().fl_attn_bwd(_ref(q), _ref(k), _ref(v), _ref(out), _ref(dout), _ref(lse), _ref(desc), _ref(aux),
                              _ref(dq), _ref(dk), _ref(dv), C.c_void_p(stream))
+
+
+def bwd_extra(*, dq2=None, dk2=None, dbias=(), dgate=None, dlambda=None) -> fl_bwd_extra:
+    x = fl_bwd_extra()
+    x.struct_size = C.sizeof(fl_bwd_extra)
+    x.dq2, x.dk2, x.dgate = tensor_desc(dq2), tensor_desc(dk2), tensor_desc(dgate)
+    for n, b in enumerate(dbias):
+        x.dbias[n] = tensor_desc(b)
+    x.dlambda = None if dlambda is None else dlambda.data_ptr()
+    return x
+
+
+def fl_attn_bwd_ex(q: fl_tensor, k: fl_tensor, v: fl_tensor, out: fl_tensor, dout: fl_tensor, lse: fl_tensor,
+                   desc: fl_variant_desc, aux: Optional[fl_aux], dq: fl_tensor, dk: fl_tensor, dv: fl_tensor,
+                   extra: Optional[fl_bwd_extra], stream: int = 0) -> int:
+    """Raw call; returns the fl_status code."""
+    return lib().fl_attn_bwd_ex(_ref(q), _ref(k), _ref(v), _ref(out), _ref(dout), _ref(lse), _ref(desc), _ref(aux),
+                                _ref(dq), _ref(dk), _ref(dv), _ref(extra), C.c_void_p(stream))
+
+
+def fl_attn_bwd_ex_workspace_size(q: fl_tensor, k: fl_tensor, v: fl_tensor, desc: fl_variant_desc) -> int:
+    return lib().fl_attn_bwd_ex_workspace_size(_ref(q), _ref(k), _ref(v), _ref(desc))
 
 
 def fl_attn_bwd_workspace_size(q: fl_tensor, k: fl_tensor, desc: fl_variant_desc) -> int:

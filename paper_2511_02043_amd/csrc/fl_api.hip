@@ -208,7 +208,7 @@ struct BwdRegistry {
   }
 };
 
-const fl::BwdEntry* find_bwd_entry(const fl_variant_desc* d, int D) {
+const fl::BwdEntry* find_bwd_entry(const fl_variant_desc* d, int D, int nbias = 0) {
   static const BwdRegistry reg;                    // initialised once, also under concurrent first calls
   const fl::BwdEntry* const* tab = reg.tab;
   const int* n = reg.n;
@@ -216,7 +216,7 @@ const fl::BwdEntry* find_bwd_entry(const fl_variant_desc* d, int D) {
   for (int t = 0; t < 2; ++t)
     for (int e = 0; e < n[t]; ++e) {
       const fl::BwdEntry& k = tab[t][e];
-      if (k.key.D == D && k.key.mod == (int)d->score_mod && k.key.mask == mask) return &k;
+      if (k.key.D == D && k.key.mod == (int)d->score_mod && k.key.mask == mask && k.key.nbias == nbias) return &k;
     }
   return nullptr;
 }
@@ -302,6 +302,240 @@ int decode_splits(int64_t B, int64_t Hkv, int64_t D, int64_t max_seq_len) {
     if (ns > 32) ns = 32;
   }
   return (int)(ns < 1 ? 1 : ns);
+}
+
+
+// ------------------------------------------------------------------------------------------------
+// Backward pass of the variants with biases, gate, RMSNorm or a second stream (fl_attn_bwd_ex): the
+// elementwise kernels around the per-stream backward kernels.
+// ------------------------------------------------------------------------------------------------
+
+// head dim the backward kernels run at for (D, Dv): tensors with a smaller one are zero-padded to it
+int core_dim(int64_t D, int64_t Dv) { return (D > Dv ? D : Dv) <= 64 ? 64 : 128; }
+
+struct EpiBwdParams {
+  fl::View dout, out, gate, dgate;  // [B, G, H, Sq, Dv]; dgate.ptr null: not wanted
+  const float* o[2];                // the streams' recomputed outputs, dense [rows, Dv] fp32 (null: not needed)
+  const float* lse;                 // [B, ns * G, H, Sq]: stream s of row-axis g at ns * g + s
+  int64_t lse_sb, lse_sg, lse_sh;
+  uint16_t* d_o[2];                 // per-stream dO, dense [rows, Dc] bf16, channels past Dv zero
+  float* delta[2];                  // per-stream rowsum(dO * O)
+  float* lse2[2];                   // per-stream lse * log2(e), +inf for rows without a visible key
+  const float* lambda;
+  const float* rms_w;
+  float* dlambda;                   // [H], atomic sums, or null
+  float rms_eps;
+  int32_t B, G, H, Sq, Dv, Dc;
+  int32_t ns, has_gate, has_rms, dgate_f32;
+};
+
+// One wave per (b, g, h, i) row; lane c holds channels c and c + 64.
+__global__ void __launch_bounds__(256) epi_bwd_kernel(const EpiBwdParams e) {
+  const int64_t rows = (int64_t)e.B * e.G * e.H * e.Sq;
+  const int64_t row = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6;
+  if (row >= rows) return;
+  const int lane = threadIdx.x & 63;
+  const int i = (int)(row % e.Sq);
+  const int h = (int)((row / e.Sq) % e.H);
+  const int g = (int)((row / ((int64_t)e.Sq * e.H)) % e.G);
+  const int b = (int)(row / ((int64_t)e.Sq * e.H * e.G));
+  auto off = [&](const fl::View& v) { return b * v.sb + g * v.sg + h * v.sh + (int64_t)i * v.ss; };
+  auto wsum = [](float x) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
+    return x;
+  };
+  const bool need_o = e.o[0] != nullptr;
+  const float lam = e.ns == 2 ? e.lambda[h] : 0.f;
+  float dy[2], ov[2], x[2], o1[2], o2[2], wv[2];
+  float sum_x2 = 0.f, sum_wdyx = 0.f, sum_dout_out = 0.f;
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int c = lane + 64 * u;
+    const bool ok = c < e.Dv;
+    const float dv_ = ok ? fl::bf16_to_f32(((const uint16_t*)e.dout.ptr)[off(e.dout) + c]) : 0.f;
+    ov[u] = ok ? fl::bf16_to_f32(((const uint16_t*)e.out.ptr)[off(e.out) + c]) : 0.f;
+    dy[u] = dv_;
+    if (e.has_gate) {
+      const float gv = ok ? fl::bf16_to_f32(((const uint16_t*)e.gate.ptr)[off(e.gate) + c]) : 0.f;
+      const float sg = 1.f / (1.f + __expf(-gv));
+      dy[u] = dv_ * sg;
+      if (ok && e.dgate.ptr != nullptr) {           // dout * y * sg (1 - sg) with out = y * sg
+        const float dg = dv_ * ov[u] * (1.f - sg);
+        if (e.dgate_f32) ((float*)e.dgate.ptr)[off(e.dgate) + c] = dg;
+        else ((uint16_t*)e.dgate.ptr)[off(e.dgate) + c] = (uint16_t)(fl::pack_bf16(dg, 0.f) & 0xFFFFu);
+      }
+    }
+    sum_dout_out += dv_ * ov[u];
+    o1[u] = need_o && ok ? e.o[0][row * e.Dv + c] : 0.f;
+    o2[u] = e.ns == 2 && ok ? e.o[1][row * e.Dv + c] : 0.f;
+    x[u] = o1[u] - lam * o2[u];
+    wv[u] = e.has_rms && ok ? (e.rms_w != nullptr ? e.rms_w[c] : 1.f) : 0.f;
+    sum_x2 += x[u] * x[u];
+    sum_wdyx += wv[u] * dy[u] * x[u];
+  }
+  float dx[2] = {dy[0], dy[1]};
+  if (e.has_rms) {
+    const float ms = wsum(sum_x2) / (float)e.Dv;
+    const float r = sqrtf(ms + e.rms_eps);
+    const float dot = wsum(sum_wdyx);
+    const float c3 = dot / ((float)e.Dv * r * r * r);
+#pragma unroll
+    for (int u = 0; u < 2; ++u) dx[u] = wv[u] * dy[u] / r - x[u] * c3;
+  }
+  float d1 = 0.f, d2 = 0.f, dl = 0.f;
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int c = lane + 64 * u;
+    if (c < e.Dc) {
+      const bool ok = c < e.Dv;
+      e.d_o[0][row * e.Dc + c] = ok ? (uint16_t)(fl::pack_bf16(dx[u], 0.f) & 0xFFFFu) : (uint16_t)0;
+      if (e.ns == 2) e.d_o[1][row * e.Dc + c] = ok ? (uint16_t)(fl::pack_bf16(-lam * dx[u], 0.f) & 0xFFFFu) : (uint16_t)0;
+    }
+    d1 += dx[u] * o1[u];
+    d2 += -lam * dx[u] * o2[u];
+    dl += -dx[u] * o2[u];
+  }
+  // without recomputed outputs (one stream, no RMSNorm): delta = rowsum(dy * y) = rowsum(dout * out)
+  d1 = need_o ? wsum(d1) : wsum(sum_dout_out);
+  if (e.ns == 2) {
+    d2 = wsum(d2);
+    dl = wsum(dl);
+  }
+  if (lane == 0) {
+    e.delta[0][row] = d1;
+    if (e.ns == 2) {
+      e.delta[1][row] = d2;
+      if (e.dlambda != nullptr) unsafeAtomicAdd(e.dlambda + h, dl);
+    }
+    for (int s = 0; s < e.ns; ++s) {
+      const float l = e.lse[b * e.lse_sb + (int64_t)(e.ns * g + s) * e.lse_sg + h * e.lse_sh + i];
+      e.lse2[s][row] = l == -INFINITY ? INFINITY : l * fl::kLog2e;
+    }
+  }
+}
+
+// bf16 [B, G, H, S, D] view -> dense [B, G, H, S, Dc] with zero channels past D (8 channels per thread)
+__global__ void __launch_bounds__(256) pad_rows_kernel(fl::View src, uint16_t* dst, int G, int H, int S, int D, int Dc, int64_t rows) {
+  const int cpr = Dc / 8;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= rows * cpr) return;
+  const int64_t row = idx / cpr;
+  const int c = (int)(idx % cpr) * 8;
+  const int i = (int)(row % S), h = (int)((row / S) % H), g = (int)((row / ((int64_t)S * H)) % G);
+  const int b = (int)(row / ((int64_t)S * H * G));
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (c < D) v = *(const uint4*)((const uint16_t*)src.ptr + b * src.sb + g * src.sg + h * src.sh + (int64_t)i * src.ss + c);
+  *(uint4*)(dst + row * Dc + c) = v;
+}
+
+// dense fp32 [B, G, H, S, Dc] (optionally the sum of two) -> the first D channels of a [B, G, H, S, D] view, bf16 or fp32
+__global__ void __launch_bounds__(256) scatter_grad_kernel(const float* a, const float* b2, fl::View dst, int dst_f32, int G, int H,
+                                                           int S, int D, int Dc, int64_t rows) {
+  const int cpr = D / 4;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= rows * cpr) return;
+  const int64_t row = idx / cpr;
+  const int c = (int)(idx % cpr) * 4;
+  const int i = (int)(row % S), h = (int)((row / S) % H), g = (int)((row / ((int64_t)S * H)) % G);
+  const int b = (int)(row / ((int64_t)S * H * G));
+  float4 v = *(const float4*)(a + row * Dc + c);
+  if (b2 != nullptr) {
+    const float4 w = *(const float4*)(b2 + row * Dc + c);
+    v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
+  }
+  const int64_t o = b * dst.sb + g * dst.sg + h * dst.sh + (int64_t)i * dst.ss + c;
+  if (dst_f32) *(float4*)((float*)dst.ptr + o) = v;
+  else *(uint2*)((uint16_t*)dst.ptr + o) = make_uint2(fl::pack_bf16(v.x, v.y), fl::pack_bf16(v.z, v.w));
+}
+
+// zero-fill of a strided fp32 [B, G, H, Sq, Sk] tensor (bias gradients are accumulated with atomic adds)
+__global__ void __launch_bounds__(256) zero_bias_grad_kernel(fl::BiasView t, int n1, int n2, int n3, int n4, int64_t total) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const int j = (int)(idx % n4), i = (int)((idx / n4) % n3), h = (int)((idx / ((int64_t)n4 * n3)) % n2);
+  const int g = (int)((idx / ((int64_t)n4 * n3 * n2)) % n1), b = (int)(idx / ((int64_t)n4 * n3 * n2 * n1));
+  ((float*)t.ptr)[b * t.sb + g * t.sg + h * t.sh + (int64_t)i * t.si + (int64_t)j * t.sj] = 0.f;
+}
+__global__ void __launch_bounds__(256) zero_f32_kernel(float* p, int64_t n) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx < n) p[idx] = 0.f;
+}
+
+inline size_t up256(size_t x) { return (x + 255) / 256 * 256; }
+
+// Workspace of fl_attn_bwd_ex (byte offsets; every region 256-byte aligned).
+struct ExLayout {
+  int Dc, ns, hsplit;
+  bool need_o, pad_qk, pad_v;
+  size_t stat, o, d_o, qpad, kpad, vpad, gq, gk, gv, sum, part;   // sizes of one region each
+  size_t off_lse2[2], off_delta[2], off_o[2], off_do[2], off_qpad[2], off_kpad[2], off_vpad, off_gq[2], off_gk[2], off_gv[2],
+      off_sum, off_part;
+  size_t total;
+};
+ExLayout ex_layout(int64_t B, int64_t G, int64_t H, int64_t Hkv, int64_t Sq, int64_t Sk, int64_t D, int64_t Dv,
+                   const fl_variant_desc* d) {
+  ExLayout L;
+  memset(&L, 0, sizeof(L));
+  const uint32_t mask = canonical_mask(d->mask);
+  L.Dc = core_dim(D, Dv);
+  L.ns = d->combine == FL_DIFFERENTIAL ? 2 : 1;
+  L.need_o = L.ns == 2 || (d->epilogue & FL_EPI_RMSNORM) != 0;
+  L.pad_qk = D != L.Dc;
+  L.pad_v = Dv != L.Dc;
+  const size_t rq = (size_t)(B * G * H * Sq), rk = (size_t)(B * G * Hkv * Sk);
+  L.stat = up256(rq * 4);
+  L.o = L.need_o ? up256(rq * Dv * 4) : 0;
+  L.d_o = up256(rq * L.Dc * 2);
+  L.qpad = L.pad_qk ? up256(rq * L.Dc * 2) : 0;
+  L.kpad = L.pad_qk ? up256(rk * L.Dc * 2) : 0;
+  L.vpad = L.pad_v ? up256(rk * L.Dc * 2) : 0;
+  L.gq = up256(rq * L.Dc * 4);
+  L.gk = up256(rk * L.Dc * 4);
+  L.gv = up256(rk * L.Dc * 4);
+  L.sum = up256(workspace_bytes(B, Sq, Sk, mask));
+  L.hsplit = choose_hsplit(B, G, H, Hkv, Sq, Sk, mask, clamp_window(d->window, Sq, Sk));
+  L.part = L.hsplit > 1 ? up256((size_t)L.hsplit * rk * L.Dc * 4) : 0;
+  size_t at = 0;
+  auto take = [&](size_t n) { const size_t o = at; at += n; return o; };
+  for (int s = 0; s < L.ns; ++s) {
+    L.off_lse2[s] = take(L.stat);
+    L.off_delta[s] = take(L.stat);
+    L.off_o[s] = take(L.o);
+    L.off_do[s] = take(L.d_o);
+    L.off_qpad[s] = take(L.qpad);
+    L.off_kpad[s] = take(L.kpad);
+    L.off_gq[s] = take(L.gq);
+    L.off_gk[s] = take(L.gk);
+    L.off_gv[s] = take(L.gv);
+  }
+  L.off_vpad = take(L.vpad);
+  L.off_sum = take(L.sum);
+  L.off_part = take(2 * L.part);
+  L.total = at;
+  return L;
+}
+
+// Is the variant one the plain backward entry point (no extra outputs, no padding) takes?
+bool bwd_simple(const fl_variant_desc* d, int64_t D, int64_t Dv) {
+  return bwd_desc_ok(d) && D == Dv && (D == 64 || D == 128);
+}
+// Can fl_attn_bwd_ex build the variant from the backward kernels?
+bool bwd_ex_ok(const fl_variant_desc* d, int64_t D, int64_t Dv) {
+  if (d->q_offset != 0) return false;
+  if (!((D == 32 || D == 64 || D == 128) && (Dv == 32 || Dv == 64 || Dv == 128))) return false;
+  if (d->n_bias > 0 && d->score_mod != FL_MOD_NONE) return false;
+  return find_bwd_entry(d, core_dim(D, Dv), (int)d->n_bias) != nullptr;
+}
+
+fl::View dense_view(void* ptr, int64_t G, int64_t H, int64_t S, int64_t Dc) {
+  fl::View v;
+  v.ptr = ptr;
+  v.ss = Dc;
+  v.sh = S * Dc;
+  v.sg = H * S * Dc;
+  v.sb = G * H * S * Dc;
+  return v;
 }
 
 }  // namespace
@@ -620,8 +854,9 @@ size_t fl_attn_bwd_workspace_size(const fl_tensor* q, const fl_tensor* k, const 
 }
 
 int fl_bwd_supported(const fl_variant_desc* desc, int dtype, int D, int Dv) {
-  if (check_desc(desc) != FL_OK || dtype != FL_BF16 || D != Dv || !bwd_desc_ok(desc)) return 0;
-  return find_bwd_entry(desc, D) != nullptr ? 1 : 0;
+  if (check_desc(desc) != FL_OK || dtype != FL_BF16) return 0;
+  if (bwd_simple(desc, D, Dv)) return find_bwd_entry(desc, D) != nullptr ? 1 : 0;
+  return bwd_ex_ok(desc, D, Dv) ? 1 : 0;
 }
 
 fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v, const fl_tensor* out,
@@ -635,9 +870,10 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
     return fail(FL_ERR_NULL, "a tensor descriptor is NULL");
   if (aux != nullptr && aux->struct_size != sizeof(fl_aux))
     return fail(FL_ERR_DESC, "aux->struct_size = %u, expected %zu", aux->struct_size, sizeof(fl_aux));
-  if (!bwd_desc_ok(desc))
-    return fail(FL_ERR_UNSUPPORTED, "the backward pass covers variants without bias, second stream, epilogue and query offset");
+  if (desc->q_offset != 0) return fail(FL_ERR_UNSUPPORTED, "the backward pass does not take a query offset");
   if (q->dtype != FL_BF16) return fail(FL_ERR_DTYPE, "the backward pass takes bf16 inputs (q dtype %d)", q->dtype);
+  if (!bwd_simple(desc, q->size[4], v->size[4]))   // biases, epilogues, second stream, other head dims: the composed pass
+    return fl_attn_bwd_ex(q, k, v, out, dout, lse, desc, aux, dq, dk, dv, nullptr, stream_v);
 
   const int64_t B = q->size[0], G = q->size[1], H = q->size[2], Sq = q->size[3], D = q->size[4];
   const int64_t Hkv = k->size[2], Sk = k->size[3], Dv = v->size[4];
@@ -759,6 +995,273 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
         return fail(FL_ERR_LAUNCH, "dk/dv reduction launch: %s", hipGetErrorString(e));
     }
   }
+  return FL_OK;
+}
+
+size_t fl_attn_bwd_ex_workspace_size(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v, const fl_variant_desc* desc) {
+  if (q == nullptr || k == nullptr || v == nullptr || desc == nullptr) return 0;
+  if (bwd_simple(desc, q->size[4], v->size[4])) return fl_attn_bwd_workspace_size(q, k, desc);
+  return ex_layout(q->size[0], q->size[1], q->size[2], k->size[2], q->size[3], k->size[3], q->size[4], v->size[4], desc).total;
+}
+
+fl_status fl_attn_bwd_ex(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v, const fl_tensor* out, const fl_tensor* dout,
+                         const fl_tensor* lse, const fl_variant_desc* desc, const fl_aux* aux, fl_tensor* dq, fl_tensor* dk,
+                         fl_tensor* dv, const fl_bwd_extra* extra, void* stream_v) {
+  g_detail[0] = 0;
+  fl_status st = check_desc(desc);
+  if (st != FL_OK) return st;
+  if (q == nullptr || k == nullptr || v == nullptr || out == nullptr || dout == nullptr || lse == nullptr || dq == nullptr ||
+      dk == nullptr || dv == nullptr)
+    return fail(FL_ERR_NULL, "a tensor descriptor is NULL");
+  if (extra != nullptr && extra->struct_size != sizeof(fl_bwd_extra))
+    return fail(FL_ERR_DESC, "extra->struct_size = %u, expected %zu", extra->struct_size, sizeof(fl_bwd_extra));
+  if (aux != nullptr && aux->struct_size != sizeof(fl_aux))
+    return fail(FL_ERR_DESC, "aux->struct_size = %u, expected %zu", aux->struct_size, sizeof(fl_aux));
+  if (q->dtype != FL_BF16) return fail(FL_ERR_DTYPE, "the backward pass takes bf16 inputs (q dtype %d)", q->dtype);
+  const int64_t B = q->size[0], G = q->size[1], H = q->size[2], Sq = q->size[3], D = q->size[4];
+  const int64_t Hkv = k->size[2], Sk = k->size[3], Dv = v->size[4];
+  if (bwd_simple(desc, D, Dv)) return fl_attn_bwd(q, k, v, out, dout, lse, desc, aux, dq, dk, dv, stream_v);
+  if (B <= 0 || G <= 0 || H <= 0 || Sq <= 0 || Sk <= 0 || Hkv <= 0 || H % Hkv != 0)
+    return fail(FL_ERR_SHAPE, "the composed backward pass needs non-empty tensors and kv heads that divide the q heads");
+  if (Sq > 0x7fffff00LL || Sk > 0x7fffff00LL || B * G * H > 0x7fffffffLL) return fail(FL_ERR_SHAPE, "size too large");
+  if (!bwd_ex_ok(desc, D, Dv))
+    return fail(FL_ERR_UNSUPPORTED, "no backward kernels for D=%lld Dv=%lld score_mod=%u mask=0x%x n_bias=%u q_offset=%d",
+                (long long)D, (long long)Dv, desc->score_mod, canonical_mask(desc->mask), desc->n_bias, desc->q_offset);
+  if (aux == nullptr) return fail(FL_ERR_AUX_MISSING, "the backward pass needs aux (workspace)");
+  const uint32_t mask = canonical_mask(desc->mask);
+  const bool diff = desc->combine == FL_DIFFERENTIAL;
+  const bool has_gate = (desc->epilogue & FL_EPI_GATE_SIGMOID) != 0, has_rms = (desc->epilogue & FL_EPI_RMSNORM) != 0;
+  const ExLayout L = ex_layout(B, G, H, Hkv, Sq, Sk, D, Dv, desc);
+  const int Dc = L.Dc, ns = L.ns;
+  const fl::BwdEntry* be = find_bwd_entry(desc, Dc, (int)desc->n_bias);
+
+  // ---- tensors
+  const int64_t qsz[5] = {B, G, H, Sq, D}, ksz[5] = {B, G, Hkv, Sk, D}, vsz[5] = {B, G, Hkv, Sk, Dv}, osz[5] = {B, G, H, Sq, Dv};
+  if ((st = check_data_tensor(q, "q", FL_BF16, qsz)) != FL_OK) return st;
+  if ((st = check_data_tensor(k, "k", FL_BF16, ksz)) != FL_OK) return st;
+  if ((st = check_data_tensor(v, "v", FL_BF16, vsz)) != FL_OK) return st;
+  if ((st = check_data_tensor(out, "out", FL_BF16, osz)) != FL_OK) return st;
+  if ((st = check_data_tensor(dout, "dout", FL_BF16, osz)) != FL_OK) return st;
+  if (dq->dtype != FL_BF16 && dq->dtype != FL_F32) return fail(FL_ERR_DTYPE, "dq dtype %d", dq->dtype);
+  if (dk->dtype != FL_BF16 && dk->dtype != FL_F32) return fail(FL_ERR_DTYPE, "dk dtype %d", dk->dtype);
+  if (dv->dtype != dk->dtype) return fail(FL_ERR_DTYPE, "dk and dv must share one dtype");
+  if ((st = check_data_tensor(dq, "dq", dq->dtype, qsz)) != FL_OK) return st;
+  if ((st = check_data_tensor(dk, "dk", dk->dtype, ksz)) != FL_OK) return st;
+  if ((st = check_data_tensor(dv, "dv", dv->dtype, vsz)) != FL_OK) return st;
+  if (lse->ptr == nullptr) return fail(FL_ERR_NULL, "lse is NULL");
+  if (lse->dtype != FL_F32) return fail(FL_ERR_DTYPE, "lse must be f32");
+  const int64_t lsz[5] = {B, ns * G, H, Sq, 1};
+  for (int a = 0; a < 5; ++a)
+    if (lse->size[a] != lsz[a])
+      return fail(FL_ERR_SHAPE, "lse size[%d] = %lld, expected %lld", a, (long long)lse->size[a], (long long)lsz[a]);
+  if (Sq > 1 && lse->stride[3] != 1) return fail(FL_ERR_STRIDE, "lse must be contiguous along Sq");
+  if (desc->score_mod == FL_MOD_ALIBI && aux->alibi_slopes == nullptr) return fail(FL_ERR_AUX_MISSING, "alibi_slopes");
+  if ((mask & FL_MASK_DOC) && (aux->q_doc_ids == nullptr || aux->kv_doc_ids == nullptr))
+    return fail(FL_ERR_AUX_MISSING, "q_doc_ids / kv_doc_ids");
+  if (diff) {
+    if (aux->lambda == nullptr) return fail(FL_ERR_AUX_MISSING, "lambda");
+    if ((st = check_data_tensor(&aux->q2, "q2", FL_BF16, qsz)) != FL_OK) return st == FL_ERR_NULL ? fail(FL_ERR_AUX_MISSING, "q2") : st;
+    if ((st = check_data_tensor(&aux->k2, "k2", FL_BF16, ksz)) != FL_OK) return st == FL_ERR_NULL ? fail(FL_ERR_AUX_MISSING, "k2") : st;
+    if (extra == nullptr) return fail(FL_ERR_AUX_MISSING, "the differential variant writes dq2 and dk2 (extra is NULL)");
+    if ((st = check_data_tensor(&extra->dq2, "dq2", dq->dtype, qsz)) != FL_OK) return st;
+    if ((st = check_data_tensor(&extra->dk2, "dk2", dk->dtype, ksz)) != FL_OK) return st;
+  }
+  if (has_gate) {
+    if ((st = check_data_tensor(&aux->gate, "gate", FL_BF16, osz)) != FL_OK) return st == FL_ERR_NULL ? fail(FL_ERR_AUX_MISSING, "gate") : st;
+    if (extra != nullptr && extra->dgate.ptr != nullptr) {
+      if (extra->dgate.dtype != FL_BF16 && extra->dgate.dtype != FL_F32) return fail(FL_ERR_DTYPE, "dgate dtype %d", extra->dgate.dtype);
+      if ((st = check_data_tensor(&extra->dgate, "dgate", extra->dgate.dtype, osz)) != FL_OK) return st;
+    }
+  }
+  // biases and their gradients
+  fl::BiasView bias[2], dbias[2];
+  memset(bias, 0, sizeof(bias));
+  memset(dbias, 0, sizeof(dbias));
+  const int64_t bwant[5] = {B, G, H, Sq, Sk};
+  for (uint32_t nb = 0; nb < desc->n_bias; ++nb) {
+    const fl_tensor* bt = &aux->bias[nb];
+    if (bt->ptr == nullptr) return fail(FL_ERR_AUX_MISSING, "bias[%u]", nb);
+    if (bt->dtype != FL_BF16) return fail(FL_ERR_DTYPE, "bias[%u]: bf16 inputs take bf16 biases", nb);
+    int64_t bs[5];
+    for (int a = 0; a < 5; ++a) {
+      if (bt->size[a] != bwant[a] && bt->size[a] != 1)
+        return fail(FL_ERR_SHAPE, "bias[%u] size[%d] = %lld, expected %lld or 1", nb, a, (long long)bt->size[a], (long long)bwant[a]);
+      bs[a] = (bt->size[a] == 1 && bwant[a] != 1) ? 0 : bt->stride[a];
+      if (bs[a] < 0) return fail(FL_ERR_STRIDE, "bias[%u] stride[%d] negative", nb, a);
+    }
+    bias[nb].ptr = bt->ptr;
+    bias[nb].sb = bs[0]; bias[nb].sg = bs[1]; bias[nb].sh = bs[2]; bias[nb].si = bs[3]; bias[nb].sj = bs[4];
+    const fl_tensor* gt = extra != nullptr ? &extra->dbias[nb] : nullptr;
+    if (gt != nullptr && gt->ptr != nullptr) {
+      if (gt->dtype != FL_F32) return fail(FL_ERR_DTYPE, "dbias[%u] must be f32", nb);
+      if (((uintptr_t)gt->ptr) % 4 != 0) return fail(FL_ERR_ALIGN, "dbias[%u] not 4-byte aligned", nb);
+      int64_t gs[5];
+      for (int a = 0; a < 5; ++a) {
+        if (gt->size[a] != bt->size[a])
+          return fail(FL_ERR_SHAPE, "dbias[%u] size[%d] = %lld, the bias has %lld", nb, a, (long long)gt->size[a], (long long)bt->size[a]);
+        gs[a] = (gt->size[a] == 1 && bwant[a] != 1) ? 0 : gt->stride[a];
+        if (gs[a] < 0 || (gt->size[a] > 1 && gs[a] == 0)) return fail(FL_ERR_STRIDE, "dbias[%u] stride[%d]", nb, a);
+      }
+      dbias[nb].ptr = gt->ptr;
+      dbias[nb].sb = gs[0]; dbias[nb].sg = gs[1]; dbias[nb].sh = gs[2]; dbias[nb].si = gs[3]; dbias[nb].sj = gs[4];
+    }
+  }
+  if (aux->workspace == nullptr || aux->workspace_bytes < L.total)
+    return fail(FL_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", L.total, aux->workspace ? aux->workspace_bytes : (size_t)0);
+  if (((uintptr_t)aux->workspace) % 16 != 0) return fail(FL_ERR_ALIGN, "workspace not 16-byte aligned");
+  const int64_t rows_q = B * G * H * Sq, rows_k = B * G * Hkv * Sk;
+  if (rows_q * Dc > 0x7fffffff00LL || rows_k * Dc > 0x7fffffff00LL) return fail(FL_ERR_SHAPE, "too many rows");
+
+  hipStream_t stream = (hipStream_t)stream_v;
+  unsigned char* ws = (unsigned char*)aux->workspace;
+  hipError_t e = hipSuccess;
+  auto blocks = [](int64_t n) { return dim3((unsigned)((n + 255) / 256)); };
+  const fl_tensor* qs[2] = {q, diff ? &aux->q2 : nullptr};
+  const fl_tensor* ks[2] = {k, diff ? &aux->k2 : nullptr};
+
+  // ---- 1. the streams' outputs, recomputed by the forward kernel without epilogue (fp32, dense)
+  if (L.need_o) {
+    fl_variant_desc d1 = *desc;
+    d1.combine = FL_SINGLE;
+    d1.epilogue = 0;
+    fl_aux a1 = *aux;
+    a1.workspace = ws + L.off_sum;
+    a1.workspace_bytes = L.sum;
+    for (int s = 0; s < ns; ++s) {
+      fl_tensor to;
+      memset(&to, 0, sizeof(to));
+      to.ptr = ws + L.off_o[s];
+      to.dtype = FL_F32;
+      const int64_t dsz[5] = {B, G, H, Sq, Dv};
+      int64_t stv = 1;
+      for (int a = 4; a >= 0; --a) {
+        to.size[a] = dsz[a];
+        to.stride[a] = stv;
+        stv *= dsz[a];
+      }
+      if ((st = fl_attn_fwd(qs[s], ks[s], v, &d1, &a1, &to, nullptr, stream_v)) != FL_OK) return st;
+    }
+  }
+
+  // ---- 2. epilogue derivative: per-stream dO, delta, lse2; gate and lambda gradients
+  if (diff && extra->dlambda != nullptr) hipLaunchKernelGGL(zero_f32_kernel, blocks(H), dim3(256), 0, stream, extra->dlambda, (int64_t)H);
+  EpiBwdParams ep;
+  memset(&ep, 0, sizeof(ep));
+  ep.dout = make_view(dout);
+  ep.out = make_view(out);
+  if (has_gate) {
+    ep.gate = make_view(&aux->gate);
+    if (extra != nullptr && extra->dgate.ptr != nullptr) {
+      ep.dgate = make_view(&extra->dgate);
+      ep.dgate_f32 = extra->dgate.dtype == FL_F32;
+    }
+  }
+  ep.lse = (const float*)lse->ptr;
+  ep.lse_sb = lse->size[0] > 1 ? lse->stride[0] : 0;
+  ep.lse_sg = lse->size[1] > 1 ? lse->stride[1] : 0;
+  ep.lse_sh = lse->size[2] > 1 ? lse->stride[2] : 0;
+  for (int s = 0; s < ns; ++s) {
+    ep.o[s] = L.need_o ? (const float*)(ws + L.off_o[s]) : nullptr;
+    ep.d_o[s] = (uint16_t*)(ws + L.off_do[s]);
+    ep.delta[s] = (float*)(ws + L.off_delta[s]);
+    ep.lse2[s] = (float*)(ws + L.off_lse2[s]);
+  }
+  ep.lambda = aux->lambda;
+  ep.rms_w = aux->rms_weight;
+  ep.dlambda = diff ? extra->dlambda : nullptr;
+  ep.rms_eps = desc->rms_eps;
+  ep.B = (int)B; ep.G = (int)G; ep.H = (int)H; ep.Sq = (int)Sq; ep.Dv = (int)Dv; ep.Dc = Dc;
+  ep.ns = ns; ep.has_gate = has_gate; ep.has_rms = has_rms;
+  hipLaunchKernelGGL(epi_bwd_kernel, blocks(rows_q * 64), dim3(256), 0, stream, ep);
+
+  // ---- 3. zero-padded copies for head dims below the kernels' own
+  for (int s = 0; s < ns && L.pad_qk; ++s) {
+    hipLaunchKernelGGL(pad_rows_kernel, blocks(rows_q * (Dc / 8)), dim3(256), 0, stream, make_view(qs[s]), (uint16_t*)(ws + L.off_qpad[s]),
+                       (int)G, (int)H, (int)Sq, (int)D, Dc, rows_q);
+    hipLaunchKernelGGL(pad_rows_kernel, blocks(rows_k * (Dc / 8)), dim3(256), 0, stream, make_view(ks[s]), (uint16_t*)(ws + L.off_kpad[s]),
+                       (int)G, (int)Hkv, (int)Sk, (int)D, Dc, rows_k);
+  }
+  if (L.pad_v)
+    hipLaunchKernelGGL(pad_rows_kernel, blocks(rows_k * (Dc / 8)), dim3(256), 0, stream, make_view(v), (uint16_t*)(ws + L.off_vpad), (int)G,
+                       (int)Hkv, (int)Sk, (int)Dv, Dc, rows_k);
+  for (uint32_t nb = 0; nb < desc->n_bias; ++nb)
+    if (dbias[nb].ptr != nullptr) {
+      const fl_tensor* gt = &extra->dbias[nb];
+      const int64_t total = gt->size[0] * gt->size[1] * gt->size[2] * gt->size[3] * gt->size[4];
+      hipLaunchKernelGGL(zero_bias_grad_kernel, blocks(total), dim3(256), 0, stream, dbias[nb], (int)gt->size[1], (int)gt->size[2],
+                         (int)gt->size[3], (int)gt->size[4], total);
+    }
+  if ((e = hipGetLastError()) != hipSuccess) return fail(FL_ERR_LAUNCH, "backward pre-pass launch: %s", hipGetErrorString(e));
+
+  // ---- 4. the backward kernels, once per stream, into dense fp32 gradient buffers
+  fl::BwdParams p;
+  memset(&p, 0, sizeof(p));
+  p.alibi_slopes = aux->alibi_slopes;
+  p.q_doc = aux->q_doc_ids;
+  p.kv_doc = aux->kv_doc_ids;
+  p.B = (int)B; p.G = (int)G; p.H = (int)H; p.Hkv = (int)Hkv; p.Sq = (int)Sq; p.Sk = (int)Sk;
+  p.window = clamp_window(desc->window, Sq, Sk);
+  p.prefix = desc->prefix_len;
+  p.scale = desc->scale;
+  p.softcap = desc->softcap;
+  p.dq_f32 = 1;
+  p.dkv_f32 = 1;
+  p.n_qtiles = (int)((Sq + be->bm - 1) / be->bm);
+  p.n_ktiles = (int)((Sk + be->bm - 1) / be->bm);
+  p.hsplit = L.hsplit;
+  p.part_dk = (float*)(ws + L.off_part);
+  p.part_dv = (float*)(ws + L.off_part + L.part);
+  const int order = g_tuning.order >= 0 ? g_tuning.order : 1;
+  p.order_q = order == 1 && (B * G * H) % 8 == 0;
+  p.order_k = order == 1 && (B * G * Hkv * p.hsplit) % 8 == 0;
+  for (int nb = 0; nb < 2; ++nb) {
+    p.bias[nb] = bias[nb];
+    p.dbias[nb] = dbias[nb];
+  }
+  const int64_t nb_q = B * G * H * p.n_qtiles, nb_k = B * G * Hkv * p.hsplit * p.n_ktiles;
+  if (nb_q > 0x7fffffffLL || nb_k > 0x7fffffffLL) return fail(FL_ERR_SHAPE, "too many workgroups");
+  if (mask & FL_MASK_DOC) {
+    const int nqs = (int)((Sq + fl::kSumBlock - 1) / fl::kSumBlock), nks = (int)((Sk + fl::kSumBlock - 1) / fl::kSumBlock);
+    p.q_sum = (int2*)(ws + L.off_sum);
+    p.kv_sum = p.q_sum + B * nqs;
+    const int tq = (int)(B * nqs), tk = (int)(B * nks);
+    hipLaunchKernelGGL(doc_summary_kernel, dim3((tq + 3) / 4), dim3(256), 0, stream, aux->q_doc_ids, p.q_sum, (int)Sq, nqs, tq);
+    hipLaunchKernelGGL(doc_summary_kernel, dim3((tk + 3) / 4), dim3(256), 0, stream, aux->kv_doc_ids, p.kv_sum, (int)Sk, nks, tk);
+    if ((e = hipGetLastError()) != hipSuccess) return fail(FL_ERR_LAUNCH, "doc summary launch: %s", hipGetErrorString(e));
+  }
+  const fl::View vview = L.pad_v ? dense_view(ws + L.off_vpad, G, Hkv, Sk, Dc) : make_view(v);
+  for (int s = 0; s < ns; ++s) {
+    p.q = L.pad_qk ? dense_view(ws + L.off_qpad[s], G, H, Sq, Dc) : make_view(qs[s]);
+    p.k = L.pad_qk ? dense_view(ws + L.off_kpad[s], G, Hkv, Sk, Dc) : make_view(ks[s]);
+    p.v = vview;
+    p.dout = dense_view(ws + L.off_do[s], G, H, Sq, Dc);
+    p.dq = dense_view(ws + L.off_gq[s], G, H, Sq, Dc);
+    p.dk = dense_view(ws + L.off_gk[s], G, Hkv, Sk, Dc);
+    p.dv = dense_view(ws + L.off_gv[s], G, Hkv, Sk, Dc);
+    p.delta = (float*)(ws + L.off_delta[s]);
+    p.lse2 = (float*)(ws + L.off_lse2[s]);
+    if ((e = be->dq(p, (int)nb_q, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dq launch: %s", hipGetErrorString(e));
+    if ((e = be->dkdv(p, (int)nb_k, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dk/dv launch: %s", hipGetErrorString(e));
+    if (p.hsplit > 1) {
+      const int64_t chunks = rows_k * (Dc / 4);
+      if ((e = be->reduce(p, (int)((chunks + 255) / 256), stream)) != hipSuccess)
+        return fail(FL_ERR_LAUNCH, "dk/dv reduction launch: %s", hipGetErrorString(e));
+    }
+  }
+
+  // ---- 5. into the caller's tensors: first D (Dv) channels, dv summed over the streams
+  fl_tensor* dqs[2] = {dq, diff ? (fl_tensor*)&extra->dq2 : nullptr};
+  fl_tensor* dks[2] = {dk, diff ? (fl_tensor*)&extra->dk2 : nullptr};
+  for (int s = 0; s < ns; ++s) {
+    hipLaunchKernelGGL(scatter_grad_kernel, blocks(rows_q * (D / 4)), dim3(256), 0, stream, (const float*)(ws + L.off_gq[s]),
+                       (const float*)nullptr, make_view(dqs[s]), (int)(dqs[s]->dtype == FL_F32), (int)G, (int)H, (int)Sq, (int)D, Dc, rows_q);
+    hipLaunchKernelGGL(scatter_grad_kernel, blocks(rows_k * (D / 4)), dim3(256), 0, stream, (const float*)(ws + L.off_gk[s]),
+                       (const float*)nullptr, make_view(dks[s]), (int)(dks[s]->dtype == FL_F32), (int)G, (int)Hkv, (int)Sk, (int)D, Dc, rows_k);
+  }
+  hipLaunchKernelGGL(scatter_grad_kernel, blocks(rows_k * (Dv / 4)), dim3(256), 0, stream, (const float*)(ws + L.off_gv[0]),
+                     ns == 2 ? (const float*)(ws + L.off_gv[1]) : (const float*)nullptr, make_view(dv), (int)(dv->dtype == FL_F32), (int)G,
+                     (int)Hkv, (int)Sk, (int)Dv, Dc, rows_k);
+  if ((e = hipGetLastError()) != hipSuccess) return fail(FL_ERR_LAUNCH, "gradient scatter launch: %s", hipGetErrorString(e));
   return FL_OK;
 }
 

@@ -56,6 +56,9 @@ struct BwdParams {
   int32_t hsplit;                  // dK/dV kernel: the query heads of a group are cut into hsplit subsets, one workgroup each
   float* part_dk;                  // hsplit > 1: fp32 partial sums [hsplit][B, G, Hkv, Sk, D], summed by bwd_reduce_kv_kernel
   float* part_dv;
+  BiasView bias[2];                // the forward pass's additive biases (kernels built with NBIAS > 0), bf16
+  BiasView dbias[2];               // their gradients: fp32, same logical [B, G, H, Sq, Sk] axes, stride 0 on the axes
+                                   // the bias broadcasts along (those are summed with atomic adds); ptr null: not wanted
 };
 
 // chunk swizzle of a tile row (see the header comment): an XOR on the 16-byte chunk index that
@@ -80,9 +83,9 @@ __device__ __forceinline__ void query_range(const uint32_t MASK, int j_lo, int j
   lo = min(lo, hi);
 }
 
-template <int D_, int MOD_, uint32_t MASK_, int BN_, int WPE_>
+template <int D_, int MOD_, uint32_t MASK_, int BN_, int WPE_, int NBIAS_ = 0>
 struct BwdCfg {
-  static constexpr int D = D_, MOD = MOD_, BN = BN_, WPE = WPE_;
+  static constexpr int D = D_, MOD = MOD_, BN = BN_, WPE = WPE_, NBIAS = NBIAS_;
   static constexpr uint32_t MASK = MASK_;
   static constexpr int NW = 4, NT = NW * 64;
   static constexpr int BM = NW * 32;               // rows (dQ kernel) or keys (dK/dV kernel) per workgroup
@@ -304,6 +307,34 @@ __device__ __forceinline__ bool hidden(int i, int j, int Sq, int Sk, int window,
   return i >= Sq || j >= Sk || is_masked(MASK, i, j, window, prefix, qdoc, kdoc);
 }
 
+// Offsets of the (b, g, h) slice of each bias / bias gradient (elements).
+template <int NBIAS>
+struct BiasHead {
+  int64_t off[NBIAS > 0 ? NBIAS : 1], doff[NBIAS > 0 ? NBIAS : 1];
+  __device__ __forceinline__ void set(const BwdParams& p, int b, int g, int h) {
+#pragma unroll
+    for (int n = 0; n < NBIAS; ++n) {
+      off[n] = b * p.bias[n].sb + g * p.bias[n].sg + h * p.bias[n].sh;
+      doff[n] = b * p.dbias[n].sb + g * p.dbias[n].sg + h * p.dbias[n].sh;
+    }
+  }
+  // sum of the biases of score (i, j) in log2 units; i, j are valid indices
+  __device__ __forceinline__ float value(const BwdParams& p, int i, int j) const {
+    float s = 0.f;
+#pragma unroll
+    for (int n = 0; n < NBIAS; ++n)
+      s += bf16_to_f32(((const uint16_t*)p.bias[n].ptr)[off[n] + (int64_t)i * p.bias[n].si + (int64_t)j * p.bias[n].sj]);
+    return s * kLog2e;
+  }
+  // dS of score (i, j) into every wanted bias gradient (the axes a bias broadcasts along have stride 0: atomic sum)
+  __device__ __forceinline__ void add_grad(const BwdParams& p, int i, int j, float ds) const {
+#pragma unroll
+    for (int n = 0; n < NBIAS; ++n)
+      if (p.dbias[n].ptr != nullptr)
+        unsafeAtomicAdd((float*)p.dbias[n].ptr + doff[n] + (int64_t)i * p.dbias[n].si + (int64_t)j * p.dbias[n].sj, ds);
+  }
+};
+
 // Four consecutive channels of a dK or dV row: to the output tensor, or (grouped-query heads cut
 // over several workgroups) to this workgroup's fp32 partial.
 __device__ __forceinline__ void store_kv_grad(const BwdParams& p, const View& out, float* part, int split, int b, int g,
@@ -435,6 +466,8 @@ bwd_dq_kernel(const BwdParams p) {
   const float slope2 = C::MOD == kModAlibi ? p.alibi_slopes[h] * kLog2e : 0.f;
   int qdoc = 0;
   if constexpr ((MASK & kMaskDoc) != 0) qdoc = p.q_doc[(int64_t)b * p.Sq + ic];
+  BiasHead<C::NBIAS> bh_;
+  bh_.set(p, b, g, h);
 
   f32x16 acc[DB];
 #pragma unroll
@@ -512,6 +545,14 @@ bwd_dq_kernel(const BwdParams p) {
                                      make_int2(0, 0), make_int2(0, 0));
       if (cls == kSkip) return;                    // nothing visible: dS = 0
       const bool need_mask = (MASK & kMaskDoc) != 0 || iw + 31 >= p.Sq || cls != kFull;
+      float bl[C::NBIAS > 0 ? 16 : 1];             // this lane's bias values of the block (requested before the matrix work)
+      if constexpr (C::NBIAS > 0) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int jj = j0 + 32 * nb + 4 * w.half + 8 * (r >> 2) + (r & 3);
+          bl[r] = bh_.value(p, ic, jj < p.Sk ? jj : p.Sk - 1);
+        }
+      }
       f32x16 s = W::zero16(), dp = W::zero16();
       w.template row_stream<ST + nb * 32 * ROW>([&](auto kk, bf16x8 a) __attribute__((always_inline)) {
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s, 0, 0, 0);
@@ -538,7 +579,8 @@ bwd_dq_kernel(const BwdParams p) {
           const int r = 2 * r2 + e;
           const int j = jb + 8 * (r >> 2) + (r & 3);
           float fac;
-          const float a = replay_score<C::MOD>(s[r], c_scale, lse2, p.softcap, slope2, (float)(i - j), fac);
+          float a = replay_score<C::MOD>(s[r], c_scale, lse2, p.softcap, slope2, (float)(i - j), fac);
+          if constexpr (C::NBIAS > 0) a += bl[r];
           pr[e] = fast_exp2(a);
           dsv[e] = dp[r] - delta;
           if constexpr (C::MOD == kModSoftcap) dsv[e] *= fac;
@@ -555,6 +597,15 @@ bwd_dq_kernel(const BwdParams p) {
         dsv[0] *= pr[0];
         dsv[1] *= pr[1];
         dsw[r2] = pack_bf16(dsv[0], dsv[1]);
+        if constexpr (C::NBIAS > 0) {              // the bias gradient is dS itself (biases follow the score_mod)
+          static_assert(C::NBIAS == 0 || C::MOD != kModSoftcap, "dsv holds dS times the soft-cap derivative");
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            const int r = 2 * r2 + e;
+            const int j = jb + 8 * (r >> 2) + (r & 3);
+            if (i < p.Sq && j < p.Sk) bh_.add_grad(p, i, j, dsv[e]);
+          }
+        }
       }
       w.template tr_stream<ST + nb * 32 * ROW>([&](auto fc, bf16x8 a) __attribute__((always_inline)) {
         constexpr int f = decltype(fc)::value, d = f % DB, ks = f / DB;
@@ -801,6 +852,16 @@ bwd_dkdv_kernel(const BwdParams p) {
         qd[r] = qdoc[i < p.Sq ? i : p.Sq - 1];
       }
     }
+    float bl[C::NBIAS > 0 ? 16 : 1];               // bias values of the current block's scores of this lane
+    if constexpr (C::NBIAS > 0) {
+      BiasHead<C::NBIAS> bh_;
+      bh_.set(p, b, g, h);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int i = irow + 8 * (r >> 2) + (r & 3);
+        bl[r] = bh_.value(p, i < p.Sq ? i : p.Sq - 1, jc);
+      }
+    }
     uint32_t pw[8], dsw[8];
     auto ew_pair = [&](int r2) __attribute__((always_inline)) {      // P and dS of registers 2*r2, 2*r2 + 1
       float pv[2], dsv[2];
@@ -810,7 +871,8 @@ bwd_dkdv_kernel(const BwdParams p) {
         const int i = irow + 8 * (r >> 2) + (r & 3);
         const float lse2 = __int_as_float(st_l[r >> 2][r & 3]), delta = __int_as_float(st_d[r >> 2][r & 3]);
         float fac;
-        const float a = replay_score<C::MOD>(cur.s[r], c_scale, lse2, p.softcap, slope2, (float)(i - j), fac);
+        float a = replay_score<C::MOD>(cur.s[r], c_scale, lse2, p.softcap, slope2, (float)(i - j), fac);
+        if constexpr (C::NBIAS > 0) a += bl[r];
         pv[e] = fast_exp2(a);
         dsv[e] = cur.dp[r] - delta;
         if constexpr (C::MOD == kModSoftcap) dsv[e] *= fac;
@@ -1101,6 +1163,16 @@ bwd_dkdv_ws_kernel(const BwdParams p) {
           qd[r] = qdoc[i < p.Sq ? i : p.Sq - 1];
         }
       }
+      float bl[C::NBIAS > 0 ? 16 : 1];             // bias values of the current block's scores of this lane
+      if constexpr (C::NBIAS > 0) {
+        BiasHead<C::NBIAS> bh_;
+        bh_.set(p, b, g, h);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int i = irow + 8 * (r >> 2) + (r & 3);
+          bl[r] = bh_.value(p, i < p.Sq ? i : p.Sq - 1, jc);
+        }
+      }
       float pf[4];
       auto ew_pair = [&](auto r2c) __attribute__((always_inline)) {
         constexpr int r2 = decltype(r2c)::value;
@@ -1110,7 +1182,8 @@ bwd_dkdv_ws_kernel(const BwdParams p) {
           const int r = 2 * r2 + e;
           const int i = irow + 8 * (r >> 2) + (r & 3);
           const float lse2 = __int_as_float(st_l[r >> 2][r & 3]);
-          const float a = replay_score<C::MOD>(cur[r], c_scale, lse2, p.softcap, slope2, (float)(i - j), fc2[e]);
+          float a = replay_score<C::MOD>(cur[r], c_scale, lse2, p.softcap, slope2, (float)(i - j), fc2[e]);
+          if constexpr (C::NBIAS > 0) a += bl[r];
           pv[e] = fast_exp2(a);
         }
         if (need_mask) {                           // uniform; kept a branch: most blocks need no mask

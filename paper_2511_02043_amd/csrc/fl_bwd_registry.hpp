@@ -9,6 +9,7 @@ namespace fl {
 struct BwdKey {
   int D;            // head dim (D == Dv)
   int mod, mask;
+  int nbias;        // additive biases the kernels read (and whose gradient the dQ kernel emits)
 };
 
 typedef hipError_t (*BwdLaunchFn)(const BwdParams& p, int nblocks, hipStream_t stream);
@@ -70,14 +71,14 @@ hipError_t launch_bwd_dkdv_ws(const BwdParams& p, int nblocks, hipStream_t strea
 
 // CQ / CK: the shapes of the dQ kernel and of the dK/dV kernel (streamed tile rows, waves per SIMD).
 // WS: the dK/dV kernel with specialised waves (eight waves, two per SIMD) instead of the plain one.
-template <int D, int MOD, uint32_t MASK, int BN_Q, int WPE_Q, int BN_K, int WPE_K, bool WS>
+template <int D, int MOD, uint32_t MASK, int BN_Q, int WPE_Q, int BN_K, int WPE_K, bool WS, int NBIAS = 0>
 constexpr BwdEntry bwd_entry() {
-  typedef BwdCfg<D, MOD, MASK, BN_Q, WPE_Q> CQ;
-  typedef BwdCfg<D, MOD, MASK, BN_K, WPE_K> CK;
+  typedef BwdCfg<D, MOD, MASK, BN_Q, WPE_Q, NBIAS> CQ;
+  typedef BwdCfg<D, MOD, MASK, BN_K, WPE_K, NBIAS> CK;
   if constexpr (WS)
-    return BwdEntry{BwdKey{D, MOD, (int)MASK}, CQ::BM, &launch_bwd_prep<D>, &launch_bwd_dq<CQ>, &launch_bwd_dkdv_ws<CK>, &launch_bwd_reduce<D>};
+    return BwdEntry{BwdKey{D, MOD, (int)MASK, NBIAS}, CQ::BM, &launch_bwd_prep<D>, &launch_bwd_dq<CQ>, &launch_bwd_dkdv_ws<CK>, &launch_bwd_reduce<D>};
   else
-    return BwdEntry{BwdKey{D, MOD, (int)MASK}, CQ::BM, &launch_bwd_prep<D>, &launch_bwd_dq<CQ>, &launch_bwd_dkdv<CK>, &launch_bwd_reduce<D>};
+    return BwdEntry{BwdKey{D, MOD, (int)MASK, NBIAS}, CQ::BM, &launch_bwd_prep<D>, &launch_bwd_dq<CQ>, &launch_bwd_dkdv<CK>, &launch_bwd_reduce<D>};
 }
 
 const BwdEntry* entries_bwd64(int* n);

@@ -14,6 +14,9 @@ static const BwdEntry kEntries[] = {
     E(kModSoftcap, 0),     E(kModSoftcap, kMaskCausal),     E(kModNone, CW),       E(kModNone, CW | kMaskDoc),
     E(kModNone, kMaskDoc), E(kModNone, kMaskCausal | kMaskDoc), E(kModNone, kMaskPrefix),
     E(kModNone, kMaskPrefix | kMaskDoc),
+    // additive biases (Evoformer pair / row biases): plain and causal, one or two biases
+    bwd_entry<64, kModNone, 0, 64, 2, 64, 2, false, 1>(), bwd_entry<64, kModNone, 0, 64, 2, 64, 2, false, 2>(),
+    bwd_entry<64, kModNone, kMaskCausal, 64, 2, 64, 2, false, 1>(), bwd_entry<64, kModNone, kMaskCausal, 64, 2, 64, 2, false, 2>(),
 };
 #undef E
 const BwdEntry* entries_bwd64(int* n) {

@@ -184,6 +184,69 @@ def upload_backward(w, dout: np.ndarray, grad_dtype: str = "f32", device="cuda:0
 
 
 @dataclasses.dataclass
+class DeviceBackwardEx:
+    """Device tensors of one fl_attn_bwd_ex call: every gradient the variant has (dq, dk, dv, and dq2 / dk2 /
+    dlambda, dbias, dgate where the workload has those inputs)."""
+    fwd: DeviceWorkload
+    dout: torch.Tensor
+    grads: dict                          # name -> tensor (dbias: list)
+    aux: fb.fl_aux
+    extra: fb.fl_bwd_extra
+    keep: List[torch.Tensor]
+    tdout: fb.fl_tensor = None
+    tdq: fb.fl_tensor = None
+    tdk: fb.fl_tensor = None
+    tdv: fb.fl_tensor = None
+
+    def run(self, stream: int = 0) -> int:
+        f = self.fwd
+        return fb.fl_attn_bwd_ex(f.tq, f.tk, f.tv, f.tout, self.tdout, f.tlse, f.desc, self.aux,
+                                 self.tdq, self.tdk, self.tdv, self.extra, stream)
+
+    def run_checked(self, stream: int = 0) -> None:
+        fb.check(self.run(stream))
+
+
+def upload_backward_ex(w, dout: np.ndarray, grad_dtype: str = "f32", device="cuda:0") -> DeviceBackwardEx:
+    """upload_backward for any variant: the forward upload's aux block (biases, gate, second stream, lambda, ...)
+    with the backward workspace, plus every gradient output.  Run fwd.run_checked() first."""
+    fwd = upload(w, out_dtype="bf16", device=device, want_lse=True)
+    tdt = torch.bfloat16
+    gdt = torch.float32 if grad_dtype == "f32" else tdt
+    d_out = to_device(dout, tdt, device)
+    g = dict(dq=empty_like_layout(fwd.q, fwd.q.shape[4], gdt), dk=empty_like_layout(fwd.k, fwd.k.shape[4], gdt),
+             dv=empty_like_layout(fwd.v, fwd.v.shape[4], gdt))
+    # the aux tensors of the forward upload, by the order upload() appended them
+    it = iter(fwd.keep)
+    slopes = next(it) if w.alibi is not None else None
+    qd = kd = None
+    if w.q_doc is not None:
+        qd = next(it)
+        kd = qd if (w.kv_doc is w.q_doc) else next(it)
+    biases = [next(it) for _ in w.biases]
+    gate = next(it) if w.gate is not None else None
+    q2 = k2 = lam = None
+    if w.q2 is not None:
+        q2, k2, lam = next(it), next(it), next(it)
+    rmsw = next(it) if w.rms_weight is not None else None
+    nbytes = fb.fl_attn_bwd_ex_workspace_size(fwd.tq, fwd.tk, fwd.tv, fwd.desc)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)
+    aux = fb.aux_desc(alibi_slopes=slopes, q_doc_ids=qd, kv_doc_ids=kd, biases=biases, gate=gate, q2=q2, k2=k2,
+                      lambda_=lam, rms_weight=rmsw, workspace=ws)
+    if q2 is not None:
+        g["dq2"], g["dk2"] = empty_like_layout(q2, q2.shape[4], gdt), empty_like_layout(k2, k2.shape[4], gdt)
+        g["dlambda"] = torch.empty(q2.shape[2], dtype=torch.float32, device=device)
+    if gate is not None:
+        g["dgate"] = empty_like_layout(gate, gate.shape[4], gdt)
+    if biases:
+        g["dbias"] = [torch.empty(tuple(b.shape), dtype=torch.float32, device=device) for b in biases]
+    extra = fb.bwd_extra(dq2=g.get("dq2"), dk2=g.get("dk2"), dbias=g.get("dbias", ()), dgate=g.get("dgate"),
+                         dlambda=g.get("dlambda"))
+    return DeviceBackwardEx(fwd, d_out, g, aux, extra, [ws] + list(fwd.keep), fb.tensor_desc(d_out), fb.tensor_desc(g["dq"]),
+                            fb.tensor_desc(g["dk"]), fb.tensor_desc(g["dv"]))
+
+
+@dataclasses.dataclass
 class DeviceDecode:
     """Device tensors of one fl_attn_decode call (an inputs.DecodeWorkload)."""
     q: torch.Tensor
