@@ -202,10 +202,10 @@ typedef struct {
   uint32_t  reserved;
   fl_tensor dq2, dk2;      /* FL_DIFFERENTIAL: gradients of aux->q2 / aux->k2; shapes and dtypes as dq / dk; required */
   fl_tensor dbias[2];      /* gradient of aux->bias[n]: f32 with the sizes of aux->bias[n] (an axis of size 1 that
-                              broadcasts holds the sum over that axis; those sums use atomic adds, so they are
-                              reproducible only up to fp32 summation order); ptr NULL: not computed            */
+                              broadcasts holds the sum over that axis); ptr NULL: not computed.  The workspace then
+                              holds dS of every score in bf16 ([B, G, H, Sq, Sk], 2 bytes each) until it is summed  */
   fl_tensor dgate;         /* FL_EPI_GATE_SIGMOID: gradient of aux->gate, shape of out, bf16 or f32; ptr NULL: not computed */
-  float*    dlambda;       /* FL_DIFFERENTIAL: [H] f32 device (atomic sums over rows); NULL: not computed      */
+  float*    dlambda;       /* FL_DIFFERENTIAL: [H] f32 device; NULL: not computed                              */
 } fl_bwd_extra;
 
 /* fl_attn_bwd for every variant of the forward pass: additive biases (with their gradients), the sigmoid

@@ -323,7 +323,7 @@ struct EpiBwdParams {
   float* lse2[2];                   // per-stream lse * log2(e), +inf for rows without a visible key
   const float* lambda;
   const float* rms_w;
-  float* dlambda;                   // [H], atomic sums, or null
+  float* dl_rows;                   // per-row terms of dlambda (summed per head by reduce_dlambda_kernel), or null
   float rms_eps;
   int32_t B, G, H, Sq, Dv, Dc;
   int32_t ns, has_gate, has_rms, dgate_f32;
@@ -406,13 +406,53 @@ __global__ void __launch_bounds__(256) epi_bwd_kernel(const EpiBwdParams e) {
     e.delta[0][row] = d1;
     if (e.ns == 2) {
       e.delta[1][row] = d2;
-      if (e.dlambda != nullptr) unsafeAtomicAdd(e.dlambda + h, dl);
+      if (e.dl_rows != nullptr) e.dl_rows[row] = dl;
     }
     for (int s = 0; s < e.ns; ++s) {
       const float l = e.lse[b * e.lse_sb + (int64_t)(e.ns * g + s) * e.lse_sg + h * e.lse_sh + i];
       e.lse2[s][row] = l == -INFINITY ? INFINITY : l * fl::kLog2e;
     }
   }
+}
+
+// dlambda[h] = sum over (b, g, i) of the per-row terms; one workgroup per head, fixed summation order
+__global__ void __launch_bounds__(256) reduce_dlambda_kernel(const float* dl_rows, float* dlambda, int B, int G, int H, int Sq) {
+  __shared__ float part[256];
+  const int h = blockIdx.x;
+  float s = 0.f;
+  const int64_t n = (int64_t)B * G * Sq;
+  for (int64_t t = threadIdx.x; t < n; t += 256) {
+    const int64_t bg = t / Sq;
+    s += dl_rows[(bg * H + h) * Sq + t % Sq];
+  }
+  part[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 128; o >= 1; o >>= 1) {
+    if ((int)threadIdx.x < o) part[threadIdx.x] += part[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) dlambda[h] = part[0];
+}
+
+// Gradient of one bias from the staged dS (bf16 dense [B, G, H, Sq, Sk]): the sum over the axes the bias
+// broadcasts along (its size-1 axes), one thread per output element, fixed summation order.
+__global__ void __launch_bounds__(256) reduce_dbias_kernel(const uint16_t* ds, fl::BiasView out, int B, int G, int H, int Sq, int Sk,
+                                                           int ob, int og, int oh, int oi, int oj, int64_t total, int accumulate) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  const int j = (int)(idx % oj), i = (int)((idx / oj) % oi), h = (int)((idx / ((int64_t)oj * oi)) % oh);
+  const int g = (int)((idx / ((int64_t)oj * oi * oh)) % og), b = (int)(idx / ((int64_t)oj * oi * oh * og));
+  const int nb = ob == 1 ? B : 1, ng = og == 1 ? G : 1, nh = oh == 1 ? H : 1, ni = oi == 1 ? Sq : 1, nj = oj == 1 ? Sk : 1;
+  float s = 0.f;
+  for (int bb = 0; bb < nb; ++bb)
+    for (int gg = 0; gg < ng; ++gg)
+      for (int hh = 0; hh < nh; ++hh)
+        for (int ii = 0; ii < ni; ++ii) {
+          const uint16_t* row = ds + ((((int64_t)(b + bb) * G + (g + gg)) * H + (h + hh)) * Sq + (i + ii)) * Sk + j;
+          for (int jj = 0; jj < nj; ++jj) s += fl::bf16_to_f32(row[jj]);
+        }
+  float* dst = (float*)out.ptr + b * out.sb + g * out.sg + h * out.sh + (int64_t)i * out.si + (int64_t)j * out.sj;
+  *dst = accumulate ? *dst + s : s;                // the second softmax stream adds to the first one's sum
 }
 
 // bf16 [B, G, H, S, D] view -> dense [B, G, H, S, Dc] with zero channels past D (8 channels per thread)
@@ -449,14 +489,7 @@ __global__ void __launch_bounds__(256) scatter_grad_kernel(const float* a, const
   else *(uint2*)((uint16_t*)dst.ptr + o) = make_uint2(fl::pack_bf16(v.x, v.y), fl::pack_bf16(v.z, v.w));
 }
 
-// zero-fill of a strided fp32 [B, G, H, Sq, Sk] tensor (bias gradients are accumulated with atomic adds)
-__global__ void __launch_bounds__(256) zero_bias_grad_kernel(fl::BiasView t, int n1, int n2, int n3, int n4, int64_t total) {
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= total) return;
-  const int j = (int)(idx % n4), i = (int)((idx / n4) % n3), h = (int)((idx / ((int64_t)n4 * n3)) % n2);
-  const int g = (int)((idx / ((int64_t)n4 * n3 * n2)) % n1), b = (int)(idx / ((int64_t)n4 * n3 * n2 * n1));
-  ((float*)t.ptr)[b * t.sb + g * t.sg + h * t.sh + (int64_t)i * t.si + (int64_t)j * t.sj] = 0.f;
-}
+// zero-fill (dS staging under masks that skip blocks)
 __global__ void __launch_bounds__(256) zero_f32_kernel(float* p, int64_t n) {
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx < n) p[idx] = 0.f;
@@ -468,9 +501,9 @@ inline size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 struct ExLayout {
   int Dc, ns, hsplit;
   bool need_o, pad_qk, pad_v;
-  size_t stat, o, d_o, qpad, kpad, vpad, gq, gk, gv, sum, part;   // sizes of one region each
+  size_t stat, o, d_o, qpad, kpad, vpad, gq, gk, gv, sum, part, ds;   // sizes of one region each
   size_t off_lse2[2], off_delta[2], off_o[2], off_do[2], off_qpad[2], off_kpad[2], off_vpad, off_gq[2], off_gk[2], off_gv[2],
-      off_sum, off_part;
+      off_sum, off_part, off_dl, off_ds;
   size_t total;
 };
 ExLayout ex_layout(int64_t B, int64_t G, int64_t H, int64_t Hkv, int64_t Sq, int64_t Sk, int64_t D, int64_t Dv,
@@ -512,6 +545,10 @@ ExLayout ex_layout(int64_t B, int64_t G, int64_t H, int64_t Hkv, int64_t Sq, int
   L.off_vpad = take(L.vpad);
   L.off_sum = take(L.sum);
   L.off_part = take(2 * L.part);
+  L.off_dl = take(L.ns == 2 ? L.stat : 0);
+  // bias gradients: dS of every score (bf16), reduced over the broadcast axes afterwards
+  L.ds = d->n_bias > 0 ? up256(rq * (size_t)Sk * 2) : 0;
+  L.off_ds = take(L.ds);
   L.total = at;
   return L;
 }
@@ -1144,7 +1181,6 @@ fl_status fl_attn_bwd_ex(const fl_tensor* q, const fl_tensor* k, const fl_tensor
   }
 
   // ---- 2. epilogue derivative: per-stream dO, delta, lse2; gate and lambda gradients
-  if (diff && extra->dlambda != nullptr) hipLaunchKernelGGL(zero_f32_kernel, blocks(H), dim3(256), 0, stream, extra->dlambda, (int64_t)H);
   EpiBwdParams ep;
   memset(&ep, 0, sizeof(ep));
   ep.dout = make_view(dout);
@@ -1168,11 +1204,14 @@ fl_status fl_attn_bwd_ex(const fl_tensor* q, const fl_tensor* k, const fl_tensor
   }
   ep.lambda = aux->lambda;
   ep.rms_w = aux->rms_weight;
-  ep.dlambda = diff ? extra->dlambda : nullptr;
+  ep.dl_rows = diff && extra->dlambda != nullptr ? (float*)(ws + L.off_dl) : nullptr;
   ep.rms_eps = desc->rms_eps;
   ep.B = (int)B; ep.G = (int)G; ep.H = (int)H; ep.Sq = (int)Sq; ep.Dv = (int)Dv; ep.Dc = Dc;
   ep.ns = ns; ep.has_gate = has_gate; ep.has_rms = has_rms;
   hipLaunchKernelGGL(epi_bwd_kernel, blocks(rows_q * 64), dim3(256), 0, stream, ep);
+  if (ep.dl_rows != nullptr)
+    hipLaunchKernelGGL(reduce_dlambda_kernel, dim3((unsigned)H), dim3(256), 0, stream, (const float*)ep.dl_rows, extra->dlambda, (int)B, (int)G,
+                       (int)H, (int)Sq);
 
   // ---- 3. zero-padded copies for head dims below the kernels' own
   for (int s = 0; s < ns && L.pad_qk; ++s) {
@@ -1184,13 +1223,10 @@ fl_status fl_attn_bwd_ex(const fl_tensor* q, const fl_tensor* k, const fl_tensor
   if (L.pad_v)
     hipLaunchKernelGGL(pad_rows_kernel, blocks(rows_k * (Dc / 8)), dim3(256), 0, stream, make_view(v), (uint16_t*)(ws + L.off_vpad), (int)G,
                        (int)Hkv, (int)Sk, (int)Dv, Dc, rows_k);
-  for (uint32_t nb = 0; nb < desc->n_bias; ++nb)
-    if (dbias[nb].ptr != nullptr) {
-      const fl_tensor* gt = &extra->dbias[nb];
-      const int64_t total = gt->size[0] * gt->size[1] * gt->size[2] * gt->size[3] * gt->size[4];
-      hipLaunchKernelGGL(zero_bias_grad_kernel, blocks(total), dim3(256), 0, stream, dbias[nb], (int)gt->size[1], (int)gt->size[2],
-                         (int)gt->size[3], (int)gt->size[4], total);
-    }
+  const bool want_dbias = dbias[0].ptr != nullptr || dbias[1].ptr != nullptr;
+  // under a mask whole blocks are skipped by the dQ kernel: their dS is zero
+  if (want_dbias && mask != 0)
+    hipLaunchKernelGGL(zero_f32_kernel, blocks((int64_t)(L.ds / 4)), dim3(256), 0, stream, (float*)(ws + L.off_ds), (int64_t)(L.ds / 4));
   if ((e = hipGetLastError()) != hipSuccess) return fail(FL_ERR_LAUNCH, "backward pre-pass launch: %s", hipGetErrorString(e));
 
   // ---- 4. the backward kernels, once per stream, into dense fp32 gradient buffers
@@ -1214,10 +1250,8 @@ fl_status fl_attn_bwd_ex(const fl_tensor* q, const fl_tensor* k, const fl_tensor
   const int order = g_tuning.order >= 0 ? g_tuning.order : 1;
   p.order_q = order == 1 && (B * G * H) % 8 == 0;
   p.order_k = order == 1 && (B * G * Hkv * p.hsplit) % 8 == 0;
-  for (int nb = 0; nb < 2; ++nb) {
-    p.bias[nb] = bias[nb];
-    p.dbias[nb] = dbias[nb];
-  }
+  for (int nb = 0; nb < 2; ++nb) p.bias[nb] = bias[nb];
+  p.ds_stage = want_dbias ? (uint16_t*)(ws + L.off_ds) : nullptr;
   const int64_t nb_q = B * G * H * p.n_qtiles, nb_k = B * G * Hkv * p.hsplit * p.n_ktiles;
   if (nb_q > 0x7fffffffLL || nb_k > 0x7fffffffLL) return fail(FL_ERR_SHAPE, "too many workgroups");
   if (mask & FL_MASK_DOC) {
@@ -1241,6 +1275,14 @@ fl_status fl_attn_bwd_ex(const fl_tensor* q, const fl_tensor* k, const fl_tensor
     p.delta = (float*)(ws + L.off_delta[s]);
     p.lse2 = (float*)(ws + L.off_lse2[s]);
     if ((e = be->dq(p, (int)nb_q, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dq launch: %s", hipGetErrorString(e));
+    for (uint32_t nb = 0; nb < desc->n_bias; ++nb)
+      if (dbias[nb].ptr != nullptr) {               // this stream's dS, summed over the axes the bias broadcasts along
+        const fl_tensor* gt = &extra->dbias[nb];
+        const int64_t total = gt->size[0] * gt->size[1] * gt->size[2] * gt->size[3] * gt->size[4];
+        hipLaunchKernelGGL(reduce_dbias_kernel, blocks(total), dim3(256), 0, stream, (const uint16_t*)p.ds_stage, dbias[nb], (int)B, (int)G,
+                           (int)H, (int)Sq, (int)Sk, (int)gt->size[0], (int)gt->size[1], (int)gt->size[2], (int)gt->size[3],
+                           (int)gt->size[4], total, s);
+      }
     if ((e = be->dkdv(p, (int)nb_k, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dk/dv launch: %s", hipGetErrorString(e));
     if (p.hsplit > 1) {
       const int64_t chunks = rows_k * (Dc / 4);

@@ -57,8 +57,8 @@ struct BwdParams {
   float* part_dk;                  // hsplit > 1: fp32 partial sums [hsplit][B, G, Hkv, Sk, D], summed by bwd_reduce_kv_kernel
   float* part_dv;
   BiasView bias[2];                // the forward pass's additive biases (kernels built with NBIAS > 0), bf16
-  BiasView dbias[2];               // their gradients: fp32, same logical [B, G, H, Sq, Sk] axes, stride 0 on the axes
-                                   // the bias broadcasts along (those are summed with atomic adds); ptr null: not wanted
+  uint16_t* ds_stage;              // bias gradients wanted: dS of every score, bf16 dense [B, G, H, Sq, Sk]; the host sums it
+                                   // over the axes each bias broadcasts along afterwards (null: not wanted)
 };
 
 // chunk swizzle of a tile row (see the header comment): an XOR on the 16-byte chunk index that
@@ -310,13 +310,10 @@ __device__ __forceinline__ bool hidden(int i, int j, int Sq, int Sk, int window,
 // Offsets of the (b, g, h) slice of each bias / bias gradient (elements).
 template <int NBIAS>
 struct BiasHead {
-  int64_t off[NBIAS > 0 ? NBIAS : 1], doff[NBIAS > 0 ? NBIAS : 1];
+  int64_t off[NBIAS > 0 ? NBIAS : 1];
   __device__ __forceinline__ void set(const BwdParams& p, int b, int g, int h) {
 #pragma unroll
-    for (int n = 0; n < NBIAS; ++n) {
-      off[n] = b * p.bias[n].sb + g * p.bias[n].sg + h * p.bias[n].sh;
-      doff[n] = b * p.dbias[n].sb + g * p.dbias[n].sg + h * p.dbias[n].sh;
-    }
+    for (int n = 0; n < NBIAS; ++n) off[n] = b * p.bias[n].sb + g * p.bias[n].sg + h * p.bias[n].sh;
   }
   // sum of the biases of score (i, j) in log2 units; i, j are valid indices
   __device__ __forceinline__ float value(const BwdParams& p, int i, int j) const {
@@ -325,13 +322,6 @@ struct BiasHead {
     for (int n = 0; n < NBIAS; ++n)
       s += bf16_to_f32(((const uint16_t*)p.bias[n].ptr)[off[n] + (int64_t)i * p.bias[n].si + (int64_t)j * p.bias[n].sj]);
     return s * kLog2e;
-  }
-  // dS of score (i, j) into every wanted bias gradient (the axes a bias broadcasts along have stride 0: atomic sum)
-  __device__ __forceinline__ void add_grad(const BwdParams& p, int i, int j, float ds) const {
-#pragma unroll
-    for (int n = 0; n < NBIAS; ++n)
-      if (p.dbias[n].ptr != nullptr)
-        unsafeAtomicAdd((float*)p.dbias[n].ptr + doff[n] + (int64_t)i * p.dbias[n].si + (int64_t)j * p.dbias[n].sj, ds);
   }
 };
 
@@ -597,13 +587,23 @@ bwd_dq_kernel(const BwdParams p) {
         dsv[0] *= pr[0];
         dsv[1] *= pr[1];
         dsw[r2] = pack_bf16(dsv[0], dsv[1]);
-        if constexpr (C::NBIAS > 0) {              // the bias gradient is dS itself (biases follow the score_mod)
-          static_assert(C::NBIAS == 0 || C::MOD != kModSoftcap, "dsv holds dS times the soft-cap derivative");
+      }
+      if constexpr (C::NBIAS > 0) {                // the bias gradient is dS itself (biases follow the score_mod):
+        // staged for the host's reduction over the axes each bias broadcasts along; registers 4q .. 4q + 3 are
+        // the four consecutive keys jb + 8q ..
+        static_assert(C::NBIAS == 0 || C::MOD != kModSoftcap, "dsw holds dS times the soft-cap derivative");
+        if (p.ds_stage != nullptr && i < p.Sq) {
+          uint16_t* row = p.ds_stage + (((int64_t)(b * p.G + g) * p.H + h) * p.Sq + i) * p.Sk;
 #pragma unroll
-          for (int e = 0; e < 2; ++e) {
-            const int r = 2 * r2 + e;
-            const int j = jb + 8 * (r >> 2) + (r & 3);
-            if (i < p.Sq && j < p.Sk) bh_.add_grad(p, i, j, dsv[e]);
+          for (int q4 = 0; q4 < 4; ++q4) {
+            const int j = jb + 8 * q4;
+            if ((p.Sk & 3) == 0 && j + 3 < p.Sk) {
+              *(uint2*)(row + j) = make_uint2(dsw[2 * q4], dsw[2 * q4 + 1]);
+            } else {
+#pragma unroll
+              for (int u = 0; u < 4; ++u)
+                if (j + u < p.Sk) row[j + u] = (uint16_t)(dsw[2 * q4 + (u >> 1)] >> (16 * (u & 1)));
+            }
           }
         }
       }
