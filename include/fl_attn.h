@@ -101,7 +101,7 @@ typedef struct {
                               position j): the positional masks and ALiBi use positions, so e.g.
                               q_offset = Sk - Sq aligns a causal mask bottom-right (a chunk of new
                               queries against a longer key/value cache, Sec. 4.1 serving).  Document
-                              ids stay per row.  Forward pass only.                               */
+                              ids stay per row.  Forward and backward pass (not the decode step).   */
 } fl_variant_desc;
 
 typedef struct {
@@ -226,8 +226,8 @@ typedef struct {
  *   aux        as for fl_attn_fwd, with aux->workspace of fl_attn_bwd_ex_workspace_size bytes (16-byte aligned)
  *   extra      may be NULL when the variant has nothing beyond dq, dk, dv to write
  * Covered: everything fl_attn_bwd covers, plus biases with score_mod = FL_MOD_NONE under no mask or
- * FL_MASK_CAUSAL, plus any epilogue / FL_DIFFERENTIAL on top of those; q_offset must be 0.  The gradient of
- * rms_weight is not computed.  Same stream, ownership and error rules as fl_attn_fwd.                     */
+ * FL_MASK_CAUSAL, plus any epilogue / FL_DIFFERENTIAL on top of those.  The gradient of rms_weight is not
+ * computed.  Same stream, ownership and error rules as fl_attn_fwd.                     */
 fl_status fl_attn_bwd_ex(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v, const fl_tensor* out,
                          const fl_tensor* dout, const fl_tensor* lse, const fl_variant_desc* desc,
                          const fl_aux* aux, fl_tensor* dq, fl_tensor* dk, fl_tensor* dv,

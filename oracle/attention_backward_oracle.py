@@ -60,9 +60,10 @@ def softmax_rows(s: np.ndarray):
 
 
 def mask_matrix(Sq: int, Sk: int, *, causal: bool, window: Optional[int], prefix: Optional[int],
-                q_doc: Optional[np.ndarray], kv_doc: Optional[np.ndarray]) -> np.ndarray:
-    """True where score (i, j) is masked; the same four mask kinds as the forward pass."""
-    i = np.arange(Sq)[:, None]
+                q_doc: Optional[np.ndarray], kv_doc: Optional[np.ndarray], q_offset: int = 0) -> np.ndarray:
+    """True where score (i, j) is masked; the same four mask kinds as the forward pass.  Query row i sits
+    at sequence position i + q_offset (the positional masks compare positions, document ids are per row)."""
+    i = np.arange(Sq)[:, None] + q_offset
     j = np.arange(Sk)[None, :]
     masked = np.zeros((Sq, Sk), dtype=bool)
     if prefix is not None:
@@ -81,7 +82,7 @@ def attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray, dout: np.nda
                        prefix: Optional[int] = None, softcap_value: Optional[float] = None,
                        alibi_slopes: Optional[np.ndarray] = None,
                        q_doc: Optional[np.ndarray] = None, kv_doc: Optional[np.ndarray] = None,
-                       return_delta: bool = False, biases=(), return_dbias: bool = False):
+                       return_delta: bool = False, biases=(), return_dbias: bool = False, q_offset: int = 0):
     """Gradients of sum(out * dout) with respect to q, k, v.
 
     q [B,G,H,Sq,D], k [B,G,Hkv,Sk,D], v [B,G,Hkv,Sk,Dv], dout [B,G,H,Sq,Dv]; biases: arrays that
@@ -100,11 +101,11 @@ def attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray, dout: np.nda
     delta = np.zeros((B, G, H, Sq))
     full_biases = [np.broadcast_to(np.asarray(bb, dtype=np.float64), (B, G, H, Sq, Sk)) for bb in biases]
     ds_all = np.zeros((B, G, H, Sq, Sk)) if (return_dbias and biases) else None
-    dist = np.abs(np.arange(Sq)[:, None] - np.arange(Sk)[None, :]).astype(np.float64)
+    dist = np.abs(np.arange(Sq)[:, None] + q_offset - np.arange(Sk)[None, :]).astype(np.float64)
     for b in range(B):
         masked = mask_matrix(Sq, Sk, causal=causal, window=window, prefix=prefix,
                              q_doc=None if q_doc is None else q_doc[b],
-                             kv_doc=None if kv_doc is None else kv_doc[b])
+                             kv_doc=None if kv_doc is None else kv_doc[b], q_offset=q_offset)
         for g in range(G):
             for h in range(H):
                 hk = h // group
@@ -156,6 +157,10 @@ def variant_backward(w, dout):
                    alibi_slopes=w.alibi, q_doc=w.q_doc, kv_doc=w.kv_doc)
     fwd = dict(variant)
     fwd["biases"] = w.biases
+    off = int(getattr(w, "q_offset", 0) or 0)
+    if off:
+        variant["q_offset"] = off
+        fwd["q_pos"] = np.arange(w.q.shape[3], dtype=np.int64) + off
     dout = np.asarray(dout, dtype=np.float64)
     B, G, H, Sq, _ = w.q.shape
     Dv = w.v.shape[4]
@@ -207,4 +212,4 @@ def run_workload_backward(w, dout):
     assert not w.biases and w.gate is None and w.q2 is None and not w.rmsnorm
     return attention_backward(w.q, w.k, w.v, dout, scale=w.scale, causal=w.causal, window=w.window,
                               prefix=w.prefix, softcap_value=w.softcap, alibi_slopes=w.alibi,
-                              q_doc=w.q_doc, kv_doc=w.kv_doc)
+                              q_doc=w.q_doc, kv_doc=w.kv_doc, q_offset=int(getattr(w, "q_offset", 0) or 0))

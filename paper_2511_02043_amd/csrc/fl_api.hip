@@ -221,9 +221,7 @@ const fl::BwdEntry* find_bwd_entry(const fl_variant_desc* d, int D, int nbias = 
   return nullptr;
 }
 
-bool bwd_desc_ok(const fl_variant_desc* d) {
-  return d->n_bias == 0 && d->combine == FL_SINGLE && d->epilogue == 0 && d->q_offset == 0;
-}
+bool bwd_desc_ok(const fl_variant_desc* d) { return d->n_bias == 0 && d->combine == FL_SINGLE && d->epilogue == 0; }
 
 // Workspace of the backward pass: delta, lse2 ([B, G, H, Sq] floats each, 256-byte aligned), then
 // the document-id summaries of the tile skipper.
@@ -559,7 +557,6 @@ bool bwd_simple(const fl_variant_desc* d, int64_t D, int64_t Dv) {
 }
 // Can fl_attn_bwd_ex build the variant from the backward kernels?
 bool bwd_ex_ok(const fl_variant_desc* d, int64_t D, int64_t Dv) {
-  if (d->q_offset != 0) return false;
   if (!((D == 32 || D == 64 || D == 128) && (Dv == 32 || Dv == 64 || Dv == 128))) return false;
   if (d->n_bias > 0 && d->score_mod != FL_MOD_NONE) return false;
   return find_bwd_entry(d, core_dim(D, Dv), (int)d->n_bias) != nullptr;
@@ -907,7 +904,6 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
     return fail(FL_ERR_NULL, "a tensor descriptor is NULL");
   if (aux != nullptr && aux->struct_size != sizeof(fl_aux))
     return fail(FL_ERR_DESC, "aux->struct_size = %u, expected %zu", aux->struct_size, sizeof(fl_aux));
-  if (desc->q_offset != 0) return fail(FL_ERR_UNSUPPORTED, "the backward pass does not take a query offset");
   if (q->dtype != FL_BF16) return fail(FL_ERR_DTYPE, "the backward pass takes bf16 inputs (q dtype %d)", q->dtype);
   if (!bwd_simple(desc, q->size[4], v->size[4]))   // biases, epilogues, second stream, other head dims: the composed pass
     return fl_attn_bwd_ex(q, k, v, out, dout, lse, desc, aux, dq, dk, dv, nullptr, stream_v);
@@ -986,8 +982,9 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   p.q_doc = aux->q_doc_ids;
   p.kv_doc = aux->kv_doc_ids;
   p.B = (int)B; p.G = (int)G; p.H = (int)H; p.Hkv = (int)Hkv; p.Sq = (int)Sq; p.Sk = (int)Sk;
-  p.window = clamp_window(desc->window, Sq, Sk);
+  p.window = clamp_window(desc->window, Sq + desc->q_offset, Sk);
   p.prefix = desc->prefix_len;
+  p.q_off = desc->q_offset;
   p.scale = desc->scale;
   p.softcap = desc->softcap;
   p.dq_f32 = dq->dtype == FL_F32;
@@ -1236,8 +1233,9 @@ fl_status fl_attn_bwd_ex(const fl_tensor* q, const fl_tensor* k, const fl_tensor
   p.q_doc = aux->q_doc_ids;
   p.kv_doc = aux->kv_doc_ids;
   p.B = (int)B; p.G = (int)G; p.H = (int)H; p.Hkv = (int)Hkv; p.Sq = (int)Sq; p.Sk = (int)Sk;
-  p.window = clamp_window(desc->window, Sq, Sk);
+  p.window = clamp_window(desc->window, Sq + desc->q_offset, Sk);
   p.prefix = desc->prefix_len;
+  p.q_off = desc->q_offset;
   p.scale = desc->scale;
   p.softcap = desc->softcap;
   p.dq_f32 = 1;

@@ -57,6 +57,7 @@ struct BwdParams {
   float* part_dk;                  // hsplit > 1: fp32 partial sums [hsplit][B, G, Hkv, Sk, D], summed by bwd_reduce_kv_kernel
   float* part_dv;
   BiasView bias[2];                // the forward pass's additive biases (kernels built with NBIAS > 0), bf16
+  int32_t q_off;                   // query row i sits at sequence position i + q_off (positional masks, ALiBi); >= 0
   uint16_t* ds_stage;              // bias gradients wanted: dS of every score, bf16 dense [B, G, H, Sq, Sk]; the host sums it
                                    // over the axes each bias broadcasts along afterwards (null: not wanted)
 };
@@ -303,8 +304,8 @@ __device__ __forceinline__ float replay_score(float x, float c_scale, float lse2
 }
 
 template <uint32_t MASK>
-__device__ __forceinline__ bool hidden(int i, int j, int Sq, int Sk, int window, int prefix, int qdoc, int kdoc) {
-  return i >= Sq || j >= Sk || is_masked(MASK, i, j, window, prefix, qdoc, kdoc);
+__device__ __forceinline__ bool hidden(int i, int j, int Sq, int Sk, int q_off, int window, int prefix, int qdoc, int kdoc) {
+  return i >= Sq || j >= Sk || is_masked(MASK, i + q_off, j, window, prefix, qdoc, kdoc);
 }
 
 // Offsets of the (b, g, h) slice of each bias / bias gradient (elements).
@@ -466,7 +467,7 @@ bwd_dq_kernel(const BwdParams p) {
   // visible key range and tile skipping
   const int i_last = (i0 + C::BM < p.Sq ? i0 + C::BM : p.Sq) - 1;
   int k_lo, k_hi;
-  key_range(MASK, i0, i_last, p.Sk, p.window, p.prefix, k_lo, k_hi);
+  key_range(MASK, i0 + p.q_off, i_last + p.q_off, p.Sk, p.window, p.prefix, k_lo, k_hi);   // rows by their positions
   const int t_lo = k_lo / BN, t_hi = (k_hi + BN - 1) / BN;
   const int nks = (p.Sk + kSumBlock - 1) / kSumBlock;
   int2 qs_wg = make_int2(0, 0);
@@ -491,7 +492,7 @@ bwd_dq_kernel(const BwdParams p) {
         ks.x = min(ks.x, x.x);
         ks.y = max(ks.y, x.y);
       }
-    return classify_block(MASK, i0, i_last, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg, ks) != kSkip;
+    return classify_block(MASK, i0 + p.q_off, i_last + p.q_off, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg, ks) != kSkip;
   };
   auto next_tile = [&](int t) __attribute__((always_inline)) -> int {
     if constexpr ((MASK & kMaskDoc) != 0) {
@@ -531,7 +532,7 @@ bwd_dq_kernel(const BwdParams p) {
     static_for<0, NB>([&](auto nbc) __attribute__((always_inline)) {
       constexpr int nb = decltype(nbc)::value;
       // the wave's 32 rows against this block's 32 keys under the positional masks (uniform)
-      const int cls = classify_block(POS, iw, iw + 31, j0 + 32 * nb, j0 + 32 * nb + 31, p.Sk, p.window, p.prefix,
+      const int cls = classify_block(POS, iw + p.q_off, iw + 31 + p.q_off, j0 + 32 * nb, j0 + 32 * nb + 31, p.Sk, p.window, p.prefix,
                                      make_int2(0, 0), make_int2(0, 0));
       if (cls == kSkip) return;                    // nothing visible: dS = 0
       const bool need_mask = (MASK & kMaskDoc) != 0 || iw + 31 >= p.Sq || cls != kFull;
@@ -569,7 +570,7 @@ bwd_dq_kernel(const BwdParams p) {
           const int r = 2 * r2 + e;
           const int j = jb + 8 * (r >> 2) + (r & 3);
           float fac;
-          float a = replay_score<C::MOD>(s[r], c_scale, lse2, p.softcap, slope2, (float)(i - j), fac);
+          float a = replay_score<C::MOD>(s[r], c_scale, lse2, p.softcap, slope2, (float)(i + p.q_off - j), fac);
           if constexpr (C::NBIAS > 0) a += bl[r];
           pr[e] = fast_exp2(a);
           dsv[e] = dp[r] - delta;
@@ -581,7 +582,7 @@ bwd_dq_kernel(const BwdParams p) {
           for (int e = 0; e < 2; ++e) {
             const int r = 2 * r2 + e;
             const int j = jb + 8 * (r >> 2) + (r & 3);
-            if (hidden<MASK>(i, j, p.Sq, p.Sk, p.window, p.prefix, qdoc, (MASK & kMaskDoc) ? kd[r] : 0)) pr[e] = 0.f;
+            if (hidden<MASK>(i, j, p.Sq, p.Sk, p.q_off, p.window, p.prefix, qdoc, (MASK & kMaskDoc) ? kd[r] : 0)) pr[e] = 0.f;
           }
         }
         dsv[0] *= pr[0];
@@ -714,7 +715,9 @@ bwd_dkdv_kernel(const BwdParams p) {
   // query rows that can see the workgroup's keys; q-tile skipping for document masks
   const int j_last = (j0 + C::BM < p.Sk ? j0 + C::BM : p.Sk) - 1;
   int q_lo, q_hi;
-  query_range(MASK, j0, j_last, p.Sq, p.window, p.prefix, q_lo, q_hi);
+  query_range(MASK, j0, j_last, p.Sq + p.q_off, p.window, p.prefix, q_lo, q_hi);   // as positions; row = position - q_off
+  q_lo = max(q_lo - p.q_off, 0);
+  q_hi = max(q_hi - p.q_off, 0);
   const int t_lo = q_lo / BN, t_hi = (q_hi + BN - 1) / BN;
   const int nt = t_hi - t_lo;                      // q-tiles per head
   const int n_items = nt > 0 ? nt * group : 0;     // (head of the group, q-tile), head-major
@@ -743,7 +746,7 @@ bwd_dkdv_kernel(const BwdParams p) {
         qs.y = max(qs.y, x.y);
       }
     const int q_last = (t * BN + BN < p.Sq ? t * BN + BN : p.Sq) - 1;
-    return classify_block(MASK, t * BN, q_last, j0, j0 + C::BM - 1, p.Sk, p.window, p.prefix, qs, ks_wg) != kSkip;
+    return classify_block(MASK, t * BN + p.q_off, q_last + p.q_off, j0, j0 + C::BM - 1, p.Sk, p.window, p.prefix, qs, ks_wg) != kSkip;
   };
   auto next_item = [&](int it) __attribute__((always_inline)) -> int {
     if constexpr ((MASK & kMaskDoc) != 0) {
@@ -807,7 +810,7 @@ bwd_dkdv_kernel(const BwdParams p) {
     const int t = t_lo + it % nt, h = h_first + it / nt;
     const int ib = t * BN + 32 * QB;
     const float slope2 = C::MOD == kModAlibi ? p.alibi_slopes[h] * kLog2e : 0.f;
-    const int cls = classify_block(POS, ib, ib + 31, jw, jw + 31, p.Sk, p.window, p.prefix, make_int2(0, 0), make_int2(0, 0));
+    const int cls = classify_block(POS, ib + p.q_off, ib + 31 + p.q_off, jw, jw + 31, p.Sk, p.window, p.prefix, make_int2(0, 0), make_int2(0, 0));
     const bool need_mask = (MASK & kMaskDoc) != 0 || ib + 31 >= p.Sq || cls != kFull;
     uint32_t ra_n[KK], ta_c[DB][2];
 #pragma unroll
@@ -871,7 +874,7 @@ bwd_dkdv_kernel(const BwdParams p) {
         const int i = irow + 8 * (r >> 2) + (r & 3);
         const float lse2 = __int_as_float(st_l[r >> 2][r & 3]), delta = __int_as_float(st_d[r >> 2][r & 3]);
         float fac;
-        float a = replay_score<C::MOD>(cur.s[r], c_scale, lse2, p.softcap, slope2, (float)(i - j), fac);
+        float a = replay_score<C::MOD>(cur.s[r], c_scale, lse2, p.softcap, slope2, (float)(i + p.q_off - j), fac);
         if constexpr (C::NBIAS > 0) a += bl[r];
         pv[e] = fast_exp2(a);
         dsv[e] = cur.dp[r] - delta;
@@ -883,7 +886,7 @@ bwd_dkdv_kernel(const BwdParams p) {
         for (int e = 0; e < 2; ++e) {
           const int r = 2 * r2 + e;
           const int i = irow + 8 * (r >> 2) + (r & 3);
-          if (hidden<MASK>(i, j, p.Sq, p.Sk, p.window, p.prefix, (MASK & kMaskDoc) ? qd[r] : 0, kdoc)) pv[e] = 0.f;
+          if (hidden<MASK>(i, j, p.Sq, p.Sk, p.q_off, p.window, p.prefix, (MASK & kMaskDoc) ? qd[r] : 0, kdoc)) pv[e] = 0.f;
         }
       }
       dsv[0] *= pv[0];
@@ -1023,7 +1026,9 @@ bwd_dkdv_ws_kernel(const BwdParams p) {
   // query rows that can see the workgroup's keys; q-tile skipping for document masks
   const int j_last = (j0 + C::BM < p.Sk ? j0 + C::BM : p.Sk) - 1;
   int q_lo, q_hi;
-  query_range(MASK, j0, j_last, p.Sq, p.window, p.prefix, q_lo, q_hi);
+  query_range(MASK, j0, j_last, p.Sq + p.q_off, p.window, p.prefix, q_lo, q_hi);   // as positions; row = position - q_off
+  q_lo = max(q_lo - p.q_off, 0);
+  q_hi = max(q_hi - p.q_off, 0);
   const int t_lo = q_lo / BN, t_hi = (q_hi + BN - 1) / BN;
   const int nt = t_hi - t_lo;                      // q-tiles per head
   const int n_items = nt > 0 ? nt * group : 0;     // (head of the group, q-tile), head-major
@@ -1052,7 +1057,7 @@ bwd_dkdv_ws_kernel(const BwdParams p) {
         qs.y = max(qs.y, x.y);
       }
     const int q_last = (t * BN + BN < p.Sq ? t * BN + BN : p.Sq) - 1;
-    return classify_block(MASK, t * BN, q_last, j0, j0 + C::BM - 1, p.Sk, p.window, p.prefix, qs, ks_wg) != kSkip;
+    return classify_block(MASK, t * BN + p.q_off, q_last + p.q_off, j0, j0 + C::BM - 1, p.Sk, p.window, p.prefix, qs, ks_wg) != kSkip;
   };
   auto next_item = [&](int it) __attribute__((always_inline)) -> int {
     if constexpr ((MASK & kMaskDoc) != 0) {
@@ -1144,7 +1149,7 @@ bwd_dkdv_ws_kernel(const BwdParams p) {
       const int t = t_lo + it % nt, h = h_first + it / nt;
       const int ib = t * BN + 32 * QB;
       const float slope2 = C::MOD == kModAlibi ? p.alibi_slopes[h] * kLog2e : 0.f;
-      const int cls = classify_block(POS, ib, ib + 31, jw, jw + 31, p.Sk, p.window, p.prefix, make_int2(0, 0), make_int2(0, 0));
+      const int cls = classify_block(POS, ib + p.q_off, ib + 31 + p.q_off, jw, jw + 31, p.Sk, p.window, p.prefix, make_int2(0, 0), make_int2(0, 0));
       const bool need_mask = (MASK & kMaskDoc) != 0 || ib + 31 >= p.Sq || cls != kFull;
       uint32_t ra_n[KK];
 #pragma unroll
@@ -1182,7 +1187,7 @@ bwd_dkdv_ws_kernel(const BwdParams p) {
           const int r = 2 * r2 + e;
           const int i = irow + 8 * (r >> 2) + (r & 3);
           const float lse2 = __int_as_float(st_l[r >> 2][r & 3]);
-          float a = replay_score<C::MOD>(cur[r], c_scale, lse2, p.softcap, slope2, (float)(i - j), fc2[e]);
+          float a = replay_score<C::MOD>(cur[r], c_scale, lse2, p.softcap, slope2, (float)(i + p.q_off - j), fc2[e]);
           if constexpr (C::NBIAS > 0) a += bl[r];
           pv[e] = fast_exp2(a);
         }
@@ -1192,7 +1197,7 @@ bwd_dkdv_ws_kernel(const BwdParams p) {
           for (int e = 0; e < 2; ++e) {
             const int r = 2 * r2 + e;
             const int i = irow + 8 * (r >> 2) + (r & 3);
-            if (hidden<MASK>(i, j, p.Sq, p.Sk, p.window, p.prefix, (MASK & kMaskDoc) ? qd[r] : 0, kdoc)) pv[e] = 0.f;
+            if (hidden<MASK>(i, j, p.Sq, p.Sk, p.q_off, p.window, p.prefix, (MASK & kMaskDoc) ? qd[r] : 0, kdoc)) pv[e] = 0.f;
           }
         }
         pw[r2] = pack_bf16(pv[0], pv[1]);

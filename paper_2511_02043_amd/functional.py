@@ -48,7 +48,7 @@ def _check_aux(name: str, t: Optional[torch.Tensor], dtype: torch.dtype, shape, 
         raise ValueError(f"{name} must have unit stride along its last axis")
 
 
-def _desc(scale, causal, window, prefix, softcap, alibi_slopes, q_doc_ids):
+def _desc(scale, causal, window, prefix, softcap, alibi_slopes, q_doc_ids, q_offset=0):
     mask = 0
     if causal:
         mask |= fb.FL_MASK_CAUSAL
@@ -62,15 +62,15 @@ def _desc(scale, causal, window, prefix, softcap, alibi_slopes, q_doc_ids):
         raise ValueError("one score_mod at a time")
     mod = fb.FL_MOD_SOFTCAP if softcap is not None else (fb.FL_MOD_ALIBI if alibi_slopes is not None else fb.FL_MOD_NONE)
     return fb.variant_desc(scale=float(scale), score_mod=mod, softcap=float(softcap or 0.0), mask=mask,
-                           window=int(window or 0), prefix_len=int(prefix or 0))
+                           window=int(window or 0), prefix_len=int(prefix or 0), q_offset=int(q_offset))
 
 
 class _Attention(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, q, k, v, scale, causal, window, prefix, softcap, alibi_slopes, q_doc_ids, kv_doc_ids):
+    def forward(ctx, q, k, v, scale, causal, window, prefix, softcap, alibi_slopes, q_doc_ids, kv_doc_ids, q_offset):
         q5, k5, v5 = _as5(q), _as5(k), _as5(v)
         B, G, H, Sq, _ = q5.shape
-        desc = _desc(scale, causal, window, prefix, softcap, alibi_slopes, q_doc_ids)
+        desc = _desc(scale, causal, window, prefix, softcap, alibi_slopes, q_doc_ids, q_offset)
         out = torch.empty((B, G, H, Sq, v5.shape[4]), dtype=q.dtype, device=q.device)
         lse = torch.empty((B, G, H, Sq, 1), dtype=torch.float32, device=q.device)
         tq, tk, tv, tout, tlse = (fb.tensor_desc(x) for x in (q5, k5, v5, out, lse))
@@ -82,19 +82,19 @@ class _Attention(torch.autograd.Function):
         stream = torch.cuda.current_stream(q.device).cuda_stream
         fb.check(fb.fl_attn_fwd(tq, tk, tv, desc, aux, tout, tlse, stream))
         ctx.save_for_backward(q, k, v, out, lse)
-        ctx.variant = (scale, causal, window, prefix, softcap)
+        ctx.variant = (scale, causal, window, prefix, softcap, q_offset)
         ctx.aux_tensors = (alibi_slopes, q_doc_ids, kv_doc_ids)
         return out if q.dim() == 5 else out.squeeze(1)
 
     @staticmethod
     def backward(ctx, dout):
         q, k, v, out, lse = ctx.saved_tensors
-        scale, causal, window, prefix, softcap = ctx.variant
+        scale, causal, window, prefix, softcap, q_offset = ctx.variant
         alibi_slopes, q_doc_ids, kv_doc_ids = ctx.aux_tensors
         q5, k5, v5, d5 = _as5(q), _as5(k), _as5(v), _as5(dout)
         if d5.stride(-1) != 1 or any(st % 8 for st in d5.stride()[:-1]):
             d5 = d5.contiguous()                   # the kernels need unit inner stride and 16-byte aligned rows
-        desc = _desc(scale, causal, window, prefix, softcap, alibi_slopes, q_doc_ids)
+        desc = _desc(scale, causal, window, prefix, softcap, alibi_slopes, q_doc_ids, q_offset)
         dq, dk, dv = torch.empty_like(q5), torch.empty_like(k5), torch.empty_like(v5)
         tq, tk, tv, tout, tdo, tlse, tdq, tdk, tdv = (fb.tensor_desc(x) for x in (q5, k5, v5, out, d5, lse, dq, dk, dv))
         nbytes = fb.fl_attn_bwd_workspace_size(tq, tk, desc)
@@ -104,17 +104,20 @@ class _Attention(torch.autograd.Function):
         fb.check(fb.fl_attn_bwd(tq, tk, tv, tout, tdo, tlse, desc, aux, tdq, tdk, tdv, stream))
         if q.dim() == 4:
             dq, dk, dv = dq.squeeze(1), dk.squeeze(1), dv.squeeze(1)
-        return (dq, dk, dv) + (None,) * 8
+        return (dq, dk, dv) + (None,) * 9
 
 
 def attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, scale: Optional[float] = None,
               causal: bool = False, window: Optional[int] = None, prefix: Optional[int] = None,
               softcap: Optional[float] = None, alibi_slopes: Optional[torch.Tensor] = None,
-              q_doc_ids: Optional[torch.Tensor] = None, kv_doc_ids: Optional[torch.Tensor] = None) -> torch.Tensor:
+              q_doc_ids: Optional[torch.Tensor] = None, kv_doc_ids: Optional[torch.Tensor] = None,
+              q_offset: int = 0) -> torch.Tensor:
     """softmax(mask(score_mod(scale * q k^T))) v on the library's fused kernels, differentiable in
     q, k and v.  q [B, (G,) H, Sq, D], k and v [B, (G,) Hkv, Sk, D] with Hkv dividing H; bf16.
 
     alibi_slopes: float32 [H]; q_doc_ids / kv_doc_ids: int32 [B, Sq] / [B, Sk] (kv defaults to q's).
+    q_offset: query row i sits at sequence position i + q_offset in the positional masks and ALiBi
+    (Sk - Sq aligns a causal mask bottom-right: a chunk of new queries against a longer cache).
     """
     if not q.is_cuda or q.dtype != torch.bfloat16:
         raise ValueError("attention() takes bf16 CUDA tensors (there is no CPU or fallback path)")
@@ -128,7 +131,9 @@ def attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, scale: Optio
     _check_aux("alibi_slopes", alibi_slopes, torch.float32, (q5.shape[2],), q.device)
     _check_aux("q_doc_ids", q_doc_ids, torch.int32, (q5.shape[0], q5.shape[3]), q.device)
     _check_aux("kv_doc_ids", kv_doc_ids, torch.int32, (k5.shape[0], k5.shape[3]), q.device)
-    return _Attention.apply(q, k, v, scale, causal, window, prefix, softcap, alibi_slopes, q_doc_ids, kv_doc_ids)
+    if q_offset < 0:
+        raise ValueError("q_offset must be >= 0")
+    return _Attention.apply(q, k, v, scale, causal, window, prefix, softcap, alibi_slopes, q_doc_ids, kv_doc_ids, int(q_offset))
 
 
 def decode_attention(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, seq_lens: torch.Tensor,

@@ -121,7 +121,7 @@ def test_backward_validation_paths_return_before_any_launch():
     assert fb.fl_bwd_supported(fb.variant_desc(scale=0.125, combine=fb.FL_DIFFERENTIAL), fb.FL_BF16, 64, 64)
     assert not fb.fl_bwd_supported(d, fb.FL_BF16, 96, 96)
     assert not fb.fl_bwd_supported(fb.variant_desc(scale=0.125, n_bias=1, mask=fb.FL_MASK_DOC), fb.FL_BF16, 64, 64)
-    assert not fb.fl_bwd_supported(fb.variant_desc(scale=0.125, mask=fb.FL_MASK_CAUSAL, q_offset=4), fb.FL_BF16, 64, 64)
+    assert fb.fl_bwd_supported(fb.variant_desc(scale=0.125, mask=fb.FL_MASK_CAUSAL, q_offset=4), fb.FL_BF16, 64, 64)
     # workspace: two float rows statistics per query row, each array padded to 256 bytes
     assert fb.fl_attn_bwd_workspace_size(t, t, d) == 2 * 512
     dd = fb.variant_desc(scale=0.125, mask=fb.FL_MASK_DOC)

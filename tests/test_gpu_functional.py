@@ -118,3 +118,25 @@ def test_wrapper_refuses_arrays_the_abi_would_misread():
     # the accepted forms still run
     out = attention(q, q, q, q_doc_ids=ids.to(torch.int32))
     assert out.shape == q.shape
+
+
+def test_autograd_with_query_offset():
+    """attention(..., q_offset=Sk - Sq): a chunk of queries against a longer key sequence, output and gradients."""
+    import torch
+    from paper_2511_02043_amd.functional import attention
+    w = inputs.causal_bf16(B=1, H=4, Hkv=2, S=100, Sk=420, D=64)
+    w.q_offset = 320
+    dout = inputs.dout_for(w)
+    dev = "cuda:0"
+    q, k, v = (torch.from_numpy(np.ascontiguousarray(x[:, 0])).to(dev, torch.bfloat16).requires_grad_(True) for x in (w.q, w.k, w.v))
+    out = attention(q, k, v, scale=w.scale, causal=True, q_offset=320)
+    out.backward(torch.from_numpy(np.ascontiguousarray(dout[:, 0])).to(dev, torch.bfloat16))
+    torch.cuda.synchronize()
+    ref_out, _ = ao.run_workload(w)
+    ref = bo.run_workload_backward(w, dout)
+    got = out.detach().float().cpu().numpy()[:, None]
+    assert np.all(np.abs(got - ref_out) <= 1e-2 + 2.0 ** -8 * np.abs(ref_out))
+    for name, t, r in zip(("dq", "dk", "dv"), (q.grad, k.grad, v.grad), ref):
+        e = rel_l2(t.float().cpu().numpy()[:, None], r)
+        print(f"offset {name}: rel_l2={e:.3e}", flush=True)
+        assert e <= 5e-3, (name, e)

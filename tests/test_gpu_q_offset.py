@@ -71,10 +71,60 @@ def test_chunks_reassemble_the_square_problem():
     assert torch.equal(got, whole) and torch.equal(got_lse, whole_lse)
 
 
-def test_offset_is_validated_and_refused_where_not_built():
+def test_offset_is_validated():
     w = inputs.causal_bf16(B=1, H=2, S=64, D=64)
     dw = runner.upload(w)
     bad = fb.variant_desc(scale=w.scale, mask=fb.FL_MASK_CAUSAL, q_offset=-1)
     assert fb.fl_attn_fwd(dw.tq, dw.tk, dw.tv, bad, None, dw.tout, dw.tlse) == fb.FL_ERR_DESC
     off = fb.variant_desc(scale=w.scale, mask=fb.FL_MASK_CAUSAL, q_offset=5)
-    assert not fb.fl_bwd_supported(off, fb.FL_BF16, 64, 64)
+    assert fb.fl_bwd_supported(off, fb.FL_BF16, 64, 64)
+    kv = fb.paged_kv(page_size=64, seq_lens=dw.q.new_zeros(1, dtype=__import__("torch").int32), max_seq_len=64)
+    assert fb.fl_attn_decode(dw.tq, dw.tk, dw.tv, kv, off, None, dw.tout, None) == fb.FL_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("kind,Sq,Sk,D", [("causal", 130, 700, 64), ("window", 300, 4096 + 37, 64), ("prefix", 200, 900, 128),
+                                           ("alibi_causal", 77, 500, 64), ("doc_causal", 256, 2000, 128), ("causal", 500, 8192 - 91, 128)])
+def test_backward_with_offset(kind, Sq, Sk, D):
+    """Gradients of a chunk of queries against a longer key sequence (bottom-right aligned masks): dq, dk, dv against the
+    backward oracle with the same positions; keys beyond the chunk's positions get exactly zero."""
+    import torch
+    from oracle import attention_backward_oracle as bo
+    w = chunk(kind, Sq, Sk, D, H=4, Hkv=2 if kind == "causal" else None, B=1)
+    if kind == "window":
+        w.window = 300
+    dout = inputs.dout_for(w)
+    db = runner.upload_backward(w, dout, grad_dtype="f32")
+    db.fwd.run_checked()
+    for t in (db.dq, db.dk, db.dv):
+        t.fill_(float("nan"))
+    db.run_checked()
+    torch.cuda.synchronize()
+    ref = bo.run_workload_backward(w, dout)
+    for name, t, r in zip(("dq", "dk", "dv"), (db.dq, db.dk, db.dv), ref):
+        g = t.float().cpu().numpy().astype(np.float64)
+        assert np.all(np.isfinite(g)), name
+        diff = g - r
+        rel = float(np.sqrt(np.sum(diff * diff) / np.sum(r * r)))
+        print(f"{w.name} {name}: rel_l2={rel:.3e}", flush=True)
+        assert rel <= 5e-3, (name, rel)
+        assert np.all(np.abs(diff) <= 1e-2 * float(np.max(np.abs(r))))
+
+
+def test_backward_ex_with_offset():
+    """The composed backward pass (gate + second stream here) takes the offset as well."""
+    import torch
+    from oracle import attention_backward_oracle as bo
+    w = inputs.combination_bf16(D=64, pos_mask="causal", diff=True, gate=True, S=90, Sk=333, B=1, H=2)
+    w.q_offset = 333 - 90
+    dout = inputs.dout_for(w)
+    db = runner.upload_backward_ex(w, dout)
+    db.fwd.run_checked()
+    db.run_checked()
+    torch.cuda.synchronize()
+    ref = bo.variant_backward(w, dout)
+    for name in ("dq", "dk", "dv", "dq2", "dk2", "dgate", "dlambda"):
+        g = db.grads[name].float().cpu().numpy().astype(np.float64)
+        diff = g - ref[name]
+        rel = float(np.sqrt(np.sum(diff * diff) / np.sum(ref[name] ** 2)))
+        print(f"offset + diff + gate {name}: rel_l2={rel:.3e}", flush=True)
+        assert rel <= 5e-3, (name, rel)

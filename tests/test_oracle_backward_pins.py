@@ -356,3 +356,45 @@ def test_variant_backward_reduces_to_the_plain_one_and_identities():
     single = bo.attention_backward(wd.q, wd.k, wd.v, dout, scale=wd.scale)
     np.testing.assert_allclose(gd["dq"], single[0], rtol=0, atol=1e-13)
     np.testing.assert_allclose(gd["dv"], single[2], rtol=0, atol=1e-13)
+
+
+# ---------------------------------------------------------------------------------------
+# 7. Query-position offset: finite differences of the forward oracle (whose offset handling is pinned
+#    against SDPA with the mask written out), and equality with the rows of the square problem.
+# ---------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("kind", ["causal", "window", "prefix", "alibi_causal"])
+def test_query_offset_backward(kind):
+    Sq, Sk, off, D = 7, 19, 12, 6
+    q, k, v = rand((1, 1, 2, Sq, D), 71), rand((1, 1, 2, Sk, D), 72), rand((1, 1, 2, Sk, D), 73)
+    dout = rand((1, 1, 2, Sq, D), 74)
+    var = dict(causal=dict(causal=True), window=dict(window=4), prefix=dict(prefix=15),
+               alibi_causal=dict(causal=True, alibi_slopes=np.array([0.3, 0.7])))[kind]
+    dq, dk, dv = bo.attention_backward(q, k, v, dout, scale=0.37, q_offset=off, **var)
+    pos = np.arange(Sq) + off
+
+    def loss(q_, k_, v_):
+        out, _ = ao.attention(q_, k_, v_, scale=0.37, q_pos=pos, **var)
+        return float(np.sum(out * dout))
+
+    r = np.random.Generator(np.random.PCG64(75))
+    eps = 1e-6
+    for grad, which in ((dq, 0), (dk, 1), (dv, 2)):
+        base = (q, k, v)[which]
+        for _ in range(10):
+            idx = tuple(int(r.integers(0, n)) for n in base.shape)
+            plus, minus = base.copy(), base.copy()
+            plus[idx] += eps
+            minus[idx] -= eps
+            args_p = [q, k, v]
+            args_m = [q, k, v]
+            args_p[which], args_m[which] = plus, minus
+            fd = (loss(*args_p) - loss(*args_m)) / (2 * eps)
+            assert abs(fd - grad[idx]) <= 2e-6 * max(1.0, abs(fd)), (kind, which, idx)
+    if kind == "causal":                            # the chunk's rows inside the square problem over the same keys
+        qf = np.concatenate([np.zeros((1, 1, 2, off, D)), q], axis=3)
+        df = np.concatenate([np.zeros((1, 1, 2, off, D)), dout], axis=3)
+        dqf, dkf, dvf = bo.attention_backward(qf, k, v, df, scale=0.37, causal=True)
+        np.testing.assert_allclose(dq, dqf[:, :, :, off:], rtol=0, atol=1e-13)
+        np.testing.assert_allclose(dk, dkf, rtol=0, atol=1e-13)
+        np.testing.assert_allclose(dv, dvf, rtol=0, atol=1e-13)
