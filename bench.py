@@ -440,18 +440,30 @@ def sustained_power_clock(dw, flops, seconds=1.5, max_seconds=6.0):
     samples, smi = [], {}
     stop = threading.Event()
 
-    def sampler():
+    def power_sampler():
         t0 = time.perf_counter()
-        asked = False
         while not stop.is_set():
             pw, cap = _read_sysfs_power()
             if pw is not None:
                 samples.append((time.perf_counter() - t0, pw, cap))
-            if not asked and time.perf_counter() - t0 > 0.5:
-                asked = True
-                smi["clk"], smi["power"] = _read_smi_clock()
-                smi["done"] = True
             time.sleep(0.02)
+
+    def sampler():                                 # the clock query takes a few tenths of a second: three of them
+        pt = threading.Thread(target=power_sampler, daemon=True)
+        pt.start()
+        time.sleep(0.4)
+        clks = []
+        for _ in range(3):
+            if stop.is_set():
+                break
+            c, pw = _read_smi_clock()
+            if c is not None:
+                clks.append(c)
+            smi["power"] = pw
+        smi["clk"] = float(np.mean(clks)) if clks else None
+        smi["clk_samples"] = clks
+        smi["done"] = True
+        pt.join(timeout=5)
 
     th = threading.Thread(target=sampler, daemon=True)
     th.start()
@@ -474,9 +486,10 @@ def sustained_power_clock(dw, flops, seconds=1.5, max_seconds=6.0):
     late = [pw for (t, pw, cap) in samples if t > 0.3]
     cap = next((c for (_, _, c) in samples if c is not None), None)
     return {"socket_power_w": float(np.mean(late)) if late else smi.get("power"),
-            "power_cap_w": cap, "sclk_mhz": smi.get("clk"), "sclk_max_mhz": 2400,
+            "power_cap_w": cap, "sclk_mhz": smi.get("clk"), "sclk_samples_mhz": smi.get("clk_samples"), "sclk_max_mhz": 2400,
             "launches": n, "tflops_sustained": flops * n / (e0.elapsed_time(e1) * 1e-3) / 1e12,
-            "source": "hwmon power1_input sampled every 20 ms; amd-smi metric -c once, both during a back-to-back run of the same launch"}
+            "source": "hwmon power1_input sampled every 20 ms; mean shader clock of the 8 XCDs from three amd-smi metric -c queries; "
+                      "both during a back-to-back run of the same launch"}
 
 
 def run_grid(steps, warmup):
