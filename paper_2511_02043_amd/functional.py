@@ -6,9 +6,10 @@ the C-ABI binding; no attention arithmetic happens here and there is no fallback
 are [B, H, S, D] (or [B, G, H, S, D] with an extra independent row axis) bf16 CUDA tensors;
 strided views are passed as they are.
 
-Differentiable variants: scale, causal / sliding-window / PrefixLM / document masks, ALiBi,
-tanh soft-cap, grouped-query heads (the variants fl_attn_bwd covers).  Biases, the sigmoid gate
-and differential attention are forward-only here: use runner.upload / fl_attn_fwd for those.
+`attention()`: scale, causal / sliding-window / PrefixLM / document masks, ALiBi, tanh soft-cap,
+grouped-query heads, query-position offset (the variants fl_attn_bwd covers).
+`variant_attention()`: the same plus additive biases, the sigmoid gate, RMSNorm and the differential
+second stream, differentiable in every tensor input (fl_attn_bwd_ex).
 """
 from __future__ import annotations
 
@@ -134,6 +135,130 @@ def attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, scale: Optio
     if q_offset < 0:
         raise ValueError("q_offset must be >= 0")
     return _Attention.apply(q, k, v, scale, causal, window, prefix, softcap, alibi_slopes, q_doc_ids, kv_doc_ids, int(q_offset))
+
+
+def _mask_bits(causal, window, prefix, q_doc_ids):
+    mask = 0
+    if causal:
+        mask |= fb.FL_MASK_CAUSAL
+    if window is not None:
+        mask |= fb.FL_MASK_WINDOW | fb.FL_MASK_CAUSAL
+    if prefix is not None:
+        mask |= fb.FL_MASK_PREFIX
+    if q_doc_ids is not None:
+        mask |= fb.FL_MASK_DOC
+    return mask
+
+
+class _VariantAttention(torch.autograd.Function):
+    """Forward fl_attn_fwd, backward fl_attn_bwd_ex, for descriptors with biases / gate / RMSNorm / second stream.
+    Tensor inputs: q, k, v, q2, k2, lam, gate, bias0, bias1 (absent ones are None)."""
+
+    @staticmethod
+    def forward(ctx, cfg, q, k, v, q2, k2, lam, gate, bias0, bias1):
+        dev = q.device
+        q5, k5, v5 = _as5(q), _as5(k), _as5(v)
+        B, G, H, Sq, _ = q5.shape
+        diff = q2 is not None
+        biases = [b for b in (bias0, bias1) if b is not None]
+        epi = (fb.FL_EPI_RMSNORM if cfg["rmsnorm"] else 0) | (fb.FL_EPI_GATE_SIGMOID if gate is not None else 0)
+        mod = fb.FL_MOD_SOFTCAP if cfg["softcap"] is not None else (fb.FL_MOD_ALIBI if cfg["alibi_slopes"] is not None else fb.FL_MOD_NONE)
+        desc = fb.variant_desc(scale=float(cfg["scale"]), score_mod=mod, softcap=float(cfg["softcap"] or 0.0),
+                               mask=_mask_bits(cfg["causal"], cfg["window"], cfg["prefix"], cfg["q_doc_ids"]),
+                               window=int(cfg["window"] or 0), prefix_len=int(cfg["prefix"] or 0), n_bias=len(biases),
+                               combine=fb.FL_DIFFERENTIAL if diff else fb.FL_SINGLE, epilogue=epi,
+                               rms_eps=float(cfg["rms_eps"]) if cfg["rmsnorm"] else 0.0, q_offset=int(cfg["q_offset"]))
+        out = torch.empty((B, G, H, Sq, v5.shape[4]), dtype=q.dtype, device=dev)
+        lse = torch.empty((B, 2 * G if diff else G, H, Sq, 1), dtype=torch.float32, device=dev)
+        tq, tk, tv, tout, tlse = (fb.tensor_desc(x) for x in (q5, k5, v5, out, lse))
+        ws = None
+        nbytes = fb.fl_attn_fwd_workspace_size(tq, tk, desc)
+        if nbytes:
+            ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        five = lambda x: None if x is None else _as5(x)
+        aux = fb.aux_desc(alibi_slopes=cfg["alibi_slopes"], q_doc_ids=cfg["q_doc_ids"], kv_doc_ids=cfg["kv_doc_ids"],
+                          biases=biases, gate=five(gate), q2=five(q2), k2=five(k2), lambda_=lam,
+                          rms_weight=cfg["rms_weight"], workspace=ws)
+        stream = torch.cuda.current_stream(dev).cuda_stream
+        fb.check(fb.fl_attn_fwd(tq, tk, tv, desc, aux, tout, tlse, stream))
+        ctx.save_for_backward(q, k, v, q2, k2, lam, gate, bias0, bias1, out, lse)
+        ctx.cfg, ctx.desc = cfg, desc
+        return out if q.dim() == 5 else out.squeeze(1)
+
+    @staticmethod
+    def backward(ctx, dout):
+        q, k, v, q2, k2, lam, gate, bias0, bias1, out, lse = ctx.saved_tensors
+        cfg, desc = ctx.cfg, ctx.desc
+        dev = q.device
+        q5, k5, v5, d5 = _as5(q), _as5(k), _as5(v), _as5(dout)
+        if d5.stride(-1) != 1 or any(st % 8 for st in d5.stride()[:-1]):
+            d5 = d5.contiguous()
+        five = lambda x: None if x is None else _as5(x)
+        biases = [b for b in (bias0, bias1) if b is not None]
+        dq, dk, dv = torch.empty_like(q5), torch.empty_like(k5), torch.empty_like(v5)
+        dq2 = None if q2 is None else torch.empty_like(five(q2))
+        dk2 = None if k2 is None else torch.empty_like(five(k2))
+        dlam = None if lam is None else torch.empty_like(lam)
+        dgate = None if gate is None else torch.empty_like(five(gate))
+        dbias = [torch.empty(tuple(b.shape), dtype=torch.float32, device=dev) for b in biases]
+        tq, tk, tv, tout, tdo, tlse, tdq, tdk, tdv = (fb.tensor_desc(x) for x in (q5, k5, v5, out, d5, lse, dq, dk, dv))
+        ws = torch.empty(max(fb.fl_attn_bwd_ex_workspace_size(tq, tk, tv, desc), 16), dtype=torch.uint8, device=dev)
+        aux = fb.aux_desc(alibi_slopes=cfg["alibi_slopes"], q_doc_ids=cfg["q_doc_ids"], kv_doc_ids=cfg["kv_doc_ids"],
+                          biases=biases, gate=five(gate), q2=five(q2), k2=five(k2), lambda_=lam,
+                          rms_weight=cfg["rms_weight"], workspace=ws)
+        extra = fb.bwd_extra(dq2=dq2, dk2=dk2, dbias=dbias, dgate=dgate, dlambda=dlam)
+        stream = torch.cuda.current_stream(dev).cuda_stream
+        fb.check(fb.fl_attn_bwd_ex(tq, tk, tv, tout, tdo, tlse, desc, aux, tdq, tdk, tdv, extra, stream))
+        sq = (lambda x: x) if q.dim() == 5 else (lambda x: None if x is None else x.squeeze(1))
+        gb = [g.to(b.dtype) for g, b in zip(dbias, biases)] + [None] * (2 - len(biases))
+        if bias0 is None and bias1 is not None:
+            gb = [None, gb[0]]
+        return (None, sq(dq), sq(dk), sq(dv), sq(dq2), sq(dk2), dlam, sq(dgate), gb[0], gb[1])
+
+
+def variant_attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, scale: Optional[float] = None,
+                      causal: bool = False, window: Optional[int] = None, prefix: Optional[int] = None,
+                      softcap: Optional[float] = None, alibi_slopes: Optional[torch.Tensor] = None,
+                      q_doc_ids: Optional[torch.Tensor] = None, kv_doc_ids: Optional[torch.Tensor] = None,
+                      q_offset: int = 0, biases=(), gate: Optional[torch.Tensor] = None,
+                      q2: Optional[torch.Tensor] = None, k2: Optional[torch.Tensor] = None,
+                      lam: Optional[torch.Tensor] = None, rmsnorm: bool = False, rms_eps: float = 1e-6,
+                      rms_weight: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Every variant of the forward pass with autograd: attention() plus
+
+    biases    up to two bf16 tensors that broadcast to [B, G, H, Sq, Sk] (5-D, size-1 axes broadcast), added to the
+              scaled score; their gradients come back in the biases' own shapes
+    gate      pre-sigmoid tensor of the output's shape: out = sigmoid(gate) * (...)
+    q2, k2, lam   the second softmax stream of differential attention and its per-head fp32 weights [H]:
+              softmax(q k^T) v - lam_h softmax(q2 k2^T) v
+    rmsnorm   RMSNorm over the output channels (rms_weight fp32 [Dv], not differentiated), before the gate
+    Tensors are [B, H, S, D] or [B, G, H, S, D], bf16, on the GPU; differentiable in q, k, v, q2, k2, lam, gate, biases."""
+    if not q.is_cuda or q.dtype != torch.bfloat16:
+        raise ValueError("variant_attention() takes bf16 CUDA tensors (there is no CPU or fallback path)")
+    if (q2 is None) != (k2 is None) or (q2 is None) != (lam is None):
+        raise ValueError("q2, k2 and lam come together")
+    if softcap is not None and alibi_slopes is not None:
+        raise ValueError("one score_mod at a time")
+    if len(biases) > 2:
+        raise ValueError("at most two biases")
+    q5, k5 = _as5(q), _as5(k)
+    if q_doc_ids is not None and kv_doc_ids is None:
+        kv_doc_ids = q_doc_ids
+    _check_aux("alibi_slopes", alibi_slopes, torch.float32, (q5.shape[2],), q.device)
+    _check_aux("q_doc_ids", q_doc_ids, torch.int32, (q5.shape[0], q5.shape[3]), q.device)
+    _check_aux("kv_doc_ids", kv_doc_ids, torch.int32, (k5.shape[0], k5.shape[3]), q.device)
+    _check_aux("lam", lam, torch.float32, (q5.shape[2],), q.device)
+    if rms_weight is not None:
+        _check_aux("rms_weight", rms_weight, torch.float32, (_as5(v).shape[4],), q.device)
+    for n, b in enumerate(biases):
+        if b.dim() != 5 or b.dtype != torch.bfloat16 or b.device != q.device:
+            raise ValueError(f"biases[{n}] must be a 5-D bf16 tensor on {q.device}")
+    cfg = dict(scale=q.shape[-1] ** -0.5 if scale is None else scale, causal=causal, window=window, prefix=prefix,
+               softcap=softcap, alibi_slopes=alibi_slopes, q_doc_ids=q_doc_ids, kv_doc_ids=kv_doc_ids, q_offset=q_offset,
+               rmsnorm=rmsnorm, rms_eps=rms_eps, rms_weight=rms_weight)
+    b0 = biases[0] if len(biases) > 0 else None
+    b1 = biases[1] if len(biases) > 1 else None
+    return _VariantAttention.apply(cfg, q, k, v, q2, k2, lam, gate, b0, b1)
 
 
 def decode_attention(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, seq_lens: torch.Tensor,
