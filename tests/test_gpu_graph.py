@@ -84,3 +84,66 @@ def test_decode_replays_from_a_graph_while_sequences_grow():
         torch.cuda.synchronize()
         for name, t, r in zip(("out", "lse"), outs, ref):
             assert torch.equal(t, r), f"decode replay {rep} differs in {name}"
+
+
+@pytest.mark.parametrize("case", ["evoformer_bias_gate_d32", "differential_rms_d64_dv128"])
+def test_composed_backward_replays_from_a_graph(case):
+    """fl_attn_bwd_ex (recomputed stream outputs, elementwise kernels, padded copies, staged bias gradients; no
+    memset nodes, no atomics): captured after one eager call, every replay bit-equal to the eager result."""
+    import torch
+    if case == "evoformer_bias_gate_d32":
+        w = inputs.evoformer_bf16(B=1, Nseq=3, Nres=150, H=4, D=32)
+    else:
+        w = inputs.differential_bf16(B=1, H=2, S=300)
+    db = runner.upload_backward_ex(w, inputs.dout_for(w), grad_dtype="f32")
+    outs = [db.fwd.out, db.fwd.lse] + [x for t in db.grads.values() for x in (t if isinstance(t, list) else [t])]
+    db.fwd.run_checked()
+    db.run_checked()                                # eager: also compiles / loads whatever the composed pass instantiates
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in outs]
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        s = torch.cuda.current_stream().cuda_stream
+        db.fwd.run_checked(s)
+        db.run_checked(s)
+        graph.capture_end()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in outs:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for n, (t, r) in enumerate(zip(outs, ref)):
+            assert torch.equal(t, r), f"{case}: replay {rep} differs in output {n}"
+
+
+def test_noalloc_forward_replays_from_a_graph():
+    """fl_attn_fwd_noalloc under capture: the document-id summaries live in the library's own buffer."""
+    import torch
+    from paper_2511_02043_amd import binding as fb
+    w = inputs.window_doc_bf16(B=2, H=2, S=500, D=64, window=120, lo=20, hi=150)
+    dw = runner.upload(w, out_dtype="f32")
+    dw.run_checked()
+    torch.cuda.synchronize()
+    ref, ref_lse = dw.out.clone(), dw.lse.clone()
+    dw.aux.workspace = None
+    dw.aux.workspace_bytes = 0
+    fb.check(fb.fl_attn_fwd_noalloc(dw.tq, dw.tk, dw.tv, dw.desc, dw.aux, dw.tout, dw.tlse))     # looks the buffer's address up
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        fb.check(fb.fl_attn_fwd_noalloc(dw.tq, dw.tk, dw.tv, dw.desc, dw.aux, dw.tout, dw.tlse, torch.cuda.current_stream().cuda_stream))
+        graph.capture_end()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        dw.out.fill_(float("nan"))
+        dw.lse.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(dw.out, ref) and torch.equal(dw.lse, ref_lse), rep
