@@ -24,6 +24,10 @@ A sequence of length 0 has out = 0 and lse = -inf.  Everything is float64.
 Pins (tests/test_oracle_decode_pins.py): the last row of the pinned forward oracle on the
 gathered contiguous keys (causal), a pure-Python brute force, invariance under a permutation of
 the physical pages, len = 1 (out = v_0), constant values, and the window's visible count.
+prefill_attention (a chunk of query rows per sequence) is pinned to the forward oracle on the gathered
+keys with the rows placed at their positions, to PyTorch's fp64 scaled_dot_product_attention with a
+bottom-right causal mask, to decode_attention at Sq = 1, to chunk-by-chunk consistency (any split of
+a prompt into chunks gives the rows of the one-shot result), and to the empty rows of len < Sq.
 """
 from __future__ import annotations
 
@@ -72,4 +76,49 @@ def decode_attention(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, bl
             l = np.sum(e)
             out[b, h] = (e / l) @ vals[:, hk]
             lse[b, h] = m + np.log(l)
+    return out, lse
+
+
+def prefill_attention(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, block_table: np.ndarray,
+                      seq_lens: np.ndarray, *, scale: float, window: Optional[int] = None,
+                      softcap_value: Optional[float] = None, alibi_slopes: Optional[np.ndarray] = None):
+    """A chunk of Sq query rows per sequence against that sequence's paged cache -- the prompt phase of
+    the serving experiment (Sec. 4.1, time to first token) when the prompt is processed in chunks, or a
+    prompt that continues a cached prefix.  The chunk's own keys are already in the cache: row i of
+    sequence b is the token at position len_b - Sq + i and sees keys 0 .. that position (causal; with a
+    window, the last window + 1 of them).  Rows whose position is negative (len_b < Sq) see nothing:
+    out = 0, lse = -inf.  Same score pipeline as decode_attention, which is the case Sq = 1.
+
+    q [B, H, Sq, D] -> out [B, H, Sq, Dv], lse [B, H, Sq] (float64)."""
+    B, H, Sq, D = q.shape
+    Hkv = k_cache.shape[2]
+    assert H % Hkv == 0
+    group = H // Hkv
+    out = np.zeros((B, H, Sq, v_cache.shape[3]))
+    lse = np.full((B, H, Sq), -np.inf)
+    for b in range(B):
+        n = int(seq_lens[b])
+        if n == 0:
+            continue
+        keys = gather_sequence(k_cache, block_table, b, n)
+        vals = gather_sequence(v_cache, block_table, b, n)
+        for i in range(Sq):
+            pos = n - Sq + i
+            if pos < 0:
+                continue
+            dist = (pos - np.arange(pos + 1)).astype(np.float64)
+            for h in range(H):
+                hk = h // group
+                s = scale * (keys[:pos + 1, hk] @ np.asarray(q[b, h, i], dtype=np.float64))
+                if softcap_value is not None:
+                    s = softcap_value * np.tanh(s / softcap_value)
+                if alibi_slopes is not None:
+                    s = s - float(alibi_slopes[h]) * dist
+                if window is not None:
+                    s = np.where(dist > window, -np.inf, s)
+                m = np.max(s)
+                e = np.exp(s - m)
+                l = np.sum(e)
+                out[b, h, i] = (e / l) @ vals[:pos + 1, hk]
+                lse[b, h, i] = m + np.log(l)
     return out, lse

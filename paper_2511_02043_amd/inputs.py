@@ -379,3 +379,16 @@ def decode_bf16(B=4, H=8, Hkv=2, D=128, page_size=16, seq_lens=None, max_len=512
     k_cache = normal((n_pages, page_size, Hkv, D), tensor_seed(8, 1, salt))
     v_cache = normal((n_pages, page_size, Hkv, D), tensor_seed(8, 2, salt))
     return DecodeWorkload(f"decode_bf16_d{D}_p{page_size}", q, k_cache, v_cache, table, seq_lens, scale=D ** -0.5)
+
+
+def prefill_paged_bf16(B=3, H=8, Hkv=2, D=128, Sq=64, page_size=16, seq_lens=None, max_len=512, salt=0,
+                       shuffle_pages=True) -> DecodeWorkload:
+    """A chunk of Sq query rows per sequence against the same kind of paged cache as decode_bf16 (the
+    prompt phase of the serving experiment of Sec. 4.1, processed in chunks): q is [B, H, Sq, D], row i
+    of sequence b being the token at position len_b - Sq + i.  Lengths (if not given) are uniform on
+    [1, max_len], so some may be shorter than the chunk."""
+    w = decode_bf16(B=B, H=H, Hkv=Hkv, D=D, page_size=page_size, seq_lens=seq_lens, max_len=max_len, salt=salt,
+                    shuffle_pages=shuffle_pages)
+    w.q = normal((len(w.seq_lens), H, Sq, D), tensor_seed(8, 6, salt))
+    w.name = f"prefill_paged_bf16_d{D}_p{page_size}_q{Sq}"
+    return w

@@ -95,3 +95,82 @@ def test_closed_forms():
     np.testing.assert_allclose(lse0[2], math.log(5), atol=1e-14)
     vals = do.gather_sequence(w.v_cache, w.block_table, 2, 21)
     np.testing.assert_allclose(out0[2, 3], vals[-5:, 1].mean(axis=0), atol=1e-14)
+
+
+# --- a chunk of query rows per sequence (prefill over the paged cache) -------------------------------------
+
+def chunk_variant(variant, H):
+    kw, fkw = {}, {}
+    if variant == "window":
+        kw["window"], fkw["window"] = 5, 5
+    if variant == "softcap":
+        kw["softcap_value"], fkw["softcap_value"] = 0.7, 0.7
+    if variant == "alibi":
+        sl = inputs.alibi_slopes(H).astype(np.float64)
+        kw["alibi_slopes"], fkw["alibi_slopes"] = sl, sl
+    return kw, fkw
+
+
+@pytest.mark.parametrize("variant", ["plain", "window", "softcap", "alibi"])
+def test_chunk_rows_of_the_forward_oracle(variant):
+    """Row i of the chunk is row len - Sq + i of causal attention over the gathered keys (the pinned forward
+    oracle, rows placed through q_pos); rows before position 0 are empty."""
+    Sq = 7
+    w = inputs.prefill_paged_bf16(B=4, H=8, Hkv=2, D=32, Sq=Sq, page_size=4, seq_lens=[1, 7, 13, 40])
+    kw, fkw = chunk_variant(variant, 8)
+    out, lse = do.prefill_attention(w.q, w.k_cache, w.v_cache, w.block_table, w.seq_lens, scale=w.scale, **kw)
+    for b in range(4):
+        n = int(w.seq_lens[b])
+        k, v = contiguous(w, b)
+        first = max(0, Sq - n)                                               # rows before it sit at negative positions
+        assert np.all(out[b, :, :first] == 0.0) and np.all(np.isneginf(lse[b, :, :first]))
+        q = w.q[b][None, None, :, first:, :].astype(np.float64)
+        ref, ref_lse = ao.attention(q, k, v, scale=w.scale, causal=True, q_pos=np.arange(n - Sq + first, n), **fkw)
+        np.testing.assert_allclose(out[b, :, first:], ref[0, 0], rtol=0, atol=1e-13)
+        np.testing.assert_allclose(lse[b, :, first:], ref_lse[0, 0], rtol=0, atol=1e-13)
+
+
+def test_chunk_against_sdpa_bottom_right_causal():
+    """PyTorch's fp64 scaled_dot_product_attention with an explicit bottom-right aligned causal mask."""
+    import torch
+    Sq = 6
+    w = inputs.prefill_paged_bf16(B=2, H=4, Hkv=2, D=16, Sq=Sq, page_size=8, seq_lens=[19, 33], salt=2)
+    out, _ = do.prefill_attention(w.q, w.k_cache, w.v_cache, w.block_table, w.seq_lens, scale=w.scale)
+    for b in range(2):
+        n = int(w.seq_lens[b])
+        k, v = contiguous(w, b)
+        kt = torch.from_numpy(k[0, 0]).repeat_interleave(2, dim=0)           # [H, n, D]
+        vt = torch.from_numpy(v[0, 0]).repeat_interleave(2, dim=0)
+        qt = torch.from_numpy(w.q[b].astype(np.float64))                     # [H, Sq, D]
+        allowed = torch.arange(n)[None, :] <= (torch.arange(Sq)[:, None] + n - Sq)
+        ref = torch.nn.functional.scaled_dot_product_attention(qt, kt, vt, attn_mask=allowed, scale=w.scale)
+        np.testing.assert_allclose(out[b], ref.numpy(), rtol=0, atol=1e-12)
+
+
+def test_chunk_of_one_row_is_the_decode_step():
+    w = inputs.prefill_paged_bf16(B=3, H=8, Hkv=4, D=16, Sq=1, page_size=4, seq_lens=[0, 9, 22], salt=3)
+    sl = inputs.alibi_slopes(8).astype(np.float64)
+    a, la = do.prefill_attention(w.q, w.k_cache, w.v_cache, w.block_table, w.seq_lens, scale=w.scale, window=6,
+                                 alibi_slopes=sl)
+    b_, lb = do.decode_attention(w.q[:, :, 0], w.k_cache, w.v_cache, w.block_table, w.seq_lens, scale=w.scale, window=6,
+                                 alibi_slopes=sl)
+    np.testing.assert_array_equal(a[:, :, 0], b_)
+    np.testing.assert_array_equal(la[:, :, 0], lb)
+
+
+def test_any_chunking_of_a_prompt_gives_the_same_rows():
+    """Processing a prompt in chunks (each against the cache filled up to the end of that chunk) gives the rows of
+    the one-shot pass: the defining property of chunked prefill."""
+    n, ps = 29, 4
+    w = inputs.prefill_paged_bf16(B=1, H=4, Hkv=2, D=16, Sq=n, page_size=ps, seq_lens=[n], salt=4)
+    whole, whole_lse = do.prefill_attention(w.q, w.k_cache, w.v_cache, w.block_table, w.seq_lens, scale=w.scale,
+                                            softcap_value=1.3)
+    start = 0
+    for size in (5, 1, 16, 7):
+        end = start + size
+        part, part_lse = do.prefill_attention(w.q[:, :, start:end], w.k_cache, w.v_cache, w.block_table, np.array([end]),
+                                              scale=w.scale, softcap_value=1.3)
+        np.testing.assert_allclose(part, whole[:, :, start:end], rtol=0, atol=1e-13)
+        np.testing.assert_allclose(part_lse, whole_lse[:, :, start:end], rtol=0, atol=1e-13)
+        start = end
+    assert start == n
