@@ -250,6 +250,60 @@ def time_decode(steps, warmup, B=64, H=32, Hkv=8, D=128, ctx=8192, page_size=16,
                 dims=dict(B=B, H=H, Hkv=Hkv, D=D, ctx=ctx, page_size=page_size, cache_layout=layout))
 
 
+def time_prefill_paged(steps, warmup, B=8, H=32, Hkv=8, D=128, ctx=8192, chunk=512, page_size=16):
+    """One fl_attn_prefill_paged call per step: the last `chunk` rows of B sequences of ctx cached tokens each (a
+    paged cache in the serving layout with shuffled page placement, bf16), and beside it fl_attn_fwd on the same
+    keys held densely (causal, query offset ctx - chunk): the difference is the cost of reading through the pages."""
+    import torch
+    from paper_2511_02043_amd import binding as fb
+    g = torch.Generator(device="cuda").manual_seed(251102043)
+    rng = np.random.Generator(np.random.PCG64(251102043))
+    per_seq = (ctx + page_size - 1) // page_size
+    n_pages = B * per_seq
+    table = rng.permutation(n_pages).astype(np.int32).reshape(B, per_seq)
+    lens = np.full(B, ctx, dtype=np.int32)
+    dev = "cuda:0"
+    kc = torch.randn((n_pages, page_size, Hkv, D), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    vc = torch.randn((n_pages, page_size, Hkv, D), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    q = torch.randn((B, 1, H, chunk, D), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    out = torch.empty_like(q)
+    t_table, t_lens = torch.from_numpy(table).to(dev), torch.from_numpy(lens).to(dev)
+    tq, tout = fb.tensor_desc(q), fb.tensor_desc(out)
+    tk, tv = fb.tensor_desc(kc.permute(0, 2, 1, 3)[:, None]), fb.tensor_desc(vc.permute(0, 2, 1, 3)[:, None])
+    kv = fb.paged_kv(block_table=t_table, page_size=page_size, seq_lens=t_lens, max_seq_len=ctx)
+    desc = fb.variant_desc(scale=D ** -0.5, mask=fb.FL_MASK_CAUSAL)
+    ws = torch.empty(max(fb.fl_attn_prefill_paged_workspace_size(tq, tk, kv), 16), dtype=torch.uint8, device=dev)
+    aux = fb.aux_desc(workspace=ws)
+    # the same keys and values held densely, [B, 1, Hkv, ctx, D]
+    idx = t_table.long()
+    kd = kc[idx].reshape(B, per_seq * page_size, Hkv, D)[:, :ctx].permute(0, 2, 1, 3)[:, None].contiguous()
+    vd = vc[idx].reshape(B, per_seq * page_size, Hkv, D)[:, :ctx].permute(0, 2, 1, 3)[:, None].contiguous()
+    out_d = torch.empty_like(q)
+    tkd, tvd, tout_d = fb.tensor_desc(kd), fb.tensor_desc(vd), fb.tensor_desc(out_d)
+    desc_d = fb.variant_desc(scale=D ** -0.5, mask=fb.FL_MASK_CAUSAL, q_offset=ctx - chunk)
+    stream = torch.cuda.current_stream().cuda_stream
+    calls = {"paged": lambda: fb.check(fb.fl_attn_prefill_paged(tq, tk, tv, kv, desc, aux, tout, None, stream)),
+             "dense": lambda: fb.check(fb.fl_attn_fwd(tq, tkd, tvd, desc_d, None, tout_d, None, stream))}
+    ms = {}
+    for name, call in calls.items():
+        for _ in range(warmup):
+            call()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        ms[name] = e0.elapsed_time(e1) / steps
+    same = bool(torch.equal(out, out_d))
+    pairs = B * H * sum(ctx - chunk + i + 1 for i in range(chunk))
+    flops = 4 * D * pairs
+    return dict(ms_per_step=ms["paged"], ms_dense=ms["dense"], flops=flops, tflops=flops / (ms["paged"] * 1e-3) / 1e12,
+                tflops_dense=flops / (ms["dense"] * 1e-3) / 1e12, identical_to_dense=same,
+                dims=dict(B=B, H=H, Hkv=Hkv, D=D, ctx=ctx, chunk=chunk, page_size=page_size))
+
+
 def time_custom(steps, warmup):
     """Variants compiled at run time, on the shapes of the ALiBi configuration (B=8 H=16 S=2048 D=64): the ALiBi
     score_mod as an expression (same arithmetic as the built-in variant, for comparison), and two variants no
@@ -610,6 +664,8 @@ def main():
     ap.add_argument("--decode-dim", type=int, default=128, choices=[64, 128], help="head dim for --decode")
     ap.add_argument("--decode-batch", type=int, default=64, help="sequences for --decode")
     ap.add_argument("--decode-ctx", type=int, default=8192, help="longest cached sequence for --decode (lengths are uniform on [ctx / 2, ctx])")
+    ap.add_argument("--prefill-chunk", type=int, default=0, metavar="ROWS",
+                    help="time fl_attn_prefill_paged: the last ROWS query rows of --decode-batch sequences of --decode-ctx cached tokens")
     ap.add_argument("--custom", action="store_true", help="time variants compiled at run time from expressions (ALiBi shapes)")
     ap.add_argument("--decode", action="store_true",
                     help="time fl_attn_decode (64 sequences of 4k-8k cached tokens, 32 / 8 heads, D = 128, 16-token pages)")
@@ -650,6 +706,20 @@ def main():
         res = time_custom(args.steps, args.warmup)
         print(json.dumps({"metric": "attention fwd TFLOP/s of run-time compiled variants", "unit": "TFLOP/s", "n_gpus": 1,
                           "steps": args.steps, "warmup": args.warmup, "dtype": "bf16", "data": "synthetic", "results": res}), flush=True)
+        return
+    if args.prefill_chunk > 0:
+        r = time_prefill_paged(args.steps, args.warmup, B=args.decode_batch, ctx=args.decode_ctx, D=args.decode_dim,
+                               page_size=args.decode_page, chunk=args.prefill_chunk)
+        print(f"# prefill over pages: {r['ms_per_step']:.4f} ms ({r['tflops']:.0f} TFLOP/s); dense keys: {r['ms_dense']:.4f} ms "
+              f"({r['tflops_dense']:.0f} TFLOP/s); outputs identical: {r['identical_to_dense']}", file=sys.stderr, flush=True)
+        print(json.dumps({"metric": "chunked-prefill attention over a paged KV cache, TFLOP/s of visible scores", "value": r["tflops"],
+                          "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                          "ms_per_step": r["ms_per_step"], "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": f"prefill_paged_b{args.decode_batch}_h32_kv8_d{args.decode_dim}_ctx{args.decode_ctx}_chunk{args.prefill_chunk}_page{args.decode_page}",
+                                     **r["dims"], "ms_dense_keys": r["ms_dense"], "tflops_dense_keys": r["tflops_dense"],
+                                     "identical_to_dense": r["identical_to_dense"]},
+                          "roofline": {"bound": "mfma", "achieved": r["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                                       "frac": r["tflops"] / PEAK_BF16_TFLOPS, "traffic": None}}), flush=True)
         return
     if args.decode:
         r = time_decode(args.steps, args.warmup, B=args.decode_batch, ctx=args.decode_ctx, D=args.decode_dim, page_size=args.decode_page,

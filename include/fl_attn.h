@@ -281,6 +281,37 @@ fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_
 /* Bytes of aux->workspace that fl_attn_decode needs. */
 size_t fl_attn_decode_workspace_size(const fl_tensor* q, const fl_tensor* k_cache, const fl_paged_kv* kv);
 
+/* A chunk of Sq query rows per sequence against that sequence's paged cache: the prompt phase of the
+ * serving experiment in Sec. 4.1 (time to first token) when a prompt is processed in chunks or continues a
+ * cached prefix.  The chunk's own keys and values are already in the cache: query row i of sequence b is the
+ * token at position len_b - Sq + i and attends to keys 0 .. that position (the causal mask is implied;
+ * FL_MASK_WINDOW keeps the last window + 1 of them), with the arithmetic of fl_attn_fwd (Eq. 3, score_mod of
+ * Eq. 4, online softmax of Sec. 3.4).  Rows at negative positions (len_b < Sq) get out = 0 and lse = -inf.
+ * Sq = 1 computes what fl_attn_decode computes.
+ *
+ *   q        [B, 1, H, Sq, D]  bf16, D in {32, 64, 128}
+ *   k_cache, v_cache, kv       as for fl_attn_decode (Hkv divides H; no limit on H / Hkv)
+ *   out      [B, 1, H, Sq, D]  bf16 or f32;  lse [B, 1, H, Sq, 1] f32 or NULL
+ *   desc     scale, score_mod, FL_MASK_CAUSAL and / or FL_MASK_WINDOW (or no mask bit: causal all the same);
+ *            other masks, biases, the second stream, epilogues and q_offset are FL_ERR_UNSUPPORTED
+ *   aux      alibi_slopes for FL_MOD_ALIBI, and aux->workspace of fl_attn_prefill_paged_workspace_size bytes
+ *            (16-byte aligned; contents undefined afterwards)
+ *
+ * How: one pass copies the cached rows of every sequence, through its block table, into dense key / value
+ * tensors of max_seq_len rows; then the forward kernel runs on them, reading each sequence's length on the
+ * device: it stops at that length and places the query rows at its last Sq positions, so a short sequence
+ * costs its own length and nothing is synchronised with the host.  The copy reads and writes the cached
+ * rows once (2 * 2 * len * Hkv * D * 2 bytes per sequence), small beside the Sq * len scores of a chunk of
+ * tens of rows or more; for single rows fl_attn_decode reads the pages in place.
+ * Stream, ownership and error rules as for fl_attn_fwd.                                                  */
+fl_status fl_attn_prefill_paged(const fl_tensor* q, const fl_tensor* k_cache, const fl_tensor* v_cache,
+                                const fl_paged_kv* kv, const fl_variant_desc* desc, const fl_aux* aux,
+                                fl_tensor* out, fl_tensor* lse, void* stream);
+
+/* Bytes of aux->workspace that fl_attn_prefill_paged needs: the dense copies, 2 * B * Hkv * max_seq_len * D * 2
+ * bytes (each rounded up to 256). */
+size_t fl_attn_prefill_paged_workspace_size(const fl_tensor* q, const fl_tensor* k_cache, const fl_paged_kv* kv);
+
 /* A variant compiled at run time from user expressions (opaque; owned by the caller until released). */
 typedef struct fl_custom_variant fl_custom_variant;
 

@@ -101,6 +101,10 @@ def lib() -> C.CDLL:
                                      TP, TP, C.c_void_p]
         L.fl_attn_decode_workspace_size.restype = C.c_size_t
         L.fl_attn_decode_workspace_size.argtypes = [TP, TP, C.POINTER(fl_paged_kv)]
+        L.fl_attn_prefill_paged.restype = C.c_int
+        L.fl_attn_prefill_paged.argtypes = L.fl_attn_decode.argtypes
+        L.fl_attn_prefill_paged_workspace_size.restype = C.c_size_t
+        L.fl_attn_prefill_paged_workspace_size.argtypes = [TP, TP, C.POINTER(fl_paged_kv)]
         L.fl_compile_variant.restype = C.c_int
         L.fl_compile_variant.argtypes = [C.c_char_p, C.c_char_p, C.c_uint32, C.c_int, C.POINTER(C.c_void_p)]
         L.fl_attn_fwd_custom.restype = C.c_int
@@ -128,7 +132,7 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ["fl_attn_fwd", "fl_attn_fwd_noalloc", "fl_attn_fwd_workspace_size", "fl_attn_bwd", "fl_attn_bwd_workspace_size", "fl_attn_bwd_ex", "fl_attn_bwd_ex_workspace_size",
-           "fl_bwd_supported", "fl_attn_decode", "fl_attn_decode_workspace_size", "fl_compile_variant", "fl_attn_fwd_custom", "fl_compile_variant_aux", "fl_attn_fwd_custom_aux",
+           "fl_bwd_supported", "fl_attn_decode", "fl_attn_decode_workspace_size", "fl_attn_prefill_paged", "fl_attn_prefill_paged_workspace_size", "fl_compile_variant", "fl_attn_fwd_custom", "fl_compile_variant_aux", "fl_attn_fwd_custom_aux",
            "fl_release_variant", "fl_variant_supported", "fl_strerror",
            "fl_last_error_detail", "fl_set_tuning", "fl_version"]
 
@@ -262,6 +266,17 @@ def fl_attn_decode(q: fl_tensor, k_cache: fl_tensor, v_cache: fl_tensor, kv: fl_
 
 def fl_attn_decode_workspace_size(q: fl_tensor, k_cache: fl_tensor, kv: fl_paged_kv) -> int:
     return lib().fl_attn_decode_workspace_size(_ref(q), _ref(k_cache), _ref(kv))
+
+
+def fl_attn_prefill_paged(q: fl_tensor, k_cache: fl_tensor, v_cache: fl_tensor, kv: fl_paged_kv, desc: fl_variant_desc,
+                          aux: Optional[fl_aux], out: fl_tensor, lse: Optional[fl_tensor], stream: int = 0) -> int:
+    """A chunk of query rows per sequence against the paged cache; returns the status code."""
+    return lib().fl_attn_prefill_paged(_ref(q), _ref(k_cache), _ref(v_cache), _ref(kv), _ref(desc), _ref(aux), _ref(out),
+                                       _ref(lse), C.c_void_p(stream))
+
+
+def fl_attn_prefill_paged_workspace_size(q: fl_tensor, k_cache: fl_tensor, kv: fl_paged_kv) -> int:
+    return lib().fl_attn_prefill_paged_workspace_size(_ref(q), _ref(k_cache), _ref(kv))
 
 
 def fl_compile_variant(score_mod: Optional[str], mask: Optional[str], D: int, base_mask: int = 0):

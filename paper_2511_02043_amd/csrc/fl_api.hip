@@ -2,6 +2,7 @@
 // Nothing here computes attention; every step of the path runs in the kernels.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -495,6 +496,57 @@ __global__ void __launch_bounds__(256) zero_f32_kernel(float* p, int64_t n) {
 
 inline size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
+// Chunked prefill over the paged cache: copies each sequence's cached rows, token by token through its block table, into
+// a dense [B, 1, Hkv, L, D] tensor, row j holding token j.  Rows at and after the sequence's length are left as they are:
+// the forward kernel is told the length and reads no row past it.  One thread per 16-byte chunk; k and v in one launch
+// (blockIdx.y).
+struct GatherParams {
+  const uint16_t* cache[2];
+  int64_t sp[2], st[2], sh[2];
+  uint16_t* dst[2];
+  const int* table;
+  const int* seq_lens;
+  int table_stride, page_shift, page_mask, num_pages, max_len, Hkv, L, chunks;     // chunks = D / 8
+  int64_t total;                                                                  // B * Hkv * L * chunks
+};
+
+__global__ void __launch_bounds__(256) gather_pages_kernel(GatherParams g) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= g.total) return;
+  const int which = blockIdx.y;
+  const int c = (int)(idx % g.chunks);
+  int64_t rest = idx / g.chunks;
+  const int j = (int)(rest % g.L);
+  rest /= g.L;
+  const int hk = (int)(rest % g.Hkv);
+  const int b = (int)(rest / g.Hkv);
+  const int len = max(0, min(g.seq_lens[b], g.max_len));
+  if (j >= len) return;
+  int page = b, within = j;
+  if (g.table != nullptr) {
+    page = max(0, min(g.table[(int64_t)b * g.table_stride + (j >> g.page_shift)], g.num_pages - 1));
+    within = j & g.page_mask;
+  }
+  *(uint4*)(g.dst[which] + idx * 8) =
+      *(const uint4*)(g.cache[which] + page * g.sp[which] + hk * g.sh[which] + within * g.st[which] + c * 8);
+}
+
+// Workspace of fl_attn_prefill_paged (byte offsets; both regions 256-byte aligned).
+struct PrefillLayout {
+  int64_t L;
+  size_t off_k, off_v, total;
+};
+
+PrefillLayout prefill_layout(int64_t B, int64_t Hkv, int64_t D, int64_t max_len) {
+  PrefillLayout L;
+  L.L = std::max<int64_t>(max_len, 1);
+  const size_t kv_bytes = up256((size_t)(B * Hkv * L.L * D) * 2);
+  L.off_k = 0;
+  L.off_v = kv_bytes;
+  L.total = 2 * kv_bytes;
+  return L;
+}
+
 // Workspace of fl_attn_bwd_ex (byte offsets; every region 256-byte aligned).
 struct ExLayout {
   int Dc, ns, hsplit;
@@ -626,8 +678,10 @@ size_t fl_attn_fwd_workspace_size(const fl_tensor* q, const fl_tensor* k, const 
   return workspace_bytes(q->size[0], q->size[3], k->size[3], desc->mask);
 }
 
-fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v, const fl_variant_desc* desc,
-                      const fl_aux* aux, fl_tensor* out, fl_tensor* lse, void* stream_v) {
+// The forward call behind fl_attn_fwd.  kv_lens (device, [B], or NULL) gives every sequence its own number of keys and puts
+// its query rows at the last Sq positions of those (fl_attn_prefill_paged); bf16 kernels without a document mask only.
+static fl_status forward_call(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v, const fl_variant_desc* desc,
+                              const fl_aux* aux, fl_tensor* out, fl_tensor* lse, void* stream_v, const int32_t* kv_lens) {
   g_detail[0] = 0;
   fl_status st = check_desc(desc);
   if (st != FL_OK) return st;
@@ -772,10 +826,13 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   }
   p.B = (int)B; p.G = (int)G; p.H = (int)H; p.Hkv = (int)Hkv; p.Sq = (int)Sq; p.Sk = (int)Sk;
   p.D = (int)D; p.Dv = (int)Dv;
-  p.window = clamp_window(desc->window, Sq + desc->q_offset, Sk);
+  p.window = clamp_window(desc->window, kv_lens != nullptr ? std::max(Sq, Sk) : Sq + desc->q_offset, Sk);
   p.prefix = desc->prefix_len;
   p.q_off = desc->q_offset;
   if ((int64_t)desc->q_offset + Sq > 0x7fffff00LL) return fail(FL_ERR_SHAPE, "q_offset + Sq too large");
+  if (kv_lens != nullptr && (dtype != FL_BF16 || (mask & FL_MASK_DOC) || desc->q_offset != 0))
+    return fail(FL_ERR_UNSUPPORTED, "per-sequence key counts: bf16, no document mask, no query offset");
+  p.kv_lens = kv_lens;
   p.scale = desc->scale;
   p.softcap = desc->softcap;
   p.rms_eps = desc->rms_eps;
@@ -836,6 +893,11 @@ fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   hipError_t e = ke->jit != nullptr ? fl::jit_forward_launch(*ke, p, (int)nblocks, stream) : ke->launch(p, (int)nblocks, stream);
   if (e != hipSuccess) return fail(FL_ERR_LAUNCH, "kernel launch: %s", hipGetErrorString(e));
   return FL_OK;
+}
+
+fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v, const fl_variant_desc* desc,
+                      const fl_aux* aux, fl_tensor* out, fl_tensor* lse, void* stream_v) {
+  return forward_call(q, k, v, desc, aux, out, lse, stream_v, nullptr);
 }
 
 // Device address of this GPU's copy of `scratch`, looked up once per device with that device current.
@@ -1425,6 +1487,132 @@ fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_
   if (ns > 1 && (e = de->combine(p, (int)(B * H), stream)) != hipSuccess)   // a single split writes the result itself
     return fail(FL_ERR_LAUNCH, "decode merge launch: %s", hipGetErrorString(e));
   return FL_OK;
+}
+
+size_t fl_attn_prefill_paged_workspace_size(const fl_tensor* q, const fl_tensor* k_cache, const fl_paged_kv* kv) {
+  if (q == nullptr || k_cache == nullptr || kv == nullptr) return 0;
+  return prefill_layout(q->size[0], k_cache->size[2], q->size[4], kv->max_seq_len).total;
+}
+
+fl_status fl_attn_prefill_paged(const fl_tensor* q, const fl_tensor* k_cache, const fl_tensor* v_cache, const fl_paged_kv* kv,
+                                const fl_variant_desc* desc, const fl_aux* aux, fl_tensor* out, fl_tensor* lse, void* stream_v) {
+  g_detail[0] = 0;
+  fl_status st = check_desc(desc);
+  if (st != FL_OK) return st;
+  if (q == nullptr || k_cache == nullptr || v_cache == nullptr || kv == nullptr || out == nullptr)
+    return fail(FL_ERR_NULL, "q, k_cache, v_cache, kv or out is NULL");
+  if (kv->struct_size != sizeof(fl_paged_kv))
+    return fail(FL_ERR_DESC, "kv->struct_size = %u, expected %zu", kv->struct_size, sizeof(fl_paged_kv));
+  if (aux != nullptr && aux->struct_size != sizeof(fl_aux))
+    return fail(FL_ERR_DESC, "aux->struct_size = %u, expected %zu", aux->struct_size, sizeof(fl_aux));
+  const uint32_t mask = canonical_mask(desc->mask);
+  if ((mask & (FL_MASK_DOC | FL_MASK_PREFIX)) || desc->n_bias != 0 || desc->combine != FL_SINGLE || desc->epilogue != 0 ||
+      desc->q_offset != 0)
+    return fail(FL_ERR_UNSUPPORTED, "prefill over the paged cache covers scale, score_mod and the sliding window only "
+                                    "(the causal mask and the rows' positions follow from seq_lens)");
+  if (q->dtype != FL_BF16) return fail(FL_ERR_DTYPE, "prefill over the paged cache takes bf16 inputs (q dtype %d)", q->dtype);
+
+  const int64_t B = q->size[0], H = q->size[2], Sq = q->size[3], D = q->size[4];
+  const int64_t pages = k_cache->size[0], Hkv = k_cache->size[2], page_size = k_cache->size[3];
+  if (B < 0 || H < 0 || Sq < 0 || D <= 0 || pages < 0 || page_size <= 0) return fail(FL_ERR_SHAPE, "negative size");
+  if (pages > 0x7fffffffLL) return fail(FL_ERR_SHAPE, "more pages than an int32 table entry can name");
+  if (pages == 0 && kv->max_seq_len > 0) return fail(FL_ERR_SHAPE, "max_seq_len = %d with an empty cache", kv->max_seq_len);
+  if (q->size[1] != 1) return fail(FL_ERR_SHAPE, "q must be [B, 1, H, Sq, D]");
+  if (Hkv <= 0 || H % Hkv != 0)
+    if (H != 0) return fail(FL_ERR_SHAPE, "kv heads (%lld) must divide q heads (%lld)", (long long)Hkv, (long long)H);
+  if (kv->page_size != page_size) return fail(FL_ERR_SHAPE, "kv->page_size = %d, cache size[3] = %lld", kv->page_size, (long long)page_size);
+  if (kv->max_seq_len < 0) return fail(FL_ERR_SHAPE, "max_seq_len negative");
+  if (D % 8 != 0 || v_cache->size[4] != D) return fail(FL_ERR_UNSUPPORTED, "D = Dv, a multiple of 8 (D=%lld Dv=%lld)", (long long)D, (long long)v_cache->size[4]);
+  int page_shift = 0;
+  if (kv->block_table != nullptr) {
+    if (page_size < 8 || (page_size & (page_size - 1)) != 0)
+      return fail(FL_ERR_SHAPE, "with a block table the page size (%lld) must be a power of two >= 8", (long long)page_size);
+    while ((1LL << page_shift) < page_size) ++page_shift;
+    if (kv->table_stride < (kv->max_seq_len + page_size - 1) / page_size)
+      return fail(FL_ERR_SHAPE, "table_stride %d is less than the pages of max_seq_len", kv->table_stride);
+  } else {
+    if (pages < B) return fail(FL_ERR_SHAPE, "without a block table the cache needs a page per sequence");
+    if (kv->max_seq_len > page_size) return fail(FL_ERR_SHAPE, "max_seq_len exceeds the page size");
+  }
+  const bool empty = (B == 0 || H == 0 || Sq == 0);
+  const int64_t qsz[5] = {B, 1, H, Sq, D}, csz[5] = {pages, 1, Hkv, page_size, D};
+  if (!empty) {
+    if ((st = check_data_tensor(q, "q", FL_BF16, qsz)) != FL_OK) return st;
+    if (kv->max_seq_len > 0) {
+      if ((st = check_data_tensor(k_cache, "k_cache", FL_BF16, csz)) != FL_OK) return st;
+      if ((st = check_data_tensor(v_cache, "v_cache", FL_BF16, csz)) != FL_OK) return st;
+    }
+    if (kv->seq_lens == nullptr) return fail(FL_ERR_NULL, "seq_lens is NULL");
+  }
+  if (empty) return FL_OK;
+  if (aux == nullptr) return fail(FL_ERR_AUX_MISSING, "prefill over the paged cache needs aux (workspace)");
+  const PrefillLayout L = prefill_layout(B, Hkv, D, kv->max_seq_len);
+  if (aux->workspace == nullptr || aux->workspace_bytes < L.total)
+    return fail(FL_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", L.total, aux->workspace ? aux->workspace_bytes : (size_t)0);
+  if (((uintptr_t)aux->workspace) % 16 != 0) return fail(FL_ERR_ALIGN, "workspace not 16-byte aligned");
+  const int64_t Sk = kv->max_seq_len;
+  const int64_t total = B * Hkv * Sk * (D / 8);
+  if ((total + 255) / 256 > 0x7fffffffLL) return fail(FL_ERR_SHAPE, "too many rows to gather");
+
+  // The dense key/value tensors of the inner call, and the descriptor that reads them: causal, with the sequences' own
+  // key counts (and through them the positions of the query rows) read on the device.
+  char* ws = (char*)aux->workspace;
+  fl_tensor kd, vd;
+  memset(&kd, 0, sizeof(kd));
+  kd.dtype = FL_BF16;
+  kd.size[0] = B; kd.size[1] = 1; kd.size[2] = Hkv; kd.size[3] = Sk; kd.size[4] = D;
+  kd.stride[4] = 1; kd.stride[3] = D; kd.stride[2] = Sk * D; kd.stride[1] = Hkv * Sk * D; kd.stride[0] = Hkv * Sk * D;
+  vd = kd;
+  kd.ptr = ws + L.off_k;
+  vd.ptr = ws + L.off_v;
+  fl_variant_desc inner = *desc;
+  inner.mask = mask | FL_MASK_CAUSAL;
+  fl_aux ia;
+  memset(&ia, 0, sizeof(ia));
+  ia.struct_size = sizeof(fl_aux);
+  ia.alibi_slopes = aux->alibi_slopes;
+  // everything the inner call can refuse is checked before the first launch: "on error nothing was launched"
+  if (!fl_variant_supported(&inner, FL_BF16, (int)D, (int)D))
+    return fail(FL_ERR_UNSUPPORTED, "no forward kernel for D=%lld score_mod=%u with this mask", (long long)D, desc->score_mod);
+  if (desc->score_mod == FL_MOD_ALIBI && aux->alibi_slopes == nullptr) return fail(FL_ERR_AUX_MISSING, "alibi_slopes");
+  if (out->dtype != FL_BF16 && out->dtype != FL_F32) return fail(FL_ERR_DTYPE, "out dtype %d", out->dtype);
+  if ((st = check_data_tensor(out, "out", out->dtype, qsz)) != FL_OK) return st;
+  if (lse != nullptr && lse->ptr != nullptr) {
+    if (lse->dtype != FL_F32) return fail(FL_ERR_DTYPE, "lse must be f32");
+    const int64_t lsz[5] = {B, 1, H, Sq, 1};
+    for (int a = 0; a < 5; ++a)
+      if (lse->size[a] != lsz[a])
+        return fail(FL_ERR_SHAPE, "lse size[%d] = %lld, expected %lld", a, (long long)lse->size[a], (long long)lsz[a]);
+  }
+
+  if (total > 0) {
+    GatherParams g;
+    memset(&g, 0, sizeof(g));
+    const fl_tensor* caches[2] = {k_cache, v_cache};
+    for (int w = 0; w < 2; ++w) {
+      g.cache[w] = (const uint16_t*)caches[w]->ptr;
+      g.sp[w] = pages > 1 ? caches[w]->stride[0] : 0;
+      g.st[w] = page_size > 1 ? caches[w]->stride[3] : 0;
+      g.sh[w] = Hkv > 1 ? caches[w]->stride[2] : 0;
+    }
+    g.dst[0] = (uint16_t*)kd.ptr;
+    g.dst[1] = (uint16_t*)vd.ptr;
+    g.table = kv->block_table;
+    g.seq_lens = kv->seq_lens;
+    g.table_stride = kv->table_stride;
+    g.page_shift = page_shift;
+    g.page_mask = (int)page_size - 1;
+    g.num_pages = (int)pages;
+    g.max_len = kv->max_seq_len;
+    g.Hkv = (int)Hkv;
+    g.L = (int)Sk;
+    g.chunks = (int)(D / 8);
+    g.total = total;
+    hipLaunchKernelGGL(gather_pages_kernel, dim3((unsigned)((total + 255) / 256), 2), dim3(256), 0, (hipStream_t)stream_v, g);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(FL_ERR_LAUNCH, "page gather launch: %s", hipGetErrorString(e));
+  }
+  return forward_call(q, &kd, &vd, &inner, &ia, out, lse, stream_v, kv->seq_lens);
 }
 
 }  // extern "C"

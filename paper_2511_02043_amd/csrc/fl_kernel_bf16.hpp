@@ -651,7 +651,7 @@ struct Wave {
 
 template <class C>
 __global__ void __launch_bounds__(C::NT) __attribute__((amdgpu_waves_per_eu(C::WPE, C::WPE)))
-fwd_bf16_kernel(const FwdParams p) {
+fwd_bf16_kernel(const FwdParams call) {
   constexpr int D = C::D, DV = C::DV, BN = C::BN, NB = C::NB, KK = C::KK, DVB = C::DVB, NS = C::NS, RB = C::RB;
   constexpr uint32_t MASK = C::MASK;
   typedef Wave<C> W;
@@ -659,16 +659,15 @@ fwd_bf16_kernel(const FwdParams p) {
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  W w(p);
 
   // ---- logical grid decode (Sec. 3.6): 1-D launch -> (b, g, h, q-tile or pair of q-tiles).
   // With p.pair a workgroup takes q-tile nq - 1 - pi and then q-tile pi: under a causal mask the
   // two together see the same number of key tiles for every pi, so all workgroups carry the same
   // load and the launch has no tail of long stragglers.  Without it, q-tiles go out longest first.
-  const int nq = p.n_qtiles, npairs = p.pair ? (nq + 1) / 2 : nq;
+  const int nq = call.n_qtiles, npairs = call.pair ? (nq + 1) / 2 : nq;
   int bid = blockIdx.x;
   int pi, bh;
-  if (p.order == 1) {
+  if (call.order == 1) {
     // XCD-aware: consecutive workgroup ids go round-robin to the 8 XCDs; give each XCD whole
     // (b, g, h) problems so that a head's K/V stay in one L2 (host checks (B*G*H) % 8 == 0).
     const int xcd = bid & 7;
@@ -679,6 +678,16 @@ fwd_bf16_kernel(const FwdParams p) {
     pi = bid % npairs;
     bh = bid / npairs;
   }
+  // The problem as this workgroup sees it.  With per-sequence key counts (a chunk of new query rows against each
+  // sequence's cached keys, Sec. 4.1 serving) sequence b has kv_lens[b] keys, cut to [0, Sk], and its query rows are the
+  // last Sq positions of those: row i sits at position kv_lens[b] - Sq + i (rows at negative positions see nothing).
+  FwdParams p = call;
+  if (call.kv_lens != nullptr) {
+    const int len = max(0, min(call.kv_lens[bh / (call.H * call.G)], call.Sk));
+    p.Sk = len;
+    p.q_off = len - call.Sq;
+  }
+  W w(p);
 #pragma nounroll
   for (int pass = 0; pass < 2; ++pass) {
   const int qt = pass == 0 ? nq - 1 - pi : pi;
@@ -803,47 +812,62 @@ fwd_bf16_kernel(const FwdParams p) {
       }
     return ks;
   };
-  // The same for a uniform t, once per step of the loop: read through the scalar cache.  A vector
-  // load there would have to wait for the tile loads in flight (vector memory operations complete
-  // in order); the summaries were written by an earlier kernel, so the scalar cache sees them.
-  // The lane-read built-in returns a signed int: both address halves go through uint32_t, or a low
-  // half with bit 31 set would be sign-extended over the high half.
+  // The same for a uniform t, waiting for the answer: set-up and the search after a run of hidden tiles only.
   auto tile_keys = [&](int t) __attribute__((always_inline)) -> int2 {
-    int2 ks = make_int2(0, 0);
-#pragma unroll
-    for (int u = 0; u < NB; ++u) {
-      const uint64_t a = (uint64_t)(ksum + min(t * NB + u, nks - 1));
-      const uint64_t au = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(a >> 32)) << 32) |
-                          (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)a);
-      unsigned long long r;
-      // (the idle cycles keep the load clear of the vector instruction that has just written its address registers)
-      asm volatile("s_nop 4\n\ts_load_dwordx2 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(r) : "s"(au) : "memory");
-      const int x = (int)(uint32_t)r, y = (int)(uint32_t)(r >> 32);
-      ks = u == 0 ? make_int2(x, y) : make_int2(min(ks.x, x), max(ks.y, y));
-    }
-    return ks;
+    const int2 ks = tile_keys_lane(t);
+    return make_int2(__builtin_amdgcn_readfirstlane(ks.x), __builtin_amdgcn_readfirstlane(ks.y));
   };
-  auto next_tile = [&](int t) __attribute__((always_inline)) -> int {             // uniform over the workgroup
+  // Inside the loop the range of the tile that the stream will most likely take next is fetched a whole step ahead, with
+  // ordinary vector loads (every lane reads the same address).  Vector memory operations complete in order and every step
+  // of a kernel with a document mask ends with a wait for all of this wave's loads, so the answer has arrived by the time
+  // it is needed, without a wait of its own.  (Scalar loads cannot be left in flight across a step: they share a counter
+  // with the LDS reads, whose counted waits rely on in-order return.)
+  int2 kpre[NB];                                   // what those loads return
+  int tpre = -1;                                   // the tile they belong to (uniform)
+#pragma unroll
+  for (int u = 0; u < NB; ++u) kpre[u] = make_int2(0, 0);
+  auto prefetch_keys = [&](int t) __attribute__((always_inline)) {
+    tpre = t;
+#pragma unroll
+    for (int u = 0; u < NB; ++u) kpre[u] = ksum[min(t * NB + u, nks - 1)];
+  };
+  auto fetched_keys = [&]() __attribute__((always_inline)) -> int2 {
+    int2 ks = kpre[0];
+#pragma unroll
+    for (int u = 1; u < NB; ++u)
+      if (tpre * NB + u < nks) {
+        ks.x = min(ks.x, kpre[u].x);
+        ks.y = max(ks.y, kpre[u].y);
+      }
+    return make_int2(__builtin_amdgcn_readfirstlane(ks.x), __builtin_amdgcn_readfirstlane(ks.y));
+  };
+  // First tile at or after t with something visible to the workgroup (t_hi if none), and the document-id range of its keys.
+  auto next_tile = [&](int t, int2& ks) __attribute__((always_inline)) -> int {   // uniform over the workgroup
+    ks = make_int2(0, 0);
     if constexpr ((MASK & kMaskDoc) != 0) {
-      // the usual case first: tile t itself has something visible (one uniform check)
-      if (t < t_hi && classify_block(MASK, pos0, pos_last, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg,
-                                     tile_keys(t)) == kSkip) {
-        // a run of hidden tiles (the other documents of a long sequence): 64 tiles per round, one per lane
-        ++t;
-        while (t < t_hi) {
-          const int tt = t + w.lane;
-          bool keep = false;
-          if (tt < t_hi)
-            keep = classify_block(MASK, pos0, pos_last, tt * BN, tt * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg,
-                                  tile_keys_lane(tt)) != kSkip;
-          const unsigned long long found = __builtin_amdgcn_ballot_w64(keep);
-          if (found != 0) {
-            t += __builtin_ctzll(found);
-            break;
+      if (t < t_hi) {
+        ks = t == tpre ? fetched_keys() : tile_keys(t);
+        // the usual case first: tile t itself has something visible (one uniform check)
+        if (classify_block(MASK, pos0, pos_last, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg, ks) == kSkip) {
+          // a run of hidden tiles (the other documents of a long sequence): 64 tiles per round, one per lane
+          ++t;
+          while (t < t_hi) {
+            const int tt = t + w.lane;
+            bool keep = false;
+            if (tt < t_hi)
+              keep = classify_block(MASK, pos0, pos_last, tt * BN, tt * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg,
+                                    tile_keys_lane(tt)) != kSkip;
+            const unsigned long long found = __builtin_amdgcn_ballot_w64(keep);
+            if (found != 0) {
+              t += __builtin_ctzll(found);
+              break;
+            }
+            t += 64;
           }
-          t += 64;
+          t = __builtin_amdgcn_readfirstlane(t < t_hi ? t : t_hi);
+          if (t < t_hi) ks = tile_keys(t);
         }
-        t = __builtin_amdgcn_readfirstlane(t < t_hi ? t : t_hi);
+        if (t < t_hi) prefetch_keys(t + 1);
       }
     }
     return t;                                      // positional masks are already in [t_lo, t_hi)
@@ -863,18 +887,16 @@ fwd_bf16_kernel(const FwdParams p) {
     tv_lo = __builtin_amdgcn_readfirstlane(lo / BN);
     tv_hi = __builtin_amdgcn_readfirstlane((hi + BN - 1) / BN);
   }
-  auto wave_class = [&](int t) __attribute__((always_inline)) -> int {            // uniform over the wave
+  auto wave_class = [&](int t, int2 ks) __attribute__((always_inline)) -> int {   // uniform over the wave; ks: the tile's id range
     if (t >= t_hi) return kTileSkip;
-    int2 ks = make_int2(0, 0);
-    if constexpr ((MASK & kMaskDoc) != 0) ks = tile_keys(t);
     const int c = classify_block(MASK, posw, posw + C::WROWS - 1, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix,
                                  qs_wave, ks);
     return __builtin_amdgcn_readfirstlane(c);
   };
 
-  auto wave_full = [&](int t) __attribute__((always_inline)) -> bool {            // is tile t fully visible to the wave?
+  auto wave_full = [&](int t, int2 ks) __attribute__((always_inline)) -> bool {   // is tile t fully visible to the wave?
     if constexpr ((MASK & kMaskCustom) != 0) return false;   // an arbitrary predicate: evaluated on every score
-    if constexpr ((MASK & kMaskDoc) != 0) return wave_class(t) == kTileFull;
+    if constexpr ((MASK & kMaskDoc) != 0) return wave_class(t, ks) == kTileFull;
     else return t >= tf_lo && t < tf_hi;
   };
 
@@ -977,11 +999,15 @@ fwd_bf16_kernel(const FwdParams p) {
     // whose K the current step streams into the rings (t_hi past the end of the list)
     constexpr int SPB = C::SPB, RING = C::RING, NTL = SPB + 2;
     int tl[NTL];
-    tl[0] = next_tile(t_lo);
+    int2 tks[NTL];                                 // document-id ranges of those tiles' keys (document masks only)
+    tl[0] = next_tile(t_lo, tks[0]);
     if (tl[0] < t_hi) {
-      auto after = [&](int t) __attribute__((always_inline)) { return t < t_hi ? next_tile(t + 1) : t_hi; };
+      auto after = [&](int t, int2& ks) __attribute__((always_inline)) {
+        ks = make_int2(0, 0);
+        return t < t_hi ? next_tile(t + 1, ks) : t_hi;
+      };
 #pragma unroll
-      for (int u = 1; u < NTL; ++u) tl[u] = after(tl[u - 1]);
+      for (int u = 1; u < NTL; ++u) tl[u] = after(tl[u - 1], tks[u]);
       w.template bias_dma<0>(tl[0] * BN);
       if (tl[1] < t_hi) w.template bias_dma<1>(tl[1] * BN);
       // K of tiles tl[0 .. SPB] into slots 0 .. SPB, V of tiles tl[0 .. SPB - 1] into slots 0 .. SPB - 1
@@ -998,7 +1024,7 @@ fwd_bf16_kernel(const FwdParams p) {
       if constexpr (C::NBIAS > 0) W::template wait_lds<0>();     // staged bias values have arrived
       w.transform(sa, tl[0] * BN, br);
       float mx[RB];
-      bool full0 = wave_full(tl[0]);
+      bool full0 = wave_full(tl[0], tks[0]);
       if (full0) {
         w.rowmax(sa, mx);
         w.advance_max(mx);
@@ -1031,7 +1057,7 @@ fwd_bf16_kernel(const FwdParams p) {
         constexpr int slot_kl = (N + SPB + 1) % RING, slot_vl = (N + SPB) % RING;   // written by this step's loads
         const int t0 = tl[0], t1 = tl[1];
         const int tn = t1;
-        const bool fulln = wave_full(t1);
+        const bool fulln = wave_full(t1, tks[1]);
         if (!full0) {                              // fully visible tiles were settled in phase B
           if (kWaveSkip && (t0 < tv_lo || t0 >= tv_hi)) {
             // nothing of the tile is visible to this wave's rows: all -inf, the running max stays
@@ -1080,8 +1106,11 @@ fwd_bf16_kernel(const FwdParams p) {
         w.template phase_b<slot_vc * C::V_BYTES>(ps, cur, nxt, tn * BN, br, fulln);
         if constexpr (N % SPB == SPB - 1) wait_loads_and_sync();
 #pragma unroll
-        for (int u = 0; u + 1 < NTL; ++u) tl[u] = tl[u + 1];
-        tl[NTL - 1] = tl[NTL - 1] < t_hi ? next_tile(tl[NTL - 1] + 1) : t_hi;
+        for (int u = 0; u + 1 < NTL; ++u) {
+          tl[u] = tl[u + 1];
+          tks[u] = tks[u + 1];
+        }
+        tl[NTL - 1] = after(tl[NTL - 1], tks[NTL - 1]);
         full0 = fulln;
         if constexpr ((MASK & kMaskDoc) == 0) {    // consecutive tiles: advance the bases until the list ends
           if (tl[SPB] < t_hi) vb += vstep;

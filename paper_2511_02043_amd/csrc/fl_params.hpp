@@ -89,6 +89,7 @@ struct FwdParams {
   int32_t pair;          // bf16 kernels: 1 = a workgroup takes q-tiles nq - 1 - i and i (balanced causal work)
   int32_t q_off;         // query row i sits at sequence position i + q_off (positional masks, ALiBi); >= 0
   const void* user_aux[4];   // run-time compiled variants: the caller's device arrays that the expressions read
+  const int32_t* kv_lens;    // bf16 kernels, or null: [B] keys of each sequence (cut to [0, Sk]); then q_off = kv_lens[b] - Sq
 };
 
 }  // namespace fl

@@ -294,3 +294,36 @@ def upload_decode(w, out_dtype: str = "f32", device="cuda:0", paged: bool = True
     slopes = None if w.alibi is None else torch.from_numpy(np.asarray(w.alibi, np.float32)).to(device)
     aux = fb.aux_desc(alibi_slopes=slopes, workspace=ws)
     return DeviceDecode(q, kc, vc, out, lse, desc, kv, aux, [table, lens, ws, slopes], tq, tk, tv, tout, tlse)
+
+
+@dataclasses.dataclass
+class DevicePrefill(DeviceDecode):
+    """Device tensors of one fl_attn_prefill_paged call (an inputs.DecodeWorkload whose q is [B, H, Sq, D])."""
+
+    def run(self, stream: int = 0) -> int:
+        return fb.fl_attn_prefill_paged(self.tq, self.tk, self.tv, self.kv, self.desc, self.aux, self.tout, self.tlse, stream)
+
+
+def upload_prefill_paged(w, out_dtype: str = "f32", device="cuda:0", paged: bool = True, max_seq_len=None) -> DevicePrefill:
+    """Cache stored and viewed as in upload_decode; q [B, H, Sq, D] viewed [B, 1, H, Sq, D]."""
+    tdt = torch.bfloat16
+    q = torch.from_numpy(np.ascontiguousarray(w.q)).to(device, tdt)[:, None]                   # [B, 1, H, Sq, D]
+    kc = torch.from_numpy(np.ascontiguousarray(w.k_cache)).to(device, tdt).permute(0, 2, 1, 3)[:, None]
+    vc = torch.from_numpy(np.ascontiguousarray(w.v_cache)).to(device, tdt).permute(0, 2, 1, 3)[:, None]
+    B, _, H, Sq, D = q.shape
+    out = torch.empty((B, 1, H, Sq, D), dtype=torch.float32 if out_dtype == "f32" else tdt, device=device)
+    lse = torch.empty((B, 1, H, Sq, 1), dtype=torch.float32, device=device)
+    table = torch.from_numpy(w.block_table).to(device) if paged else None
+    lens = torch.from_numpy(w.seq_lens).to(device)
+    mod = fb.FL_MOD_SOFTCAP if w.softcap is not None else (fb.FL_MOD_ALIBI if w.alibi is not None else fb.FL_MOD_NONE)
+    desc = fb.variant_desc(scale=float(w.scale), score_mod=mod, softcap=float(w.softcap or 0.0),
+                           mask=(fb.FL_MASK_WINDOW | fb.FL_MASK_CAUSAL) if w.window is not None else fb.FL_MASK_CAUSAL,
+                           window=int(w.window or 0))
+    if max_seq_len is None:
+        max_seq_len = int(w.seq_lens.max()) if len(w.seq_lens) else 0
+    kv = fb.paged_kv(block_table=table, page_size=w.k_cache.shape[1], seq_lens=lens, max_seq_len=max_seq_len)
+    tq, tk, tv, tout, tlse = (fb.tensor_desc(x) for x in (q, kc, vc, out, lse))
+    ws = torch.empty(max(fb.fl_attn_prefill_paged_workspace_size(tq, tk, kv), 16), dtype=torch.uint8, device=device)
+    slopes = None if w.alibi is None else torch.from_numpy(np.asarray(w.alibi, np.float32)).to(device)
+    aux = fb.aux_desc(alibi_slopes=slopes, workspace=ws)
+    return DevicePrefill(q, kc, vc, out, lse, desc, kv, aux, [table, lens, ws, slopes], tq, tk, tv, tout, tlse)
