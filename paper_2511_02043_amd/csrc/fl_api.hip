@@ -209,17 +209,34 @@ struct BwdRegistry {
   }
 };
 
-const fl::BwdEntry* find_bwd_entry(const fl_variant_desc* d, int D, int nbias = 0) {
+// Can the backward kernel templates be instantiated for this variant at run time (head dim of the core kernels)?
+bool bwd_jit_ok(const fl_variant_desc* d, int D, int nbias) {
+  return (D == 64 || D == 128) && d->score_mod <= FL_MOD_SOFTCAP && nbias >= 0 && nbias <= 2;
+}
+
+// The compiled specialisation of the variant; with `instantiate`, otherwise one built from the kernel templates on first
+// use (a few seconds, once per process and variant).
+const fl::BwdEntry* find_bwd_entry(const fl_variant_desc* d, int D, int nbias = 0, bool instantiate = false) {
   static const BwdRegistry reg;                    // initialised once, also under concurrent first calls
   const fl::BwdEntry* const* tab = reg.tab;
   const int* n = reg.n;
   const int mask = (int)canonical_mask(d->mask);
+  const fl::BwdEntry* same_dim = nullptr;
   for (int t = 0; t < 2; ++t)
     for (int e = 0; e < n[t]; ++e) {
       const fl::BwdEntry& k = tab[t][e];
+      if (k.key.D == D && same_dim == nullptr) same_dim = &k;
       if (k.key.D == D && k.key.mod == (int)d->score_mod && k.key.mask == mask && k.key.nbias == nbias) return &k;
     }
-  return nullptr;
+  if (!instantiate || same_dim == nullptr || !bwd_jit_ok(d, D, nbias)) return nullptr;
+  return fl::jit_backward_entry(D, (int)d->score_mod, (uint32_t)mask, nbias, same_dim->prep, same_dim->reduce);
+}
+
+hipError_t launch_bwd_dq(const fl::BwdEntry* be, const fl::BwdParams& p, int nblocks, hipStream_t stream) {
+  return be->jit != nullptr ? fl::jit_backward_launch(*be, 0, p, nblocks, stream) : be->dq(p, nblocks, stream);
+}
+hipError_t launch_bwd_dkdv(const fl::BwdEntry* be, const fl::BwdParams& p, int nblocks, hipStream_t stream) {
+  return be->jit != nullptr ? fl::jit_backward_launch(*be, 1, p, nblocks, stream) : be->dkdv(p, nblocks, stream);
 }
 
 bool bwd_desc_ok(const fl_variant_desc* d) { return d->n_bias == 0 && d->combine == FL_SINGLE && d->epilogue == 0; }
@@ -610,8 +627,7 @@ bool bwd_simple(const fl_variant_desc* d, int64_t D, int64_t Dv) {
 // Can fl_attn_bwd_ex build the variant from the backward kernels?
 bool bwd_ex_ok(const fl_variant_desc* d, int64_t D, int64_t Dv) {
   if (!((D == 32 || D == 64 || D == 128) && (Dv == 32 || Dv == 64 || Dv == 128))) return false;
-  if (d->n_bias > 0 && d->score_mod != FL_MOD_NONE) return false;
-  return find_bwd_entry(d, core_dim(D, Dv), (int)d->n_bias) != nullptr;
+  return find_bwd_entry(d, core_dim(D, Dv), (int)d->n_bias) != nullptr || bwd_jit_ok(d, core_dim(D, Dv), (int)d->n_bias);
 }
 
 fl::View dense_view(void* ptr, int64_t G, int64_t H, int64_t S, int64_t Dc) {
@@ -951,7 +967,7 @@ size_t fl_attn_bwd_workspace_size(const fl_tensor* q, const fl_tensor* k, const 
 
 int fl_bwd_supported(const fl_variant_desc* desc, int dtype, int D, int Dv) {
   if (check_desc(desc) != FL_OK || dtype != FL_BF16) return 0;
-  if (bwd_simple(desc, D, Dv)) return find_bwd_entry(desc, D) != nullptr ? 1 : 0;
+  if (bwd_simple(desc, D, Dv)) return find_bwd_entry(desc, D) != nullptr || bwd_jit_ok(desc, D, 0) ? 1 : 0;
   return bwd_ex_ok(desc, D, Dv) ? 1 : 0;
 }
 
@@ -977,7 +993,7 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   if (Hkv <= 0 || H % (Hkv > 0 ? Hkv : 1) != 0)
     if (H != 0) return fail(FL_ERR_SHAPE, "k heads (%lld) must divide q heads (%lld)", (long long)Hkv, (long long)H);
   const uint32_t mask = canonical_mask(desc->mask);
-  const fl::BwdEntry* be = D == Dv ? find_bwd_entry(desc, (int)D) : nullptr;
+  const fl::BwdEntry* be = D == Dv ? find_bwd_entry(desc, (int)D, 0, true) : nullptr;
   if (be == nullptr)
     return fail(FL_ERR_UNSUPPORTED, "no backward specialisation for D=%lld Dv=%lld score_mod=%u mask=0x%x", (long long)D,
                 (long long)Dv, desc->score_mod, mask);
@@ -1080,11 +1096,11 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
     const int64_t nb_prep = (rows * lanes_per_row + 255) / 256;
     if ((e = be->prep(p, (int)nb_prep, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "pre-pass launch: %s", hipGetErrorString(e));
     // Sk == 0: the key loop is empty and dq comes out as zeros
-    if ((e = be->dq(p, (int)nb_q, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dq launch: %s", hipGetErrorString(e));
+    if ((e = launch_bwd_dq(be, p, (int)nb_q, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dq launch: %s", hipGetErrorString(e));
   }
   if (!no_keys) {
     // Sq == 0: the query loop is empty and dk, dv come out as zeros
-    if ((e = be->dkdv(p, (int)nb_k, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dk/dv launch: %s", hipGetErrorString(e));
+    if ((e = launch_bwd_dkdv(be, p, (int)nb_k, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dk/dv launch: %s", hipGetErrorString(e));
     if (p.hsplit > 1) {
       const int64_t chunks = B * G * Hkv * Sk * (D / 4);
       if ((e = be->reduce(p, (int)((chunks + 255) / 256), stream)) != hipSuccess)
@@ -1129,7 +1145,7 @@ fl_status fl_attn_bwd_ex(const fl_tensor* q, const fl_tensor* k, const fl_tensor
   const bool has_gate = (desc->epilogue & FL_EPI_GATE_SIGMOID) != 0, has_rms = (desc->epilogue & FL_EPI_RMSNORM) != 0;
   const ExLayout L = ex_layout(B, G, H, Hkv, Sq, Sk, D, Dv, desc);
   const int Dc = L.Dc, ns = L.ns;
-  const fl::BwdEntry* be = find_bwd_entry(desc, Dc, (int)desc->n_bias);
+  const fl::BwdEntry* be = find_bwd_entry(desc, Dc, (int)desc->n_bias, true);
 
   // ---- tensors
   const int64_t qsz[5] = {B, G, H, Sq, D}, ksz[5] = {B, G, Hkv, Sk, D}, vsz[5] = {B, G, Hkv, Sk, Dv}, osz[5] = {B, G, H, Sq, Dv};
@@ -1334,7 +1350,7 @@ fl_status fl_attn_bwd_ex(const fl_tensor* q, const fl_tensor* k, const fl_tensor
     p.dv = dense_view(ws + L.off_gv[s], G, Hkv, Sk, Dc);
     p.delta = (float*)(ws + L.off_delta[s]);
     p.lse2 = (float*)(ws + L.off_lse2[s]);
-    if ((e = be->dq(p, (int)nb_q, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dq launch: %s", hipGetErrorString(e));
+    if ((e = launch_bwd_dq(be, p, (int)nb_q, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dq launch: %s", hipGetErrorString(e));
     for (uint32_t nb = 0; nb < desc->n_bias; ++nb)
       if (dbias[nb].ptr != nullptr) {               // this stream's dS, summed over the axes the bias broadcasts along
         const fl_tensor* gt = &extra->dbias[nb];
@@ -1343,7 +1359,7 @@ fl_status fl_attn_bwd_ex(const fl_tensor* q, const fl_tensor* k, const fl_tensor
                            (int)H, (int)Sq, (int)Sk, (int)gt->size[0], (int)gt->size[1], (int)gt->size[2], (int)gt->size[3],
                            (int)gt->size[4], total, s);
       }
-    if ((e = be->dkdv(p, (int)nb_k, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dk/dv launch: %s", hipGetErrorString(e));
+    if ((e = launch_bwd_dkdv(be, p, (int)nb_k, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dk/dv launch: %s", hipGetErrorString(e));
     if (p.hsplit > 1) {
       const int64_t chunks = rows_k * (Dc / 4);
       if ((e = be->reduce(p, (int)((chunks + 255) / 256), stream)) != hipSuccess)

@@ -414,7 +414,12 @@ bwd_dq_kernel(const BwdParams p) {
   constexpr uint32_t MASK = C::MASK;
   constexpr uint32_t POS = MASK & ~kMaskDoc;
   typedef BwdWave<C> W;
+#ifdef FL_LDS_STATIC   // instantiated at run time: the size is part of the code object (a launch through the module API
+                       // cannot ask for more than 64 KiB of dynamic LDS)
+  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[2 * C::STAGE_DQ];
+#else
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+#endif
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -561,10 +566,13 @@ bwd_dq_kernel(const BwdParams p) {
           kd[r] = kdoc[j < p.Sk ? j : p.Sk - 1];
         }
       }
-      uint32_t dsw[8];
+      // dsw: the gradient of the raw scaled score (what dQ contracts with K); dbw: the gradient of the score after the
+      // score_mod, which is the bias gradient (biases follow the score_mod) -- the two differ by the soft-cap derivative
+      constexpr bool kSplit = C::NBIAS > 0 && C::MOD == kModSoftcap;
+      uint32_t dsw[8], dbw[8];                   // (dbw is only written and read when the two differ)
 #pragma unroll
       for (int r2 = 0; r2 < 8; ++r2) {
-        float dsv[2], pr[2];
+        float dsv[2], dbv[2], pr[2];
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
           const int r = 2 * r2 + e;
@@ -573,8 +581,8 @@ bwd_dq_kernel(const BwdParams p) {
           float a = replay_score<C::MOD>(s[r], c_scale, lse2, p.softcap, slope2, (float)(i + p.q_off - j), fac);
           if constexpr (C::NBIAS > 0) a += bl[r];
           pr[e] = fast_exp2(a);
-          dsv[e] = dp[r] - delta;
-          if constexpr (C::MOD == kModSoftcap) dsv[e] *= fac;
+          dbv[e] = dp[r] - delta;
+          dsv[e] = C::MOD == kModSoftcap ? dbv[e] * fac : dbv[e];
         }
         if (need_mask) {                           // uniform; kept a branch: most tiles need no mask
           asm volatile("");
@@ -588,22 +596,22 @@ bwd_dq_kernel(const BwdParams p) {
         dsv[0] *= pr[0];
         dsv[1] *= pr[1];
         dsw[r2] = pack_bf16(dsv[0], dsv[1]);
+        if constexpr (kSplit) dbw[r2] = pack_bf16(dbv[0] * pr[0], dbv[1] * pr[1]);
       }
-      if constexpr (C::NBIAS > 0) {                // the bias gradient is dS itself (biases follow the score_mod):
-        // staged for the host's reduction over the axes each bias broadcasts along; registers 4q .. 4q + 3 are
-        // the four consecutive keys jb + 8q ..
-        static_assert(C::NBIAS == 0 || C::MOD != kModSoftcap, "dsw holds dS times the soft-cap derivative");
+      if constexpr (C::NBIAS > 0) {                // staged for the host's reduction over the axes each bias broadcasts
+        // along; registers 4q .. 4q + 3 are the four consecutive keys jb + 8q ..
+        auto staged = [&](int n) __attribute__((always_inline)) { return kSplit ? dbw[n] : dsw[n]; };
         if (p.ds_stage != nullptr && i < p.Sq) {
           uint16_t* row = p.ds_stage + (((int64_t)(b * p.G + g) * p.H + h) * p.Sq + i) * p.Sk;
 #pragma unroll
           for (int q4 = 0; q4 < 4; ++q4) {
             const int j = jb + 8 * q4;
             if ((p.Sk & 3) == 0 && j + 3 < p.Sk) {
-              *(uint2*)(row + j) = make_uint2(dsw[2 * q4], dsw[2 * q4 + 1]);
+              *(uint2*)(row + j) = make_uint2(staged(2 * q4), staged(2 * q4 + 1));
             } else {
 #pragma unroll
               for (int u = 0; u < 4; ++u)
-                if (j + u < p.Sk) row[j + u] = (uint16_t)(dsw[2 * q4 + (u >> 1)] >> (16 * (u & 1)));
+                if (j + u < p.Sk) row[j + u] = (uint16_t)(staged(2 * q4 + (u >> 1)) >> (16 * (u & 1)));
             }
           }
         }
@@ -664,7 +672,12 @@ bwd_dkdv_kernel(const BwdParams p) {
   constexpr uint32_t MASK = C::MASK;
   constexpr uint32_t POS = MASK & ~kMaskDoc;
   typedef BwdWave<C> W;
+#ifdef FL_LDS_STATIC   // instantiated at run time: the size is part of the code object (a launch through the module API
+                       // cannot ask for more than 64 KiB of dynamic LDS)
+  __shared__ __attribute__((aligned(16))) unsigned char lds_raw[3 * C::STAGE_KV];
+#else
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+#endif
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);

@@ -18,7 +18,15 @@ struct BwdEntry {
   BwdKey key;
   int bm;           // query rows per workgroup of the dQ kernel = keys per workgroup of the dK/dV kernel
   BwdLaunchFn prep, dq, dkdv, reduce;   // reduce: sum of the head-subset partials of dK / dV (nblocks of 256 threads)
+  void* jit;        // entries instantiated at run time: their dq / dkdv are null and launched through jit_backward_launch
 };
+
+// A backward specialisation outside the compiled table, instantiated from the same kernel templates with hipRTC
+// on first use and kept for the life of the process (null if it does not compile).  prep / reduce: the compiled
+// pre-pass and partial-sum kernels of that head dim, which do not depend on the variant.
+const BwdEntry* jit_backward_entry(int D, int mod, uint32_t mask, int nbias, BwdLaunchFn prep, BwdLaunchFn reduce);
+// which: 0 = the dQ kernel, 1 = the dK/dV kernel
+hipError_t jit_backward_launch(const BwdEntry& e, int which, const BwdParams& p, int nblocks, hipStream_t stream);
 
 template <class K>
 hipError_t raise_lds_limit(K kernel) {
@@ -76,9 +84,9 @@ constexpr BwdEntry bwd_entry() {
   typedef BwdCfg<D, MOD, MASK, BN_Q, WPE_Q, NBIAS> CQ;
   typedef BwdCfg<D, MOD, MASK, BN_K, WPE_K, NBIAS> CK;
   if constexpr (WS)
-    return BwdEntry{BwdKey{D, MOD, (int)MASK, NBIAS}, CQ::BM, &launch_bwd_prep<D>, &launch_bwd_dq<CQ>, &launch_bwd_dkdv_ws<CK>, &launch_bwd_reduce<D>};
+    return BwdEntry{BwdKey{D, MOD, (int)MASK, NBIAS}, CQ::BM, &launch_bwd_prep<D>, &launch_bwd_dq<CQ>, &launch_bwd_dkdv_ws<CK>, &launch_bwd_reduce<D>, nullptr};
   else
-    return BwdEntry{BwdKey{D, MOD, (int)MASK, NBIAS}, CQ::BM, &launch_bwd_prep<D>, &launch_bwd_dq<CQ>, &launch_bwd_dkdv<CK>, &launch_bwd_reduce<D>};
+    return BwdEntry{BwdKey{D, MOD, (int)MASK, NBIAS}, CQ::BM, &launch_bwd_prep<D>, &launch_bwd_dq<CQ>, &launch_bwd_dkdv<CK>, &launch_bwd_reduce<D>, nullptr};
 }
 
 const BwdEntry* entries_bwd64(int* n);

@@ -18,10 +18,11 @@
 
 #include "../../include/fl_attn.h"
 #include "fl_host.hpp"
+#include "fl_bwd_registry.hpp"
 #include "fl_registry.hpp"
 
 namespace {
-#include "_build/fl_embedded.inc"   // kParamsHpp, kKernelHpp: the two kernel headers as strings
+#include "_build/fl_embedded.inc"   // kParamsHpp, kKernelHpp, kBwdHpp: the kernel headers as strings
 }
 
 struct fl_custom_variant {
@@ -51,17 +52,18 @@ bool expression_ok(const char* e) {
 }
 
 
-// Compiles `src` (which instantiates the kernel named by the expression `inst`) for gfx950 with the
-// library's own flags; returns the code object and the lowered kernel name.
-fl_status compile_instance(const std::string& src, const char* inst, const char* what, std::vector<char>* code,
-                           std::string* kernel_name) {
-  const char* headers[] = {kParamsHpp, kKernelHpp};
-  const char* names[] = {"fl_params.hpp", "fl_kernel_bf16.hpp"};
+// Compiles `src` (which instantiates the kernels named by the expressions `insts`) for gfx950 with the
+// library's own flags; returns the code object and the lowered kernel names.
+fl_status compile_program(const std::string& src, const std::vector<std::string>& insts, const char* what,
+                          std::vector<char>* code, std::vector<std::string>* kernel_names) {
+  const char* headers[] = {kParamsHpp, kKernelHpp, kBwdHpp};
+  const char* names[] = {"fl_params.hpp", "fl_kernel_bf16.hpp", "fl_bwd_bf16.hpp"};
   hiprtcProgram prog;
-  if (hiprtcCreateProgram(&prog, src.c_str(), "fl_variant.hip", 2, headers, names) != HIPRTC_SUCCESS)
+  if (hiprtcCreateProgram(&prog, src.c_str(), "fl_variant.hip", 3, headers, names) != HIPRTC_SUCCESS)
     return fl::host::fail(FL_ERR_LAUNCH, "hiprtcCreateProgram failed");
-  std::string expr = std::string("&") + inst;
-  hiprtcAddNameExpression(prog, expr.c_str());
+  std::vector<std::string> exprs;
+  for (const std::string& i : insts) exprs.push_back("&" + i);
+  for (const std::string& e : exprs) hiprtcAddNameExpression(prog, e.c_str());
   // gfx950 only, packed fp32 instructions off
   const char* opts[] = {"--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
   const hiprtcResult r = hiprtcCompileProgram(prog, (int)(sizeof(opts) / sizeof(opts[0])), opts);
@@ -80,14 +82,25 @@ fl_status compile_instance(const std::string& src, const char* inst, const char*
   hiprtcGetCodeSize(prog, &cs);
   code->resize(cs);
   hiprtcGetCode(prog, code->data());
-  const char* lowered = nullptr;
-  if (hiprtcGetLoweredName(prog, expr.c_str(), &lowered) != HIPRTC_SUCCESS || lowered == nullptr) {
-    hiprtcDestroyProgram(&prog);
-    return fl::host::fail(FL_ERR_LAUNCH, "no lowered kernel name");
+  kernel_names->clear();
+  for (const std::string& e : exprs) {
+    const char* lowered = nullptr;
+    if (hiprtcGetLoweredName(prog, e.c_str(), &lowered) != HIPRTC_SUCCESS || lowered == nullptr) {
+      hiprtcDestroyProgram(&prog);
+      return fl::host::fail(FL_ERR_LAUNCH, "no lowered kernel name");
+    }
+    kernel_names->push_back(lowered);
   }
-  *kernel_name = lowered;
   hiprtcDestroyProgram(&prog);
   return FL_OK;
+}
+
+fl_status compile_instance(const std::string& src, const char* inst, const char* what, std::vector<char>* code,
+                           std::string* kernel_name) {
+  std::vector<std::string> names;
+  const fl_status st = compile_program(src, {inst}, what, code, &names);
+  if (st == FL_OK) *kernel_name = names[0];
+  return st;
 }
 
 // A code object loaded lazily, once per device.
@@ -167,6 +180,57 @@ hipError_t jit_forward_launch(const KernelEntry& e, const FwdParams& p, int nblo
   FwdParams copy = p;
   void* args[] = {&copy};
   return hipModuleLaunchKernel(f, (unsigned)nblocks, 1, 1, (unsigned)j->nthreads, 1, 1, (unsigned)p.lds_bytes, stream, args, nullptr);
+}
+
+namespace {
+struct JitBackward {
+  LoadedKernel dq, dkdv;            // one code object (held twice) with both kernels
+  BwdEntry entry;
+};
+}  // namespace
+
+const BwdEntry* jit_backward_entry(int D, int mod, uint32_t mask, int nbias, BwdLaunchFn prep, BwdLaunchFn reduce) {
+  typedef std::tuple<int, int, uint32_t, int> Key;
+  static std::mutex mu;
+  static std::map<Key, JitBackward*> cache;       // entries live until the process ends
+  const Key key(D, mod, mask, nbias);
+  std::lock_guard<std::mutex> lock(mu);            // one compilation at a time; a hit only takes the lookup
+  auto it = cache.find(key);
+  if (it != cache.end()) return it->second != nullptr ? &it->second->entry : nullptr;
+  // Shapes: the dQ kernel streams 64-key tiles at two waves per SIMD; the dK/dV kernel is the plain one (four waves,
+  // 64-row tiles), two waves per SIMD at head dim 64 and one at 128.  Their LDS is declared statically in the
+  // generated code (FL_LDS_STATIC): a launch through the module API cannot ask for more than 64 KiB dynamically.
+  const int bn_k = 64, wpe_k = D == 128 ? 1 : 2;
+  char cq[160], ck[160];
+  snprintf(cq, sizeof(cq), "fl::BwdCfg<%d, %d, %uu, 64, 2, %d>", D, mod, mask, nbias);
+  snprintf(ck, sizeof(ck), "fl::BwdCfg<%d, %d, %uu, %d, %d, %d>", D, mod, mask, bn_k, wpe_k, nbias);
+  const std::string iq = std::string("fl::bwd_dq_kernel<") + cq + ">", ik = std::string("fl::bwd_dkdv_kernel<") + ck + ">";
+  std::string src = "#define FL_LDS_STATIC 1\n#include \"fl_bwd_bf16.hpp\"\n";
+  src += "template __global__ void " + iq + "(const fl::BwdParams);\n";
+  src += "template __global__ void " + ik + "(const fl::BwdParams);\n";
+  JitBackward* j = new JitBackward;
+  std::vector<std::string> names;
+  if (compile_program(src, {iq, ik}, "run-time backward specialisation does not compile", &j->dq.code, &names) != FL_OK) {
+    delete j;
+    cache[key] = nullptr;                          // do not try again
+    return nullptr;
+  }
+  j->dkdv.code = j->dq.code;
+  j->dq.kernel_name = names[0];
+  j->dkdv.kernel_name = names[1];
+  j->entry = BwdEntry{BwdKey{D, mod, (int)mask, nbias}, 128, prep, nullptr, nullptr, reduce, j};
+  cache[key] = j;
+  return &j->entry;
+}
+
+hipError_t jit_backward_launch(const BwdEntry& e, int which, const BwdParams& p, int nblocks, hipStream_t stream) {
+  JitBackward* j = (JitBackward*)e.jit;
+  hipFunction_t f = nullptr;
+  hipError_t err = (which == 0 ? j->dq : j->dkdv).get(&f);
+  if (err != hipSuccess) return err;
+  BwdParams copy = p;
+  void* args[] = {&copy};
+  return hipModuleLaunchKernel(f, (unsigned)nblocks, 1, 1, 256, 1, 1, 0, stream, args, nullptr);
 }
 
 }  // namespace fl

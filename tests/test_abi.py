@@ -120,7 +120,9 @@ def test_backward_validation_paths_return_before_any_launch():
     assert fb.fl_bwd_supported(fb.variant_desc(scale=0.125, n_bias=1), fb.FL_BF16, 64, 64)
     assert fb.fl_bwd_supported(fb.variant_desc(scale=0.125, combine=fb.FL_DIFFERENTIAL), fb.FL_BF16, 64, 64)
     assert not fb.fl_bwd_supported(d, fb.FL_BF16, 96, 96)
-    assert not fb.fl_bwd_supported(fb.variant_desc(scale=0.125, n_bias=1, mask=fb.FL_MASK_DOC), fb.FL_BF16, 64, 64)
+    # variants outside the compiled backward table are instantiated from the kernel templates at run time
+    assert fb.fl_bwd_supported(fb.variant_desc(scale=0.125, n_bias=1, mask=fb.FL_MASK_DOC), fb.FL_BF16, 64, 64)
+    assert fb.fl_bwd_supported(fb.variant_desc(scale=0.125, score_mod=fb.FL_MOD_SOFTCAP, softcap=2.0, mask=fb.FL_MASK_PREFIX), fb.FL_BF16, 128, 128)
     assert fb.fl_bwd_supported(fb.variant_desc(scale=0.125, mask=fb.FL_MASK_CAUSAL, q_offset=4), fb.FL_BF16, 64, 64)
     # workspace: two float rows statistics per query row, each array padded to 256 bytes
     assert fb.fl_attn_bwd_workspace_size(t, t, d) == 2 * 512
@@ -144,7 +146,7 @@ def test_backward_validation_paths_return_before_any_launch():
     g = fb.variant_desc(scale=0.125, epilogue=fb.FL_EPI_GATE_SIGMOID)
     assert fb.fl_attn_bwd(t, t, t, t, t, lse, g, a, t, t, t) == fb.FL_ERR_AUX_MISSING      # the gate tensor
     gb = fb.variant_desc(scale=0.125, n_bias=1, mask=fb.FL_MASK_DOC)
-    assert fb.fl_attn_bwd(t, t, t, t, t, lse, gb, a, t, t, t) == fb.FL_ERR_UNSUPPORTED
+    assert fb.fl_attn_bwd(t, t, t, t, t, lse, gb, a, t, t, t) == fb.FL_ERR_AUX_MISSING      # the document ids, the bias
     assert fb.fl_attn_bwd_ex_workspace_size(t, t, t, d) == fb.fl_attn_bwd_workspace_size(t, t, d)
     assert fb.fl_attn_bwd_ex_workspace_size(t, t, t, g) > fb.fl_attn_bwd_workspace_size(t, t, d)
     f32 = fb.fl_tensor()

@@ -164,11 +164,12 @@ def test_backward_error_paths():
     desc = fb.variant_desc(scale=0.125, epilogue=fb.FL_EPI_GATE_SIGMOID)
     st = fb.fl_attn_bwd(f.tq, f.tk, f.tv, f.tout, db.tdout, f.tlse, desc, db.aux, db.tdq, db.tdk, db.tdv)
     assert st == fb.FL_ERR_AUX_MISSING
-    # a variant without backward kernels: a bias under a document mask
-    desc = fb.variant_desc(scale=0.125, n_bias=1, mask=fb.FL_MASK_DOC)
+    # a biased variant goes the same way and asks for the bias tensor
+    desc = fb.variant_desc(scale=0.125, n_bias=1, mask=fb.FL_MASK_PREFIX, prefix_len=8)
     st = fb.fl_attn_bwd(f.tq, f.tk, f.tv, f.tout, db.tdout, f.tlse, desc, db.aux, db.tdq, db.tdk, db.tdv)
-    assert st == fb.FL_ERR_UNSUPPORTED
-    assert not fb.fl_bwd_supported(desc, fb.FL_BF16, 64, 64)
+    assert st in (fb.FL_ERR_AUX_MISSING, fb.FL_ERR_NULL)
+    assert fb.fl_bwd_supported(desc, fb.FL_BF16, 64, 64)
+    assert not fb.fl_bwd_supported(desc, fb.FL_BF16, 96, 96)
     assert fb.fl_bwd_supported(f.desc, fb.FL_BF16, 64, 64)
     assert fb.fl_bwd_supported(f.desc, fb.FL_BF16, 32, 32)       # zero-padded to the kernels' head dim 64
     # missing aux

@@ -95,8 +95,9 @@ def test_supported_and_error_paths():
     assert fb.fl_bwd_supported(d, fb.FL_BF16, 32, 32) and fb.fl_bwd_supported(d, fb.FL_BF16, 128, 128)
     d4 = fb.variant_desc(scale=0.1, mask=fb.FL_MASK_CAUSAL, combine=fb.FL_DIFFERENTIAL, epilogue=fb.FL_EPI_RMSNORM, rms_eps=1e-6)
     assert fb.fl_bwd_supported(d4, fb.FL_BF16, 64, 128)
-    assert not fb.fl_bwd_supported(fb.variant_desc(scale=0.1, n_bias=1, score_mod=fb.FL_MOD_SOFTCAP, softcap=2.0), fb.FL_BF16, 64, 64)
-    assert not fb.fl_bwd_supported(fb.variant_desc(scale=0.1, n_bias=1, mask=fb.FL_MASK_DOC), fb.FL_BF16, 64, 64)
+    assert fb.fl_bwd_supported(fb.variant_desc(scale=0.1, n_bias=1, score_mod=fb.FL_MOD_SOFTCAP, softcap=2.0), fb.FL_BF16, 64, 64)
+    assert fb.fl_bwd_supported(fb.variant_desc(scale=0.1, n_bias=1, mask=fb.FL_MASK_DOC), fb.FL_BF16, 64, 64)
+    assert not fb.fl_bwd_supported(d, fb.FL_BF16, 96, 96)
     w = inputs.differential_bf16(B=1, H=2, S=100)
     db = runner.upload_backward_ex(w, inputs.dout_for(w))
     db.fwd.run_checked()
