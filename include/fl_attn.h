@@ -23,8 +23,10 @@
  * All tensor pointers are DEVICE pointers owned by the caller.  The library never allocates,
  * frees or keeps device memory; work is enqueued on the caller's stream and the call returns
  * without synchronising.  Every validation failure returns before anything is launched and
- * leaves the outputs untouched.  There is no CPU fallback and no generic slow path for a
- * descriptor without a compiled specialisation: that is FL_ERR_UNSUPPORTED.
+ * leaves the outputs untouched.  There is no CPU fallback and no generic slow path: a bf16
+ * descriptor without a compiled specialisation is instantiated from the same kernel templates on
+ * its first use (hipRTC, a few seconds, once per process); head dims outside {32, 64, 128} are
+ * FL_ERR_UNSUPPORTED.
  */
 #ifndef FL_ATTN_H
 #define FL_ATTN_H
@@ -175,7 +177,8 @@ fl_status fl_attn_fwd_noalloc(const fl_tensor* q, const fl_tensor* k, const fl_t
  * from the saved lse, dP = dout V^T, dS = P * (dP - rowsum(dout * out)) (times 1 - tanh^2 under a
  * soft-cap), and dv = P^T dout, dk = scale * dS^T q, dq = scale * dS k.
  *
- *   q, k, v      as given to fl_attn_fwd (bf16; D == Dv in {64, 128})
+ *   q, k, v      as given to fl_attn_fwd (bf16; D == Dv in {64, 128}; any score_mod and mask: a combination
+ *                without a compiled backward kernel is instantiated on first use, as in the forward pass)
  *   out, lse     what fl_attn_fwd wrote for them: out [B, G, H, Sq, Dv] bf16, lse [B, G, H, Sq, 1] f32
  *   dout         [B, G, H, Sq, Dv] bf16, the gradient arriving at out
  *   dq           [B, G, H,   Sq, D ] bf16 or f32, written
@@ -225,9 +228,11 @@ typedef struct {
  *   out, lse   what fl_attn_fwd wrote (lse [B, 2G, H, Sq, 1] for FL_DIFFERENTIAL)
  *   aux        as for fl_attn_fwd, with aux->workspace of fl_attn_bwd_ex_workspace_size bytes (16-byte aligned)
  *   extra      may be NULL when the variant has nothing beyond dq, dk, dv to write
- * Covered: everything fl_attn_bwd covers, plus biases with score_mod = FL_MOD_NONE under no mask or
- * FL_MASK_CAUSAL, plus any epilogue / FL_DIFFERENTIAL on top of those.  The gradient of rms_weight is not
- * computed.  Same stream, ownership and error rules as fl_attn_fwd.                     */
+ * Covered: every descriptor fl_attn_fwd takes for bf16 inputs (any score_mod with any mask, zero to two
+ * biases, both epilogues, the second stream; D, Dv in {32, 64, 128}).  Variants outside the compiled table
+ * of backward kernels are instantiated from the kernel templates on first use (hipRTC, a few seconds, once
+ * per process and variant).  The gradient of rms_weight is not computed.
+ * Same stream, ownership and error rules as fl_attn_fwd.                                  */
 fl_status fl_attn_bwd_ex(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v, const fl_tensor* out,
                          const fl_tensor* dout, const fl_tensor* lse, const fl_variant_desc* desc,
                          const fl_aux* aux, fl_tensor* dq, fl_tensor* dk, fl_tensor* dv,
