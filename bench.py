@@ -318,22 +318,25 @@ def time_custom(steps, warmup):
     i = np.arange(S, dtype=np.int64)[:, None]
     j = np.arange(S, dtype=np.int64)[None, :]
     cases = [
-        ("built-in ALiBi (descriptor)", None, None, 0, S * S),
-        ("ALiBi as an expression", "s - exp2f(-0.5f * (float)(h + 1)) * fabsf((float)(i - j))", None, 0, S * S),
+        ("built-in ALiBi (descriptor)", None, None, 0, S * S, False),
+        ("ALiBi as an expression", "s - exp2f(-0.5f * (float)(h + 1)) * fabsf((float)(i - j))", None, 0, S * S, False),
         ("bucketed relative bias, causal as an expression (every tile computed)", "s + 0.05f * (float)((i - j) % 7)", "j > i", 0,
-         int((j <= i).sum())),
+         int((j <= i).sum()), False),
+        ("bucketed relative bias, causal as an expression, tile classes from a pre-pass", "s + 0.05f * (float)((i - j) % 7)", "j > i", 0,
+         int((j <= i).sum()), True),
         ("bucketed relative bias, causal as base mask", "s + 0.05f * (float)((i - j) % 7)", None, fb.FL_MASK_CAUSAL,
-         int((j <= i).sum())),
+         int((j <= i).sum()), False),
         ("dilated window 768: base window + expression", None, "(i - j) % 3 != 0", fb.FL_MASK_WINDOW,
-         int(((j <= i) & ((i - j) % 3 == 0) & (i - j <= 768)).sum())),
+         int(((j <= i) & ((i - j) % 3 == 0) & (i - j <= 768)).sum()), False),
     ]
     res = []
-    for name, mod, mask, base, pairs in cases:
+    for name, mod, mask, base, pairs, skip in cases:
         t0 = time.perf_counter()
         var = None if (mod is None and mask is None) else fb.CustomVariant(mod, mask, d["D"], base_mask=base)
         compile_s = time.perf_counter() - t0
+        ws = torch.empty(max(var.skip_workspace_size(dw.tq, dw.tk), 16), dtype=torch.uint8, device="cuda:0") if skip else None
         call = (lambda: dw.run_checked(stream)) if var is None else \
-            (lambda: fb.check(var.forward(dw.tq, dw.tk, dw.tv, float(w.scale), dw.tout, dw.tlse, stream, window=768)))
+            (lambda: fb.check(var.forward(dw.tq, dw.tk, dw.tv, float(w.scale), dw.tout, dw.tlse, stream, window=768, workspace=ws)))
         for _ in range(warmup):
             call()
         torch.cuda.synchronize()
@@ -354,11 +357,13 @@ def time_custom(steps, warmup):
     dd = runner.upload(wd, out_dtype="same")
     ids = dd.keep[0]
     pairs = unmasked_pairs(wd)
-    for name, var in (("document mask (descriptor, tile skipper)", None),
-                      ("document mask as an expression over captured id arrays",
-                       fb.CustomVariant(None, "aux0[b * Sq + i] != aux1[b * Sk + j]", wd.dims["D"], aux=[ids, ids]))):
+    doc_var = fb.CustomVariant(None, "aux0[b * Sq + i] != aux1[b * Sk + j]", wd.dims["D"], aux=[ids, ids])
+    map_ws = torch.empty(max(doc_var.skip_workspace_size(dd.tq, dd.tk), 16), dtype=torch.uint8, device="cuda:0")
+    for name, var, ws in (("document mask (descriptor, tile skipper)", None, None),
+                          ("document mask as an expression over captured id arrays (every tile computed)", doc_var, None),
+                          ("document mask as an expression, tile classes from a pre-pass (fl_attn_fwd_custom_skip)", doc_var, map_ws)):
         call = (lambda: dd.run_checked(stream)) if var is None else \
-            (lambda: fb.check(var.forward(dd.tq, dd.tk, dd.tv, float(wd.scale), dd.tout, dd.tlse, stream)))
+            (lambda: fb.check(var.forward(dd.tq, dd.tk, dd.tv, float(wd.scale), dd.tout, dd.tlse, stream, workspace=ws)))
         for _ in range(warmup):
             call()
         torch.cuda.synchronize()

@@ -364,6 +364,22 @@ fl_status fl_attn_fwd_custom_aux(fl_custom_variant* variant, const fl_tensor* q,
                                  float scale, int32_t window, int32_t prefix_len, const void* const* aux_ptrs,
                                  fl_tensor* out, fl_tensor* lse, void* stream);
 
+/* fl_attn_fwd_custom_aux with tile skipping for the mask expression (the block sparsity that the mask_mod of
+ * Sec. 2.2 allows; Sec. 4.3 notes that the paper's own kernels evaluate every block).  A pre-pass, compiled with the
+ * variant, evaluates the whole mask (base_mask and mask_expr) once per score and writes one class byte per
+ * (32 query rows, 64 keys) into the workspace: nothing visible / some / all; the attention kernel then passes over
+ * tiles with nothing visible to its workgroup and does not evaluate the mask on tiles that are all visible.  Same
+ * results as fl_attn_fwd_custom_aux.  The pre-pass runs in every call (the arrays an expression reads may have
+ * changed); it is per batch element unless the expression reads g or h, then per (b, g, h).
+ *   workspace   DEVICE, fl_custom_skip_workspace_size bytes, 16-byte aligned; contents undefined afterwards
+ * A variant without a mask expression needs no workspace and behaves like fl_attn_fwd_custom_aux.  */
+fl_status fl_attn_fwd_custom_skip(fl_custom_variant* variant, const fl_tensor* q, const fl_tensor* k, const fl_tensor* v,
+                                  float scale, int32_t window, int32_t prefix_len, const void* const* aux_ptrs,
+                                  void* workspace, size_t workspace_bytes, fl_tensor* out, fl_tensor* lse, void* stream);
+
+/* Bytes of workspace that fl_attn_fwd_custom_skip needs for these shapes (0 without a mask expression). */
+size_t fl_custom_skip_workspace_size(fl_custom_variant* variant, const fl_tensor* q, const fl_tensor* k);
+
 /* Unloads and frees a compiled variant (no launch of it may be in flight). */
 void fl_release_variant(fl_custom_variant* variant);
 

@@ -115,6 +115,11 @@ def lib() -> C.CDLL:
         L.fl_attn_fwd_custom_aux.restype = C.c_int
         L.fl_attn_fwd_custom_aux.argtypes = [C.c_void_p, TP, TP, TP, C.c_float, C.c_int32, C.c_int32,
                                              C.POINTER(C.c_void_p), TP, TP, C.c_void_p]
+        L.fl_attn_fwd_custom_skip.restype = C.c_int
+        L.fl_attn_fwd_custom_skip.argtypes = [C.c_void_p, TP, TP, TP, C.c_float, C.c_int32, C.c_int32,
+                                              C.POINTER(C.c_void_p), C.c_void_p, C.c_size_t, TP, TP, C.c_void_p]
+        L.fl_custom_skip_workspace_size.restype = C.c_size_t
+        L.fl_custom_skip_workspace_size.argtypes = [C.c_void_p, TP, TP]
         L.fl_release_variant.restype = None
         L.fl_release_variant.argtypes = [C.c_void_p]
         L.fl_variant_supported.restype = C.c_int
@@ -132,7 +137,7 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ["fl_attn_fwd", "fl_attn_fwd_noalloc", "fl_attn_fwd_workspace_size", "fl_attn_bwd", "fl_attn_bwd_workspace_size", "fl_attn_bwd_ex", "fl_attn_bwd_ex_workspace_size",
-           "fl_bwd_supported", "fl_attn_decode", "fl_attn_decode_workspace_size", "fl_attn_prefill_paged", "fl_attn_prefill_paged_workspace_size", "fl_compile_variant", "fl_attn_fwd_custom", "fl_compile_variant_aux", "fl_attn_fwd_custom_aux",
+           "fl_bwd_supported", "fl_attn_decode", "fl_attn_decode_workspace_size", "fl_attn_prefill_paged", "fl_attn_prefill_paged_workspace_size", "fl_compile_variant", "fl_attn_fwd_custom", "fl_compile_variant_aux", "fl_attn_fwd_custom_aux", "fl_attn_fwd_custom_skip", "fl_custom_skip_workspace_size",
            "fl_release_variant", "fl_variant_supported", "fl_strerror",
            "fl_last_error_detail", "fl_set_tuning", "fl_version"]
 
@@ -312,6 +317,20 @@ def fl_attn_fwd_custom_aux(handle, q: fl_tensor, k: fl_tensor, v: fl_tensor, sca
                                         _ref(out), _ref(lse), C.c_void_p(stream))
 
 
+def fl_attn_fwd_custom_skip(handle, q: fl_tensor, k: fl_tensor, v: fl_tensor, scale: float, aux, workspace, out: fl_tensor,
+                            lse: Optional[fl_tensor] = None, stream: int = 0, window: int = 0, prefix_len: int = 0) -> int:
+    """fl_attn_fwd_custom_aux with the tile-class pre-pass; workspace: a uint8 device tensor (or None).  Returns the status."""
+    ptrs = (C.c_void_p * 4)(*([(None if a is None else a.data_ptr()) for a in aux] + [None] * (4 - len(aux))))
+    ws_ptr = None if workspace is None else workspace.data_ptr()
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    return lib().fl_attn_fwd_custom_skip(handle, _ref(q), _ref(k), _ref(v), C.c_float(scale), window, prefix_len, ptrs,
+                                         C.c_void_p(ws_ptr), C.c_size_t(ws_bytes), _ref(out), _ref(lse), C.c_void_p(stream))
+
+
+def fl_custom_skip_workspace_size(handle, q: fl_tensor, k: fl_tensor) -> int:
+    return lib().fl_custom_skip_workspace_size(handle, _ref(q), _ref(k))
+
+
 def fl_release_variant(handle) -> None:
     lib().fl_release_variant(handle)
 
@@ -330,10 +349,17 @@ class CustomVariant:
         self.handle = h
 
     def forward(self, q: fl_tensor, k: fl_tensor, v: fl_tensor, scale: float, out: fl_tensor,
-                lse: Optional[fl_tensor] = None, stream: int = 0, window: int = 0, prefix_len: int = 0) -> int:
+                lse: Optional[fl_tensor] = None, stream: int = 0, window: int = 0, prefix_len: int = 0,
+                workspace=None) -> int:
+        """workspace (a uint8 device tensor of skip_workspace_size bytes): run with the tile-class pre-pass."""
+        if workspace is not None:
+            return fl_attn_fwd_custom_skip(self.handle, q, k, v, scale, self.aux, workspace, out, lse, stream, window, prefix_len)
         if self.aux:
             return fl_attn_fwd_custom_aux(self.handle, q, k, v, scale, self.aux, out, lse, stream, window, prefix_len)
         return fl_attn_fwd_custom(self.handle, q, k, v, scale, out, lse, stream, window, prefix_len)
+
+    def skip_workspace_size(self, q: fl_tensor, k: fl_tensor) -> int:
+        return fl_custom_skip_workspace_size(self.handle, q, k)
 
     def release(self) -> None:
         if self.handle is not None and self.handle.value:

@@ -800,63 +800,100 @@ fwd_bf16_kernel(const FwdParams call) {
       }
   }
   const int2* ksum = (MASK & kMaskDoc) ? p.kv_sum + (int64_t)b * nks : nullptr;
+  // A mask given as an expression can come with a map of tile classes, written by block_map_kernel below: one byte per
+  // (32-row query block, BN-key tile) -- 0 nothing visible, 1 some, 2 all -- stored [problem][tile][query block] so that
+  // the blocks of a workgroup are bytes of one aligned 8-byte word.  Without a map every tile counts as "some".
+  constexpr bool kMapped = (MASK & kMaskCustom) != 0;
+  static_assert(!kMapped || (RB == 1 && !C::DIFF && C::NROWG <= 8), "tile-class bytes: one per wave, at most eight per workgroup");
+  const bool mapped = kMapped && p.block_map != nullptr;
+  const unsigned char* mrow = nullptr;             // the word of this workgroup's query blocks in tile 0
+  int map_shift = 0;
+  if constexpr (kMapped) {
+    if (mapped) {
+      const int64_t prob = p.map_per_head ? ((int64_t)b * p.G + g) * p.H + h : b;
+      const int qb0 = i0 / 32;
+      mrow = p.block_map + prob * p.map_nkt * p.map_nqb8 + (qb0 & ~7);
+      map_shift = (qb0 & 7) * 8;
+    }
+  }
+  // the class bytes of this workgroup's query blocks, byte n = wave n's block
+  auto my_classes = [&](int2 ks) __attribute__((always_inline)) -> unsigned long long {
+    const unsigned long long word = (unsigned long long)(uint32_t)ks.x | ((unsigned long long)(uint32_t)ks.y << 32);
+    constexpr unsigned long long keep = C::NROWG >= 8 ? ~0ull : ((1ull << (8 * (C::NROWG & 7))) - 1);
+    return (word >> map_shift) & keep;
+  };
 
-  auto tile_keys_lane = [&](int t) __attribute__((always_inline)) -> int2 {       // document-id range of the keys of tile t (t per lane)
-    int2 ks = ksum[min(t * NB, nks - 1)];
+  // What the skipper knows about tile t (t per lane): the document-id range of its keys, or its word of class bytes.
+  auto tile_keys_lane = [&](int t) __attribute__((always_inline)) -> int2 {
+    if constexpr (kMapped) {
+      if (!mapped) return make_int2(0x01010101, 0x01010101);
+      return *(const int2*)(mrow + (int64_t)min(t, p.map_nkt - 1) * p.map_nqb8);
+    } else {
+      int2 ks = ksum[min(t * NB, nks - 1)];
 #pragma unroll
-    for (int u = 1; u < NB; ++u)
-      if (t * NB + u < nks) {
-        const int2 x = ksum[t * NB + u];
-        ks.x = min(ks.x, x.x);
-        ks.y = max(ks.y, x.y);
-      }
-    return ks;
+      for (int u = 1; u < NB; ++u)
+        if (t * NB + u < nks) {
+          const int2 x = ksum[t * NB + u];
+          ks.x = min(ks.x, x.x);
+          ks.y = max(ks.y, x.y);
+        }
+      return ks;
+    }
   };
   // The same for a uniform t, waiting for the answer: set-up and the search after a run of hidden tiles only.
   auto tile_keys = [&](int t) __attribute__((always_inline)) -> int2 {
     const int2 ks = tile_keys_lane(t);
     return make_int2(__builtin_amdgcn_readfirstlane(ks.x), __builtin_amdgcn_readfirstlane(ks.y));
   };
-  // Inside the loop the range of the tile that the stream will most likely take next is fetched a whole step ahead, with
+  // Inside the loop the answer for the tile that the stream will most likely take next is fetched a whole step ahead, with
   // ordinary vector loads (every lane reads the same address).  Vector memory operations complete in order and every step
-  // of a kernel with a document mask ends with a wait for all of this wave's loads, so the answer has arrived by the time
-  // it is needed, without a wait of its own.  (Scalar loads cannot be left in flight across a step: they share a counter
-  // with the LDS reads, whose counted waits rely on in-order return.)
+  // of these kernels ends with a wait for all of this wave's loads, so the answer has arrived by the time it is needed,
+  // without a wait of its own.  (Scalar loads cannot be left in flight across a step: they share a counter with the LDS
+  // reads, whose counted waits rely on in-order return.)
   int2 kpre[NB];                                   // what those loads return
   int tpre = -1;                                   // the tile they belong to (uniform)
 #pragma unroll
   for (int u = 0; u < NB; ++u) kpre[u] = make_int2(0, 0);
   auto prefetch_keys = [&](int t) __attribute__((always_inline)) {
     tpre = t;
+    if constexpr (kMapped) {
+      kpre[0] = tile_keys_lane(t);
+    } else {
 #pragma unroll
-    for (int u = 0; u < NB; ++u) kpre[u] = ksum[min(t * NB + u, nks - 1)];
+      for (int u = 0; u < NB; ++u) kpre[u] = ksum[min(t * NB + u, nks - 1)];
+    }
   };
   auto fetched_keys = [&]() __attribute__((always_inline)) -> int2 {
     int2 ks = kpre[0];
+    if constexpr (!kMapped) {
 #pragma unroll
-    for (int u = 1; u < NB; ++u)
-      if (tpre * NB + u < nks) {
-        ks.x = min(ks.x, kpre[u].x);
-        ks.y = max(ks.y, kpre[u].y);
-      }
+      for (int u = 1; u < NB; ++u)
+        if (tpre * NB + u < nks) {
+          ks.x = min(ks.x, kpre[u].x);
+          ks.y = max(ks.y, kpre[u].y);
+        }
+    }
     return make_int2(__builtin_amdgcn_readfirstlane(ks.x), __builtin_amdgcn_readfirstlane(ks.y));
   };
-  // First tile at or after t with something visible to the workgroup (t_hi if none), and the document-id range of its keys.
+  // Is every score of tile t hidden from the workgroup's rows?  (t and ks may be per lane)
+  auto tile_hidden = [&](int t, int2 ks) __attribute__((always_inline)) -> bool {
+    if constexpr (kMapped) return my_classes(ks) == 0;
+    else return classify_block(MASK, pos0, pos_last, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg, ks) == kSkip;
+  };
+  // First tile at or after t with something visible to the workgroup (t_hi if none), and what the skipper knows about it.
   auto next_tile = [&](int t, int2& ks) __attribute__((always_inline)) -> int {   // uniform over the workgroup
     ks = make_int2(0, 0);
-    if constexpr ((MASK & kMaskDoc) != 0) {
+    if constexpr ((MASK & kMaskDoc) != 0 || kMapped) {
       if (t < t_hi) {
         ks = t == tpre ? fetched_keys() : tile_keys(t);
         // the usual case first: tile t itself has something visible (one uniform check)
-        if (classify_block(MASK, pos0, pos_last, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg, ks) == kSkip) {
+        if (tile_hidden(t, ks)) {
           // a run of hidden tiles (the other documents of a long sequence): 64 tiles per round, one per lane
           ++t;
           while (t < t_hi) {
             const int tt = t + w.lane;
             bool keep = false;
-            if (tt < t_hi)
-              keep = classify_block(MASK, pos0, pos_last, tt * BN, tt * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg,
-                                    tile_keys_lane(tt)) != kSkip;
+            if (tt < t_hi) keep = !tile_hidden(tt, tile_keys_lane(tt));
             const unsigned long long found = __builtin_amdgcn_ballot_w64(keep);
             if (found != 0) {
               t += __builtin_ctzll(found);
@@ -895,7 +932,10 @@ fwd_bf16_kernel(const FwdParams call) {
   };
 
   auto wave_full = [&](int t, int2 ks) __attribute__((always_inline)) -> bool {   // is tile t fully visible to the wave?
-    if constexpr ((MASK & kMaskCustom) != 0) return false;   // an arbitrary predicate: evaluated on every score
+    if constexpr (kMapped) {                       // an arbitrary predicate: evaluated on every score unless the map says "all"
+      if (t >= t_hi) return false;
+      return ((my_classes(ks) >> (8 * (wave % C::NROWG))) & 0xffull) == 2;
+    }
     if constexpr ((MASK & kMaskDoc) != 0) return wave_class(t, ks) == kTileFull;
     else return t >= tf_lo && t < tf_hi;
   };
@@ -1221,6 +1261,44 @@ fwd_bf16_kernel(const FwdParams call) {
       p.lse[b * p.lse_sb + (int64_t)(C::DIFF ? 2 * g + stream : g) * p.lse_sg + h * p.lse_sh + i] = lse_v;
   }
   }  // pass
+}
+
+// Tile classes of a mask given as an expression (run-time compiled variants): one wave evaluates the whole predicate --
+// the variant's positional base mask and fl_user_mask -- on one (32-row query block, BN-key tile) and writes one byte:
+// 0 nothing visible, 1 some, 2 all (a tile that reaches past Sk is never "all": its tail has to be masked).  Rows past
+// Sq do not count; query blocks past the last one (the row of a tile is padded to a multiple of 8 blocks) get 0.
+// Launch: 256 threads, one wave per tile; blockIdx.x runs over [problem][query block][group of 4 tiles].
+template <uint32_t MASK, int BN>
+__global__ void __launch_bounds__(256) block_map_kernel(const FwdParams p, unsigned char* map) {
+  const int lane = threadIdx.x & 63;
+  const int groups = (p.map_nkt + 3) / 4;
+  const int64_t bid = blockIdx.x;
+  const int kt = (int)(bid % groups) * 4 + (int)(threadIdx.x >> 6);
+  const int qb = (int)((bid / groups) % p.map_nqb8);
+  const int prob = (int)(bid / ((int64_t)groups * p.map_nqb8));
+  if (kt >= p.map_nkt) return;                     // uniform over the wave
+  int b = prob, g = 0, h = 0;
+  if (p.map_per_head) {
+    h = prob % p.H;
+    g = (prob / p.H) % p.G;
+    b = prob / (p.H * p.G);
+  }
+  const int i = qb * 32 + (lane & 31);
+  const int j0 = kt * BN + (lane >> 5) * (BN / 2);
+  bool some_visible = false, some_hidden = false;
+  if (i < p.Sq) {
+    for (int u = 0; u < BN / 2; ++u) {
+      const int j = j0 + u;
+      bool hide = j >= p.Sk;
+      if (!hide)
+        hide = is_masked(MASK & (kMaskCausal | kMaskWindow | kMaskPrefix), i + p.q_off, j, p.window, p.prefix, 0, 0) ||
+               fl_user_mask(b, g, h, i + p.q_off, j, p);
+      some_visible = some_visible || !hide;
+      some_hidden = some_hidden || hide;
+    }
+  }
+  const bool vis = __builtin_amdgcn_ballot_w64(some_visible) != 0, hid = __builtin_amdgcn_ballot_w64(some_hidden) != 0;
+  if (lane == 0) map[((int64_t)prob * p.map_nkt + kt) * p.map_nqb8 + qb] = (unsigned char)(vis ? (hid ? 1 : 2) : 0);
 }
 
 }  // namespace fl

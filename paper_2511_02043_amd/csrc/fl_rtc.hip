@@ -30,11 +30,15 @@ struct fl_custom_variant {
   int waves = 4;                   // waves per workgroup of the instantiated kernel shape
   int aux_dtype[4] = {0, 0, 0, 0}; // element types of the arrays the expressions read (0: not used)
   unsigned mask = 0;               // mask bits the kernel was instantiated with
+  bool has_mask_expr = false;      // a mask expression was given (a tile-class map can be built for it)
+  bool per_head = false;           // ... and it reads g or h: the map is per (b, g, h), else per b
   std::vector<char> code;          // the compiled code object
   std::string kernel_name;         // lowered name of the instantiated kernel
+  std::string map_kernel_name;     // lowered name of the tile-class pre-pass (variants with a mask expression)
   std::mutex mu;
   hipModule_t module[64] = {};     // loaded lazily, once per device
   hipFunction_t func[64] = {};
+  hipFunction_t map_func[64] = {};
 };
 
 namespace {
@@ -43,6 +47,15 @@ namespace {
 // waves per workgroup at head dim 128 (the shape the compiled causal / plain kernels default to), four at 64.
 constexpr int kBN = 64;
 constexpr int waves_for(int D) { return D == 128 ? 8 : 4; }
+
+// Does the expression use the identifier `name` (as a whole word)?
+bool mentions(const char* e, const char* name) {
+  const size_t n = strlen(name);
+  auto word = [](char c) { return (c >= 'a' && c <= 'z') || (c >= 'A' && c <= 'Z') || (c >= '0' && c <= '9') || c == '_'; };
+  for (const char* c = e; *c; ++c)
+    if (strncmp(c, name, n) == 0 && (c == e || !word(c[-1])) && !word(c[n])) return true;
+  return false;
+}
 
 bool expression_ok(const char* e) {
   // one C expression: no statement separators, braces, preprocessor lines or string literals
@@ -287,17 +300,29 @@ fl_status fl_compile_variant_aux(const char* score_mod_expr, const char* mask_ex
   src += "); }\ntemplate __global__ void ";
   src += inst;
   src += "(const fl::FwdParams);\n";
+  std::vector<std::string> insts = {inst};
+  if (mask_expr != nullptr) {                      // the pre-pass that classifies tiles under this mask
+    char minst[128];
+    snprintf(minst, sizeof(minst), "fl::block_map_kernel<%uu, %d>", mask, kBN);
+    src += std::string("template __global__ void ") + minst + "(const fl::FwdParams, unsigned char*);\n";
+    insts.push_back(minst);
+  }
 
   fl_custom_variant* v = new fl_custom_variant;
   v->D = D;
   v->waves = waves_for(D);
   for (int n = 0; n < 4; ++n) v->aux_dtype[n] = adt[n];
   v->mask = mask;
-  const fl_status st = compile_instance(src, inst, "expression does not compile", &v->code, &v->kernel_name);
+  v->has_mask_expr = mask_expr != nullptr;
+  v->per_head = mask_expr != nullptr && (mentions(mask_expr, "h") || mentions(mask_expr, "g"));
+  std::vector<std::string> names;
+  const fl_status st = compile_program(src, insts, "expression does not compile", &v->code, &names);
   if (st != FL_OK) {
     delete v;
     return st;
   }
+  v->kernel_name = names[0];
+  if (names.size() > 1) v->map_kernel_name = names[1];
   *handle = v;
   return FL_OK;
 }
@@ -314,9 +339,37 @@ fl_status fl_attn_fwd_custom(fl_custom_variant* v, const fl_tensor* q, const fl_
   return fl_attn_fwd_custom_aux(v, q, k, vv, scale, window, prefix_len, nullptr, out, lse, stream_v);
 }
 
+// Bytes of the tile-class map of a call: one byte per (32-row query block, 64-key tile), rows of a tile padded to 8 blocks.
+static size_t block_map_bytes(const fl_custom_variant* v, int64_t B, int64_t G, int64_t H, int64_t Sq, int64_t Sk) {
+  const int64_t nqb8 = ((Sq + 31) / 32 + 7) / 8 * 8, nkt = (Sk + kBN - 1) / kBN;
+  return (size_t)((v->per_head ? B * G * H : B) * nkt * nqb8);
+}
+
+size_t fl_custom_skip_workspace_size(fl_custom_variant* v, const fl_tensor* q, const fl_tensor* k) {
+  if (v == nullptr || q == nullptr || k == nullptr || !v->has_mask_expr) return 0;
+  if (q->size[0] < 0 || q->size[1] < 0 || q->size[2] < 0 || q->size[3] < 0 || k->size[3] < 0) return 0;
+  return block_map_bytes(v, q->size[0], q->size[1], q->size[2], q->size[3], k->size[3]);
+}
+
+static fl_status custom_forward(fl_custom_variant* v, const fl_tensor* q, const fl_tensor* k, const fl_tensor* vv, float scale,
+                                int32_t window, int32_t prefix_len, const void* const* aux_ptrs, bool skip, void* workspace,
+                                size_t workspace_bytes, fl_tensor* out, fl_tensor* lse, void* stream_v);
+
 fl_status fl_attn_fwd_custom_aux(fl_custom_variant* v, const fl_tensor* q, const fl_tensor* k, const fl_tensor* vv, float scale,
                                  int32_t window, int32_t prefix_len, const void* const* aux_ptrs, fl_tensor* out, fl_tensor* lse,
                                  void* stream_v) {
+  return custom_forward(v, q, k, vv, scale, window, prefix_len, aux_ptrs, false, nullptr, 0, out, lse, stream_v);
+}
+
+fl_status fl_attn_fwd_custom_skip(fl_custom_variant* v, const fl_tensor* q, const fl_tensor* k, const fl_tensor* vv, float scale,
+                                  int32_t window, int32_t prefix_len, const void* const* aux_ptrs, void* workspace,
+                                  size_t workspace_bytes, fl_tensor* out, fl_tensor* lse, void* stream_v) {
+  return custom_forward(v, q, k, vv, scale, window, prefix_len, aux_ptrs, true, workspace, workspace_bytes, out, lse, stream_v);
+}
+
+static fl_status custom_forward(fl_custom_variant* v, const fl_tensor* q, const fl_tensor* k, const fl_tensor* vv, float scale,
+                                int32_t window, int32_t prefix_len, const void* const* aux_ptrs, bool skip, void* workspace,
+                                size_t workspace_bytes, fl_tensor* out, fl_tensor* lse, void* stream_v) {
   fl::host::clear_detail();
   if (v == nullptr || q == nullptr || k == nullptr || vv == nullptr || out == nullptr)
     return fl::host::fail(FL_ERR_NULL, "handle, q, k, v or out is NULL");
@@ -361,6 +414,9 @@ fl_status fl_attn_fwd_custom_aux(fl_custom_variant* v, const fl_tensor* q, const
         return fl::host::fail(FL_ERR_LAUNCH, "hipModuleLoadData: %s", hipGetErrorString(e));
       if ((e = hipModuleGetFunction(&v->func[dev], v->module[dev], v->kernel_name.c_str())) != hipSuccess)
         return fl::host::fail(FL_ERR_LAUNCH, "hipModuleGetFunction(%s): %s", v->kernel_name.c_str(), hipGetErrorString(e));
+      if (!v->map_kernel_name.empty() &&
+          (e = hipModuleGetFunction(&v->map_func[dev], v->module[dev], v->map_kernel_name.c_str())) != hipSuccess)
+        return fl::host::fail(FL_ERR_LAUNCH, "hipModuleGetFunction(%s): %s", v->map_kernel_name.c_str(), hipGetErrorString(e));
     }
   }
 
@@ -393,6 +449,24 @@ fl_status fl_attn_fwd_custom_aux(fl_custom_variant* v, const fl_tensor* q, const
   p.pair = tri && nbh * ((p.n_qtiles + 1) / 2) >= 512;
   const int64_t nblocks = nbh * (p.pair ? (p.n_qtiles + 1) / 2 : p.n_qtiles);
   if (nblocks > 0x7fffffffLL) return fl::host::fail(FL_ERR_SHAPE, "too many workgroups");
+  if (skip && v->has_mask_expr) {
+    // the pre-pass: the mask once per score, one class byte per (32-row block, 64-key tile); the kernel then passes over
+    // tiles with nothing visible and skips the per-score mask on tiles where everything is
+    const size_t need = block_map_bytes(v, B, G, H, Sq, Sk);
+    if (workspace == nullptr || workspace_bytes < need)
+      return fl::host::fail(FL_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", need, workspace ? workspace_bytes : (size_t)0);
+    if (((uintptr_t)workspace) % 16 != 0) return fl::host::fail(FL_ERR_ALIGN, "workspace not 16-byte aligned");
+    p.block_map = (const unsigned char*)workspace;
+    p.map_nqb8 = (int)(((Sq + 31) / 32 + 7) / 8 * 8);
+    p.map_nkt = (int)((Sk + kBN - 1) / kBN);
+    p.map_per_head = v->per_head ? 1 : 0;
+    const int64_t mblocks = (v->per_head ? nbh : B) * p.map_nqb8 * ((p.map_nkt + 3) / 4);
+    if (mblocks > 0x7fffffffLL) return fl::host::fail(FL_ERR_SHAPE, "too many tiles to classify");
+    unsigned char* map = (unsigned char*)workspace;
+    void* margs[] = {&p, &map};
+    e = hipModuleLaunchKernel(v->map_func[dev], (unsigned)mblocks, 1, 1, 256, 1, 1, 0, (hipStream_t)stream_v, margs, nullptr);
+    if (e != hipSuccess) return fl::host::fail(FL_ERR_LAUNCH, "tile-class pre-pass launch: %s", hipGetErrorString(e));
+  }
   void* args[] = {&p};
   e = hipModuleLaunchKernel(v->func[dev], (unsigned)nblocks, 1, 1, (unsigned)v->waves * 64, 1, 1, (unsigned)p.lds_bytes, (hipStream_t)stream_v, args, nullptr);
   if (e != hipSuccess) return fl::host::fail(FL_ERR_LAUNCH, "custom variant launch: %s", hipGetErrorString(e));

@@ -159,3 +159,86 @@ def test_expressions_that_capture_tensors(D):
     assert float((dd.out - dw.out).abs().max()) <= 1e-2
     # a variant that reads an array refuses a call without it
     assert fb.fl_attn_fwd_custom(var2.handle, dw.tq, dw.tk, dw.tv, float(w.scale), dw.tout, dw.tlse) == fb.FL_ERR_AUX_MISSING
+
+
+# --- tile skipping for mask expressions (fl_attn_fwd_custom_skip) ---------------------------------------------------
+
+def run_both_ways(var, dw, scale, **kw):
+    """The variant without and with the tile-class pre-pass; returns (out, lse) of both as numpy arrays."""
+    import torch
+    res = []
+    need = var.skip_workspace_size(dw.tq, dw.tk)
+    for ws in (None, torch.empty(max(need, 16), dtype=torch.uint8, device="cuda:0")):
+        dw.out.fill_(float("nan"))
+        dw.lse.fill_(float("nan"))
+        fb.check(var.forward(dw.tq, dw.tk, dw.tv, scale, dw.tout, dw.tlse, workspace=ws, **kw))
+        torch.cuda.synchronize()
+        res.append((dw.out.cpu().numpy().copy(), dw.lse.cpu().numpy()[..., 0].copy()))
+    return res, need
+
+
+@pytest.mark.parametrize("name", ["dilated_causal_window", "head_dependent_decay_and_checker", "softcap_then_alibi"])
+@pytest.mark.parametrize("D", [64, 128])
+def test_tile_skipping_changes_nothing(name, D):
+    """Tiles the pre-pass classifies as hidden contribute exact zeros and tiles classified as fully visible lose only a
+    mask evaluation that hid nothing, so the result is bit-equal to the run that evaluates the mask everywhere -- and
+    within tolerance of the oracle.  Ragged sizes (Sq and Sk multiples of neither 32 nor 64), a mask that reads h."""
+    c_mod, c_mask, np_mod, np_mask = CASES[name]
+    w = inputs.causal_bf16(B=2, H=4, Hkv=2, S=333, Sk=715, D=D, causal=False, salt=5)
+    var = fb.CustomVariant(c_mod, c_mask, D)
+    dw = runner.upload(w, out_dtype="f32")
+    (plain, skip), need = run_both_ways(var, dw, float(w.scale))
+    nqb8, nkt = ((333 + 31) // 32 + 7) // 8 * 8, (715 + 63) // 64
+    assert need == (2 * 4 if name.startswith("head") else 2) * nkt * nqb8       # per (b, g, h) only when the mask reads h
+    assert np.array_equal(plain[0], skip[0]) and np.array_equal(plain[1], skip[1])
+    ref, ref_lse = ao.attention_custom(w.q, w.k, w.v, scale=w.scale, score_mod=np_mod, mask=np_mask)
+    dead = np.isneginf(ref_lse)
+    assert np.array_equal(np.isneginf(skip[1]), dead)
+    assert float(np.max(np.abs(skip[0] - ref))) <= 1e-2
+    assert float(np.max(np.abs(skip[1][~dead] - ref_lse[~dead]))) <= 1e-3
+    var.release()
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_document_mask_expression_with_tile_skipping(D):
+    """The document mask of Sec. 4.1 as an expression over captured id arrays, on a causal base mask, long enough that
+    most tiles are hidden (runs of hidden tiles between a row's document and the diagonal do not occur under causal +
+    document, so a second variant without the causal base covers those runs)."""
+    import torch
+    B, H, S = 2, 4, 2100
+    w = inputs.causal_bf16(B=B, H=H, Hkv=2, S=S, D=D, causal=False, salt=11)
+    ids = inputs.doc_ids(B, S, seed=5, lo=100, hi=400)
+    t_ids = torch.from_numpy(ids).to("cuda:0")
+    dw = runner.upload(w, out_dtype="f32")
+    for base, np_mask in ((fb.FL_MASK_CAUSAL, lambda b, g, h, i, j: (j > i) | (ids[b][:, None] != ids[b][None, :])),
+                          (0, lambda b, g, h, i, j: (ids[b][:, None] != ids[b][None, :]) & ((i - j) % 5 != 0))):
+        expr = "aux0[b * Sq + i] != aux1[b * Sk + j]" + ("" if base else " && (i - j) % 5 != 0")
+        var = fb.CustomVariant(None, expr, D, base_mask=base, aux=[t_ids, t_ids])
+        (plain, skip), need = run_both_ways(var, dw, float(w.scale))
+        assert need == B * ((S + 63) // 64) * (((S + 31) // 32 + 7) // 8 * 8)        # the expression reads neither g nor h
+        assert np.array_equal(plain[0], skip[0]) and np.array_equal(plain[1], skip[1])
+        ref, ref_lse = ao.attention_custom(w.q, w.k, w.v, scale=w.scale, score_mod=None, mask=np_mask)
+        assert float(np.max(np.abs(skip[0] - ref))) <= 1e-2
+        assert float(np.max(np.abs(skip[1] - ref_lse))) <= 1e-3
+        var.release()
+
+
+def test_tile_skipping_with_a_window_base_mask_and_errors():
+    import torch
+    w = inputs.causal_bf16(B=1, H=8, Hkv=8, S=900, D=64, causal=False, salt=12)
+    dw = runner.upload(w, out_dtype="f32")
+    var = fb.CustomVariant(None, "(i >> 6) % 2 == 1 && (j >> 6) % 2 == 0", 64, base_mask=fb.FL_MASK_WINDOW)
+    (plain, skip), need = run_both_ways(var, dw, float(w.scale), window=300)
+    assert np.array_equal(plain[0], skip[0]) and np.array_equal(plain[1], skip[1])
+    ref, ref_lse = ao.attention_custom(w.q, w.k, w.v, scale=w.scale, score_mod=None,
+                                       mask=lambda b, g, h, i, j: (j > i) | (i - j > 300) | (((i >> 6) % 2 == 1) & ((j >> 6) % 2 == 0)))
+    assert float(np.max(np.abs(skip[0] - ref))) <= 1e-2
+    small = torch.empty(need - 8, dtype=torch.uint8, device="cuda:0")
+    assert var.forward(dw.tq, dw.tk, dw.tv, float(w.scale), dw.tout, dw.tlse, workspace=small, window=300) == fb.FL_ERR_WORKSPACE
+    var.release()
+    # a variant without a mask expression has nothing to classify: no workspace needed, same call
+    mod_only = fb.CustomVariant("s * 0.5f", None, 64)
+    assert mod_only.skip_workspace_size(dw.tq, dw.tk) == 0
+    assert fb.fl_attn_fwd_custom_skip(mod_only.handle, dw.tq, dw.tk, dw.tv, float(w.scale), [], None, dw.tout, dw.tlse) == fb.FL_OK
+    torch.cuda.synchronize()
+    mod_only.release()
