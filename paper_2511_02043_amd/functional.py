@@ -313,3 +313,54 @@ def decode_attention(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tens
     fb.check(fb.fl_attn_decode(tq, tk, tv, kv, desc, aux, tout, tlse, torch.cuda.current_stream(q.device).cuda_stream))
     out = out[:, 0, :, 0, :]
     return (out, lse[:, 0, :, 0, 0]) if return_lse else out
+
+
+def paged_prefill_attention(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, seq_lens: torch.Tensor,
+                            block_table: Optional[torch.Tensor] = None, *, max_seq_len: Optional[int] = None,
+                            scale: Optional[float] = None, window: Optional[int] = None, softcap: Optional[float] = None,
+                            alibi_slopes: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                            return_lse: bool = False):
+    """A chunk of query rows per sequence against the paged cache (fl_attn_prefill_paged): the last Sq tokens of every
+    sequence, whose keys and values are already cached, attend causally to that sequence's cached keys.
+
+    q [B, H, Sq, D] bf16; caches, seq_lens, block_table, max_seq_len as for decode_attention().  workspace: a uint8
+    tensor of at least prefill workspace bytes (two dense copies of the cached rows) to reuse across calls;
+    allocated here when omitted.  Returns out [B, H, Sq, D] bf16 (and lse [B, H, Sq] float32 with return_lse);
+    rows at negative positions (a sequence shorter than the chunk) are zero.  Not differentiable."""
+    if not q.is_cuda or q.dtype != torch.bfloat16 or q.dim() != 4:
+        raise ValueError("paged_prefill_attention() takes a bf16 CUDA q of shape [B, H, Sq, D]")
+    B, H, Sq, D = q.shape
+    page_size = k_cache.shape[1]
+    _check_aux("seq_lens", seq_lens, torch.int32, (B,), q.device)
+    if block_table is not None:
+        if block_table.dim() != 2:
+            raise ValueError("block_table must be [B, max_pages]")
+        _check_aux("block_table", block_table, torch.int32, (B, block_table.shape[1]), q.device, contiguous=False,
+                   inner_unit=True)
+    _check_aux("alibi_slopes", alibi_slopes, torch.float32, (H,), q.device)
+    if max_seq_len is None:
+        max_seq_len = (block_table.shape[1] if block_table is not None else 1) * page_size
+    if scale is None:
+        scale = D ** -0.5
+    if softcap is not None and alibi_slopes is not None:
+        raise ValueError("one score_mod at a time")
+    mod = fb.FL_MOD_SOFTCAP if softcap is not None else (fb.FL_MOD_ALIBI if alibi_slopes is not None else fb.FL_MOD_NONE)
+    desc = fb.variant_desc(scale=float(scale), score_mod=mod, softcap=float(softcap or 0.0),
+                           mask=(fb.FL_MASK_WINDOW | fb.FL_MASK_CAUSAL) if window is not None else fb.FL_MASK_CAUSAL,
+                           window=int(window or 0))
+    q5 = q[:, None]
+    k5, v5 = k_cache.permute(0, 2, 1, 3)[:, None], v_cache.permute(0, 2, 1, 3)[:, None]    # [pages, 1, Hkv, page_size, D]
+    out = torch.empty((B, 1, H, Sq, D), dtype=torch.bfloat16, device=q.device)
+    lse = torch.empty((B, 1, H, Sq, 1), dtype=torch.float32, device=q.device) if return_lse else None
+    kv = fb.paged_kv(block_table=block_table, page_size=page_size, seq_lens=seq_lens, max_seq_len=int(max_seq_len))
+    tq, tk, tv, tout = (fb.tensor_desc(x) for x in (q5, k5, v5, out))
+    tlse = fb.tensor_desc(lse) if return_lse else None
+    need = max(fb.fl_attn_prefill_paged_workspace_size(tq, tk, kv), 16)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    elif workspace.numel() * workspace.element_size() < need:
+        raise ValueError(f"workspace holds {workspace.numel() * workspace.element_size()} bytes, {need} needed")
+    aux = fb.aux_desc(alibi_slopes=alibi_slopes, workspace=workspace)
+    fb.check(fb.fl_attn_prefill_paged(tq, tk, tv, kv, desc, aux, tout, tlse, torch.cuda.current_stream(q.device).cuda_stream))
+    out = out[:, 0]
+    return (out, lse[:, 0, :, :, 0]) if return_lse else out

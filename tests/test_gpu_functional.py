@@ -92,6 +92,30 @@ def test_decode_wrapper_matches_oracle():
         decode_attention(q, kc, vc, lens, table, workspace=torch.empty(8, dtype=torch.uint8, device=dev))
 
 
+def test_paged_prefill_wrapper_matches_oracle():
+    import torch
+    from oracle import decode_oracle as do
+    from paper_2511_02043_amd.functional import paged_prefill_attention
+    w = inputs.prefill_paged_bf16(H=8, Hkv=2, D=128, Sq=70, page_size=16, seq_lens=[30, 70, 600, 1025])
+    dev = "cuda:0"
+    q = torch.from_numpy(w.q).to(dev, torch.bfloat16)
+    kc = torch.from_numpy(w.k_cache).to(dev, torch.bfloat16)
+    vc = torch.from_numpy(w.v_cache).to(dev, torch.bfloat16)
+    table, lens = torch.from_numpy(w.block_table).to(dev), torch.from_numpy(w.seq_lens).to(dev)
+    ref, ref_lse = do.prefill_attention(w.q, w.k_cache, w.v_cache, w.block_table, w.seq_lens, scale=w.scale, softcap_value=3.0)
+    out, lse = paged_prefill_attention(q, kc, vc, lens, table, softcap=3.0, return_lse=True)
+    torch.cuda.synchronize()
+    got, got_lse = out.float().cpu().numpy(), lse.cpu().numpy()
+    dead = np.isneginf(ref_lse)
+    assert np.array_equal(np.isneginf(got_lse), dead) and dead[0, :, :40].all()      # the 30-token sequence: 40 rows before position 0
+    assert np.all(np.abs(got - ref) <= 1e-2 + 2.0 ** -8 * np.abs(ref))
+    assert np.max(np.abs(got_lse[~dead] - ref_lse[~dead])) <= 1e-3
+    with pytest.raises(ValueError):
+        paged_prefill_attention(q, kc, vc, lens.long(), table)
+    with pytest.raises(ValueError):
+        paged_prefill_attention(q, kc, vc, lens, table, workspace=torch.empty(8, dtype=torch.uint8, device=dev))
+
+
 def test_wrapper_refuses_arrays_the_abi_would_misread():
     """int64 document ids (torch's default integer type), sliced id views, slopes on the CPU and
     int64 lengths would be reinterpreted as int32 / float32 memory by the C ABI: the wrapper raises."""
