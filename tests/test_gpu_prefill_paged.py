@@ -60,6 +60,16 @@ def test_prefill_matches_oracle(name):
     compare(CASES[name](), name)
 
 
+@pytest.mark.parametrize("Sq", [1, 17, 128, 500])
+def test_chunks_against_a_long_cache(Sq):
+    """Chunks of 1, 17, 128 and 500 rows against 4k - 8k cached tokens per sequence (the serving shape of Sec. 4.1:
+    32 query heads on 8 kv heads would take the oracle minutes, so 8 on 2), every row checked."""
+    w = inputs.prefill_paged_bf16(H=8, Hkv=2, D=128, Sq=Sq, page_size=16, seq_lens=[4096, 5000, 8191], salt=20 + Sq)
+    compare(w, f"long_cache_q{Sq}")
+    w.window = 1000
+    compare(w, f"long_cache_q{Sq}_window")
+
+
 def test_prefill_variants():
     w = inputs.prefill_paged_bf16(H=8, Hkv=2, D=128, Sq=80, page_size=16, seq_lens=[5, 100, 700, 1500], salt=1)
     w.window = 255
