@@ -147,3 +147,52 @@ def test_noalloc_forward_replays_from_a_graph():
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(dw.out, ref) and torch.equal(dw.lse, ref_lse), rep
+
+
+def test_paged_prefill_replays_from_a_graph_while_sequences_grow():
+    """Chunked prefill in a serving loop: one captured fl_attn_prefill_paged call (page gather + forward kernel, lengths
+    read on the device) replayed as the sequences grow by a chunk per step, with new query rows each time."""
+    import torch
+    from oracle import decode_oracle as do
+    Sq = 48
+    final = np.array([4 * Sq, 3 * Sq + 5, Sq, 7], dtype=np.int32)          # the last one stays shorter than a chunk
+    w = inputs.prefill_paged_bf16(H=8, Hkv=2, D=128, Sq=Sq, page_size=16, seq_lens=final)
+    dd = runner.upload_prefill_paged(w)             # pages, table and max_seq_len sized for the final lengths
+    lens = dd.keep[1]
+    outs = (dd.out, dd.lse)
+    q_steps = [torch.randn(dd.q.shape, device="cuda:0", generator=torch.Generator(device="cuda:0").manual_seed(s)).to(torch.bfloat16)
+               for s in (1, 2)] + [dd.q.clone()]
+    steps = [np.maximum(final - 2 * Sq, 0).astype(np.int32), np.maximum(final - Sq, 0).astype(np.int32), final]
+
+    def eager(cur, qs):
+        lens.copy_(torch.from_numpy(cur))
+        dd.q.copy_(qs)
+        dd.run_checked()
+        torch.cuda.synchronize()
+        return [t.clone() for t in outs]
+
+    refs = [eager(cur, qs) for cur, qs in zip(steps, q_steps)]
+    ref_out, ref_lse = do.prefill_attention(w.q, w.k_cache, w.v_cache, w.block_table, final, scale=w.scale)
+    got_out, got_lse = refs[-1][0].float().cpu().numpy()[:, 0], refs[-1][1].cpu().numpy()[:, 0, :, :, 0]
+    dead = np.isneginf(ref_lse)
+    assert np.array_equal(np.isneginf(got_lse), dead)
+    assert np.max(np.abs(got_out - ref_out)) <= 1e-2 and np.max(np.abs(got_lse[~dead] - ref_lse[~dead])) <= 1e-3
+
+    lens.copy_(torch.from_numpy(steps[0]))
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        dd.run_checked(torch.cuda.current_stream().cuda_stream)
+        graph.capture_end()
+    torch.cuda.synchronize()
+    for rep, (cur, qs, ref) in enumerate(zip(steps, q_steps, refs)):
+        lens.copy_(torch.from_numpy(cur))           # eager work between the replays
+        dd.q.copy_(qs)
+        for t in outs:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, t, r in zip(("out", "lse"), outs, ref):
+            assert torch.equal(t, r), f"prefill replay {rep} differs in {name}"
