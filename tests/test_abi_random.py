@@ -79,3 +79,58 @@ def test_random_descriptors_never_crash_the_host():
     # the mutations reach every kind of outcome: a valid call ends in FL_ERR_LAUNCH here (no device), an empty one in FL_OK
     assert seen >= {fb.FL_OK, fb.FL_ERR_NULL, fb.FL_ERR_DTYPE, fb.FL_ERR_SHAPE, fb.FL_ERR_STRIDE, fb.FL_ERR_ALIGN,
                     fb.FL_ERR_UNSUPPORTED, fb.FL_ERR_AUX_MISSING, fb.FL_ERR_WORKSPACE, fb.FL_ERR_LAUNCH, fb.FL_ERR_DESC}, seen
+
+
+@pytest.mark.skipif(_gpu_present(), reason="fake pointers: host validation only, must not reach a GPU")
+def test_random_paged_calls_never_crash_the_host():
+    """The two entry points over a paged cache (one query row per sequence, a chunk of rows per sequence): a valid call
+    with one to three random fields of the tensors, the page description or the descriptor broken."""
+    rng = np.random.Generator(np.random.PCG64(20251102044))
+    seen = {"decode": set(), "prefill": set()}
+    for case in range(400):
+        B, H, Hkv, Sq, D, pages, page_size, max_len, stride = 3, 8, 2, 40, 128, 50, 16, 200, 13
+        kw = dict(scale=0.0884, score_mod=fb.FL_MOD_NONE, softcap=0.0, mask=fb.FL_MASK_CAUSAL, window=0)
+        muts = rng.choice(22, size=int(rng.integers(0, 4)), replace=False)
+        if 0 in muts: B = 0
+        if 1 in muts: Hkv = int(rng.choice([0, 3, 16]))
+        if 2 in muts: D = int(rng.choice([0, 8, 96, 256]))
+        if 3 in muts: page_size = int(rng.choice([0, 4, 12, 1 << 20]))
+        if 4 in muts: max_len = int(rng.choice([-1, 0, 1 << 30]))
+        if 5 in muts: stride = int(rng.choice([0, 1, -5]))
+        if 6 in muts: pages = int(rng.choice([0, 1, 1 << 33]))
+        if 7 in muts: kw["mask"] = int(rng.integers(0, 40))
+        if 8 in muts: kw["score_mod"] = int(rng.integers(1, 5))
+        if 9 in muts: kw["scale"] = float(rng.choice([0.0, float("inf")]))
+        if 10 in muts: Sq = int(rng.choice([0, 1, 1 << 31]))
+        q1, qc = _tensor(fb.FL_BF16, [B, 1, H, 1, D]), _tensor(fb.FL_BF16, [B, 1, H, Sq, D])
+        kc, vc = _tensor(fb.FL_BF16, [pages, 1, Hkv, page_size, D]), _tensor(fb.FL_BF16, [pages, 1, Hkv, page_size, D])
+        o1, oc = _tensor(fb.FL_BF16, [B, 1, H, 1, D]), _tensor(fb.FL_BF16, [B, 1, H, Sq, D])
+        l1, lc = _tensor(fb.FL_F32, [B, 1, H, 1, 1]), _tensor(fb.FL_F32, [B, 1, H, Sq, 1])
+        if 11 in muts: kc.ptr = 0
+        if 12 in muts: vc.stride[3] = int(rng.choice([-8, 3]))
+        if 13 in muts: q1.dtype = qc.dtype = fb.FL_F32
+        if 14 in muts: o1.dtype = oc.dtype = 9
+        if 15 in muts: l1.size[2] = lc.size[2] = H + 1
+        kv = fb.fl_paged_kv()
+        kv.struct_size = fb.C.sizeof(fb.fl_paged_kv)
+        kv.block_table, kv.seq_lens = 0x7f0000300000, 0x7f0000400000
+        kv.table_stride, kv.page_size, kv.max_seq_len = stride, page_size, max_len
+        if 16 in muts: kv.struct_size = 5
+        if 17 in muts: kv.block_table = 0
+        if 18 in muts: kv.seq_lens = 0
+        d = fb.variant_desc(**kw)
+        a = fb.fl_aux()
+        a.struct_size = fb.C.sizeof(fb.fl_aux)
+        a.workspace, a.workspace_bytes, a.alibi_slopes = 0x7f0000100000, 1 << 34, 0x7f0000200000
+        if 19 in muts: a.workspace_bytes = 64
+        if 20 in muts: a.workspace = 0x7f0000100004
+        aux = None if 21 in muts else a
+        for name, status in (("decode", fb.fl_attn_decode(q1, kc, vc, kv, d, aux, o1, l1)),
+                             ("prefill", fb.fl_attn_prefill_paged(qc, kc, vc, kv, d, aux, oc, lc))):
+            assert isinstance(status, int) and 0 <= status <= fb.FL_ERR_DESC, (name, status)
+            assert isinstance(fb.fl_last_error_detail(), str)
+            seen[name].add(status)
+        assert fb.fl_attn_decode_workspace_size(q1, kc, kv) >= 0 and fb.fl_attn_prefill_paged_workspace_size(qc, kc, kv) >= 0
+    for name in seen:
+        assert seen[name] >= {fb.FL_OK, fb.FL_ERR_NULL, fb.FL_ERR_DTYPE, fb.FL_ERR_SHAPE, fb.FL_ERR_UNSUPPORTED, fb.FL_ERR_AUX_MISSING,
+                              fb.FL_ERR_WORKSPACE, fb.FL_ERR_LAUNCH, fb.FL_ERR_DESC}, (name, seen[name])
