@@ -367,9 +367,10 @@ fl_status fl_attn_fwd_custom_aux(fl_custom_variant* variant, const fl_tensor* q,
 /* fl_attn_fwd_custom_aux with tile skipping for the mask expression (the block sparsity that the mask_mod of
  * Sec. 2.2 allows; Sec. 4.3 notes that the paper's own kernels evaluate every block).  A pre-pass, compiled with the
  * variant, evaluates the whole mask (base_mask and mask_expr) once per score and writes one class byte per
- * (32 query rows, 64 keys) into the workspace: nothing visible / some / all; the attention kernel then passes over
- * tiles with nothing visible to its workgroup and does not evaluate the mask on tiles that are all visible.  Same
- * results as fl_attn_fwd_custom_aux.  The pre-pass runs in every call (the arrays an expression reads may have
+ * (32 query rows, 64 keys) into the workspace: nothing visible / some / all, and (while Sq * Sk / 8 bytes per
+ * problem stay under 1 GiB in all) one bit per score; the attention kernel then passes over tiles with nothing
+ * visible to its workgroup, does not mask tiles that are all visible, and on the others applies the stored bits
+ * instead of evaluating the expression.  Same results as fl_attn_fwd_custom_aux.  The pre-pass runs in every call (the arrays an expression reads may have
  * changed); it is per batch element unless the expression reads g or h, then per (b, g, h).
  *   workspace   DEVICE, fl_custom_skip_workspace_size bytes, 16-byte aligned; contents undefined afterwards
  * A variant without a mask expression needs no workspace and behaves like fl_attn_fwd_custom_aux.  */

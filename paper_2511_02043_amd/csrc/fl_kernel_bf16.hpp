@@ -389,8 +389,22 @@ struct Wave {
   // and the end of the key range are therefore two per-lane bounds on c: hidden iff c > d_hi
   // (causal: j > i; PrefixLM: j > max(i, prefix - 1); always: j > Sk - 1) or c < d_lo (window:
   // i - j > window) -- one or two compares per score instead of evaluating every mask on (i, j).
-  __device__ __forceinline__ void mask(Scores& sc, int j0) const {
+  // `word` (mask expressions with a precomputed map only): bit 16*nb + r set = this lane's score register r of key block
+  // nb is hidden; then nothing is evaluated here.
+  __device__ __forceinline__ void mask(Scores& sc, int j0, uint32_t word = 0) const {
     constexpr uint32_t MASK = C::MASK;
+    if constexpr ((MASK & kMaskCustom) != 0) {
+      if (p.block_bits != nullptr) {               // uniform
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              if ((word >> (16 * nb + r)) & 1u) sc[rb][nb][r] = -INFINITY;
+        return;
+      }
+    }
     const int jl = j0 + 4 * half;
     int d_hi[RB], d_lo[RB];
 #pragma unroll
@@ -807,6 +821,7 @@ fwd_bf16_kernel(const FwdParams call) {
   static_assert(!kMapped || (RB == 1 && !C::DIFF && C::NROWG <= 8), "tile-class bytes: one per wave, at most eight per workgroup");
   const bool mapped = kMapped && p.block_map != nullptr;
   const unsigned char* mrow = nullptr;             // the word of this workgroup's query blocks in tile 0
+  const uint32_t* brow_bits = nullptr;             // this lane's word of hidden-score bits in tile 0 (if the map has them)
   int map_shift = 0;
   if constexpr (kMapped) {
     if (mapped) {
@@ -814,8 +829,16 @@ fwd_bf16_kernel(const FwdParams call) {
       const int qb0 = i0 / 32;
       mrow = p.block_map + prob * p.map_nkt * p.map_nqb8 + (qb0 & ~7);
       map_shift = (qb0 & 7) * 8;
+      if (p.block_bits != nullptr) brow_bits = p.block_bits + (prob * p.map_nkt * p.map_nqb8 + iw / 32) * 64 + lane;
     }
   }
+  // the lane's hidden-score bits of tile t: one coalesced dword per lane
+  auto tile_bits_lane = [&](int t) __attribute__((always_inline)) -> uint32_t {
+    if constexpr (kMapped) {
+      if (brow_bits != nullptr) return brow_bits[(int64_t)min(t, p.map_nkt - 1) * p.map_nqb8 * 64];
+    }
+    return 0u;
+  };
   // the class bytes of this workgroup's query blocks, byte n = wave n's block
   auto my_classes = [&](int2 ks) __attribute__((always_inline)) -> unsigned long long {
     const unsigned long long word = (unsigned long long)(uint32_t)ks.x | ((unsigned long long)(uint32_t)ks.y << 32);
@@ -851,6 +874,7 @@ fwd_bf16_kernel(const FwdParams call) {
   // without a wait of its own.  (Scalar loads cannot be left in flight across a step: they share a counter with the LDS
   // reads, whose counted waits rely on in-order return.)
   int2 kpre[NB];                                   // what those loads return
+  uint32_t bpre = 0;                               // ... and the lane's hidden-score bits of that tile (mapped expressions)
   int tpre = -1;                                   // the tile they belong to (uniform)
 #pragma unroll
   for (int u = 0; u < NB; ++u) kpre[u] = make_int2(0, 0);
@@ -858,6 +882,7 @@ fwd_bf16_kernel(const FwdParams call) {
     tpre = t;
     if constexpr (kMapped) {
       kpre[0] = tile_keys_lane(t);
+      bpre = tile_bits_lane(t);
     } else {
 #pragma unroll
       for (int u = 0; u < NB; ++u) kpre[u] = ksum[min(t * NB + u, nks - 1)];
@@ -881,10 +906,12 @@ fwd_bf16_kernel(const FwdParams call) {
     else return classify_block(MASK, pos0, pos_last, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg, ks) == kSkip;
   };
   // First tile at or after t with something visible to the workgroup (t_hi if none), and what the skipper knows about it.
-  auto next_tile = [&](int t, int2& ks) __attribute__((always_inline)) -> int {   // uniform over the workgroup
+  auto next_tile = [&](int t, int2& ks, uint32_t& bw) __attribute__((always_inline)) -> int {   // uniform over the workgroup
     ks = make_int2(0, 0);
+    bw = 0;
     if constexpr ((MASK & kMaskDoc) != 0 || kMapped) {
       if (t < t_hi) {
+        bw = t == tpre ? bpre : tile_bits_lane(t);
         ks = t == tpre ? fetched_keys() : tile_keys(t);
         // the usual case first: tile t itself has something visible (one uniform check)
         if (tile_hidden(t, ks)) {
@@ -902,7 +929,10 @@ fwd_bf16_kernel(const FwdParams call) {
             t += 64;
           }
           t = __builtin_amdgcn_readfirstlane(t < t_hi ? t : t_hi);
-          if (t < t_hi) ks = tile_keys(t);
+          if (t < t_hi) {
+            ks = tile_keys(t);
+            bw = tile_bits_lane(t);
+          }
         }
         if (t < t_hi) prefetch_keys(t + 1);
       }
@@ -1039,15 +1069,17 @@ fwd_bf16_kernel(const FwdParams call) {
     // whose K the current step streams into the rings (t_hi past the end of the list)
     constexpr int SPB = C::SPB, RING = C::RING, NTL = SPB + 2;
     int tl[NTL];
-    int2 tks[NTL];                                 // document-id ranges of those tiles' keys (document masks only)
-    tl[0] = next_tile(t_lo, tks[0]);
+    int2 tks[NTL];                                 // what the skipper knows about those tiles (document masks, mapped expressions)
+    uint32_t tbw[NTL];                             // this lane's hidden-score bits of those tiles (mapped expressions)
+    tl[0] = next_tile(t_lo, tks[0], tbw[0]);
     if (tl[0] < t_hi) {
-      auto after = [&](int t, int2& ks) __attribute__((always_inline)) {
+      auto after = [&](int t, int2& ks, uint32_t& bw) __attribute__((always_inline)) {
         ks = make_int2(0, 0);
-        return t < t_hi ? next_tile(t + 1, ks) : t_hi;
+        bw = 0;
+        return t < t_hi ? next_tile(t + 1, ks, bw) : t_hi;
       };
 #pragma unroll
-      for (int u = 1; u < NTL; ++u) tl[u] = after(tl[u - 1], tks[u]);
+      for (int u = 1; u < NTL; ++u) tl[u] = after(tl[u - 1], tks[u], tbw[u]);
       w.template bias_dma<0>(tl[0] * BN);
       if (tl[1] < t_hi) w.template bias_dma<1>(tl[1] * BN);
       // K of tiles tl[0 .. SPB] into slots 0 .. SPB, V of tiles tl[0 .. SPB - 1] into slots 0 .. SPB - 1
@@ -1108,7 +1140,7 @@ fwd_bf16_kernel(const FwdParams call) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) cur[rb][nb][r] = -INFINITY;
           } else {
-            w.mask(cur, t0 * BN);
+            w.mask(cur, t0 * BN, tbw[0]);
             w.rowmax(cur, mx);
             w.advance_max(mx);
           }
@@ -1149,8 +1181,9 @@ fwd_bf16_kernel(const FwdParams call) {
         for (int u = 0; u + 1 < NTL; ++u) {
           tl[u] = tl[u + 1];
           tks[u] = tks[u + 1];
+          tbw[u] = tbw[u + 1];
         }
-        tl[NTL - 1] = after(tl[NTL - 1], tks[NTL - 1]);
+        tl[NTL - 1] = after(tl[NTL - 1], tks[NTL - 1], tbw[NTL - 1]);
         full0 = fulln;
         if constexpr ((MASK & kMaskDoc) == 0) {    // consecutive tiles: advance the bases until the list ends
           if (tl[SPB] < t_hi) vb += vstep;
@@ -1267,9 +1300,12 @@ fwd_bf16_kernel(const FwdParams call) {
 // the variant's positional base mask and fl_user_mask -- on one (32-row query block, BN-key tile) and writes one byte:
 // 0 nothing visible, 1 some, 2 all (a tile that reaches past Sk is never "all": its tail has to be masked).  Rows past
 // Sq do not count; query blocks past the last one (the row of a tile is padded to a multiple of 8 blocks) get 0.
+// With `bits`, every lane also stores the word of its own 32 scores' hidden bits (64 words per block, in the attention
+// kernel's register order), so that the attention kernel applies the mask of a partly visible tile from one coalesced
+// load per lane instead of evaluating the expression again.
 // Launch: 256 threads, one wave per tile; blockIdx.x runs over [problem][query block][group of 4 tiles].
 template <uint32_t MASK, int BN>
-__global__ void __launch_bounds__(256) block_map_kernel(const FwdParams p, unsigned char* map) {
+__global__ void __launch_bounds__(256) block_map_kernel(const FwdParams p, unsigned char* map, uint32_t* bits) {
   const int lane = threadIdx.x & 63;
   const int groups = (p.map_nkt + 3) / 4;
   const int64_t bid = blockIdx.x;
@@ -1283,22 +1319,33 @@ __global__ void __launch_bounds__(256) block_map_kernel(const FwdParams p, unsig
     g = (prob / p.H) % p.G;
     b = prob / (p.H * p.G);
   }
+  // the scores of a lane in the attention kernel's register order: row = lane % 32 of the block, key block nb, register r
+  // -> key 32 nb + 8 (r / 4) + r % 4 + 4 (lane / 32) of the tile; bit 16 nb + r of the lane's word = hidden
   const int i = qb * 32 + (lane & 31);
-  const int j0 = kt * BN + (lane >> 5) * (BN / 2);
+  const int jl = kt * BN + 4 * (lane >> 5);
   bool some_visible = false, some_hidden = false;
+  uint32_t word = 0;
   if (i < p.Sq) {
-    for (int u = 0; u < BN / 2; ++u) {
-      const int j = j0 + u;
-      bool hide = j >= p.Sk;
-      if (!hide)
-        hide = is_masked(MASK & (kMaskCausal | kMaskWindow | kMaskPrefix), i + p.q_off, j, p.window, p.prefix, 0, 0) ||
-               fl_user_mask(b, g, h, i + p.q_off, j, p);
-      some_visible = some_visible || !hide;
-      some_hidden = some_hidden || hide;
-    }
+#pragma unroll
+    for (int nb = 0; nb < BN / 32; ++nb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int j = jl + 32 * nb + 8 * (r >> 2) + (r & 3);
+        bool hide = j >= p.Sk;
+        if (!hide)
+          hide = is_masked(MASK & (kMaskCausal | kMaskWindow | kMaskPrefix), i + p.q_off, j, p.window, p.prefix, 0, 0) ||
+                 fl_user_mask(b, g, h, i + p.q_off, j, p);
+        some_visible = some_visible || !hide;
+        some_hidden = some_hidden || hide;
+        word |= hide ? (1u << (16 * nb + r)) : 0u;
+      }
+  } else {
+    word = ~0u;
   }
   const bool vis = __builtin_amdgcn_ballot_w64(some_visible) != 0, hid = __builtin_amdgcn_ballot_w64(some_hidden) != 0;
-  if (lane == 0) map[((int64_t)prob * p.map_nkt + kt) * p.map_nqb8 + qb] = (unsigned char)(vis ? (hid ? 1 : 2) : 0);
+  const int64_t block = ((int64_t)prob * p.map_nkt + kt) * p.map_nqb8 + qb;
+  if (lane == 0) map[block] = (unsigned char)(vis ? (hid ? 1 : 2) : 0);
+  if (bits != nullptr) bits[block * 64 + lane] = word;
 }
 
 }  // namespace fl

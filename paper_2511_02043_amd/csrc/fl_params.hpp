@@ -90,6 +90,7 @@ struct FwdParams {
   int32_t q_off;         // query row i sits at sequence position i + q_off (positional masks, ALiBi); >= 0
   const void* user_aux[4];   // run-time compiled variants: the caller's device arrays that the expressions read
   const unsigned char* block_map;   // run-time compiled masks, or null: tile classes [problem][key tile][query block] (block_map_kernel)
+  const uint32_t* block_bits;       // ... and, or null: per block 64 words (one per lane) of hidden-score bits
   int32_t map_nqb8, map_nkt;        // query blocks per tile row (a multiple of 8) and key tiles of the map
   int32_t map_per_head;             // 1: a problem of the map is (b, g, h); 0: b (the expression reads neither g nor h)
   const int32_t* kv_lens;    // bf16 kernels, or null: [B] keys of each sequence (cut to [0, Sk]); then q_off = kv_lens[b] - Sq

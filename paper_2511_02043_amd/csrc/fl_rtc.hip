@@ -304,7 +304,7 @@ fl_status fl_compile_variant_aux(const char* score_mod_expr, const char* mask_ex
   if (mask_expr != nullptr) {                      // the pre-pass that classifies tiles under this mask
     char minst[128];
     snprintf(minst, sizeof(minst), "fl::block_map_kernel<%uu, %d>", mask, kBN);
-    src += std::string("template __global__ void ") + minst + "(const fl::FwdParams, unsigned char*);\n";
+    src += std::string("template __global__ void ") + minst + "(const fl::FwdParams, unsigned char*, unsigned int*);\n";
     insts.push_back(minst);
   }
 
@@ -339,16 +339,27 @@ fl_status fl_attn_fwd_custom(fl_custom_variant* v, const fl_tensor* q, const fl_
   return fl_attn_fwd_custom_aux(v, q, k, vv, scale, window, prefix_len, nullptr, out, lse, stream_v);
 }
 
-// Bytes of the tile-class map of a call: one byte per (32-row query block, 64-key tile), rows of a tile padded to 8 blocks.
-static size_t block_map_bytes(const fl_custom_variant* v, int64_t B, int64_t G, int64_t H, int64_t Sq, int64_t Sk) {
+// Workspace of the tile-class map of a call: one class byte per (32-row query block, 64-key tile), rows of a tile padded to
+// 8 blocks; then, while they stay under 1 GiB, 64 words of hidden-score bits per block (one per lane of the wave that owns
+// the block in the attention kernel).  Beyond that size the attention kernel evaluates the expression on partly visible tiles.
+struct MapLayout {
+  int64_t blocks;
+  size_t off_bits, bits_bytes, total;
+};
+static MapLayout map_layout(const fl_custom_variant* v, int64_t B, int64_t G, int64_t H, int64_t Sq, int64_t Sk) {
   const int64_t nqb8 = ((Sq + 31) / 32 + 7) / 8 * 8, nkt = (Sk + kBN - 1) / kBN;
-  return (size_t)((v->per_head ? B * G * H : B) * nkt * nqb8);
+  MapLayout L;
+  L.blocks = (v->per_head ? B * G * H : B) * nkt * nqb8;
+  L.off_bits = ((size_t)L.blocks + 255) / 256 * 256;
+  L.bits_bytes = (size_t)L.blocks * 256 <= ((size_t)1 << 30) ? (size_t)L.blocks * 256 : 0;
+  L.total = L.off_bits + L.bits_bytes;
+  return L;
 }
 
 size_t fl_custom_skip_workspace_size(fl_custom_variant* v, const fl_tensor* q, const fl_tensor* k) {
   if (v == nullptr || q == nullptr || k == nullptr || !v->has_mask_expr) return 0;
   if (q->size[0] < 0 || q->size[1] < 0 || q->size[2] < 0 || q->size[3] < 0 || k->size[3] < 0) return 0;
-  return block_map_bytes(v, q->size[0], q->size[1], q->size[2], q->size[3], k->size[3]);
+  return map_layout(v, q->size[0], q->size[1], q->size[2], q->size[3], k->size[3]).total;
 }
 
 static fl_status custom_forward(fl_custom_variant* v, const fl_tensor* q, const fl_tensor* k, const fl_tensor* vv, float scale,
@@ -452,18 +463,20 @@ static fl_status custom_forward(fl_custom_variant* v, const fl_tensor* q, const 
   if (skip && v->has_mask_expr) {
     // the pre-pass: the mask once per score, one class byte per (32-row block, 64-key tile); the kernel then passes over
     // tiles with nothing visible and skips the per-score mask on tiles where everything is
-    const size_t need = block_map_bytes(v, B, G, H, Sq, Sk);
-    if (workspace == nullptr || workspace_bytes < need)
-      return fl::host::fail(FL_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", need, workspace ? workspace_bytes : (size_t)0);
+    const MapLayout ML = map_layout(v, B, G, H, Sq, Sk);
+    if (workspace == nullptr || workspace_bytes < ML.total)
+      return fl::host::fail(FL_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", ML.total, workspace ? workspace_bytes : (size_t)0);
     if (((uintptr_t)workspace) % 16 != 0) return fl::host::fail(FL_ERR_ALIGN, "workspace not 16-byte aligned");
     p.block_map = (const unsigned char*)workspace;
+    p.block_bits = ML.bits_bytes != 0 ? (const uint32_t*)((const char*)workspace + ML.off_bits) : nullptr;
     p.map_nqb8 = (int)(((Sq + 31) / 32 + 7) / 8 * 8);
     p.map_nkt = (int)((Sk + kBN - 1) / kBN);
     p.map_per_head = v->per_head ? 1 : 0;
     const int64_t mblocks = (v->per_head ? nbh : B) * p.map_nqb8 * ((p.map_nkt + 3) / 4);
     if (mblocks > 0x7fffffffLL) return fl::host::fail(FL_ERR_SHAPE, "too many tiles to classify");
     unsigned char* map = (unsigned char*)workspace;
-    void* margs[] = {&p, &map};
+    uint32_t* bits = (uint32_t*)p.block_bits;
+    void* margs[] = {&p, &map, &bits};
     e = hipModuleLaunchKernel(v->map_func[dev], (unsigned)mblocks, 1, 1, 256, 1, 1, 0, (hipStream_t)stream_v, margs, nullptr);
     if (e != hipSuccess) return fl::host::fail(FL_ERR_LAUNCH, "tile-class pre-pass launch: %s", hipGetErrorString(e));
   }

@@ -189,7 +189,8 @@ def test_tile_skipping_changes_nothing(name, D):
     dw = runner.upload(w, out_dtype="f32")
     (plain, skip), need = run_both_ways(var, dw, float(w.scale))
     nqb8, nkt = ((333 + 31) // 32 + 7) // 8 * 8, (715 + 63) // 64
-    assert need == (2 * 4 if name.startswith("head") else 2) * nkt * nqb8       # per (b, g, h) only when the mask reads h
+    blocks = (2 * 4 if name.startswith("head") else 2) * nkt * nqb8            # per (b, g, h) only when the mask reads h
+    assert need == (blocks + 255) // 256 * 256 + blocks * 256                   # class bytes, then 64 words per block
     assert np.array_equal(plain[0], skip[0]) and np.array_equal(plain[1], skip[1])
     ref, ref_lse = ao.attention_custom(w.q, w.k, w.v, scale=w.scale, score_mod=np_mod, mask=np_mask)
     dead = np.isneginf(ref_lse)
@@ -215,7 +216,8 @@ def test_document_mask_expression_with_tile_skipping(D):
         expr = "aux0[b * Sq + i] != aux1[b * Sk + j]" + ("" if base else " && (i - j) % 5 != 0")
         var = fb.CustomVariant(None, expr, D, base_mask=base, aux=[t_ids, t_ids])
         (plain, skip), need = run_both_ways(var, dw, float(w.scale))
-        assert need == B * ((S + 63) // 64) * (((S + 31) // 32 + 7) // 8 * 8)        # the expression reads neither g nor h
+        blocks = B * ((S + 63) // 64) * (((S + 31) // 32 + 7) // 8 * 8)              # the expression reads neither g nor h
+        assert need == (blocks + 255) // 256 * 256 + blocks * 256
         assert np.array_equal(plain[0], skip[0]) and np.array_equal(plain[1], skip[1])
         ref, ref_lse = ao.attention_custom(w.q, w.k, w.v, scale=w.scale, score_mod=None, mask=np_mask)
         assert float(np.max(np.abs(skip[0] - ref))) <= 1e-2
