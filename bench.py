@@ -27,7 +27,17 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
 
+WINDOW_OVERRIDE = None           # --window: replaces the window of a windowed configuration (0: a row sees its own key only)
+
+
 def make_workload(name):
+    w = _make_workload(name)
+    if WINDOW_OVERRIDE is not None and w.window is not None:
+        w.window = WINDOW_OVERRIDE
+    return w
+
+
+def _make_workload(name):
     from paper_2511_02043_amd import inputs
     if name == "c2_d128":
         return inputs.causal_bf16(D=128)
@@ -676,6 +686,9 @@ def main():
                     help="time fl_attn_decode (64 sequences of 4k-8k cached tokens, 32 / 8 heads, D = 128, 16-token pages)")
     ap.add_argument("--no-gemm-reference", action="store_true",
                     help="skip the bf16 GEMM that shows what the matrix cores sustain on random data")
+    ap.add_argument("--window", type=int, default=None,
+                    help="override the window of a windowed configuration (c3c): --window 0 leaves one key tile per row "
+                         "block, i.e. the launch's memory traffic without its key loop")
     ap.add_argument("--rotate", type=int, default=1,
                     help="cycle the timed launches over this many independent buffer sets (a workload smaller than the "
                          "256 MB Infinity Cache is then timed from HBM)")
@@ -684,6 +697,8 @@ def main():
                     help="only run a plain device-to-device copy of MIB MiB a few times (scale factor of the "
                          "FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
     args = ap.parse_args()
+    global WINDOW_OVERRIDE
+    WINDOW_OVERRIDE = args.window
     if args.out_dir:
         global OUT_DIR
         OUT_DIR = os.path.abspath(args.out_dir)
