@@ -163,12 +163,17 @@ size_t workspace_bytes(int64_t B, int64_t Sq, int64_t Sk, uint32_t mask) {
   return (size_t)(B * (nq + nk)) * sizeof(int2);
 }
 
-// (min, max) of the document ids of each block of 32 tokens: one wave per block.
-__global__ void doc_summary_kernel(const int32_t* __restrict__ ids, int2* __restrict__ sum, int S, int nblk,
-                                   int total) {
-  const int w = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+// (min, max) of the document ids of each block of 32 tokens, one wave per block; the query-side and the key-side
+// summaries in one launch (waves [0, tq) and [tq, tq + tk)).
+__global__ void doc_summary_kernel(const int32_t* __restrict__ q_ids, int2* __restrict__ q_sum, int Sq, int nqs, int tq,
+                                   const int32_t* __restrict__ k_ids, int2* __restrict__ k_sum, int Sk, int nks, int tk) {
+  int w = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
   const int lane = threadIdx.x & 63;
-  if (w >= total) return;
+  if (w >= tq + tk) return;
+  const bool keys = w >= tq;                       // uniform over the wave
+  if (keys) w -= tq;
+  const int32_t* ids = keys ? k_ids : q_ids;
+  const int S = keys ? Sk : Sq, nblk = keys ? nks : nqs;
   const int b = w / nblk, blk = w % nblk;
   const int j = blk * fl::kSumBlock + (lane & 31);
   const int jc = j < S ? j : S - 1;
@@ -178,7 +183,13 @@ __global__ void doc_summary_kernel(const int32_t* __restrict__ ids, int2* __rest
     lo = min(lo, __shfl_xor(lo, o));
     hi = max(hi, __shfl_xor(hi, o));
   }
-  if (lane == 0) sum[w] = make_int2(lo, hi);
+  if (lane == 0) (keys ? k_sum : q_sum)[w] = make_int2(lo, hi);
+}
+
+void launch_doc_summaries(const int32_t* q_ids, int2* q_sum, int Sq, int nqs, int tq, const int32_t* k_ids, int2* k_sum, int Sk,
+                          int nks, int tk, hipStream_t stream) {
+  hipLaunchKernelGGL(doc_summary_kernel, dim3((tq + tk + 3) / 4), dim3(256), 0, stream, q_ids, q_sum, Sq, nqs, tq, k_ids, k_sum, Sk,
+                     nks, tk);
 }
 
 // Degenerate Sk == 0: every row is fully masked, so out = 0 and lse = -inf.
@@ -901,8 +912,7 @@ static fl_status forward_call(const fl_tensor* q, const fl_tensor* k, const fl_t
     p.q_sum = (int2*)aux->workspace;
     p.kv_sum = p.q_sum + B * nqs;
     const int tq = (int)(B * nqs), tk = (int)(B * nks);
-    hipLaunchKernelGGL(doc_summary_kernel, dim3((tq + 3) / 4), dim3(256), 0, stream, aux->q_doc_ids, p.q_sum, (int)Sq, nqs, tq);
-    hipLaunchKernelGGL(doc_summary_kernel, dim3((tk + 3) / 4), dim3(256), 0, stream, aux->kv_doc_ids, p.kv_sum, (int)Sk, nks, tk);
+    launch_doc_summaries(aux->q_doc_ids, p.q_sum, (int)Sq, nqs, tq, aux->kv_doc_ids, p.kv_sum, (int)Sk, nks, tk, stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(FL_ERR_LAUNCH, "doc summary launch: %s", hipGetErrorString(e));
   }
@@ -1087,8 +1097,7 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
     p.q_sum = (int2*)((unsigned char*)aux->workspace + 2 * wsz.stat_bytes);
     p.kv_sum = p.q_sum + B * nqs;
     const int tq = (int)(B * nqs), tk = (int)(B * nks);
-    hipLaunchKernelGGL(doc_summary_kernel, dim3((tq + 3) / 4), dim3(256), 0, stream, aux->q_doc_ids, p.q_sum, (int)Sq, nqs, tq);
-    hipLaunchKernelGGL(doc_summary_kernel, dim3((tk + 3) / 4), dim3(256), 0, stream, aux->kv_doc_ids, p.kv_sum, (int)Sk, nks, tk);
+    launch_doc_summaries(aux->q_doc_ids, p.q_sum, (int)Sq, nqs, tq, aux->kv_doc_ids, p.kv_sum, (int)Sk, nks, tk, stream);
     if ((e = hipGetLastError()) != hipSuccess) return fail(FL_ERR_LAUNCH, "doc summary launch: %s", hipGetErrorString(e));
   }
   if (!no_rows) {
@@ -1335,8 +1344,7 @@ fl_status fl_attn_bwd_ex(const fl_tensor* q, const fl_tensor* k, const fl_tensor
     p.q_sum = (int2*)(ws + L.off_sum);
     p.kv_sum = p.q_sum + B * nqs;
     const int tq = (int)(B * nqs), tk = (int)(B * nks);
-    hipLaunchKernelGGL(doc_summary_kernel, dim3((tq + 3) / 4), dim3(256), 0, stream, aux->q_doc_ids, p.q_sum, (int)Sq, nqs, tq);
-    hipLaunchKernelGGL(doc_summary_kernel, dim3((tk + 3) / 4), dim3(256), 0, stream, aux->kv_doc_ids, p.kv_sum, (int)Sk, nks, tk);
+    launch_doc_summaries(aux->q_doc_ids, p.q_sum, (int)Sq, nqs, tq, aux->kv_doc_ids, p.kv_sum, (int)Sk, nks, tk, stream);
     if ((e = hipGetLastError()) != hipSuccess) return fail(FL_ERR_LAUNCH, "doc summary launch: %s", hipGetErrorString(e));
   }
   const fl::View vview = L.pad_v ? dense_view(ws + L.off_vpad, G, Hkv, Sk, Dc) : make_view(v);
