@@ -209,6 +209,8 @@ typedef struct {
                               holds dS of every score in bf16 ([B, G, H, Sq, Sk], 2 bytes each) until it is summed  */
   fl_tensor dgate;         /* FL_EPI_GATE_SIGMOID: gradient of aux->gate, shape of out, bf16 or f32; ptr NULL: not computed */
   float*    dlambda;       /* FL_DIFFERENTIAL: [H] f32 device; NULL: not computed                              */
+  float*    drms_weight;   /* FL_EPI_RMSNORM: gradient of aux->rms_weight (of the implied all-ones weight when that is
+                              NULL), [Dv] f32 device; NULL: not computed                                       */
 } fl_bwd_extra;
 
 /* fl_attn_bwd for every variant of the forward pass: additive biases (with their gradients), the sigmoid
@@ -217,6 +219,7 @@ typedef struct {
  * description in Sec. 4.1):
  *     dy = dout * sigmoid(g),  dg = dout * y * sigmoid(g) (1 - sigmoid(g))           gate
  *     dx = w dy / r - x (sum_c w_c dy_c x_c) / (Dv r^3),  r = sqrt(mean(x^2) + eps)  RMSNorm
+ *     dw_c = sum over rows of dy_c x_c / r
  *     dO1 = dx,  dO2 = -lambda_h dx,  dlambda_h = -sum dx * O2                       x = O1 - lambda_h O2
  *     dbias = dS summed over the axes the bias broadcasts along
  * and then the softmax / contraction derivative of fl_attn_bwd per stream (dv sums both streams).
@@ -231,7 +234,7 @@ typedef struct {
  * Covered: every descriptor fl_attn_fwd takes for bf16 inputs (any score_mod with any mask, zero to two
  * biases, both epilogues, the second stream; D, Dv in {32, 64, 128}).  Variants outside the compiled table
  * of backward kernels are instantiated from the kernel templates on first use (hipRTC, a few seconds, once
- * per process and variant).  The gradient of rms_weight is not computed.
+ * per process and variant).
  * Same stream, ownership and error rules as fl_attn_fwd.                                  */
 fl_status fl_attn_bwd_ex(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v, const fl_tensor* out,
                          const fl_tensor* dout, const fl_tensor* lse, const fl_variant_desc* desc,

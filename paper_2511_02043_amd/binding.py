@@ -45,7 +45,7 @@ class fl_aux(C.Structure):
 
 class fl_bwd_extra(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("reserved", C.c_uint32), ("dq2", fl_tensor), ("dk2", fl_tensor),
-                ("dbias", fl_tensor * 2), ("dgate", fl_tensor), ("dlambda", C.c_void_p)]
+                ("dbias", fl_tensor * 2), ("dgate", fl_tensor), ("dlambda", C.c_void_p), ("drms_weight", C.c_void_p)]
 
 
 class fl_paged_kv(C.Structure):
@@ -221,13 +221,14 @@ def fl_attn_bwd(q: fl_tensor, k: fl_tensor, v: fl_tensor, out: fl_tensor, dout: 
                              _ref(dq), _ref(dk), _ref(dv), C.c_void_p(stream))
 
 
-def bwd_extra(*, dq2=None, dk2=None, dbias=(), dgate=None, dlambda=None) -> fl_bwd_extra:
+def bwd_extra(*, dq2=None, dk2=None, dbias=(), dgate=None, dlambda=None, drms_weight=None) -> fl_bwd_extra:
     x = fl_bwd_extra()
     x.struct_size = C.sizeof(fl_bwd_extra)
     x.dq2, x.dk2, x.dgate = tensor_desc(dq2), tensor_desc(dk2), tensor_desc(dgate)
     for n, b in enumerate(dbias):
         x.dbias[n] = tensor_desc(b)
     x.dlambda = None if dlambda is None else dlambda.data_ptr()
+    x.drms_weight = None if drms_weight is None else drms_weight.data_ptr()
     return x
 
 

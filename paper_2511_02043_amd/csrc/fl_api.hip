@@ -351,6 +351,7 @@ struct EpiBwdParams {
   const float* lambda;
   const float* rms_w;
   float* dl_rows;                   // per-row terms of dlambda (summed per head by reduce_dlambda_kernel), or null
+  float* dw_part;                   // per-workgroup partial sums of the rms_weight gradient, [workgroups, Dv], or null
   float rms_eps;
   int32_t B, G, H, Sq, Dv, Dc;
   int32_t ns, has_gate, has_rms, dgate_f32;
@@ -360,8 +361,21 @@ struct EpiBwdParams {
 __global__ void __launch_bounds__(256) epi_bwd_kernel(const EpiBwdParams e) {
   const int64_t rows = (int64_t)e.B * e.G * e.H * e.Sq;
   const int64_t row = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6;
-  if (row >= rows) return;
   const int lane = threadIdx.x & 63;
+  // rms_weight gradient: the four rows of a workgroup are added through LDS, the workgroups by reduce_drms_kernel
+  __shared__ float dw_rows[4][128];
+  auto dw_finish = [&](float t0, float t1) {         // every wave of the workgroup calls this exactly once (or none does)
+    dw_rows[threadIdx.x >> 6][lane] = t0;
+    dw_rows[threadIdx.x >> 6][lane + 64] = t1;
+    __syncthreads();
+    if ((int)threadIdx.x < e.Dv)
+      e.dw_part[(int64_t)blockIdx.x * e.Dv + threadIdx.x] =
+          (dw_rows[0][threadIdx.x] + dw_rows[1][threadIdx.x]) + (dw_rows[2][threadIdx.x] + dw_rows[3][threadIdx.x]);
+  };
+  if (row >= rows) {
+    if (e.dw_part != nullptr) dw_finish(0.f, 0.f);
+    return;
+  }
   const int i = (int)(row % e.Sq);
   const int h = (int)((row / e.Sq) % e.H);
   const int g = (int)((row / ((int64_t)e.Sq * e.H)) % e.G);
@@ -409,6 +423,8 @@ __global__ void __launch_bounds__(256) epi_bwd_kernel(const EpiBwdParams e) {
     const float c3 = dot / ((float)e.Dv * r * r * r);
 #pragma unroll
     for (int u = 0; u < 2; ++u) dx[u] = wv[u] * dy[u] / r - x[u] * c3;
+    if (e.dw_part != nullptr)                      // (channels past Dv carry dy = x = 0)
+      dw_finish(dy[0] * x[0] / r, dy[1] * x[1] / r);
   }
   float d1 = 0.f, d2 = 0.f, dl = 0.f;
 #pragma unroll
@@ -440,6 +456,21 @@ __global__ void __launch_bounds__(256) epi_bwd_kernel(const EpiBwdParams e) {
       e.lse2[s][row] = l == -INFINITY ? INFINITY : l * fl::kLog2e;
     }
   }
+}
+
+// drms_weight[c] = sum over the workgroups' partial sums; one workgroup per channel, fixed summation order
+__global__ void __launch_bounds__(256) reduce_drms_kernel(const float* dw_part, float* dw, int64_t nwg, int Dv) {
+  __shared__ float part[256];
+  const int c = blockIdx.x;
+  float s = 0.f;
+  for (int64_t t = threadIdx.x; t < nwg; t += 256) s += dw_part[t * Dv + c];
+  part[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 128; o >= 1; o >>= 1) {
+    if ((int)threadIdx.x < o) part[threadIdx.x] += part[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) dw[c] = part[0];
 }
 
 // dlambda[h] = sum over (b, g, i) of the per-row terms; one workgroup per head, fixed summation order
@@ -581,7 +612,7 @@ struct ExLayout {
   bool need_o, pad_qk, pad_v;
   size_t stat, o, d_o, qpad, kpad, vpad, gq, gk, gv, sum, part, ds;   // sizes of one region each
   size_t off_lse2[2], off_delta[2], off_o[2], off_do[2], off_qpad[2], off_kpad[2], off_vpad, off_gq[2], off_gk[2], off_gv[2],
-      off_sum, off_part, off_dl, off_ds;
+      off_sum, off_part, off_dl, off_ds, off_dw;
   size_t total;
 };
 ExLayout ex_layout(int64_t B, int64_t G, int64_t H, int64_t Hkv, int64_t Sq, int64_t Sk, int64_t D, int64_t Dv,
@@ -627,6 +658,8 @@ ExLayout ex_layout(int64_t B, int64_t G, int64_t H, int64_t Hkv, int64_t Sq, int
   // bias gradients: dS of every score (bf16), reduced over the broadcast axes afterwards
   L.ds = d->n_bias > 0 ? up256(rq * (size_t)Sk * 2) : 0;
   L.off_ds = take(L.ds);
+  // rms_weight gradient: one partial sum per workgroup (four rows) of the epilogue-derivative kernel
+  L.off_dw = take((d->epilogue & FL_EPI_RMSNORM) != 0 ? up256(((rq + 3) / 4) * (size_t)Dv * 4) : 0);
   L.total = at;
   return L;
 }
@@ -1289,10 +1322,14 @@ fl_status fl_attn_bwd_ex(const fl_tensor* q, const fl_tensor* k, const fl_tensor
   ep.lambda = aux->lambda;
   ep.rms_w = aux->rms_weight;
   ep.dl_rows = diff && extra->dlambda != nullptr ? (float*)(ws + L.off_dl) : nullptr;
+  ep.dw_part = has_rms && extra != nullptr && extra->drms_weight != nullptr ? (float*)(ws + L.off_dw) : nullptr;
   ep.rms_eps = desc->rms_eps;
   ep.B = (int)B; ep.G = (int)G; ep.H = (int)H; ep.Sq = (int)Sq; ep.Dv = (int)Dv; ep.Dc = Dc;
   ep.ns = ns; ep.has_gate = has_gate; ep.has_rms = has_rms;
   hipLaunchKernelGGL(epi_bwd_kernel, blocks(rows_q * 64), dim3(256), 0, stream, ep);
+  if (ep.dw_part != nullptr)
+    hipLaunchKernelGGL(reduce_drms_kernel, dim3((unsigned)Dv), dim3(256), 0, stream, (const float*)ep.dw_part, extra->drms_weight,
+                       (int64_t)((rows_q + 3) / 4), (int)Dv);
   if (ep.dl_rows != nullptr)
     hipLaunchKernelGGL(reduce_dlambda_kernel, dim3((unsigned)H), dim3(256), 0, stream, (const float*)ep.dl_rows, extra->dlambda, (int)B, (int)G,
                        (int)H, (int)Sq);

@@ -152,10 +152,10 @@ def _mask_bits(causal, window, prefix, q_doc_ids):
 
 class _VariantAttention(torch.autograd.Function):
     """Forward fl_attn_fwd, backward fl_attn_bwd_ex, for descriptors with biases / gate / RMSNorm / second stream.
-    Tensor inputs: q, k, v, q2, k2, lam, gate, bias0, bias1 (absent ones are None)."""
+    Tensor inputs: q, k, v, q2, k2, lam, gate, bias0, bias1, rms_weight (absent ones are None)."""
 
     @staticmethod
-    def forward(ctx, cfg, q, k, v, q2, k2, lam, gate, bias0, bias1):
+    def forward(ctx, cfg, q, k, v, q2, k2, lam, gate, bias0, bias1, rms_weight):
         dev = q.device
         q5, k5, v5 = _as5(q), _as5(k), _as5(v)
         B, G, H, Sq, _ = q5.shape
@@ -178,16 +178,16 @@ class _VariantAttention(torch.autograd.Function):
         five = lambda x: None if x is None else _as5(x)
         aux = fb.aux_desc(alibi_slopes=cfg["alibi_slopes"], q_doc_ids=cfg["q_doc_ids"], kv_doc_ids=cfg["kv_doc_ids"],
                           biases=biases, gate=five(gate), q2=five(q2), k2=five(k2), lambda_=lam,
-                          rms_weight=cfg["rms_weight"], workspace=ws)
+                          rms_weight=rms_weight, workspace=ws)
         stream = torch.cuda.current_stream(dev).cuda_stream
         fb.check(fb.fl_attn_fwd(tq, tk, tv, desc, aux, tout, tlse, stream))
-        ctx.save_for_backward(q, k, v, q2, k2, lam, gate, bias0, bias1, out, lse)
+        ctx.save_for_backward(q, k, v, q2, k2, lam, gate, bias0, bias1, rms_weight, out, lse)
         ctx.cfg, ctx.desc = cfg, desc
         return out if q.dim() == 5 else out.squeeze(1)
 
     @staticmethod
     def backward(ctx, dout):
-        q, k, v, q2, k2, lam, gate, bias0, bias1, out, lse = ctx.saved_tensors
+        q, k, v, q2, k2, lam, gate, bias0, bias1, rms_weight, out, lse = ctx.saved_tensors
         cfg, desc = ctx.cfg, ctx.desc
         dev = q.device
         q5, k5, v5, d5 = _as5(q), _as5(k), _as5(v), _as5(dout)
@@ -205,15 +205,16 @@ class _VariantAttention(torch.autograd.Function):
         ws = torch.empty(max(fb.fl_attn_bwd_ex_workspace_size(tq, tk, tv, desc), 16), dtype=torch.uint8, device=dev)
         aux = fb.aux_desc(alibi_slopes=cfg["alibi_slopes"], q_doc_ids=cfg["q_doc_ids"], kv_doc_ids=cfg["kv_doc_ids"],
                           biases=biases, gate=five(gate), q2=five(q2), k2=five(k2), lambda_=lam,
-                          rms_weight=cfg["rms_weight"], workspace=ws)
-        extra = fb.bwd_extra(dq2=dq2, dk2=dk2, dbias=dbias, dgate=dgate, dlambda=dlam)
+                          rms_weight=rms_weight, workspace=ws)
+        drms = torch.empty(v5.shape[4], dtype=torch.float32, device=dev) if (cfg["rmsnorm"] and rms_weight is not None) else None
+        extra = fb.bwd_extra(dq2=dq2, dk2=dk2, dbias=dbias, dgate=dgate, dlambda=dlam, drms_weight=drms)
         stream = torch.cuda.current_stream(dev).cuda_stream
         fb.check(fb.fl_attn_bwd_ex(tq, tk, tv, tout, tdo, tlse, desc, aux, tdq, tdk, tdv, extra, stream))
         sq = (lambda x: x) if q.dim() == 5 else (lambda x: None if x is None else x.squeeze(1))
         gb = [g.to(b.dtype) for g, b in zip(dbias, biases)] + [None] * (2 - len(biases))
         if bias0 is None and bias1 is not None:
             gb = [None, gb[0]]
-        return (None, sq(dq), sq(dk), sq(dv), sq(dq2), sq(dk2), dlam, sq(dgate), gb[0], gb[1])
+        return (None, sq(dq), sq(dk), sq(dv), sq(dq2), sq(dk2), dlam, sq(dgate), gb[0], gb[1], drms)
 
 
 def variant_attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, scale: Optional[float] = None,
@@ -231,8 +232,9 @@ def variant_attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, scal
     gate      pre-sigmoid tensor of the output's shape: out = sigmoid(gate) * (...)
     q2, k2, lam   the second softmax stream of differential attention and its per-head fp32 weights [H]:
               softmax(q k^T) v - lam_h softmax(q2 k2^T) v
-    rmsnorm   RMSNorm over the output channels (rms_weight fp32 [Dv], not differentiated), before the gate
-    Tensors are [B, H, S, D] or [B, G, H, S, D], bf16, on the GPU; differentiable in q, k, v, q2, k2, lam, gate, biases."""
+    rmsnorm   RMSNorm over the output channels (rms_weight fp32 [Dv] or None for all ones), before the gate
+    Tensors are [B, H, S, D] or [B, G, H, S, D], bf16, on the GPU; differentiable in q, k, v, q2, k2, lam, gate, biases
+    and rms_weight."""
     if not q.is_cuda or q.dtype != torch.bfloat16:
         raise ValueError("variant_attention() takes bf16 CUDA tensors (there is no CPU or fallback path)")
     if (q2 is None) != (k2 is None) or (q2 is None) != (lam is None):
@@ -255,10 +257,10 @@ def variant_attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, *, scal
             raise ValueError(f"biases[{n}] must be a 5-D bf16 tensor on {q.device}")
     cfg = dict(scale=q.shape[-1] ** -0.5 if scale is None else scale, causal=causal, window=window, prefix=prefix,
                softcap=softcap, alibi_slopes=alibi_slopes, q_doc_ids=q_doc_ids, kv_doc_ids=kv_doc_ids, q_offset=q_offset,
-               rmsnorm=rmsnorm, rms_eps=rms_eps, rms_weight=rms_weight)
+               rmsnorm=rmsnorm, rms_eps=rms_eps)
     b0 = biases[0] if len(biases) > 0 else None
     b1 = biases[1] if len(biases) > 1 else None
-    return _VariantAttention.apply(cfg, q, k, v, q2, k2, lam, gate, b0, b1)
+    return _VariantAttention.apply(cfg, q, k, v, q2, k2, lam, gate, b0, b1, rms_weight if rmsnorm else None)
 
 
 def decode_attention(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, seq_lens: torch.Tensor,

@@ -186,7 +186,7 @@ def upload_backward(w, dout: np.ndarray, grad_dtype: str = "f32", device="cuda:0
 @dataclasses.dataclass
 class DeviceBackwardEx:
     """Device tensors of one fl_attn_bwd_ex call: every gradient the variant has (dq, dk, dv, and dq2 / dk2 /
-    dlambda, dbias, dgate where the workload has those inputs)."""
+    dlambda, dbias, dgate, drms_weight where the workload has those inputs)."""
     fwd: DeviceWorkload
     dout: torch.Tensor
     grads: dict                          # name -> tensor (dbias: list)
@@ -240,8 +240,10 @@ def upload_backward_ex(w, dout: np.ndarray, grad_dtype: str = "f32", device="cud
         g["dgate"] = empty_like_layout(gate, gate.shape[4], gdt)
     if biases:
         g["dbias"] = [torch.empty(tuple(b.shape), dtype=torch.float32, device=device) for b in biases]
+    if w.rmsnorm:
+        g["drms_weight"] = torch.empty(w.v.shape[4], dtype=torch.float32, device=device)
     extra = fb.bwd_extra(dq2=g.get("dq2"), dk2=g.get("dk2"), dbias=g.get("dbias", ()), dgate=g.get("dgate"),
-                         dlambda=g.get("dlambda"))
+                         dlambda=g.get("dlambda"), drms_weight=g.get("drms_weight"))
     return DeviceBackwardEx(fwd, d_out, g, aux, extra, [ws] + list(fwd.keep), fb.tensor_desc(d_out), fb.tensor_desc(g["dq"]),
                             fb.tensor_desc(g["dk"]), fb.tensor_desc(g["dv"]))
 

@@ -33,7 +33,7 @@ def compare(w, grad_dtype="f32", label=None, rel_l2=REL_L2):
     db.run_checked()
     torch.cuda.synchronize()
     ref = bo.variant_backward(w, dout)
-    names = [n for n in ("dq", "dk", "dv", "dq2", "dk2", "dlambda", "dgate") if n in db.grads]
+    names = [n for n in ("dq", "dk", "dv", "dq2", "dk2", "dlambda", "dgate", "drms_weight") if n in db.grads]
     pairs = [(n, db.grads[n], ref[n]) for n in names]
     for n, t in enumerate(db.grads.get("dbias", [])):
         pairs.append((f"dbias[{n}]", t, ref["dbias"][n]))

@@ -186,7 +186,7 @@ def test_variant_attention_autograd(case):
     q, k, v, gate, q2, k2 = (leaf(x) for x in (w.q, w.k, w.v, w.gate, w.q2, w.k2))
     lam = leaf(w.lam, torch.float32)
     biases = [leaf(b) for b in w.biases]
-    rw = None if w.rms_weight is None else torch.from_numpy(np.asarray(w.rms_weight, np.float32)).to(dev)
+    rw = leaf(None if w.rms_weight is None else np.asarray(w.rms_weight, np.float32), torch.float32)
     out = variant_attention(q, k, v, scale=w.scale, causal=w.causal, biases=biases, gate=gate, q2=q2, k2=k2, lam=lam,
                             rmsnorm=w.rmsnorm, rms_eps=w.rms_eps, rms_weight=rw)
     out.backward(torch.from_numpy(np.ascontiguousarray(dout)).to(dev, torch.bfloat16))
@@ -195,7 +195,7 @@ def test_variant_attention_autograd(case):
     got = out.detach().float().cpu().numpy()
     assert np.all(np.abs(got - ref_out) <= 1e-2 + 2.0 ** -8 * np.abs(ref_out))
     ref = bo.variant_backward(w, dout)
-    pairs = [("dq", q), ("dk", k), ("dv", v), ("dq2", q2), ("dk2", k2), ("dlambda", lam), ("dgate", gate)]
+    pairs = [("dq", q), ("dk", k), ("dv", v), ("dq2", q2), ("dk2", k2), ("dlambda", lam), ("dgate", gate), ("drms_weight", rw)]
     pairs += [(("dbias", n), b) for n, b in enumerate(biases)]
     for name, t in pairs:
         if t is None:
