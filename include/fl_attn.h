@@ -384,6 +384,30 @@ fl_status fl_attn_fwd_custom_skip(fl_custom_variant* variant, const fl_tensor* q
 /* Bytes of workspace that fl_attn_fwd_custom_skip needs for these shapes (0 without a mask expression). */
 size_t fl_custom_skip_workspace_size(fl_custom_variant* variant, const fl_tensor* q, const fl_tensor* k);
 
+/* fl_compile_variant_aux for callers who also want the backward pass of the variant (the paper leaves training as future
+ * work; this extends its "arbitrary attention program" to the gradient):
+ *   score_mod_grad_expr  C expression for the derivative of score_mod_expr with respect to s, of the same names
+ *                        (s, b, g, h, i, j, aux0 .. aux3, B, G, H, Sq, Sk); NULL: 1, which is right for every score_mod of
+ *                        the form s + f(b, g, h, i, j) (relative biases, ALiBi-like terms).  E.g. for
+ *                        "8.0f * tanhf(s / 8.0f)": "1.0f - tanhf(s / 8.0f) * tanhf(s / 8.0f)".
+ * With a derivative expression the backward kernels are compiled here too (a few seconds more), so that an error in it
+ * is reported by this call; without one they are compiled by the first fl_attn_bwd_custom call.            */
+fl_status fl_compile_variant_grad(const char* score_mod_expr, const char* score_mod_grad_expr, const char* mask_expr,
+                                  uint32_t base_mask, int D, const int32_t* aux_dtypes, fl_custom_variant** handle);
+
+/* Gradients of a compiled variant with respect to q, k, v: fl_attn_bwd with the variant's score_mod (and its derivative
+ * expression) and mask in place of the descriptor's.  out, lse: what fl_attn_fwd_custom[_aux | _skip] wrote; dout, dq, dk,
+ * dv, the stream and the error rules as for fl_attn_bwd; scale, window, prefix_len, aux_ptrs as in the forward call.
+ * The mask expression is evaluated on every score of every tile inside the base mask's range (no tile-class map here).
+ *   workspace   DEVICE, fl_attn_bwd_custom_workspace_size bytes, 16-byte aligned; contents undefined afterwards   */
+fl_status fl_attn_bwd_custom(fl_custom_variant* variant, const fl_tensor* q, const fl_tensor* k, const fl_tensor* v,
+                             const fl_tensor* out, const fl_tensor* dout, const fl_tensor* lse, float scale,
+                             int32_t window, int32_t prefix_len, const void* const* aux_ptrs, void* workspace,
+                             size_t workspace_bytes, fl_tensor* dq, fl_tensor* dk, fl_tensor* dv, void* stream);
+
+/* Bytes of workspace that fl_attn_bwd_custom needs for these shapes. */
+size_t fl_attn_bwd_custom_workspace_size(fl_custom_variant* variant, const fl_tensor* q, const fl_tensor* k);
+
 /* Unloads and frees a compiled variant (no launch of it may be in flight). */
 void fl_release_variant(fl_custom_variant* variant);
 

@@ -41,7 +41,9 @@ axes the bias broadcasts along.  The epilogues and the second softmax stream (va
 Pins (tests/test_oracle_backward_pins.py): central finite differences of the forward oracle
 on every variant; autograd through PyTorch's fp64 CPU scaled_dot_product_attention;
 closed forms for Q = 0; the identities sum_j dV_j = sum_i dO_i and rowsum(dS) = 0;
-zero gradient for fully masked rows and for keys no row can see.
+zero gradient for fully masked rows and for keys no row can see.  attention_custom_backward (callable score_mod with
+its derivative, callable mask) is pinned by finite differences of the forward oracle's attention_custom and by
+attention_backward on named variants written as callables.
 """
 from __future__ import annotations
 
@@ -213,3 +215,45 @@ def run_workload_backward(w, dout):
     return attention_backward(w.q, w.k, w.v, dout, scale=w.scale, causal=w.causal, window=w.window,
                               prefix=w.prefix, softcap_value=w.softcap, alibi_slopes=w.alibi,
                               q_doc=w.q_doc, kv_doc=w.kv_doc, q_offset=int(getattr(w, "q_offset", 0) or 0))
+
+
+def attention_custom_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray, dout: np.ndarray, *, scale: float,
+                              score_mod=None, score_mod_grad=None, mask=None):
+    """Gradients of sum(out * dout) for the forward oracle's attention_custom(): an arbitrary score_mod (Eq. 4) and mask
+    predicate (the mask_mod of Sec. 2.2, inverted), given as callables on NumPy arrays, plus the derivative of the
+    score_mod with respect to the scaled score:
+
+        score_mod(s, b, g, h, i, j) -> new scores          s [Sq, Sk], i [Sq, 1], j [1, Sk]
+        score_mod_grad(s, b, g, h, i, j) -> d new / d s    (None: ones, right for s + f(b, g, h, i, j))
+        mask(b, g, h, i, j) -> bool [Sq, Sk], True = hidden
+
+    The same chain as attention_backward(): dV = P^T dO, dS = P * (dO V^T - rowsum), dZ = dS * score_mod_grad(z),
+    dQ = scale dZ K, dK = scale dZ^T Q.  Returns dq, dk, dv (float64)."""
+    B, G, H, Sq, D = q.shape
+    Hkv, Sk = k.shape[2], k.shape[3]
+    group = H // Hkv
+    i = np.arange(Sq, dtype=np.int64)[:, None]
+    j = np.arange(Sk, dtype=np.int64)[None, :]
+    dq, dk, dv = np.zeros(q.shape), np.zeros(k.shape), np.zeros(v.shape)
+    for b in range(B):
+        for g in range(G):
+            for h in range(H):
+                hk = h // group
+                qh = np.asarray(q[b, g, h], dtype=np.float64)
+                kh = np.asarray(k[b, g, hk], dtype=np.float64)
+                vh = np.asarray(v[b, g, hk], dtype=np.float64)
+                do = np.asarray(dout[b, g, h], dtype=np.float64)
+                z = (qh @ kh.T) * scale
+                s = z if score_mod is None else np.asarray(score_mod(z, b, g, h, i, j), dtype=np.float64)
+                slope = np.ones_like(z) if score_mod_grad is None else \
+                    np.broadcast_to(np.asarray(score_mod_grad(z, b, g, h, i, j), dtype=np.float64), z.shape)
+                if mask is not None:
+                    s = np.where(np.broadcast_to(mask(b, g, h, i, j), z.shape), -np.inf, s)
+                p = softmax_rows(s)
+                dv[b, g, hk] += p.T @ do
+                dp = do @ vh.T
+                ds = p * (dp - np.sum(p * dp, axis=1)[:, None])
+                dz = ds * slope
+                dq[b, g, h] = scale * (dz @ kh)
+                dk[b, g, hk] += scale * (dz.T @ qh)
+    return dq, dk, dv

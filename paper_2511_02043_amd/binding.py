@@ -120,6 +120,14 @@ def lib() -> C.CDLL:
                                               C.POINTER(C.c_void_p), C.c_void_p, C.c_size_t, TP, TP, C.c_void_p]
         L.fl_custom_skip_workspace_size.restype = C.c_size_t
         L.fl_custom_skip_workspace_size.argtypes = [C.c_void_p, TP, TP]
+        L.fl_compile_variant_grad.restype = C.c_int
+        L.fl_compile_variant_grad.argtypes = [C.c_char_p, C.c_char_p, C.c_char_p, C.c_uint32, C.c_int, C.POINTER(C.c_int32),
+                                              C.POINTER(C.c_void_p)]
+        L.fl_attn_bwd_custom.restype = C.c_int
+        L.fl_attn_bwd_custom.argtypes = [C.c_void_p, TP, TP, TP, TP, TP, TP, C.c_float, C.c_int32, C.c_int32,
+                                         C.POINTER(C.c_void_p), C.c_void_p, C.c_size_t, TP, TP, TP, C.c_void_p]
+        L.fl_attn_bwd_custom_workspace_size.restype = C.c_size_t
+        L.fl_attn_bwd_custom_workspace_size.argtypes = [C.c_void_p, TP, TP]
         L.fl_release_variant.restype = None
         L.fl_release_variant.argtypes = [C.c_void_p]
         L.fl_variant_supported.restype = C.c_int
@@ -137,7 +145,7 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ["fl_attn_fwd", "fl_attn_fwd_noalloc", "fl_attn_fwd_workspace_size", "fl_attn_bwd", "fl_attn_bwd_workspace_size", "fl_attn_bwd_ex", "fl_attn_bwd_ex_workspace_size",
-           "fl_bwd_supported", "fl_attn_decode", "fl_attn_decode_workspace_size", "fl_attn_prefill_paged", "fl_attn_prefill_paged_workspace_size", "fl_compile_variant", "fl_attn_fwd_custom", "fl_compile_variant_aux", "fl_attn_fwd_custom_aux", "fl_attn_fwd_custom_skip", "fl_custom_skip_workspace_size",
+           "fl_bwd_supported", "fl_attn_decode", "fl_attn_decode_workspace_size", "fl_attn_prefill_paged", "fl_attn_prefill_paged_workspace_size", "fl_compile_variant", "fl_attn_fwd_custom", "fl_compile_variant_aux", "fl_attn_fwd_custom_aux", "fl_attn_fwd_custom_skip", "fl_custom_skip_workspace_size", "fl_compile_variant_grad", "fl_attn_bwd_custom", "fl_attn_bwd_custom_workspace_size",
            "fl_release_variant", "fl_variant_supported", "fl_strerror",
            "fl_last_error_detail", "fl_set_tuning", "fl_version"]
 
@@ -332,6 +340,32 @@ def fl_custom_skip_workspace_size(handle, q: fl_tensor, k: fl_tensor) -> int:
     return lib().fl_custom_skip_workspace_size(handle, _ref(q), _ref(k))
 
 
+def fl_compile_variant_grad(score_mod: Optional[str], score_mod_grad: Optional[str], mask: Optional[str], D: int, aux=(),
+                            base_mask: int = 0):
+    """Compile with a derivative expression for the score_mod (and the backward kernels).  Returns (status, handle)."""
+    h = C.c_void_p()
+    codes = (C.c_int32 * 4)(*([(_dtype_code(a) if hasattr(a, "dtype") else int(a or 0)) for a in aux] + [0] * (4 - len(aux))))
+    enc = lambda x: None if x is None else x.encode()
+    st = lib().fl_compile_variant_grad(enc(score_mod), enc(score_mod_grad), enc(mask), base_mask, D, codes, C.byref(h))
+    return st, h
+
+
+def fl_attn_bwd_custom(handle, q: fl_tensor, k: fl_tensor, v: fl_tensor, out: fl_tensor, dout: fl_tensor, lse: fl_tensor,
+                       scale: float, aux, workspace, dq: fl_tensor, dk: fl_tensor, dv: fl_tensor, stream: int = 0,
+                       window: int = 0, prefix_len: int = 0) -> int:
+    """Gradients of a compiled variant; workspace: a uint8 device tensor.  Returns the status code."""
+    ptrs = (C.c_void_p * 4)(*([(None if a is None else a.data_ptr()) for a in aux] + [None] * (4 - len(aux))))
+    ws_ptr = None if workspace is None else workspace.data_ptr()
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    return lib().fl_attn_bwd_custom(handle, _ref(q), _ref(k), _ref(v), _ref(out), _ref(dout), _ref(lse), C.c_float(scale), window,
+                                    prefix_len, ptrs, C.c_void_p(ws_ptr), C.c_size_t(ws_bytes), _ref(dq), _ref(dk), _ref(dv),
+                                    C.c_void_p(stream))
+
+
+def fl_attn_bwd_custom_workspace_size(handle, q: fl_tensor, k: fl_tensor) -> int:
+    return lib().fl_attn_bwd_custom_workspace_size(handle, _ref(q), _ref(k))
+
+
 def fl_release_variant(handle) -> None:
     lib().fl_release_variant(handle)
 
@@ -339,10 +373,14 @@ def fl_release_variant(handle) -> None:
 class CustomVariant:
     """A variant compiled at run time from a score_mod and / or a mask expression (C syntax)."""
 
-    def __init__(self, score_mod: Optional[str], mask: Optional[str], D: int, base_mask: int = 0, aux=()):
-        """aux: up to four device tensors the expressions read as aux0 .. aux3 (kept alive by this object)."""
+    def __init__(self, score_mod: Optional[str], mask: Optional[str], D: int, base_mask: int = 0, aux=(),
+                 score_mod_grad: Optional[str] = None):
+        """aux: up to four device tensors the expressions read as aux0 .. aux3 (kept alive by this object).
+        score_mod_grad: derivative of score_mod with respect to s (compiles the backward kernels too)."""
         self.aux = list(aux)
-        if self.aux:
+        if score_mod_grad is not None:
+            st, h = fl_compile_variant_grad(score_mod, score_mod_grad, mask, D, self.aux, base_mask)
+        elif self.aux:
             st, h = fl_compile_variant_aux(score_mod, mask, D, self.aux, base_mask)
         else:
             st, h = fl_compile_variant(score_mod, mask, D, base_mask)
@@ -358,6 +396,14 @@ class CustomVariant:
         if self.aux:
             return fl_attn_fwd_custom_aux(self.handle, q, k, v, scale, self.aux, out, lse, stream, window, prefix_len)
         return fl_attn_fwd_custom(self.handle, q, k, v, scale, out, lse, stream, window, prefix_len)
+
+    def backward(self, q: fl_tensor, k: fl_tensor, v: fl_tensor, out: fl_tensor, dout: fl_tensor, lse: fl_tensor, scale: float,
+                 workspace, dq: fl_tensor, dk: fl_tensor, dv: fl_tensor, stream: int = 0, window: int = 0, prefix_len: int = 0) -> int:
+        return fl_attn_bwd_custom(self.handle, q, k, v, out, dout, lse, scale, self.aux, workspace, dq, dk, dv, stream, window,
+                                  prefix_len)
+
+    def backward_workspace_size(self, q: fl_tensor, k: fl_tensor) -> int:
+        return fl_attn_bwd_custom_workspace_size(self.handle, q, k)
 
     def skip_workspace_size(self, q: fl_tensor, k: fl_tensor) -> int:
         return fl_custom_skip_workspace_size(self.handle, q, k)

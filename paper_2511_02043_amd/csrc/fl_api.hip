@@ -243,10 +243,10 @@ const fl::BwdEntry* find_bwd_entry(const fl_variant_desc* d, int D, int nbias = 
   return fl::jit_backward_entry(D, (int)d->score_mod, (uint32_t)mask, nbias, same_dim->prep, same_dim->reduce);
 }
 
-hipError_t launch_bwd_dq(const fl::BwdEntry* be, const fl::BwdParams& p, int nblocks, hipStream_t stream) {
+hipError_t run_bwd_dq(const fl::BwdEntry* be, const fl::BwdParams& p, int nblocks, hipStream_t stream) {
   return be->jit != nullptr ? fl::jit_backward_launch(*be, 0, p, nblocks, stream) : be->dq(p, nblocks, stream);
 }
-hipError_t launch_bwd_dkdv(const fl::BwdEntry* be, const fl::BwdParams& p, int nblocks, hipStream_t stream) {
+hipError_t run_bwd_dkdv(const fl::BwdEntry* be, const fl::BwdParams& p, int nblocks, hipStream_t stream) {
   return be->jit != nullptr ? fl::jit_backward_launch(*be, 1, p, nblocks, stream) : be->dkdv(p, nblocks, stream);
 }
 
@@ -1014,9 +1014,22 @@ int fl_bwd_supported(const fl_variant_desc* desc, int dtype, int D, int Dv) {
   return bwd_ex_ok(desc, D, Dv) ? 1 : 0;
 }
 
+}  // extern "C"
+
+extern "C" {
+
 fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v, const fl_tensor* out,
                       const fl_tensor* dout, const fl_tensor* lse, const fl_variant_desc* desc, const fl_aux* aux,
                       fl_tensor* dq, fl_tensor* dk, fl_tensor* dv, void* stream_v) {
+  return fl::backward_call(q, k, v, out, dout, lse, desc, aux, dq, dk, dv, stream_v, nullptr, nullptr);
+}
+
+}  // extern "C"
+
+fl_status fl::backward_call(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v, const fl_tensor* out,
+                            const fl_tensor* dout, const fl_tensor* lse, const fl_variant_desc* desc, const fl_aux* aux,
+                            fl_tensor* dq, fl_tensor* dk, fl_tensor* dv, void* stream_v, const fl::BwdEntry* custom,
+                            const void* const* user_aux) {
   g_detail[0] = 0;
   fl_status st = check_desc(desc);
   if (st != FL_OK) return st;
@@ -1026,7 +1039,7 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   if (aux != nullptr && aux->struct_size != sizeof(fl_aux))
     return fail(FL_ERR_DESC, "aux->struct_size = %u, expected %zu", aux->struct_size, sizeof(fl_aux));
   if (q->dtype != FL_BF16) return fail(FL_ERR_DTYPE, "the backward pass takes bf16 inputs (q dtype %d)", q->dtype);
-  if (!bwd_simple(desc, q->size[4], v->size[4]))   // biases, epilogues, second stream, other head dims: the composed pass
+  if (custom == nullptr && !bwd_simple(desc, q->size[4], v->size[4]))   // biases, epilogues, second stream, other head dims: the composed pass
     return fl_attn_bwd_ex(q, k, v, out, dout, lse, desc, aux, dq, dk, dv, nullptr, stream_v);
 
   const int64_t B = q->size[0], G = q->size[1], H = q->size[2], Sq = q->size[3], D = q->size[4];
@@ -1036,7 +1049,7 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   if (Hkv <= 0 || H % (Hkv > 0 ? Hkv : 1) != 0)
     if (H != 0) return fail(FL_ERR_SHAPE, "k heads (%lld) must divide q heads (%lld)", (long long)Hkv, (long long)H);
   const uint32_t mask = canonical_mask(desc->mask);
-  const fl::BwdEntry* be = D == Dv ? find_bwd_entry(desc, (int)D, 0, true) : nullptr;
+  const fl::BwdEntry* be = custom != nullptr ? custom : (D == Dv ? find_bwd_entry(desc, (int)D, 0, true) : nullptr);
   if (be == nullptr)
     return fail(FL_ERR_UNSUPPORTED, "no backward specialisation for D=%lld Dv=%lld score_mod=%u mask=0x%x", (long long)D,
                 (long long)Dv, desc->score_mod, mask);
@@ -1106,6 +1119,7 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   p.window = clamp_window(desc->window, Sq + desc->q_offset, Sk);
   p.prefix = desc->prefix_len;
   p.q_off = desc->q_offset;
+  for (int n = 0; n < 4; ++n) p.user_aux[n] = user_aux != nullptr ? user_aux[n] : nullptr;
   p.scale = desc->scale;
   p.softcap = desc->softcap;
   p.dq_f32 = dq->dtype == FL_F32;
@@ -1138,11 +1152,11 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
     const int64_t nb_prep = (rows * lanes_per_row + 255) / 256;
     if ((e = be->prep(p, (int)nb_prep, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "pre-pass launch: %s", hipGetErrorString(e));
     // Sk == 0: the key loop is empty and dq comes out as zeros
-    if ((e = launch_bwd_dq(be, p, (int)nb_q, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dq launch: %s", hipGetErrorString(e));
+    if ((e = run_bwd_dq(be, p, (int)nb_q, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dq launch: %s", hipGetErrorString(e));
   }
   if (!no_keys) {
     // Sq == 0: the query loop is empty and dk, dv come out as zeros
-    if ((e = launch_bwd_dkdv(be, p, (int)nb_k, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dk/dv launch: %s", hipGetErrorString(e));
+    if ((e = run_bwd_dkdv(be, p, (int)nb_k, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dk/dv launch: %s", hipGetErrorString(e));
     if (p.hsplit > 1) {
       const int64_t chunks = B * G * Hkv * Sk * (D / 4);
       if ((e = be->reduce(p, (int)((chunks + 255) / 256), stream)) != hipSuccess)
@@ -1151,6 +1165,8 @@ fl_status fl_attn_bwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v
   }
   return FL_OK;
 }
+
+extern "C" {
 
 size_t fl_attn_bwd_ex_workspace_size(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v, const fl_variant_desc* desc) {
   if (q == nullptr || k == nullptr || v == nullptr || desc == nullptr) return 0;
@@ -1395,7 +1411,7 @@ fl_status fl_attn_bwd_ex(const fl_tensor* q, const fl_tensor* k, const fl_tensor
     p.dv = dense_view(ws + L.off_gv[s], G, Hkv, Sk, Dc);
     p.delta = (float*)(ws + L.off_delta[s]);
     p.lse2 = (float*)(ws + L.off_lse2[s]);
-    if ((e = launch_bwd_dq(be, p, (int)nb_q, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dq launch: %s", hipGetErrorString(e));
+    if ((e = run_bwd_dq(be, p, (int)nb_q, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dq launch: %s", hipGetErrorString(e));
     for (uint32_t nb = 0; nb < desc->n_bias; ++nb)
       if (dbias[nb].ptr != nullptr) {               // this stream's dS, summed over the axes the bias broadcasts along
         const fl_tensor* gt = &extra->dbias[nb];
@@ -1404,7 +1420,7 @@ fl_status fl_attn_bwd_ex(const fl_tensor* q, const fl_tensor* k, const fl_tensor
                            (int)H, (int)Sq, (int)Sk, (int)gt->size[0], (int)gt->size[1], (int)gt->size[2], (int)gt->size[3],
                            (int)gt->size[4], total, s);
       }
-    if ((e = launch_bwd_dkdv(be, p, (int)nb_k, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dk/dv launch: %s", hipGetErrorString(e));
+    if ((e = run_bwd_dkdv(be, p, (int)nb_k, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dk/dv launch: %s", hipGetErrorString(e));
     if (p.hsplit > 1) {
       const int64_t chunks = rows_k * (Dc / 4);
       if ((e = be->reduce(p, (int)((chunks + 255) / 256), stream)) != hipSuccess)

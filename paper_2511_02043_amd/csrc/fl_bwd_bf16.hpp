@@ -58,6 +58,7 @@ struct BwdParams {
   float* part_dv;
   BiasView bias[2];                // the forward pass's additive biases (kernels built with NBIAS > 0), bf16
   int32_t q_off;                   // query row i sits at sequence position i + q_off (positional masks, ALiBi); >= 0
+  const void* user_aux[4];         // run-time compiled variants: the caller's device arrays that the expressions read
   uint16_t* ds_stage;              // bias gradients wanted: dS of every score, bf16 dense [B, G, H, Sq, Sk]; the host sums it
                                    // over the axes each bias broadcasts along afterwards (null: not wanted)
 };
@@ -308,6 +309,34 @@ __device__ __forceinline__ bool hidden(int i, int j, int Sq, int Sk, int q_off, 
   return i >= Sq || j >= Sk || is_masked(MASK, i + q_off, j, window, prefix, qdoc, kdoc);
 }
 
+// Run-time compiled variants (kModCustom / kMaskCustom): the caller's expressions see the sizes of the call and their
+// captured arrays through the forward pass's parameter block; this is the part of it they read.
+__device__ __forceinline__ FwdParams user_context(const BwdParams& p) {
+  FwdParams u;
+  u.B = p.B; u.G = p.G; u.H = p.H; u.Sq = p.Sq; u.Sk = p.Sk;
+#pragma unroll
+  for (int n = 0; n < 4; ++n) u.user_aux[n] = p.user_aux[n];
+  return u;
+}
+// The score pipeline of a compiled score_mod replayed on the raw dot product x of (i, j) (valid indices): exponent
+// argument and derivative factor, as replay_score.
+template <int MOD>
+__device__ __forceinline__ float replay_user(float x, const BwdParams& p, const FwdParams& u, float lse2, int b, int g, int h,
+                                             int i, int j, float& fac) {
+  const int ic = i < p.Sq ? i : p.Sq - 1, jc = j < p.Sk ? j : p.Sk - 1;
+  const float s = x * p.scale;
+  fac = fl_user_score_mod_grad(s, b, g, h, ic + p.q_off, jc, u);
+  return fmaf(fl_user_score_mod(s, b, g, h, ic + p.q_off, jc, u), kLog2e, -lse2);
+}
+// hidden() with the compiled mask expression on top (evaluated on valid indices only)
+template <uint32_t MASK>
+__device__ __forceinline__ bool hidden_user(int i, int j, const BwdParams& p, const FwdParams& u, int b, int g, int h, int qdoc,
+                                            int kdoc) {
+  if (hidden<MASK>(i, j, p.Sq, p.Sk, p.q_off, p.window, p.prefix, qdoc, kdoc)) return true;
+  if constexpr ((MASK & kMaskCustom) != 0) return fl_user_mask(b, g, h, i + p.q_off, j, u);
+  return false;
+}
+
 // Offsets of the (b, g, h) slice of each bias / bias gradient (elements).
 template <int NBIAS>
 struct BiasHead {
@@ -442,6 +471,7 @@ bwd_dq_kernel(const BwdParams p) {
   }
   const int h = bh % p.H, g = (bh / p.H) % p.G, b = bh / (p.H * p.G);
   const int hk = h / (p.H / p.Hkv);
+  const FwdParams uctx = user_context(p);          // what a compiled variant's expressions read (unused otherwise)
   const int i0 = qt * C::BM, iw = i0 + 32 * wave;
   const int i = iw + w.col, ic = i < p.Sq ? i : p.Sq - 1;
   const int64_t srow = ((int64_t)(b * p.G + g) * p.H + h) * p.Sq + ic;
@@ -540,7 +570,7 @@ bwd_dq_kernel(const BwdParams p) {
       const int cls = classify_block(POS, iw + p.q_off, iw + 31 + p.q_off, j0 + 32 * nb, j0 + 32 * nb + 31, p.Sk, p.window, p.prefix,
                                      make_int2(0, 0), make_int2(0, 0));
       if (cls == kSkip) return;                    // nothing visible: dS = 0
-      const bool need_mask = (MASK & kMaskDoc) != 0 || iw + 31 >= p.Sq || cls != kFull;
+      const bool need_mask = (MASK & (kMaskDoc | kMaskCustom)) != 0 || iw + 31 >= p.Sq || cls != kFull;
       float bl[C::NBIAS > 0 ? 16 : 1];             // this lane's bias values of the block (requested before the matrix work)
       if constexpr (C::NBIAS > 0) {
 #pragma unroll
@@ -578,11 +608,13 @@ bwd_dq_kernel(const BwdParams p) {
           const int r = 2 * r2 + e;
           const int j = jb + 8 * (r >> 2) + (r & 3);
           float fac;
-          float a = replay_score<C::MOD>(s[r], c_scale, lse2, p.softcap, slope2, (float)(i + p.q_off - j), fac);
+          float a;
+          if constexpr (C::MOD == kModCustom) a = replay_user<C::MOD>(s[r], p, uctx, lse2, b, g, h, i, j, fac);
+          else a = replay_score<C::MOD>(s[r], c_scale, lse2, p.softcap, slope2, (float)(i + p.q_off - j), fac);
           if constexpr (C::NBIAS > 0) a += bl[r];
           pr[e] = fast_exp2(a);
           dbv[e] = dp[r] - delta;
-          dsv[e] = C::MOD == kModSoftcap ? dbv[e] * fac : dbv[e];
+          dsv[e] = (C::MOD == kModSoftcap || C::MOD == kModCustom) ? dbv[e] * fac : dbv[e];
         }
         if (need_mask) {                           // uniform; kept a branch: most tiles need no mask
           asm volatile("");
@@ -590,7 +622,7 @@ bwd_dq_kernel(const BwdParams p) {
           for (int e = 0; e < 2; ++e) {
             const int r = 2 * r2 + e;
             const int j = jb + 8 * (r >> 2) + (r & 3);
-            if (hidden<MASK>(i, j, p.Sq, p.Sk, p.q_off, p.window, p.prefix, qdoc, (MASK & kMaskDoc) ? kd[r] : 0)) pr[e] = 0.f;
+            if (hidden_user<MASK>(i, j, p, uctx, b, g, h, qdoc, (MASK & kMaskDoc) ? kd[r] : 0)) pr[e] = 0.f;
           }
         }
         dsv[0] *= pr[0];
@@ -703,6 +735,7 @@ bwd_dkdv_kernel(const BwdParams p) {
   const int h_first = hk * (p.H / p.Hkv) + split * group;
   const int j0 = kt * C::BM, jw = j0 + 32 * wave;
   const int j = jw + w.col, jc = j < p.Sk ? j : p.Sk - 1;
+  const FwdParams uctx = user_context(p);          // what a compiled variant's expressions read (unused otherwise)
 
   bf16x8 kf[KK], vf[KK];
   {
@@ -824,7 +857,7 @@ bwd_dkdv_kernel(const BwdParams p) {
     const int ib = t * BN + 32 * QB;
     const float slope2 = C::MOD == kModAlibi ? p.alibi_slopes[h] * kLog2e : 0.f;
     const int cls = classify_block(POS, ib + p.q_off, ib + 31 + p.q_off, jw, jw + 31, p.Sk, p.window, p.prefix, make_int2(0, 0), make_int2(0, 0));
-    const bool need_mask = (MASK & kMaskDoc) != 0 || ib + 31 >= p.Sq || cls != kFull;
+    const bool need_mask = (MASK & (kMaskDoc | kMaskCustom)) != 0 || ib + 31 >= p.Sq || cls != kFull;
     uint32_t ra_n[KK], ta_c[DB][2];
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) ra_n[kk] = w.ra[kk] + base_n;
@@ -887,11 +920,13 @@ bwd_dkdv_kernel(const BwdParams p) {
         const int i = irow + 8 * (r >> 2) + (r & 3);
         const float lse2 = __int_as_float(st_l[r >> 2][r & 3]), delta = __int_as_float(st_d[r >> 2][r & 3]);
         float fac;
-        float a = replay_score<C::MOD>(cur.s[r], c_scale, lse2, p.softcap, slope2, (float)(i + p.q_off - j), fac);
+        float a;
+        if constexpr (C::MOD == kModCustom) a = replay_user<C::MOD>(cur.s[r], p, uctx, lse2, b, g, h, i, j, fac);
+        else a = replay_score<C::MOD>(cur.s[r], c_scale, lse2, p.softcap, slope2, (float)(i + p.q_off - j), fac);
         if constexpr (C::NBIAS > 0) a += bl[r];
         pv[e] = fast_exp2(a);
         dsv[e] = cur.dp[r] - delta;
-        if constexpr (C::MOD == kModSoftcap) dsv[e] *= fac;
+        if constexpr (C::MOD == kModSoftcap || C::MOD == kModCustom) dsv[e] *= fac;
       }
       if (need_mask) {                             // uniform; kept a branch: most blocks need no mask
         asm volatile("");
@@ -899,7 +934,7 @@ bwd_dkdv_kernel(const BwdParams p) {
         for (int e = 0; e < 2; ++e) {
           const int r = 2 * r2 + e;
           const int i = irow + 8 * (r >> 2) + (r & 3);
-          if (hidden<MASK>(i, j, p.Sq, p.Sk, p.q_off, p.window, p.prefix, (MASK & kMaskDoc) ? qd[r] : 0, kdoc)) pv[e] = 0.f;
+          if (hidden_user<MASK>(i, j, p, uctx, b, g, h, (MASK & kMaskDoc) ? qd[r] : 0, kdoc)) pv[e] = 0.f;
         }
       }
       dsv[0] *= pv[0];
@@ -1000,6 +1035,7 @@ bwd_dkdv_ws_kernel(const BwdParams p) {
   constexpr int D = C::D, BN = C::BN, NB = C::NB, KK = C::KK, DB = C::DB, ROW = C::ROW;
   constexpr uint32_t MASK = C::MASK;
   constexpr uint32_t POS = MASK & ~kMaskDoc;
+  static_assert(C::MOD != kModCustom && (MASK & kMaskCustom) == 0, "compiled variants run the plain dK/dV kernel");
   constexpr int NWS = 8;                           // waves of the workgroup
   constexpr int NSTAGE = 3;
   constexpr int XBUF = 64 * 16 * 4;                // one exchange buffer: 16 floats per lane, [quad][lane][4]

@@ -2,6 +2,9 @@
 #pragma once
 #include "fl_bwd_bf16.hpp"
 #include <atomic>
+#include <string>
+#include <vector>
+#include "../../include/fl_attn.h"
 #include "fl_registry.hpp"
 
 namespace fl {
@@ -27,6 +30,11 @@ struct BwdEntry {
 const BwdEntry* jit_backward_entry(int D, int mod, uint32_t mask, int nbias, BwdLaunchFn prep, BwdLaunchFn reduce);
 // which: 0 = the dQ kernel, 1 = the dK/dV kernel
 hipError_t jit_backward_launch(const BwdEntry& e, int which, const BwdParams& p, int nblocks, hipStream_t stream);
+// A run-time entry around an already compiled code object with the two kernels (variants compiled from expressions);
+// owned by the caller, released with jit_backward_release.
+BwdEntry* jit_backward_wrap(const std::vector<char>& code, const std::string& dq_name, const std::string& dkdv_name, int D, int mod,
+                            uint32_t mask, BwdLaunchFn prep, BwdLaunchFn reduce);
+void jit_backward_release(BwdEntry* e);
 
 template <class K>
 hipError_t raise_lds_limit(K kernel) {
@@ -88,6 +96,12 @@ constexpr BwdEntry bwd_entry() {
   else
     return BwdEntry{BwdKey{D, MOD, (int)MASK, NBIAS}, CQ::BM, &launch_bwd_prep<D>, &launch_bwd_dq<CQ>, &launch_bwd_dkdv<CK>, &launch_bwd_reduce<D>, nullptr};
 }
+
+// The call behind fl_attn_bwd (fl_api.hip).  custom / user_aux: the backward kernels of a variant compiled at run time from
+// expressions and the arrays its expressions read, instead of the specialisation the descriptor names.
+fl_status backward_call(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v, const fl_tensor* out, const fl_tensor* dout,
+                        const fl_tensor* lse, const fl_variant_desc* desc, const fl_aux* aux, fl_tensor* dq, fl_tensor* dk,
+                        fl_tensor* dv, void* stream, const BwdEntry* custom, const void* const* user_aux);
 
 const BwdEntry* entries_bwd64(int* n);
 const BwdEntry* entries_bwd128(int* n);

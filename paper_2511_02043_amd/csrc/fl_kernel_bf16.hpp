@@ -296,7 +296,9 @@ struct Wave {
         const float d = slope_l2 * (float)(i[rb] + p.q_off - j0 - 32 * nb - 4 * half);
         x = fmaf(x, c_scale, -fabsf(d - alibi_c[r]));
       } else if constexpr (C::MOD == kModCustom) {
-        x = fl_user_score_mod(x * p.scale, b, g, h, i[rb] + p.q_off, j, p) * kLog2e;
+        // (rows past Sq and keys past Sk are computed like the last valid ones and never used: an expression that
+        // indexes a captured array by i or j must not be handed an index outside the call's sizes)
+        x = fl_user_score_mod(x * p.scale, b, g, h, ic[rb] + p.q_off, j < p.Sk ? j : p.Sk - 1, p) * kLog2e;
       } else {
         x *= c_scale;
       }
@@ -444,7 +446,8 @@ struct Wave {
           bool hide = c > d_hi[rb];
           if constexpr ((MASK & kMaskWindow) != 0) hide = hide || c < d_lo[rb];
           if constexpr ((MASK & kMaskDoc) != 0) hide = hide || kd[r] != qdoc[rb];
-          if constexpr ((MASK & kMaskCustom) != 0) hide = hide || fl_user_mask(b, g, h, i[rb] + p.q_off, jl + c, p);
+          if constexpr ((MASK & kMaskCustom) != 0)  // (valid indices only, as for the score_mod; a key past Sk is hidden already)
+            hide = hide || fl_user_mask(b, g, h, ic[rb] + p.q_off, jl + c < p.Sk ? jl + c : p.Sk - 1, p);
           if (hide) sc[rb][nb][r] = -INFINITY;
         }
     }

@@ -100,6 +100,8 @@ struct FwdParams {
 // new score from the scaled score s of query i and key j (Eq. 4's score_mod); p gives the expression
 // the call's sizes and the caller's captured arrays
 __device__ float fl_user_score_mod(float s, int b, int g, int h, int i, int j, const fl::FwdParams& p);
+// derivative of fl_user_score_mod with respect to s at the same arguments (the backward pass of a compiled variant)
+__device__ float fl_user_score_mod_grad(float s, int b, int g, int h, int i, int j, const fl::FwdParams& p);
 // true where the score of (i, j) is to be replaced by -inf (the mask_mod of Sec. 2.2, inverted)
 __device__ bool fl_user_mask(int b, int g, int h, int i, int j, const fl::FwdParams& p);
 namespace fl {

@@ -39,6 +39,10 @@ struct fl_custom_variant {
   hipModule_t module[64] = {};     // loaded lazily, once per device
   hipFunction_t func[64] = {};
   hipFunction_t map_func[64] = {};
+  // backward pass: the expressions are kept, the two backward kernels are compiled when first needed
+  std::string mod_expr, grad_expr, mask_expr;
+  bool has_mod = false;
+  fl::BwdEntry* bwd = nullptr;
 };
 
 namespace {
@@ -246,6 +250,26 @@ hipError_t jit_backward_launch(const BwdEntry& e, int which, const BwdParams& p,
   return hipModuleLaunchKernel(f, (unsigned)nblocks, 1, 1, 256, 1, 1, 0, stream, args, nullptr);
 }
 
+BwdEntry* jit_backward_wrap(const std::vector<char>& code, const std::string& dq_name, const std::string& dkdv_name, int D, int mod,
+                            uint32_t mask, BwdLaunchFn prep, BwdLaunchFn reduce) {
+  JitBackward* j = new JitBackward;
+  j->dq.code = code;
+  j->dkdv.code = code;
+  j->dq.kernel_name = dq_name;
+  j->dkdv.kernel_name = dkdv_name;
+  j->entry = BwdEntry{BwdKey{D, mod, (int)mask, 0}, 128, prep, nullptr, nullptr, reduce, j};
+  return &j->entry;
+}
+
+void jit_backward_release(BwdEntry* e) {
+  if (e == nullptr) return;
+  JitBackward* j = (JitBackward*)e->jit;
+  for (LoadedKernel* k : {&j->dq, &j->dkdv})
+    for (int d = 0; d < 64; ++d)
+      if (k->module[d] != nullptr) (void)hipModuleUnload(k->module[d]);
+  delete j;
+}
+
 }  // namespace fl
 
 extern "C" {
@@ -257,6 +281,59 @@ fl_status fl_compile_variant(const char* score_mod_expr, const char* mask_expr, 
 
 fl_status fl_compile_variant_aux(const char* score_mod_expr, const char* mask_expr, uint32_t base_mask, int D,
                                  const int32_t* aux_dtypes, fl_custom_variant** handle) {
+  return fl_compile_variant_grad(score_mod_expr, nullptr, mask_expr, base_mask, D, aux_dtypes, handle);
+}
+
+// The three device functions that wrap a variant's expressions (what an expression sees besides its arguments: the
+// call's sizes and the captured arrays aux0 .. aux3; bf16 arrays read as float through a one-field wrapper).
+static std::string hook_source(const fl_custom_variant* v, bool with_grad) {
+  std::string scope = "  const int B = fl_p.B, G = fl_p.G, H = fl_p.H, Sq = fl_p.Sq, Sk = fl_p.Sk; (void)B; (void)G; (void)H; (void)Sq; (void)Sk;\n";
+  for (int n = 0; n < 4; ++n) {
+    if (v->aux_dtype[n] == 0) continue;
+    const char* ty = v->aux_dtype[n] == FL_I32 ? "int" : (v->aux_dtype[n] == FL_F32 ? "float" : "fl_bf16_elem");
+    char line[160];
+    snprintf(line, sizeof(line), "  const %s* aux%d = (const %s*)fl_p.user_aux[%d]; (void)aux%d;\n", ty, n, ty, n, n);
+    scope += line;
+  }
+  std::string src = "struct fl_bf16_elem { unsigned short u; __device__ operator float() const { return __uint_as_float((unsigned)u << 16); } };\n";
+  src += "__device__ float fl_user_score_mod(float s, int b, int g, int h, int i, int j, const fl::FwdParams& fl_p) {\n" + scope + "  return (";
+  src += v->has_mod ? v->mod_expr : std::string("s");
+  src += "); }\n";
+  if (with_grad) {
+    src += "__device__ float fl_user_score_mod_grad(float s, int b, int g, int h, int i, int j, const fl::FwdParams& fl_p) {\n" + scope + "  return (";
+    src += v->grad_expr.empty() ? std::string("1.0f") : v->grad_expr;
+    src += "); }\n";
+  }
+  src += "__device__ bool fl_user_mask(int b, int g, int h, int i, int j, const fl::FwdParams& fl_p) {\n" + scope + "  return (";
+  src += v->has_mask_expr ? v->mask_expr : std::string("false");
+  src += "); }\n";
+  return src;
+}
+
+// The two backward kernels of a variant, compiled when its backward pass is first asked for.
+static fl_status compile_backward(fl_custom_variant* v) {
+  std::lock_guard<std::mutex> lock(v->mu);
+  if (v->bwd != nullptr) return FL_OK;
+  const int mod = v->has_mod ? fl::kModCustom : fl::kModNone;
+  char cq[160], ck[160];
+  snprintf(cq, sizeof(cq), "fl::BwdCfg<%d, %d, %uu, 64, 2, 0>", v->D, mod, v->mask);
+  snprintf(ck, sizeof(ck), "fl::BwdCfg<%d, %d, %uu, 64, %d, 0>", v->D, mod, v->mask, v->D == 128 ? 1 : 2);
+  const std::string iq = std::string("fl::bwd_dq_kernel<") + cq + ">", ik = std::string("fl::bwd_dkdv_kernel<") + ck + ">";
+  std::string src = "#define FL_LDS_STATIC 1\n#include \"fl_bwd_bf16.hpp\"\n" + hook_source(v, true);
+  src += "template __global__ void " + iq + "(const fl::BwdParams);\n";
+  src += "template __global__ void " + ik + "(const fl::BwdParams);\n";
+  std::vector<char> code;
+  std::vector<std::string> names;
+  const fl_status st = compile_program(src, {iq, ik}, "backward pass of the variant does not compile", &code, &names);
+  if (st != FL_OK) return st;
+  int n = 0;
+  const fl::BwdEntry* tab = v->D == 128 ? fl::entries_bwd128(&n) : fl::entries_bwd64(&n);
+  v->bwd = fl::jit_backward_wrap(code, names[0], names[1], v->D, mod, v->mask, tab[0].prep, tab[0].reduce);
+  return FL_OK;
+}
+
+fl_status fl_compile_variant_grad(const char* score_mod_expr, const char* score_mod_grad_expr, const char* mask_expr,
+                                  uint32_t base_mask, int D, const int32_t* aux_dtypes, fl_custom_variant** handle) {
   fl::host::clear_detail();
   if (handle == nullptr) return fl::host::fail(FL_ERR_NULL, "handle is NULL");
   *handle = nullptr;
@@ -267,8 +344,11 @@ fl_status fl_compile_variant_aux(const char* score_mod_expr, const char* mask_ex
   if ((base_mask & FL_MASK_PREFIX) && (base_mask & (FL_MASK_CAUSAL | FL_MASK_WINDOW)))
     return fl::host::fail(FL_ERR_DESC, "FL_MASK_PREFIX excludes FL_MASK_CAUSAL and FL_MASK_WINDOW");
   if (base_mask & FL_MASK_WINDOW) base_mask |= FL_MASK_CAUSAL;
-  if ((score_mod_expr && !expression_ok(score_mod_expr)) || (mask_expr && !expression_ok(mask_expr)))
+  if ((score_mod_expr && !expression_ok(score_mod_expr)) || (mask_expr && !expression_ok(mask_expr)) ||
+      (score_mod_grad_expr && !expression_ok(score_mod_grad_expr)))
     return fl::host::fail(FL_ERR_DESC, "an expression may not contain ; { } # \" \\ or a line break");
+  if (score_mod_grad_expr != nullptr && score_mod_expr == nullptr)
+    return fl::host::fail(FL_ERR_DESC, "a derivative expression without a score_mod expression");
 
   int adt[4] = {0, 0, 0, 0};
   for (int n = 0; n < 4 && aux_dtypes != nullptr; ++n) {
@@ -281,23 +361,19 @@ fl_status fl_compile_variant_aux(const char* score_mod_expr, const char* mask_ex
   const unsigned mask = (mask_expr ? fl::kMaskCustom : 0u) | base_mask;
   char inst[256];
   snprintf(inst, sizeof(inst), "fl::fwd_bf16_kernel<fl::Bf16Cfg<%d, %d, %d, 1, %d, 2, %d, %uu, 0, false, 0u>>", D, D, waves_for(D), kBN, mod, mask);
-  // what an expression sees besides its arguments: the call's sizes and the captured arrays aux0 .. aux3
-  // (bf16 arrays read as float through a one-field wrapper)
-  std::string scope = "  const int B = fl_p.B, G = fl_p.G, H = fl_p.H, Sq = fl_p.Sq, Sk = fl_p.Sk; (void)B; (void)G; (void)H; (void)Sq; (void)Sk;\n";
-  for (int n = 0; n < 4; ++n) {
-    if (adt[n] == 0) continue;
-    const char* ty = adt[n] == FL_I32 ? "int" : (adt[n] == FL_F32 ? "float" : "fl_bf16_elem");
-    char line[160];
-    snprintf(line, sizeof(line), "  const %s* aux%d = (const %s*)fl_p.user_aux[%d]; (void)aux%d;\n", ty, n, ty, n, n);
-    scope += line;
-  }
-  std::string src = "#include \"fl_kernel_bf16.hpp\"\n";
-  src += "struct fl_bf16_elem { unsigned short u; __device__ operator float() const { return __uint_as_float((unsigned)u << 16); } };\n";
-  src += "__device__ float fl_user_score_mod(float s, int b, int g, int h, int i, int j, const fl::FwdParams& fl_p) {\n" + scope + "  return (";
-  src += score_mod_expr ? score_mod_expr : "s";
-  src += "); }\n__device__ bool fl_user_mask(int b, int g, int h, int i, int j, const fl::FwdParams& fl_p) {\n" + scope + "  return (";
-  src += mask_expr ? mask_expr : "false";
-  src += "); }\ntemplate __global__ void ";
+  fl_custom_variant* v = new fl_custom_variant;
+  v->D = D;
+  v->waves = waves_for(D);
+  for (int n = 0; n < 4; ++n) v->aux_dtype[n] = adt[n];
+  v->mask = mask;
+  v->has_mod = score_mod_expr != nullptr;
+  v->has_mask_expr = mask_expr != nullptr;
+  v->per_head = mask_expr != nullptr && (mentions(mask_expr, "h") || mentions(mask_expr, "g"));
+  if (score_mod_expr) v->mod_expr = score_mod_expr;
+  if (score_mod_grad_expr) v->grad_expr = score_mod_grad_expr;
+  if (mask_expr) v->mask_expr = mask_expr;
+  std::string src = "#include \"fl_kernel_bf16.hpp\"\n" + hook_source(v, false);
+  src += "template __global__ void ";
   src += inst;
   src += "(const fl::FwdParams);\n";
   std::vector<std::string> insts = {inst};
@@ -308,15 +384,11 @@ fl_status fl_compile_variant_aux(const char* score_mod_expr, const char* mask_ex
     insts.push_back(minst);
   }
 
-  fl_custom_variant* v = new fl_custom_variant;
-  v->D = D;
-  v->waves = waves_for(D);
-  for (int n = 0; n < 4; ++n) v->aux_dtype[n] = adt[n];
-  v->mask = mask;
-  v->has_mask_expr = mask_expr != nullptr;
-  v->per_head = mask_expr != nullptr && (mentions(mask_expr, "h") || mentions(mask_expr, "g"));
   std::vector<std::string> names;
-  const fl_status st = compile_program(src, insts, "expression does not compile", &v->code, &names);
+  fl_status st = compile_program(src, insts, "expression does not compile", &v->code, &names);
+  // a derivative expression is given by callers who want the backward pass: its kernels are compiled now, so that an
+  // error in that expression is reported here
+  if (st == FL_OK && score_mod_grad_expr != nullptr) st = compile_backward(v);
   if (st != FL_OK) {
     delete v;
     return st;
@@ -331,6 +403,7 @@ void fl_release_variant(fl_custom_variant* v) {
   if (v == nullptr) return;
   for (int d = 0; d < 64; ++d)
     if (v->module[d] != nullptr) (void)hipModuleUnload(v->module[d]);
+  fl::jit_backward_release(v->bwd);
   delete v;
 }
 
@@ -484,6 +557,49 @@ static fl_status custom_forward(fl_custom_variant* v, const fl_tensor* q, const 
   e = hipModuleLaunchKernel(v->func[dev], (unsigned)nblocks, 1, 1, (unsigned)v->waves * 64, 1, 1, (unsigned)p.lds_bytes, (hipStream_t)stream_v, args, nullptr);
   if (e != hipSuccess) return fl::host::fail(FL_ERR_LAUNCH, "custom variant launch: %s", hipGetErrorString(e));
   return FL_OK;
+}
+
+size_t fl_attn_bwd_custom_workspace_size(fl_custom_variant* v, const fl_tensor* q, const fl_tensor* k) {
+  if (v == nullptr || q == nullptr || k == nullptr) return 0;
+  fl_variant_desc d;
+  memset(&d, 0, sizeof(d));
+  d.struct_size = sizeof(d);
+  d.scale = 1.f;
+  d.mask = v->mask & (FL_MASK_CAUSAL | FL_MASK_WINDOW | FL_MASK_PREFIX);
+  return fl_attn_bwd_workspace_size(q, k, &d);
+}
+
+fl_status fl_attn_bwd_custom(fl_custom_variant* v, const fl_tensor* q, const fl_tensor* k, const fl_tensor* vv, const fl_tensor* out,
+                             const fl_tensor* dout, const fl_tensor* lse, float scale, int32_t window, int32_t prefix_len,
+                             const void* const* aux_ptrs, void* workspace, size_t workspace_bytes, fl_tensor* dq, fl_tensor* dk,
+                             fl_tensor* dv, void* stream_v) {
+  fl::host::clear_detail();
+  if (v == nullptr) return fl::host::fail(FL_ERR_NULL, "handle is NULL");
+  if (!(scale > 0.f) || scale != scale || scale > 3.0e38f) return fl::host::fail(FL_ERR_DESC, "scale must be finite and > 0");
+  for (int n = 0; n < 4; ++n)
+    if (v->aux_dtype[n] != 0 && (aux_ptrs == nullptr || aux_ptrs[n] == nullptr))
+      return fl::host::fail(FL_ERR_AUX_MISSING, "this variant reads aux%d, which was not given", n);
+  if (q != nullptr && (q->size[4] != v->D || (vv != nullptr && vv->size[4] != v->D)))
+    return fl::host::fail(FL_ERR_SHAPE, "this variant was compiled for head dim %d", v->D);
+  fl_status st = compile_backward(v);
+  if (st != FL_OK) return st;
+  // the structural part of the variant as a descriptor: the backward call checks tensors, sizes the launches and fills the
+  // parameter block from it; the kernels are the variant's own
+  fl_variant_desc d;
+  memset(&d, 0, sizeof(d));
+  d.struct_size = sizeof(d);
+  d.scale = scale;
+  d.mask = v->mask & (FL_MASK_CAUSAL | FL_MASK_WINDOW | FL_MASK_PREFIX);
+  d.window = (d.mask & FL_MASK_WINDOW) ? window : 0;
+  d.prefix_len = (d.mask & FL_MASK_PREFIX) ? prefix_len : 0;
+  fl_aux a;
+  memset(&a, 0, sizeof(a));
+  a.struct_size = sizeof(a);
+  a.workspace = workspace;
+  a.workspace_bytes = workspace_bytes;
+  const void* ptrs[4];
+  for (int n = 0; n < 4; ++n) ptrs[n] = (aux_ptrs != nullptr && v->aux_dtype[n] != 0) ? aux_ptrs[n] : nullptr;
+  return fl::backward_call(q, k, vv, out, dout, lse, &d, &a, dq, dk, dv, stream_v, v->bwd, ptrs);
 }
 
 }  // extern "C"

@@ -398,3 +398,56 @@ def test_query_offset_backward(kind):
         np.testing.assert_allclose(dq, dqf[:, :, :, off:], rtol=0, atol=1e-13)
         np.testing.assert_allclose(dk, dkf, rtol=0, atol=1e-13)
         np.testing.assert_allclose(dv, dvf, rtol=0, atol=1e-13)
+
+
+# --- arbitrary score_mod / mask callables -------------------------------------------------------------------------------
+
+def test_custom_backward_equals_the_named_variants_written_as_callables():
+    """Soft-cap + causal and ALiBi + window as callables against attention_backward's own branches."""
+    from paper_2511_02043_amd import inputs
+    w = inputs.causal_bf16(B=1, H=4, Hkv=2, S=37, Sk=53, D=16, causal=False, salt=31)
+    dout = inputs.dout_for(w)
+    cap = 1.7
+    a = bo.attention_custom_backward(w.q, w.k, w.v, dout, scale=w.scale,
+                                     score_mod=lambda s, b, g, h, i, j: cap * np.tanh(s / cap),
+                                     score_mod_grad=lambda s, b, g, h, i, j: 1.0 - np.tanh(s / cap) ** 2,
+                                     mask=lambda b, g, h, i, j: j > i)
+    r = bo.attention_backward(w.q, w.k, w.v, dout, scale=w.scale, causal=True, softcap_value=cap)
+    for x, y in zip(a, r):
+        np.testing.assert_allclose(x, y, rtol=0, atol=1e-13)
+    slopes = inputs.alibi_slopes(4).astype(np.float64)
+    a = bo.attention_custom_backward(w.q, w.k, w.v, dout, scale=w.scale,
+                                     score_mod=lambda s, b, g, h, i, j: s - slopes[h] * np.abs(i - j),
+                                     mask=lambda b, g, h, i, j: (j > i) | (i - j > 9))
+    r = bo.attention_backward(w.q, w.k, w.v, dout, scale=w.scale, causal=True, window=9, alibi_slopes=slopes)
+    for x, y in zip(a, r):
+        np.testing.assert_allclose(x, y, rtol=0, atol=1e-13)
+
+
+def test_custom_backward_against_finite_differences_of_the_forward_oracle():
+    """A score_mod that is neither additive nor monotone in a simple way, a mask that reads h, grouped heads."""
+    from oracle import attention_oracle as ao
+    rng = np.random.Generator(np.random.PCG64(77))
+    B, G, H, Hkv, Sq, Sk, D = 1, 1, 2, 1, 5, 7, 4
+    q, k, v = rng.normal(size=(B, G, H, Sq, D)), rng.normal(size=(B, G, Hkv, Sk, D)), rng.normal(size=(B, G, Hkv, Sk, D))
+    dout = rng.normal(size=(B, G, H, Sq, D))
+    mod = lambda s, b, g, h, i, j: 2.0 * np.sin(0.7 * s) + 0.1 * s * s - 0.05 * (h + 1) * np.abs(i - j)
+    grad = lambda s, b, g, h, i, j: 1.4 * np.cos(0.7 * s) + 0.2 * s
+    msk = lambda b, g, h, i, j: ((i + j + h) % 3 == 0) & (j > 0)
+    dq, dk, dv = bo.attention_custom_backward(q, k, v, dout, scale=0.5, score_mod=mod, score_mod_grad=grad, mask=msk)
+
+    def loss(q_, k_, v_):
+        o, _ = ao.attention_custom(q_, k_, v_, scale=0.5, score_mod=mod, mask=msk)
+        return float(np.sum(o * dout))
+
+    eps = 1e-6
+    for name, x, gx in (("q", q, dq), ("k", k, dk), ("v", v, dv)):
+        flat = x.reshape(-1)
+        for idx in rng.choice(flat.size, size=12, replace=False):
+            old = flat[idx]
+            flat[idx] = old + eps
+            up = loss(q, k, v)
+            flat[idx] = old - eps
+            dn = loss(q, k, v)
+            flat[idx] = old
+            np.testing.assert_allclose(gx.reshape(-1)[idx], (up - dn) / (2 * eps), rtol=2e-6, atol=2e-8, err_msg=name)
