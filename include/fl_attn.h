@@ -303,21 +303,22 @@ size_t fl_attn_decode_workspace_size(const fl_tensor* q, const fl_tensor* k_cach
  *   desc     scale, score_mod, FL_MASK_CAUSAL and / or FL_MASK_WINDOW (or no mask bit: causal all the same);
  *            other masks, biases, the second stream, epilogues and q_offset are FL_ERR_UNSUPPORTED
  *   aux      alibi_slopes for FL_MOD_ALIBI, and aux->workspace of fl_attn_prefill_paged_workspace_size bytes
- *            (16-byte aligned; contents undefined afterwards)
+ *            (16-byte aligned; contents undefined afterwards); may be NULL when neither is needed
  *
- * How: one pass copies the cached rows of every sequence, through its block table, into dense key / value
- * tensors of max_seq_len rows; then the forward kernel runs on them, reading each sequence's length on the
- * device: it stops at that length and places the query rows at its last Sq positions, so a short sequence
- * costs its own length and nothing is synchronised with the host.  The copy reads and writes the cached
- * rows once (2 * 2 * len * Hkv * D * 2 bytes per sequence), small beside the Sq * len scores of a chunk of
- * tens of rows or more; for single rows fl_attn_decode reads the pages in place.
+ * How: the forward kernel runs with each sequence's length read on the device: it stops at that length and places the
+ * query rows at its last Sq positions, so a short sequence costs its own length and nothing is synchronised with the
+ * host.  For chunks of up to 256 rows its key / value tile loads go to the pages themselves (page numbers from the block
+ * table, fetched a step ahead; needs page_size >= 512 / D with a block table): no copy and no workspace.  For longer
+ * chunks one pass first copies the cached rows of every sequence into dense tensors in the workspace (2 * 2 * len * Hkv
+ * * D * 2 bytes read and written per sequence, small beside the Sq * len scores of such a chunk) and the tuned dense
+ * kernel runs on those.  fl_attn_prefill_paged_workspace_size says which: 0 for the first way.
  * Stream, ownership and error rules as for fl_attn_fwd.                                                  */
 fl_status fl_attn_prefill_paged(const fl_tensor* q, const fl_tensor* k_cache, const fl_tensor* v_cache,
                                 const fl_paged_kv* kv, const fl_variant_desc* desc, const fl_aux* aux,
                                 fl_tensor* out, fl_tensor* lse, void* stream);
 
-/* Bytes of aux->workspace that fl_attn_prefill_paged needs: the dense copies, 2 * B * Hkv * max_seq_len * D * 2
- * bytes (each rounded up to 256). */
+/* Bytes of aux->workspace that fl_attn_prefill_paged needs: 0 when the pages are read in place, else the dense
+ * copies, 2 * B * Hkv * max_seq_len * D * 2 bytes (each rounded up to 256). */
 size_t fl_attn_prefill_paged_workspace_size(const fl_tensor* q, const fl_tensor* k_cache, const fl_paged_kv* kv);
 
 /* A variant compiled at run time from user expressions (opaque; owned by the caller until released). */

@@ -93,7 +93,7 @@ __device__ __forceinline__ int swz_v(int r, int c) {
 }
 
 template <int D_, int DV_, int NWAVES_, int RB_, int BN_, int WPE_, int MOD_, uint32_t MASK_, int NBIAS_,
-          bool DIFF_, uint32_t EPI_, int RING_ = 2>
+          bool DIFF_, uint32_t EPI_, int RING_ = 2, bool PAGED_ = false>
 struct Bf16Cfg {
   static constexpr int D = D_, DV = DV_, NWAVES = NWAVES_, RB = RB_, BN = BN_, MOD = MOD_, NBIAS = NBIAS_;
   static constexpr uint32_t MASK = MASK_, EPI = EPI_;
@@ -136,6 +136,13 @@ struct Bf16Cfg {
   static constexpr int V_ROWS_PI = 64 / (DV / 8);
   static_assert(NWAVES % 4 == 0, "the direct-load lane offsets assume NWAVES % 4 == 0");
   static_assert(!(DIFF_ && RB_ != 1), "the two-stream path keeps one row block per wave");
+  // Keys and values read in place from a paged cache (a chunk of query rows per sequence, Sec. 4.1 serving): every
+  // direct-load instruction of a tile covers K_ROWS_PI consecutive tokens, which lie in one page (pages hold a power of two
+  // >= K_ROWS_PI tokens), so per instruction only a uniform base address changes; the page numbers come from the
+  // sequence's block table, fetched a step ahead.
+  static constexpr bool PAGED = PAGED_;
+  static_assert(!PAGED_ || (!DIFF_ && NBIAS_ == 0 && RING_ == 2 && D_ == DV_ && (MASK_ & (kMaskDoc | kMaskCustom)) == 0),
+                "paged keys: one stream, no bias, two ring slots, D == Dv, positional masks");
 };
 
 enum TileClass : int { kTileSkip = 0, kTileFull = 1, kTilePartial = 2 };
@@ -1004,12 +1011,15 @@ fwd_bf16_kernel(const FwdParams call) {
     const int dst_row = v_instr(u) * C::V_ROWS_PI + vr_lane;
     return (uint32_t)row * (uint32_t)vss + (uint32_t)swz_v<DV>(dst_row, lane % (DV / 8)) * 16u;
   };
+  // (paged keys: the uniform base of an instruction already points at its first token, a lane adds its row within
+  // the instruction; in a ragged tile tokens past the last one are replaced by the last one, which lies in the page
+  // of the instruction's -- likewise cut -- first token)
 #pragma unroll
   for (int u = 0; u < KPW; ++u)
 #pragma unroll
-    for (int s = 0; s < NS; ++s) k_off[s][u] = k_lane_off(s, u, k_instr(u) * C::K_ROWS_PI + kr_lane);
+    for (int s = 0; s < NS; ++s) k_off[s][u] = k_lane_off(s, u, C::PAGED ? kr_lane : k_instr(u) * C::K_ROWS_PI + kr_lane);
 #pragma unroll
-  for (int u = 0; u < VPW; ++u) v_off[u] = v_lane_off(u, v_instr(u) * C::V_ROWS_PI + vr_lane);
+  for (int u = 0; u < VPW; ++u) v_off[u] = v_lane_off(u, C::PAGED ? vr_lane : v_instr(u) * C::V_ROWS_PI + vr_lane);
   auto clamp_k = [&](int t) __attribute__((always_inline)) {
     const int nvalid = p.Sk - t * BN;              // uniform
     if (nvalid < BN) {
@@ -1018,7 +1028,10 @@ fwd_bf16_kernel(const FwdParams call) {
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
           const int row = k_instr(u) * C::K_ROWS_PI + kr_lane;
-          k_off[s][u] = k_lane_off(s, u, row < nvalid ? row : nvalid - 1);
+          if constexpr (C::PAGED)
+            k_off[s][u] = k_lane_off(s, u, min(row, nvalid - 1) - min(k_instr(u) * C::K_ROWS_PI, nvalid - 1));
+          else
+            k_off[s][u] = k_lane_off(s, u, row < nvalid ? row : nvalid - 1);
         }
     }
   };
@@ -1028,9 +1041,27 @@ fwd_bf16_kernel(const FwdParams call) {
 #pragma unroll
       for (int u = 0; u < VPW; ++u) {
         const int row = v_instr(u) * C::V_ROWS_PI + vr_lane;
-        v_off[u] = v_lane_off(u, row < nvalid ? row : nvalid - 1);
+        if constexpr (C::PAGED)
+          v_off[u] = v_lane_off(u, min(row, nvalid - 1) - min(v_instr(u) * C::V_ROWS_PI, nvalid - 1));
+        else
+          v_off[u] = v_lane_off(u, row < nvalid ? row : nvalid - 1);
       }
     }
+  };
+  // paged keys: the page of load instruction u of tile t (every lane the same value; t < t_hi, so the sequence has a token)
+  auto page_of_lane = [&](int t, int u) __attribute__((always_inline)) -> int {
+    if (p.block_table == nullptr) return b;        // one page per sequence
+    const int token = min(t * BN + k_instr(u) * C::K_ROWS_PI, p.Sk - 1);
+    return max(0, min(p.block_table[(int64_t)b * p.table_stride + (token >> p.page_shift)], p.num_pages - 1));
+  };
+  auto page_of = [&](int t, int u) __attribute__((always_inline)) -> int {
+    return __builtin_amdgcn_readfirstlane(page_of_lane(t, u));
+  };
+  // ... and the address of that instruction's first token in that page (view: the cache as [pages, 1, Hkv, page_size, D])
+  auto paged_base = [&](const View& view, int t, int u, int page) __attribute__((always_inline)) -> const unsigned char* {
+    const int token = min(t * BN + k_instr(u) * C::K_ROWS_PI, p.Sk - 1);
+    const int within = p.block_table != nullptr ? (token & p.page_mask) : token;
+    return (const unsigned char*)((const uint16_t*)view.ptr + (int64_t)page * view.sb + hk * view.sh + (int64_t)within * view.ss);
   };
   // one load instruction of a K tile (stream s) / V tile whose first row is at `tile_base`
   auto issue_k = [&](int s, int u, const unsigned char* tile_base, int lds_off) __attribute__((always_inline)) {
@@ -1049,12 +1080,14 @@ fwd_bf16_kernel(const FwdParams call) {
 #pragma unroll
     for (int s = 0; s < NS; ++s)
 #pragma unroll
-      for (int u = 0; u < KPW; ++u) issue_k(s, u, k_tile_base(s, t), C::K_RING + (buf * NS + s) * C::K_BYTES);
+      for (int u = 0; u < KPW; ++u)
+        issue_k(s, u, C::PAGED ? paged_base(p.k, t, u, page_of(t, u)) : k_tile_base(s, t), C::K_RING + (buf * NS + s) * C::K_BYTES);
   };
   auto load_v = [&](int t, int buf) __attribute__((always_inline)) {
     clamp_v(t);
 #pragma unroll
-    for (int u = 0; u < VPW; ++u) issue_v(u, v_tile_base(t), C::V_RING + buf * C::V_BYTES);
+    for (int u = 0; u < VPW; ++u)
+      issue_v(u, C::PAGED ? paged_base(p.v, t, u, page_of(t, u)) : v_tile_base(t), C::V_RING + buf * C::V_BYTES);
   };
   auto wait_loads_and_sync = [&]() __attribute__((always_inline)) {
     __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wave's direct loads have landed
@@ -1113,6 +1146,19 @@ fwd_bf16_kernel(const FwdParams call) {
 #pragma unroll
       for (int s = 0; s < NS; ++s) kb[s] = k_tile_base(s, tl[SPB + 1] < t_hi ? tl[SPB + 1] : t_hi - 1);
       const unsigned char* vb = v_tile_base(tl[SPB] < t_hi ? tl[SPB] : t_hi - 1);
+      // paged keys: pages of the tiles whose K / V the next step loads (uniform), and those of the step after it on
+      // their way (vector loads, every lane the same address: they land behind the step's wait for its tile loads)
+      int pgk[KPW], pgv[KPW], pgpre[KPW];
+      static_assert(!C::PAGED || KPW == VPW, "K and V tiles of paged keys are cut into the same load instructions");
+#pragma unroll
+      for (int u = 0; u < KPW; ++u) pgk[u] = pgv[u] = pgpre[u] = 0;
+      if constexpr (C::PAGED) {
+#pragma unroll
+        for (int u = 0; u < KPW; ++u) {
+          pgk[u] = page_of(tl[SPB + 1] < t_hi ? tl[SPB + 1] : t_hi - 1, u);
+          pgv[u] = page_of(tl[SPB] < t_hi ? tl[SPB] : t_hi - 1, u);
+        }
+      }
       // One pipeline step.  cur / nxt hold the scores of the current / next tile.  Step number N
       // (mod 4) fixes the roles at compile time: tile number n of the list lives in ring slot
       // n % RING, so V of the current tile sits in slot N % RING and K of the next tile in slot
@@ -1163,6 +1209,17 @@ fwd_bf16_kernel(const FwdParams call) {
         }
         if (__builtin_expect(tk == t_rag, 0)) clamp_k(tk);
         if (__builtin_expect(tv == t_rag, 0)) clamp_v(tv);
+        const unsigned char* kbp[KPW];             // paged keys: one base per load instruction
+        const unsigned char* vbp[KPW];
+        if constexpr (C::PAGED) {
+          const int tk_next = tk + 1 < t_hi ? tk + 1 : t_hi - 1;   // the tile whose K the next step loads
+#pragma unroll
+          for (int u = 0; u < KPW; ++u) {
+            pgpre[u] = page_of_lane(tk_next, u);
+            kbp[u] = paged_base(p.k, tk, u, pgk[u]);
+            vbp[u] = paged_base(p.v, tv, u, pgv[u]);
+          }
+        }
         w.template phase_a<C::K_RING + slot_kn * NS * C::K_BYTES>(
             nxt, cur, ps, tn * BN, br, [&](auto fc) __attribute__((always_inline)) {
               constexpr int f = decltype(fc)::value, NF = NB * KK;
@@ -1170,16 +1227,23 @@ fwd_bf16_kernel(const FwdParams call) {
               static_for<0, NK>([&](auto ic) __attribute__((always_inline)) {
                 constexpr int i = decltype(ic)::value, ss = i / KPW, u = i % KPW;
                 if constexpr (f == ((2 * i + 1) * NF) / (2 * LN))
-                  issue_k(ss, u, kb[ss], C::K_RING + (slot_kl * NS + ss) * C::K_BYTES);
+                  issue_k(ss, u, C::PAGED ? kbp[u] : kb[ss], C::K_RING + (slot_kl * NS + ss) * C::K_BYTES);
               });
               static_for<0, NV>([&](auto uc) __attribute__((always_inline)) {
                 constexpr int u = decltype(uc)::value;
                 if constexpr (f == ((2 * (NK + u) + 1) * NF) / (2 * LN))
-                  issue_v(u, vb, C::V_RING + slot_vl * C::V_BYTES);
+                  issue_v(u, C::PAGED ? vbp[u] : vb, C::V_RING + slot_vl * C::V_BYTES);
               });
             });
         w.template phase_b<slot_vc * C::V_BYTES>(ps, cur, nxt, tn * BN, br, fulln);
         if constexpr (N % SPB == SPB - 1) wait_loads_and_sync();
+        if constexpr (C::PAGED) {                  // this step's K tile is the next step's V tile
+#pragma unroll
+          for (int u = 0; u < KPW; ++u) {
+            pgv[u] = pgk[u];
+            pgk[u] = __builtin_amdgcn_readfirstlane(pgpre[u]);
+          }
+        }
 #pragma unroll
         for (int u = 0; u + 1 < NTL; ++u) {
           tl[u] = tl[u + 1];

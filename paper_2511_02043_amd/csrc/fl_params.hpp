@@ -93,6 +93,9 @@ struct FwdParams {
   const uint32_t* block_bits;       // ... and, or null: per block 64 words (one per lane) of hidden-score bits
   int32_t map_nqb8, map_nkt;        // query blocks per tile row (a multiple of 8) and key tiles of the map
   int32_t map_per_head;             // 1: a problem of the map is (b, g, h); 0: b (the expression reads neither g nor h)
+  const int32_t* block_table;  // kernels that read keys in place from a paged cache (k, v: [pages, 1, Hkv, page_size, D]):
+  int32_t table_stride;        // [B, table_stride] page of each block of tokens, or null: sequence b is page b
+  int32_t page_shift, page_mask, num_pages;   // tokens per page = 1 << page_shift; entries are cut to [0, num_pages)
   const int32_t* kv_lens;    // bf16 kernels, or null: [B] keys of each sequence (cut to [0, Sk]); then q_off = kv_lens[b] - Sq
 };
 

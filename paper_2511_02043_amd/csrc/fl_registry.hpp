@@ -40,6 +40,7 @@ struct JitRequest {
   int nbias;
   bool diff;
   uint32_t epi;
+  bool paged = false;   // keys and values read in place from a paged cache
 };
 const KernelEntry* jit_forward_entry(const JitRequest& r);
 hipError_t jit_forward_launch(const KernelEntry& e, const FwdParams& p, int nblocks, hipStream_t stream);

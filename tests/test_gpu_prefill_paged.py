@@ -13,6 +13,16 @@ from paper_2511_02043_amd import inputs, runner
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(params=["in_place", "gather"], autouse=True)
+def prefill_mode(request):
+    """Every test runs twice: with the forward kernel reading the pages in place (the library's choice for chunks of
+    up to 256 rows), and with the pages copied into dense tensors first (its choice for longer chunks and for page
+    sizes below a load instruction's rows)."""
+    fb.check(fb.fl_set_tuning("prefill_gather", 1 if request.param == "gather" else 2))
+    yield request.param
+    fb.fl_set_tuning("prefill_gather", 0)
+
+
 def run(w, out_dtype="f32", paged=True, max_seq_len=None):
     import torch
     dd = runner.upload_prefill_paged(w, out_dtype=out_dtype, paged=paged, max_seq_len=max_seq_len)
@@ -152,14 +162,18 @@ def test_lengths_and_table_entries_out_of_range_are_cut_not_followed():
     assert np.all(np.isfinite(dd.out.cpu().numpy()))
 
 
-def test_errors():
+def test_errors(prefill_mode):
     w = inputs.prefill_paged_bf16(H=4, Hkv=2, D=64, Sq=16, page_size=16, seq_lens=[40, 60], salt=7)
     dd = runner.upload_prefill_paged(w)
     need = fb.fl_attn_prefill_paged_workspace_size(dd.tq, dd.tk, dd.kv)
-    assert need >= 2 * 2 * 2 * 60 * 64 * 2
-    small = fb.aux_desc(workspace=dd.keep[2][: need - 256])
-    assert fb.fl_attn_prefill_paged(dd.tq, dd.tk, dd.tv, dd.kv, dd.desc, small, dd.tout, dd.tlse) == fb.FL_ERR_WORKSPACE
-    assert fb.fl_attn_prefill_paged(dd.tq, dd.tk, dd.tv, dd.kv, dd.desc, None, dd.tout, dd.tlse) == fb.FL_ERR_AUX_MISSING
+    if prefill_mode == "gather":
+        assert need >= 2 * 2 * 2 * 60 * 64 * 2
+        small = fb.aux_desc(workspace=dd.keep[2][: need - 256])
+        assert fb.fl_attn_prefill_paged(dd.tq, dd.tk, dd.tv, dd.kv, dd.desc, small, dd.tout, dd.tlse) == fb.FL_ERR_WORKSPACE
+        assert fb.fl_attn_prefill_paged(dd.tq, dd.tk, dd.tv, dd.kv, dd.desc, None, dd.tout, dd.tlse) == fb.FL_ERR_AUX_MISSING
+    else:                                           # in place: no workspace, and no aux unless the variant needs slopes
+        assert need == 0
+        assert fb.fl_attn_prefill_paged(dd.tq, dd.tk, dd.tv, dd.kv, dd.desc, None, dd.tout, dd.tlse) == fb.FL_OK
     for bad in (fb.variant_desc(scale=1.0, mask=fb.FL_MASK_DOC), fb.variant_desc(scale=1.0, mask=fb.FL_MASK_PREFIX, prefix_len=4),
                 fb.variant_desc(scale=1.0, q_offset=3), fb.variant_desc(scale=1.0, epilogue=fb.FL_EPI_GATE_SIGMOID)):
         assert fb.fl_attn_prefill_paged(dd.tq, dd.tk, dd.tv, dd.kv, bad, dd.aux, dd.tout, dd.tlse) == fb.FL_ERR_UNSUPPORTED
