@@ -307,7 +307,7 @@ size_t fl_attn_decode_workspace_size(const fl_tensor* q, const fl_tensor* k_cach
  *
  * How: the forward kernel runs with each sequence's length read on the device: it stops at that length and places the
  * query rows at its last Sq positions, so a short sequence costs its own length and nothing is synchronised with the
- * host.  For chunks of up to 256 rows its key / value tile loads go to the pages themselves (page numbers from the block
+ * host.  For chunks of up to 1024 rows its key / value tile loads go to the pages themselves (page numbers from the block
  * table, fetched a step ahead; needs page_size >= 512 / D with a block table): no copy and no workspace.  For longer
  * chunks one pass first copies the cached rows of every sequence into dense tensors in the workspace (2 * 2 * len * Hkv
  * * D * 2 bytes read and written per sequence, small beside the Sq * len scores of such a chunk) and the tuned dense

@@ -858,7 +858,7 @@ static fl_status forward_call(const fl_tensor* q, const fl_tensor* k, const fl_t
   if (ke == nullptr && dtype == FL_BF16 && jit_dims_ok(D, Dv)) {
     // not in the compiled table: the same kernel template, instantiated for this descriptor on first use
     ke = fl::jit_forward_entry(fl::JitRequest{(int)D, (int)Dv, (int)desc->score_mod, mask, (int)desc->n_bias, diff, desc->epilogue,
-                                              paged != nullptr});
+                                              paged != nullptr, paged != nullptr && D == 128 && Sq >= 512 && B * G * H * ((Sq + 255) / 256) >= 512});
     if (ke == nullptr) {
       char why[300];
       snprintf(why, sizeof(why), "%s", g_detail);
@@ -1590,14 +1590,16 @@ fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_
 }
 
 // Does the forward kernel read these pages in place?  It can when every direct-load instruction of a tile (512 / D
-// consecutive tokens) lies in one page.  It does for chunks of up to 256 rows: the in-place kernel is the run-time
-// instantiated shape (four waves, two ring slots) with a page lookup per load instruction and runs at 0.65 - 0.75 of
-// the tuned dense kernel, while the copy costs the time of about 100 query rows of attention -- measured equal at 256 rows
-// (32 / 8 heads, D = 128, 8192 cached tokens), in place 22 % faster at 128 rows and 43 % at 64, the copy 17 % faster at 1024.
+// consecutive tokens) lies in one page.  It does for chunks of up to 1024 rows: the in-place kernel is a run-time
+// instantiated shape (two ring slots; four waves, eight from 512 rows on at head dim 128) with a page lookup and a
+// 64-bit base per load instruction and runs at 0.75 - 0.9 of the tuned dense kernel, while the copy costs the time of
+// about 100 query rows of attention.  Measured at 32 / 8 heads, D = 128, 8192 cached tokens (ms in place / copied):
+// 64 rows 0.76 / 1.32, 128 rows 0.43 / 0.55, 256 rows 0.40 / 0.41, 384 rows 0.66 / 0.59, 512 rows 0.59 / 0.64,
+// 1024 rows 1.07 / 1.06, 2048 rows 1.95 / 1.77.
 static bool prefill_in_place(int64_t D, int64_t page_size, bool has_table, int64_t Sq) {
   if (g_tuning.prefill_gather == 1 || !(D == 32 || D == 64 || D == 128)) return false;
   if (has_table && page_size < 512 / D) return false;
-  return g_tuning.prefill_gather == 2 || Sq <= 256;
+  return g_tuning.prefill_gather == 2 || Sq <= 1024;
 }
 
 size_t fl_attn_prefill_paged_workspace_size(const fl_tensor* q, const fl_tensor* k_cache, const fl_paged_kv* kv) {

@@ -41,6 +41,7 @@ struct JitRequest {
   bool diff;
   uint32_t epi;
   bool paged = false;   // keys and values read in place from a paged cache
+  bool wide = false;    // eight waves (256 query rows) per workgroup instead of four: long query tiles at head dim 128
 };
 const KernelEntry* jit_forward_entry(const JitRequest& r);
 hipError_t jit_forward_launch(const KernelEntry& e, const FwdParams& p, int nblocks, hipStream_t stream);

@@ -153,17 +153,17 @@ struct JitForward {
 namespace fl {
 
 const KernelEntry* jit_forward_entry(const JitRequest& r) {
-  typedef std::tuple<int, int, int, uint32_t, int, bool, uint32_t, bool> Key;
+  typedef std::tuple<int, int, int, uint32_t, int, bool, uint32_t, bool, bool> Key;
   static std::mutex mu;
   static std::map<Key, JitForward*> cache;        // entries live until the process ends
-  const Key key(r.D, r.DV, r.mod, r.mask, r.nbias, r.diff, r.epi, r.paged);
+  const Key key(r.D, r.DV, r.mod, r.mask, r.nbias, r.diff, r.epi, r.paged, r.wide);
   std::lock_guard<std::mutex> lock(mu);            // one compilation at a time; a hit only takes the lookup
   auto it = cache.find(key);
   if (it != cache.end()) return it->second != nullptr ? &it->second->entry : nullptr;
   // Shape of the generated kernels: one 32-row block per wave, two waves per SIMD; 4 waves (8 for the two
   // softmax streams of the differential variant); 64-key tiles unless the rings would pass 64 KiB of LDS
   // (a launch through the module API gets no more than that).
-  const int nw = r.diff ? 8 : 4;
+  const int nw = (r.diff || r.wide) ? 8 : 4;
   const int ns = r.diff ? 2 : 1;
   int bn = 64;
   if (2 * bn * 2 * (ns * r.D + r.DV) > 65536) bn = 32;

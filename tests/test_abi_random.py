@@ -88,7 +88,7 @@ def test_random_paged_calls_never_crash_the_host():
     rng = np.random.Generator(np.random.PCG64(20251102044))
     seen = {"decode": set(), "prefill": set()}
     for case in range(400):
-        B, H, Hkv, Sq, D, pages, page_size, max_len, stride = 3, 8, 2, 300, 128, 50, 16, 200, 13     # (a chunk long enough for the path with a workspace)
+        B, H, Hkv, Sq, D, pages, page_size, max_len, stride = 3, 8, 2, 1100, 128, 50, 16, 200, 13     # (a chunk long enough for the path with a workspace)
         kw = dict(scale=0.0884, score_mod=fb.FL_MOD_NONE, softcap=0.0, mask=fb.FL_MASK_CAUSAL, window=0)
         muts = rng.choice(22, size=int(rng.integers(0, 4)), replace=False)
         if 0 in muts: B = 0

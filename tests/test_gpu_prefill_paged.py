@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 @pytest.fixture(params=["in_place", "gather"], autouse=True)
 def prefill_mode(request):
     """Every test runs twice: with the forward kernel reading the pages in place (the library's choice for chunks of
-    up to 256 rows), and with the pages copied into dense tensors first (its choice for longer chunks and for page
+    up to 1024 rows), and with the pages copied into dense tensors first (its choice for longer chunks and for page
     sizes below a load instruction's rows)."""
     fb.check(fb.fl_set_tuning("prefill_gather", 1 if request.param == "gather" else 2))
     yield request.param
@@ -181,3 +181,27 @@ def test_errors(prefill_mode):
     assert fb.fl_attn_prefill_paged(dd.tq, dd.tk, dd.tv, dd.kv, alibi, dd.aux, dd.tout, dd.tlse) == fb.FL_ERR_AUX_MISSING
     kv = fb.paged_kv(block_table=dd.keep[0], page_size=8, seq_lens=dd.keep[1], max_seq_len=60)
     assert fb.fl_attn_prefill_paged(dd.tq, dd.tk, dd.tv, kv, dd.desc, dd.aux, dd.tout, dd.tlse) == fb.FL_ERR_SHAPE
+
+
+def test_wide_in_place_shape_at_serving_size():
+    """32 query heads on 8 kv heads, 8 sequences, 512-row chunks: the launch for which the in-place kernel takes its
+    eight-wave shape.  Both ways must agree bit for bit (same arithmetic on the same keys), and the first query-head group
+    of one sequence is checked against the oracle."""
+    import torch
+    w = inputs.prefill_paged_bf16(B=8, H=32, Hkv=8, D=128, Sq=512, page_size=16,
+                                  seq_lens=[512, 700, 1500, 1023, 1024, 1025, 600, 2000], salt=40)
+    outs = []
+    for mode in (2, 1):
+        fb.check(fb.fl_set_tuning("prefill_gather", mode))
+        dd = runner.upload_prefill_paged(w)
+        dd.out.fill_(float("nan"))
+        dd.run_checked()
+        torch.cuda.synchronize()
+        outs.append((dd.out.clone(), dd.lse.clone()))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    b = 2
+    ref, ref_lse = do.prefill_attention(w.q[b:b + 1, :4], w.k_cache[:, :, :1], w.v_cache[:, :, :1], w.block_table[b:b + 1],
+                                        w.seq_lens[b:b + 1], scale=w.scale)
+    got = outs[0][0].float().cpu().numpy()[b:b + 1, 0, :4]
+    got_lse = outs[0][1].cpu().numpy()[b:b + 1, 0, :4, :, 0]
+    check(got, got_lse, ref, ref_lse, "wide_in_place")
