@@ -15,6 +15,11 @@ static const KernelEntry kEntries[] = {
     // it for short key loops (Sk <= 4096 unmasked, <= 2048 causal), where it measured 3 - 12 % faster
     BOTH(64, 4, 2, 32, 2),  BOTH(64, 4, 1, 64, 2),  BOTH(64, 8, 1, 64, 2),  BOTH(64, 4, 1, 32, 4),
     BOTH(32, 4, 1, 64, 2),  BOTH(32, 4, 2, 64, 2),
+    // causal attention with keys and values read in place from a paged cache (chunked prefill; other variants of it are
+    // instantiated on first use): the default shapes with two ring slots
+    bf16_entry<128, 128, 8, 1, 64, 2, kModNone, kMaskCausal, 0, false, 0, 2, true>(),
+    bf16_entry<128, 128, 4, 1, 64, 2, kModNone, kMaskCausal, 0, false, 0, 2, true>(),
+    bf16_entry<64, 64, 4, 1, 64, 2, kModNone, kMaskCausal, 0, false, 0, 2, true>(),
 };
 #undef BOTH
 #undef BOTH4

@@ -17,6 +17,7 @@ struct KernelKey {
   int epi;          // -1 in f32 entries
   int nwaves, rb, bn, wpe;         // kernel shape: waves, 32-row blocks per wave, keys per tile, waves per SIMD
   int ring;                        // slots of the K / V rings in LDS (a barrier every ring / 2 tiles)
+  int paged;                       // 1: keys and values are read in place from a paged cache
 };
 
 typedef hipError_t (*LaunchFn)(const FwdParams& p, int nblocks, hipStream_t stream);
@@ -65,12 +66,12 @@ hipError_t launch_bf16(const FwdParams& p, int nblocks, hipStream_t stream) {
 }
 
 template <int D, int DV, int NWAVES, int RB, int BN, int WPE, int MOD, uint32_t MASK, int NBIAS, bool DIFF,
-          uint32_t EPI, int RING = 2>
+          uint32_t EPI, int RING = 2, bool PAGED = false>
 constexpr KernelEntry bf16_entry() {
-  typedef Bf16Cfg<D, DV, NWAVES, RB, BN, WPE, MOD, MASK, NBIAS, DIFF, EPI, RING> C;
+  typedef Bf16Cfg<D, DV, NWAVES, RB, BN, WPE, MOD, MASK, NBIAS, DIFF, EPI, RING, PAGED> C;
   static_assert(C::LDS_BYTES <= kMaxLdsBytes, "rings exceed the LDS of a compute unit");
-  return KernelEntry{KernelKey{1, D, DV, MOD, (int)MASK, NBIAS, DIFF ? 1 : 0, (int)EPI, NWAVES, RB, BN, WPE, RING}, C::BM,
-                     C::LDS_BYTES, &launch_bf16<C>};
+  return KernelEntry{KernelKey{1, D, DV, MOD, (int)MASK, NBIAS, DIFF ? 1 : 0, (int)EPI, NWAVES, RB, BN, WPE, RING, PAGED ? 1 : 0},
+                     C::BM, C::LDS_BYTES, &launch_bf16<C>};
 }
 
 // Each instance file defines one of these.

@@ -183,7 +183,7 @@ const KernelEntry* jit_forward_entry(const JitRequest& r) {
     return nullptr;
   }
   j->nthreads = nw * 64;
-  j->entry = KernelEntry{KernelKey{1, r.D, r.DV, r.mod, (int)r.mask, r.nbias, r.diff ? 1 : 0, (int)r.epi, nw, 1, bn, 2, 2},
+  j->entry = KernelEntry{KernelKey{1, r.D, r.DV, r.mod, (int)r.mask, r.nbias, r.diff ? 1 : 0, (int)r.epi, nw, 1, bn, 2, 2, r.paged ? 1 : 0},
                          (nw / ns) * 32, lds > xch ? lds : xch, nullptr, j, 65536};
   cache[key] = j;
   return &j->entry;
