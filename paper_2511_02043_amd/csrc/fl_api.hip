@@ -301,13 +301,16 @@ BwdWorkspace bwd_workspace(int64_t B, int64_t G, int64_t H, int64_t Hkv, int64_t
   return w;
 }
 
-const fl::DecodeEntry* find_decode_entry(int D, int mod) {
+const fl::DecodeEntry* find_decode_entry(int D, int mod, int cb) {
   int n = 0;
   const fl::DecodeEntry* tab = fl::entries_decode(&n);
   for (int e = 0; e < n; ++e)
-    if (tab[e].D == D && tab[e].mod == mod) return &tab[e];
+    if (tab[e].D == D && tab[e].mod == mod && tab[e].cb == cb) return &tab[e];
   return nullptr;
 }
+
+// The decode kernels hold the (query row, head) pairs of a kv head as MFMA columns: at most two blocks of 32.
+constexpr int64_t kDecodeMaxPairs = 64;
 
 // Splits of a sequence's key range, a function of the shapes and the host-side length bound only.
 // Measured on (sequences x kv heads) = 8 ... 2048 units and 1k ... 128k cached tokens: few units want
@@ -1475,9 +1478,9 @@ fl_status fl_attn_bwd_ex(const fl_tensor* q, const fl_tensor* k, const fl_tensor
 
 size_t fl_attn_decode_workspace_size(const fl_tensor* q, const fl_tensor* k_cache, const fl_paged_kv* kv) {
   if (q == nullptr || k_cache == nullptr || kv == nullptr) return 0;
-  const int64_t B = q->size[0], H = q->size[2], D = q->size[4];
+  const int64_t B = q->size[0], H = q->size[2], T = q->size[3], D = q->size[4];
   const int ns = decode_splits(B, k_cache->size[2], D, kv->max_seq_len);
-  return (size_t)(B * H * ns) * (size_t)(D + 2) * sizeof(float);
+  return (size_t)(B * T * H * ns) * (size_t)(D + 2) * sizeof(float);
 }
 
 fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_tensor* v_cache, const fl_paged_kv* kv,
@@ -1497,14 +1500,16 @@ fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_
     return fail(FL_ERR_UNSUPPORTED, "the decode step covers scale, score_mod and the sliding window only");
   if (q->dtype != FL_BF16) return fail(FL_ERR_DTYPE, "the decode step takes bf16 inputs (q dtype %d)", q->dtype);
 
-  const int64_t B = q->size[0], H = q->size[2], D = q->size[4];
+  const int64_t B = q->size[0], H = q->size[2], T = q->size[3], D = q->size[4];
   const int64_t pages = k_cache->size[0], Hkv = k_cache->size[2], page_size = k_cache->size[3];
-  if (B < 0 || H < 0 || D <= 0 || pages < 0 || page_size <= 0) return fail(FL_ERR_SHAPE, "negative size");
+  if (B < 0 || H < 0 || T < 0 || D <= 0 || pages < 0 || page_size <= 0) return fail(FL_ERR_SHAPE, "negative size");
   if (pages > 0x7fffffffLL) return fail(FL_ERR_SHAPE, "more pages than an int32 table entry can name");
   if (pages == 0 && kv->max_seq_len > 0) return fail(FL_ERR_SHAPE, "max_seq_len = %d with an empty cache", kv->max_seq_len);
-  if (q->size[1] != 1 || q->size[3] != 1) return fail(FL_ERR_SHAPE, "q must be [B, 1, H, 1, D]");
-  if (Hkv <= 0 || H % Hkv != 0 || H / Hkv > 32)
-    if (H != 0) return fail(FL_ERR_SHAPE, "kv heads (%lld) must divide q heads (%lld), at most 32 q heads per kv head", (long long)Hkv, (long long)H);
+  if (q->size[1] != 1) return fail(FL_ERR_SHAPE, "q must be [B, 1, H, T, D]");
+  if (Hkv <= 0 || H % Hkv != 0 || (H / Hkv) * T > kDecodeMaxPairs)
+    if (H != 0)
+      return fail(FL_ERR_SHAPE, "kv heads (%lld) must divide q heads (%lld), at most %lld (query row, q head) pairs per kv head (T = %lld)",
+                  (long long)Hkv, (long long)H, (long long)kDecodeMaxPairs, (long long)T);
   if (kv->page_size != page_size) return fail(FL_ERR_SHAPE, "kv->page_size = %d, cache size[3] = %lld", kv->page_size, (long long)page_size);
   if (kv->max_seq_len < 0) return fail(FL_ERR_SHAPE, "max_seq_len negative");
   int page_shift = 0;
@@ -1518,12 +1523,12 @@ fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_
     if (pages < B) return fail(FL_ERR_SHAPE, "without a block table the cache needs a page per sequence");
     if (kv->max_seq_len > page_size) return fail(FL_ERR_SHAPE, "max_seq_len exceeds the page size");
   }
-  const fl::DecodeEntry* de = find_decode_entry((int)D, (int)desc->score_mod);
+  const fl::DecodeEntry* de = find_decode_entry((int)D, (int)desc->score_mod, H > 0 && (H / Hkv) * T > 32 ? 2 : 1);
   if (de == nullptr || v_cache->size[4] != D)
     return fail(FL_ERR_UNSUPPORTED, "no decode specialisation for D=%lld Dv=%lld score_mod=%u", (long long)D,
                 (long long)v_cache->size[4], desc->score_mod);
-  const bool empty = (B == 0 || H == 0);
-  const int64_t qsz[5] = {B, 1, H, 1, D}, csz[5] = {pages, 1, Hkv, page_size, D};
+  const bool empty = (B == 0 || H == 0 || T == 0);
+  const int64_t qsz[5] = {B, 1, H, T, D}, csz[5] = {pages, 1, Hkv, page_size, D};
   if (!empty) {
     if ((st = check_data_tensor(q, "q", FL_BF16, qsz)) != FL_OK) return st;
     if (kv->max_seq_len > 0) {
@@ -1537,7 +1542,7 @@ fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_
   const bool want_lse = lse != nullptr && lse->ptr != nullptr;
   if (want_lse && !empty) {
     if (lse->dtype != FL_F32) return fail(FL_ERR_DTYPE, "lse must be f32");
-    const int64_t lsz[5] = {B, 1, H, 1, 1};
+    const int64_t lsz[5] = {B, 1, H, T, 1};
     for (int a = 0; a < 5; ++a)
       if (lse->size[a] != lsz[a])
         return fail(FL_ERR_SHAPE, "lse size[%d] = %lld, expected %lld", a, (long long)lse->size[a], (long long)lsz[a]);
@@ -1546,17 +1551,18 @@ fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_
   if (aux == nullptr) return fail(FL_ERR_AUX_MISSING, "the decode step needs aux (workspace)");
   if (desc->score_mod == FL_MOD_ALIBI && aux->alibi_slopes == nullptr) return fail(FL_ERR_AUX_MISSING, "alibi_slopes");
   const int ns = decode_splits(B, Hkv, D, kv->max_seq_len);
-  const size_t ws_need = (size_t)(B * H * ns) * (size_t)(D + 2) * sizeof(float);
+  const size_t ws_need = (size_t)(B * T * H * ns) * (size_t)(D + 2) * sizeof(float);
   if (aux->workspace == nullptr || aux->workspace_bytes < ws_need)
     return fail(FL_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", ws_need, aux->workspace ? aux->workspace_bytes : (size_t)0);
   if (((uintptr_t)aux->workspace) % 16 != 0) return fail(FL_ERR_ALIGN, "workspace not 16-byte aligned");
-  if (B * Hkv * ns > 0x7fffffffLL || B * H > 0x7fffffffLL) return fail(FL_ERR_SHAPE, "too many workgroups");
+  if (B * Hkv * ns > 0x7fffffffLL || B * T * H > 0x7fffffffLL) return fail(FL_ERR_SHAPE, "too many workgroups");
 
   fl::DecodeParams p;
   memset(&p, 0, sizeof(p));
   p.q = (const uint16_t*)q->ptr;
   p.q_sb = B > 1 ? q->stride[0] : 0;
   p.q_sh = H > 1 ? q->stride[2] : 0;
+  p.q_st = T > 1 ? q->stride[3] : 0;
   p.k = (const uint16_t*)k_cache->ptr;
   p.v = (const uint16_t*)v_cache->ptr;
   p.k_sp = pages > 1 ? k_cache->stride[0] : 0;
@@ -1572,16 +1578,18 @@ fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_
   p.out = out->ptr;
   p.o_sb = B > 1 ? out->stride[0] : 0;
   p.o_sh = H > 1 ? out->stride[2] : 0;
+  p.o_st = T > 1 ? out->stride[3] : 0;
   p.out_f32 = out->dtype == FL_F32;
   if (want_lse) {
     p.lse = (float*)lse->ptr;
     p.lse_sb = B > 1 ? lse->stride[0] : 0;
     p.lse_sh = H > 1 ? lse->stride[2] : 0;
+    p.lse_st = T > 1 ? lse->stride[3] : 0;
   }
   p.part_o = (float*)aux->workspace;
-  p.part_ml = p.part_o + B * H * ns * D;
+  p.part_ml = p.part_o + B * T * H * ns * D;
   p.alibi_slopes = aux->alibi_slopes;
-  p.B = (int)B; p.H = (int)H; p.Hkv = (int)Hkv; p.nsplit = ns;
+  p.B = (int)B; p.H = (int)H; p.Hkv = (int)Hkv; p.nsplit = ns; p.T = (int)T;
   p.max_len = kv->max_seq_len;
   p.num_pages = (int)pages;
   p.window = (mask & FL_MASK_WINDOW) ? clamp_window(desc->window, kv->max_seq_len, kv->max_seq_len) : -1;
@@ -1590,7 +1598,7 @@ fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_
   hipStream_t stream = (hipStream_t)stream_v;
   hipError_t e = de->main(p, (int)(B * Hkv * ns), stream);
   if (e != hipSuccess) return fail(FL_ERR_LAUNCH, "decode launch: %s", hipGetErrorString(e));
-  if (ns > 1 && (e = de->combine(p, (int)(B * H), stream)) != hipSuccess)   // a single split writes the result itself
+  if (ns > 1 && (e = de->combine(p, (int)(B * T * H), stream)) != hipSuccess)   // a single split writes the result itself
     return fail(FL_ERR_LAUNCH, "decode merge launch: %s", hipGetErrorString(e));
   return FL_OK;
 }
@@ -1602,6 +1610,13 @@ fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_
 // about 100 query rows of attention.  Measured at 32 / 8 heads, D = 128, 8192 cached tokens (ms in place / copied):
 // 64 rows 0.76 / 1.32, 128 rows 0.43 / 0.55, 256 rows 0.40 / 0.41, 384 rows 0.66 / 0.59, 512 rows 0.59 / 0.64,
 // 1024 rows 1.07 / 1.06, 2048 rows 1.95 / 1.77.
+// Chunks of so few rows that all (query row, head) pairs of a kv head fit the columns of the decode kernels go
+// there: the cache is then read once per kv head instead of once per query head, and no MFMA row is idle.
+static bool prefill_as_decode(int64_t D, int64_t H, int64_t Hkv, int64_t Sq) {
+  if (g_tuning.prefill_gather != 0) return false;
+  return (D == 64 || D == 128) && Hkv > 0 && H % Hkv == 0 && Sq * (H / Hkv) <= kDecodeMaxPairs;
+}
+
 static bool prefill_in_place(int64_t D, int64_t page_size, bool has_table, int64_t Sq) {
   if (g_tuning.prefill_gather == 1 || !(D == 32 || D == 64 || D == 128)) return false;
   if (has_table && page_size < 512 / D) return false;
@@ -1610,6 +1625,7 @@ static bool prefill_in_place(int64_t D, int64_t page_size, bool has_table, int64
 
 size_t fl_attn_prefill_paged_workspace_size(const fl_tensor* q, const fl_tensor* k_cache, const fl_paged_kv* kv) {
   if (q == nullptr || k_cache == nullptr || kv == nullptr) return 0;
+  if (prefill_as_decode(q->size[4], q->size[2], k_cache->size[2], q->size[3])) return fl_attn_decode_workspace_size(q, k_cache, kv);
   if (prefill_in_place(q->size[4], k_cache->size[3], kv->block_table != nullptr, q->size[3])) return 0;
   return prefill_layout(q->size[0], k_cache->size[2], q->size[4], kv->max_seq_len).total;
 }
@@ -1686,6 +1702,9 @@ fl_status fl_attn_prefill_paged(const fl_tensor* q, const fl_tensor* k_cache, co
       if (lse->size[a] != lsz[a])
         return fail(FL_ERR_SHAPE, "lse size[%d] = %lld, expected %lld", a, (long long)lse->size[a], (long long)lsz[a]);
   }
+
+  // A few rows: the decode kernels, with their own checks of the same arguments.
+  if (prefill_as_decode(D, H, Hkv, Sq)) return fl_attn_decode(q, k_cache, v_cache, kv, desc, aux, out, lse, stream_v);
 
   // In place (short chunks): the forward kernel takes the cache tensors as its keys and values and finds every tile's
   // pages through the block table itself; no copy, no workspace.

@@ -8,8 +8,8 @@ namespace fl {
 typedef hipError_t (*DecodeLaunchFn)(const DecodeParams& p, int nblocks, hipStream_t stream);
 
 struct DecodeEntry {
-  int D, mod;
-  DecodeLaunchFn main, combine;   // main: B * Hkv * nsplit workgroups; combine: B * H workgroups
+  int D, mod, cb;                 // cb: blocks of 32 (query row, head) columns per kv head
+  DecodeLaunchFn main, combine;   // main: B * Hkv * nsplit workgroups; combine: B * T * H workgroups
 };
 
 template <class C>
@@ -26,9 +26,9 @@ hipError_t launch_decode_combine(const DecodeParams& p, int nblocks, hipStream_t
   return hipGetLastError();
 }
 
-template <int D, int MOD>
+template <int D, int MOD, int CB = 1>
 constexpr DecodeEntry decode_entry() {
-  return DecodeEntry{D, MOD, &launch_decode<DecodeCfg<D, MOD>>, &launch_decode_combine<D>};
+  return DecodeEntry{D, MOD, CB, &launch_decode<DecodeCfg<D, MOD, CB>>, &launch_decode_combine<D>};
 }
 
 const DecodeEntry* entries_decode(int* n);

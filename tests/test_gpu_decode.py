@@ -202,3 +202,31 @@ def test_all_sequences_empty_without_table_columns():
     fb.check(fb.fl_attn_decode(dd.tq, dd.tk, dd.tv, kv, dd.desc, dd.aux, dd.tout, dd.tlse))
     torch.cuda.synchronize()
     assert bool((dd.out == 0).all()) and bool(torch.isneginf(dd.lse).all())
+
+
+def test_decode_of_several_rows():
+    """fl_attn_decode on q [B, 1, H, T, D]: the T newest tokens of every sequence, causal among themselves (a speculative
+    step's verification), against the oracle of a chunk of rows over the paged cache; more than 64 (row, head) pairs
+    per kv head are refused."""
+    import torch
+    from paper_2511_02043_amd import binding as fb
+    for H, Hkv, D, T in ((8, 2, 128, 4), (8, 2, 64, 16), (8, 8, 128, 33)):
+        w = inputs.prefill_paged_bf16(H=H, Hkv=Hkv, D=D, Sq=T, page_size=16, seq_lens=[2, T, T + 1, 95, 1300, 4000], salt=50 + T)
+        dd = runner.upload_prefill_paged(w)
+        ws = torch.empty(fb.fl_attn_decode_workspace_size(dd.tq, dd.tk, dd.kv), dtype=torch.uint8, device="cuda:0")
+        dd.out.fill_(float("nan"))
+        dd.lse.fill_(float("nan"))
+        fb.check(fb.fl_attn_decode(dd.tq, dd.tk, dd.tv, dd.kv, dd.desc, fb.aux_desc(workspace=ws), dd.tout, dd.tlse))
+        torch.cuda.synchronize()
+        got, got_lse = dd.out.cpu().numpy()[:, 0], dd.lse.cpu().numpy()[:, 0, :, :, 0]
+        ref, ref_lse = do.prefill_attention(w.q, w.k_cache, w.v_cache, w.block_table, w.seq_lens, scale=w.scale)
+        dead = np.isneginf(ref_lse)
+        assert np.array_equal(np.isneginf(got_lse), dead) and np.all(got[dead] == 0.0)
+        err = float(np.max(np.abs(got - ref)))
+        le = float(np.max(np.abs(got_lse[~dead] - ref_lse[~dead])))
+        print(f"decode H={H}/{Hkv} D={D} T={T}: max_abs={err:.3e} lse={le:.3e}", flush=True)
+        assert err <= 1e-2 and le <= 1e-3
+    w = inputs.prefill_paged_bf16(H=8, Hkv=2, D=128, Sq=17, page_size=16, seq_lens=[100, 200], salt=60)
+    dd = runner.upload_prefill_paged(w)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda:0")
+    assert fb.fl_attn_decode(dd.tq, dd.tk, dd.tv, dd.kv, dd.desc, fb.aux_desc(workspace=ws), dd.tout, dd.tlse) == fb.FL_ERR_SHAPE

@@ -13,12 +13,13 @@ from paper_2511_02043_amd import inputs, runner
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(params=["in_place", "gather"], autouse=True)
+@pytest.fixture(params=["auto", "in_place", "gather"], autouse=True)
 def prefill_mode(request):
-    """Every test runs twice: with the forward kernel reading the pages in place (the library's choice for chunks of
-    up to 1024 rows), and with the pages copied into dense tensors first (its choice for longer chunks and for page
-    sizes below a load instruction's rows)."""
-    fb.check(fb.fl_set_tuning("prefill_gather", 1 if request.param == "gather" else 2))
+    """Every test runs three times: with the library's own choice (the decode kernels for chunks whose (row, head) pairs
+    per kv head number at most 64, else as follows), with the forward kernel reading the pages in place (its choice for
+    chunks of up to 1024 rows), and with the pages copied into dense tensors first (its choice for longer chunks and for
+    page sizes below a load instruction's rows)."""
+    fb.check(fb.fl_set_tuning("prefill_gather", {"auto": 0, "gather": 1, "in_place": 2}[request.param]))
     yield request.param
     fb.fl_set_tuning("prefill_gather", 0)
 
@@ -61,6 +62,17 @@ CASES = {
                                                            seq_lens=[7, 300, 301, 900, 2049]),
     "mha_d128_p8_q17": lambda: inputs.prefill_paged_bf16(H=4, Hkv=4, D=128, Sq=17, page_size=8, seq_lens=[15, 16, 17, 18, 333]),
     "mqa_d64_p128_q64": lambda: inputs.prefill_paged_bf16(H=8, Hkv=1, D=64, Sq=64, page_size=128, seq_lens=[129, 1000, 3]),
+    # few rows: all (row, head) pairs of a kv head are columns of one or two MFMA tiles of the decode kernels; lengths
+    # below the chunk (rows at negative positions), around the 32-key tile and the pages
+    "few_gqa4_d128_q8": lambda: inputs.prefill_paged_bf16(H=8, Hkv=2, D=128, Sq=8, page_size=16,
+                                                          seq_lens=[0, 1, 7, 8, 9, 31, 32, 33, 64, 500, 1027], salt=11),
+    "few_gqa4_d128_q16": lambda: inputs.prefill_paged_bf16(H=8, Hkv=2, D=128, Sq=16, page_size=16,
+                                                           seq_lens=[3, 15, 16, 17, 40, 65, 900], salt=12),
+    "few_gqa8_d64_q5": lambda: inputs.prefill_paged_bf16(H=16, Hkv=2, D=64, Sq=5, page_size=8,
+                                                         seq_lens=[4, 5, 6, 32, 36, 37, 777], salt=13),
+    "few_mha_d64_q40": lambda: inputs.prefill_paged_bf16(H=2, Hkv=2, D=64, Sq=40, page_size=32,
+                                                         seq_lens=[39, 40, 41, 100, 1500], salt=14),
+    "few_gqa4_d128_q3": lambda: inputs.prefill_paged_bf16(H=4, Hkv=1, D=128, Sq=3, page_size=64, seq_lens=[2, 3, 4, 64, 66, 2100], salt=15),
     "d32_p16_q40": lambda: inputs.prefill_paged_bf16(H=4, Hkv=2, D=32, Sq=40, page_size=16, seq_lens=[40, 41, 200]),
 }
 
@@ -70,9 +82,9 @@ def test_prefill_matches_oracle(name):
     compare(CASES[name](), name)
 
 
-@pytest.mark.parametrize("Sq", [1, 17, 128, 500])
+@pytest.mark.parametrize("Sq", [1, 4, 16, 17, 128, 500])
 def test_chunks_against_a_long_cache(Sq):
-    """Chunks of 1, 17, 128 and 500 rows against 4k - 8k cached tokens per sequence (the serving shape of Sec. 4.1:
+    """Chunks of 1, 4, 16 (the decode kernels' range, several splits of the key range), 17, 128 and 500 rows against 4k - 8k cached tokens per sequence (the serving shape of Sec. 4.1:
     32 query heads on 8 kv heads would take the oracle minutes, so 8 on 2), every row checked."""
     w = inputs.prefill_paged_bf16(H=8, Hkv=2, D=128, Sq=Sq, page_size=16, seq_lens=[4096, 5000, 8191], salt=20 + Sq)
     compare(w, f"long_cache_q{Sq}")
@@ -94,6 +106,29 @@ def test_prefill_variants():
     compare(w, "alibi")
     w.window = 300
     compare(w, "alibi_window")
+
+
+def test_few_row_variants():
+    """Window, soft-cap and ALiBi on chunks of a few rows, windows shorter than the chunk included (the rows' windows
+    then differ inside one key tile)."""
+    for D, Sq in ((128, 6), (64, 13)):
+        w = inputs.prefill_paged_bf16(H=8, Hkv=2, D=D, Sq=Sq, page_size=16, seq_lens=[5, 33, 100, 700, 1500], salt=30 + Sq)
+        for window in (255, 3, 0):
+            w.window = window
+            compare(w, f"few_d{D}_window_{window}")
+        w.window = None
+        w.softcap = 2.0
+        compare(w, f"few_d{D}_softcap")
+        w.softcap = None
+        w.alibi = inputs.alibi_slopes(8)
+        compare(w, f"few_d{D}_alibi")
+        w.window = 40
+        compare(w, f"few_d{D}_alibi_window")
+    w = inputs.prefill_paged_bf16(H=8, Hkv=2, D=128, Sq=7, page_size=16, seq_lens=[33, 500, 77], salt=31)
+    compare(w, "few_bf16_out", out_dtype="bf16")
+    compare(w, "few_max_seq_len_512", max_seq_len=512)
+    c = inputs.prefill_paged_bf16(H=8, Hkv=4, D=128, Sq=9, page_size=1024, seq_lens=[1000, 7, 513], salt=32, shuffle_pages=False)
+    compare(c, "few_contiguous", paged=False)
 
 
 def test_prefill_bf16_output_contiguous_cache_and_loose_bound():
@@ -166,7 +201,12 @@ def test_errors(prefill_mode):
     w = inputs.prefill_paged_bf16(H=4, Hkv=2, D=64, Sq=16, page_size=16, seq_lens=[40, 60], salt=7)
     dd = runner.upload_prefill_paged(w)
     need = fb.fl_attn_prefill_paged_workspace_size(dd.tq, dd.tk, dd.kv)
-    if prefill_mode == "gather":
+    if prefill_mode == "auto":                      # 16 rows x 2 heads per kv head: the decode kernels and their workspace
+        assert need == fb.fl_attn_decode_workspace_size(dd.tq, dd.tk, dd.kv) > 0
+        small = fb.aux_desc(workspace=dd.keep[2][: need - 16])
+        assert fb.fl_attn_prefill_paged(dd.tq, dd.tk, dd.tv, dd.kv, dd.desc, small, dd.tout, dd.tlse) == fb.FL_ERR_WORKSPACE
+        assert fb.fl_attn_prefill_paged(dd.tq, dd.tk, dd.tv, dd.kv, dd.desc, None, dd.tout, dd.tlse) == fb.FL_ERR_AUX_MISSING
+    elif prefill_mode == "gather":
         assert need >= 2 * 2 * 2 * 60 * 64 * 2
         small = fb.aux_desc(workspace=dd.keep[2][: need - 256])
         assert fb.fl_attn_prefill_paged(dd.tq, dd.tk, dd.tv, dd.kv, dd.desc, small, dd.tout, dd.tlse) == fb.FL_ERR_WORKSPACE
