@@ -265,17 +265,19 @@ typedef struct {
   int32_t        reserved2;
 } fl_paged_kv;
 
-/* One decode step: for every sequence b, attention of its single query row (the token at position
- * len_b - 1) over its len_b cached keys and values -- the per-token call of the serving experiment
- * in Sec. 4.1.  Same arithmetic as fl_attn_fwd for that row (Eq. 3, score_mod of Eq. 4, online
- * softmax of Sec. 3.4); a causal mask is implied and changes nothing, FL_MASK_WINDOW keeps the last
- * window + 1 keys; other masks, biases, the second stream and epilogues are FL_ERR_UNSUPPORTED.
+/* One decode step: for every sequence b, attention of its newest query rows over its len_b cached keys and
+ * values -- the per-token call of the serving experiment in Sec. 4.1.  T = 1 is the token being generated (the
+ * row at position len_b - 1); T > 1 are the T newest tokens (a speculative step's verification): row i sits at
+ * position len_b - T + i and sees keys 0 .. that position, rows at negative positions (len_b < T) get out = 0
+ * and lse = -inf.  Same arithmetic as fl_attn_fwd for those rows (Eq. 3, score_mod of Eq. 4, online softmax of
+ * Sec. 3.4); the causal mask is implied, FL_MASK_WINDOW keeps each row's last window + 1 keys; other masks,
+ * biases, the second stream and epilogues are FL_ERR_UNSUPPORTED.
  *
- *   q        [B, 1, H, 1, D]  bf16, D in {64, 128}
+ *   q        [B, 1, H, T, D]  bf16, D in {64, 128}
  *   k_cache  [pages, 1, Hkv, page_size, D]  bf16, any strides with unit inner stride and 16-byte
  *   v_cache  [pages, 1, Hkv, page_size, D]  aligned rows (e.g. a view of [pages, page_size, Hkv, D]);
- *                                           Hkv divides H, H / Hkv <= 32
- *   out      [B, 1, H, 1, D]  bf16 or f32;  lse [B, 1, H, 1, 1] f32 or NULL
+ *                                           Hkv divides H, T * H / Hkv <= 64 (else FL_ERR_SHAPE)
+ *   out      [B, 1, H, T, D]  bf16 or f32;  lse [B, 1, H, T, 1] f32 or NULL
  *   aux      alibi_slopes for FL_MOD_ALIBI, and aux->workspace of fl_attn_decode_workspace_size bytes
  *            (per-split partial results; 16-byte aligned; contents undefined afterwards)
  *
@@ -305,20 +307,23 @@ size_t fl_attn_decode_workspace_size(const fl_tensor* q, const fl_tensor* k_cach
  *   aux      alibi_slopes for FL_MOD_ALIBI, and aux->workspace of fl_attn_prefill_paged_workspace_size bytes
  *            (16-byte aligned; contents undefined afterwards); may be NULL when neither is needed
  *
- * How: the forward kernel runs with each sequence's length read on the device: it stops at that length and places the
+ * How: chunks of so few rows that Sq * H / Hkv <= 64 (D 64 or 128) are an fl_attn_decode call on the same arguments
+ * (the cache is then read once per kv head; the workspace is that call's).  Otherwise the forward kernel runs with each
+ * sequence's length read on the device: it stops at that length and places the
  * query rows at its last Sq positions, so a short sequence costs its own length and nothing is synchronised with the
  * host.  For chunks of up to 1024 rows its key / value tile loads go to the pages themselves (page numbers from the block
  * table, fetched a step ahead; needs page_size >= 512 / D with a block table): no copy and no workspace.  For longer
  * chunks one pass first copies the cached rows of every sequence into dense tensors in the workspace (2 * 2 * len * Hkv
  * * D * 2 bytes read and written per sequence, small beside the Sq * len scores of such a chunk) and the tuned dense
- * kernel runs on those.  fl_attn_prefill_paged_workspace_size says which: 0 for the first way.
+ * kernel runs on those.  fl_attn_prefill_paged_workspace_size says which: 0 for reading in place.
  * Stream, ownership and error rules as for fl_attn_fwd.                                                  */
 fl_status fl_attn_prefill_paged(const fl_tensor* q, const fl_tensor* k_cache, const fl_tensor* v_cache,
                                 const fl_paged_kv* kv, const fl_variant_desc* desc, const fl_aux* aux,
                                 fl_tensor* out, fl_tensor* lse, void* stream);
 
-/* Bytes of aux->workspace that fl_attn_prefill_paged needs: 0 when the pages are read in place, else the dense
- * copies, 2 * B * Hkv * max_seq_len * D * 2 bytes (each rounded up to 256). */
+/* Bytes of aux->workspace that fl_attn_prefill_paged needs: fl_attn_decode_workspace_size for chunks of a few rows,
+ * 0 when the forward kernel reads the pages in place, else the dense copies, 2 * B * Hkv * max_seq_len * D * 2 bytes
+ * (each rounded up to 256). */
 size_t fl_attn_prefill_paged_workspace_size(const fl_tensor* q, const fl_tensor* k_cache, const fl_paged_kv* kv);
 
 /* A variant compiled at run time from user expressions (opaque; owned by the caller until released). */
