@@ -44,6 +44,12 @@
 #pragma once
 #include "fl_params.hpp"
 
+// Run-time compiled expressions are handed row and key indices inside the call's sizes when they may index a captured
+// array with them (1, the default); a variant without captured arrays is compiled with 0.
+#ifndef FL_USER_CLAMP
+#define FL_USER_CLAMP 1
+#endif
+
 namespace fl {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -305,7 +311,9 @@ struct Wave {
       } else if constexpr (C::MOD == kModCustom) {
         // (rows past Sq and keys past Sk are computed like the last valid ones and never used: an expression that
         // indexes a captured array by i or j must not be handed an index outside the call's sizes)
-        x = fl_user_score_mod(x * p.scale, b, g, h, ic[rb] + p.q_off, j < p.Sk ? j : p.Sk - 1, p) * kLog2e;
+        // (FL_USER_CLAMP 0: the expressions capture no array, so any index is as good as another and the minimum per
+        // score is saved)
+        x = fl_user_score_mod(x * p.scale, b, g, h, ic[rb] + p.q_off, FL_USER_CLAMP && j >= p.Sk ? p.Sk - 1 : j, p) * kLog2e;
       } else {
         x *= c_scale;
       }
@@ -454,7 +462,7 @@ struct Wave {
           if constexpr ((MASK & kMaskWindow) != 0) hide = hide || c < d_lo[rb];
           if constexpr ((MASK & kMaskDoc) != 0) hide = hide || kd[r] != qdoc[rb];
           if constexpr ((MASK & kMaskCustom) != 0)  // (valid indices only, as for the score_mod; a key past Sk is hidden already)
-            hide = hide || fl_user_mask(b, g, h, ic[rb] + p.q_off, jl + c < p.Sk ? jl + c : p.Sk - 1, p);
+            hide = hide || fl_user_mask(b, g, h, ic[rb] + p.q_off, FL_USER_CLAMP && jl + c >= p.Sk ? p.Sk - 1 : jl + c, p);
           if (hide) sc[rb][nb][r] = -INFINITY;
         }
     }
@@ -802,26 +810,20 @@ fwd_bf16_kernel(const FwdParams call) {
   const int t_lo = k_lo / BN;
   const int t_hi = (k_hi + BN - 1) / BN;
   const int nks = (p.Sk + kSumBlock - 1) / kSumBlock;
+  // Query-side summaries of the workgroup's and of the wave's rows.  All of them are requested before any is used (past
+  // the last block: the last block again, which changes no minimum or maximum), and so are, further down, the key-side
+  // answers for the first tiles: the set-up then waits for memory once.
   int2 qs_wg = make_int2(0, 0), qs_wave = make_int2(0, 0);
+  constexpr int NQW = C::BM / kSumBlock;
+  int2 qraw_wg[NQW], qraw_wave[RB];
   if constexpr ((MASK & kMaskDoc) != 0) {
     const int nqs = (p.Sq + kSumBlock - 1) / kSumBlock;
     const int2* qsum = p.q_sum + (int64_t)b * nqs;
-    const int s0 = i0 / kSumBlock;
-    qs_wg = qsum[s0];
-    for (int ww = 1; ww < C::BM / kSumBlock; ++ww)
-      if (s0 + ww < nqs) {
-        const int2 t = qsum[s0 + ww];
-        qs_wg.x = min(qs_wg.x, t.x);
-        qs_wg.y = max(qs_wg.y, t.y);
-      }
-    const int sw = iw / kSumBlock;
-    qs_wave = qsum[min(sw, nqs - 1)];
-    for (int rb = 1; rb < RB; ++rb)
-      if (sw + rb < nqs) {
-        const int2 t = qsum[sw + rb];
-        qs_wave.x = min(qs_wave.x, t.x);
-        qs_wave.y = max(qs_wave.y, t.y);
-      }
+    const int s0 = i0 / kSumBlock, sw = iw / kSumBlock;
+#pragma unroll
+    for (int ww = 0; ww < NQW; ++ww) qraw_wg[ww] = qsum[min(s0 + ww, nqs - 1)];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) qraw_wave[rb] = qsum[min(sw + rb, nqs - 1)];
   }
   const int2* ksum = (MASK & kMaskDoc) ? p.kv_sum + (int64_t)b * nks : nullptr;
   // A mask given as an expression can come with a map of tile classes, written by block_map_kernel below: one byte per
@@ -910,19 +912,62 @@ fwd_bf16_kernel(const FwdParams call) {
     }
     return make_int2(__builtin_amdgcn_readfirstlane(ks.x), __builtin_amdgcn_readfirstlane(ks.y));
   };
+  // Set-up: what the skipper knows about the first tiles of the range, requested in one go (with the loads of Q and of
+  // the query-side summaries, before anything waits), so that building the first tile list costs one memory round
+  // trip instead of one per tile.
+  constexpr int NPF = 4;
+  int2 kfirst[NPF];
+  uint32_t bfirst[NPF];
+  if constexpr ((MASK & kMaskDoc) != 0 || kMapped) {
+#pragma unroll
+    for (int u = 0; u < NPF; ++u) {
+      kfirst[u] = tile_keys_lane(t_lo + u);
+      bfirst[u] = tile_bits_lane(t_lo + u);
+    }
+  }
+  if constexpr ((MASK & kMaskDoc) != 0) {
+    qs_wg = qraw_wg[0];
+#pragma unroll
+    for (int ww = 1; ww < NQW; ++ww) {
+      qs_wg.x = min(qs_wg.x, qraw_wg[ww].x);
+      qs_wg.y = max(qs_wg.y, qraw_wg[ww].y);
+    }
+    qs_wave = qraw_wave[0];
+#pragma unroll
+    for (int rb = 1; rb < RB; ++rb) {
+      qs_wave.x = min(qs_wave.x, qraw_wave[rb].x);
+      qs_wave.y = max(qs_wave.y, qraw_wave[rb].y);
+    }
+  }
+  auto first_keys = [&](int t, uint32_t& bw) __attribute__((always_inline)) -> int2 {   // t_lo <= t < t_lo + NPF, uniform
+    int2 ks = kfirst[0];
+    bw = bfirst[0];
+#pragma unroll
+    for (int u = 1; u < NPF; ++u)
+      if (t - t_lo == u) {
+        ks = kfirst[u];
+        bw = bfirst[u];
+      }
+    return make_int2(__builtin_amdgcn_readfirstlane(ks.x), __builtin_amdgcn_readfirstlane(ks.y));
+  };
   // Is every score of tile t hidden from the workgroup's rows?  (t and ks may be per lane)
   auto tile_hidden = [&](int t, int2 ks) __attribute__((always_inline)) -> bool {
     if constexpr (kMapped) return my_classes(ks) == 0;
     else return classify_block(MASK, pos0, pos_last, t * BN, t * BN + BN - 1, p.Sk, p.window, p.prefix, qs_wg, ks) == kSkip;
   };
   // First tile at or after t with something visible to the workgroup (t_hi if none), and what the skipper knows about it.
-  auto next_tile = [&](int t, int2& ks, uint32_t& bw) __attribute__((always_inline)) -> int {   // uniform over the workgroup
+  // (setup: called while the first tile list is built, when the answers for the first NPF tiles are at hand)
+  auto next_tile = [&](int t, int2& ks, uint32_t& bw, auto setup) __attribute__((always_inline)) -> int {   // uniform over the workgroup
     ks = make_int2(0, 0);
     bw = 0;
     if constexpr ((MASK & kMaskDoc) != 0 || kMapped) {
       if (t < t_hi) {
-        bw = t == tpre ? bpre : tile_bits_lane(t);
-        ks = t == tpre ? fetched_keys() : tile_keys(t);
+        if (decltype(setup)::value && t < t_lo + NPF) {
+          ks = first_keys(t, bw);
+        } else {
+          bw = t == tpre ? bpre : tile_bits_lane(t);
+          ks = t == tpre ? fetched_keys() : tile_keys(t);
+        }
         // the usual case first: tile t itself has something visible (one uniform check)
         if (tile_hidden(t, ks)) {
           // a run of hidden tiles (the other documents of a long sequence): 64 tiles per round, one per lane
@@ -1107,15 +1152,15 @@ fwd_bf16_kernel(const FwdParams call) {
     int tl[NTL];
     int2 tks[NTL];                                 // what the skipper knows about those tiles (document masks, mapped expressions)
     uint32_t tbw[NTL];                             // this lane's hidden-score bits of those tiles (mapped expressions)
-    tl[0] = next_tile(t_lo, tks[0], tbw[0]);
+    tl[0] = next_tile(t_lo, tks[0], tbw[0], std::integral_constant<bool, true>());
     if (tl[0] < t_hi) {
-      auto after = [&](int t, int2& ks, uint32_t& bw) __attribute__((always_inline)) {
+      auto after = [&](int t, int2& ks, uint32_t& bw, auto setup) __attribute__((always_inline)) {
         ks = make_int2(0, 0);
         bw = 0;
-        return t < t_hi ? next_tile(t + 1, ks, bw) : t_hi;
+        return t < t_hi ? next_tile(t + 1, ks, bw, setup) : t_hi;
       };
 #pragma unroll
-      for (int u = 1; u < NTL; ++u) tl[u] = after(tl[u - 1], tks[u], tbw[u]);
+      for (int u = 1; u < NTL; ++u) tl[u] = after(tl[u - 1], tks[u], tbw[u], std::integral_constant<bool, true>());
       w.template bias_dma<0>(tl[0] * BN);
       if (tl[1] < t_hi) w.template bias_dma<1>(tl[1] * BN);
       // K of tiles tl[0 .. SPB] into slots 0 .. SPB, V of tiles tl[0 .. SPB - 1] into slots 0 .. SPB - 1
@@ -1250,7 +1295,7 @@ fwd_bf16_kernel(const FwdParams call) {
           tks[u] = tks[u + 1];
           tbw[u] = tbw[u + 1];
         }
-        tl[NTL - 1] = after(tl[NTL - 1], tks[NTL - 1], tbw[NTL - 1]);
+        tl[NTL - 1] = after(tl[NTL - 1], tks[NTL - 1], tbw[NTL - 1], std::integral_constant<bool, false>());
         full0 = fulln;
         if constexpr ((MASK & kMaskDoc) == 0) {    // consecutive tiles: advance the bases until the list ends
           if (tl[SPB] < t_hi) vb += vstep;

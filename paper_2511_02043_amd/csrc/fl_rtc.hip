@@ -372,7 +372,9 @@ fl_status fl_compile_variant_grad(const char* score_mod_expr, const char* score_
   if (score_mod_expr) v->mod_expr = score_mod_expr;
   if (score_mod_grad_expr) v->grad_expr = score_mod_grad_expr;
   if (mask_expr) v->mask_expr = mask_expr;
-  std::string src = "#include \"fl_kernel_bf16.hpp\"\n" + hook_source(v, false);
+  bool captures = false;
+  for (int n = 0; n < 4; ++n) captures = captures || adt[n] != 0;
+  std::string src = std::string("#define FL_USER_CLAMP ") + (captures ? "1" : "0") + "\n#include \"fl_kernel_bf16.hpp\"\n" + hook_source(v, false);
   src += "template __global__ void ";
   src += inst;
   src += "(const fl::FwdParams);\n";
