@@ -51,10 +51,12 @@ struct DecodeParams {
 template <int D_, int MOD_, int CB_ = 1>
 struct DecodeCfg : BwdCfg<D_, MOD_, 0, 32, 1> {
   static constexpr int CB = CB_;                   // blocks of 32 (query row, head) columns per kv head
-  // D = 128: four waves (one per SIMD) with 16 KiB stages; D = 64: eight waves (two per SIMD) with 8 KiB
+  // D = 128: five waves with 16 KiB stages, which fill the CU's 160 KiB of LDS (four, one per SIMD, moved 4 % fewer
+  // bytes per second; three waves with three stages each -- more bytes in flight per wave, fewer waves -- 15 % fewer;
+  // with two column blocks the register budget allows one wave per SIMD only); D = 64: eight waves (two per SIMD) with 8 KiB
   // stages -- a tile carries half the bytes there, and a second wave on the SIMD hides the first one's
-  // per-tile chain of waits (load, LDS read, matrix core, exponentials)
-  static constexpr int NWV = D_ == 128 ? 4 : 8;    // waves per workgroup
+  // per-tile chain of waits (load, LDS read, matrix core, exponentials); ten waves, or six with three stages, measured no better
+  static constexpr int NWV = D_ == 128 ? (CB_ == 1 ? 5 : 4) : 8;    // waves per workgroup
   static constexpr int NSTG = 2;                   // ring stages per wave
   // register budget: the workgroup fills a CU's LDS, so D = 128 has one wave per SIMD anyway; two column blocks
   // there need more than 256 registers
