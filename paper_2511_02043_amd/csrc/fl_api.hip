@@ -469,6 +469,157 @@ __global__ void __launch_bounds__(256) epi_bwd_kernel(const EpiBwdParams e) {
   }
 }
 
+// The same with LPR lanes per row, eight channels per lane (16-byte loads and stores), 64 / LPR rows per wave: for tensors
+// whose rows are 16-byte aligned (the host checks).  LPR = Dc / 8; lanes whose channels lie past Dv only write the zero
+// padding of the per-stream dO.  The rms_weight partial sums are per workgroup as above, over 4 * 64 / LPR rows.
+template <int LPR>
+__global__ void __launch_bounds__(256) epi_bwd_rows_kernel(const EpiBwdParams e) {
+  constexpr int RPW = 64 / LPR;
+  const int64_t rows = (int64_t)e.B * e.G * e.H * e.Sq;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, sub = lane % LPR;
+  const int64_t row_raw = ((int64_t)blockIdx.x * 4 + wave) * RPW + lane / LPR;
+  const bool live = row_raw < rows;
+  const int64_t row = live ? row_raw : rows - 1;
+  const int c0 = sub * 8;
+  const bool ok = live && c0 < e.Dv;               // Dv is a multiple of 8: a lane's channels are all inside or all outside
+  const int i = (int)(row % e.Sq);
+  const int h = (int)((row / e.Sq) % e.H);
+  const int g = (int)((row / ((int64_t)e.Sq * e.H)) % e.G);
+  const int b = (int)(row / ((int64_t)e.Sq * e.H * e.G));
+  auto off = [&](const fl::View& v) { return b * v.sb + g * v.sg + h * v.sh + (int64_t)i * v.ss + c0; };
+  auto gsum = [](float x) {                        // over the lanes of a row
+#pragma unroll
+    for (int o = LPR / 2; o >= 1; o >>= 1) x += __shfl_xor(x, o);
+    return x;
+  };
+  auto load8 = [&](const fl::View& v, float (&f)[8]) {
+    uint4 q = make_uint4(0, 0, 0, 0);
+    if (ok) q = *(const uint4*)((const uint16_t*)v.ptr + off(v));
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      f[2 * k] = __uint_as_float(w[k] << 16);
+      f[2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u);
+    }
+  };
+  auto load8f = [&](const float* src, float (&f)[8]) {   // dense fp32 [rows, Dv] or [Dv]
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f), c = a;
+    if (ok) {
+      a = *(const float4*)src;
+      c = *(const float4*)(src + 4);
+    }
+    f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = c.x; f[5] = c.y; f[6] = c.z; f[7] = c.w;
+  };
+  auto pack8 = [](const float (&f)[8]) {
+    return make_uint4(fl::pack_bf16(f[0], f[1]), fl::pack_bf16(f[2], f[3]), fl::pack_bf16(f[4], f[5]), fl::pack_bf16(f[6], f[7]));
+  };
+  const bool need_o = e.o[0] != nullptr;
+  const float lam = e.ns == 2 ? e.lambda[h] : 0.f;
+  float dout[8], ov[8], dy[8], o1[8], o2[8], x[8], wv[8], dx[8];
+  load8(e.dout, dout);
+  load8(e.out, ov);
+#pragma unroll
+  for (int k = 0; k < 8; ++k) dy[k] = dout[k];
+  if (e.has_gate) {
+    float gv[8], dg[8];
+    load8(e.gate, gv);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const float sg = 1.f / (1.f + __expf(-gv[k]));
+      dy[k] = dout[k] * sg;
+      dg[k] = dout[k] * ov[k] * (1.f - sg);        // dout * y * sg (1 - sg) with out = y * sg
+    }
+    if (ok && e.dgate.ptr != nullptr) {
+      if (e.dgate_f32) {
+        float* dst = (float*)e.dgate.ptr + off(e.dgate);
+        *(float4*)dst = make_float4(dg[0], dg[1], dg[2], dg[3]);
+        *(float4*)(dst + 4) = make_float4(dg[4], dg[5], dg[6], dg[7]);
+      } else {
+        *(uint4*)((uint16_t*)e.dgate.ptr + off(e.dgate)) = pack8(dg);
+      }
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < 8; ++k) o1[k] = o2[k] = wv[k] = 0.f;
+  if (need_o) load8f(e.o[0] + row * e.Dv + c0, o1);
+  if (e.ns == 2) load8f(e.o[1] + row * e.Dv + c0, o2);
+  if (e.has_rms) {
+    if (e.rms_w != nullptr) load8f(e.rms_w + c0, wv);
+    else
+#pragma unroll
+      for (int k = 0; k < 8; ++k) wv[k] = ok ? 1.f : 0.f;
+  }
+  float sum_x2 = 0.f, sum_wdyx = 0.f, sum_dout_out = 0.f;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    x[k] = o1[k] - lam * o2[k];
+    sum_dout_out += dout[k] * ov[k];
+    sum_x2 += x[k] * x[k];
+    sum_wdyx += wv[k] * dy[k] * x[k];
+    dx[k] = dy[k];
+  }
+  if (e.has_rms) {
+    const float ms = gsum(sum_x2) / (float)e.Dv;
+    const float r = sqrtf(ms + e.rms_eps);
+    const float dot = gsum(sum_wdyx);
+    const float c3 = dot / ((float)e.Dv * r * r * r);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) dx[k] = wv[k] * dy[k] / r - x[k] * c3;
+    if (e.dw_part != nullptr) {                    // rows of the wave by shuffles, waves of the workgroup through LDS
+      __shared__ float dw_rows[4][LPR * 8];
+      float t[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        t[k] = dy[k] * x[k] / r;                   // (channels past Dv and rows past the end carry dy = x = 0)
+#pragma unroll
+        for (int o = LPR; o < 64; o <<= 1) t[k] += __shfl_xor(t[k], o);
+      }
+      if (lane < LPR)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) dw_rows[wave][c0 + k] = t[k];
+      __syncthreads();
+      if ((int)threadIdx.x < e.Dv)
+        e.dw_part[(int64_t)blockIdx.x * e.Dv + threadIdx.x] =
+            (dw_rows[0][threadIdx.x] + dw_rows[1][threadIdx.x]) + (dw_rows[2][threadIdx.x] + dw_rows[3][threadIdx.x]);
+    }
+  }
+  float d1 = 0.f, d2 = 0.f, dl = 0.f;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    d1 += dx[k] * o1[k];
+    d2 += -lam * dx[k] * o2[k];
+    dl += -dx[k] * o2[k];
+  }
+  if (live && c0 < e.Dc) {
+    float z[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) z[k] = ok ? dx[k] : 0.f;
+    *(uint4*)(e.d_o[0] + row * e.Dc + c0) = pack8(z);
+    if (e.ns == 2) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) z[k] = ok ? -lam * dx[k] : 0.f;
+      *(uint4*)(e.d_o[1] + row * e.Dc + c0) = pack8(z);
+    }
+  }
+  // without recomputed outputs (one stream, no RMSNorm): delta = rowsum(dy * y) = rowsum(dout * out)
+  d1 = need_o ? gsum(d1) : gsum(sum_dout_out);
+  if (e.ns == 2) {
+    d2 = gsum(d2);
+    dl = gsum(dl);
+  }
+  if (live && sub == 0) {
+    e.delta[0][row] = d1;
+    if (e.ns == 2) {
+      e.delta[1][row] = d2;
+      if (e.dl_rows != nullptr) e.dl_rows[row] = dl;
+    }
+    for (int s = 0; s < e.ns; ++s) {
+      const float l = e.lse[b * e.lse_sb + (int64_t)(e.ns * g + s) * e.lse_sg + h * e.lse_sh + i];
+      e.lse2[s][row] = l == -INFINITY ? INFINITY : l * fl::kLog2e;
+    }
+  }
+}
+
 // drms_weight[c] = sum over the workgroups' partial sums; one workgroup per channel, fixed summation order
 __global__ void __launch_bounds__(256) reduce_drms_kernel(const float* dw_part, float* dw, int64_t nwg, int Dv) {
   __shared__ float part[256];
@@ -522,6 +673,50 @@ __global__ void __launch_bounds__(256) reduce_dbias_kernel(const uint16_t* ds, f
         }
   float* dst = (float*)out.ptr + b * out.sb + g * out.sg + h * out.sh + (int64_t)i * out.si + (int64_t)j * out.sj;
   *dst = accumulate ? *dst + s : s;                // the second softmax stream adds to the first one's sum
+}
+
+// The same for a bias that is not broadcast along the keys, Sk a multiple of 8 and a gradient tensor with unit key stride
+// and 16-byte aligned rows: eight keys per thread (one 16-byte load per staged row), four rows in flight.  The terms of an
+// output element are added in the same order as above.
+__global__ void __launch_bounds__(256) reduce_dbias_vec8_kernel(const uint16_t* ds, fl::BiasView out, int B, int G, int H, int Sq, int Sk,
+                                                                int ob, int og, int oh, int oi, int64_t total8, int accumulate) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total8) return;
+  const int oj8 = Sk / 8;
+  const int j = (int)(idx % oj8) * 8, i = (int)((idx / oj8) % oi), h = (int)((idx / ((int64_t)oj8 * oi)) % oh);
+  const int g = (int)((idx / ((int64_t)oj8 * oi * oh)) % og), b = (int)(idx / ((int64_t)oj8 * oi * oh * og));
+  const int nb = ob == 1 ? B : 1, ng = og == 1 ? G : 1, nh = oh == 1 ? H : 1, ni = oi == 1 ? Sq : 1;
+  const int64_t n_terms = (int64_t)nb * ng * nh * ni;
+  auto term = [&](int64_t n) -> const uint4* {     // n-th staged row of this output, in the nesting order b, g, h, i
+    const int ii = (int)(n % ni), hh = (int)((n / ni) % nh), gg = (int)((n / ((int64_t)ni * nh)) % ng);
+    const int bb = (int)(n / ((int64_t)ni * nh * ng));
+    return (const uint4*)(ds + ((((int64_t)(b + bb) * G + (g + gg)) * H + (h + hh)) * Sq + (i + ii)) * Sk + j);
+  };
+  float s[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) s[k] = 0.f;
+  auto add = [&](const uint4& v) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      s[2 * k] += __uint_as_float(w[k] << 16);
+      s[2 * k + 1] += __uint_as_float(w[k] & 0xFFFF0000u);
+    }
+  };
+  int64_t n = 0;
+  for (; n + 4 <= n_terms; n += 4) {
+    const uint4 v0 = *term(n), v1 = *term(n + 1), v2 = *term(n + 2), v3 = *term(n + 3);
+    add(v0); add(v1); add(v2); add(v3);
+  }
+  for (; n < n_terms; ++n) add(*term(n));
+  float4* dst = (float4*)((float*)out.ptr + b * out.sb + g * out.sg + h * out.sh + (int64_t)i * out.si + j);
+  if (accumulate) {                                // the second softmax stream adds to the first one's sum
+    const float4 a = dst[0], c = dst[1];
+    s[0] += a.x; s[1] += a.y; s[2] += a.z; s[3] += a.w;
+    s[4] += c.x; s[5] += c.y; s[6] += c.z; s[7] += c.w;
+  }
+  dst[0] = make_float4(s[0], s[1], s[2], s[3]);
+  dst[1] = make_float4(s[4], s[5], s[6], s[7]);
 }
 
 // bf16 [B, G, H, S, D] view -> dense [B, G, H, S, Dc] with zero channels past D (8 channels per thread)
@@ -1374,10 +1569,23 @@ fl_status fl_attn_bwd_ex(const fl_tensor* q, const fl_tensor* k, const fl_tensor
   ep.rms_eps = desc->rms_eps;
   ep.B = (int)B; ep.G = (int)G; ep.H = (int)H; ep.Sq = (int)Sq; ep.Dv = (int)Dv; ep.Dc = Dc;
   ep.ns = ns; ep.has_gate = has_gate; ep.has_rms = has_rms;
-  hipLaunchKernelGGL(epi_bwd_kernel, blocks(rows_q * 64), dim3(256), 0, stream, ep);
+  // rows 16-byte aligned everywhere: several rows per wave, eight channels per lane; else one row per wave
+  auto rows_aligned = [](const fl::View& v, int elem_bytes) {
+    if (v.ptr == nullptr) return true;
+    const int64_t m = 16 / elem_bytes;
+    return ((uintptr_t)v.ptr) % 16 == 0 && v.sb % m == 0 && v.sg % m == 0 && v.sh % m == 0 && v.ss % m == 0;
+  };
+  const bool by_rows = rows_aligned(ep.dout, 2) && rows_aligned(ep.out, 2) && rows_aligned(ep.gate, 2) &&
+                       rows_aligned(ep.dgate, ep.dgate_f32 ? 4 : 2) && ((uintptr_t)ep.rms_w) % 16 == 0;
+  const int rows_per_wg = by_rows ? 4 * (64 / (Dc / 8)) : 4;
+  const int64_t epi_wgs = (rows_q + rows_per_wg - 1) / rows_per_wg;
+  if (epi_wgs > 0x7fffffffLL) return fail(FL_ERR_SHAPE, "too many rows");
+  if (!by_rows) hipLaunchKernelGGL(epi_bwd_kernel, dim3((unsigned)epi_wgs), dim3(256), 0, stream, ep);
+  else if (Dc == 64) hipLaunchKernelGGL(epi_bwd_rows_kernel<8>, dim3((unsigned)epi_wgs), dim3(256), 0, stream, ep);
+  else hipLaunchKernelGGL(epi_bwd_rows_kernel<16>, dim3((unsigned)epi_wgs), dim3(256), 0, stream, ep);
   if (ep.dw_part != nullptr)
     hipLaunchKernelGGL(reduce_drms_kernel, dim3((unsigned)Dv), dim3(256), 0, stream, (const float*)ep.dw_part, extra->drms_weight,
-                       (int64_t)((rows_q + 3) / 4), (int)Dv);
+                       epi_wgs, (int)Dv);
   if (ep.dl_rows != nullptr)
     hipLaunchKernelGGL(reduce_dlambda_kernel, dim3((unsigned)H), dim3(256), 0, stream, (const float*)ep.dl_rows, extra->dlambda, (int)B, (int)G,
                        (int)H, (int)Sq);
@@ -1448,9 +1656,17 @@ fl_status fl_attn_bwd_ex(const fl_tensor* q, const fl_tensor* k, const fl_tensor
       if (dbias[nb].ptr != nullptr) {               // this stream's dS, summed over the axes the bias broadcasts along
         const fl_tensor* gt = &extra->dbias[nb];
         const int64_t total = gt->size[0] * gt->size[1] * gt->size[2] * gt->size[3] * gt->size[4];
-        hipLaunchKernelGGL(reduce_dbias_kernel, blocks(total), dim3(256), 0, stream, (const uint16_t*)p.ds_stage, dbias[nb], (int)B, (int)G,
-                           (int)H, (int)Sq, (int)Sk, (int)gt->size[0], (int)gt->size[1], (int)gt->size[2], (int)gt->size[3],
-                           (int)gt->size[4], total, s);
+        const fl::BiasView& bv = dbias[nb];
+        const bool vec8 = gt->size[4] == Sk && Sk % 8 == 0 && bv.sj == 1 && ((uintptr_t)bv.ptr) % 16 == 0 && bv.sb % 4 == 0 &&
+                          bv.sg % 4 == 0 && bv.sh % 4 == 0 && bv.si % 4 == 0;
+        if (vec8)
+          hipLaunchKernelGGL(reduce_dbias_vec8_kernel, blocks(total / 8), dim3(256), 0, stream, (const uint16_t*)p.ds_stage, bv, (int)B,
+                             (int)G, (int)H, (int)Sq, (int)Sk, (int)gt->size[0], (int)gt->size[1], (int)gt->size[2], (int)gt->size[3],
+                             total / 8, s);
+        else
+          hipLaunchKernelGGL(reduce_dbias_kernel, blocks(total), dim3(256), 0, stream, (const uint16_t*)p.ds_stage, bv, (int)B, (int)G,
+                             (int)H, (int)Sq, (int)Sk, (int)gt->size[0], (int)gt->size[1], (int)gt->size[2], (int)gt->size[3],
+                             (int)gt->size[4], total, s);
       }
     if ((e = run_bwd_dkdv(be, p, (int)nb_k, stream)) != hipSuccess) return fail(FL_ERR_LAUNCH, "dk/dv launch: %s", hipGetErrorString(e));
     if (p.hsplit > 1) {
