@@ -21,11 +21,13 @@ REL_L2 = 5e-3
 MAX_REL = 1e-2
 
 
-def compare(w, grad_dtype="f32", label=None, rel_l2=REL_L2):
+def compare(w, grad_dtype="f32", label=None, rel_l2=REL_L2, tweak=None):
     max_rel = 2 * MAX_REL if w.rmsnorm else MAX_REL
     import torch
     dout = inputs.dout_for(w)
     db = runner.upload_backward_ex(w, dout, grad_dtype=grad_dtype)
+    if tweak is not None:
+        tweak(db)
     db.fwd.run_checked()
     for t in db.grads.values():
         for x in (t if isinstance(t, list) else [t]):
@@ -79,6 +81,23 @@ def test_backward_ex_matches_oracle(name):
 def test_bf16_gradient_outputs():
     compare(C(D=64, pos_mask="causal", n_bias=1, gate=True, S=200), "bf16", label="bias_gate_bf16_grads")
     compare(inputs.differential_bf16(B=1, H=2, S=200), "bf16", label="diff_rms_bf16_grads")
+
+
+def test_rms_weight_without_16_byte_alignment():
+    """The derivative of the epilogue reads eight channels per lane when every row it touches is 16-byte aligned; an
+    rms_weight that is only 4-byte aligned (the header asks for no more) takes the one-row-per-wave kernel instead."""
+    import torch
+    w = C(D=64, pos_mask="causal", n_bias=1, diff=True, rmsnorm=True, gate=True, S=180)
+
+    def shift(db):
+        buf = torch.empty(len(w.rms_weight) + 1, dtype=torch.float32, device="cuda:0")
+        buf[1:].copy_(torch.from_numpy(np.asarray(w.rms_weight, np.float32)))
+        db.keep.append(buf)
+        assert buf[1:].data_ptr() % 16 == 4
+        db.aux.rms_weight = buf[1:].data_ptr()
+        db.fwd.aux.rms_weight = buf[1:].data_ptr()
+
+    compare(w, "f32", label="rms_weight_4_byte_aligned", tweak=shift)
 
 
 def test_benchmark_shapes_reduced_batch():
