@@ -230,3 +230,50 @@ def test_decode_of_several_rows():
     dd = runner.upload_prefill_paged(w)
     ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda:0")
     assert fb.fl_attn_decode(dd.tq, dd.tk, dd.tv, dd.kv, dd.desc, fb.aux_desc(workspace=ws), dd.tout, dd.tlse) == fb.FL_ERR_SHAPE
+
+
+@pytest.mark.parametrize("T", [8, 16])
+def test_decode_of_several_rows_full_size_sampled(T):
+    """The decode workload at full size (64 sequences of 4k-8k cached tokens, 32 / 8 heads, D = 128, 16-token pages) with
+    the T newest rows of every sequence (one and two blocks of MFMA columns), through fl_attn_prefill_paged as
+    `bench.py --prefill-chunk T --decode-batch 64` launches it; two sequences against the oracle, everything finite."""
+    import torch
+    from paper_2511_02043_amd import binding as fb
+    B, H, Hkv, D, ctx, ps = 64, 32, 8, 128, 8192, 16
+    g = torch.Generator(device="cuda").manual_seed(11 + T)
+    rng = np.random.Generator(np.random.PCG64(11 + T))
+    lens = rng.integers(ctx // 2, ctx + 1, size=B).astype(np.int32)
+    npg = (lens + ps - 1) // ps
+    pool = rng.permutation(int(npg.sum())).astype(np.int32)
+    table = np.zeros((B, int(npg.max())), dtype=np.int32)
+    pos = 0
+    for b in range(B):
+        table[b, :npg[b]] = pool[pos:pos + npg[b]]
+        pos += npg[b]
+    dev = "cuda:0"
+    kc = torch.randn((int(npg.sum()), ps, Hkv, D), generator=g, device=dev).to(torch.bfloat16)
+    vc = torch.randn((int(npg.sum()), ps, Hkv, D), generator=g, device=dev).to(torch.bfloat16)
+    q = torch.randn((B, 1, H, T, D), generator=g, device=dev).to(torch.bfloat16)
+    out = torch.full((B, 1, H, T, D), float("nan"), dtype=torch.float32, device=dev)
+    lse = torch.full((B, 1, H, T, 1), float("nan"), dtype=torch.float32, device=dev)
+    t_table, t_lens = torch.from_numpy(table).to(dev), torch.from_numpy(lens).to(dev)
+    tq, tout, tlse = fb.tensor_desc(q), fb.tensor_desc(out), fb.tensor_desc(lse)
+    tk, tv = fb.tensor_desc(kc.permute(0, 2, 1, 3)[:, None]), fb.tensor_desc(vc.permute(0, 2, 1, 3)[:, None])
+    kv = fb.paged_kv(block_table=t_table, page_size=ps, seq_lens=t_lens, max_seq_len=int(lens.max()))
+    desc = fb.variant_desc(scale=D ** -0.5, mask=fb.FL_MASK_CAUSAL)
+    need = fb.fl_attn_prefill_paged_workspace_size(tq, tk, kv)
+    assert need == fb.fl_attn_decode_workspace_size(tq, tk, kv) > 0      # the decode kernels' route
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    fb.check(fb.fl_attn_prefill_paged(tq, tk, tv, kv, desc, fb.aux_desc(workspace=ws), tout, tlse))
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all()) and bool(torch.isfinite(lse).all())
+    for b in (int(np.argmax(lens)), 23):
+        pages = torch.from_numpy(table[b, :npg[b]].astype(np.int64)).to(dev)
+        k_b = kc[pages].float().cpu().numpy()
+        v_b = vc[pages].float().cpu().numpy()
+        ident = np.arange(npg[b], dtype=np.int32)[None]
+        ref, ref_lse = do.prefill_attention(q[b:b + 1, 0].float().cpu().numpy(), k_b, v_b, ident, lens[b:b + 1], scale=D ** -0.5)
+        err = float(np.max(np.abs(out[b, 0].cpu().numpy() - ref[0])))
+        le = float(np.max(np.abs(lse[b, 0, :, :, 0].cpu().numpy() - ref_lse[0])))
+        print(f"decode of {T} rows at full size, sequence {b} (len {lens[b]}): max_abs={err:.3e} lse={le:.3e}", flush=True)
+        assert err <= 1e-2 and le <= 1e-3
