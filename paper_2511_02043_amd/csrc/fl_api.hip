@@ -1819,13 +1819,6 @@ fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_
   return FL_OK;
 }
 
-// Does the forward kernel read these pages in place?  It can when every direct-load instruction of a tile (512 / D
-// consecutive tokens) lies in one page.  It does for chunks of up to 1024 rows: the in-place kernel is a run-time
-// instantiated shape (two ring slots; four waves, eight from 512 rows on at head dim 128) with a page lookup and a
-// 64-bit base per load instruction and runs at 0.75 - 0.9 of the tuned dense kernel, while the copy costs the time of
-// about 100 query rows of attention.  Measured at 32 / 8 heads, D = 128, 8192 cached tokens (ms in place / copied):
-// 64 rows 0.76 / 1.32, 128 rows 0.43 / 0.55, 256 rows 0.40 / 0.41, 384 rows 0.66 / 0.59, 512 rows 0.59 / 0.64,
-// 1024 rows 1.07 / 1.06, 2048 rows 1.95 / 1.77.
 // Chunks of so few rows that all (query row, head) pairs of a kv head fit the columns of the decode kernels go
 // there: the cache is then read once per kv head instead of once per query head, and no MFMA row is idle.
 static bool prefill_as_decode(int64_t D, int64_t H, int64_t Hkv, int64_t Sq) {
@@ -1833,8 +1826,16 @@ static bool prefill_as_decode(int64_t D, int64_t H, int64_t Hkv, int64_t Sq) {
   return (D == 64 || D == 128) && Hkv > 0 && H % Hkv == 0 && Sq * (H / Hkv) <= kDecodeMaxPairs;
 }
 
-static bool prefill_in_place(int64_t D, int64_t page_size, bool has_table, int64_t Sq) {
+// Does the forward kernel read these pages in place?  It can when every direct-load instruction of a tile (512 / D
+// consecutive tokens) lies in one page.  It does for chunks of up to 1024 rows: the in-place kernel (two ring slots; four
+// waves, eight from 512 rows on at head dim 128) looks up a page and forms a base per wave and tile (per load instruction
+// when pages hold fewer than the wave's 8 or 16 tokens) and runs at 0.85 - 0.93 of the tuned dense kernel, while the copy costs the time of
+// about 100 query rows of attention.  Measured at 32 / 8 heads, D = 128, 8192 cached tokens (ms in place / copied):
+// 64 rows 0.66 / 1.32, 128 rows 0.36 / 0.55, 256 rows 0.34 / 0.41, 512 rows 0.57 / 0.64,
+// 1024 rows 1.03 / 1.06, 2048 rows 1.89 / 1.77.
+static bool prefill_in_place(int64_t D, int64_t page_size, bool has_table, int64_t Sq, int64_t page_stride) {
   if (g_tuning.prefill_gather == 1 || !(D == 32 || D == 64 || D == 128)) return false;
+  if (page_stride * 2 >= (1LL << 32)) return false;   // the kernel multiplies page numbers by 32-bit byte strides
   if (has_table && page_size < 512 / D) return false;
   return g_tuning.prefill_gather == 2 || Sq <= 1024;
 }
@@ -1842,7 +1843,7 @@ static bool prefill_in_place(int64_t D, int64_t page_size, bool has_table, int64
 size_t fl_attn_prefill_paged_workspace_size(const fl_tensor* q, const fl_tensor* k_cache, const fl_paged_kv* kv) {
   if (q == nullptr || k_cache == nullptr || kv == nullptr) return 0;
   if (prefill_as_decode(q->size[4], q->size[2], k_cache->size[2], q->size[3])) return fl_attn_decode_workspace_size(q, k_cache, kv);
-  if (prefill_in_place(q->size[4], k_cache->size[3], kv->block_table != nullptr, q->size[3])) return 0;
+  if (prefill_in_place(q->size[4], k_cache->size[3], kv->block_table != nullptr, q->size[3], k_cache->stride[0])) return 0;
   return prefill_layout(q->size[0], k_cache->size[2], q->size[4], kv->max_seq_len).total;
 }
 
@@ -1924,7 +1925,8 @@ fl_status fl_attn_prefill_paged(const fl_tensor* q, const fl_tensor* k_cache, co
 
   // In place (short chunks): the forward kernel takes the cache tensors as its keys and values and finds every tile's
   // pages through the block table itself; no copy, no workspace.
-  if (prefill_in_place(D, page_size, kv->block_table != nullptr, Sq)) {
+  if (prefill_in_place(D, page_size, kv->block_table != nullptr, Sq, k_cache->stride[0])) {
+    if (v_cache->stride[0] * 2 >= (1LL << 32)) return fail(FL_ERR_STRIDE, "v_cache page stride is not below 2^32 bytes");
     if (kv->max_seq_len == 0) {                    // nothing cached anywhere: out = 0, lse = -inf through the dense path's Sk = 0
       fl_tensor none = *k_cache;
       none.size[0] = B; none.size[3] = 0;

@@ -1046,8 +1046,18 @@ fwd_bf16_kernel(const FwdParams call) {
   // then, once, because tiles are visited in increasing order and nothing follows a ragged one.
   constexpr int KPW = (C::K_INSTR + C::NWAVES - 1) / C::NWAVES, VPW = (C::V_INSTR + C::NWAVES - 1) / C::NWAVES;
   uint32_t k_off[NS][KPW], v_off[VPW];
-  auto k_instr = [&](int u) __attribute__((always_inline)) { return (wave + u * C::NWAVES) % C::K_INSTR; };
-  auto v_instr = [&](int u) __attribute__((always_inline)) { return (wave + u * C::NWAVES) % C::V_INSTR; };
+  // (paged keys: a wave takes KPW consecutive instructions instead, i.e. KPW * K_ROWS_PI consecutive tokens -- 8 or 16 --
+  // which lie in one page unless the pages are smaller than that: one page-table entry then serves them all)
+  static_assert(!C::PAGED || (C::K_INSTR % KPW == 0 && C::V_INSTR % VPW == 0), "a wave's instructions of a paged tile are consecutive");
+  auto k_instr = [&](int u) __attribute__((always_inline)) {
+    return (C::PAGED ? wave * KPW + u : wave + u * C::NWAVES) % C::K_INSTR;
+  };
+  auto v_instr = [&](int u) __attribute__((always_inline)) {
+    return (C::PAGED ? wave * VPW + u : wave + u * C::NWAVES) % C::V_INSTR;
+  };
+  // do this wave's instructions of a paged tile share a page?  (uniform)  Then they also share one scalar base, the
+  // address of the wave's first token of the tile, and the lanes' offsets carry the instruction's rows as in a dense tile.
+  const bool one_page = C::PAGED && (p.block_table == nullptr || (1 << p.page_shift) >= KPW * C::K_ROWS_PI);
   auto k_lane_off = [&](int s, int u, int row) __attribute__((always_inline)) {   // row: the tile row to fetch
     const int dst_row = k_instr(u) * C::K_ROWS_PI + kr_lane;                         // decides the LDS chunk
     return (uint32_t)row * (uint32_t)kss[s] + (uint32_t)swz_k<D>(dst_row, lane % (D / 8)) * 16u;
@@ -1062,9 +1072,11 @@ fwd_bf16_kernel(const FwdParams call) {
 #pragma unroll
   for (int u = 0; u < KPW; ++u)
 #pragma unroll
-    for (int s = 0; s < NS; ++s) k_off[s][u] = k_lane_off(s, u, C::PAGED ? kr_lane : k_instr(u) * C::K_ROWS_PI + kr_lane);
+    for (int s = 0; s < NS; ++s)
+      k_off[s][u] = k_lane_off(s, u, C::PAGED ? (one_page ? u * C::K_ROWS_PI : 0) + kr_lane : k_instr(u) * C::K_ROWS_PI + kr_lane);
 #pragma unroll
-  for (int u = 0; u < VPW; ++u) v_off[u] = v_lane_off(u, C::PAGED ? vr_lane : v_instr(u) * C::V_ROWS_PI + vr_lane);
+  for (int u = 0; u < VPW; ++u)
+    v_off[u] = v_lane_off(u, C::PAGED ? (one_page ? u * C::V_ROWS_PI : 0) + vr_lane : v_instr(u) * C::V_ROWS_PI + vr_lane);
   auto clamp_k = [&](int t) __attribute__((always_inline)) {
     const int nvalid = p.Sk - t * BN;              // uniform
     if (nvalid < BN) {
@@ -1074,7 +1086,7 @@ fwd_bf16_kernel(const FwdParams call) {
         for (int s = 0; s < NS; ++s) {
           const int row = k_instr(u) * C::K_ROWS_PI + kr_lane;
           if constexpr (C::PAGED)
-            k_off[s][u] = k_lane_off(s, u, min(row, nvalid - 1) - min(k_instr(u) * C::K_ROWS_PI, nvalid - 1));
+            k_off[s][u] = k_lane_off(s, u, min(row, nvalid - 1) - min(k_instr(one_page ? 0 : u) * C::K_ROWS_PI, nvalid - 1));
           else
             k_off[s][u] = k_lane_off(s, u, row < nvalid ? row : nvalid - 1);
         }
@@ -1087,7 +1099,7 @@ fwd_bf16_kernel(const FwdParams call) {
       for (int u = 0; u < VPW; ++u) {
         const int row = v_instr(u) * C::V_ROWS_PI + vr_lane;
         if constexpr (C::PAGED)
-          v_off[u] = v_lane_off(u, min(row, nvalid - 1) - min(v_instr(u) * C::V_ROWS_PI, nvalid - 1));
+          v_off[u] = v_lane_off(u, min(row, nvalid - 1) - min(v_instr(one_page ? 0 : u) * C::V_ROWS_PI, nvalid - 1));
         else
           v_off[u] = v_lane_off(u, row < nvalid ? row : nvalid - 1);
       }
@@ -1102,11 +1114,36 @@ fwd_bf16_kernel(const FwdParams call) {
   auto page_of = [&](int t, int u) __attribute__((always_inline)) -> int {
     return __builtin_amdgcn_readfirstlane(page_of_lane(t, u));
   };
+  // the pages of all of this wave's instructions of tile t, as loaded (per lane) / made uniform
+  auto pages_of_lane = [&](int t, int (&pg)[KPW]) __attribute__((always_inline)) {
+    pg[0] = page_of_lane(t, 0);
+#pragma unroll
+    for (int u = 1; u < KPW; ++u) pg[u] = one_page ? pg[0] : page_of_lane(t, u);
+  };
+  auto pages_of = [&](int t, int (&pg)[KPW]) __attribute__((always_inline)) {
+    pages_of_lane(t, pg);
+#pragma unroll
+    for (int u = 0; u < KPW; ++u) pg[u] = __builtin_amdgcn_readfirstlane(pg[u]);
+  };
   // ... and the address of that instruction's first token in that page (view: the cache as [pages, 1, Hkv, page_size, D])
+  // (page and token strides are below 2^32 bytes -- the host checks -- so each product is one 32 x 32 -> 64 bit multiply;
+  // the shared scalar unit of the CU is what these kernels load most)
   auto paged_base = [&](const View& view, int t, int u, int page) __attribute__((always_inline)) -> const unsigned char* {
     const int token = min(t * BN + k_instr(u) * C::K_ROWS_PI, p.Sk - 1);
     const int within = p.block_table != nullptr ? (token & p.page_mask) : token;
-    return (const unsigned char*)((const uint16_t*)view.ptr + (int64_t)page * view.sb + hk * view.sh + (int64_t)within * view.ss);
+    const unsigned char* head = (const unsigned char*)((const uint16_t*)view.ptr + hk * view.sh);   // loop invariant
+    return head + (uint64_t)(uint32_t)page * (uint32_t)(view.sb * 2) + (uint64_t)(uint32_t)within * (uint32_t)(view.ss * 2);
+  };
+  // the bases of all of this wave's instructions of tile t
+  auto paged_bases = [&](const View& view, int t, const int (&pg)[KPW], const unsigned char* (&base)[KPW]) __attribute__((always_inline)) {
+    base[0] = paged_base(view, t, 0, pg[0]);
+    if (one_page) {
+#pragma unroll
+      for (int u = 1; u < KPW; ++u) base[u] = base[0];
+    } else {
+#pragma unroll
+      for (int u = 1; u < KPW; ++u) base[u] = paged_base(view, t, u, pg[u]);
+    }
   };
   // one load instruction of a K tile (stream s) / V tile whose first row is at `tile_base`
   auto issue_k = [&](int s, int u, const unsigned char* tile_base, int lds_off) __attribute__((always_inline)) {
@@ -1122,17 +1159,29 @@ fwd_bf16_kernel(const FwdParams call) {
   // whole-tile loads in one burst (prologue, two-stream loop)
   auto load_k = [&](int t, int buf) __attribute__((always_inline)) {
     clamp_k(t);
+    int pg[KPW] = {};
+    const unsigned char* pb[KPW] = {};
+    if constexpr (C::PAGED) {
+      pages_of(t, pg);
+      paged_bases(p.k, t, pg, pb);
+    }
 #pragma unroll
     for (int s = 0; s < NS; ++s)
 #pragma unroll
       for (int u = 0; u < KPW; ++u)
-        issue_k(s, u, C::PAGED ? paged_base(p.k, t, u, page_of(t, u)) : k_tile_base(s, t), C::K_RING + (buf * NS + s) * C::K_BYTES);
+        issue_k(s, u, C::PAGED ? pb[u] : k_tile_base(s, t), C::K_RING + (buf * NS + s) * C::K_BYTES);
   };
   auto load_v = [&](int t, int buf) __attribute__((always_inline)) {
     clamp_v(t);
+    int pg[KPW] = {};
+    const unsigned char* pb[KPW] = {};
+    if constexpr (C::PAGED) {
+      pages_of(t, pg);
+      paged_bases(p.v, t, pg, pb);
+    }
 #pragma unroll
     for (int u = 0; u < VPW; ++u)
-      issue_v(u, C::PAGED ? paged_base(p.v, t, u, page_of(t, u)) : v_tile_base(t), C::V_RING + buf * C::V_BYTES);
+      issue_v(u, C::PAGED ? pb[u < KPW ? u : 0] : v_tile_base(t), C::V_RING + buf * C::V_BYTES);
   };
   auto wait_loads_and_sync = [&]() __attribute__((always_inline)) {
     __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wave's direct loads have landed
@@ -1198,11 +1247,8 @@ fwd_bf16_kernel(const FwdParams call) {
 #pragma unroll
       for (int u = 0; u < KPW; ++u) pgk[u] = pgv[u] = pgpre[u] = 0;
       if constexpr (C::PAGED) {
-#pragma unroll
-        for (int u = 0; u < KPW; ++u) {
-          pgk[u] = page_of(tl[SPB + 1] < t_hi ? tl[SPB + 1] : t_hi - 1, u);
-          pgv[u] = page_of(tl[SPB] < t_hi ? tl[SPB] : t_hi - 1, u);
-        }
+        pages_of(tl[SPB + 1] < t_hi ? tl[SPB + 1] : t_hi - 1, pgk);
+        pages_of(tl[SPB] < t_hi ? tl[SPB] : t_hi - 1, pgv);
       }
       // One pipeline step.  cur / nxt hold the scores of the current / next tile.  Step number N
       // (mod 4) fixes the roles at compile time: tile number n of the list lives in ring slot
@@ -1258,12 +1304,9 @@ fwd_bf16_kernel(const FwdParams call) {
         const unsigned char* vbp[KPW];
         if constexpr (C::PAGED) {
           const int tk_next = tk + 1 < t_hi ? tk + 1 : t_hi - 1;   // the tile whose K the next step loads
-#pragma unroll
-          for (int u = 0; u < KPW; ++u) {
-            pgpre[u] = page_of_lane(tk_next, u);
-            kbp[u] = paged_base(p.k, tk, u, pgk[u]);
-            vbp[u] = paged_base(p.v, tv, u, pgv[u]);
-          }
+          pages_of_lane(tk_next, pgpre);
+          paged_bases(p.k, tk, pgk, kbp);
+          paged_bases(p.v, tv, pgv, vbp);
         }
         w.template phase_a<C::K_RING + slot_kn * NS * C::K_BYTES>(
             nxt, cur, ps, tn * BN, br, [&](auto fc) __attribute__((always_inline)) {
