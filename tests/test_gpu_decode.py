@@ -277,3 +277,47 @@ def test_decode_of_several_rows_full_size_sampled(T):
         le = float(np.max(np.abs(lse[b, 0, :, :, 0].cpu().numpy() - ref_lse[0])))
         print(f"decode of {T} rows at full size, sequence {b} (len {lens[b]}): max_abs={err:.3e} lse={le:.3e}", flush=True)
         assert err <= 1e-2 and le <= 1e-3
+
+
+def test_decode_of_several_rows_random_shapes():
+    """Thirty seeded random shapes of the several-row decode step: head groups of 1 ... 16, 1 ... 64 (row, head) pairs per
+    kv head (one and two column blocks, partly filled), both head dims, page sizes 8 ... 64, windows, soft-cap, ALiBi,
+    lengths from below the row count to a few key-range splits; every output against the oracle."""
+    import torch
+    from paper_2511_02043_amd import binding as fb
+    rng = np.random.Generator(np.random.PCG64(20251102043))
+    for case in range(30):
+        group = int(rng.choice([1, 2, 4, 8, 16]))
+        T = int(rng.integers(1, 64 // group + 1))
+        Hkv = int(rng.choice([1, 2, 3]))
+        D = int(rng.choice([64, 128]))
+        ps = int(rng.choice([8, 16, 32, 64]))
+        B = int(rng.integers(1, 5))
+        hi = int(rng.choice([40, 300, 2500]))
+        lens = [int(x) for x in rng.integers(0, hi + 1, size=B)]
+        w = inputs.prefill_paged_bf16(H=group * Hkv, Hkv=Hkv, D=D, Sq=T, page_size=ps, seq_lens=lens, salt=100 + case)
+        kind = int(rng.integers(0, 4))
+        if kind == 1:
+            w.softcap = 3.0
+        elif kind == 2:
+            w.alibi = inputs.alibi_slopes(group * Hkv)
+        if rng.integers(0, 2):
+            w.window = int(rng.choice([0, 1, T, 33, 500]))
+        label = f"case {case}: group={group} T={T} Hkv={Hkv} D={D} page={ps} lens={lens} kind={kind} window={w.window}"
+        print(label, flush=True)
+        dd = runner.upload_prefill_paged(w)
+        ws = torch.empty(max(fb.fl_attn_decode_workspace_size(dd.tq, dd.tk, dd.kv), 16), dtype=torch.uint8, device="cuda:0")
+        slopes = dd.keep[3]
+        dd.out.fill_(float("nan"))
+        dd.lse.fill_(float("nan"))
+        fb.check(fb.fl_attn_decode(dd.tq, dd.tk, dd.tv, dd.kv, dd.desc, fb.aux_desc(alibi_slopes=slopes, workspace=ws), dd.tout, dd.tlse))
+        torch.cuda.synchronize()
+        got, got_lse = dd.out.cpu().numpy()[:, 0], dd.lse.cpu().numpy()[:, 0, :, :, 0]
+        ref, ref_lse = do.prefill_attention(w.q, w.k_cache, w.v_cache, w.block_table, w.seq_lens, scale=w.scale, window=w.window,
+                                            softcap_value=w.softcap, alibi_slopes=w.alibi)
+        dead = np.isneginf(ref_lse)
+        assert np.array_equal(np.isneginf(got_lse), dead), label
+        assert np.all(got[dead] == 0.0) and np.all(np.isfinite(got)), label
+        assert float(np.max(np.abs(got - ref))) <= 1e-2, label
+        if np.any(~dead):
+            assert float(np.max(np.abs(got_lse[~dead] - ref_lse[~dead]))) <= 1e-3, label
