@@ -310,7 +310,8 @@ size_t fl_attn_decode_workspace_size(const fl_tensor* q, const fl_tensor* k_cach
  * How: chunks of so few rows that Sq * H / Hkv <= 64 (D 64 or 128) are an fl_attn_decode call on the same arguments
  * (the cache is then read once per kv head; the workspace is that call's).  Otherwise the forward kernel runs with each
  * sequence's length read on the device: it stops at that length and places the
- * query rows at its last Sq positions, so a short sequence costs its own length and nothing is synchronised with the
+ * query rows at its last Sq positions (for chunks much shorter than its 128- or 256-row tiles a workgroup takes the rows
+ * of several query heads of one kv head), so a short sequence costs its own length and nothing is synchronised with the
  * host.  For chunks of up to 1024 rows its key / value tile loads go to the pages themselves (page numbers from the block
  * table, fetched a step ahead; needs page_size >= 512 / D with a block table): no copy and no workspace.  For longer
  * chunks one pass first copies the cached rows of every sequence into dense tensors in the workspace (2 * 2 * len * Hkv
@@ -434,7 +435,10 @@ const char* fl_last_error_detail(void);
  * "order" (1 = plain, 2 = XCD-aware workgroup order), "pair" (1 = one q-tile per workgroup,
  * 2 = a long and a short q-tile per workgroup), "decode_splits" (key-range splits per sequence and
  * kv head of fl_attn_decode), "bwd_wg_target" (workgroups up to which fl_attn_bwd cuts a group of
- * query heads into subsets; both change the workspace size the matching *_workspace_size reports).
+ * query heads into subsets; both change the workspace size the matching *_workspace_size reports),
+ * "prefill_gather" (fl_attn_prefill_paged: 1 = always copy the pages first, 2 = always read them in place with the
+ * forward kernel; either also keeps chunks of a few rows away from the decode kernels), "prefill_pack" (1 = never
+ * pack the query heads of a kv head into one workgroup of the in-place kernel).
  * Value 0 restores the built-in choice.  Returns FL_OK or FL_ERR_UNSUPPORTED.  The requests are kept
  * per host thread: they change the later calls of the calling thread only, so this call is as
  * thread-safe as the others and no state is shared between threads.                          */

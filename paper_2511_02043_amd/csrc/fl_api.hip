@@ -40,6 +40,7 @@ using fl::host::make_view;
 struct Tuning {
   int bm = 0, bn = 0, rb = 0, nw = 0, wpe = 0, ring = 0, order = -1, pair = -1;
   int decode_splits = 0;           // 0: chosen by decode_splits() from the shapes
+  int prefill_pack = 0;            // fl_attn_prefill_paged in place: 1 never packs the query heads of a kv head into one workgroup
   int prefill_gather = 0;          // fl_attn_prefill_paged: 1 always copies the pages into dense tensors first, 2 never
                                    // (where the pages allow it); 0: by chunk length
   int bwd_wg_target = 0;           // 0: the default of choose_hsplit
@@ -98,8 +99,13 @@ fl_status check_desc(const fl_variant_desc* d) {
 
 // Sk > 0: the key length of the call, for the shape preference; <= 0: any shape of the variant will do.
 // heads x Sq (both > 0): the independent rows of the call, for the size of the launch.
+struct PagedShape {
+  int pack;    // query heads of one kv head per workgroup
+  bool wide;   // eight waves (256 rows) per workgroup instead of four (128)
+};
+
 const fl::KernelEntry* find_entry(const fl_variant_desc* d, int dtype, int D, int Dv, int64_t Sk = 0, int64_t heads = 0,
-                                  int64_t Sq = 0, bool paged = false) {
+                                  int64_t Sq = 0, const PagedShape* paged = nullptr) {
   const Registry& r = registry();
   const int mask = (int)canonical_mask(d->mask);
   const fl::KernelEntry* best = nullptr;
@@ -109,7 +115,8 @@ const fl::KernelEntry* find_entry(const fl_variant_desc* d, int dtype, int D, in
   for (int t = 0; t < 5; ++t)
     for (int e = 0; e < r.n[t]; ++e) {
       const fl::KernelEntry& k = r.tab[t][e];
-      if (k.key.dtype != dtype || k.key.diff != (int)d->combine || (k.key.paged != 0) != paged) continue;
+      if (k.key.dtype != dtype || k.key.diff != (int)d->combine || (k.key.paged != 0) != (paged != nullptr)) continue;
+      if (paged != nullptr && (k.key.pack != paged->pack || k.key.nwaves != (paged->wide ? 8 : 4))) continue;
       if (dtype == FL_F32) {
         if (D > k.key.D || Dv > k.key.DV) continue;
         if (best == nullptr || k.key.D < best->key.D) best = &k;   // smallest register budget that fits
@@ -133,12 +140,7 @@ const fl::KernelEntry* find_entry(const fl_variant_desc* d, int dtype, int D, in
   // small workgroups per CU hide them better than two large ones (measured on the paper's grid at
   // head dim 64; the crossover is at a few dozen key tiles per query tile).
   const bool tuned = g_tuning.bm || g_tuning.bn || g_tuning.rb || g_tuning.nw || g_tuning.wpe || g_tuning.ring;
-  // Keys read in place from a paged cache: 256-row workgroups from 512 query rows on when that still gives 512
-  // workgroups (measured 17 % faster there than the 128-row shape, which wins below).
-  if (paged && !tuned) {
-    const bool wide = heads > 0 && Sq >= 512 && heads * ((Sq + 255) / 256) >= 512;
-    return (!wide && four_waves != nullptr) ? four_waves : best;
-  }
+  if (paged != nullptr) return best;               // the shape was chosen by paged_shape()
   // (it needs a launch that fills the CUs four workgroups deep: on a small launch the fewer, larger tiles win)
   const bool known = heads > 0 && Sq > 0;
   if (!tuned && best != nullptr && short_loop != nullptr && Sk > 0 && Sk <= (mask == 0 ? 4096 : 2048) &&
@@ -158,6 +160,33 @@ const fl::KernelEntry* find_entry(const fl_variant_desc* d, int dtype, int D, in
       Sk >= 2048)
     best = deep_ring;
   return best;
+}
+
+// Shape of the kernel that reads a paged cache in place.  Unpacked: 256-row workgroups from 512 query rows on when
+// that still gives 512 workgroups (measured 17 % faster there than the 128-row shape, which wins below).  A chunk that
+// leaves much of such a tile empty packs the query heads of a kv head into the workgroup instead: with R rows per head
+// and tile (32, 64 or 128; 256 / R or 128 / R heads, which has to divide the heads per kv head) the MFMA rows are
+// filled to Sq / (ceil(Sq / R) R); the R with the best fill is taken when that beats the unpacked tile by a fifth, with
+// as many heads as fit (K / V are then fetched once for all of them).
+PagedShape paged_shape(int64_t heads, int64_t group, int64_t Sq) {
+  PagedShape s;
+  s.pack = 1;
+  s.wide = heads > 0 && Sq >= 512 && heads * ((Sq + 255) / 256) >= 512;
+  if (g_tuning.nw != 0) s.wide = g_tuning.nw == 8;
+  if (g_tuning.prefill_pack == 1 || Sq <= 0 || group <= 1) return s;
+  auto fill = [&](int64_t rows) { return (double)Sq / (double)(((Sq + rows - 1) / rows) * rows); };
+  double best = fill(s.wide ? 256 : 128) * 1.2;
+  for (int rows = 128; rows >= 32; rows /= 2) {
+    const bool can_wide = group % (256 / rows) == 0, can_narrow = rows < 128 && group % (128 / rows) == 0;
+    if (!can_wide && !can_narrow) continue;
+    const double f = fill(rows);
+    if (f > best) {
+      best = f;
+      s.wide = can_wide;
+      s.pack = (can_wide ? 256 : 128) / rows;
+    }
+  }
+  return s;
 }
 
 // Head dims the bf16 kernel template can be instantiated for at run time.
@@ -927,6 +956,7 @@ fl_status fl_set_tuning(const char* key, int value) {
   else if (!strcmp(key, "order")) g_tuning.order = value == 0 ? -1 : value - 1;
   else if (!strcmp(key, "pair")) g_tuning.pair = value == 0 ? -1 : value - 1;
   else if (!strcmp(key, "decode_splits")) g_tuning.decode_splits = value;
+  else if (!strcmp(key, "prefill_pack")) g_tuning.prefill_pack = value;
   else if (!strcmp(key, "prefill_gather")) g_tuning.prefill_gather = value;
   else if (!strcmp(key, "bwd_wg_target")) g_tuning.bwd_wg_target = value;
   else return fail(FL_ERR_UNSUPPORTED, "unknown tuning key '%s'", key);
@@ -1058,11 +1088,13 @@ static fl_status forward_call(const fl_tensor* q, const fl_tensor* k, const fl_t
     if (!empty && out->dtype != FL_F32) return fail(FL_ERR_DTYPE, "f32 inputs need f32 out");
   }
   // (of the kernels that read a paged cache in place only the causal one is in the table)
-  const fl::KernelEntry* ke = find_entry(desc, dtype, (int)D, (int)Dv, Sk, B * G * H, Sq, paged != nullptr);
+  PagedShape shape = {1, false};
+  if (paged != nullptr) shape = paged_shape(B * G * H, Hkv > 0 ? H / Hkv : 1, Sq);
+  const fl::KernelEntry* ke = find_entry(desc, dtype, (int)D, (int)Dv, Sk, B * G * H, Sq, paged != nullptr ? &shape : nullptr);
   if (ke == nullptr && dtype == FL_BF16 && jit_dims_ok(D, Dv)) {
     // not in the compiled table: the same kernel template, instantiated for this descriptor on first use
     ke = fl::jit_forward_entry(fl::JitRequest{(int)D, (int)Dv, (int)desc->score_mod, mask, (int)desc->n_bias, diff, desc->epilogue,
-                                              paged != nullptr, paged != nullptr && D == 128 && Sq >= 512 && B * G * H * ((Sq + 255) / 256) >= 512});
+                                              paged != nullptr, shape.wide, shape.pack});
     if (ke == nullptr) {
       char why[300];
       snprintf(why, sizeof(why), "%s", g_detail);
@@ -1143,7 +1175,7 @@ static fl_status forward_call(const fl_tensor* q, const fl_tensor* k, const fl_t
     p.bias_lds_wave = staged ? (int)per_wave : 0;
     p.lds_bytes = (int)(kv + (staged ? stage : 0));
   }
-  const int64_t nbh = B * G * H;
+  const int64_t nbh = B * G * H / ke->key.pack;    // (packed heads: a workgroup takes key.pack heads of one kv head)
   // bf16 kernels under a causal / prefix mask without a window: the work of a q-tile grows with
   // its index, so a workgroup takes a long and a short one -- when that still leaves every CU
   // several workgroups
@@ -1160,7 +1192,7 @@ static fl_status forward_call(const fl_tensor* q, const fl_tensor* k, const fl_t
 
   hipStream_t stream = (hipStream_t)stream_v;
   if (Sk == 0) {
-    const int64_t total = nbh * Sq;
+    const int64_t total = B * G * H * Sq;
     hipLaunchKernelGGL(empty_keys_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, p.out,
                        p.out_f32, p.lse, p.lse_sb, p.lse_sg, p.lse_sh, p.G, p.H, p.Sq, p.Dv, diff ? 2 : 1, total);
     hipError_t e0 = hipGetLastError();

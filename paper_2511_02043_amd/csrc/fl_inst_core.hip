@@ -20,6 +20,14 @@ static const KernelEntry kEntries[] = {
     bf16_entry<128, 128, 8, 1, 64, 2, kModNone, kMaskCausal, 0, false, 0, 2, true>(),
     bf16_entry<128, 128, 4, 1, 64, 2, kModNone, kMaskCausal, 0, false, 0, 2, true>(),
     bf16_entry<64, 64, 4, 1, 64, 2, kModNone, kMaskCausal, 0, false, 0, 2, true>(),
+    // ... and with the query heads of a kv head packed into one workgroup, for chunks shorter than a workgroup's rows:
+    // 8 waves x 4 heads x 64 rows, 8 waves x 8 heads x 32 rows, 8 waves x 2 heads x 128 rows, 4 waves x 4 heads x 32 rows,
+    // 4 waves x 2 heads x 64 rows
+    bf16_entry<128, 128, 8, 1, 64, 2, kModNone, kMaskCausal, 0, false, 0, 2, true, 4>(),
+    bf16_entry<128, 128, 8, 1, 64, 2, kModNone, kMaskCausal, 0, false, 0, 2, true, 8>(),
+    bf16_entry<128, 128, 8, 1, 64, 2, kModNone, kMaskCausal, 0, false, 0, 2, true, 2>(),
+    bf16_entry<128, 128, 4, 1, 64, 2, kModNone, kMaskCausal, 0, false, 0, 2, true, 4>(),
+    bf16_entry<128, 128, 4, 1, 64, 2, kModNone, kMaskCausal, 0, false, 0, 2, true, 2>(),
 };
 #undef BOTH
 #undef BOTH4

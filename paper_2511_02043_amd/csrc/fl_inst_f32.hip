@@ -11,7 +11,7 @@ static hipError_t launch_f32(const FwdParams& p, int nblocks, hipStream_t stream
 }
 #define E(DIFF, DMAX)                                                                        \
   KernelEntry {                                                                              \
-    KernelKey{2, DMAX, DMAX, -1, -1, -1, DIFF ? 1 : 0, -1, 4, 1, kF32Keys, 0, 0, 0}, kF32Rows,           \
+    KernelKey{2, DMAX, DMAX, -1, -1, -1, DIFF ? 1 : 0, -1, 4, 1, kF32Keys, 0, 0, 0, 1}, kF32Rows,           \
         ((DIFF ? 2 : 1) * kF32Keys * DMAX + kF32Keys * DMAX) * 4, &launch_f32<DIFF, DMAX>    \
   }
 static const KernelEntry kEntries[] = {E(false, 64), E(false, 128), E(true, 64), E(true, 128)};

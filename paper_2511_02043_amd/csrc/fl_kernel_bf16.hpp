@@ -99,7 +99,7 @@ __device__ __forceinline__ int swz_v(int r, int c) {
 }
 
 template <int D_, int DV_, int NWAVES_, int RB_, int BN_, int WPE_, int MOD_, uint32_t MASK_, int NBIAS_,
-          bool DIFF_, uint32_t EPI_, int RING_ = 2, bool PAGED_ = false>
+          bool DIFF_, uint32_t EPI_, int RING_ = 2, bool PAGED_ = false, int PACK_ = 1>
 struct Bf16Cfg {
   static constexpr int D = D_, DV = DV_, NWAVES = NWAVES_, RB = RB_, BN = BN_, MOD = MOD_, NBIAS = NBIAS_;
   static constexpr uint32_t MASK = MASK_, EPI = EPI_;
@@ -149,6 +149,13 @@ struct Bf16Cfg {
   static constexpr bool PAGED = PAGED_;
   static_assert(!PAGED_ || (!DIFF_ && NBIAS_ == 0 && RING_ == 2 && D_ == DV_ && (MASK_ & (kMaskDoc | kMaskCustom)) == 0),
                 "paged keys: one stream, no bias, two ring slots, D == Dv, positional masks");
+  // Grouped-query heads packed into one workgroup (short chunks of query rows over a paged cache): the workgroup's BM
+  // rows are BM / PACK rows of each of PACK consecutive query heads that share a kv head, so that K / V tiles are read
+  // once for all of them and a chunk shorter than BM rows still fills the MFMA rows.  A wave's rows belong to one head.
+  static constexpr int PACK = PACK_;
+  static constexpr int HEAD_ROWS = BM / PACK_;     // query rows per head and workgroup
+  static_assert(PACK_ == 1 || (PAGED_ && BM % PACK_ == 0 && HEAD_ROWS % WROWS == 0 && (EPI_ & kEpiGate) == 0),
+                "packed heads: paged keys, whole waves per head");
 };
 
 enum TileClass : int { kTileSkip = 0, kTileFull = 1, kTilePartial = 2 };
@@ -713,9 +720,11 @@ fwd_bf16_kernel(const FwdParams call) {
   // The problem as this workgroup sees it.  With per-sequence key counts (a chunk of new query rows against each
   // sequence's cached keys, Sec. 4.1 serving) sequence b has kv_lens[b] keys, cut to [0, Sk], and its query rows are the
   // last Sq positions of those: row i sits at position kv_lens[b] - Sq + i (rows at negative positions see nothing).
+  // (packed heads: bh counts groups of PACK heads)
+  const int heads_wg = call.H / C::PACK;
   FwdParams p = call;
   if (call.kv_lens != nullptr) {
-    const int len = max(0, min(call.kv_lens[bh / (call.H * call.G)], call.Sk));
+    const int len = max(0, min(call.kv_lens[bh / (heads_wg * call.G)], call.Sk));
     p.Sk = len;
     p.q_off = len - call.Sq;
   }
@@ -733,13 +742,14 @@ fwd_bf16_kernel(const FwdParams call) {
   w.lane = lane;
   w.half = lane >> 5;
   w.col = lane & 31;
-  const int h = bh % p.H;
-  const int g = (bh / p.H) % p.G;
-  const int b = bh / (p.H * p.G);
-  const int hk = h / (p.H / p.Hkv);
+  const int wrow = (wave % C::NROWG) * C::WROWS;   // the wave's first row among the workgroup's BM
+  const int h = (bh % heads_wg) * C::PACK + wrow / C::HEAD_ROWS;   // (one head per workgroup unless heads are packed)
+  const int g = (bh / heads_wg) % p.G;
+  const int b = bh / (heads_wg * p.G);
+  const int hk = h / (p.H / p.Hkv);                // the same for all heads of a pack (the host checks)
   const int stream = C::DIFF ? wave / C::NROWG : 0;   // softmax stream of this wave (uniform)
-  const int i0 = qt * C::BM;                       // first query row of the workgroup
-  const int iw = i0 + (wave % C::NROWG) * C::WROWS;   // first query row of the wave
+  const int i0 = qt * C::HEAD_ROWS;                // first query row of the workgroup
+  const int iw = i0 + wrow % C::HEAD_ROWS;         // first query row of the wave
   w.b = b; w.g = g; w.h = h;
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
@@ -802,7 +812,7 @@ fwd_bf16_kernel(const FwdParams call) {
   }
 
   // ---- tile skipper (a0): visible key range and document-id summaries
-  const int i_last = (i0 + C::BM - 1 < p.Sq ? i0 + C::BM : p.Sq) - 1;
+  const int i_last = (i0 + C::HEAD_ROWS - 1 < p.Sq ? i0 + C::HEAD_ROWS : p.Sq) - 1;
   // positions of the workgroup's / the wave's first and last query row: what the positional masks compare with keys
   const int pos0 = i0 + p.q_off, pos_last = i_last + p.q_off, posw = iw + p.q_off;
   int k_lo, k_hi;

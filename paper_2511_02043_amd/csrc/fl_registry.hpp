@@ -18,13 +18,14 @@ struct KernelKey {
   int nwaves, rb, bn, wpe;         // kernel shape: waves, 32-row blocks per wave, keys per tile, waves per SIMD
   int ring;                        // slots of the K / V rings in LDS (a barrier every ring / 2 tiles)
   int paged;                       // 1: keys and values are read in place from a paged cache
+  int pack;                        // query heads of one kv head per workgroup (1 unless paged: short chunks)
 };
 
 typedef hipError_t (*LaunchFn)(const FwdParams& p, int nblocks, hipStream_t stream);
 
 struct KernelEntry {
   KernelKey key;
-  int bm;           // query rows per workgroup
+  int bm;           // query rows per workgroup and head (the workgroup's rows / key.pack)
   int lds_bytes;    // LDS of the K/V rings per workgroup
   LaunchFn launch;  // compiled specialisations; null for one compiled at run time
   void* jit;        // run-time compiled specialisations: the loaded code object (see jit_forward_entry)
@@ -43,6 +44,7 @@ struct JitRequest {
   uint32_t epi;
   bool paged = false;   // keys and values read in place from a paged cache
   bool wide = false;    // eight waves (256 query rows) per workgroup instead of four: long query tiles at head dim 128
+  int pack = 1;         // paged only: query heads of one kv head per workgroup
 };
 const KernelEntry* jit_forward_entry(const JitRequest& r);
 hipError_t jit_forward_launch(const KernelEntry& e, const FwdParams& p, int nblocks, hipStream_t stream);
@@ -66,12 +68,12 @@ hipError_t launch_bf16(const FwdParams& p, int nblocks, hipStream_t stream) {
 }
 
 template <int D, int DV, int NWAVES, int RB, int BN, int WPE, int MOD, uint32_t MASK, int NBIAS, bool DIFF,
-          uint32_t EPI, int RING = 2, bool PAGED = false>
+          uint32_t EPI, int RING = 2, bool PAGED = false, int PACK = 1>
 constexpr KernelEntry bf16_entry() {
-  typedef Bf16Cfg<D, DV, NWAVES, RB, BN, WPE, MOD, MASK, NBIAS, DIFF, EPI, RING, PAGED> C;
+  typedef Bf16Cfg<D, DV, NWAVES, RB, BN, WPE, MOD, MASK, NBIAS, DIFF, EPI, RING, PAGED, PACK> C;
   static_assert(C::LDS_BYTES <= kMaxLdsBytes, "rings exceed the LDS of a compute unit");
-  return KernelEntry{KernelKey{1, D, DV, MOD, (int)MASK, NBIAS, DIFF ? 1 : 0, (int)EPI, NWAVES, RB, BN, WPE, RING, PAGED ? 1 : 0},
-                     C::BM, C::LDS_BYTES, &launch_bf16<C>};
+  return KernelEntry{KernelKey{1, D, DV, MOD, (int)MASK, NBIAS, DIFF ? 1 : 0, (int)EPI, NWAVES, RB, BN, WPE, RING, PAGED ? 1 : 0, PACK},
+                     C::HEAD_ROWS, C::LDS_BYTES, &launch_bf16<C>};
 }
 
 // Each instance file defines one of these.

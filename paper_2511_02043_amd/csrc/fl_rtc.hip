@@ -153,10 +153,10 @@ struct JitForward {
 namespace fl {
 
 const KernelEntry* jit_forward_entry(const JitRequest& r) {
-  typedef std::tuple<int, int, int, uint32_t, int, bool, uint32_t, bool, bool> Key;
+  typedef std::tuple<int, int, int, uint32_t, int, bool, uint32_t, bool, bool, int> Key;
   static std::mutex mu;
   static std::map<Key, JitForward*> cache;        // entries live until the process ends
-  const Key key(r.D, r.DV, r.mod, r.mask, r.nbias, r.diff, r.epi, r.paged, r.wide);
+  const Key key(r.D, r.DV, r.mod, r.mask, r.nbias, r.diff, r.epi, r.paged, r.wide, r.pack);
   std::lock_guard<std::mutex> lock(mu);            // one compilation at a time; a hit only takes the lookup
   auto it = cache.find(key);
   if (it != cache.end()) return it->second != nullptr ? &it->second->entry : nullptr;
@@ -170,8 +170,8 @@ const KernelEntry* jit_forward_entry(const JitRequest& r) {
   const int lds = 2 * bn * 2 * (ns * r.D + r.DV);
   const int xch = r.diff ? (nw / 2) * 64 * (r.DV / 32) * 16 * 4 : 0;
   char inst[320];
-  snprintf(inst, sizeof(inst), "fl::fwd_bf16_kernel<fl::Bf16Cfg<%d, %d, %d, 1, %d, 2, %d, %uu, %d, %s, %uu, 2, %s>>", r.D, r.DV, nw, bn,
-           r.mod, r.mask, r.nbias, r.diff ? "true" : "false", r.epi, r.paged ? "true" : "false");
+  snprintf(inst, sizeof(inst), "fl::fwd_bf16_kernel<fl::Bf16Cfg<%d, %d, %d, 1, %d, 2, %d, %uu, %d, %s, %uu, 2, %s, %d>>", r.D, r.DV, nw, bn,
+           r.mod, r.mask, r.nbias, r.diff ? "true" : "false", r.epi, r.paged ? "true" : "false", r.pack);
   std::string src = "#include \"fl_kernel_bf16.hpp\"\ntemplate __global__ void ";
   src += inst;
   src += "(const fl::FwdParams);\n";
@@ -183,8 +183,8 @@ const KernelEntry* jit_forward_entry(const JitRequest& r) {
     return nullptr;
   }
   j->nthreads = nw * 64;
-  j->entry = KernelEntry{KernelKey{1, r.D, r.DV, r.mod, (int)r.mask, r.nbias, r.diff ? 1 : 0, (int)r.epi, nw, 1, bn, 2, 2, r.paged ? 1 : 0},
-                         (nw / ns) * 32, lds > xch ? lds : xch, nullptr, j, 65536};
+  j->entry = KernelEntry{KernelKey{1, r.D, r.DV, r.mod, (int)r.mask, r.nbias, r.diff ? 1 : 0, (int)r.epi, nw, 1, bn, 2, 2, r.paged ? 1 : 0, r.pack},
+                         (nw / ns) * 32 / r.pack, lds > xch ? lds : xch, nullptr, j, 65536};
   cache[key] = j;
   return &j->entry;
 }
