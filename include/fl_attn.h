@@ -307,8 +307,8 @@ size_t fl_attn_decode_workspace_size(const fl_tensor* q, const fl_tensor* k_cach
  *   aux      alibi_slopes for FL_MOD_ALIBI, and aux->workspace of fl_attn_prefill_paged_workspace_size bytes
  *            (16-byte aligned; contents undefined afterwards); may be NULL when neither is needed
  *
- * How: chunks of so few rows that Sq * H / Hkv <= 64 (D 64 or 128) are an fl_attn_decode call on the same arguments
- * (the cache is then read once per kv head; the workspace is that call's).  Otherwise the forward kernel runs with each
+ * How: chunks of so few rows that Sq * H / Hkv <= 32 (D 64 or 128; <= 64 when the forward kernel would not fill the chip)
+ * are an fl_attn_decode call on the same arguments (the cache is then read once per kv head; the workspace is that call's).  Otherwise the forward kernel runs with each
  * sequence's length read on the device: it stops at that length and places the
  * query rows at its last Sq positions (for chunks much shorter than its 128- or 256-row tiles a workgroup takes the rows
  * of several query heads of one kv head), so a short sequence costs its own length and nothing is synchronised with the

@@ -1852,10 +1852,17 @@ fl_status fl_attn_decode(const fl_tensor* q, const fl_tensor* k_cache, const fl_
 }
 
 // Chunks of so few rows that all (query row, head) pairs of a kv head fit the columns of the decode kernels go
-// there: the cache is then read once per kv head instead of once per query head, and no MFMA row is idle.
-static bool prefill_as_decode(int64_t D, int64_t H, int64_t Hkv, int64_t Sq) {
+// there: the cache is then read once per kv head instead of once per query head, no MFMA row is idle, and the key
+// range is split so that few or ragged sequences still fill the chip.  With more than 32 pairs (two column blocks) the
+// in-place forward kernel with packed heads measured faster when it has the workgroups to fill the chip (64 sequences x
+// 16 rows, 32 / 8 heads: 0.41 against 0.53 ms), so those chunks go there when it packs and launches 512 or more.
+static bool prefill_as_decode(int64_t D, int64_t B, int64_t H, int64_t Hkv, int64_t Sq, bool in_place_ok) {
   if (g_tuning.prefill_gather != 0) return false;
-  return (D == 64 || D == 128) && Hkv > 0 && H % Hkv == 0 && Sq * (H / Hkv) <= kDecodeMaxPairs;
+  if (!((D == 64 || D == 128) && Hkv > 0 && H % Hkv == 0 && Sq * (H / Hkv) <= kDecodeMaxPairs)) return false;
+  if (Sq * (H / Hkv) <= 32 || !in_place_ok) return true;
+  const PagedShape s = paged_shape(B * H, H / Hkv, Sq);
+  const int64_t rows = (s.wide ? 256 : 128) / s.pack;
+  return !(s.pack > 1 && (B * H / s.pack) * ((Sq + rows - 1) / rows) >= 512);
 }
 
 // Does the forward kernel read these pages in place?  It can when every direct-load instruction of a tile (512 / D
@@ -1874,8 +1881,10 @@ static bool prefill_in_place(int64_t D, int64_t page_size, bool has_table, int64
 
 size_t fl_attn_prefill_paged_workspace_size(const fl_tensor* q, const fl_tensor* k_cache, const fl_paged_kv* kv) {
   if (q == nullptr || k_cache == nullptr || kv == nullptr) return 0;
-  if (prefill_as_decode(q->size[4], q->size[2], k_cache->size[2], q->size[3])) return fl_attn_decode_workspace_size(q, k_cache, kv);
-  if (prefill_in_place(q->size[4], k_cache->size[3], kv->block_table != nullptr, q->size[3], k_cache->stride[0])) return 0;
+  const bool in_place = prefill_in_place(q->size[4], k_cache->size[3], kv->block_table != nullptr, q->size[3], k_cache->stride[0]);
+  if (prefill_as_decode(q->size[4], q->size[0], q->size[2], k_cache->size[2], q->size[3], in_place))
+    return fl_attn_decode_workspace_size(q, k_cache, kv);
+  if (in_place) return 0;
   return prefill_layout(q->size[0], k_cache->size[2], q->size[4], kv->max_seq_len).total;
 }
 
@@ -1953,11 +1962,12 @@ fl_status fl_attn_prefill_paged(const fl_tensor* q, const fl_tensor* k_cache, co
   }
 
   // A few rows: the decode kernels, with their own checks of the same arguments.
-  if (prefill_as_decode(D, H, Hkv, Sq)) return fl_attn_decode(q, k_cache, v_cache, kv, desc, aux, out, lse, stream_v);
+  const bool in_place = prefill_in_place(D, page_size, kv->block_table != nullptr, Sq, k_cache->stride[0]);
+  if (prefill_as_decode(D, B, H, Hkv, Sq, in_place)) return fl_attn_decode(q, k_cache, v_cache, kv, desc, aux, out, lse, stream_v);
 
   // In place (short chunks): the forward kernel takes the cache tensors as its keys and values and finds every tile's
   // pages through the block table itself; no copy, no workspace.
-  if (prefill_in_place(D, page_size, kv->block_table != nullptr, Sq, k_cache->stride[0])) {
+  if (in_place) {
     if (v_cache->stride[0] * 2 >= (1LL << 32)) return fail(FL_ERR_STRIDE, "v_cache page stride is not below 2^32 bytes");
     if (kv->max_seq_len == 0) {                    // nothing cached anywhere: out = 0, lse = -inf through the dense path's Sk = 0
       fl_tensor none = *k_cache;
