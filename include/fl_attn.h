@@ -141,7 +141,8 @@ typedef struct {
  * Supported head dims: D, Dv in {32, 64, 128} for bf16 (the pairs listed by
  * fl_variant_supported), any multiple of 4 up to 128 for f32.  Sq, Sk >= 1 are arbitrary;
  * empty problems (any of B, G, H, Sq equal to 0) return FL_OK without a launch; Sk == 0 is
- * treated as every row fully masked.
+ * treated as every row fully masked.  (Grouped heads with at most 64 query rows against 1024 keys or more, the chunk
+ * shape of q_offset: the query heads of a kv head share a workgroup; that kernel shape is compiled on the first such call.)
  * Returns FL_OK or an error code; on error nothing was launched.                            */
 fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v,
                       const fl_variant_desc* desc, const fl_aux* aux,

@@ -105,7 +105,7 @@ struct PagedShape {
 };
 
 const fl::KernelEntry* find_entry(const fl_variant_desc* d, int dtype, int D, int Dv, int64_t Sk = 0, int64_t heads = 0,
-                                  int64_t Sq = 0, const PagedShape* paged = nullptr) {
+                                  int64_t Sq = 0, const PagedShape* paged = nullptr, const PagedShape* packed = nullptr) {
   const Registry& r = registry();
   const int mask = (int)canonical_mask(d->mask);
   const fl::KernelEntry* best = nullptr;
@@ -117,6 +117,8 @@ const fl::KernelEntry* find_entry(const fl_variant_desc* d, int dtype, int D, in
       const fl::KernelEntry& k = r.tab[t][e];
       if (k.key.dtype != dtype || k.key.diff != (int)d->combine || (k.key.paged != 0) != (paged != nullptr)) continue;
       if (paged != nullptr && (k.key.pack != paged->pack || k.key.nwaves != (paged->wide ? 8 : 4))) continue;
+      if (paged == nullptr && k.key.pack != (packed != nullptr ? packed->pack : 1)) continue;
+      if (packed != nullptr && k.key.nwaves != (packed->wide ? 8 : 4)) continue;
       if (dtype == FL_F32) {
         if (D > k.key.D || Dv > k.key.DV) continue;
         if (best == nullptr || k.key.D < best->key.D) best = &k;   // smallest register budget that fits
@@ -140,7 +142,7 @@ const fl::KernelEntry* find_entry(const fl_variant_desc* d, int dtype, int D, in
   // small workgroups per CU hide them better than two large ones (measured on the paper's grid at
   // head dim 64; the crossover is at a few dozen key tiles per query tile).
   const bool tuned = g_tuning.bm || g_tuning.bn || g_tuning.rb || g_tuning.nw || g_tuning.wpe || g_tuning.ring;
-  if (paged != nullptr) return best;               // the shape was chosen by paged_shape()
+  if (paged != nullptr || packed != nullptr) return best;   // the shape was chosen by paged_shape()
   // (it needs a launch that fills the CUs four workgroups deep: on a small launch the fewer, larger tiles win)
   const bool known = heads > 0 && Sq > 0;
   if (!tuned && best != nullptr && short_loop != nullptr && Sk > 0 && Sk <= (mask == 0 ? 4096 : 2048) &&
@@ -1090,11 +1092,23 @@ static fl_status forward_call(const fl_tensor* q, const fl_tensor* k, const fl_t
   // (of the kernels that read a paged cache in place only the causal one is in the table)
   PagedShape shape = {1, false};
   if (paged != nullptr) shape = paged_shape(B * G * H, Hkv > 0 ? H / Hkv : 1, Sq);
-  const fl::KernelEntry* ke = find_entry(desc, dtype, (int)D, (int)Dv, Sk, B * G * H, Sq, paged != nullptr ? &shape : nullptr);
+  // Dense keys: a chunk of at most 64 query rows of grouped heads against 1024 keys or more (a query offset into a long
+  // key sequence, typically) fills half of the smallest tile or less; the kernel shapes with packed heads are
+  // instantiated for it on first use.
+  const bool can_pack = paged == nullptr && dtype == FL_BF16 && !diff && desc->n_bias == 0 && desc->epilogue == 0 &&
+                        (mask & FL_MASK_DOC) == 0 && D == Dv && Sq <= 64 && Sk >= 1024 && Hkv > 0 && H / Hkv > 1 && !empty &&
+                        !(g_tuning.bm || g_tuning.bn || g_tuning.rb || g_tuning.nw || g_tuning.wpe || g_tuning.ring);
+  if (can_pack) {
+    shape = paged_shape(B * G * H, H / Hkv, Sq);
+    if (shape.pack == 1) shape.wide = false;
+  }
+  const bool packed = can_pack && shape.pack > 1;
+  const fl::KernelEntry* ke = find_entry(desc, dtype, (int)D, (int)Dv, Sk, B * G * H, Sq, paged != nullptr ? &shape : nullptr,
+                                         packed ? &shape : nullptr);
   if (ke == nullptr && dtype == FL_BF16 && jit_dims_ok(D, Dv)) {
     // not in the compiled table: the same kernel template, instantiated for this descriptor on first use
     ke = fl::jit_forward_entry(fl::JitRequest{(int)D, (int)Dv, (int)desc->score_mod, mask, (int)desc->n_bias, diff, desc->epilogue,
-                                              paged != nullptr, shape.wide, shape.pack});
+                                              paged != nullptr, (paged != nullptr || packed) && shape.wide, shape.pack});
     if (ke == nullptr) {
       char why[300];
       snprintf(why, sizeof(why), "%s", g_detail);

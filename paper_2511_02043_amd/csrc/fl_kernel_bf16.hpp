@@ -149,13 +149,14 @@ struct Bf16Cfg {
   static constexpr bool PAGED = PAGED_;
   static_assert(!PAGED_ || (!DIFF_ && NBIAS_ == 0 && RING_ == 2 && D_ == DV_ && (MASK_ & (kMaskDoc | kMaskCustom)) == 0),
                 "paged keys: one stream, no bias, two ring slots, D == Dv, positional masks");
-  // Grouped-query heads packed into one workgroup (short chunks of query rows over a paged cache): the workgroup's BM
+  // Grouped-query heads packed into one workgroup (short chunks of query rows against long key sequences): the workgroup's BM
   // rows are BM / PACK rows of each of PACK consecutive query heads that share a kv head, so that K / V tiles are read
   // once for all of them and a chunk shorter than BM rows still fills the MFMA rows.  A wave's rows belong to one head.
   static constexpr int PACK = PACK_;
   static constexpr int HEAD_ROWS = BM / PACK_;     // query rows per head and workgroup
-  static_assert(PACK_ == 1 || (PAGED_ && BM % PACK_ == 0 && HEAD_ROWS % WROWS == 0 && (EPI_ & kEpiGate) == 0),
-                "packed heads: paged keys, whole waves per head");
+  static_assert(PACK_ == 1 || (!DIFF_ && NBIAS_ == 0 && EPI_ == 0 && (MASK_ & (kMaskDoc | kMaskCustom)) == 0 && MOD_ != kModCustom &&
+                               BM % PACK_ == 0 && HEAD_ROWS % WROWS == 0),
+                "packed heads: one stream, no bias, no epilogue, positional masks, whole waves per head");
 };
 
 enum TileClass : int { kTileSkip = 0, kTileFull = 1, kTilePartial = 2 };

@@ -128,3 +128,28 @@ def test_backward_ex_with_offset():
         rel = float(np.sqrt(np.sum(diff * diff) / np.sum(ref[name] ** 2)))
         print(f"offset + diff + gate {name}: rel_l2={rel:.3e}", flush=True)
         assert rel <= 5e-3, (name, rel)
+
+
+@pytest.mark.parametrize("kind", ["causal", "window", "alibi_causal", "prefix"])
+def test_short_chunks_of_grouped_heads_pack_a_kv_heads_query_heads(kind):
+    """At most 64 query rows of grouped heads against 1024 keys or more: the query heads of a kv head share a workgroup
+    (kernel shapes instantiated on first use).  Element by element against the oracle, and against the call with packing
+    switched off (which may run another tile shape, so equal up to the rounding order: 2e-3); head groups of 2, 4 and 8,
+    both head dims."""
+    import torch
+    for Sq, Sk, D, H, Hkv in ((64, 1500, 128, 8, 2), (20, 2100, 64, 8, 1), (33, 1024, 128, 4, 2)):
+        w = chunk(kind, Sq, Sk, D, H=H, Hkv=Hkv, B=2)
+        w.name += f"_h{H}_kv{Hkv}_packed"
+        run_and_compare(w)
+        outs = []
+        for pack_off in (0, 1):
+            fb.check(fb.fl_set_tuning("prefill_pack", pack_off))
+            try:
+                dw = runner.upload(w, out_dtype="f32")
+                dw.out.fill_(float("nan"))
+                dw.run_checked()
+                torch.cuda.synchronize()
+                outs.append((dw.out.clone(), dw.lse.clone()))
+            finally:
+                fb.fl_set_tuning("prefill_pack", 0)
+        assert float((outs[0][0] - outs[1][0]).abs().max()) <= 2e-3 and float((outs[0][1] - outs[1][1]).abs().max()) <= 1e-4, w.name
