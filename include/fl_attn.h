@@ -143,6 +143,8 @@ typedef struct {
  * empty problems (any of B, G, H, Sq equal to 0) return FL_OK without a launch; Sk == 0 is
  * treated as every row fully masked.  (Grouped heads with at most 64 query rows against 1024 keys or more, the chunk
  * shape of q_offset: the query heads of a kv head share a workgroup; that kernel shape is compiled on the first such call.)
+ * A call that compiles a kernel (a descriptor combination or shape outside the compiled table, first use in the process)
+ * takes about a second on the host and loads a code object: make it once outside any stream capture.
  * Returns FL_OK or an error code; on error nothing was launched.                            */
 fl_status fl_attn_fwd(const fl_tensor* q, const fl_tensor* k, const fl_tensor* v,
                       const fl_variant_desc* desc, const fl_aux* aux,
