@@ -223,48 +223,6 @@ def test_errors(prefill_mode):
     assert fb.fl_attn_prefill_paged(dd.tq, dd.tk, dd.tv, kv, dd.desc, dd.aux, dd.tout, dd.tlse) == fb.FL_ERR_SHAPE
 
 
-PACKED = {
-    # chunks that leave a 128- or 256-row tile mostly empty: the in-place kernel packs the query heads of a kv head into
-    # one workgroup (rows per head x heads: 64 x 4, 32 x 8, 32 x 4, 64 x 2, 32 x 4 with three tiles per head, 64 x 2 at D = 64)
-    "g4_q64": lambda: inputs.prefill_paged_bf16(H=8, Hkv=2, D=128, Sq=64, page_size=16, seq_lens=[10, 64, 65, 300, 1500], salt=70),
-    "g8_q20": lambda: inputs.prefill_paged_bf16(H=16, Hkv=2, D=128, Sq=20, page_size=16, seq_lens=[5, 20, 21, 900], salt=71),
-    "g4_q30": lambda: inputs.prefill_paged_bf16(H=4, Hkv=1, D=128, Sq=30, page_size=8, seq_lens=[29, 30, 31, 700], salt=72),
-    "g2_q50": lambda: inputs.prefill_paged_bf16(H=4, Hkv=2, D=128, Sq=50, page_size=32, seq_lens=[49, 64, 1000], salt=73),
-    "g4_q96": lambda: inputs.prefill_paged_bf16(H=8, Hkv=2, D=128, Sq=96, page_size=16, seq_lens=[95, 96, 200, 1300], salt=74),
-    "g2_q40_d64": lambda: inputs.prefill_paged_bf16(H=4, Hkv=2, D=64, Sq=40, page_size=16, seq_lens=[40, 41, 800], salt=75),
-}
-
-
-@pytest.mark.parametrize("name", list(PACKED))
-def test_packed_heads_match_the_unpacked_kernel_and_the_oracle(name, prefill_mode):
-    """The same rows go through the same arithmetic whether or not the heads of a kv head share a workgroup: bit-equal
-    outputs with packing switched off, and parity with the oracle (plain, and one variant instantiated at run time)."""
-    import torch
-    if prefill_mode != "in_place":
-        pytest.skip("the packed shapes belong to the kernel that reads the pages in place")
-    for variant in ("plain", "alibi_window"):
-        w = PACKED[name]()
-        if variant == "alibi_window":
-            w.alibi = inputs.alibi_slopes(w.q.shape[1])
-            w.window = 200
-        outs = []
-        for pack_off in (0, 1):
-            fb.check(fb.fl_set_tuning("prefill_pack", pack_off))
-            try:
-                dd = runner.upload_prefill_paged(w)
-                dd.out.fill_(float("nan"))
-                dd.lse.fill_(float("nan"))
-                dd.run_checked()
-                torch.cuda.synchronize()
-                outs.append((dd.out.clone(), dd.lse.clone()))
-            finally:
-                fb.fl_set_tuning("prefill_pack", 0)
-        assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1]), (name, variant)
-        ref, ref_lse = do.prefill_attention(w.q, w.k_cache, w.v_cache, w.block_table, w.seq_lens, scale=w.scale, window=w.window,
-                                            alibi_slopes=w.alibi)
-        check(outs[0][0].cpu().numpy()[:, 0], outs[0][1].cpu().numpy()[:, 0, :, :, 0], ref, ref_lse, f"packed_{name}_{variant}")
-
-
 def test_wide_in_place_shape_at_serving_size():
     """32 query heads on 8 kv heads, 8 sequences, 512-row chunks: the launch for which the in-place kernel takes its
     eight-wave shape.  Both ways must agree bit for bit (same arithmetic on the same keys), and the first query-head group
