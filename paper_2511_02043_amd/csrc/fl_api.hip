@@ -1884,8 +1884,8 @@ static bool prefill_as_decode(int64_t D, int64_t B, int64_t H, int64_t Hkv, int6
 // waves, eight from 512 rows on at head dim 128) looks up a page and forms a base per wave and tile (per load instruction
 // when pages hold fewer than the wave's 8 or 16 tokens) and runs at 0.85 - 0.93 of the tuned dense kernel, while the copy costs the time of
 // about 100 query rows of attention.  Measured at 32 / 8 heads, D = 128, 8192 cached tokens (ms in place / copied):
-// 64 rows 0.66 / 1.32, 128 rows 0.36 / 0.55, 256 rows 0.34 / 0.41, 512 rows 0.57 / 0.64,
-// 1024 rows 1.03 / 1.06, 2048 rows 1.89 / 1.77.
+// 64 rows 0.35 (heads packed) / 1.32, 128 rows 0.355 / 0.55, 256 rows 0.32 / 0.41, 512 rows 0.55 / 0.64,
+// 1024 rows 1.00 / 1.06, 2048 rows 1.82 / 1.77.
 static bool prefill_in_place(int64_t D, int64_t page_size, bool has_table, int64_t Sq, int64_t page_stride) {
   if (g_tuning.prefill_gather == 1 || !(D == 32 || D == 64 || D == 128)) return false;
   if (page_stride * 2 >= (1LL << 32)) return false;   // the kernel multiplies page numbers by 32-bit byte strides

@@ -1117,24 +1117,32 @@ fwd_bf16_kernel(const FwdParams call) {
     }
   };
   // paged keys: the page of load instruction u of tile t (every lane the same value; t < t_hi, so the sequence has a token)
+  // (the table entry as loaded: nothing may touch it before it is needed, or the wait for it -- and with it for every
+  // tile load issued before it -- moves up to here; cut_page() makes it uniform and cuts it to the cache's pages)
   auto page_of_lane = [&](int t, int u) __attribute__((always_inline)) -> int {
     if (p.block_table == nullptr) return b;        // one page per sequence
     const int token = min(t * BN + k_instr(u) * C::K_ROWS_PI, p.Sk - 1);
-    return max(0, min(p.block_table[(int64_t)b * p.table_stride + (token >> p.page_shift)], p.num_pages - 1));
+    return p.block_table[(int64_t)b * p.table_stride + (token >> p.page_shift)];
   };
-  auto page_of = [&](int t, int u) __attribute__((always_inline)) -> int {
-    return __builtin_amdgcn_readfirstlane(page_of_lane(t, u));
+  auto cut_page = [&](int entry) __attribute__((always_inline)) -> int {
+    return max(0, min(__builtin_amdgcn_readfirstlane(entry), p.num_pages - 1));
   };
   // the pages of all of this wave's instructions of tile t, as loaded (per lane) / made uniform
+  // (with a shared page only entry 0 is loaded; not even a copy of it is made here: that, too, would wait for it)
   auto pages_of_lane = [&](int t, int (&pg)[KPW]) __attribute__((always_inline)) {
     pg[0] = page_of_lane(t, 0);
 #pragma unroll
-    for (int u = 1; u < KPW; ++u) pg[u] = one_page ? pg[0] : page_of_lane(t, u);
+    for (int u = 1; u < KPW; ++u) pg[u] = one_page ? 0 : page_of_lane(t, u);
+  };
+  auto cut_pages = [&](const int (&raw)[KPW], int (&pg)[KPW]) __attribute__((always_inline)) {
+    pg[0] = cut_page(raw[0]);
+#pragma unroll
+    for (int u = 1; u < KPW; ++u) pg[u] = one_page ? pg[0] : cut_page(raw[u]);
   };
   auto pages_of = [&](int t, int (&pg)[KPW]) __attribute__((always_inline)) {
-    pages_of_lane(t, pg);
-#pragma unroll
-    for (int u = 0; u < KPW; ++u) pg[u] = __builtin_amdgcn_readfirstlane(pg[u]);
+    int raw[KPW];
+    pages_of_lane(t, raw);
+    cut_pages(raw, pg);
   };
   // ... and the address of that instruction's first token in that page (view: the cache as [pages, 1, Hkv, page_size, D])
   // (page and token strides are below 2^32 bytes -- the host checks -- so each product is one 32 x 32 -> 64 bit multiply;
@@ -1338,10 +1346,8 @@ fwd_bf16_kernel(const FwdParams call) {
         if constexpr (N % SPB == SPB - 1) wait_loads_and_sync();
         if constexpr (C::PAGED) {                  // this step's K tile is the next step's V tile
 #pragma unroll
-          for (int u = 0; u < KPW; ++u) {
-            pgv[u] = pgk[u];
-            pgk[u] = __builtin_amdgcn_readfirstlane(pgpre[u]);
-          }
+          for (int u = 0; u < KPW; ++u) pgv[u] = pgk[u];
+          cut_pages(pgpre, pgk);
         }
 #pragma unroll
         for (int u = 0; u + 1 < NTL; ++u) {
