@@ -141,7 +141,7 @@ typedef struct {
  * Supported head dims: D, Dv in {32, 64, 128} for bf16 (the pairs listed by
  * fl_variant_supported), any multiple of 4 up to 128 for f32.  Sq, Sk >= 1 are arbitrary;
  * empty problems (any of B, G, H, Sq equal to 0) return FL_OK without a launch; Sk == 0 is
- * treated as every row fully masked.  (Grouped heads with at most 64 query rows against 1024 keys or more, the chunk
+ * treated as every row fully masked.  (Grouped heads with fewer than 128 query rows against 1024 keys or more, the chunk
  * shape of q_offset: the query heads of a kv head share a workgroup; that kernel shape is compiled on the first such call.)
  * A call that compiles a kernel (a descriptor combination or shape outside the compiled table, first use in the process)
  * takes about a second on the host and loads a code object: make it once outside any stream capture.

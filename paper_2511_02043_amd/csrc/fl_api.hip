@@ -1092,11 +1092,11 @@ static fl_status forward_call(const fl_tensor* q, const fl_tensor* k, const fl_t
   // (of the kernels that read a paged cache in place only the causal one is in the table)
   PagedShape shape = {1, false};
   if (paged != nullptr) shape = paged_shape(B * G * H, Hkv > 0 ? H / Hkv : 1, Sq);
-  // Dense keys: a chunk of at most 64 query rows of grouped heads against 1024 keys or more (a query offset into a long
-  // key sequence, typically) fills half of the smallest tile or less; the kernel shapes with packed heads are
-  // instantiated for it on first use.
+  // Dense keys: a chunk of fewer than 128 query rows of grouped heads against 1024 keys or more (a query offset into a
+  // long key sequence, typically) leaves part of the smallest tile empty; where packing fills it better by a fifth
+  // (paged_shape), the kernel shapes with packed heads are instantiated on first use.
   const bool can_pack = paged == nullptr && dtype == FL_BF16 && !diff && desc->n_bias == 0 && desc->epilogue == 0 &&
-                        (mask & FL_MASK_DOC) == 0 && D == Dv && Sq <= 64 && Sk >= 1024 && Hkv > 0 && H / Hkv > 1 && !empty &&
+                        (mask & FL_MASK_DOC) == 0 && D == Dv && Sq < 128 && Sk >= 1024 && Hkv > 0 && H / Hkv > 1 && !empty &&
                         !(g_tuning.bm || g_tuning.bn || g_tuning.rb || g_tuning.nw || g_tuning.wpe || g_tuning.ring);
   if (can_pack) {
     shape = paged_shape(B * G * H, H / Hkv, Sq);

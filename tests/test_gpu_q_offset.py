@@ -132,12 +132,12 @@ def test_backward_ex_with_offset():
 
 @pytest.mark.parametrize("kind", ["causal", "window", "alibi_causal", "prefix"])
 def test_short_chunks_of_grouped_heads_pack_a_kv_heads_query_heads(kind):
-    """At most 64 query rows of grouped heads against 1024 keys or more: the query heads of a kv head share a workgroup
+    """Fewer than 128 query rows of grouped heads against 1024 keys or more: the query heads of a kv head share a workgroup
     (kernel shapes instantiated on first use).  Element by element against the oracle, and against the call with packing
     switched off (which may run another tile shape, so equal up to the rounding order: 2e-3); head groups of 2, 4 and 8,
     both head dims."""
     import torch
-    for Sq, Sk, D, H, Hkv in ((64, 1500, 128, 8, 2), (20, 2100, 64, 8, 1), (33, 1024, 128, 4, 2)):
+    for Sq, Sk, D, H, Hkv in ((64, 1500, 128, 8, 2), (20, 2100, 64, 8, 1), (33, 1024, 128, 4, 2), (96, 1300, 128, 8, 2)):
         w = chunk(kind, Sq, Sk, D, H=H, Hkv=Hkv, B=2)
         w.name += f"_h{H}_kv{Hkv}_packed"
         run_and_compare(w)
