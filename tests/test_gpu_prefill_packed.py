@@ -57,3 +57,32 @@ def test_packed_heads_match_the_unpacked_kernel_and_the_oracle(name):
         ref, ref_lse = do.prefill_attention(w.q, w.k_cache, w.v_cache, w.block_table, w.seq_lens, scale=w.scale, window=w.window,
                                             alibi_slopes=w.alibi)
         check(outs[0][0].cpu().numpy()[:, 0], outs[0][1].cpu().numpy()[:, 0, :, :, 0], ref, ref_lse, f"packed_{name}_{variant}")
+
+
+def test_packed_and_unpacked_random_shapes():
+    """Twenty-four seeded random chunks through the kernel that reads the pages in place: head groups of 1 ... 8, 1 ... 127
+    rows, both head dims, page sizes 8 ... 64, lengths from below the chunk to a few thousand tokens -- whatever tile shape
+    and head packing the library picks for each, every output against the oracle."""
+    import numpy as np
+    import torch
+    rng = np.random.Generator(np.random.PCG64(2511020431))
+    fb.check(fb.fl_set_tuning("prefill_gather", 2))
+    for case in range(24):
+        group = int(rng.choice([1, 2, 4, 8]))
+        Hkv = int(rng.choice([1, 2]))
+        D = int(rng.choice([64, 128, 128]))
+        Sq = int(rng.integers(1, 128))
+        ps = int(rng.choice([8, 16, 32, 64]))
+        B = int(rng.integers(1, 4))
+        hi = int(rng.choice([150, 1200, 3000]))
+        lens = [int(x) for x in rng.integers(1, hi + 1, size=B)]
+        w = inputs.prefill_paged_bf16(H=group * Hkv, Hkv=Hkv, D=D, Sq=Sq, page_size=ps, seq_lens=lens, salt=300 + case)
+        label = f"case {case}: group={group} Hkv={Hkv} D={D} Sq={Sq} page={ps} lens={lens}"
+        print(label, flush=True)
+        dd = runner.upload_prefill_paged(w)
+        dd.out.fill_(float("nan"))
+        dd.lse.fill_(float("nan"))
+        dd.run_checked()
+        torch.cuda.synchronize()
+        ref, ref_lse = do.prefill_attention(w.q, w.k_cache, w.v_cache, w.block_table, w.seq_lens, scale=w.scale)
+        check(dd.out.cpu().numpy()[:, 0], dd.lse.cpu().numpy()[:, 0, :, :, 0], ref, ref_lse, label)
