@@ -345,6 +345,23 @@ struct BiasHead {
 #pragma unroll
     for (int n = 0; n < NBIAS; ++n) off[n] = b * p.bias[n].sb + g * p.bias[n].sg + h * p.bias[n].sh;
   }
+  // can four consecutive keys of a row be fetched with one 8-byte load?  (uniform)
+  __device__ __forceinline__ bool rows_vec4(const BwdParams& p) const {
+    bool ok = true;
+#pragma unroll
+    for (int n = 0; n < NBIAS; ++n) {
+      const BiasView& v = p.bias[n];
+      ok = ok && v.sj == 1 && ((uint64_t)v.ptr) % 8 == 0 && ((v.sb | v.sg | v.sh | v.si) & 3) == 0;
+    }
+    return ok;
+  }
+  // the four bf16 values of keys j .. j + 3 of row i of bias n, as loaded (j a multiple of 4, rows_vec4())
+  __device__ __forceinline__ uint2 raw4(const BwdParams& p, int n, int i, int j) const {
+    return *(const uint2*)((const uint16_t*)p.bias[n].ptr + off[n] + (int64_t)i * p.bias[n].si + j);
+  }
+  __device__ __forceinline__ uint16_t raw1(const BwdParams& p, int n, int i, int j) const {
+    return ((const uint16_t*)p.bias[n].ptr)[off[n] + (int64_t)i * p.bias[n].si + (int64_t)j * p.bias[n].sj];
+  }
   // sum of the biases of score (i, j) in log2 units; i, j are valid indices
   __device__ __forceinline__ float value(const BwdParams& p, int i, int j) const {
     float s = 0.f;
@@ -494,6 +511,7 @@ bwd_dq_kernel(const BwdParams p) {
   if constexpr ((MASK & kMaskDoc) != 0) qdoc = p.q_doc[(int64_t)b * p.Sq + ic];
   BiasHead<C::NBIAS> bh_;
   bh_.set(p, b, g, h);
+  const bool bias_vec4 = C::NBIAS > 0 && bh_.rows_vec4(p);
 
   f32x16 acc[DB];
 #pragma unroll
@@ -561,24 +579,46 @@ bwd_dq_kernel(const BwdParams p) {
     }
   };
 
-  auto compute = [&](auto stage_c, int t) __attribute__((always_inline)) {
+  // (tn: the tile to request into the other stage while this one is worked on; with biases its loads are issued behind
+  // the first block's bias loads, so that waiting for those -- vector loads return in order -- leaves them in flight)
+  auto compute = [&](auto stage_c, int t, int tn) __attribute__((always_inline)) {
     constexpr int ST = decltype(stage_c)::value * C::STAGE_DQ;
+    if constexpr (C::NBIAS == 0) load_tile(tn, 1 - decltype(stage_c)::value);
     const int j0 = t * BN;
     static_for<0, NB>([&](auto nbc) __attribute__((always_inline)) {
       constexpr int nb = decltype(nbc)::value;
       // the wave's 32 rows against this block's 32 keys under the positional masks (uniform)
       const int cls = classify_block(POS, iw + p.q_off, iw + 31 + p.q_off, j0 + 32 * nb, j0 + 32 * nb + 31, p.Sk, p.window, p.prefix,
                                      make_int2(0, 0), make_int2(0, 0));
-      if (cls == kSkip) return;                    // nothing visible: dS = 0
+      if (cls == kSkip) {                          // nothing visible: dS = 0
+        if constexpr (C::NBIAS > 0 && nb == 0) load_tile(tn, 1 - decltype(stage_c)::value);
+        return;
+      }
       const bool need_mask = (MASK & (kMaskDoc | kMaskCustom)) != 0 || iw + 31 >= p.Sq || cls != kFull;
-      float bl[C::NBIAS > 0 ? 16 : 1];             // this lane's bias values of the block (requested before the matrix work)
+      // This lane's bias values of the block: requested before the matrix work and left untouched until after it (a
+      // conversion right here would put the wait for them, and for the tile loads issued before them, in front of the
+      // MFMAs); four keys per load where the rows allow it.
+      constexpr int NBR = C::NBIAS > 0 ? C::NBIAS : 1;
+      uint2 bq[NBR][4];
+      uint16_t b1[NBR][16];
+      const bool bvec = C::NBIAS > 0 && bias_vec4 && j0 + 32 * nb + 32 <= p.Sk;   // uniform
       if constexpr (C::NBIAS > 0) {
+        if (bvec) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int jj = j0 + 32 * nb + 4 * w.half + 8 * (r >> 2) + (r & 3);
-          bl[r] = bh_.value(p, ic, jj < p.Sk ? jj : p.Sk - 1);
+          for (int n = 0; n < C::NBIAS; ++n)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) bq[n][q4] = bh_.raw4(p, n, ic, j0 + 32 * nb + 4 * w.half + 8 * q4);
+        } else {
+#pragma unroll
+          for (int n = 0; n < C::NBIAS; ++n)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int jj = j0 + 32 * nb + 4 * w.half + 8 * (r >> 2) + (r & 3);
+              b1[n][r] = bh_.raw1(p, n, ic, jj < p.Sk ? jj : p.Sk - 1);
+            }
         }
       }
+      if constexpr (C::NBIAS > 0 && nb == 0) load_tile(tn, 1 - decltype(stage_c)::value);
       f32x16 s = W::zero16(), dp = W::zero16();
       w.template row_stream<ST + nb * 32 * ROW>([&](auto kk, bf16x8 a) __attribute__((always_inline)) {
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s, 0, 0, 0);
@@ -587,6 +627,31 @@ bwd_dq_kernel(const BwdParams p) {
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, dof[kk], dp, 0, 0, 0);
       });
       const int jb = j0 + 32 * nb + 4 * w.half;    // key of register 0
+      float bl[C::NBIAS > 0 ? 16 : 1];             // sum of the biases of each score, log2 units
+      if constexpr (C::NBIAS > 0) {
+        // the first block's values are older than the next tile's loads: all but those have to have landed
+        if constexpr (nb == 0) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * (C::TILE_INSTR / C::NW)));
+        if (bvec) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            float sum = 0.f;
+#pragma unroll
+            for (int n = 0; n < C::NBIAS; ++n) {
+              const uint32_t wd = (r & 2) ? bq[n][r >> 2].y : bq[n][r >> 2].x;
+              sum += __uint_as_float((r & 1) ? (wd & 0xFFFF0000u) : (wd << 16));
+            }
+            bl[r] = sum * kLog2e;
+          }
+        } else {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            float sum = 0.f;
+#pragma unroll
+            for (int n = 0; n < C::NBIAS; ++n) sum += bf16_to_f32(b1[n][r]);
+            bl[r] = sum * kLog2e;
+          }
+        }
+      }
       int kd[16];
       if constexpr ((MASK & kMaskDoc) != 0) {
         const int32_t* kdoc = p.kv_doc + (int64_t)b * p.Sk;
@@ -667,8 +732,7 @@ bwd_dq_kernel(const BwdParams p) {
       static_for<0, 2>([&](auto sc) __attribute__((always_inline)) {
         if (!done) {
           const int tn = next_tile(t + 1);
-          if (tn < t_hi) load_tile(tn, 1 - decltype(sc)::value);
-          compute(sc, t);
+          compute(sc, t, tn < t_hi ? tn : t);      // (past the last tile: the current one again, into the stage nobody reads)
           __builtin_amdgcn_s_waitcnt(0x0F70);
           __syncthreads();
           t = tn;
