@@ -28,6 +28,11 @@ static const KernelEntry kEntries[] = {
     bf16_entry<128, 128, 8, 1, 64, 2, kModNone, kMaskCausal, 0, false, 0, 2, true, 2>(),
     bf16_entry<128, 128, 4, 1, 64, 2, kModNone, kMaskCausal, 0, false, 0, 2, true, 4>(),
     bf16_entry<128, 128, 4, 1, 64, 2, kModNone, kMaskCausal, 0, false, 0, 2, true, 2>(),
+    // head dim 64 (32 query / 8 kv heads is the model of the paper's serving experiment): the eight-wave shape and the packed ones
+    bf16_entry<64, 64, 8, 1, 64, 2, kModNone, kMaskCausal, 0, false, 0, 2, true>(),
+    bf16_entry<64, 64, 8, 1, 64, 2, kModNone, kMaskCausal, 0, false, 0, 2, true, 4>(),
+    bf16_entry<64, 64, 4, 1, 64, 2, kModNone, kMaskCausal, 0, false, 0, 2, true, 4>(),
+    bf16_entry<64, 64, 4, 1, 64, 2, kModNone, kMaskCausal, 0, false, 0, 2, true, 2>(),
 };
 #undef BOTH
 #undef BOTH4
